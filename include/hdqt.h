@@ -1,0 +1,191 @@
+/*
+ * hdqt.h -- C ABI of the MI355X (gfx950) library for the matmuls of Hadamard
+ * Domain Quantized Training (HDQT).
+ *
+ * The paper's problem statement (Methodology section) is Z = X W with
+ * Z in R^{N x C}, X in R^{N x D}, W in R^{D x C}, needed in the forward and the
+ * backward pass.  This header writes the three shapes as M (the paper's N,
+ * batch x positions), K (the paper's D, fan-in) and N (the paper's C, output
+ * features), to keep "N" unambiguous:
+ *
+ *   forward          Z [M,N] = X[M,K]   W[K,N]      contraction over K
+ *   input gradient   dX[M,K] = G[M,N]   W[K,N]^T    contraction over N
+ *   weight gradient  dW[K,N] = X[M,K]^T G[M,N]      contraction over M
+ *
+ * Each matmul runs, on the device, the steps the paper describes:
+ *   - blocked Sylvester-Hadamard transform of both operands along the
+ *     contraction dimension (H = BlockDiag(H_k,..,H_k), order n = 2^k,
+ *     entries +-1, so H H^T = n I and the product needs no inverse transform);
+ *   - the quantizer Q: max calibration over the transformed tensor, scaling
+ *     into +-1, b-bit integer codes, rounding to nearest-even or stochastic;
+ *   - the tiled integer matmul: the contraction is cut into tiles of length s,
+ *     each tile's sum is held in an a-bit signed accumulator (it saturates),
+ *     tile results are added in 32 bits;
+ *   - dequantization: acc * scaleA * scaleB / n.
+ *
+ * Conventions for every entry point
+ *   pointers    DEVICE memory owned by the caller unless a parameter says
+ *               "host"; 16-byte aligned; dense row-major, no strides
+ *   allocation  the library allocates nothing and keeps no state between
+ *               calls; scratch comes from the caller's workspace
+ *   ordering    all work is enqueued on `stream` (a hipStream_t passed as
+ *               void*, NULL = the default stream) and the call returns without
+ *               waiting; outputs are valid once the stream reaches that point
+ *   errors      0 on success; a negative HDQT_E* code for argument errors,
+ *               found on the host before anything is launched; HDQT_EHIP when
+ *               a launch fails (hdqt_last_hip_error() gives the HIP code)
+ *   inputs      must be finite and such that 2^(b-1)/max|.| is finite;
+ *               otherwise the result is unspecified (no fault, no error)
+ */
+#ifndef HDQT_H
+#define HDQT_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define HDQT_VERSION 1
+
+/* ---- rounding inside Q (Methodology: nearest by default, stochastic on the
+ *      tensors the ablation found sensitive) ---- */
+typedef enum { HDQT_ROUND_NEAREST = 0, HDQT_ROUND_STOCHASTIC = 1 } hdqt_round_t;
+
+typedef enum { HDQT_GEMM_FWD = 0, HDQT_GEMM_BWD_INPUT = 1, HDQT_GEMM_BWD_WEIGHT = 2 } hdqt_gemm_kind_t;
+
+/* ---- error codes ---- */
+#define HDQT_OK 0
+#define HDQT_EINVAL_NULL (-1)     /* a required pointer is NULL */
+#define HDQT_EINVAL_DIM (-2)      /* a dimension is <= 0 or too large */
+#define HDQT_EINVAL_HADAMARD (-3) /* had_block is not a power of two in [1, 256] */
+#define HDQT_EINVAL_BITS (-4)     /* b outside [2, 8] */
+#define HDQT_EINVAL_ACC (-5)      /* acc_bits outside [2, 32], or the sum of all tiles may leave int32 */
+#define HDQT_EINVAL_TILE (-6)     /* s < 1, or one tile's exact sum may leave int32 */
+#define HDQT_EINVAL_CLIP (-7)     /* clip outside (0, 1] */
+#define HDQT_EINVAL_ROUND (-8)    /* unknown rounding mode */
+#define HDQT_EINVAL_AXIS (-9)     /* axis not 0 or 1 / unknown gemm kind */
+#define HDQT_EWORKSPACE (-10)     /* workspace NULL or smaller than required */
+#define HDQT_EALIGN (-11)         /* a pointer is not 16-byte aligned */
+#define HDQT_EHIP (-12)           /* a HIP call failed */
+
+/* One quantized operand; names follow the paper's quantizer Q. */
+typedef struct {
+    int32_t b;          /* bit width of the integer codes, 2..8 (the paper's b)            */
+    int32_t round;      /* hdqt_round_t                                                      */
+    float clip;         /* factor on max|x| before scaling, in (0, 1]: 1, or 0.975 as in
+                           the paper's forward pass for weights and activations            */
+    uint32_t tensor_id; /* selects the random stream of this tensor (stochastic only)       */
+} hdqt_operand_t;
+
+typedef struct {
+    int32_t had_block;  /* requested Hadamard order n = 2^k, 1..256; 1 = no transform.  The
+                           order used is the largest power of two <= n dividing the
+                           contraction length (see hdqt_n_eff)                             */
+    int32_t acc_bits;   /* accumulator width a, 2..32; 32 never saturates                   */
+    int64_t s;          /* tile length along the contraction, >= 1; s >= D is one tile      */
+    uint64_t seed;      /* key of the stochastic-rounding generator                         */
+    hdqt_operand_t A;   /* left operand of the product  (X, G, X for the three kinds)       */
+    hdqt_operand_t B;   /* right operand of the product (W, W, G)                           */
+} hdqt_params_t;
+
+/* Where hdqt_gemm_* keeps its intermediates inside the caller's workspace
+ * (byte offsets).  Lets a test read the codes and scales of a whole matmul. */
+typedef struct {
+    size_t scaleA;   /* float: value of one code step of operand A */
+    size_t scaleB;   /* float */
+    size_t codesA;   /* packed codes [RA, D] */
+    size_t codesB;   /* packed codes [RB, D] */
+    size_t acc;      /* int32 [RA, RB] */
+    size_t total;    /* bytes required */
+    int64_t RA, RB, D;
+    int32_t n_eff;
+} hdqt_ws_layout_t;
+
+/* Block order used for a contraction of length D when n is requested: the
+ * largest power of two <= n that divides D ("the highest k delivering a valid
+ * block-diagonal matrix for the given dimension").  Host function. */
+int hdqt_n_eff(int64_t D, int had_block);
+
+/* Row pitch in bytes of packed codes: ceil(D/2) for b <= 4, D for b > 4. */
+int64_t hdqt_codes_pitch(int64_t D, int b);
+
+/* Workspace bytes hdqt_quantize needs (a small constant). */
+size_t hdqt_quantize_workspace_size(void);
+
+/* Workspace bytes (and layout) one hdqt_gemm_* call needs.  Returns 0 and
+ * fills *layout (if not NULL) on success, a negative code on bad arguments. */
+int hdqt_workspace_layout(int gemm_kind, int64_t M, int64_t K, int64_t N,
+                          const hdqt_params_t *params, hdqt_ws_layout_t *layout);
+size_t hdqt_workspace_size(int gemm_kind, int64_t M, int64_t K, int64_t N,
+                           const hdqt_params_t *params); /* 0 on bad arguments */
+
+/*
+ * Transform and quantize one tensor (Methodology: Hadamard domain + Q).
+ *   T          fp32 [rows, cols], row-major (device)
+ *   axis       contraction axis: 1 = along a row (D = cols), 0 = along a
+ *              column (D = rows)
+ *   had_block  requested Hadamard order
+ *   op         width, rounding, clip, tensor_id (host pointer)
+ *   seed       stochastic-rounding seed
+ *   codes_out  packed codes, contraction-major: `lines` x D with the
+ *              contraction index contiguous (lines = rows for axis 1, cols for
+ *              axis 0, i.e. axis 0 writes the transpose).  b <= 4: byte j of a
+ *              line holds code 2j in bits 0-3 and code 2j+1 in bits 4-7
+ *              (two's complement nibbles), pitch ceil(D/2), zero pad nibble if
+ *              D is odd; b > 4: one int8 per code, pitch D.  (device)
+ *   scale_out  one float: the value of a code step, clip*max|y| / 2^(b-1)
+ *              (0 for an all-zero tensor).  (device)
+ * Stochastic rounding of element e (row-major index in T): floor(v) + [u < frac(v) 2^16]
+ * with u the 16-bit half-word (e mod 2) of word ((e/2) mod 4) of the
+ * Philox4x32-10 block with counter (e/8 low, e/8 high, tensor_id, 0) and key
+ * (seed low, seed high).
+ */
+int hdqt_quantize(const float *T, int64_t rows, int64_t cols, int axis, int had_block,
+                  const hdqt_operand_t *op, uint64_t seed, void *codes_out, float *scale_out,
+                  void *workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * Tiled integer matmul on packed codes (Methodology: tiles of size s, low-bit
+ * accumulators) followed by dequantization:
+ *   acc[i,j] = sum_t sat_a( sum_{d in tile t} qA[i,d] qB[j,d] )
+ *   out[i,j] = (float)acc[i,j] * (scaleA * scaleB) * (1/n_eff)
+ *   qA [RA, D], qB [RB, D]  packed codes as written by hdqt_quantize (device)
+ *   bA, bB                  their code widths
+ *   scaleA, scaleB          device pointers to one float each
+ *   out     fp32 [RA, RB] (device, may be NULL if acc_out is given)
+ *   acc_out int32 [RA, RB] (device, may be NULL)
+ *   workspace: RA*RB*4 bytes are needed only when both acc_out is NULL and the
+ *   contraction is split over workgroups; hdqt_workspace_size covers it.
+ */
+int hdqt_gemm_codes(const void *qA, const void *qB, int bA, int bB, const float *scaleA,
+                    const float *scaleB, int64_t RA, int64_t RB, int64_t D, int n_eff,
+                    int acc_bits, int64_t s, float *out, int32_t *acc_out, void *workspace,
+                    size_t workspace_bytes, void *stream);
+
+/*
+ * The three matmuls of a training step.  X, W, G, the outputs: fp32 device
+ * tensors with the shapes at the top of this file.  `acc_out` (nullable)
+ * receives the int32 accumulators of the output's shape.  `params` is a host
+ * pointer.  Workspace: hdqt_workspace_size(kind, ...) bytes.
+ */
+int hdqt_gemm_fwd(const float *X, const float *W, float *Z, int64_t M, int64_t K, int64_t N,
+                  const hdqt_params_t *params, int32_t *acc_out, void *workspace,
+                  size_t workspace_bytes, void *stream);
+int hdqt_gemm_bwd_input(const float *G, const float *W, float *dX, int64_t M, int64_t K,
+                        int64_t N, const hdqt_params_t *params, int32_t *acc_out,
+                        void *workspace, size_t workspace_bytes, void *stream);
+int hdqt_gemm_bwd_weight(const float *X, const float *G, float *dW, int64_t M, int64_t K,
+                         int64_t N, const hdqt_params_t *params, int32_t *acc_out,
+                         void *workspace, size_t workspace_bytes, void *stream);
+
+/* Text for an error code (static string, host). */
+const char *hdqt_strerror(int code);
+/* HIP error code of the last HDQT_EHIP on this thread (0 if none). */
+int hdqt_last_hip_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* HDQT_H */

@@ -1,0 +1,242 @@
+"""Thin Python binding of include/hdqt.h: argument marshalling only.
+
+Every step of the path runs inside libhdqt.so (hand-written HIP for gfx950).
+PyTorch is used for device memory and streams; nothing here computes.  If the
+library is missing the import of a function fails loudly: there is no CPU or
+PyTorch fallback.
+"""
+import ctypes as C
+import os
+from dataclasses import dataclass, field
+from typing import Optional
+
+import torch
+
+ROUND_NEAREST, ROUND_STOCHASTIC = 0, 1
+GEMM_FWD, GEMM_BWD_INPUT, GEMM_BWD_WEIGHT = 0, 1, 2
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libhdqt.so")
+
+EXPORTED = [
+    "hdqt_n_eff", "hdqt_codes_pitch", "hdqt_quantize_workspace_size", "hdqt_workspace_layout",
+    "hdqt_workspace_size", "hdqt_quantize", "hdqt_gemm_codes", "hdqt_gemm_fwd",
+    "hdqt_gemm_bwd_input", "hdqt_gemm_bwd_weight", "hdqt_strerror", "hdqt_last_hip_error",
+]
+
+
+class HdqtError(RuntimeError):
+    def __init__(self, code: int, where: str):
+        self.code = code
+        super().__init__(f"{where}: {strerror(code)} (code {code})")
+
+
+class COperand(C.Structure):
+    _fields_ = [("b", C.c_int32), ("round", C.c_int32), ("clip", C.c_float),
+                ("tensor_id", C.c_uint32)]
+
+
+class CParams(C.Structure):
+    _fields_ = [("had_block", C.c_int32), ("acc_bits", C.c_int32), ("s", C.c_int64),
+                ("seed", C.c_uint64), ("A", COperand), ("B", COperand)]
+
+
+class CLayout(C.Structure):
+    _fields_ = [("scaleA", C.c_size_t), ("scaleB", C.c_size_t), ("codesA", C.c_size_t),
+                ("codesB", C.c_size_t), ("acc", C.c_size_t), ("total", C.c_size_t),
+                ("RA", C.c_int64), ("RB", C.c_int64), ("D", C.c_int64), ("n_eff", C.c_int32)]
+
+
+@dataclass
+class Operand:
+    b: int = 4
+    round: int = ROUND_NEAREST
+    clip: float = 1.0
+    tensor_id: int = 0
+
+    def c(self) -> COperand:
+        return COperand(self.b, self.round, self.clip, self.tensor_id)
+
+
+@dataclass
+class Params:
+    had_block: int = 64
+    acc_bits: int = 8
+    s: int = 32
+    seed: int = 0
+    A: Operand = field(default_factory=Operand)
+    B: Operand = field(default_factory=Operand)
+
+    def c(self) -> CParams:
+        return CParams(self.had_block, self.acc_bits, self.s, self.seed, self.A.c(), self.B.c())
+
+
+_lib = None
+
+
+def load() -> C.CDLL:
+    """Load libhdqt.so (built by paper_2310_03675_amd.build).  Raises if absent."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise ImportError(f"{LIB_PATH} is missing: run `python -m paper_2310_03675_amd.build` "
+                          "(there is no fallback path)")
+    lib = C.CDLL(LIB_PATH)
+    vp, i64, i32, sz = C.c_void_p, C.c_int64, C.c_int, C.c_size_t
+    lib.hdqt_n_eff.restype = i32
+    lib.hdqt_n_eff.argtypes = [i64, i32]
+    lib.hdqt_codes_pitch.restype = i64
+    lib.hdqt_codes_pitch.argtypes = [i64, i32]
+    lib.hdqt_quantize_workspace_size.restype = sz
+    lib.hdqt_quantize_workspace_size.argtypes = []
+    lib.hdqt_workspace_layout.restype = i32
+    lib.hdqt_workspace_layout.argtypes = [i32, i64, i64, i64, C.POINTER(CParams), C.POINTER(CLayout)]
+    lib.hdqt_workspace_size.restype = sz
+    lib.hdqt_workspace_size.argtypes = [i32, i64, i64, i64, C.POINTER(CParams)]
+    lib.hdqt_quantize.restype = i32
+    lib.hdqt_quantize.argtypes = [vp, i64, i64, i32, i32, C.POINTER(COperand), C.c_uint64, vp, vp,
+                                  vp, sz, vp]
+    lib.hdqt_gemm_codes.restype = i32
+    lib.hdqt_gemm_codes.argtypes = [vp, vp, i32, i32, vp, vp, i64, i64, i64, i32, i32, i64, vp, vp,
+                                    vp, sz, vp]
+    for name in ("hdqt_gemm_fwd", "hdqt_gemm_bwd_input", "hdqt_gemm_bwd_weight"):
+        fn = getattr(lib, name)
+        fn.restype = i32
+        fn.argtypes = [vp, vp, vp, i64, i64, i64, C.POINTER(CParams), vp, vp, sz, vp]
+    lib.hdqt_strerror.restype = C.c_char_p
+    lib.hdqt_strerror.argtypes = [i32]
+    lib.hdqt_last_hip_error.restype = i32
+    lib.hdqt_last_hip_error.argtypes = []
+    _lib = lib
+    return lib
+
+
+def strerror(code: int) -> str:
+    return load().hdqt_strerror(code).decode()
+
+
+def n_eff(D: int, had_block: int) -> int:
+    return load().hdqt_n_eff(D, had_block)
+
+
+def codes_pitch(D: int, b: int) -> int:
+    return load().hdqt_codes_pitch(D, b)
+
+
+def workspace_layout(kind: int, M: int, K: int, N: int, params: Params) -> CLayout:
+    L = CLayout()
+    p = params.c()
+    rc = load().hdqt_workspace_layout(kind, M, K, N, C.byref(p), C.byref(L))
+    if rc:
+        raise HdqtError(rc, "hdqt_workspace_layout")
+    return L
+
+
+def workspace_size(kind: int, M: int, K: int, N: int, params: Params) -> int:
+    p = params.c()
+    return load().hdqt_workspace_size(kind, M, K, N, C.byref(p))
+
+
+def _ptr(t: Optional[torch.Tensor]):
+    return None if t is None else C.c_void_p(t.data_ptr())
+
+
+def _stream(stream: Optional[torch.cuda.Stream]):
+    s = stream if stream is not None else torch.cuda.current_stream()
+    return C.c_void_p(s.cuda_stream)
+
+
+def _check_dev(*tensors):
+    for t in tensors:
+        if t is not None and not (t.is_cuda and t.is_contiguous()):
+            raise ValueError("tensors must be contiguous device tensors")
+
+
+def quantize(T: torch.Tensor, axis: int, had_block: int, op: Operand, seed: int = 0,
+             stream: Optional[torch.cuda.Stream] = None):
+    """hdqt_quantize -> (codes uint8 [lines, pitch], scale float32 [1]) on the device."""
+    _check_dev(T)
+    assert T.dtype == torch.float32 and T.dim() == 2
+    rows, cols = T.shape
+    D, lines = (cols, rows) if axis == 1 else (rows, cols)
+    pitch = codes_pitch(D, op.b)
+    codes = torch.empty((lines, pitch), dtype=torch.uint8, device=T.device)
+    scale = torch.empty(1, dtype=torch.float32, device=T.device)
+    ws = torch.empty(load().hdqt_quantize_workspace_size(), dtype=torch.uint8, device=T.device)
+    cop = op.c()
+    rc = load().hdqt_quantize(_ptr(T), rows, cols, axis, had_block, C.byref(cop), seed,
+                              _ptr(codes), _ptr(scale), _ptr(ws), ws.numel(), _stream(stream))
+    if rc:
+        raise HdqtError(rc, "hdqt_quantize")
+    return codes, scale
+
+
+def gemm_codes(qA: torch.Tensor, qB: torch.Tensor, bA: int, bB: int, scaleA: torch.Tensor,
+               scaleB: torch.Tensor, D: int, n: int, acc_bits: int, s: int,
+               want_out: bool = True, want_acc: bool = True,
+               workspace: Optional[torch.Tensor] = None,
+               out: Optional[torch.Tensor] = None, acc: Optional[torch.Tensor] = None,
+               stream: Optional[torch.cuda.Stream] = None):
+    """hdqt_gemm_codes -> (out fp32 [RA, RB] | None, acc int32 [RA, RB] | None)."""
+    _check_dev(qA, qB, scaleA, scaleB)
+    RA, RB = qA.shape[0], qB.shape[0]
+    if out is None and want_out:
+        out = torch.empty((RA, RB), dtype=torch.float32, device=qA.device)
+    if acc is None and want_acc:
+        acc = torch.empty((RA, RB), dtype=torch.int32, device=qA.device)
+    if workspace is None:
+        workspace = torch.empty(max(RA * RB * 4, 256), dtype=torch.uint8, device=qA.device)
+    rc = load().hdqt_gemm_codes(_ptr(qA), _ptr(qB), bA, bB, _ptr(scaleA), _ptr(scaleB), RA, RB, D,
+                                n, acc_bits, s, _ptr(out), _ptr(acc), _ptr(workspace),
+                                workspace.numel(), _stream(stream))
+    if rc:
+        raise HdqtError(rc, "hdqt_gemm_codes")
+    return out, acc
+
+
+_GEMM_FN = {GEMM_FWD: "hdqt_gemm_fwd", GEMM_BWD_INPUT: "hdqt_gemm_bwd_input",
+            GEMM_BWD_WEIGHT: "hdqt_gemm_bwd_weight"}
+
+
+def out_shape(kind: int, M: int, K: int, N: int):
+    return {GEMM_FWD: (M, N), GEMM_BWD_INPUT: (M, K), GEMM_BWD_WEIGHT: (K, N)}[kind]
+
+
+def gemm(kind: int, P: torch.Tensor, Q: torch.Tensor, M: int, K: int, N: int, params: Params,
+         out: Optional[torch.Tensor] = None, acc: Optional[torch.Tensor] = None,
+         want_acc: bool = False, workspace: Optional[torch.Tensor] = None,
+         stream: Optional[torch.cuda.Stream] = None):
+    """hdqt_gemm_{fwd,bwd_input,bwd_weight}.  P, Q are the two source tensors of
+    `kind`: (X, W), (G, W), (X, G).  -> (out, acc | None, workspace)."""
+    _check_dev(P, Q, out, acc, workspace)
+    shape = out_shape(kind, M, K, N)
+    if out is None:
+        out = torch.empty(shape, dtype=torch.float32, device=P.device)
+    if acc is None and want_acc:
+        acc = torch.empty(shape, dtype=torch.int32, device=P.device)
+    p = params.c()
+    need = load().hdqt_workspace_size(kind, M, K, N, C.byref(p))
+    if workspace is None:
+        workspace = torch.empty(max(need, 256), dtype=torch.uint8, device=P.device)
+    rc = getattr(load(), _GEMM_FN[kind])(_ptr(P), _ptr(Q), _ptr(out), M, K, N, C.byref(p),
+                                         _ptr(acc), _ptr(workspace), workspace.numel(),
+                                         _stream(stream))
+    if rc:
+        raise HdqtError(rc, _GEMM_FN[kind])
+    return out, acc, workspace
+
+
+def gemm_fwd(X, W, params: Params, **kw):
+    M, K = X.shape
+    return gemm(GEMM_FWD, X, W, M, K, W.shape[1], params, **kw)
+
+
+def gemm_bwd_input(G, W, params: Params, **kw):
+    M, N = G.shape
+    return gemm(GEMM_BWD_INPUT, G, W, M, W.shape[0], N, params, **kw)
+
+
+def gemm_bwd_weight(X, G, params: Params, **kw):
+    M, K = X.shape
+    return gemm(GEMM_BWD_WEIGHT, X, G, M, K, G.shape[1], params, **kw)

@@ -1,0 +1,35 @@
+"""Compile the HIP library for gfx950 into paper_2310_03675_amd/libhdqt.so.
+
+    python -m paper_2310_03675_amd.build
+"""
+import os
+import subprocess
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+CSRC = os.path.join(HERE, "csrc")
+LIB = os.path.join(HERE, "libhdqt.so")
+SOURCES = ["api.hip", "quantize.hip", "gemm.hip"]
+
+# -ffp-contract=off: every binary32 operation of the quantizer rounds on its own,
+# as in the definition the results are checked against.
+# packed-fp32-ops off: keep the compiler from pairing float operations into the
+# packed forms.
+HIPCC_FLAGS = [
+    "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
+    "-ffp-contract=off", "-fno-fast-math",
+    "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+    "-Wall", "-Wno-unused-function", "-Wno-unused-command-line-argument",
+]
+
+
+def build(verbose: bool = False, extra=()) -> str:
+    hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+    cmd = [hipcc, *HIPCC_FLAGS, *extra, *[os.path.join(CSRC, s) for s in SOURCES], "-o", LIB]
+    if verbose:
+        print(" ".join(cmd))
+    subprocess.run(cmd, check=True)
+    return LIB
+
+
+if __name__ == "__main__":
+    print(build(verbose=True))

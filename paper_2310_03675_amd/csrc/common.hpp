@@ -1,0 +1,119 @@
+// Shared declarations of the HDQT device library (gfx950 only).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace hdqt {
+
+constexpr int kMaxHadamard = 256;   // largest supported block order
+constexpr int kWave = 64;
+
+// Per-operand calibration record in the workspace.  `amax_bits` is the
+// bit pattern of max|y| (non-negative floats order like unsigned integers, so
+// the reduction is an integer atomicMax); `scale` is the value of one code step.
+struct QMeta {
+    uint32_t amax_bits;
+    float scale;
+    uint32_t pad[2];
+};
+
+// One quantize request, resolved by the host.
+struct QuantArgs {
+    const float* T;
+    int64_t rows, cols;     // source tensor, row-major
+    int axis;               // 1: contraction along a row, 0: along a column
+    int log2n;              // log2 of the block order actually used
+    int b;                  // code width
+    int stochastic;         // 0 nearest-even, 1 stochastic
+    float clip;
+    uint32_t tensor_id;
+    uint32_t seed_lo, seed_hi;
+    QMeta* meta;            // device
+    uint8_t* codes;         // device, packed, contraction-major
+    float* scale_out;       // device, may alias &meta->scale, may be null
+};
+
+struct GemmArgs {
+    const uint8_t* qA;      // [RA, pitchA] packed codes
+    const uint8_t* qB;      // [RB, pitchB]
+    int64_t pitchA, pitchB;
+    int bA, bB;
+    int64_t RA, RB, D;
+    int64_t s;              // tile length in codes
+    int s_pad;              // tile length rounded up to the MFMA K granularity
+    int64_t n_tiles;        // ceil(D / s)
+    int acc_lo, acc_hi;     // accumulator range [-2^(a-1), 2^(a-1)-1]
+    const float* scaleA;    // device scalars
+    const float* scaleB;
+    float inv_n;            // 1 / n_eff (a power of two)
+    float* out;             // [RA, RB] or null
+    int32_t* acc_out;       // [RA, RB] or null; with splits > 1 it is the atomic target
+    int splits;             // workgroups sharing one output tile along the contraction
+    int64_t tiles_per_split;
+};
+
+// Launchers (host).  Each returns the hipError_t of its last launch.
+hipError_t launch_quantize(const QuantArgs& q, hipStream_t stream);
+hipError_t launch_gemm(const GemmArgs& g, hipStream_t stream);
+hipError_t launch_fill_u32(uint32_t* p, int64_t count, uint32_t value, hipStream_t stream);
+hipError_t launch_dequant(const int32_t* acc, int64_t count, const float* scaleA,
+                          const float* scaleB, float inv_n, float* out, hipStream_t stream);
+
+// ---- device helpers -------------------------------------------------------
+
+// Philox4x32-10 (Salmon et al., SC'11): ten rounds of two 32x32->64 multiplies
+// and a Weyl key schedule.
+__device__ __forceinline__ void philox4x32_10(uint32_t c0, uint32_t c1, uint32_t c2, uint32_t c3,
+                                               uint32_t k0, uint32_t k1, uint32_t out[4])
+{
+#pragma unroll
+    for (int r = 0; r < 10; ++r) {
+        const uint64_t p0 = (uint64_t)0xD2511F53u * c0;
+        const uint64_t p1 = (uint64_t)0xCD9E8D57u * c2;
+        const uint32_t n0 = (uint32_t)(p1 >> 32) ^ c1 ^ k0;
+        const uint32_t n2 = (uint32_t)(p0 >> 32) ^ c3 ^ k1;
+        c1 = (uint32_t)p1;
+        c3 = (uint32_t)p0;
+        c0 = n0;
+        c2 = n2;
+        k0 += 0x9E3779B9u;
+        k1 += 0xBB67AE85u;
+    }
+    out[0] = c0; out[1] = c1; out[2] = c2; out[3] = c3;
+}
+
+// Random 16 bits of element e: half-word (e & 1) of word ((e >> 1) & 3) of `blk`.
+__device__ __forceinline__ uint32_t sr_halfword(const uint32_t blk[4], uint32_t e_low3)
+{
+    const uint32_t w = blk[(e_low3 >> 1) & 3];
+    return (w >> (16 * (e_low3 & 1))) & 0xFFFFu;
+}
+
+// alpha * 2^(b-1): one correctly rounded division.  A binary64 quotient of two
+// binary32 values rounds to binary32 without double-rounding error (53 >= 2*24+2).
+__device__ __forceinline__ float inverse_step(float amax_clipped, int b)
+{
+    const double levels = (double)(1 << (b - 1));
+    return (float)(levels / (double)amax_clipped);
+}
+
+// Rounding step of Q.  v = y * inv; nearest-even, or floor + Bernoulli(frac)
+// with a 16-bit threshold; then the clamp to the b-bit range.
+__device__ __forceinline__ int quantize_value(float y, float inv, int qmin, int qmax,
+                                              bool stochastic, uint32_t u16)
+{
+    const float v = y * inv;
+    float q;
+    if (stochastic) {
+        const float fl = floorf(v);
+        const float frac = v - fl;
+        q = fl + (((float)u16 < frac * 65536.0f) ? 1.0f : 0.0f);
+    } else {
+        q = rintf(v);
+    }
+    q = fminf(fmaxf(q, (float)qmin), (float)qmax);
+    return (int)q;
+}
+
+} // namespace hdqt

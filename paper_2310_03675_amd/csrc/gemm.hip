@@ -1,0 +1,229 @@
+// Tiled integer matmul with a-bit accumulators on the int8 MFMA units (gfx950).
+//
+// Paper, Methodology section: the contraction is cut into tiles of size s and
+// each tile's partial sum is kept in a low-bit accumulator; Experiments: 8-bit
+// accumulators, tile 32.  Here:
+//   acc[i,j] = sum_t clamp( sum_{d in tile t} qA[i,d] qB[j,d], -2^(a-1), 2^(a-1)-1 )
+//   out[i,j] = float(acc[i,j]) * (scaleA*scaleB) * (1/n)
+//
+// Both operands are contraction-major packed codes.  A workgroup (4 waves)
+// owns a 128 x 128 output tile; each wave a 64 x 64 quarter as 2 x 2 MFMA
+// blocks of 32 x 32.  Codes are unpacked to int8 on their way into LDS.  Every
+// tile of the contraction is padded (with zeros, in LDS only) to a multiple of
+// the MFMA depth, so an MFMA never mixes two tiles; after a tile's last MFMA
+// the 32-bit tile sums are clamped and added to the running totals.
+
+#include "common.hpp"
+
+namespace hdqt {
+
+namespace {
+
+typedef int v16i __attribute__((ext_vector_type(16)));
+
+constexpr int kThreads = 256;
+constexpr int BM = 128, BN = 128;
+constexpr int KC = 64;          // virtual contraction positions per LDS stage
+constexpr int KG = 16;          // contraction depth of one MFMA
+constexpr int LDP = KC + 16;    // LDS row pitch in bytes
+
+__device__ __forceinline__ int sext_nibble(uint32_t nib)
+{
+    return ((int)(nib << 28)) >> 28;
+}
+
+// code d of a line (generic, any width)
+__device__ __forceinline__ int fetch_code(const uint8_t* line, int64_t d, int b)
+{
+    if (b <= 4) {
+        const uint32_t byte = line[d >> 1];
+        return sext_nibble((d & 1) ? (byte >> 4) : (byte & 0xFu));
+    }
+    return (int)(int8_t)line[d];
+}
+
+// Fill rows [row0, row0+128) x virtual positions [kv0, kv0+KC) of one operand.
+// ALIGNED: s and D are multiples of 16, so virtual position == code index and
+// 16 codes are 8 (b <= 4) or 16 (b > 4) aligned bytes.
+template <bool ALIGNED>
+__device__ __forceinline__ void load_operand(uint8_t (*lds)[LDP], const uint8_t* q, int64_t pitch,
+                                             int b, int64_t R, int64_t D, int64_t row0,
+                                             int64_t kv0, int64_t kv_end, int64_t s, int s_pad)
+{
+    const int tid = threadIdx.x;
+    if (ALIGNED) {
+#pragma unroll
+        for (int it = 0; it < (BM * KC / 16) / kThreads; ++it) {
+            const int idx = tid + it * kThreads;
+            const int r = idx >> 2, ch = idx & 3;
+            const int64_t row = row0 + r;
+            const int64_t d = kv0 + ch * 16;
+            uint32_t o[4] = {0u, 0u, 0u, 0u};
+            if (row < R && d < kv_end && d < D) {
+                if (b <= 4) {
+                    const uint2 w = *reinterpret_cast<const uint2*>(q + row * pitch + (d >> 1));
+                    const uint32_t ww[2] = {w.x, w.y};
+#pragma unroll
+                    for (int h = 0; h < 2; ++h) {
+#pragma unroll
+                        for (int k = 0; k < 8; ++k) {
+                            const int c = sext_nibble((ww[h] >> (4 * k)) & 0xFu);
+                            o[h * 2 + (k >> 2)] |= ((uint32_t)c & 0xFFu) << (8 * (k & 3));
+                        }
+                    }
+                } else {
+                    const uint4 w = *reinterpret_cast<const uint4*>(q + row * pitch + d);
+                    o[0] = w.x; o[1] = w.y; o[2] = w.z; o[3] = w.w;
+                }
+            }
+            *reinterpret_cast<uint4*>(&lds[r][ch * 16]) = make_uint4(o[0], o[1], o[2], o[3]);
+        }
+    } else {
+        // 32 consecutive virtual positions of one row per thread
+        const int r = tid >> 1, half = tid & 1;
+        const int64_t row = row0 + r;
+        const int64_t p0 = kv0 + half * 32;
+        int64_t tile = p0 / s_pad;
+        int off = (int)(p0 - tile * s_pad);
+        const uint8_t* line = q + row * pitch;
+        for (int i = 0; i < 32; i += 4) {
+            uint32_t w = 0;
+            for (int k = 0; k < 4; ++k) {
+                const int64_t d = tile * s + off;
+                int c = 0;
+                if (row < R && off < s && d < D && (p0 + i + k) < kv_end) c = fetch_code(line, d, b);
+                w |= ((uint32_t)c & 0xFFu) << (8 * k);
+                if (++off == s_pad) { off = 0; ++tile; }
+            }
+            *reinterpret_cast<uint32_t*>(&lds[r][half * 32 + i]) = w;
+        }
+    }
+}
+
+template <bool ALIGNED>
+__global__ __launch_bounds__(kThreads) void gemm_tiled_kernel(GemmArgs g)
+{
+    __shared__ __attribute__((aligned(16))) uint8_t As[BM][LDP];
+    __shared__ __attribute__((aligned(16))) uint8_t Bs[BN][LDP];
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63, wave = tid >> 6;
+    const int wm = wave >> 1, wn = wave & 1;
+    const int64_t row0 = (int64_t)blockIdx.y * BM;     // rows of A -> output rows
+    const int64_t col0 = (int64_t)blockIdx.x * BN;     // rows of B -> output columns
+
+    // contraction range of this workgroup, in tiles and in virtual positions
+    const int64_t t_begin = (int64_t)blockIdx.z * g.tiles_per_split;
+    int64_t t_end = t_begin + g.tiles_per_split;
+    if (t_end > g.n_tiles) t_end = g.n_tiles;
+    const int64_t kv_begin = t_begin * g.s_pad, kv_end = t_end * g.s_pad;
+    const int steps_per_tile = g.s_pad / KG;
+
+    v16i part[2][2], total[2][2];
+#pragma unroll
+    for (int a = 0; a < 2; ++a)
+#pragma unroll
+        for (int c = 0; c < 2; ++c)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) { part[a][c][r] = 0; total[a][c][r] = 0; }
+
+    int step_in_tile = 0;
+    for (int64_t kv0 = kv_begin; kv0 < kv_end; kv0 += KC) {
+        __syncthreads();
+        load_operand<ALIGNED>(As, g.qA, g.pitchA, g.bA, g.RA, g.D, row0, kv0, kv_end, g.s, g.s_pad);
+        load_operand<ALIGNED>(Bs, g.qB, g.pitchB, g.bB, g.RB, g.D, col0, kv0, kv_end, g.s, g.s_pad);
+        __syncthreads();
+#pragma unroll
+        for (int ks = 0; ks < KC / KG; ++ks) {
+            if (kv0 + ks * KG >= kv_end) break;
+            long fa[2], fb[2];
+#pragma unroll
+            for (int a = 0; a < 2; ++a)
+                fa[a] = *reinterpret_cast<const long*>(
+                    &As[wm * 64 + a * 32 + (lane & 31)][ks * KG + (lane >> 5) * 8]);
+#pragma unroll
+            for (int c = 0; c < 2; ++c)
+                fb[c] = *reinterpret_cast<const long*>(
+                    &Bs[wn * 64 + c * 32 + (lane & 31)][ks * KG + (lane >> 5) * 8]);
+#pragma unroll
+            for (int a = 0; a < 2; ++a)
+#pragma unroll
+                for (int c = 0; c < 2; ++c)
+                    part[a][c] = __builtin_amdgcn_mfma_i32_32x32x16_i8(fa[a], fb[c], part[a][c], 0, 0, 0);
+            if (++step_in_tile == steps_per_tile) {
+                step_in_tile = 0;
+#pragma unroll
+                for (int a = 0; a < 2; ++a)
+#pragma unroll
+                    for (int c = 0; c < 2; ++c)
+#pragma unroll
+                        for (int r = 0; r < 16; ++r) {
+                            int p = part[a][c][r];
+                            p = p < g.acc_lo ? g.acc_lo : (p > g.acc_hi ? g.acc_hi : p);
+                            total[a][c][r] += p;
+                            part[a][c][r] = 0;
+                        }
+            }
+        }
+    }
+
+    // ---- store.  32x32 block: lane holds column (lane & 31); register r is
+    // row 8*(r/4) + 4*(lane/32) + (r%4).
+    const float dq = (g.scaleA[0] * g.scaleB[0]) * g.inv_n;
+#pragma unroll
+    for (int a = 0; a < 2; ++a)
+#pragma unroll
+        for (int c = 0; c < 2; ++c) {
+            const int64_t j = col0 + wn * 64 + c * 32 + (lane & 31);
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int64_t i = row0 + wm * 64 + a * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
+                if (i < g.RA && j < g.RB) {
+                    const int v = total[a][c][r];
+                    if (g.splits > 1) {
+                        atomicAdd(&g.acc_out[i * g.RB + j], v);
+                    } else {
+                        if (g.acc_out) g.acc_out[i * g.RB + j] = v;
+                        if (g.out) g.out[i * g.RB + j] = (float)v * dq;
+                    }
+                }
+            }
+        }
+}
+
+__global__ __launch_bounds__(256) void dequant_kernel(const int32_t* acc, int64_t count,
+                                                      const float* scaleA, const float* scaleB,
+                                                      float inv_n, float* out)
+{
+    const float dq = (scaleA[0] * scaleB[0]) * inv_n;
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < count;
+         i += (int64_t)gridDim.x * blockDim.x)
+        out[i] = (float)acc[i] * dq;
+}
+
+} // namespace
+
+hipError_t launch_dequant(const int32_t* acc, int64_t count, const float* scaleA,
+                          const float* scaleB, float inv_n, float* out, hipStream_t stream)
+{
+    int64_t blocks = (count + 255) / 256;
+    if (blocks > 4096) blocks = 4096;
+    if (blocks < 1) blocks = 1;
+    hipLaunchKernelGGL(dequant_kernel, dim3((unsigned)blocks), dim3(256), 0, stream, acc, count,
+                       scaleA, scaleB, inv_n, out);
+    return hipGetLastError();
+}
+
+hipError_t launch_gemm(const GemmArgs& g, hipStream_t stream)
+{
+    const dim3 grid((unsigned)((g.RB + BN - 1) / BN), (unsigned)((g.RA + BM - 1) / BM),
+                    (unsigned)g.splits);
+    const bool aligned = (g.s % 16 == 0) && (g.D % 16 == 0) && (g.s_pad == g.s);
+    if (aligned)
+        hipLaunchKernelGGL(gemm_tiled_kernel<true>, grid, dim3(kThreads), 0, stream, g);
+    else
+        hipLaunchKernelGGL(gemm_tiled_kernel<false>, grid, dim3(kThreads), 0, stream, g);
+    return hipGetLastError();
+}
+
+} // namespace hdqt

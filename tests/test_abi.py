@@ -1,0 +1,150 @@
+"""The C-ABI library loads, exports every symbol include/hdqt.h declares, and
+rejects bad arguments on the host before anything is launched (no GPU needed:
+no call here reaches a kernel launch)."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+from paper_2310_03675_amd import binding as B
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+FAKE = C.c_void_p(0x10000)          # non-null, 16-byte aligned, never dereferenced on the host
+
+
+def _declared_functions():
+    text = open(os.path.join(ROOT, "include", "hdqt.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(hdqt_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_every_declared_symbol_is_exported():
+    lib = B.load()
+    names = _declared_functions()
+    assert len(names) >= 12
+    for name in names:
+        assert hasattr(lib, name), name
+    assert sorted(B.EXPORTED) == names
+
+
+def test_block_order_and_pitch_helpers():
+    assert B.n_eff(576, 64) == 64 and B.n_eff(1152, 64) == 64 and B.n_eff(27, 64) == 1
+    assert B.n_eff(100, 64) == 4 and B.n_eff(320, 32) == 32 and B.n_eff(96, 64) == 32
+    assert B.codes_pitch(27, 4) == 14 and B.codes_pitch(27, 8) == 27 and B.codes_pitch(64, 3) == 32
+
+
+def test_struct_layout_matches_header():
+    assert C.sizeof(B.COperand) == 16
+    assert C.sizeof(B.CParams) == 8 + 8 + 8 + 32
+    assert B.CParams.s.offset == 8 and B.CParams.seed.offset == 16 and B.CParams.A.offset == 24
+
+
+def test_workspace_layout():
+    p = B.Params(had_block=64, acc_bits=8, s=32)
+    L = B.workspace_layout(B.GEMM_BWD_WEIGHT, 65536, 1152, 128, p)
+    assert (L.RA, L.RB, L.D, L.n_eff) == (1152, 128, 65536, 64)
+    assert L.codesA % 256 == 0 and L.codesB % 256 == 0 and L.acc % 256 == 0
+    assert L.codesB - L.codesA >= 1152 * 32768
+    assert L.total >= L.acc + 1152 * 128 * 4
+    assert B.workspace_size(B.GEMM_BWD_WEIGHT, 65536, 1152, 128, p) == L.total
+    L = B.workspace_layout(B.GEMM_FWD, 128, 27, 64, p)
+    assert (L.RA, L.RB, L.D, L.n_eff) == (128, 64, 27, 1)
+    L = B.workspace_layout(B.GEMM_BWD_INPUT, 128, 512, 100, p)
+    assert (L.RA, L.RB, L.D, L.n_eff) == (128, 512, 100, 4)
+
+
+def _gemm_rc(kind=B.GEMM_FWD, M=64, K=64, N=64, ws_bytes=1 << 20, **over):
+    p = B.Params(**{k: v for k, v in over.items() if k in ("had_block", "acc_bits", "s")})
+    if "A" in over:
+        p.A = over["A"]
+    if "B" in over:
+        p.B = over["B"]
+    cp = p.c()
+    fn = getattr(B.load(), B._GEMM_FN[kind])
+    return fn(over.get("P", FAKE), over.get("Q", FAKE), over.get("out", FAKE), M, K, N,
+              C.byref(cp), None, over.get("ws", FAKE), ws_bytes, None)
+
+
+@pytest.mark.parametrize("kind", [B.GEMM_FWD, B.GEMM_BWD_INPUT, B.GEMM_BWD_WEIGHT])
+def test_gemm_argument_errors(kind):
+    assert _gemm_rc(kind, P=None) == -1
+    assert _gemm_rc(kind, out=None) == -1
+    assert _gemm_rc(kind, M=0) == -2
+    assert _gemm_rc(kind, N=-5) == -2
+    assert _gemm_rc(kind, K=1 << 31) == -2
+    assert _gemm_rc(kind, had_block=48) == -3
+    assert _gemm_rc(kind, had_block=512) == -3
+    assert _gemm_rc(kind, had_block=0) == -3
+    assert _gemm_rc(kind, A=B.Operand(b=1)) == -4
+    assert _gemm_rc(kind, B=B.Operand(b=9)) == -4
+    assert _gemm_rc(kind, acc_bits=1) == -5
+    assert _gemm_rc(kind, acc_bits=33) == -5
+    assert _gemm_rc(kind, s=0) == -6
+    assert _gemm_rc(kind, A=B.Operand(clip=0.0)) == -7
+    assert _gemm_rc(kind, A=B.Operand(clip=1.5)) == -7
+    assert _gemm_rc(kind, B=B.Operand(round=2)) == -8
+    assert _gemm_rc(kind, ws=None) == -10
+    assert _gemm_rc(kind, ws_bytes=16) == -10
+    assert _gemm_rc(kind, P=C.c_void_p(0x10004)) == -11
+
+
+def test_accumulation_range_errors():
+    # 8-bit codes, one tile of 2^20: tile sum up to 2^34 does not fit int32
+    big = dict(A=B.Operand(b=8), B=B.Operand(b=8))
+    assert _gemm_rc(B.GEMM_FWD, M=64, K=1 << 20, N=64, s=1 << 20, acc_bits=32, ws_bytes=1 << 40, **big) == -6
+    # 2^24 tiles of one element clamped to 2^15: total up to 2^39
+    assert _gemm_rc(B.GEMM_FWD, M=16, K=1 << 24, N=16, s=1, acc_bits=16, ws_bytes=1 << 40, **big) == -5
+
+
+def test_unknown_kind():
+    p = B.Params().c()
+    assert B.load().hdqt_workspace_layout(7, 8, 8, 8, C.byref(p), None) == -9
+    assert B.load().hdqt_workspace_size(7, 8, 8, 8, C.byref(p)) == 0
+
+
+def _quant_rc(T=FAKE, rows=64, cols=64, axis=1, had=64, op=None, codes=FAKE, scale=FAKE, ws=FAKE,
+              ws_bytes=256):
+    cop = (op or B.Operand()).c()
+    return B.load().hdqt_quantize(T, rows, cols, axis, had, C.byref(cop), 0, codes, scale, ws,
+                                  ws_bytes, None)
+
+
+def test_quantize_argument_errors():
+    assert _quant_rc(T=None) == -1
+    assert _quant_rc(codes=None) == -1
+    assert _quant_rc(scale=None) == -1
+    assert _quant_rc(rows=0) == -2
+    assert _quant_rc(axis=2) == -9
+    assert _quant_rc(had=3) == -3
+    assert _quant_rc(op=B.Operand(b=0)) == -4
+    assert _quant_rc(op=B.Operand(clip=-1.0)) == -7
+    assert _quant_rc(op=B.Operand(round=5)) == -8
+    assert _quant_rc(ws=None) == -10
+    assert _quant_rc(ws_bytes=8) == -10
+    assert _quant_rc(T=C.c_void_p(0x10008)) == -11
+
+
+def test_gemm_codes_argument_errors():
+    lib = B.load()
+
+    def rc(qA=FAKE, qB=FAKE, bA=4, bB=4, sA=FAKE, sB=FAKE, RA=8, RB=8, D=64, n=64, a=8, s=32,
+           out=FAKE, acc=None):
+        return lib.hdqt_gemm_codes(qA, qB, bA, bB, sA, sB, RA, RB, D, n, a, s, out, acc, None, 0,
+                                   None)
+    assert rc(qA=None) == -1
+    assert rc(out=None, acc=None) == -1
+    assert rc(RA=0) == -2
+    assert rc(bA=9) == -4
+    assert rc(n=48) == -3
+    assert rc(D=96, n=64) == -3
+    assert rc(a=40) == -5
+    assert rc(s=0) == -6
+
+
+def test_strerror_texts():
+    assert B.strerror(0) == "success"
+    for code in range(-12, 0):
+        assert B.strerror(code) and "unknown error" not in B.strerror(code)
+    assert "unknown error" in B.strerror(-99)
+    assert B.load().hdqt_last_hip_error() == 0

@@ -1,0 +1,282 @@
+"""GPU parity: the HIP path (through the C ABI) against the CPU oracle, element
+by element, on the same seeded inputs.  Integer outputs (codes, accumulators)
+must be bit-exact; dequantized fp32 outputs within 1e-6 relative."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import capi
+from paper_2310_03675_amd import binding as B
+from paper_2310_03675_amd import workloads
+
+pytestmark = pytest.mark.gpu
+
+RTOL = 1e-6
+
+
+def dev(a):
+    t = torch.from_numpy(np.ascontiguousarray(a)) if isinstance(a, np.ndarray) else a
+    return t.contiguous().to("cuda:0")
+
+
+def host(t):
+    torch.cuda.synchronize()
+    return t.cpu().numpy()
+
+
+def assert_close_f32(got, want):
+    assert got.shape == want.shape
+    denom = np.maximum(np.abs(want), np.finfo(np.float32).tiny)
+    bad = np.abs(got.astype(np.float64) - want.astype(np.float64)) > RTOL * denom
+    assert not bad.any(), f"{bad.sum()} of {bad.size} outputs differ by more than {RTOL} relative"
+
+
+def o_operand(op: B.Operand) -> capi.Operand:
+    return capi.Operand(b=op.b, round_mode=op.round, clip=op.clip, tensor_id=op.tensor_id)
+
+
+def o_params(p: B.Params) -> capi.Params:
+    return capi.Params(had_block=p.had_block, acc_bits=p.acc_bits, s=p.s, seed=p.seed,
+                       A=o_operand(p.A), B=o_operand(p.B))
+
+
+# ------------------------------------------------------------------ quantize
+
+def check_quantize(T: np.ndarray, axis: int, n: int, op: B.Operand, seed: int = 0):
+    print(f"quantize shape={T.shape} axis={axis} n={n} b={op.b} round={op.round} clip={op.clip}",
+          flush=True)
+    codes_g, scale_g = B.quantize(dev(T), axis, n, op, seed)
+    codes_o, scale_o, n_eff = capi.quantize(T, axis, n, o_operand(op), seed)
+    want = capi.pack_codes(codes_o, op.b)
+    got = host(codes_g)
+    assert got.shape == want.shape
+    assert host(scale_g)[0] == scale_o, (host(scale_g)[0], scale_o)
+    if not np.array_equal(got, want):
+        bad = np.argwhere(got != want)
+        raise AssertionError(f"{len(bad)} code bytes differ, first at {bad[0]}: "
+                             f"got {got[tuple(bad[0])]:#x} want {want[tuple(bad[0])]:#x}")
+    assert B.n_eff(T.shape[1] if axis == 1 else T.shape[0], n) == n_eff
+
+
+QUANT_SHAPES = [
+    # (rows, cols, axis, n)
+    (64, 256, 1, 16), (256, 128, 0, 16), (64, 128, 1, 16), (64, 128, 0, 16),   # FC layer operands
+    (33, 320, 1, 32), (320, 40, 0, 32), (320, 40, 0, 64),
+    (70, 576, 1, 64), (576, 24, 0, 64), (1152, 36, 0, 64),
+    (8, 512, 1, 256), (1024, 40, 0, 256), (512, 12, 0, 128), (16, 1024, 1, 128),
+    (3, 100, 1, 64), (100, 7, 0, 64), (5, 27, 1, 64), (27, 5, 0, 64),          # n_eff 4, 1 (odd D)
+    (64, 101, 0, 64), (7, 6, 1, 8), (6, 7, 0, 8), (1, 8, 1, 8), (8, 1, 0, 8),
+    (300, 96, 0, 64), (2048, 48, 0, 64), (48, 2048, 1, 64), (520, 33, 0, 8),
+    (129, 64, 1, 1), (64, 129, 0, 1),
+]
+
+
+@pytest.mark.parametrize("rows,cols,axis,n", QUANT_SHAPES)
+def test_quantize_nearest_4bit(rows, cols, axis, n):
+    rng = np.random.default_rng(rows * 1000 + cols)
+    T = (rng.standard_normal((rows, cols)) * 3.0).astype(np.float32)
+    check_quantize(T, axis, n, B.Operand(b=4))
+
+
+@pytest.mark.parametrize("rows,cols,axis,n", QUANT_SHAPES)
+def test_quantize_stochastic_4bit(rows, cols, axis, n):
+    rng = np.random.default_rng(rows * 1000 + cols + 1)
+    T = (rng.standard_normal((rows, cols)) * 1e-2).astype(np.float32)
+    check_quantize(T, axis, n, B.Operand(b=4, round=B.ROUND_STOCHASTIC, tensor_id=7), seed=0x1234567887654321)
+
+
+@pytest.mark.parametrize("b", [2, 3, 5, 6, 8])
+@pytest.mark.parametrize("rows,cols,axis,n", [(40, 192, 1, 64), (192, 40, 0, 64), (9, 27, 1, 64),
+                                              (27, 9, 0, 64), (3, 100, 1, 4)])
+def test_quantize_other_widths(b, rows, cols, axis, n):
+    rng = np.random.default_rng(b * 77 + rows)
+    T = rng.standard_normal((rows, cols)).astype(np.float32)
+    check_quantize(T, axis, n, B.Operand(b=b, clip=0.975))
+    check_quantize(T, axis, n, B.Operand(b=b, round=B.ROUND_STOCHASTIC, tensor_id=b), seed=b)
+
+
+def test_quantize_degenerate_inputs():
+    check_quantize(np.zeros((16, 64), np.float32), 1, 64, B.Operand(b=4))
+    check_quantize(np.zeros((64, 16), np.float32), 0, 64, B.Operand(b=4, round=B.ROUND_STOCHASTIC))
+    one = np.zeros((64, 64), np.float32)
+    one[5, 9] = -3.0
+    check_quantize(one, 1, 64, B.Operand(b=4))
+    check_quantize(one, 0, 64, B.Operand(b=4))
+    # ties and exact grid values
+    grid = (np.arange(-64, 64, dtype=np.float32) / 8.0).reshape(2, 64)
+    grid[0, 0] = 8.0
+    check_quantize(grid, 1, 1, B.Operand(b=4))
+    check_quantize(grid, 1, 1, B.Operand(b=4, round=B.ROUND_STOCHASTIC, tensor_id=3), seed=9)
+
+
+def test_quantize_heavy_tails_and_wide_range():
+    X = workloads.outlier_matrix(512, 256, seed=0, role="X").numpy()
+    for n in (64, 256):
+        check_quantize(X, 1, n, B.Operand(b=4))
+        check_quantize(X, 0, n, B.Operand(b=4))
+    rng = np.random.default_rng(5)
+    T = (rng.standard_normal((256, 256)) * 10.0 ** rng.integers(-6, 6, size=(256, 256))).astype(np.float32)
+    check_quantize(T, 1, 64, B.Operand(b=8))
+    check_quantize(T, 0, 64, B.Operand(b=8))
+
+
+# ------------------------------------------------------------------ integer matmul on codes
+
+def random_codes(rng, lines, D, b, extreme=0.0):
+    lo, hi = -(1 << (b - 1)), (1 << (b - 1)) - 1
+    c = rng.integers(lo, hi + 1, size=(lines, D)).astype(np.int8)
+    if extreme > 0:
+        mask = rng.random((lines, D)) < extreme
+        c = np.where(mask, np.where(rng.random((lines, D)) < 0.5, lo, hi), c).astype(np.int8)
+    return c
+
+
+def check_gemm_codes(RA, RB, D, bA, bB, s, a, n=1, extreme=0.0, seed=0):
+    print(f"gemm_codes RA={RA} RB={RB} D={D} bA={bA} bB={bB} s={s} a={a}", flush=True)
+    rng = np.random.default_rng(seed + RA * 7 + RB * 13 + D)
+    cA = random_codes(rng, RA, D, bA, extreme)
+    cB = random_codes(rng, RB, D, bB, extreme)
+    sA, sB = np.float32(0.0123), np.float32(3.21e-4)
+    want_acc = capi.tiled_matmul(cA, cB, s, a)
+    want_out = capi.dequantize(want_acc, sA, sB, n)
+    out, acc = B.gemm_codes(dev(capi.pack_codes(cA, bA)), dev(capi.pack_codes(cB, bB)), bA, bB,
+                            dev(np.array([sA])), dev(np.array([sB])), D, n, a, s)
+    got_acc, got_out = host(acc), host(out)
+    if not np.array_equal(got_acc, want_acc):
+        bad = np.argwhere(got_acc != want_acc)
+        raise AssertionError(f"{len(bad)} accumulators differ, first at {bad[0]}: got "
+                             f"{got_acc[tuple(bad[0])]} want {want_acc[tuple(bad[0])]}")
+    assert_close_f32(got_out, want_out)
+
+
+@pytest.mark.parametrize("s", [16, 32, 64, 256])
+@pytest.mark.parametrize("a", [8, 16, 32])
+def test_gemm_codes_aligned(s, a):
+    check_gemm_codes(200, 136, 512, 4, 4, s, a, n=64)
+    check_gemm_codes(200, 136, 512, 4, 4, s, a, n=64, extreme=0.5)
+
+
+@pytest.mark.parametrize("s", [1, 5, 16, 27, 32, 48, 100, 1000])
+def test_gemm_codes_ragged(s):
+    check_gemm_codes(37, 29, 100, 4, 4, s, 8, n=4, extreme=0.3)
+    check_gemm_codes(130, 5, 27, 4, 4, s, 8, extreme=0.3)
+    check_gemm_codes(9, 300, 144, 4, 4, s, 6, n=16, extreme=0.3)
+
+
+@pytest.mark.parametrize("bA,bB", [(8, 8), (4, 8), (3, 5), (2, 2), (8, 4)])
+def test_gemm_codes_widths(bA, bB):
+    for s, a in ((16, 8), (64, 16), (40, 12), (512, 32)):
+        check_gemm_codes(96, 72, 512, bA, bB, s, a, n=64, extreme=0.2)
+        check_gemm_codes(33, 47, 77, bA, bB, s, a, n=1, extreme=0.2)
+
+
+def test_gemm_codes_split_contraction():
+    # few output tiles and a long contraction: several workgroups share a tile
+    check_gemm_codes(128, 128, 16384, 4, 4, 32, 8, n=64, extreme=0.1)
+    check_gemm_codes(100, 60, 8192 + 64, 4, 4, 64, 8, n=64, extreme=0.5)
+    check_gemm_codes(64, 64, 4096, 4, 4, 48, 8, n=64, extreme=0.5)
+    check_gemm_codes(1, 1, 4096, 4, 4, 16, 4, n=64, extreme=0.9)
+
+
+def test_gemm_codes_hand_cases():
+    # all (7, 7): each 16-tile sums to 784 -> 127
+    D = 64
+    cA = np.full((32, D), 7, np.int8)
+    cB = np.full((32, D), 7, np.int8)
+    one = dev(np.array([1.0], np.float32))
+    out, acc = B.gemm_codes(dev(capi.pack_codes(cA, 4)), dev(capi.pack_codes(cB, 4)), 4, 4, one, one,
+                            D, 1, 8, 16)
+    assert np.all(host(acc) == 4 * 127) and np.all(host(out) == 508.0)
+    cA[:] = -8
+    out, acc = B.gemm_codes(dev(capi.pack_codes(cA, 4)), dev(capi.pack_codes(cB, 4)), 4, 4, one, one,
+                            D, 1, 8, 16)
+    assert np.all(host(acc) == -512)
+
+
+# ------------------------------------------------------------------ whole matmuls
+
+KIND_NAME = {B.GEMM_FWD: "fwd", B.GEMM_BWD_INPUT: "bwd_input", B.GEMM_BWD_WEIGHT: "bwd_weight"}
+
+
+def operands(kind, layer):
+    return {B.GEMM_FWD: (layer.X, layer.W), B.GEMM_BWD_INPUT: (layer.G, layer.W),
+            B.GEMM_BWD_WEIGHT: (layer.X, layer.G)}[kind]
+
+
+def check_whole_gemm(kind, layer, params: B.Params, sample: int = 0):
+    M, K, N = layer.M, layer.K, layer.N
+    print(f"gemm {KIND_NAME[kind]} {layer.name} n={params.had_block} s={params.s} a={params.acc_bits} "
+          f"bA={params.A.b} bB={params.B.b} rA={params.A.round} rB={params.B.round}", flush=True)
+    P, Q = operands(kind, layer)
+    out, acc, ws = B.gemm(kind, dev(P), dev(Q), M, K, N, params, want_acc=True)
+    L = B.workspace_layout(kind, M, K, N, params)
+    ws_h = host(ws)
+    got_out, got_acc = host(out), host(acc)
+    Pn, Qn = P.numpy(), Q.numpy()
+    axes = {B.GEMM_FWD: (1, 0), B.GEMM_BWD_INPUT: (1, 1), B.GEMM_BWD_WEIGHT: (0, 0)}[kind]
+    op = o_params(params)
+    cA, sA, nA = capi.quantize(Pn, axes[0], params.had_block, op.A, params.seed)
+    cB, sB, nB = capi.quantize(Qn, axes[1], params.had_block, op.B, params.seed)
+    assert nA == nB == L.n_eff
+    # codes and scales inside the workspace
+    pA, pB = capi.pack_codes(cA, params.A.b), capi.pack_codes(cB, params.B.b)
+    gA = ws_h[L.codesA:L.codesA + pA.size].reshape(pA.shape)
+    gB = ws_h[L.codesB:L.codesB + pB.size].reshape(pB.shape)
+    assert np.array_equal(gA, pA), "codes of operand A differ"
+    assert np.array_equal(gB, pB), "codes of operand B differ"
+    assert ws_h[L.scaleA:L.scaleA + 4].view(np.float32)[0] == sA
+    assert ws_h[L.scaleB:L.scaleB + 4].view(np.float32)[0] == sB
+    if sample:
+        rng = np.random.default_rng(99)
+        ii = rng.integers(0, L.RA, size=sample)
+        jj = rng.integers(0, L.RB, size=sample)
+        want_acc = capi.tiled_matmul_sampled(cA, cB, params.s, params.acc_bits, ii, jj)
+        assert np.array_equal(got_acc[ii, jj], want_acc)
+        assert_close_f32(got_out[ii, jj], capi.dequantize(want_acc, sA, sB, nA))
+    else:
+        want_acc = capi.tiled_matmul(cA, cB, params.s, params.acc_bits)
+        assert np.array_equal(got_acc, want_acc), f"{(got_acc != want_acc).sum()} accumulators differ"
+        assert_close_f32(got_out, capi.dequantize(want_acc, sA, sB, nA))
+
+
+def step_params(kind, n, s, a=8, b=4, layer_id=0, sr_x=False, clip_fwd=1.0, seed=0):
+    """Measured configuration: G stochastic in both backward matmuls, the rest nearest."""
+    tid = lambda role: 16 * layer_id + {"X": 0, "W": 1, "G": 2}[role] + 4 * kind
+    NE, ST = B.ROUND_NEAREST, B.ROUND_STOCHASTIC
+    if kind == B.GEMM_FWD:
+        A, Bq = B.Operand(b, NE, clip_fwd, tid("X")), B.Operand(b, NE, clip_fwd, tid("W"))
+    elif kind == B.GEMM_BWD_INPUT:
+        A, Bq = B.Operand(b, ST, 1.0, tid("G")), B.Operand(b, NE, 1.0, tid("W"))
+    else:
+        A, Bq = B.Operand(b, ST if sr_x else NE, 1.0, tid("X")), B.Operand(b, ST, 1.0, tid("G"))
+    return B.Params(had_block=n, acc_bits=a, s=s, seed=seed, A=A, B=Bq)
+
+
+@pytest.mark.parametrize("kind", [B.GEMM_FWD, B.GEMM_BWD_INPUT, B.GEMM_BWD_WEIGHT])
+def test_fc_layer_step(kind):
+    layer = workloads.fc_layer(64, 256, 128, seed=0)
+    check_whole_gemm(kind, layer, step_params(kind, 16, 16))
+    # the paper's own settings: forward without transform, clip 0.975, tile 32;
+    # activations stochastic too in the weight-gradient matmul
+    if kind == B.GEMM_FWD:
+        check_whole_gemm(kind, layer, step_params(kind, 1, 32, clip_fwd=0.975))
+    else:
+        check_whole_gemm(kind, layer, step_params(kind, 64, 32, sr_x=True))
+        check_whole_gemm(kind, layer, step_params(kind, 64, 10 ** 6, a=12, sr_x=True))
+
+
+@pytest.mark.parametrize("kind", [B.GEMM_FWD, B.GEMM_BWD_INPUT, B.GEMM_BWD_WEIGHT])
+def test_har_conv_layer_step(kind):
+    layer = workloads.har_conv_layer(seed=0)
+    check_whole_gemm(kind, layer, step_params(kind, 32, 32))
+
+
+@pytest.mark.parametrize("kind", [B.GEMM_FWD, B.GEMM_BWD_INPUT, B.GEMM_BWD_WEIGHT])
+def test_ragged_layers(kind):
+    # stem-like K = 27 (odd, no transform), classifier-like N = 100 (block order 4)
+    layer = workloads.fc_layer(256, 27, 64, seed=3)
+    check_whole_gemm(kind, layer, step_params(kind, 64, 32))
+    layer = workloads.fc_layer(128, 512, 100, seed=4)
+    check_whole_gemm(kind, layer, step_params(kind, 64, 32))
+    layer = workloads.fc_layer(128, 561, 11, seed=5)      # HAR FCN widths of the paper's energy table
+    check_whole_gemm(kind, layer, step_params(kind, 32, 32))
