@@ -1,0 +1,206 @@
+#!/usr/bin/env python3
+"""Benchmark of the HDQT matmul path on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME] [--s S]
+
+One step = the three matmuls of a training step of one layer (forward, input
+gradient, weight gradient), each with its two Hadamard-domain quantizations,
+its tiled integer matmul and its dequantization, on synthetic inputs already
+resident in HBM.  Prints ONE JSON line:
+
+  value       effective int TOPS of the whole step = 3 * 2MKN / step time
+  roofline    the kernel that takes most of the step, priced against HBM
+  cpu_baseline the CPU oracle timed on a bounded row slice of the same layer
+
+Per-kernel durations are taken with HIP events recorded by the library around
+every launch of the timed region (hdqt_profile_enable), on the launch stream.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+METRIC = "effective int TOPS of HDQT backward GEMMs (% int8 MFMA peak); FWHT-quant GB/s"
+HBM_PEAK_GBPS = 8000.0          # MI355X HBM3E
+INT8_MFMA_PEAK_TOPS = 5000.0    # MI355X dense int8
+
+WORKLOADS = {
+    # name: (constructor kwargs, Hadamard block)
+    "resnet_k1152": dict(kind="resnet", batch=256, cin=128, cout=128, hw=16, n=64),
+    "resnet_k576": dict(kind="resnet", batch=256, cin=64, cout=64, hw=32, n=64),
+    "har": dict(kind="har", n=32),
+    "fc": dict(kind="fc", n=16),
+}
+
+
+def make_layer(name, seed=0):
+    from paper_2310_03675_amd import workloads
+    w = WORKLOADS[name]
+    if w["kind"] == "resnet":
+        return workloads.resnet_conv_layer(w["batch"], w["cin"], w["cout"], w["hw"], seed=seed), w["n"]
+    if w["kind"] == "har":
+        return workloads.har_conv_layer(seed=seed), w["n"]
+    return workloads.fc_layer(seed=seed), w["n"]
+
+
+def step_params(B, kind, n, s, a=8, b=4):
+    """G stochastic in both backward matmuls, everything else nearest."""
+    NE, ST = B.ROUND_NEAREST, B.ROUND_STOCHASTIC
+    tid = lambda role: {"X": 0, "W": 1, "G": 2}[role] + 4 * kind
+    if kind == B.GEMM_FWD:
+        A, Bq = B.Operand(b, NE, 1.0, tid("X")), B.Operand(b, NE, 1.0, tid("W"))
+    elif kind == B.GEMM_BWD_INPUT:
+        A, Bq = B.Operand(b, ST, 1.0, tid("G")), B.Operand(b, NE, 1.0, tid("W"))
+    else:
+        A, Bq = B.Operand(b, NE, 1.0, tid("X")), B.Operand(b, ST, 1.0, tid("G"))
+    return B.Params(had_block=n, acc_bits=a, s=s, seed=0, A=A, B=Bq)
+
+
+def cpu_baseline(layer, n, s, rows):
+    """The oracle, as it stands, on the first `rows` rows of the layer (all three
+    matmuls).  -> dict for the JSON line."""
+    from oracle import capi
+    X = layer.X[:rows].numpy()
+    G = layer.G[:rows].numpy()
+    W = layer.W.numpy()
+    M, K, N = rows, layer.K, layer.N
+    NE, ST = capi.ROUND_NEAREST, capi.ROUND_STOCHASTIC
+    runs = [
+        (capi.FWD, X, W, capi.Operand(4, NE, 1.0, 0), capi.Operand(4, NE, 1.0, 1)),
+        (capi.BWD_INPUT, G, W, capi.Operand(4, ST, 1.0, 6), capi.Operand(4, NE, 1.0, 5)),
+        (capi.BWD_WEIGHT, X, G, capi.Operand(4, NE, 1.0, 8), capi.Operand(4, ST, 1.0, 10)),
+    ]
+    capi.lib()
+    t0 = time.perf_counter()
+    for kind, P, Q, opA, opB in runs:
+        capi.gemm(kind, P, Q, M, K, N, capi.Params(n, 8, s, 0, opA, opB), want_codes=False)
+    dt = time.perf_counter() - t0
+    ops = 3 * 2.0 * M * K * N
+    return {"value": ops / dt / 1e12, "unit": "TOPS", "cores": capi.num_threads(), "kind": "oracle",
+            "sample": f"first {rows} of {layer.M} rows of the layer, fwd + bwd_input + bwd_weight, "
+                      f"{dt:.1f} s wall"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default="resnet_k1152", choices=sorted(WORKLOADS))
+    ap.add_argument("--s", type=int, default=32, help="tile length along the contraction")
+    ap.add_argument("--acc-bits", type=int, default=8)
+    ap.add_argument("--cpu-rows", type=int, default=8192, help="rows of the oracle's sample")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--calib-copy", action="store_true",
+                    help="also run one plain 256 MiB device copy (counter calibration for rocprofv3 --pmc)")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (no collectives, no sharding); "
+              "run with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from paper_2310_03675_amd import binding as B
+
+    B.load()
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    dev = torch.device("cuda:0")
+    layer, n = make_layer(args.workload)
+    M, K, N = layer.M, layer.K, layer.N
+    X, W, G = (t.to(dev) for t in (layer.X, layer.W, layer.G))
+    kinds = [B.GEMM_FWD, B.GEMM_BWD_INPUT, B.GEMM_BWD_WEIGHT]
+    prm = {k: step_params(B, k, n, args.s, args.acc_bits) for k in kinds}
+    srcs = {B.GEMM_FWD: (X, W), B.GEMM_BWD_INPUT: (G, W), B.GEMM_BWD_WEIGHT: (X, G)}
+    outs = {k: torch.empty(B.out_shape(k, M, K, N), dtype=torch.float32, device=dev) for k in kinds}
+    ws_bytes = max(B.workspace_size(k, M, K, N, prm[k]) for k in kinds)
+    ws = torch.empty(ws_bytes, dtype=torch.uint8, device=dev)
+    stream = torch.cuda.current_stream()
+
+    def step():
+        for k in kinds:
+            B.gemm(k, srcs[k][0], srcs[k][1], M, K, N, prm[k], out=outs[k], workspace=ws, stream=stream)
+
+    if args.calib_copy:
+        a = torch.empty(256 << 20, dtype=torch.uint8, device=dev)
+        c = torch.empty_like(a)
+        c.copy_(a)
+        torch.cuda.synchronize()
+        del a, c
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    B.profile_enable(True)
+    B.profile_collect()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    B.profile_enable(False)
+    kern = B.profile_collect()
+
+    ms_per_step = dt / args.steps * 1e3
+    ops_step = 3 * 2.0 * M * K * N
+    value = ops_step / (dt / args.steps) / 1e12
+
+    # ---- per-kernel table (HIP events of the timed region)
+    kernels = {name: {"launches": l, "avg_us": tot / l * 1e3, "share": tot / (dt * 1e3)}
+               for name, (l, tot) in kern.items()}
+    dominant = max(kern, key=lambda k: kern[k][1])
+    # algorithmic bytes per launch of the quantization kernels: the X tensor is the
+    # large one; per launch the kernel sees one of X, W, G, so average over its launches
+    elems = {"X": M * K, "W": K * N, "G": M * N}
+    per_elem = {"absmax": 4.0, "quant": 4.0 + 0.5}
+    # tensors each kernel processes in one step (axis 1 -> row kernels, axis 0 -> col kernels)
+    seen = {"fwht_row": ["X", "G", "W"],      # X (fwd), G and W (bwd_input)
+            "fwht_col": ["W", "X", "G"]}      # W (fwd), X and G (bwd_weight)
+    roof_all = {}
+    for name, (l, tot) in kern.items():
+        for fam in seen:
+            if name.startswith(fam):
+                kind = "absmax" if name.endswith("absmax") else "quant"
+                bytes_per_launch = per_elem[kind] * sum(elems[t] for t in seen[fam]) / len(seen[fam])
+                avg_s = tot / l * 1e-3
+                roof_all[name] = {"bound": "hbm", "achieved": bytes_per_launch / avg_s / 1e9,
+                                  "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                                  "frac": bytes_per_launch / avg_s / 1e9 / HBM_PEAK_GBPS,
+                                  "traffic": None}
+    gemm_names = [k for k in kern if k.startswith("gemm")]
+    gemm_ms = sum(kern[k][1] for k in gemm_names) + kern.get("dequant", (0, 0.0))[1]
+    gemm_tops = ops_step * args.steps / (gemm_ms * 1e-3) / 1e12 if gemm_ms else None
+    roofline = roof_all.get(dominant)
+    if roofline is None:       # the matmul kernel dominates
+        roofline = {"bound": "mfma", "achieved": gemm_tops, "peak": INT8_MFMA_PEAK_TOPS,
+                    "unit": "TOP/s", "frac": gemm_tops / INT8_MFMA_PEAK_TOPS, "traffic": None}
+    roofline = dict(roofline, kernel=dominant)
+    quant_ms = sum(tot for name, (l, tot) in kern.items() if name.startswith("fwht"))
+    quant_bytes = args.steps * 2 * (per_elem["absmax"] + per_elem["quant"]) * sum(elems.values())
+    line = {
+        "metric": METRIC, "value": value, "unit": "TOPS", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": "int8",
+        "data": "synthetic",
+        "config": {"workload": f"{args.workload}: {layer.name} (M={M}, K={K}, N={N}), one training "
+                               f"step = fwd + bwd_input + bwd_weight",
+                   "had_block": n, "input_bits": 4, "acc_bits": args.acc_bits, "s": args.s,
+                   "rounding": "G stochastic, X and W nearest"},
+        "roofline": roofline,
+        "gemm": {"tops": gemm_tops, "frac_of_int8_mfma_peak": (gemm_tops or 0) / INT8_MFMA_PEAK_TOPS,
+                 "ms_per_step": gemm_ms / args.steps},
+        "fwht_quant_GBps": quant_bytes / (quant_ms * 1e-3) / 1e9 if quant_ms else None,
+        "kernels": kernels,
+        "roofline_all": roof_all,
+    }
+    if not args.no_cpu_baseline:
+        line["cpu_baseline"] = cpu_baseline(layer, n, args.s, min(args.cpu_rows, M))
+    print(json.dumps(line))
+
+
+if __name__ == "__main__":
+    main()

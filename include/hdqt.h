@@ -180,6 +180,23 @@ int hdqt_gemm_bwd_weight(const float *X, const float *G, float *dW, int64_t M, i
                          int64_t N, const hdqt_params_t *params, int32_t *acc_out,
                          void *workspace, size_t workspace_bytes, void *stream);
 
+/*
+ * Optional per-kernel timing, for benchmarks.  While enabled, every kernel the
+ * library launches is bracketed by two HIP events on its stream (this is the
+ * only state the library keeps, and events are the only thing it creates).
+ * hdqt_profile_collect waits for all recorded events, writes one row per
+ * kernel that ran (name, number of launches, summed elapsed milliseconds) into
+ * rows[0 .. max_rows) (host memory), clears the record and returns the number
+ * of kernels that ran.  Not for use under graph capture.
+ */
+typedef struct {
+    char name[48];
+    int64_t launches;
+    double total_ms;
+} hdqt_kernel_time_t;
+int hdqt_profile_enable(int on);
+int hdqt_profile_collect(hdqt_kernel_time_t *rows, int max_rows);
+
 /* Text for an error code (static string, host). */
 const char *hdqt_strerror(int code);
 /* HIP error code of the last HDQT_EHIP on this thread (0 if none). */

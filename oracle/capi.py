@@ -212,3 +212,7 @@ def gemm(kind: int, P, Q, M: int, K: int, N: int, prm: Params, want_codes: bool 
     if rc != 0:
         raise ValueError("orc_gemm: bad arguments")
     return dict(out=out, acc=acc, codesA=cA, codesB=cB, scaleA=scales[0], scaleB=scales[1])
+
+
+def num_threads() -> int:
+    return int(lib().orc_num_threads())

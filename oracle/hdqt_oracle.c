@@ -440,3 +440,11 @@ int orc_gemm(int kind, const float *P, const float *Q, int64_t M, int64_t K, int
     if (!acc_out) free(acc);
     return rc;
 }
+
+/* Number of threads the OpenMP loops above use (for reporting timings). */
+#ifdef _OPENMP
+#include <omp.h>
+int orc_num_threads(void) { return omp_get_max_threads(); }
+#else
+int orc_num_threads(void) { return 1; }
+#endif

@@ -22,6 +22,7 @@ EXPORTED = [
     "hdqt_n_eff", "hdqt_codes_pitch", "hdqt_quantize_workspace_size", "hdqt_workspace_layout",
     "hdqt_workspace_size", "hdqt_quantize", "hdqt_gemm_codes", "hdqt_gemm_fwd",
     "hdqt_gemm_bwd_input", "hdqt_gemm_bwd_weight", "hdqt_strerror", "hdqt_last_hip_error",
+    "hdqt_profile_enable", "hdqt_profile_collect",
 ]
 
 
@@ -45,6 +46,10 @@ class CLayout(C.Structure):
     _fields_ = [("scaleA", C.c_size_t), ("scaleB", C.c_size_t), ("codesA", C.c_size_t),
                 ("codesB", C.c_size_t), ("acc", C.c_size_t), ("total", C.c_size_t),
                 ("RA", C.c_int64), ("RB", C.c_int64), ("D", C.c_int64), ("n_eff", C.c_int32)]
+
+
+class CKernelTime(C.Structure):
+    _fields_ = [("name", C.c_char * 48), ("launches", C.c_int64), ("total_ms", C.c_double)]
 
 
 @dataclass
@@ -108,12 +113,27 @@ def load() -> C.CDLL:
     lib.hdqt_strerror.argtypes = [i32]
     lib.hdqt_last_hip_error.restype = i32
     lib.hdqt_last_hip_error.argtypes = []
+    lib.hdqt_profile_enable.restype = i32
+    lib.hdqt_profile_enable.argtypes = [i32]
+    lib.hdqt_profile_collect.restype = i32
+    lib.hdqt_profile_collect.argtypes = [C.POINTER(CKernelTime), i32]
     _lib = lib
     return lib
 
 
 def strerror(code: int) -> str:
     return load().hdqt_strerror(code).decode()
+
+
+def profile_enable(on: bool) -> None:
+    load().hdqt_profile_enable(1 if on else 0)
+
+
+def profile_collect() -> dict:
+    """-> {kernel name: (launches, total milliseconds)} since the last collect."""
+    rows = (CKernelTime * 32)()
+    n = load().hdqt_profile_collect(rows, 32)
+    return {rows[i].name.decode(): (rows[i].launches, rows[i].total_ms) for i in range(min(n, 32))}
 
 
 def n_eff(D: int, had_block: int) -> int:

@@ -44,6 +44,7 @@ struct GemmArgs {
     int s_pad;              // tile length rounded up to the MFMA K granularity
     int64_t n_tiles;        // ceil(D / s)
     int acc_lo, acc_hi;     // accumulator range [-2^(a-1), 2^(a-1)-1]
+    int acc_lo_scaled, acc_hi_scaled;   // the same bounds times 256 (set by the 4-bit fast path)
     const float* scaleA;    // device scalars
     const float* scaleB;
     float inv_n;            // 1 / n_eff (a power of two)
@@ -59,6 +60,24 @@ hipError_t launch_gemm(const GemmArgs& g, hipStream_t stream);
 hipError_t launch_fill_u32(uint32_t* p, int64_t count, uint32_t value, hipStream_t stream);
 hipError_t launch_dequant(const int32_t* acc, int64_t count, const float* scaleA,
                           const float* scaleB, float inv_n, float* out, hipStream_t stream);
+
+// Optional per-kernel timing (off by default).  When enabled through the C ABI,
+// every launch is bracketed by two HIP events on its stream.
+enum KernelId {
+    K_FILL = 0, K_ROW_ABSMAX, K_ROW_QUANT, K_COL_ABSMAX, K_COL_QUANT, K_PLAIN_ABSMAX,
+    K_PLAIN_QUANT, K_GEMM_ALIGNED, K_GEMM_GENERIC, K_DEQUANT, K_GEMM_I4, K_COUNT
+};
+bool gemm_fast_eligible(const GemmArgs& g);
+hipError_t launch_gemm_fast(const GemmArgs& g, hipStream_t stream);
+const char* kernel_name(int id);
+bool profiling_enabled();
+void profile_begin(int id, hipStream_t stream);
+void profile_end(int id, hipStream_t stream);
+struct ProfileScope {
+    int id; hipStream_t stream; bool on;
+    ProfileScope(int i, hipStream_t s) : id(i), stream(s), on(profiling_enabled()) { if (on) profile_begin(id, stream); }
+    ~ProfileScope() { if (on) profile_end(id, stream); }
+};
 
 // ---- device helpers -------------------------------------------------------
 

@@ -209,6 +209,7 @@ hipError_t launch_dequant(const int32_t* acc, int64_t count, const float* scaleA
     int64_t blocks = (count + 255) / 256;
     if (blocks > 4096) blocks = 4096;
     if (blocks < 1) blocks = 1;
+    ProfileScope ps(K_DEQUANT, stream);
     hipLaunchKernelGGL(dequant_kernel, dim3((unsigned)blocks), dim3(256), 0, stream, acc, count,
                        scaleA, scaleB, inv_n, out);
     return hipGetLastError();
@@ -216,9 +217,11 @@ hipError_t launch_dequant(const int32_t* acc, int64_t count, const float* scaleA
 
 hipError_t launch_gemm(const GemmArgs& g, hipStream_t stream)
 {
+    if (gemm_fast_eligible(g)) return launch_gemm_fast(g, stream);
     const dim3 grid((unsigned)((g.RB + BN - 1) / BN), (unsigned)((g.RA + BM - 1) / BM),
                     (unsigned)g.splits);
     const bool aligned = (g.s % 16 == 0) && (g.D % 16 == 0) && (g.s_pad == g.s);
+    ProfileScope ps(aligned ? K_GEMM_ALIGNED : K_GEMM_GENERIC, stream);
     if (aligned)
         hipLaunchKernelGGL(gemm_tiled_kernel<true>, grid, dim3(kThreads), 0, stream, g);
     else

@@ -1,0 +1,270 @@
+// Fast path of the tiled integer matmul for 4-bit codes (gfx950).
+//
+// Same result as the generic kernel (tiles of size s along the contraction,
+// each tile's sum clamped to the a-bit accumulator range, 32-bit total), for
+//   both operands packed 4-bit, s a multiple of 32, D a multiple of 32.
+//
+// What differs from the generic kernel:
+//   * v_mfma_i32_32x32x32_i8: one MFMA consumes 32 contraction positions.
+//   * Nibble unpack without sign extension: a code in the high nibble of a
+//     byte IS 16*code as int8, so (w << 4) & 0xF0F0F0F0 and w & 0xF0F0F0F0 give
+//     the even and the odd codes of a dword, each scaled by 16.  Both operands
+//     use the same order of positions inside a 32-group, so the dot product is
+//     unchanged; it arrives scaled by 256.
+//   * 8-bit accumulators (the paper's setting), s = 32 or 64: saturating the
+//     scaled tile sum to int16 (v_cvt_pk_i16_i32, two sums per instruction)
+//     leaves exactly clamp(sum, -128, 127) in the high byte of each half, and
+//     v_dot4c_i32_i8 with the byte selector (0,1,0,1) adds the two high bytes
+//     to the running total: one VALU instruction per tile sum.  The two sums
+//     of a pair are two consecutive tiles of the same output element.
+//   * any other accumulator width or tile length: v_med3_i32 against bounds
+//     scaled by 256, add, and one exact shift at the end.
+//   * LDS holds int8, double-buffered; the next stage's global loads are in
+//     flight while the current stage is multiplied.
+
+#include "common.hpp"
+
+namespace hdqt {
+
+namespace {
+
+typedef int v4i __attribute__((ext_vector_type(4)));
+typedef int v16i __attribute__((ext_vector_type(16)));
+typedef short v2s __attribute__((ext_vector_type(2)));
+
+constexpr int kThreads = 256;
+constexpr int BM = 128, BN = 128;
+constexpr int KS = 128;               // codes per LDS stage (4 MFMA steps)
+constexpr int KSTEP = 32;             // codes per MFMA
+constexpr int NSTEP = KS / KSTEP;
+constexpr int LDP = KS + 16;          // LDS row pitch in bytes (int8 codes)
+constexpr int kScaleShift = 8;        // both operands carry a factor 16
+
+enum Epilogue { EPI_GENERIC = 0, EPI_SAT8_S32 = 1, EPI_SAT8_S64 = 2 };
+
+struct Staged {
+    uint4 a[2], b[2];                 // two (row, k-step) units per operand per thread
+};
+
+__device__ __forceinline__ uint4 load_unit(const uint8_t* q, int64_t pitch, int64_t R, int64_t row,
+                                           int64_t k, int64_t k_end)
+{
+    if (row < R && k < k_end) return *reinterpret_cast<const uint4*>(q + row * pitch + (k >> 1));
+    return make_uint4(0u, 0u, 0u, 0u);
+}
+
+__device__ __forceinline__ void store_unit(uint8_t* lds_row_k, const uint4& w)
+{
+    const uint32_t m = 0xF0F0F0F0u;
+    const uint4 even = make_uint4((w.x << 4) & m, (w.y << 4) & m, (w.z << 4) & m, (w.w << 4) & m);
+    const uint4 odd = make_uint4(w.x & m, w.y & m, w.z & m, w.w & m);
+    *reinterpret_cast<uint4*>(lds_row_k) = even;
+    *reinterpret_cast<uint4*>(lds_row_k + 16) = odd;
+}
+
+// total += clamp(p0/256, -128, 127) + clamp(p1/256, -128, 127)
+__device__ __forceinline__ int add_sat8_pair(int total, int p0, int p1)
+{
+    const v2s pk = __builtin_amdgcn_cvt_pk_i16(p0, p1);
+    return __builtin_amdgcn_sdot4(__builtin_bit_cast(int, pk), 0x01000100, total, false);
+}
+
+__device__ __forceinline__ int clamp3(int v, int lo, int hi)
+{
+    int r;
+    asm("v_med3_i32 %0, %1, %2, %3" : "=v"(r) : "v"(v), "v"(lo), "v"(hi));
+    return r;
+}
+
+template <int EPI>
+__global__ __launch_bounds__(kThreads, 2) void gemm_i4_kernel(GemmArgs g)
+{
+    __shared__ __attribute__((aligned(16))) uint8_t As[2][BM][LDP];
+    __shared__ __attribute__((aligned(16))) uint8_t Bs[2][BN][LDP];
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63, wave = tid >> 6;
+    const int wm = wave >> 1, wn = wave & 1;
+    const int64_t row0 = (int64_t)blockIdx.y * BM;
+    const int64_t col0 = (int64_t)blockIdx.x * BN;
+
+    const int64_t t_begin = (int64_t)blockIdx.z * g.tiles_per_split;
+    int64_t t_end = t_begin + g.tiles_per_split;
+    if (t_end > g.n_tiles) t_end = g.n_tiles;
+    const int64_t k_begin = t_begin * g.s;
+    int64_t k_end = t_end * g.s;
+    if (k_end > g.D) k_end = g.D;
+    const int steps_per_tile = (int)(g.s / KSTEP);
+    const int lo = g.acc_lo_scaled, hi = g.acc_hi_scaled;
+
+    // loader mapping: unit u = tid + 256*i -> row u/4, k-step u%4
+    const int lrow = tid >> 2, lks = tid & 3;
+
+    v16i total[2][2];
+    v16i part[2][2];                  // EPI_GENERIC only
+#pragma unroll
+    for (int a = 0; a < 2; ++a)
+#pragma unroll
+        for (int c = 0; c < 2; ++c)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) { total[a][c][r] = 0; part[a][c][r] = 0; }
+    const v16i zero = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
+
+    Staged st;
+    auto fetch = [&](int64_t k0) {
+#pragma unroll
+        for (int i = 0; i < 2; ++i) {
+            const int r = lrow + 64 * i;
+            st.a[i] = load_unit(g.qA, g.pitchA, g.RA, row0 + r, k0 + lks * KSTEP, k_end);
+            st.b[i] = load_unit(g.qB, g.pitchB, g.RB, col0 + r, k0 + lks * KSTEP, k_end);
+        }
+    };
+    auto stash = [&](int buf) {
+#pragma unroll
+        for (int i = 0; i < 2; ++i) {
+            const int r = lrow + 64 * i;
+            store_unit(&As[buf][r][lks * KSTEP], st.a[i]);
+            store_unit(&Bs[buf][r][lks * KSTEP], st.b[i]);
+        }
+    };
+    auto frag = [&](const uint8_t(*lds)[LDP], int base_row, int ks) -> v4i {
+        return *reinterpret_cast<const v4i*>(&lds[base_row + (lane & 31)][ks * KSTEP + (lane >> 5) * 16]);
+    };
+
+    int step_in_tile = 0;
+    int buf = 0;
+    if (k_begin < k_end) fetch(k_begin);
+    // Whole stages only: positions at or beyond k_end are zero in LDS and add nothing.
+    for (int64_t k0 = k_begin; k0 < k_end; k0 += KS, buf ^= 1) {
+        stash(buf);
+        __syncthreads();
+        if (k0 + KS < k_end) fetch(k0 + KS);
+
+        if (EPI == EPI_SAT8_S32 || EPI == EPI_SAT8_S64) {
+            // two tiles per half stage (s = 32) or per stage (s = 64)
+#pragma unroll
+            for (int pr = 0; pr < (EPI == EPI_SAT8_S32 ? 2 : 1); ++pr) {
+                constexpr int SPT = (EPI == EPI_SAT8_S32) ? 1 : 2;      // steps per tile
+                v4i fa[2 * SPT][2], fb[2 * SPT][2];
+#pragma unroll
+                for (int q = 0; q < 2 * SPT; ++q)
+#pragma unroll
+                    for (int h = 0; h < 2; ++h) {
+                        fa[q][h] = frag(As[buf], wm * 64 + h * 32, pr * 2 * SPT + q);
+                        fb[q][h] = frag(Bs[buf], wn * 64 + h * 32, pr * 2 * SPT + q);
+                    }
+#pragma unroll
+                for (int a = 0; a < 2; ++a)
+#pragma unroll
+                    for (int c = 0; c < 2; ++c) {
+                        v16i p0 = __builtin_amdgcn_mfma_i32_32x32x32_i8(fa[0][a], fb[0][c], zero, 0, 0, 0);
+                        if (SPT == 2)
+                            p0 = __builtin_amdgcn_mfma_i32_32x32x32_i8(fa[1][a], fb[1][c], p0, 0, 0, 0);
+                        v16i p1 = __builtin_amdgcn_mfma_i32_32x32x32_i8(fa[SPT][a], fb[SPT][c], zero, 0, 0, 0);
+                        if (SPT == 2)
+                            p1 = __builtin_amdgcn_mfma_i32_32x32x32_i8(fa[SPT + 1][a], fb[SPT + 1][c], p1, 0, 0, 0);
+#pragma unroll
+                        for (int r = 0; r < 16; ++r)
+                            total[a][c][r] = add_sat8_pair(total[a][c][r], p0[r], p1[r]);
+                    }
+            }
+        } else {
+#pragma unroll
+            for (int ks = 0; ks < NSTEP; ++ks) {
+                v4i fa[2], fb[2];
+#pragma unroll
+                for (int h = 0; h < 2; ++h) {
+                    fa[h] = frag(As[buf], wm * 64 + h * 32, ks);
+                    fb[h] = frag(Bs[buf], wn * 64 + h * 32, ks);
+                }
+#pragma unroll
+                for (int a = 0; a < 2; ++a)
+#pragma unroll
+                    for (int c = 0; c < 2; ++c)
+                        part[a][c] =
+                            __builtin_amdgcn_mfma_i32_32x32x32_i8(fa[a], fb[c], part[a][c], 0, 0, 0);
+                if (++step_in_tile == steps_per_tile) {
+                    step_in_tile = 0;
+#pragma unroll
+                    for (int a = 0; a < 2; ++a)
+#pragma unroll
+                        for (int c = 0; c < 2; ++c)
+#pragma unroll
+                            for (int r = 0; r < 16; ++r) {
+                                total[a][c][r] += clamp3(part[a][c][r], lo, hi);
+                                part[a][c][r] = 0;
+                            }
+                }
+            }
+        }
+    }
+    if (EPI == EPI_GENERIC) {
+        // a short last tile (D not a multiple of s) ends without reaching steps_per_tile
+        if (step_in_tile != 0) {
+#pragma unroll
+            for (int a = 0; a < 2; ++a)
+#pragma unroll
+                for (int c = 0; c < 2; ++c)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) total[a][c][r] += clamp3(part[a][c][r], lo, hi);
+        }
+    }
+
+    const float dq = (g.scaleA[0] * g.scaleB[0]) * g.inv_n;
+#pragma unroll
+    for (int a = 0; a < 2; ++a)
+#pragma unroll
+        for (int c = 0; c < 2; ++c) {
+            const int64_t j = col0 + wn * 64 + c * 32 + (lane & 31);
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int64_t i = row0 + wm * 64 + a * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
+                if (i < g.RA && j < g.RB) {
+                    const int v = (EPI == EPI_GENERIC) ? (total[a][c][r] >> kScaleShift) : total[a][c][r];
+                    if (g.splits > 1) {
+                        atomicAdd(&g.acc_out[i * g.RB + j], v);
+                    } else {
+                        if (g.acc_out) g.acc_out[i * g.RB + j] = v;
+                        if (g.out) g.out[i * g.RB + j] = (float)v * dq;
+                    }
+                }
+            }
+        }
+}
+
+bool sat8_path(const GemmArgs& g) { return g.acc_hi == 127 && (g.s == 32 || g.s == 64); }
+
+} // namespace
+
+bool gemm_fast_eligible(const GemmArgs& g)
+{
+    if (g.bA > 4 || g.bB > 4) return false;
+    if (g.s % KSTEP != 0 || g.D % KSTEP != 0) return false;
+    if (sat8_path(g)) return true;      // unscaled int32 total: covered by the API's range check
+    // generic epilogue: totals carry a factor 256 and must stay inside int32
+    const int64_t tile_max = g.s * 64;                            // |code| <= 8 on both sides
+    const int64_t acc_max = (int64_t)g.acc_hi + 1;
+    const int64_t per_tile = tile_max < acc_max ? tile_max : acc_max;
+    if (tile_max >= ((int64_t)1 << 22)) return false;
+    return per_tile * g.tiles_per_split < ((int64_t)1 << 22);
+}
+
+hipError_t launch_gemm_fast(const GemmArgs& g_in, hipStream_t stream)
+{
+    GemmArgs g = g_in;
+    const int64_t lo = (int64_t)g.acc_lo * 256, hi = (int64_t)g.acc_hi * 256;
+    g.acc_lo_scaled = lo < INT32_MIN ? INT32_MIN : (int)lo;
+    g.acc_hi_scaled = hi > INT32_MAX ? INT32_MAX : (int)hi;
+    const dim3 grid((unsigned)((g.RB + BN - 1) / BN), (unsigned)((g.RA + BM - 1) / BM),
+                    (unsigned)g.splits);
+    ProfileScope ps(K_GEMM_I4, stream);
+    if (sat8_path(g) && g.s == 32)
+        hipLaunchKernelGGL(gemm_i4_kernel<EPI_SAT8_S32>, grid, dim3(kThreads), 0, stream, g);
+    else if (sat8_path(g))
+        hipLaunchKernelGGL(gemm_i4_kernel<EPI_SAT8_S64>, grid, dim3(kThreads), 0, stream, g);
+    else
+        hipLaunchKernelGGL(gemm_i4_kernel<EPI_GENERIC>, grid, dim3(kThreads), 0, stream, g);
+    return hipGetLastError();
+}
+
+} // namespace hdqt

@@ -1,0 +1,100 @@
+// Optional per-kernel timing with HIP events (host code only).
+//
+// Off by default.  While enabled, every kernel launch of the library is
+// bracketed by two events recorded on the launch stream; hdqt_profile_collect
+// waits for them, sums the elapsed times per kernel and clears the list.  This
+// is the only state the library keeps, and only while the caller asked for it.
+
+#include "../../include/hdqt.h"
+#include "common.hpp"
+
+#include <mutex>
+#include <string.h>
+#include <vector>
+
+namespace hdqt {
+
+namespace {
+struct Pending { int id; hipEvent_t start, stop; };
+std::mutex g_mu;
+bool g_enabled = false;
+std::vector<Pending> g_pending;
+std::vector<Pending> g_open;     // begun, not yet ended (per launch, LIFO)
+} // namespace
+
+const char* kernel_name(int id)
+{
+    static const char* names[K_COUNT] = {
+        "fill_u32", "fwht_row_absmax", "fwht_row_quant", "fwht_col_absmax", "fwht_col_quant",
+        "plain_absmax", "plain_quant", "gemm_tiled_aligned", "gemm_tiled_generic", "dequant",
+        "gemm_i4"};
+    return (id >= 0 && id < K_COUNT) ? names[id] : "?";
+}
+
+bool profiling_enabled() { return g_enabled; }
+
+void profile_begin(int id, hipStream_t stream)
+{
+    std::lock_guard<std::mutex> lock(g_mu);
+    Pending p{id, nullptr, nullptr};
+    if (hipEventCreate(&p.start) != hipSuccess || hipEventCreate(&p.stop) != hipSuccess) return;
+    (void)hipEventRecord(p.start, stream);
+    g_open.push_back(p);
+}
+
+void profile_end(int id, hipStream_t stream)
+{
+    std::lock_guard<std::mutex> lock(g_mu);
+    for (size_t k = g_open.size(); k-- > 0;) {
+        if (g_open[k].id == id) {
+            Pending p = g_open[k];
+            g_open.erase(g_open.begin() + (long)k);
+            (void)hipEventRecord(p.stop, stream);
+            g_pending.push_back(p);
+            return;
+        }
+    }
+}
+
+} // namespace hdqt
+
+extern "C" {
+
+int hdqt_profile_enable(int on)
+{
+    std::lock_guard<std::mutex> lock(hdqt::g_mu);
+    hdqt::g_enabled = (on != 0);
+    return HDQT_OK;
+}
+
+int hdqt_profile_collect(hdqt_kernel_time_t* rows, int max_rows)
+{
+    std::lock_guard<std::mutex> lock(hdqt::g_mu);
+    double total[hdqt::K_COUNT] = {0};
+    long launches[hdqt::K_COUNT] = {0};
+    for (const hdqt::Pending& p : hdqt::g_pending) {
+        float ms = 0.0f;
+        if (hipEventSynchronize(p.stop) == hipSuccess &&
+            hipEventElapsedTime(&ms, p.start, p.stop) == hipSuccess) {
+            total[p.id] += ms;
+            launches[p.id] += 1;
+        }
+        (void)hipEventDestroy(p.start);
+        (void)hipEventDestroy(p.stop);
+    }
+    hdqt::g_pending.clear();
+    int n = 0;
+    for (int id = 0; id < hdqt::K_COUNT; ++id) {
+        if (!launches[id]) continue;
+        if (rows && n < max_rows) {
+            strncpy(rows[n].name, hdqt::kernel_name(id), sizeof(rows[n].name) - 1);
+            rows[n].name[sizeof(rows[n].name) - 1] = 0;
+            rows[n].launches = launches[id];
+            rows[n].total_ms = total[id];
+        }
+        ++n;
+    }
+    return n;
+}
+
+} // extern "C"

@@ -411,6 +411,7 @@ int clamp_grid(int64_t blocks, int64_t cap)
 hipError_t launch_fill_u32(uint32_t* p, int64_t count, uint32_t value, hipStream_t stream)
 {
     const int grid = clamp_grid((count + 255) / 256, 2048);
+    ProfileScope ps(K_FILL, stream);
     hipLaunchKernelGGL(fill_u32_kernel, dim3(grid), dim3(256), 0, stream, p, count, value);
     return hipGetLastError();
 }
@@ -420,30 +421,40 @@ hipError_t launch_quantize(const QuantArgs& q, hipStream_t stream)
     const int64_t D = q.axis ? q.cols : q.rows;
     const int64_t total = q.rows * q.cols;
     // calibration record starts at zero (max of non-negative values)
-    hipLaunchKernelGGL(fill_u32_kernel, dim3(1), dim3(64), 0, stream,
-                       reinterpret_cast<uint32_t*>(q.meta), (int64_t)4, 0u);
-    hipError_t err = hipGetLastError();
+    hipError_t err = launch_fill_u32(reinterpret_cast<uint32_t*>(q.meta), 4, 0u, stream);
     if (err != hipSuccess) return err;
 
     if (D & 1) {   // odd contraction length: block order is 1
         const int grid1 = clamp_grid((total + kThreads - 1) / kThreads, 4096);
-        hipLaunchKernelGGL(absmax_plain_kernel, dim3(grid1), dim3(kThreads), 0, stream, q);
+        {
+            ProfileScope ps(K_PLAIN_ABSMAX, stream);
+            hipLaunchKernelGGL(absmax_plain_kernel, dim3(grid1), dim3(kThreads), 0, stream, q);
+        }
         const int64_t lines = q.axis ? q.rows : q.cols;
         const int64_t bytes = lines * ((q.b <= 4) ? ((D + 1) >> 1) : D);
         const int grid2 = clamp_grid((bytes + kThreads - 1) / kThreads, 4096);
+        ProfileScope ps(K_PLAIN_QUANT, stream);
         hipLaunchKernelGGL(quant_plain_kernel, dim3(grid2), dim3(kThreads), 0, stream, q);
         return hipGetLastError();
     }
     if (q.axis == 1) {
         const int64_t nchunks = (total + 7) >> 3;
         const int grid = clamp_grid((nchunks + kThreads - 1) / kThreads, 256 * 16);
-        hipLaunchKernelGGL(fwht_row_kernel<false>, dim3(grid), dim3(kThreads), 0, stream, q);
+        {
+            ProfileScope ps(K_ROW_ABSMAX, stream);
+            hipLaunchKernelGGL(fwht_row_kernel<false>, dim3(grid), dim3(kThreads), 0, stream, q);
+        }
+        ProfileScope ps(K_ROW_QUANT, stream);
         hipLaunchKernelGGL(fwht_row_kernel<true>, dim3(grid), dim3(kThreads), 0, stream, q);
         return hipGetLastError();
     }
     const dim3 grid((unsigned)((q.cols + kColTileCols - 1) / kColTileCols),
                     (unsigned)((D + kColTileRows - 1) / kColTileRows));
-    hipLaunchKernelGGL(fwht_col_kernel<false>, grid, dim3(kThreads), 0, stream, q);
+    {
+        ProfileScope ps(K_COL_ABSMAX, stream);
+        hipLaunchKernelGGL(fwht_col_kernel<false>, grid, dim3(kThreads), 0, stream, q);
+    }
+    ProfileScope ps(K_COL_QUANT, stream);
     hipLaunchKernelGGL(fwht_col_kernel<true>, grid, dim3(kThreads), 0, stream, q);
     return hipGetLastError();
 }
