@@ -67,6 +67,8 @@ enum KernelId {
     K_FILL = 0, K_ROW_ABSMAX, K_ROW_QUANT, K_COL_ABSMAX, K_COL_QUANT, K_PLAIN_ABSMAX,
     K_PLAIN_QUANT, K_GEMM_ALIGNED, K_GEMM_GENERIC, K_DEQUANT, K_GEMM_I4, K_COUNT
 };
+bool quantize_fast_eligible(const QuantArgs& q);
+hipError_t launch_quantize_fast(const QuantArgs& q, hipStream_t stream);
 bool gemm_fast_eligible(const GemmArgs& g);
 hipError_t launch_gemm_fast(const GemmArgs& g, hipStream_t stream);
 const char* kernel_name(int id);

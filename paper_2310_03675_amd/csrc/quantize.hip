@@ -77,7 +77,11 @@ __device__ __forceinline__ void block_atomic_max(float m, uint32_t* target, floa
     if (threadIdx.x == 0) {
         float r = smem[0];
         for (int w = 1; w < kThreads / kWave; ++w) r = fmaxf(r, smem[w]);
-        atomicMax(target, __float_as_uint(r));
+        // all workgroups target one word and atomics on one address are serialised:
+        // skip the ones that cannot raise the value
+        const uint32_t bits = __float_as_uint(r);
+        if (bits > __hip_atomic_load(target, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT))
+            atomicMax(target, bits);
     }
 }
 
@@ -423,6 +427,7 @@ hipError_t launch_quantize(const QuantArgs& q, hipStream_t stream)
     // calibration record starts at zero (max of non-negative values)
     hipError_t err = launch_fill_u32(reinterpret_cast<uint32_t*>(q.meta), 4, 0u, stream);
     if (err != hipSuccess) return err;
+    if (quantize_fast_eligible(q)) return launch_quantize_fast(q, stream);
 
     if (D & 1) {   // odd contraction length: block order is 1
         const int grid1 = clamp_grid((total + kThreads - 1) / kThreads, 4096);
