@@ -94,7 +94,7 @@ def main():
     ap.add_argument("--workload", default="resnet_k1152", choices=sorted(WORKLOADS))
     ap.add_argument("--s", type=int, default=32, help="tile length along the contraction")
     ap.add_argument("--acc-bits", type=int, default=8)
-    ap.add_argument("--cpu-rows", type=int, default=8192, help="rows of the oracle's sample")
+    ap.add_argument("--cpu-rows", type=int, default=65536, help="rows of the oracle's sample")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--calib-copy", action="store_true",
                     help="also run one plain 256 MiB device copy (counter calibration for rocprofv3 --pmc)")
@@ -132,16 +132,26 @@ def main():
         torch.cuda.synchronize()
         del a, c
 
+    # ---- timed region: K steps, no instrumentation
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
-    B.profile_enable(True)
-    B.profile_collect()
     t0 = time.perf_counter()
     for _ in range(args.steps):
         step()
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
+
+    # ---- the same K steps again with the library's per-kernel HIP events switched on
+    # (two events per launch on the launch stream; they cost a few microseconds per
+    # launch, which is why the figure above is taken without them)
+    B.profile_enable(True)
+    B.profile_collect()
+    t1 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    dt_events = time.perf_counter() - t1
     B.profile_enable(False)
     kern = B.profile_collect()
 
@@ -149,51 +159,54 @@ def main():
     ops_step = 3 * 2.0 * M * K * N
     value = ops_step / (dt / args.steps) / 1e12
 
-    # ---- per-kernel table (HIP events of the timed region)
-    kernels = {name: {"launches": l, "avg_us": tot / l * 1e3, "share": tot / (dt * 1e3)}
-               for name, (l, tot) in kern.items()}
-    dominant = max(kern, key=lambda k: kern[k][1])
-    # algorithmic bytes per launch of the quantization kernels: the X tensor is the
-    # large one; per launch the kernel sees one of X, W, G, so average over its launches
+    # ---- per-kernel table.  Algorithmic bytes / operations of one step, per kernel:
+    #   absmax pass: 4 B read per element; quantize pass: 4 B read + 0.5 B written;
+    #   matmul: packed operands read once (0.5 B per code) + fp32 output written once,
+    #   2*M*K*N operations each.
     elems = {"X": M * K, "W": K * N, "G": M * N}
     per_elem = {"absmax": 4.0, "quant": 4.0 + 0.5}
-    # tensors each kernel processes in one step (axis 1 -> row kernels, axis 0 -> col kernels)
-    seen = {"fwht_row": ["X", "G", "W"],      # X (fwd), G and W (bwd_input)
-            "fwht_col": ["W", "X", "G"]}      # W (fwd), X and G (bwd_weight)
-    roof_all = {}
+    seen = {"fwht_row": ["X", "G", "W"],      # axis 1: X (fwd), G and W (bwd_input)
+            "fwht_col": ["W", "X", "G"]}      # axis 0: W (fwd), X and G (bwd_weight)
+    gemm_bytes_step = (0.5 * (M * K + K * N) + 4.0 * M * N) + (0.5 * (M * N + K * N) + 4.0 * M * K) \
+        + (0.5 * (M * K + M * N) + 4.0 * K * N)
+    kernels, roof_all = {}, {}
     for name, (l, tot) in kern.items():
-        for fam in seen:
-            if name.startswith(fam):
-                kind = "absmax" if name.endswith("absmax") else "quant"
-                bytes_per_launch = per_elem[kind] * sum(elems[t] for t in seen[fam]) / len(seen[fam])
-                avg_s = tot / l * 1e-3
-                roof_all[name] = {"bound": "hbm", "achieved": bytes_per_launch / avg_s / 1e9,
-                                  "peak": HBM_PEAK_GBPS, "unit": "GB/s",
-                                  "frac": bytes_per_launch / avg_s / 1e9 / HBM_PEAK_GBPS,
-                                  "traffic": None}
-    gemm_names = [k for k in kern if k.startswith("gemm")]
-    gemm_ms = sum(kern[k][1] for k in gemm_names) + kern.get("dequant", (0, 0.0))[1]
+        avg_s = tot / l * 1e-3
+        kernels[name] = {"launches_per_step": l / args.steps, "avg_us": avg_s * 1e6,
+                         "us_per_step": tot / args.steps * 1e3}
+        fam = name[:8]
+        if fam in seen:
+            kind = "absmax" if name.endswith("absmax") else "quant"
+            bytes_step = per_elem[kind] * sum(elems[t] for t in seen[fam])
+            gbps = bytes_step * args.steps / (tot * 1e-3) / 1e9
+            roof_all[name] = {"bound": "hbm", "achieved": gbps, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                              "frac": gbps / HBM_PEAK_GBPS, "traffic": None,
+                              "algorithmic_bytes_per_launch": bytes_step / (l / args.steps)}
+        elif name.startswith("gemm"):
+            tops = ops_step * args.steps / (tot * 1e-3) / 1e12
+            roof_all[name] = {"bound": "mfma", "achieved": tops, "peak": INT8_MFMA_PEAK_TOPS,
+                              "unit": "TOP/s", "frac": tops / INT8_MFMA_PEAK_TOPS, "traffic": None,
+                              "algorithmic_ops_per_launch": ops_step / (l / args.steps),
+                              "hbm_GBps": gemm_bytes_step * args.steps / (tot * 1e-3) / 1e9}
+    dominant = max(roof_all, key=lambda k: kern[k][1])
+    roofline = dict(roof_all[dominant], kernel=dominant)
+    gemm_ms = sum(tot for name, (l, tot) in kern.items() if name.startswith("gemm") or name == "dequant")
     gemm_tops = ops_step * args.steps / (gemm_ms * 1e-3) / 1e12 if gemm_ms else None
-    roofline = roof_all.get(dominant)
-    if roofline is None:       # the matmul kernel dominates
-        roofline = {"bound": "mfma", "achieved": gemm_tops, "peak": INT8_MFMA_PEAK_TOPS,
-                    "unit": "TOP/s", "frac": gemm_tops / INT8_MFMA_PEAK_TOPS, "traffic": None}
-    roofline = dict(roofline, kernel=dominant)
     quant_ms = sum(tot for name, (l, tot) in kern.items() if name.startswith("fwht"))
     quant_bytes = args.steps * 2 * (per_elem["absmax"] + per_elem["quant"]) * sum(elems.values())
     line = {
         "metric": METRIC, "value": value, "unit": "TOPS", "n_gpus": 1, "steps": args.steps,
         "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": True,
-        "scaling": "weak", "vs_baseline": None, "dtype": "int8",
-        "data": "synthetic",
+        "scaling": "weak", "vs_baseline": None, "dtype": "int8", "data": "synthetic",
         "config": {"workload": f"{args.workload}: {layer.name} (M={M}, K={K}, N={N}), one training "
                                f"step = fwd + bwd_input + bwd_weight",
                    "had_block": n, "input_bits": 4, "acc_bits": args.acc_bits, "s": args.s,
                    "rounding": "G stochastic, X and W nearest"},
         "roofline": roofline,
         "gemm": {"tops": gemm_tops, "frac_of_int8_mfma_peak": (gemm_tops or 0) / INT8_MFMA_PEAK_TOPS,
-                 "ms_per_step": gemm_ms / args.steps},
+                 "us_per_step": gemm_ms / args.steps * 1e3},
         "fwht_quant_GBps": quant_bytes / (quant_ms * 1e-3) / 1e9 if quant_ms else None,
+        "ms_per_step_with_kernel_events": dt_events / args.steps * 1e3,
         "kernels": kernels,
         "roofline_all": roof_all,
     }

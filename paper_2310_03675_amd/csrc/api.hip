@@ -118,6 +118,8 @@ int choose_splits(int64_t RA, int64_t RB, int64_t n_tiles)
     return want < 1 ? 1 : (int)want;
 }
 
+constexpr size_t kMetaBytes = (sizeof(hdqt::QMeta) + 255) / 256 * 256;
+
 int run_quantize(const float* T, int64_t rows, int64_t cols, int axis, int n_eff,
                  const hdqt_operand_t* op, uint64_t seed, hdqt::QMeta* meta, void* codes,
                  float* scale_out, hipStream_t stream)
@@ -133,9 +135,10 @@ int run_quantize(const float* T, int64_t rows, int64_t cols, int axis, int n_eff
     return e == hipSuccess ? HDQT_OK : hip_fail(e);
 }
 
-int run_gemm_codes(const void* qA, const void* qB, int bA, int bB, const float* scaleA,
-                   const float* scaleB, int64_t RA, int64_t RB, int64_t D, int n_eff, int acc_bits,
-                   int64_t s, float* out, int32_t* acc_out, int32_t* acc_ws, hipStream_t stream)
+// Resolve tile length, accumulator range and the split of the contraction.
+hdqt::GemmArgs plan_gemm(const void* qA, const void* qB, int bA, int bB, const float* scaleA,
+                         const float* scaleB, int64_t RA, int64_t RB, int64_t D, int n_eff,
+                         int acc_bits, int64_t s, float* out, int32_t* acc_out)
 {
     hdqt::GemmArgs g{};
     g.qA = static_cast<const uint8_t*>(qA); g.qB = static_cast<const uint8_t*>(qB);
@@ -152,17 +155,27 @@ int run_gemm_codes(const void* qA, const void* qB, int bA, int bB, const float* 
     g.splits = choose_splits(RA, RB, g.n_tiles);
     g.tiles_per_split = (g.n_tiles + g.splits - 1) / g.splits;
     g.splits = (int)((g.n_tiles + g.tiles_per_split - 1) / g.tiles_per_split);
+    return g;
+}
+
+// With a split contraction the workgroups add their partial totals into an
+// int32 buffer (acc_out, or the workspace when the caller wants no accumulators)
+// that must be zero beforehand; the dequantization is then a pass of its own.
+int run_planned_gemm(hdqt::GemmArgs g, int32_t* acc_ws, bool target_is_zero, hipStream_t stream)
+{
     hipError_t e;
     if (g.splits > 1) {
-        int32_t* target = acc_out ? acc_out : acc_ws;
+        int32_t* target = g.acc_out ? g.acc_out : acc_ws;
         if (!target) return HDQT_EWORKSPACE;
         g.acc_out = target;
-        e = hdqt::launch_fill_u32(reinterpret_cast<uint32_t*>(target), RA * RB, 0u, stream);
-        if (e != hipSuccess) return hip_fail(e);
+        if (!target_is_zero) {
+            e = hdqt::launch_zero2(reinterpret_cast<uint32_t*>(target), g.RA * g.RB, nullptr, 0, stream);
+            if (e != hipSuccess) return hip_fail(e);
+        }
         e = hdqt::launch_gemm(g, stream);
         if (e != hipSuccess) return hip_fail(e);
-        if (out) {
-            e = hdqt::launch_dequant(target, RA * RB, scaleA, scaleB, g.inv_n, out, stream);
+        if (g.out) {
+            e = hdqt::launch_dequant(target, g.RA * g.RB, g.scaleA, g.scaleB, g.inv_n, g.out, stream);
             if (e != hipSuccess) return hip_fail(e);
         }
         return HDQT_OK;
@@ -185,21 +198,26 @@ int run_gemm(int kind, const float* P, const float* Q, float* out, int64_t M, in
     orient(kind, M, K, N, &o);
     hipStream_t stream = static_cast<hipStream_t>(stream_v);
     char* base = static_cast<char*>(ws);
-    // the two calibration records are 16-byte structs whose `scale` member sits at
-    // the offsets the layout reports
-    hdqt::QMeta* metaA = reinterpret_cast<hdqt::QMeta*>(base + L.scaleA - offsetof(hdqt::QMeta, scale));
-    hdqt::QMeta* metaB = reinterpret_cast<hdqt::QMeta*>(base + L.scaleB - offsetof(hdqt::QMeta, scale));
+    hdqt::QMeta* metaA = reinterpret_cast<hdqt::QMeta*>(base + L.scaleA);
+    hdqt::QMeta* metaB = reinterpret_cast<hdqt::QMeta*>(base + L.scaleB);
     void* codesA = base + L.codesA;
     void* codesB = base + L.codesB;
     int32_t* acc_ws = reinterpret_cast<int32_t*>(base + L.acc);
+    hdqt::GemmArgs g = plan_gemm(codesA, codesB, prm->A.b, prm->B.b, &metaA->scale, &metaB->scale,
+                                 o.RA, o.RB, o.D, L.n_eff, prm->acc_bits, prm->s, out, acc_out);
+    // one launch clears both calibration records (they are adjacent) and, when the
+    // contraction is split, the accumulation target
+    uint32_t* acc_target = g.splits > 1 ? reinterpret_cast<uint32_t*>(acc_out ? acc_out : acc_ws) : nullptr;
+    hipError_t e = hdqt::launch_zero2(reinterpret_cast<uint32_t*>(metaA), (int64_t)(2 * kMetaBytes / 4),
+                                      acc_target, acc_target ? o.RA * o.RB : 0, stream);
+    if (e != hipSuccess) return hip_fail(e);
     rc = run_quantize(P, o.a_rows, o.a_cols, o.a_axis, L.n_eff, &prm->A, prm->seed, metaA, codesA,
                       nullptr, stream);
     if (rc) return rc;
     rc = run_quantize(Q, o.b_rows, o.b_cols, o.b_axis, L.n_eff, &prm->B, prm->seed, metaB, codesB,
                       nullptr, stream);
     if (rc) return rc;
-    return run_gemm_codes(codesA, codesB, prm->A.b, prm->B.b, &metaA->scale, &metaB->scale, o.RA,
-                          o.RB, o.D, L.n_eff, prm->acc_bits, prm->s, out, acc_out, acc_ws, stream);
+    return run_planned_gemm(g, acc_ws, true, stream);
 }
 
 } // namespace
@@ -216,7 +234,7 @@ int hdqt_n_eff(int64_t D, int had_block)
 
 int64_t hdqt_codes_pitch(int64_t D, int b) { return b <= 4 ? (D + 1) / 2 : D; }
 
-size_t hdqt_quantize_workspace_size(void) { return 256; }
+size_t hdqt_quantize_workspace_size(void) { return kMetaBytes; }
 
 int hdqt_workspace_layout(int gemm_kind, int64_t M, int64_t K, int64_t N,
                           const hdqt_params_t* params, hdqt_ws_layout_t* layout)
@@ -228,10 +246,11 @@ int hdqt_workspace_layout(int gemm_kind, int64_t M, int64_t K, int64_t N,
     L.RA = o.RA; L.RB = o.RB; L.D = o.D;
     L.n_eff = hdqt_n_eff(o.D, params->had_block);
     size_t off = 0;
-    L.scaleA = off + offsetof(hdqt::QMeta, scale);
-    off += 128;
-    L.scaleB = off + offsetof(hdqt::QMeta, scale);
-    off += 128;
+    // two calibration records, adjacent; `scale` is the first member of each
+    L.scaleA = off;
+    off += kMetaBytes;
+    L.scaleB = off;
+    off += kMetaBytes;
     L.codesA = off;
     off = align_up(off + (size_t)(o.RA * hdqt_codes_pitch(o.D, params->A.b)), 256);
     L.codesB = off;
@@ -264,6 +283,9 @@ int hdqt_quantize(const float* T, int64_t rows, int64_t cols, int axis, int had_
     if (misaligned(T) || misaligned(codes_out) || misaligned(workspace)) return HDQT_EALIGN;
     if ((reinterpret_cast<uintptr_t>(scale_out) & 3u) != 0) return HDQT_EALIGN;
     const int64_t D = axis ? cols : rows;
+    const hipError_t e = hdqt::launch_zero2(static_cast<uint32_t*>(workspace), hdqt::kQMetaDwords,
+                                            nullptr, 0, static_cast<hipStream_t>(stream));
+    if (e != hipSuccess) return hip_fail(e);
     return run_quantize(T, rows, cols, axis, hdqt_n_eff(D, had_block), op, seed,
                         static_cast<hdqt::QMeta*>(workspace), codes_out, scale_out,
                         static_cast<hipStream_t>(stream));
@@ -290,8 +312,9 @@ int hdqt_gemm_codes(const void* qA, const void* qB, int bA, int bB, const float*
     int32_t* acc_ws = nullptr;
     if (workspace && workspace_bytes >= (size_t)(RA * RB) * sizeof(int32_t))
         acc_ws = static_cast<int32_t*>(workspace);
-    return run_gemm_codes(qA, qB, bA, bB, scaleA, scaleB, RA, RB, D, n_eff, acc_bits, s, out,
-                          acc_out, acc_ws, static_cast<hipStream_t>(stream));
+    return run_planned_gemm(plan_gemm(qA, qB, bA, bB, scaleA, scaleB, RA, RB, D, n_eff, acc_bits, s,
+                                      out, acc_out),
+                            acc_ws, false, static_cast<hipStream_t>(stream));
 }
 
 int hdqt_gemm_fwd(const float* X, const float* W, float* Z, int64_t M, int64_t K, int64_t N,

@@ -9,14 +9,20 @@ namespace hdqt {
 constexpr int kMaxHadamard = 256;   // largest supported block order
 constexpr int kWave = 64;
 
-// Per-operand calibration record in the workspace.  `amax_bits` is the
-// bit pattern of max|y| (non-negative floats order like unsigned integers, so
-// the reduction is an integer atomicMax); `scale` is the value of one code step.
+// Per-operand calibration record in the workspace.  max|y| is reduced with
+// integer atomicMax on the bit patterns (non-negative floats order like unsigned
+// integers).  Atomics on one address are serialised, so the workgroups spread
+// over 64 slots, each on its own 128-byte line; pass 2 reads one slot per lane
+// and finishes the reduction inside the wave.  `scale` is the value of one
+// code step, written by pass 2.
+constexpr int kAmaxSlots = 64;
+constexpr int kAmaxSlotStride = 32;     // dwords
 struct QMeta {
-    uint32_t amax_bits;
     float scale;
-    uint32_t pad[2];
+    uint32_t pad[31];
+    uint32_t amax[kAmaxSlots * kAmaxSlotStride];
 };
+constexpr int64_t kQMetaDwords = sizeof(QMeta) / 4;
 
 // One quantize request, resolved by the host.
 struct QuantArgs {
@@ -57,7 +63,8 @@ struct GemmArgs {
 // Launchers (host).  Each returns the hipError_t of its last launch.
 hipError_t launch_quantize(const QuantArgs& q, hipStream_t stream);
 hipError_t launch_gemm(const GemmArgs& g, hipStream_t stream);
-hipError_t launch_fill_u32(uint32_t* p, int64_t count, uint32_t value, hipStream_t stream);
+// zero a[0, na) and b[0, nb) (b may be null) in one launch
+hipError_t launch_zero2(uint32_t* a, int64_t na, uint32_t* b, int64_t nb, hipStream_t stream);
 hipError_t launch_dequant(const int32_t* acc, int64_t count, const float* scaleA,
                           const float* scaleB, float inv_n, float* out, hipStream_t stream);
 
@@ -135,6 +142,61 @@ __device__ __forceinline__ int quantize_value(float y, float inv, int qmin, int 
     }
     q = fminf(fmaxf(q, (float)qmin), (float)qmax);
     return (int)q;
+}
+
+
+// ---- calibration helpers --------------------------------------------------
+
+__device__ __forceinline__ float wave_max_shfl(float m)
+{
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) m = fmaxf(m, __shfl_xor(m, off, kWave));
+    return m;
+}
+
+// One atomicMax per workgroup (256 threads), into the workgroup's slot, and only
+// if it can raise the slot.  `smem` holds one float per wave.
+__device__ __forceinline__ void block_atomic_max(float m, QMeta* meta, float* smem)
+{
+    m = wave_max_shfl(m);
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    if (lane == 0) smem[wave] = m;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        float r = smem[0];
+        for (int w = 1; w < (int)(blockDim.x >> 6); ++w) r = fmaxf(r, smem[w]);
+        const uint32_t slot = (blockIdx.x + blockIdx.y * gridDim.x) % kAmaxSlots;
+        uint32_t* target = &meta->amax[slot * kAmaxSlotStride];
+        const uint32_t bits = __float_as_uint(r);
+        if (bits > __hip_atomic_load(target, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT))
+            atomicMax(target, bits);
+    }
+}
+
+struct Scaling {
+    float inv;      // alpha * 2^(b-1); 0 for an all-zero tensor (every code is then 0)
+    float scale;    // value of one code step
+};
+
+// Must be reached by whole waves: lane l reads slot l.
+__device__ __forceinline__ Scaling load_scaling(const QMeta* meta, float clip, int b)
+{
+    const float slot = __uint_as_float(meta->amax[(threadIdx.x & 63) * kAmaxSlotStride]);
+    const float amax = wave_max_shfl(slot);
+    const float amax_c = clip * amax;
+    Scaling s;
+    const bool zero = (amax_c == 0.0f);
+    s.inv = zero ? 0.0f : inverse_step(amax_c, b);
+    s.scale = zero ? 0.0f : amax_c / (float)(1 << (b - 1));
+    return s;
+}
+
+__device__ __forceinline__ void publish_scale(const QuantArgs& q, const Scaling& s)
+{
+    if (blockIdx.x == 0 && blockIdx.y == 0 && threadIdx.x == 0) {
+        q.meta->scale = s.scale;
+        if (q.scale_out) *q.scale_out = s.scale;
+    }
 }
 
 } // namespace hdqt

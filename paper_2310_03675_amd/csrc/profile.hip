@@ -25,7 +25,7 @@ std::vector<Pending> g_open;     // begun, not yet ended (per launch, LIFO)
 const char* kernel_name(int id)
 {
     static const char* names[K_COUNT] = {
-        "fill_u32", "fwht_row_absmax", "fwht_row_quant", "fwht_col_absmax", "fwht_col_quant",
+        "zero", "fwht_row_absmax", "fwht_row_quant", "fwht_col_absmax", "fwht_col_quant",
         "plain_absmax", "plain_quant", "gemm_tiled_aligned", "gemm_tiled_generic", "dequant",
         "gemm_i4"};
     return (id >= 0 && id < K_COUNT) ? names[id] : "?";

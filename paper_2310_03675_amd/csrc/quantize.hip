@@ -60,56 +60,6 @@ __device__ __forceinline__ float pair_lanes(float own, int lane, int mask)
     return (lane & mask) ? (other - own) : (own + other);
 }
 
-__device__ __forceinline__ float wave_max(float m)
-{
-#pragma unroll
-    for (int off = 32; off >= 1; off >>= 1)
-        m = fmaxf(m, __shfl_xor(m, off, kWave));
-    return m;
-}
-
-__device__ __forceinline__ void block_atomic_max(float m, uint32_t* target, float* smem)
-{
-    m = wave_max(m);
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    if (lane == 0) smem[wave] = m;
-    __syncthreads();
-    if (threadIdx.x == 0) {
-        float r = smem[0];
-        for (int w = 1; w < kThreads / kWave; ++w) r = fmaxf(r, smem[w]);
-        // all workgroups target one word and atomics on one address are serialised:
-        // skip the ones that cannot raise the value
-        const uint32_t bits = __float_as_uint(r);
-        if (bits > __hip_atomic_load(target, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT))
-            atomicMax(target, bits);
-    }
-}
-
-struct Scaling {
-    float inv;      // alpha * 2^(b-1)
-    float scale;    // value of one code step
-    bool zero;      // all-zero tensor
-};
-
-__device__ __forceinline__ Scaling load_scaling(const QMeta* meta, float clip, int b)
-{
-    Scaling s;
-    const float amax = __uint_as_float(meta->amax_bits);
-    const float amax_c = clip * amax;
-    s.zero = (amax_c == 0.0f);
-    s.inv = s.zero ? 0.0f : inverse_step(amax_c, b);
-    s.scale = s.zero ? 0.0f : amax_c / (float)(1 << (b - 1));
-    return s;
-}
-
-__device__ __forceinline__ void publish_scale(const QuantArgs& q, const Scaling& s)
-{
-    if (blockIdx.x == 0 && blockIdx.y == 0 && threadIdx.x == 0) {
-        q.meta->scale = s.scale;
-        if (q.scale_out) *q.scale_out = s.scale;
-    }
-}
-
 // ---------------------------------------------------------------------------
 // Contraction along rows of the source (axis 1).  Blocks of n consecutive
 // elements never straddle a row (n | cols), so the tensor is one flat array
@@ -166,8 +116,7 @@ __global__ __launch_bounds__(kThreads) void fwht_row_kernel(QuantArgs q)
         int code[8];
 #pragma unroll
         for (int i = 0; i < 8; ++i)
-            code[i] = sc.zero ? 0
-                              : quantize_value(v[i], sc.inv, qmin, qmax, q.stochastic != 0,
+            code[i] = quantize_value(v[i], sc.inv, qmin, qmax, q.stochastic != 0,
                                                sr_halfword(rnd, (uint32_t)i));
         const bool full = (e0 + 8 <= total);
         if (q.b <= 4) {
@@ -194,7 +143,7 @@ __global__ __launch_bounds__(kThreads) void fwht_row_kernel(QuantArgs q)
             }
         }
     }
-    if (!QUANT) block_atomic_max(amax, &q.meta->amax_bits, red);
+    if (!QUANT) block_atomic_max(amax, q.meta, red);
 }
 
 // ---------------------------------------------------------------------------
@@ -285,7 +234,7 @@ __global__ __launch_bounds__(kThreads) void fwht_col_kernel(QuantArgs q)
         for (int j = 0; j < 4; ++j)
 #pragma unroll
             for (int i = 0; i < 8; ++i) amax = fmaxf(amax, fabsf(v[j][i]));
-        block_atomic_max(amax, &q.meta->amax_bits, red);
+        block_atomic_max(amax, q.meta, red);
         return;
     }
 
@@ -311,7 +260,7 @@ __global__ __launch_bounds__(kThreads) void fwht_col_kernel(QuantArgs q)
                 u = sr_halfword(rnd, (uint32_t)(e & 7));
             }
             const int code =
-                sc.zero ? 0 : quantize_value(v[j][i], sc.inv, qmin, qmax, q.stochastic != 0, u);
+                quantize_value(v[j][i], sc.inv, qmin, qmax, q.stochastic != 0, u);
             if (q.b <= 4)
                 packed[j][0] |= ((uint32_t)code & 0xFu) << (4 * i);
             else
@@ -361,7 +310,7 @@ __global__ __launch_bounds__(kThreads) void absmax_plain_kernel(QuantArgs q)
     for (int64_t e = (int64_t)blockIdx.x * kThreads + threadIdx.x; e < total;
          e += (int64_t)gridDim.x * kThreads)
         amax = fmaxf(amax, fabsf(q.T[e]));
-    block_atomic_max(amax, &q.meta->amax_bits, red);
+    block_atomic_max(amax, q.meta, red);
 }
 
 __global__ __launch_bounds__(kThreads) void quant_plain_kernel(QuantArgs q)
@@ -390,18 +339,20 @@ __global__ __launch_bounds__(kThreads) void quant_plain_kernel(QuantArgs q)
                 u = sr_halfword(rnd, (uint32_t)(e & 7));
             }
             const int code =
-                sc.zero ? 0 : quantize_value(q.T[e], sc.inv, qmin, qmax, q.stochastic != 0, u);
+                quantize_value(q.T[e], sc.inv, qmin, qmax, q.stochastic != 0, u);
             byte |= (q.b <= 4) ? (((uint32_t)code & 0xFu) << (4 * h)) : ((uint32_t)code & 0xFFu);
         }
         q.codes[idx] = (uint8_t)byte;
     }
 }
 
-__global__ void fill_u32_kernel(uint32_t* p, int64_t count, uint32_t value)
+__global__ void zero2_kernel(uint32_t* a, int64_t na, uint32_t* b, int64_t nb)
 {
-    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < count;
-         i += (int64_t)gridDim.x * blockDim.x)
-        p[i] = value;
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < na + nb;
+         i += (int64_t)gridDim.x * blockDim.x) {
+        if (i < na) a[i] = 0u;
+        else b[i - na] = 0u;
+    }
 }
 
 int clamp_grid(int64_t blocks, int64_t cap)
@@ -412,21 +363,20 @@ int clamp_grid(int64_t blocks, int64_t cap)
 
 } // namespace
 
-hipError_t launch_fill_u32(uint32_t* p, int64_t count, uint32_t value, hipStream_t stream)
+hipError_t launch_zero2(uint32_t* a, int64_t na, uint32_t* b, int64_t nb, hipStream_t stream)
 {
-    const int grid = clamp_grid((count + 255) / 256, 2048);
+    if (!b) nb = 0;
+    const int grid = clamp_grid((na + nb + 255) / 256, 2048);
     ProfileScope ps(K_FILL, stream);
-    hipLaunchKernelGGL(fill_u32_kernel, dim3(grid), dim3(256), 0, stream, p, count, value);
+    hipLaunchKernelGGL(zero2_kernel, dim3(grid), dim3(256), 0, stream, a, na, b, nb);
     return hipGetLastError();
 }
 
+// Pass 1 and pass 2 of one tensor.  The calibration record must be zero.
 hipError_t launch_quantize(const QuantArgs& q, hipStream_t stream)
 {
     const int64_t D = q.axis ? q.cols : q.rows;
     const int64_t total = q.rows * q.cols;
-    // calibration record starts at zero (max of non-negative values)
-    hipError_t err = launch_fill_u32(reinterpret_cast<uint32_t*>(q.meta), 4, 0u, stream);
-    if (err != hipSuccess) return err;
     if (quantize_fast_eligible(q)) return launch_quantize_fast(q, stream);
 
     if (D & 1) {   // odd contraction length: block order is 1

@@ -109,45 +109,51 @@ __device__ __forceinline__ float wave_max(float m)
     return m;
 }
 
-// One atomicMax per workgroup, and only if it can raise the current value: all
-// workgroups target one word, and atomics on one address are serialised.
-__device__ __forceinline__ void block_atomic_max(float m, uint32_t* target, float* smem)
+// ---- rounding and packing -------------------------------------------------
+// code_word() returns 0x4B400000 + code + offset, offset = 8 (b <= 4) or 128:
+// adding 1.5 * 2^23 (+ offset) to a binary32 value of magnitude below 2^22 rounds
+// it to the nearest integer, ties to even, and leaves that integer in the low
+// mantissa bits.  The clamp is applied first; clamp and rounding commute because
+// the bounds are integers.  The stochastic path adds the same constant to an
+// integer, which is exact.
+constexpr float kMagic = 12582912.0f;          // 1.5 * 2^23, bit pattern 0x4B400000
+constexpr uint32_t kMagicBits = 0x4B400000u;
+
+template <bool STOCH>
+__device__ __forceinline__ uint32_t code_word(float y, float inv, float qminf, float qmaxf,
+                                              float magic, uint32_t u16)
 {
-    m = wave_max(m);
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    if (lane == 0) smem[wave] = m;
-    __syncthreads();
-    if (threadIdx.x == 0) {
-        float r = smem[0];
-        for (int w = 1; w < kThreads / kWave; ++w) r = fmaxf(r, smem[w]);
-        const uint32_t bits = __float_as_uint(r);
-        if (bits > __hip_atomic_load(target, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT))
-            atomicMax(target, bits);
-    }
+    const float v = y * inv;
+    if (!STOCH) return __float_as_uint(__builtin_amdgcn_fmed3f(v, qminf, qmaxf) + magic);
+    const float fl = floorf(v);
+    const float frac = v - fl;
+    const float up = fl + (((float)u16 < frac * 65536.0f) ? 1.0f : 0.0f);
+    return __float_as_uint(__builtin_amdgcn_fmed3f(up, qminf, qmaxf) + magic);
 }
 
-struct Scaling {
-    float inv, scale;
-    bool zero;
-};
-
-__device__ __forceinline__ Scaling load_scaling(const QMeta* meta, float clip, int b)
+constexpr uint32_t pack_bias(int fields, int width)
 {
-    Scaling s;
-    const float amax = __uint_as_float(meta->amax_bits);
-    const float amax_c = clip * amax;
-    s.zero = (amax_c == 0.0f);
-    s.inv = s.zero ? 0.0f : inverse_step(amax_c, b);
-    s.scale = s.zero ? 0.0f : amax_c / (float)(1 << (b - 1));
-    return s;
+    uint32_t c = 0;
+    for (int i = 0; i < fields; ++i) c += kMagicBits << (width * i);
+    return c;
 }
 
-__device__ __forceinline__ void publish_scale(const QuantArgs& q, const Scaling& s)
+// eight words -> eight two's-complement nibbles (low nibble = first code)
+__device__ __forceinline__ uint32_t pack_nibbles(const uint32_t w[8])
 {
-    if (blockIdx.x == 0 && blockIdx.y == 0 && threadIdx.x == 0) {
-        q.meta->scale = s.scale;
-        if (q.scale_out) *q.scale_out = s.scale;
-    }
+    uint32_t acc = w[0];
+#pragma unroll
+    for (int i = 1; i < 8; ++i) acc += w[i] << (4 * i);
+    return (acc - pack_bias(8, 4)) ^ 0x88888888u;
+}
+
+// four words -> four two's-complement bytes
+__device__ __forceinline__ uint32_t pack_bytes(const uint32_t w[4])
+{
+    uint32_t acc = w[0];
+#pragma unroll
+    for (int i = 1; i < 4; ++i) acc += w[i] << (8 * i);
+    return (acc - pack_bias(4, 8)) ^ 0x80808080u;
 }
 
 // ---------------------------------------------------------------------------
@@ -155,118 +161,174 @@ __device__ __forceinline__ void publish_scale(const QuantArgs& q, const Scaling&
 // consecutive elements, so blocks of up to 512 never leave a wave (the library
 // caps the order at 256).  Requires an even row length when b <= 4.
 // ---------------------------------------------------------------------------
-constexpr int kRowUnroll = 2;
 
-template <bool QUANT, bool STOCH>
+struct RowCtx {
+    const QuantArgs* q;
+    int64_t total;
+    int log2n;
+    float qminf, qmaxf, magic, inv;
+    uint32_t flip1, flip2, flip4, flip8;
+};
+
+// One iteration of a workgroup: kRowUnroll chunks per thread, chunk index
+// base + u*stride + thread.  GUARD = false: every chunk of the iteration lies
+// wholly inside the tensor, loads and stores are unconditional.
+template <int U>
+struct RowRegs {
+    float v[U][8];
+};
+
+template <int U, bool GUARD>
+__device__ __forceinline__ void row_load(RowRegs<U>& r, const RowCtx& x, int64_t base, int64_t stride)
+{
+    const QuantArgs& q = *x.q;
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+        const int64_t e0 = (base + u * stride + threadIdx.x) << 3;
+        if (!GUARD || e0 + 8 <= x.total) {
+            const float4 lo = *reinterpret_cast<const float4*>(q.T + e0);
+            const float4 hi = *reinterpret_cast<const float4*>(q.T + e0 + 4);
+            r.v[u][0] = lo.x; r.v[u][1] = lo.y; r.v[u][2] = lo.z; r.v[u][3] = lo.w;
+            r.v[u][4] = hi.x; r.v[u][5] = hi.y; r.v[u][6] = hi.z; r.v[u][7] = hi.w;
+        } else {
+#pragma unroll
+            for (int i = 0; i < 8; ++i) r.v[u][i] = (e0 + i < x.total) ? q.T[e0 + i] : 0.0f;
+        }
+    }
+}
+
+// Transform and reduce / quantize the chunks loaded by row_load for `base`.
+template <int U, bool QUANT, bool STOCH, bool GUARD>
+__device__ __forceinline__ void row_compute(RowRegs<U>& r, const RowCtx& x, int64_t base, int64_t stride,
+                                            float& amax)
+{
+    const QuantArgs& q = *x.q;
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+        float* v = r.v[u];
+        butterfly8(v, x.log2n);
+        if (x.log2n > 3) {
+#pragma unroll
+            for (int i = 0; i < 8; ++i) v[i] = stage_dpp<1>(v[i], x.flip1);
+        }
+        if (x.log2n > 4) {
+#pragma unroll
+            for (int i = 0; i < 8; ++i) v[i] = stage_dpp<2>(v[i], x.flip2);
+        }
+        if (x.log2n > 5) {
+#pragma unroll
+            for (int i = 0; i < 8; ++i) v[i] = stage_dpp<4>(v[i], x.flip4);
+        }
+        if (x.log2n > 6) {
+#pragma unroll
+            for (int i = 0; i < 8; ++i) v[i] = stage_dpp<8>(v[i], x.flip8);
+        }
+        if (x.log2n > 7) {
+#pragma unroll
+            for (int i = 0; i < 8; i += 2) stage_swap<false>(v[i], v[i + 1]);
+        }
+    }
+    if (!QUANT) {
+#pragma unroll
+        for (int u = 0; u < U; ++u)
+#pragma unroll
+            for (int i = 0; i < 8; ++i) amax = fmaxf(amax, fabsf(r.v[u][i]));
+        return;
+    }
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+        const int64_t c = base + u * stride + threadIdx.x;
+        const int64_t e0 = c << 3;
+        if (GUARD && e0 >= x.total) continue;
+        uint32_t rnd[4] = {0, 0, 0, 0};
+        if (STOCH)
+            philox4x32_10((uint32_t)c, (uint32_t)(c >> 32), q.tensor_id, 0u, q.seed_lo, q.seed_hi, rnd);
+        uint32_t cw[8];
+#pragma unroll
+        for (int i = 0; i < 8; ++i)
+            cw[i] = code_word<STOCH>(r.v[u][i], x.inv, x.qminf, x.qmaxf, x.magic,
+                                     sr_halfword(rnd, (uint32_t)i));
+        const bool full = !GUARD || (e0 + 8 <= x.total);
+        if (q.b <= 4) {
+            const uint32_t w = pack_nibbles(cw);
+            if (full) {
+                reinterpret_cast<uint32_t*>(q.codes)[c] = w;
+            } else {
+                for (int i = 0; i < 8 && e0 + i < x.total; i += 2)
+                    q.codes[(e0 + i) >> 1] = (uint8_t)(w >> (4 * i));
+            }
+        } else {
+            const uint32_t w0 = pack_bytes(cw), w1 = pack_bytes(cw + 4);
+            if (full) {
+                reinterpret_cast<uint2*>(q.codes)[c] = make_uint2(w0, w1);
+            } else {
+                for (int i = 0; i < 8 && e0 + i < x.total; ++i)
+                    q.codes[e0 + i] = (uint8_t)((i < 4 ? w0 : w1) >> (8 * (i & 3)));
+            }
+        }
+    }
+}
+
+template <int U, bool QUANT, bool STOCH>
 __global__ __launch_bounds__(kThreads) void fwht_row_fast_kernel(QuantArgs q)
 {
     __shared__ float red[kThreads / kWave];
-    const int64_t total = q.rows * q.cols;
-    const int64_t nchunks = (total + 7) >> 3;
     const int lane = threadIdx.x & 63;
-    const int log2n = q.log2n;
-    const int qmin = -(1 << (q.b - 1)), qmax = (1 << (q.b - 1)) - 1;
-    const uint32_t flip1 = (uint32_t)(lane & 1) << 31, flip2 = (uint32_t)(lane & 2) << 30,
-                   flip4 = (uint32_t)(lane & 4) << 29, flip8 = (uint32_t)(lane & 8) << 28;
+    RowCtx x;
+    x.q = &q;
+    x.total = q.rows * q.cols;
+    x.log2n = q.log2n;
+    x.qminf = (float)(-(1 << (q.b - 1)));
+    x.qmaxf = (float)((1 << (q.b - 1)) - 1);
+    x.magic = kMagic + (q.b <= 4 ? 8.0f : 128.0f);
+    x.flip1 = (uint32_t)(lane & 1) << 31;
+    x.flip2 = (uint32_t)(lane & 2) << 30;
+    x.flip4 = (uint32_t)(lane & 4) << 29;
+    x.flip8 = (uint32_t)(lane & 8) << 28;
+    x.inv = 0.0f;
+    const int64_t nchunks = (x.total + 7) >> 3;
+    const int64_t nfull = x.total >> 3;
+    // Iteration `it` of the tensor covers chunks [it*256*U, (it+1)*256*U): a contiguous
+    // span per workgroup and iteration, chunk = it*256*U + u*256 + thread.
+    // Pass 2 walks the iterations from the end of the tensor to the start: the part
+    // pass 1 read last is the part most likely still held by the memory-side cache.
+    const int64_t stride = kThreads;
+    const int64_t per_iter = (int64_t)kThreads * U;
+    const int64_t n_iter = (nchunks + per_iter - 1) / per_iter;
+    auto base_of = [&](int64_t it) { return (QUANT ? (n_iter - 1 - it) : it) * per_iter; };
+    auto guarded = [&](int64_t base) { return base + (U - 1) * stride + kThreads > nfull; };
 
-    Scaling sc{};
+    // software pipeline: the loads of the next iteration are issued before the
+    // current one is transformed, so requests stay outstanding during the arithmetic
+    int64_t it = blockIdx.x;
+    RowRegs<U> cur, nxt;
+    bool g_cur = false;
+    if (it < n_iter) {
+        g_cur = guarded(base_of(it));
+        if (g_cur) row_load<U, true>(cur, x, base_of(it), stride);
+        else row_load<U, false>(cur, x, base_of(it), stride);
+    }
     if (QUANT) {
-        sc = load_scaling(q.meta, q.clip, q.b);
+        const Scaling sc = load_scaling(q.meta, q.clip, q.b);
         publish_scale(q, sc);
+        x.inv = sc.inv;
     }
     float amax = 0.0f;
-    const int64_t stride = (int64_t)gridDim.x * kThreads;
-
-    for (int64_t base = (int64_t)blockIdx.x * kThreads; base < nchunks; base += stride * kRowUnroll) {
-        float v[kRowUnroll][8];
-        int64_t cidx[kRowUnroll];
-#pragma unroll
-        for (int u = 0; u < kRowUnroll; ++u) {
-            const int64_t c = base + u * stride + threadIdx.x;
-            cidx[u] = c;
-            const int64_t e0 = c << 3;
-            if (e0 + 8 <= total) {
-                const float4 lo = *reinterpret_cast<const float4*>(q.T + e0);
-                const float4 hi = *reinterpret_cast<const float4*>(q.T + e0 + 4);
-                v[u][0] = lo.x; v[u][1] = lo.y; v[u][2] = lo.z; v[u][3] = lo.w;
-                v[u][4] = hi.x; v[u][5] = hi.y; v[u][6] = hi.z; v[u][7] = hi.w;
-            } else {
-#pragma unroll
-                for (int i = 0; i < 8; ++i) v[u][i] = (e0 + i < total) ? q.T[e0 + i] : 0.0f;
-            }
+    while (it < n_iter) {
+        const int64_t it_next = it + gridDim.x;
+        bool g_nxt = false;
+        if (it_next < n_iter) {
+            g_nxt = guarded(base_of(it_next));
+            if (g_nxt) row_load<U, true>(nxt, x, base_of(it_next), stride);
+            else row_load<U, false>(nxt, x, base_of(it_next), stride);
         }
-#pragma unroll
-        for (int u = 0; u < kRowUnroll; ++u) {
-            butterfly8(v[u], log2n);
-            if (log2n > 3) {
-#pragma unroll
-                for (int i = 0; i < 8; ++i) v[u][i] = stage_dpp<1>(v[u][i], flip1);
-            }
-            if (log2n > 4) {
-#pragma unroll
-                for (int i = 0; i < 8; ++i) v[u][i] = stage_dpp<2>(v[u][i], flip2);
-            }
-            if (log2n > 5) {
-#pragma unroll
-                for (int i = 0; i < 8; ++i) v[u][i] = stage_dpp<4>(v[u][i], flip4);
-            }
-            if (log2n > 6) {
-#pragma unroll
-                for (int i = 0; i < 8; ++i) v[u][i] = stage_dpp<8>(v[u][i], flip8);
-            }
-            if (log2n > 7) {
-#pragma unroll
-                for (int i = 0; i < 8; i += 2) stage_swap<false>(v[u][i], v[u][i + 1]);
-            }
-        }
-        if (!QUANT) {
-#pragma unroll
-            for (int u = 0; u < kRowUnroll; ++u)
-#pragma unroll
-                for (int i = 0; i < 8; ++i) amax = fmaxf(amax, fabsf(v[u][i]));
-            continue;
-        }
-#pragma unroll
-        for (int u = 0; u < kRowUnroll; ++u) {
-            const int64_t c = cidx[u];
-            const int64_t e0 = c << 3;
-            if (e0 >= total) continue;
-            uint32_t rnd[4] = {0, 0, 0, 0};
-            if (STOCH)
-                philox4x32_10((uint32_t)c, (uint32_t)(c >> 32), q.tensor_id, 0u, q.seed_lo,
-                              q.seed_hi, rnd);
-            int code[8];
-#pragma unroll
-            for (int i = 0; i < 8; ++i)
-                code[i] = quantize_value(v[u][i], sc.inv, qmin, qmax, STOCH,
-                                         sr_halfword(rnd, (uint32_t)i));
-            const bool full = (e0 + 8 <= total);
-            if (q.b <= 4) {
-                uint32_t w = 0;
-#pragma unroll
-                for (int i = 0; i < 8; ++i) w |= ((uint32_t)code[i] & 0xFu) << (4 * i);
-                if (full) {
-                    reinterpret_cast<uint32_t*>(q.codes)[c] = w;
-                } else {
-                    for (int i = 0; i < 8 && e0 + i < total; i += 2)
-                        q.codes[(e0 + i) >> 1] = (uint8_t)(w >> (4 * i));
-                }
-            } else {
-                uint32_t w0 = 0, w1 = 0;
-#pragma unroll
-                for (int i = 0; i < 4; ++i) {
-                    w0 |= ((uint32_t)code[i] & 0xFFu) << (8 * i);
-                    w1 |= ((uint32_t)code[i + 4] & 0xFFu) << (8 * i);
-                }
-                if (full) {
-                    reinterpret_cast<uint2*>(q.codes)[c] = make_uint2(w0, w1);
-                } else {
-                    for (int i = 0; i < 8 && e0 + i < total; ++i) q.codes[e0 + i] = (uint8_t)code[i];
-                }
-            }
-        }
+        if (g_cur) row_compute<U, QUANT, STOCH, true>(cur, x, base_of(it), stride, amax);
+        else row_compute<U, QUANT, STOCH, false>(cur, x, base_of(it), stride, amax);
+        cur = nxt;
+        g_cur = g_nxt;
+        it = it_next;
     }
-    if (!QUANT) block_atomic_max(amax, &q.meta->amax_bits, red);
+    if (!QUANT) block_atomic_max(amax, q.meta, red);
 }
 
 // ---------------------------------------------------------------------------
@@ -280,13 +342,14 @@ struct ColStep {
     float v[4][8];       // [column][row]
 };
 
+template <bool GUARD>
 __device__ __forceinline__ void col_load(ColStep& s, const float* T, int64_t D, int64_t cols,
                                          int64_t row0, int64_t col0)
 {
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
         float4 x = make_float4(0.f, 0.f, 0.f, 0.f);
-        if (row0 + i < D && col0 < cols)
+        if (!GUARD || (row0 + i < D && col0 < cols))
             x = *reinterpret_cast<const float4*>(T + (row0 + i) * cols + col0);
         s.v[0][i] = x.x; s.v[1][i] = x.y; s.v[2][i] = x.z; s.v[3][i] = x.w;
     }
@@ -316,37 +379,26 @@ __device__ __forceinline__ void col_transform(ColStep& s, int log2n, uint32_t fl
     }
 }
 
-template <bool QUANT, bool STOCH, int SUBS>
-__global__ __launch_bounds__(kThreads) void fwht_col_fast_kernel(QuantArgs q, int WC)
+// Load, transform and (QUANT) quantize the wave's strip; packed codes go to the
+// wave's LDS staging area `stage_w` ([32 columns][pitch dwords]); returns max|y|.
+template <bool QUANT, bool STOCH, bool B4, int SUBS, bool GUARD>
+__device__ __forceinline__ float col_strip(const QuantArgs& q, float inv, int64_t tile_row0,
+                                           int64_t col0, int lane, uint32_t* stage_w, int stage_pitch)
 {
-    __shared__ float red[kThreads / kWave];
-    __shared__ uint32_t stage[QUANT ? 4 : 1][32][QUANT ? (SUBS * 16 + 1) : 1];
-
     const int64_t D = q.rows, cols = q.cols;
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int cg = lane & 7, rg = lane >> 3;
-    const int wc = wave % WC, wr = wave / WC;
-    const int WR = 4 / WC;
-    const int64_t tile_row0 = ((int64_t)blockIdx.y * WR + wr) * (64 * SUBS);
-    const int64_t strip_col0 = ((int64_t)blockIdx.x * WC + wc) * 32;
-    const int64_t col0 = strip_col0 + cg * 4;
     const int log2n = q.log2n;
-    const int qmin = -(1 << (q.b - 1)), qmax = (1 << (q.b - 1)) - 1;
+    const float qminf = (float)(-(1 << (q.b - 1))), qmaxf = (float)((1 << (q.b - 1)) - 1);
+    const float magic = kMagic + (B4 ? 8.0f : 128.0f);
     const uint32_t flip8 = (uint32_t)(lane & 8) << 28;
-
-    Scaling sc{};
-    if (QUANT) {
-        sc = load_scaling(q.meta, q.clip, q.b);
-        publish_scale(q, sc);
-    }
     float amax = 0.0f;
 
     ColStep cur, nxt;
-    col_load(cur, q.T, D, cols, tile_row0 + rg * 8, col0);
+    col_load<GUARD>(cur, q.T, D, cols, tile_row0 + rg * 8, col0);
 #pragma unroll
     for (int sub = 0; sub < SUBS; ++sub) {
         const int64_t row0 = tile_row0 + sub * 64 + rg * 8;
-        if (sub + 1 < SUBS) col_load(nxt, q.T, D, cols, row0 + 64, col0);
+        if (sub + 1 < SUBS) col_load<GUARD>(nxt, q.T, D, cols, row0 + 64, col0);
         col_transform(cur, log2n, flip8);
         if (!QUANT) {
 #pragma unroll
@@ -354,9 +406,7 @@ __global__ __launch_bounds__(kThreads) void fwht_col_fast_kernel(QuantArgs q, in
 #pragma unroll
                 for (int i = 0; i < 8; ++i) amax = fmaxf(amax, fabsf(cur.v[j][i]));
         } else {
-            uint32_t packed[4][2];
-#pragma unroll
-            for (int j = 0; j < 4; ++j) packed[j][0] = packed[j][1] = 0u;
+            uint32_t cw[4][8];
 #pragma unroll
             for (int i = 0; i < 8; ++i) {
                 // the lane's four elements of this row, e .. e+3 with e % 4 == 0, lie in
@@ -375,49 +425,79 @@ __global__ __launch_bounds__(kThreads) void fwht_col_fast_kernel(QuantArgs q, in
 #pragma unroll
                 for (int j = 0; j < 4; ++j) {
                     const uint32_t u = (w01[j >> 1] >> (16 * (j & 1))) & 0xFFFFu;
-                    const int code = quantize_value(cur.v[j][i], sc.inv, qmin, qmax, STOCH, u);
-                    if (q.b <= 4)
-                        packed[j][0] |= ((uint32_t)code & 0xFu) << (4 * i);
-                    else
-                        packed[j][i >> 2] |= ((uint32_t)code & 0xFFu) << (8 * (i & 3));
+                    cw[j][i] = code_word<STOCH>(cur.v[j][i], inv, qminf, qmaxf, magic, u);
                 }
             }
             // dword index inside the column's run: 8 codes are 1 (b <= 4) or 2 dwords
-            if (q.b <= 4) {
 #pragma unroll
-                for (int j = 0; j < 4; ++j) stage[wave][cg * 4 + j][sub * 8 + rg] = packed[j][0];
-            } else {
-#pragma unroll
-                for (int j = 0; j < 4; ++j) {
-                    stage[wave][cg * 4 + j][(sub * 8 + rg) * 2] = packed[j][0];
-                    stage[wave][cg * 4 + j][(sub * 8 + rg) * 2 + 1] = packed[j][1];
+            for (int j = 0; j < 4; ++j) {
+                uint32_t* dst = stage_w + (cg * 4 + j) * stage_pitch;
+                if (B4) {
+                    dst[sub * 8 + rg] = pack_nibbles(cw[j]);
+                } else {
+                    dst[(sub * 8 + rg) * 2] = pack_bytes(cw[j]);
+                    dst[(sub * 8 + rg) * 2 + 1] = pack_bytes(cw[j] + 4);
                 }
             }
         }
         if (sub + 1 < SUBS) cur = nxt;
     }
+    return amax;
+}
+
+template <bool QUANT, bool STOCH, bool B4, int SUBS>
+__global__ __launch_bounds__(kThreads) void fwht_col_fast_kernel(QuantArgs q, int WC)
+{
+    __shared__ float red[kThreads / kWave];
+    constexpr int kDw = B4 ? 1 : 2;          // dwords per 8 codes
+    constexpr int kPitch = SUBS * 8 * kDw + 1;
+    __shared__ uint32_t stage[QUANT ? 4 : 1][QUANT ? 32 * kPitch : 1];
+
+    const int64_t D = q.rows, cols = q.cols;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wc = wave % WC, wr = wave / WC;
+    const int WR = 4 / WC;
+    // pass 2 walks the tensor from its end to its start (see the axis-1 kernel)
+    const int64_t by = QUANT ? (gridDim.y - 1 - blockIdx.y) : blockIdx.y;
+    const int64_t bx = QUANT ? (gridDim.x - 1 - blockIdx.x) : blockIdx.x;
+    const int64_t tile_row0 = (by * WR + wr) * (64 * SUBS);
+    const int64_t strip_col0 = (bx * WC + wc) * 32;
+    const int64_t col0 = strip_col0 + (lane & 7) * 4;
+
+    float inv = 0.0f;
+    if (QUANT) {
+        const Scaling sc = load_scaling(q.meta, q.clip, q.b);
+        publish_scale(q, sc);
+        inv = sc.inv;
+    }
+    uint32_t* stage_w = QUANT ? stage[wave] : nullptr;
+    float amax;
+    if (tile_row0 + 64 * SUBS <= D && strip_col0 + 32 <= cols)
+        amax = col_strip<QUANT, STOCH, B4, SUBS, false>(q, inv, tile_row0, col0, lane, stage_w, kPitch);
+    else
+        amax = col_strip<QUANT, STOCH, B4, SUBS, true>(q, inv, tile_row0, col0, lane, stage_w, kPitch);
 
     if (!QUANT) {
-        block_atomic_max(amax, &q.meta->amax_bits, red);
+        block_atomic_max(amax, q.meta, red);
         return;
     }
     __syncthreads();
 
     // ---- store: 16-byte (b <= 4) or 32-byte (b > 4) units, 2*SUBS units per column
-    const int64_t pitch = (q.b <= 4) ? (D >> 1) : D;
-    const int unit_bytes = (q.b <= 4) ? 16 : 32;
-    const int units = 2 * SUBS;
+    const int64_t pitch = B4 ? (D >> 1) : D;
+    constexpr int unit_bytes = B4 ? 16 : 32;
+    constexpr int units = 2 * SUBS;
 #pragma unroll
     for (int it = 0; it < SUBS; ++it) {
         const int idx = it * 64 + lane;
         const int col_l = idx / units, part = idx - col_l * units;
         const int64_t c = strip_col0 + col_l;
         if (c >= cols) continue;
-        const int64_t byte0 = ((q.b <= 4) ? (tile_row0 >> 1) : tile_row0) + part * unit_bytes;
+        const int64_t byte0 = (B4 ? (tile_row0 >> 1) : tile_row0) + part * unit_bytes;
         const int64_t valid = pitch - byte0;
         if (valid <= 0) continue;
         uint8_t* dst = q.codes + c * pitch + byte0;
-        const uint32_t* src = &stage[wave][col_l][part * (unit_bytes / 4)];
+        const uint32_t* src = stage_w + col_l * kPitch + part * (unit_bytes / 4);
         if ((pitch & 15) == 0 && valid >= unit_bytes) {
             uint4* d4 = reinterpret_cast<uint4*>(dst);
             d4[0] = make_uint4(src[0], src[1], src[2], src[3]);
@@ -446,10 +526,33 @@ hipError_t launch_col(const QuantArgs& q, hipStream_t stream)
                     (unsigned)((D + 64 * SUBS * WR - 1) / (64 * SUBS * WR)));
     {
         ProfileScope ps(K_COL_ABSMAX, stream);
-        hipLaunchKernelGGL((fwht_col_fast_kernel<false, false, SUBS>), grid, dim3(kThreads), 0, stream, q, WC);
+        hipLaunchKernelGGL((fwht_col_fast_kernel<false, false, true, SUBS>), grid, dim3(kThreads), 0,
+                           stream, q, WC);
     }
     ProfileScope ps(K_COL_QUANT, stream);
-    hipLaunchKernelGGL((fwht_col_fast_kernel<true, STOCH, SUBS>), grid, dim3(kThreads), 0, stream, q, WC);
+    if (q.b <= 4)
+        hipLaunchKernelGGL((fwht_col_fast_kernel<true, STOCH, true, SUBS>), grid, dim3(kThreads), 0,
+                           stream, q, WC);
+    else
+        hipLaunchKernelGGL((fwht_col_fast_kernel<true, STOCH, false, SUBS>), grid, dim3(kThreads), 0,
+                           stream, q, WC);
+    return hipGetLastError();
+}
+
+template <int U>
+hipError_t launch_row(const QuantArgs& q, int64_t nchunks, hipStream_t stream)
+{
+    const int64_t per_block = (int64_t)kThreads * U;
+    const int grid = clamp_grid((nchunks + per_block - 1) / per_block, 1 << 16);
+    {
+        ProfileScope ps(K_ROW_ABSMAX, stream);
+        hipLaunchKernelGGL((fwht_row_fast_kernel<U, false, false>), dim3(grid), dim3(kThreads), 0, stream, q);
+    }
+    ProfileScope ps(K_ROW_QUANT, stream);
+    if (q.stochastic)
+        hipLaunchKernelGGL((fwht_row_fast_kernel<U, true, true>), dim3(grid), dim3(kThreads), 0, stream, q);
+    else
+        hipLaunchKernelGGL((fwht_row_fast_kernel<U, true, false>), dim3(grid), dim3(kThreads), 0, stream, q);
     return hipGetLastError();
 }
 
@@ -468,18 +571,9 @@ hipError_t launch_quantize_fast(const QuantArgs& q, hipStream_t stream)
 {
     if (q.axis == 1) {
         const int64_t nchunks = (q.rows * q.cols + 7) >> 3;
-        const int64_t per_block = (int64_t)kThreads * kRowUnroll;
-        const int grid = clamp_grid((nchunks + per_block - 1) / per_block, 256 * 8);
-        {
-            ProfileScope ps(K_ROW_ABSMAX, stream);
-            hipLaunchKernelGGL((fwht_row_fast_kernel<false, false>), dim3(grid), dim3(kThreads), 0, stream, q);
-        }
-        ProfileScope ps(K_ROW_QUANT, stream);
-        if (q.stochastic)
-            hipLaunchKernelGGL((fwht_row_fast_kernel<true, true>), dim3(grid), dim3(kThreads), 0, stream, q);
-        else
-            hipLaunchKernelGGL((fwht_row_fast_kernel<true, false>), dim3(grid), dim3(kThreads), 0, stream, q);
-        return hipGetLastError();
+        // four chunks per thread when that still leaves every CU several workgroups
+        if (nchunks >= (int64_t)kThreads * 4 * 4096) return launch_row<4>(q, nchunks, stream);
+        return launch_row<1>(q, nchunks, stream);
     }
     // long strips (256 rows per wave) when that still gives every CU several waves
     const int64_t waves_long = ((q.cols + 31) / 32) * ((q.rows + 255) / 256);

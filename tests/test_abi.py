@@ -104,7 +104,7 @@ def test_unknown_kind():
 
 
 def _quant_rc(T=FAKE, rows=64, cols=64, axis=1, had=64, op=None, codes=FAKE, scale=FAKE, ws=FAKE,
-              ws_bytes=256):
+              ws_bytes=1 << 16):
     cop = (op or B.Operand()).c()
     return B.load().hdqt_quantize(T, rows, cols, axis, had, C.byref(cop), 0, codes, scale, ws,
                                   ws_bytes, None)
