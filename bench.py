@@ -96,6 +96,8 @@ def main():
     ap.add_argument("--acc-bits", type=int, default=8)
     ap.add_argument("--cpu-rows", type=int, default=65536, help="rows of the oracle's sample")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--separate", action="store_true",
+                    help="run the step as the three per-matmul entry points instead of hdqt_layer_step")
     ap.add_argument("--calib-copy", action="store_true",
                     help="also run one plain 256 MiB device copy (counter calibration for rocprofv3 --pmc)")
     args = ap.parse_args()
@@ -117,13 +119,23 @@ def main():
     prm = {k: step_params(B, k, n, args.s, args.acc_bits) for k in kinds}
     srcs = {B.GEMM_FWD: (X, W), B.GEMM_BWD_INPUT: (G, W), B.GEMM_BWD_WEIGHT: (X, G)}
     outs = {k: torch.empty(B.out_shape(k, M, K, N), dtype=torch.float32, device=dev) for k in kinds}
-    ws_bytes = max(B.workspace_size(k, M, K, N, prm[k]) for k in kinds)
-    ws = torch.empty(ws_bytes, dtype=torch.uint8, device=dev)
     stream = torch.cuda.current_stream()
+    if args.separate:
+        ws_bytes = max(B.workspace_size(k, M, K, N, prm[k]) for k in kinds)
+    else:
+        ws_bytes = B.layer_step_workspace_size(M, K, N, *(prm[k] for k in kinds))
+    ws = torch.empty(ws_bytes, dtype=torch.uint8, device=dev)
+    step_out = tuple(outs[k] for k in kinds)
 
     def step():
-        for k in kinds:
-            B.gemm(k, srcs[k][0], srcs[k][1], M, K, N, prm[k], out=outs[k], workspace=ws, stream=stream)
+        if args.separate:
+            for k in kinds:
+                B.gemm(k, srcs[k][0], srcs[k][1], M, K, N, prm[k], out=outs[k], workspace=ws, stream=stream)
+        else:
+            # Z, dX, dW bit-identical to the three calls above; X and G are read once
+            # per quantization pass for both of their Hadamard domains
+            B.layer_step(X, W, G, prm[kinds[0]], prm[kinds[1]], prm[kinds[2]], out=step_out,
+                         workspace=ws, stream=stream)
 
     if args.calib_copy:
         a = torch.empty(256 << 20, dtype=torch.uint8, device=dev)
@@ -164,9 +176,13 @@ def main():
     #   matmul: packed operands read once (0.5 B per code) + fp32 output written once,
     #   2*M*K*N operations each.
     elems = {"X": M * K, "W": K * N, "G": M * N}
+    #   two-axis kernels: 4 B read per element per pass, 2 x 0.5 B written in the second.
     per_elem = {"absmax": 4.0, "quant": 4.0 + 0.5}
-    seen = {"fwht_row": ["X", "G", "W"],      # axis 1: X (fwd), G and W (bwd_input)
-            "fwht_col": ["W", "X", "G"]}      # axis 0: W (fwd), X and G (bwd_weight)
+    if args.separate:
+        seen = {"fwht_row": ["X", "G", "W"],      # axis 1: X (fwd), G and W (bwd_input)
+                "fwht_col": ["W", "X", "G"]}      # axis 0: W (fwd), X and G (bwd_weight)
+    else:
+        seen = {"fwht_row": ["W"], "fwht_col": ["W"], "fwht_dua": ["X", "G"]}
     gemm_bytes_step = (0.5 * (M * K + K * N) + 4.0 * M * N) + (0.5 * (M * N + K * N) + 4.0 * M * K) \
         + (0.5 * (M * K + M * N) + 4.0 * K * N)
     kernels, roof_all = {}, {}
@@ -177,7 +193,8 @@ def main():
         fam = name[:8]
         if fam in seen:
             kind = "absmax" if name.endswith("absmax") else "quant"
-            bytes_step = per_elem[kind] * sum(elems[t] for t in seen[fam])
+            bytes_step = (per_elem[kind] + (0.5 if fam == "fwht_dua" and kind == "quant" else 0.0)) \
+                * sum(elems[t] for t in seen[fam])
             gbps = bytes_step * args.steps / (tot * 1e-3) / 1e9
             roof_all[name] = {"bound": "hbm", "achieved": gbps, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                               "frac": gbps / HBM_PEAK_GBPS, "traffic": None,
@@ -193,13 +210,16 @@ def main():
     gemm_ms = sum(tot for name, (l, tot) in kern.items() if name.startswith("gemm") or name == "dequant")
     gemm_tops = ops_step * args.steps / (gemm_ms * 1e-3) / 1e12 if gemm_ms else None
     quant_ms = sum(tot for name, (l, tot) in kern.items() if name.startswith("fwht"))
-    quant_bytes = args.steps * 2 * (per_elem["absmax"] + per_elem["quant"]) * sum(elems.values())
+    quant_bytes = args.steps * sum(
+        (per_elem["absmax"] + per_elem["quant"] + (0.5 if fam == "fwht_dua" else 0.0)) * elems[t]
+        for fam, ts in seen.items() for t in ts)
     line = {
         "metric": METRIC, "value": value, "unit": "TOPS", "n_gpus": 1, "steps": args.steps,
         "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": True,
         "scaling": "weak", "vs_baseline": None, "dtype": "int8", "data": "synthetic",
         "config": {"workload": f"{args.workload}: {layer.name} (M={M}, K={K}, N={N}), one training "
                                f"step = fwd + bwd_input + bwd_weight",
+                   "entry": "3 x hdqt_gemm_*" if args.separate else "hdqt_layer_step",
                    "had_block": n, "input_bits": 4, "acc_bits": args.acc_bits, "s": args.s,
                    "rounding": "G stochastic, X and W nearest"},
         "roofline": roofline,

@@ -147,6 +147,25 @@ int hdqt_quantize(const float *T, int64_t rows, int64_t cols, int axis, int had_
                   void *workspace, size_t workspace_bytes, void *stream);
 
 /*
+ * The same quantization along BOTH axes of one tensor, from one read of it per
+ * pass.  A training step needs every activation and gradient tensor in two
+ * Hadamard domains (X along K for the forward product and along M for the weight
+ * gradient; G along N for the input gradient and along M for the weight
+ * gradient); the passes over the source are what costs.  The outputs are
+ * bit-identical to two hdqt_quantize calls with axis 1 and axis 0:
+ *   codes_axis1 [rows, pitch(cols)], scale_axis1   contraction along a row
+ *   codes_axis0 [cols, pitch(rows)], scale_axis0   contraction along a column
+ * Workspace: hdqt_quantize_dual_workspace_size() bytes.  Shapes the fused
+ * kernels do not cover (rows or cols not a multiple of 64, block order above
+ * 64, codes wider than 4 bits) run as two single-axis quantizations.
+ */
+size_t hdqt_quantize_dual_workspace_size(void);
+int hdqt_quantize_dual(const float *T, int64_t rows, int64_t cols, int had_block,
+                       const hdqt_operand_t *op_axis1, const hdqt_operand_t *op_axis0,
+                       uint64_t seed, void *codes_axis1, float *scale_axis1, void *codes_axis0,
+                       float *scale_axis0, void *workspace, size_t workspace_bytes, void *stream);
+
+/*
  * Tiled integer matmul on packed codes (Methodology: tiles of size s, low-bit
  * accumulators) followed by dequantization:
  *   acc[i,j] = sum_t sat_a( sum_{d in tile t} qA[i,d] qB[j,d] )
@@ -179,6 +198,31 @@ int hdqt_gemm_bwd_input(const float *G, const float *W, float *dX, int64_t M, in
 int hdqt_gemm_bwd_weight(const float *X, const float *G, float *dW, int64_t M, int64_t K,
                          int64_t N, const hdqt_params_t *params, int32_t *acc_out,
                          void *workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * All three matmuls of one layer's training step in one call (Methodology: every
+ * matmul of the forward and the backward pass is quantized in its own Hadamard
+ * domain):
+ *   Z  = hdqt_gemm_fwd(X, W; *fwd)
+ *   dX = hdqt_gemm_bwd_input(G, W; *bwd_input)      skipped when dX is NULL
+ *   dW = hdqt_gemm_bwd_weight(X, G; *bwd_weight)
+ * with results bit-identical to those three calls.  What the call saves is memory
+ * traffic: X and G are each needed along both of their axes, and here each is
+ * read once per quantization pass for both (see hdqt_quantize_dual), so the
+ * step reads X and G four times in total instead of eight.
+ * X, W, G, Z, dX, dW: fp32 device tensors; the three params are host pointers
+ * (bwd_input may be NULL when dX is); the operands' tensor_ids and the seeds
+ * are taken from the params of the matmul each quantization belongs to.
+ * Workspace: hdqt_layer_step_workspace_size(...) bytes (0 = invalid arguments),
+ * device memory, 16-byte aligned, contents undefined on entry and on return.
+ */
+size_t hdqt_layer_step_workspace_size(int64_t M, int64_t K, int64_t N, const hdqt_params_t *fwd,
+                                      const hdqt_params_t *bwd_input,
+                                      const hdqt_params_t *bwd_weight);
+int hdqt_layer_step(const float *X, const float *W, const float *G, float *Z, float *dX,
+                    float *dW, int64_t M, int64_t K, int64_t N, const hdqt_params_t *fwd,
+                    const hdqt_params_t *bwd_input, const hdqt_params_t *bwd_weight,
+                    void *workspace, size_t workspace_bytes, void *stream);
 
 /*
  * Optional per-kernel timing, for benchmarks.  While enabled, every kernel the

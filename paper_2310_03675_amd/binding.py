@@ -22,7 +22,8 @@ EXPORTED = [
     "hdqt_n_eff", "hdqt_codes_pitch", "hdqt_quantize_workspace_size", "hdqt_workspace_layout",
     "hdqt_workspace_size", "hdqt_quantize", "hdqt_gemm_codes", "hdqt_gemm_fwd",
     "hdqt_gemm_bwd_input", "hdqt_gemm_bwd_weight", "hdqt_strerror", "hdqt_last_hip_error",
-    "hdqt_profile_enable", "hdqt_profile_collect",
+    "hdqt_profile_enable", "hdqt_profile_collect", "hdqt_quantize_dual",
+    "hdqt_quantize_dual_workspace_size", "hdqt_layer_step_workspace_size", "hdqt_layer_step",
 ]
 
 
@@ -102,6 +103,15 @@ def load() -> C.CDLL:
     lib.hdqt_quantize.restype = i32
     lib.hdqt_quantize.argtypes = [vp, i64, i64, i32, i32, C.POINTER(COperand), C.c_uint64, vp, vp,
                                   vp, sz, vp]
+    lib.hdqt_quantize_dual_workspace_size.restype = sz
+    lib.hdqt_quantize_dual_workspace_size.argtypes = []
+    lib.hdqt_layer_step_workspace_size.restype = sz
+    lib.hdqt_layer_step_workspace_size.argtypes = [i64, i64, i64] + [C.POINTER(CParams)] * 3
+    lib.hdqt_layer_step.restype = i32
+    lib.hdqt_layer_step.argtypes = [vp] * 6 + [i64, i64, i64] + [C.POINTER(CParams)] * 3 + [vp, sz, vp]
+    lib.hdqt_quantize_dual.restype = i32
+    lib.hdqt_quantize_dual.argtypes = [vp, i64, i64, i32, C.POINTER(COperand), C.POINTER(COperand),
+                                       C.c_uint64, vp, vp, vp, vp, vp, sz, vp]
     lib.hdqt_gemm_codes.restype = i32
     lib.hdqt_gemm_codes.argtypes = [vp, vp, i32, i32, vp, vp, i64, i64, i64, i32, i32, i64, vp, vp,
                                     vp, sz, vp]
@@ -192,6 +202,32 @@ def quantize(T: torch.Tensor, axis: int, had_block: int, op: Operand, seed: int 
     return codes, scale
 
 
+def quantize_dual(T: torch.Tensor, had_block: int, op_axis1: Operand, op_axis0: Operand, seed: int = 0,
+                  out=None, workspace: Optional[torch.Tensor] = None,
+                  stream: Optional[torch.cuda.Stream] = None):
+    """hdqt_quantize_dual -> (codes_axis1, scale_axis1, codes_axis0, scale_axis0).
+    `out` may carry preallocated (codes1, scale1, codes0, scale0)."""
+    _check_dev(T)
+    assert T.dtype == torch.float32 and T.dim() == 2
+    rows, cols = T.shape
+    if out is None:
+        out = (torch.empty((rows, codes_pitch(cols, op_axis1.b)), dtype=torch.uint8, device=T.device),
+               torch.empty(1, dtype=torch.float32, device=T.device),
+               torch.empty((cols, codes_pitch(rows, op_axis0.b)), dtype=torch.uint8, device=T.device),
+               torch.empty(1, dtype=torch.float32, device=T.device))
+    c1, s1, c0, s0 = out
+    if workspace is None:
+        workspace = torch.empty(load().hdqt_quantize_dual_workspace_size(), dtype=torch.uint8,
+                                device=T.device)
+    o1, o0 = op_axis1.c(), op_axis0.c()
+    rc = load().hdqt_quantize_dual(_ptr(T), rows, cols, had_block, C.byref(o1), C.byref(o0), seed,
+                                   _ptr(c1), _ptr(s1), _ptr(c0), _ptr(s0), _ptr(workspace),
+                                   workspace.numel(), _stream(stream))
+    if rc:
+        raise HdqtError(rc, "hdqt_quantize_dual")
+    return c1, s1, c0, s0
+
+
 def gemm_codes(qA: torch.Tensor, qB: torch.Tensor, bA: int, bB: int, scaleA: torch.Tensor,
                scaleB: torch.Tensor, D: int, n: int, acc_bits: int, s: int,
                want_out: bool = True, want_acc: bool = True,
@@ -260,3 +296,37 @@ def gemm_bwd_input(G, W, params: Params, **kw):
 def gemm_bwd_weight(X, G, params: Params, **kw):
     M, K = X.shape
     return gemm(GEMM_BWD_WEIGHT, X, G, M, K, G.shape[1], params, **kw)
+
+
+def layer_step_workspace_size(M: int, K: int, N: int, fwd: Params, bwd_input: Optional[Params],
+                              bwd_weight: Params) -> int:
+    pf, pw = fwd.c(), bwd_weight.c()
+    pi = bwd_input.c() if bwd_input is not None else None
+    return load().hdqt_layer_step_workspace_size(M, K, N, C.byref(pf),
+                                                 C.byref(pi) if pi is not None else None, C.byref(pw))
+
+
+def layer_step(X: torch.Tensor, W: torch.Tensor, G: torch.Tensor, fwd: Params,
+               bwd_input: Optional[Params], bwd_weight: Params, out=None,
+               workspace: Optional[torch.Tensor] = None, stream: Optional[torch.cuda.Stream] = None):
+    """hdqt_layer_step -> (Z, dX | None, dW, workspace).  dX is skipped when
+    `bwd_input` is None.  `out` may carry preallocated (Z, dX, dW)."""
+    _check_dev(X, W, G, workspace)
+    M, K = X.shape
+    N = W.shape[1]
+    assert W.shape[0] == K and tuple(G.shape) == (M, N)
+    if out is None:
+        new = lambda *shape: torch.empty(shape, dtype=torch.float32, device=X.device)
+        out = (new(M, N), new(M, K) if bwd_input is not None else None, new(K, N))
+    Z, dX, dW = out
+    if workspace is None:
+        need = layer_step_workspace_size(M, K, N, fwd, bwd_input, bwd_weight)
+        workspace = torch.empty(max(need, 256), dtype=torch.uint8, device=X.device)
+    pf, pw = fwd.c(), bwd_weight.c()
+    pi = bwd_input.c() if bwd_input is not None else None
+    rc = load().hdqt_layer_step(_ptr(X), _ptr(W), _ptr(G), _ptr(Z), _ptr(dX), _ptr(dW), M, K, N,
+                                C.byref(pf), C.byref(pi) if pi is not None else None, C.byref(pw),
+                                _ptr(workspace), workspace.numel(), _stream(stream))
+    if rc:
+        raise HdqtError(rc, "hdqt_layer_step")
+    return Z, dX, dW, workspace

@@ -112,7 +112,8 @@ int choose_splits(int64_t RA, int64_t RB, int64_t n_tiles)
 {
     const int64_t blocks = ((RA + 127) / 128) * ((RB + 127) / 128);
     if (blocks >= 512 || n_tiles < 8) return 1;
-    int64_t want = (1024 + blocks - 1) / blocks;
+    // two workgroups per CU; every further split adds a full set of output atomics
+    int64_t want = (512 + blocks - 1) / blocks;
     if (want > n_tiles / 4) want = n_tiles / 4;
     if (want > 1024) want = 1024;
     return want < 1 ? 1 : (int)want;
@@ -133,6 +134,35 @@ int run_quantize(const float* T, int64_t rows, int64_t cols, int axis, int n_eff
     q.meta = meta; q.codes = static_cast<uint8_t*>(codes); q.scale_out = scale_out;
     const hipError_t e = hdqt::launch_quantize(q, stream);
     return e == hipSuccess ? HDQT_OK : hip_fail(e);
+}
+
+// Both quantizations of one tensor (axis 1 and axis 0): from a single read per
+// pass when the fused kernel takes the shape, else one after the other.  Both
+// calibration records must be zero.
+int run_quantize_pair(const float* T, int64_t rows, int64_t cols, int n1, const hdqt_operand_t* op1,
+                      uint64_t seed1, int n0, const hdqt_operand_t* op0, uint64_t seed0,
+                      hdqt::QMeta* meta1, hdqt::QMeta* meta0, void* codes1, void* codes0,
+                      float* scale1_out, float* scale0_out, hipStream_t stream)
+{
+    hdqt::DualArgs d{};
+    d.T = T; d.rows = rows; d.cols = cols;
+    d.log2n_row = log2i(n1); d.log2n_col = log2i(n0);
+    d.b_row = op1->b; d.st_row = (op1->round == HDQT_ROUND_STOCHASTIC);
+    d.clip_row = op1->clip; d.tid_row = op1->tensor_id;
+    d.b_col = op0->b; d.st_col = (op0->round == HDQT_ROUND_STOCHASTIC);
+    d.clip_col = op0->clip; d.tid_col = op0->tensor_id;
+    d.seed_row_lo = (uint32_t)seed1; d.seed_row_hi = (uint32_t)(seed1 >> 32);
+    d.seed_col_lo = (uint32_t)seed0; d.seed_col_hi = (uint32_t)(seed0 >> 32);
+    d.meta_row = meta1; d.meta_col = meta0;
+    d.codes_row = static_cast<uint8_t*>(codes1); d.codes_col = static_cast<uint8_t*>(codes0);
+    d.scale_row_out = scale1_out; d.scale_col_out = scale0_out;
+    if (hdqt::quantize_dual_eligible(d)) {
+        const hipError_t e = hdqt::launch_quantize_dual(d, stream);
+        return e == hipSuccess ? HDQT_OK : hip_fail(e);
+    }
+    const int rc = run_quantize(T, rows, cols, 1, n1, op1, seed1, meta1, codes1, scale1_out, stream);
+    if (rc) return rc;
+    return run_quantize(T, rows, cols, 0, n0, op0, seed0, meta0, codes0, scale0_out, stream);
 }
 
 // Resolve tile length, accumulator range and the split of the contraction.
@@ -220,6 +250,60 @@ int run_gemm(int kind, const float* P, const float* Q, float* out, int64_t M, in
     return run_planned_gemm(g, acc_ws, true, stream);
 }
 
+
+// Workspace of hdqt_layer_step.  Offsets in bytes; the calibration records and the
+// accumulation targets of split contractions are contiguous from offset 0, so one
+// launch clears them all.
+enum { T_X1, T_X0, T_W0, T_W1, T_G1, T_G0, T_COUNT };
+struct StepLayout {
+    size_t meta[T_COUNT];
+    size_t codes[T_COUNT];
+    size_t acc[3];           // per matmul; meaningful when splits[k] > 1
+    int splits[3];
+    int n_eff[3];
+    size_t zero_bytes;
+    size_t total;
+};
+
+int plan_step(int64_t M, int64_t K, int64_t N, const hdqt_params_t* const prm[3], bool with_dx,
+              StepLayout* L)
+{
+    Orientation o[3];
+    for (int k = 0; k < 3; ++k) {
+        if (k == HDQT_GEMM_BWD_INPUT && !with_dx) continue;
+        const int rc = check_gemm(k, M, K, N, prm[k], &o[k]);
+        if (rc) return rc;
+    }
+    size_t off = 0;
+    for (int t = 0; t < T_COUNT; ++t) { L->meta[t] = off; off += kMetaBytes; }
+    for (int k = 0; k < 3; ++k) {
+        L->acc[k] = off;
+        L->splits[k] = 1;
+        L->n_eff[k] = 1;
+        if (k == HDQT_GEMM_BWD_INPUT && !with_dx) continue;
+        L->n_eff[k] = hdqt_n_eff(o[k].D, prm[k]->had_block);
+        const int64_t s = prm[k]->s < o[k].D ? prm[k]->s : o[k].D;
+        L->splits[k] = choose_splits(o[k].RA, o[k].RB, (o[k].D + s - 1) / s);
+        if (L->splits[k] > 1) off = align_up(off + (size_t)(o[k].RA * o[k].RB) * sizeof(int32_t), 256);
+    }
+    L->zero_bytes = off;
+    const hdqt_params_t *fwd = prm[0], *bwi = prm[1], *bww = prm[2];
+    const size_t bytes[T_COUNT] = {
+        (size_t)(M * hdqt_codes_pitch(K, fwd->A.b)),                 // X along K
+        (size_t)(K * hdqt_codes_pitch(M, bww->A.b)),                 // X along M
+        (size_t)(N * hdqt_codes_pitch(K, fwd->B.b)),                 // W along K
+        with_dx ? (size_t)(K * hdqt_codes_pitch(N, bwi->B.b)) : 0,   // W along N
+        with_dx ? (size_t)(M * hdqt_codes_pitch(N, bwi->A.b)) : 0,   // G along N
+        (size_t)(N * hdqt_codes_pitch(M, bww->B.b)),                 // G along M
+    };
+    for (int t = 0; t < T_COUNT; ++t) {
+        L->codes[t] = off;
+        off = align_up(off + bytes[t], 256);
+    }
+    L->total = off;
+    return HDQT_OK;
+}
+
 } // namespace
 
 extern "C" {
@@ -291,6 +375,36 @@ int hdqt_quantize(const float* T, int64_t rows, int64_t cols, int axis, int had_
                         static_cast<hipStream_t>(stream));
 }
 
+size_t hdqt_quantize_dual_workspace_size(void) { return 2 * kMetaBytes; }
+
+int hdqt_quantize_dual(const float* T, int64_t rows, int64_t cols, int had_block,
+                       const hdqt_operand_t* op_axis1, const hdqt_operand_t* op_axis0, uint64_t seed,
+                       void* codes_axis1, float* scale_axis1, void* codes_axis0, float* scale_axis0,
+                       void* workspace, size_t workspace_bytes, void* stream_v)
+{
+    if (!T || !op_axis1 || !op_axis0 || !codes_axis1 || !codes_axis0 || !scale_axis1 || !scale_axis0)
+        return HDQT_EINVAL_NULL;
+    int rc = check_dims2(rows, cols);
+    if (rc) return rc;
+    if ((rc = check_hadamard(had_block))) return rc;
+    if ((rc = check_operand(op_axis1)) || (rc = check_operand(op_axis0))) return rc;
+    if (!workspace || workspace_bytes < hdqt_quantize_dual_workspace_size()) return HDQT_EWORKSPACE;
+    if (misaligned(T) || misaligned(codes_axis1) || misaligned(codes_axis0) || misaligned(workspace))
+        return HDQT_EALIGN;
+    if (((reinterpret_cast<uintptr_t>(scale_axis1) | reinterpret_cast<uintptr_t>(scale_axis0)) & 3u) != 0)
+        return HDQT_EALIGN;
+    hipStream_t stream = static_cast<hipStream_t>(stream_v);
+    char* base = static_cast<char*>(workspace);
+    hdqt::QMeta* meta1 = reinterpret_cast<hdqt::QMeta*>(base);
+    hdqt::QMeta* meta0 = reinterpret_cast<hdqt::QMeta*>(base + kMetaBytes);
+    const hipError_t e = hdqt::launch_zero2(reinterpret_cast<uint32_t*>(base),
+                                            (int64_t)(2 * kMetaBytes / 4), nullptr, 0, stream);
+    if (e != hipSuccess) return hip_fail(e);
+    return run_quantize_pair(T, rows, cols, hdqt_n_eff(cols, had_block), op_axis1, seed,
+                             hdqt_n_eff(rows, had_block), op_axis0, seed, meta1, meta0, codes_axis1,
+                             codes_axis0, scale_axis1, scale_axis0, stream);
+}
+
 int hdqt_gemm_codes(const void* qA, const void* qB, int bA, int bB, const float* scaleA,
                     const float* scaleB, int64_t RA, int64_t RB, int64_t D, int n_eff,
                     int acc_bits, int64_t s, float* out, int32_t* acc_out, void* workspace,
@@ -315,6 +429,78 @@ int hdqt_gemm_codes(const void* qA, const void* qB, int bA, int bB, const float*
     return run_planned_gemm(plan_gemm(qA, qB, bA, bB, scaleA, scaleB, RA, RB, D, n_eff, acc_bits, s,
                                       out, acc_out),
                             acc_ws, false, static_cast<hipStream_t>(stream));
+}
+
+size_t hdqt_layer_step_workspace_size(int64_t M, int64_t K, int64_t N, const hdqt_params_t* fwd,
+                                      const hdqt_params_t* bwd_input, const hdqt_params_t* bwd_weight)
+{
+    const hdqt_params_t* prm[3] = {fwd, bwd_input, bwd_weight};
+    StepLayout L;
+    return plan_step(M, K, N, prm, bwd_input != nullptr, &L) == HDQT_OK ? L.total : 0;
+}
+
+int hdqt_layer_step(const float* X, const float* W, const float* G, float* Z, float* dX, float* dW,
+                    int64_t M, int64_t K, int64_t N, const hdqt_params_t* fwd,
+                    const hdqt_params_t* bwd_input, const hdqt_params_t* bwd_weight,
+                    void* workspace, size_t workspace_bytes, void* stream_v)
+{
+    if (!X || !W || !G || !Z || !dW || !fwd || !bwd_weight) return HDQT_EINVAL_NULL;
+    const bool with_dx = dX != nullptr;
+    if (with_dx && !bwd_input) return HDQT_EINVAL_NULL;
+    const hdqt_params_t* prm[3] = {fwd, bwd_input, bwd_weight};
+    StepLayout L;
+    int rc = plan_step(M, K, N, prm, with_dx, &L);
+    if (rc) return rc;
+    if (!workspace || workspace_bytes < L.total) return HDQT_EWORKSPACE;
+    if (misaligned(X) || misaligned(W) || misaligned(G) || misaligned(Z) || misaligned(dX) ||
+        misaligned(dW) || misaligned(workspace))
+        return HDQT_EALIGN;
+    hipStream_t stream = static_cast<hipStream_t>(stream_v);
+    char* base = static_cast<char*>(workspace);
+    auto meta = [&](int t) { return reinterpret_cast<hdqt::QMeta*>(base + L.meta[t]); };
+    auto codes = [&](int t) { return static_cast<void*>(base + L.codes[t]); };
+    auto acc = [&](int k) { return L.splits[k] > 1 ? reinterpret_cast<int32_t*>(base + L.acc[k]) : nullptr; };
+
+    hipError_t e = hdqt::launch_zero2(reinterpret_cast<uint32_t*>(base), (int64_t)(L.zero_bytes / 4),
+                                      nullptr, 0, stream);
+    if (e != hipSuccess) return hip_fail(e);
+
+    // ---- forward: X along K (and along M, kept for the weight gradient), W along K
+    const int nF = L.n_eff[HDQT_GEMM_FWD], nI = L.n_eff[HDQT_GEMM_BWD_INPUT],
+              nW = L.n_eff[HDQT_GEMM_BWD_WEIGHT];
+    rc = run_quantize_pair(X, M, K, nF, &fwd->A, fwd->seed, nW, &bwd_weight->A, bwd_weight->seed,
+                           meta(T_X1), meta(T_X0), codes(T_X1), codes(T_X0), nullptr, nullptr, stream);
+    if (rc) return rc;
+    rc = run_quantize(W, K, N, 0, nF, &fwd->B, fwd->seed, meta(T_W0), codes(T_W0), nullptr, stream);
+    if (rc) return rc;
+    rc = run_planned_gemm(plan_gemm(codes(T_X1), codes(T_W0), fwd->A.b, fwd->B.b, &meta(T_X1)->scale,
+                                    &meta(T_W0)->scale, M, N, K, nF, fwd->acc_bits, fwd->s, Z, nullptr),
+                          acc(HDQT_GEMM_FWD), true, stream);
+    if (rc) return rc;
+
+    // ---- backward: G along N and along M, W along N
+    if (with_dx) {
+        rc = run_quantize_pair(G, M, N, nI, &bwd_input->A, bwd_input->seed, nW, &bwd_weight->B,
+                               bwd_weight->seed, meta(T_G1), meta(T_G0), codes(T_G1), codes(T_G0),
+                               nullptr, nullptr, stream);
+        if (rc) return rc;
+        rc = run_quantize(W, K, N, 1, nI, &bwd_input->B, bwd_input->seed, meta(T_W1), codes(T_W1),
+                          nullptr, stream);
+        if (rc) return rc;
+        rc = run_planned_gemm(plan_gemm(codes(T_G1), codes(T_W1), bwd_input->A.b, bwd_input->B.b,
+                                        &meta(T_G1)->scale, &meta(T_W1)->scale, M, K, N, nI,
+                                        bwd_input->acc_bits, bwd_input->s, dX, nullptr),
+                              acc(HDQT_GEMM_BWD_INPUT), true, stream);
+        if (rc) return rc;
+    } else {
+        rc = run_quantize(G, M, N, 0, nW, &bwd_weight->B, bwd_weight->seed, meta(T_G0), codes(T_G0),
+                          nullptr, stream);
+        if (rc) return rc;
+    }
+    return run_planned_gemm(plan_gemm(codes(T_X0), codes(T_G0), bwd_weight->A.b, bwd_weight->B.b,
+                                      &meta(T_X0)->scale, &meta(T_G0)->scale, K, N, M, nW,
+                                      bwd_weight->acc_bits, bwd_weight->s, dW, nullptr),
+                          acc(HDQT_GEMM_BWD_WEIGHT), true, stream);
 }
 
 int hdqt_gemm_fwd(const float* X, const float* W, float* Z, int64_t M, int64_t K, int64_t N,

@@ -40,6 +40,28 @@ struct QuantArgs {
     float* scale_out;       // device, may alias &meta->scale, may be null
 };
 
+// One tensor quantized along both axes from one read ("row" = axis 1, along the
+// columns; "col" = axis 0, along the rows).
+struct DualArgs {
+    const float* T;
+    int64_t rows, cols;
+    int log2n_row, log2n_col;
+    int b_row, st_row;
+    float clip_row;
+    uint32_t tid_row;
+    int b_col, st_col;
+    float clip_col;
+    uint32_t tid_col;
+    uint32_t seed_row_lo, seed_row_hi;   // Philox key per axis
+    uint32_t seed_col_lo, seed_col_hi;
+    QMeta* meta_row;
+    QMeta* meta_col;
+    uint8_t* codes_row;     // [rows, cols/2]
+    uint8_t* codes_col;     // [cols, rows/2]
+    float* scale_row_out;   // may be null
+    float* scale_col_out;
+};
+
 struct GemmArgs {
     const uint8_t* qA;      // [RA, pitchA] packed codes
     const uint8_t* qB;      // [RB, pitchB]
@@ -72,10 +94,13 @@ hipError_t launch_dequant(const int32_t* acc, int64_t count, const float* scaleA
 // every launch is bracketed by two HIP events on its stream.
 enum KernelId {
     K_FILL = 0, K_ROW_ABSMAX, K_ROW_QUANT, K_COL_ABSMAX, K_COL_QUANT, K_PLAIN_ABSMAX,
-    K_PLAIN_QUANT, K_GEMM_ALIGNED, K_GEMM_GENERIC, K_DEQUANT, K_GEMM_I4, K_COUNT
+    K_PLAIN_QUANT, K_GEMM_ALIGNED, K_GEMM_GENERIC, K_DEQUANT, K_GEMM_I4, K_DUAL_ABSMAX, K_DUAL_QUANT,
+    K_COUNT
 };
 bool quantize_fast_eligible(const QuantArgs& q);
 hipError_t launch_quantize_fast(const QuantArgs& q, hipStream_t stream);
+bool quantize_dual_eligible(const DualArgs& q);
+hipError_t launch_quantize_dual(const DualArgs& q, hipStream_t stream);
 bool gemm_fast_eligible(const GemmArgs& g);
 hipError_t launch_gemm_fast(const GemmArgs& g, hipStream_t stream);
 const char* kernel_name(int id);

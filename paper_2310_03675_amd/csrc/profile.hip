@@ -27,7 +27,7 @@ const char* kernel_name(int id)
     static const char* names[K_COUNT] = {
         "zero", "fwht_row_absmax", "fwht_row_quant", "fwht_col_absmax", "fwht_col_quant",
         "plain_absmax", "plain_quant", "gemm_tiled_aligned", "gemm_tiled_generic", "dequant",
-        "gemm_i4"};
+        "gemm_i4", "fwht_dual_absmax", "fwht_dual_quant"};
     return (id >= 0 && id < K_COUNT) ? names[id] : "?";
 }
 

@@ -1,0 +1,363 @@
+// Hadamard-domain quantization of one tensor along BOTH axes from one read
+// (gfx950).
+//
+// A training step needs every activation and gradient tensor quantized twice:
+// along its rows for one matmul and along its columns for another (X along K
+// for the forward product and along M for the weight gradient; G along N for
+// the input gradient and along M for the weight gradient).  The two results
+// are the paper's quantizer Q applied in two Hadamard domains; they share
+// nothing but the source, and the source is what costs: the kernels are
+// HBM-bound.  Here pass 1 computes both maxima and pass 2 both code sets from a
+// single read of the tensor each.  The results are bit-identical to two
+// single-axis quantizations.
+//
+// A wave holds a tile of 64 rows x 64 columns in registers, 64 values per lane:
+// lane (rg, cg) = (lane / 8, lane % 8) has rows 8*rg + i (i < 8) of columns
+// 32*h + 4*cg + j (h < 2, j < 4).  Both transforms run on that one layout:
+//   along the columns of a row (axis 1): strides 1, 2 pair registers (j),
+//     strides 4, 8, 16 pair lanes (lane xor 1, 2, 4), stride 32 pairs registers (h);
+//   along the rows of a column (axis 0): strides 1, 2, 4 pair registers (i),
+//     strides 8, 16, 32 pair lanes (lane xor 8, 16, 32).
+// The axis-1 transform is done row by row on copies (eight values at a time),
+// the axis-0 transform then in place.  No LDS is involved.
+// Requires rows and cols multiples of 64, block orders up to 64 and codes of at
+// most 4 bits.
+
+#include "common.hpp"
+#include "lane_ops.hpp"
+
+namespace hdqt {
+
+namespace {
+
+using namespace lanes;
+
+constexpr int kThreads = 256;
+constexpr int kTile = 64;
+
+struct Tile {
+    float v[2][4][8];        // [h][j][i]
+};
+
+struct DualCtx {
+    const DualArgs* q;
+    int cg, rg;
+    uint32_t flip1, flip2, flip4, flip8;
+    float inv_row, inv_col;
+    float qmin_row, qmax_row, qmin_col, qmax_col;
+};
+
+__device__ __forceinline__ void tile_load(Tile& t, const DualArgs& q, const DualCtx& x, int64_t row0,
+                                          int64_t col0)
+{
+    const float* src = q.T + (row0 + x.rg * 8) * q.cols + col0 + x.cg * 4;
+#pragma unroll
+    for (int i = 0; i < 8; ++i)
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+            const float4 a = *reinterpret_cast<const float4*>(src + i * q.cols + 32 * h);
+            t.v[h][0][i] = a.x; t.v[h][1][i] = a.y; t.v[h][2][i] = a.z; t.v[h][3][i] = a.w;
+        }
+}
+
+// The two 32-bit words of random bits that cover the lane's four consecutive
+// elements e .. e+3 (e % 4 == 0): they lie in one Philox block, in its words
+// (e % 8) / 2 and (e % 8) / 2 + 1.
+__device__ __forceinline__ void random_pair(int64_t e, uint32_t tensor_id, uint32_t k0, uint32_t k1,
+                                            uint32_t w01[2])
+{
+    const uint64_t blk = (uint64_t)e >> 3;
+    uint32_t rnd[4];
+    philox4x32_10((uint32_t)blk, (uint32_t)(blk >> 32), tensor_id, 0u, k0, k1, rnd);
+    const bool upper = (e & 4) != 0;
+    w01[0] = upper ? rnd[2] : rnd[0];
+    w01[1] = upper ? rnd[3] : rnd[1];
+}
+
+// Axis 1 for the lane's row 8*rg + i of the tile: transform, then absmax (pass
+// 1) or codes (pass 2).
+template <bool QUANT, bool STOCH>
+__device__ __forceinline__ void row_line(const Tile& t, int i, const DualCtx& x, int64_t row0,
+                                         int64_t col0, float& amax)
+{
+    const DualArgs& q = *x.q;
+    const int log2n = q.log2n_row;
+    float w[8];              // index 4*h + j
+#pragma unroll
+    for (int h = 0; h < 2; ++h)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) w[4 * h + j] = t.v[h][j][i];
+    if (log2n >= 1) {
+#pragma unroll
+        for (int k = 0; k < 8; k += 2) {
+            const float a = w[k], c = w[k + 1];
+            w[k] = a + c;
+            w[k + 1] = a - c;
+        }
+    }
+    if (log2n >= 2) {
+#pragma unroll
+        for (int k = 0; k < 8; ++k)
+            if (!(k & 2)) {
+                const float a = w[k], c = w[k + 2];
+                w[k] = a + c;
+                w[k + 2] = a - c;
+            }
+    }
+    if (log2n >= 3) {
+#pragma unroll
+        for (int k = 0; k < 8; ++k) w[k] = stage_dpp<1>(w[k], x.flip1);
+    }
+    if (log2n >= 4) {
+#pragma unroll
+        for (int k = 0; k < 8; ++k) w[k] = stage_dpp<2>(w[k], x.flip2);
+    }
+    if (log2n >= 5) {
+#pragma unroll
+        for (int k = 0; k < 8; ++k) w[k] = stage_dpp<4>(w[k], x.flip4);
+    }
+    if (log2n >= 6) {
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            const float a = w[k], c = w[k + 4];
+            w[k] = a + c;
+            w[k + 4] = a - c;
+        }
+    }
+    if (!QUANT) {
+#pragma unroll
+        for (int k = 0; k < 8; ++k) amax = fmaxf(amax, fabsf(w[k]));
+        return;
+    }
+    const int64_t row = row0 + x.rg * 8 + i;
+    const float magic = kMagic + 8.0f;
+    uint32_t both = 0;       // the lane's eight codes: low half h = 0, high half h = 1
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+        uint32_t w01[2] = {0u, 0u};
+        if (STOCH)
+            random_pair(row * q.cols + col0 + 32 * h + x.cg * 4, q.tid_row, q.seed_row_lo, q.seed_row_hi, w01);
+        // 0x4B400000 << 4j has no bits in the low 16: the low half of the sum is the
+        // four offset nibbles
+        uint32_t acc = 0;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const uint32_t u = (w01[j >> 1] >> (16 * (j & 1))) & 0xFFFFu;
+            acc += code_word<STOCH>(w[4 * h + j], x.inv_row, x.qmin_row, x.qmax_row, magic, u) << (4 * j);
+        }
+        both |= (acc & 0xFFFFu) << (16 * h);
+    }
+    both ^= 0x88888888u;
+    // Lanes cg and cg ^ 1 trade halves: the even one ends up with columns
+    // 4cg .. 4cg+7 (bytes 2cg .. 2cg+3 of the row's 32), the odd one with columns
+    // 32+4(cg-1) .. 32+4cg+3 (bytes 16+2(cg-1) ..).
+    const uint32_t other = __float_as_uint(lane_xor<1>(__uint_as_float(both)));
+    const bool odd = (x.cg & 1) != 0;
+    const uint32_t word = __builtin_amdgcn_perm(other, both, odd ? 0x03020706u : 0x05040100u);
+    const int byte_off = odd ? 16 + 2 * (x.cg - 1) : 2 * x.cg;
+    *reinterpret_cast<uint32_t*>(q.codes_row + row * (q.cols >> 1) + (col0 >> 1) + byte_off) = word;
+}
+
+// Axis 0 on the whole tile, in place.
+__device__ __forceinline__ void col_transform(Tile& t, int log2n, uint32_t flip8)
+{
+#pragma unroll
+    for (int h = 0; h < 2; ++h)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            float* v = t.v[h][j];
+            butterfly8(v, log2n);
+            if (log2n > 3) {
+#pragma unroll
+                for (int i = 0; i < 8; ++i) v[i] = stage_dpp<8>(v[i], flip8);
+            }
+            if (log2n > 4) {
+#pragma unroll
+                for (int i = 0; i < 8; i += 2) stage_swap<false>(v[i], v[i + 1]);
+            }
+            if (log2n > 5) {
+#pragma unroll
+                for (int i = 0; i < 8; i += 2) stage_swap<true>(v[i], v[i + 1]);
+            }
+        }
+}
+
+template <bool STOCH>
+__device__ __forceinline__ void col_codes(const Tile& t, const DualCtx& x, int64_t row0, int64_t col0)
+{
+    const DualArgs& q = *x.q;
+    const float magic = kMagic + 8.0f;
+    const int64_t pitch = q.rows >> 1;
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+        uint32_t cw[4][8];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            uint32_t w01[2] = {0u, 0u};
+            if (STOCH)
+                random_pair((row0 + x.rg * 8 + i) * q.cols + col0 + 32 * h + x.cg * 4, q.tid_col,
+                            q.seed_col_lo, q.seed_col_hi, w01);
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const uint32_t u = (w01[j >> 1] >> (16 * (j & 1))) & 0xFFFFu;
+                cw[j][i] = code_word<STOCH>(t.v[h][j][i], x.inv_col, x.qmin_col, x.qmax_col, magic, u);
+            }
+        }
+        // column 32h + 4cg + j, rows 8rg .. 8rg+7: one dword; the eight rg lanes of a
+        // column write 32 consecutive bytes
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            uint8_t* dst = q.codes_col + (col0 + 32 * h + x.cg * 4 + j) * pitch + (row0 >> 1) + x.rg * 4;
+            *reinterpret_cast<uint32_t*>(dst) = pack_nibbles(cw[j]);
+        }
+    }
+}
+
+// One atomicMax per workgroup and record (see block_atomic_max in common.hpp).
+__device__ __forceinline__ void block_atomic_max2(float m_row, float m_col, QMeta* meta_row,
+                                                  QMeta* meta_col, float (*smem)[2])
+{
+    m_row = wave_max(m_row);
+    m_col = wave_max(m_col);
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    if (lane == 0) { smem[wave][0] = m_row; smem[wave][1] = m_col; }
+    __syncthreads();
+    if (threadIdx.x < 2) {
+        const int which = threadIdx.x;
+        float r = smem[0][which];
+        for (int w = 1; w < kThreads / kWave; ++w) r = fmaxf(r, smem[w][which]);
+        QMeta* meta = which ? meta_col : meta_row;
+        const uint32_t slot = (blockIdx.x + blockIdx.y * gridDim.x) % kAmaxSlots;
+        uint32_t* target = &meta->amax[slot * kAmaxSlotStride];
+        const uint32_t bits = __float_as_uint(r);
+        if (bits > __hip_atomic_load(target, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT))
+            atomicMax(target, bits);
+    }
+}
+
+// Wave w of a workgroup owns columns [64*wc, 64*wc + 64) of the workgroup's
+// strip and rows [64*SUBS*wr, 64*SUBS*(wr+1)), (wc, wr) = (w % WC, w / WC).
+#ifndef HDQT_DUAL_MINW
+#define HDQT_DUAL_MINW 1
+#endif
+template <bool QUANT, bool ST_ROW, bool ST_COL, int SUBS>
+__global__ __launch_bounds__(kThreads, HDQT_DUAL_MINW) void fwht_dual_kernel(DualArgs q, int WC)
+{
+    __shared__ float red[kThreads / kWave][2];
+
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int wc = wave % WC, wr = wave / WC, WR = 4 / WC;
+    // pass 2 walks the tensor from its end to its start: it begins with what pass 1
+    // read last, which is most likely still in the memory-side cache
+    const int64_t by = QUANT ? (gridDim.y - 1 - blockIdx.y) : blockIdx.y;
+    const int64_t bx = QUANT ? (gridDim.x - 1 - blockIdx.x) : blockIdx.x;
+    const int64_t col0 = (bx * WC + wc) * kTile;
+    const int64_t strip_row0 = (by * WR + wr) * (kTile * SUBS);
+    // rows % 64 == cols % 64 == 0: a tile is entirely inside the tensor or entirely outside
+    const bool live = col0 < q.cols && strip_row0 < q.rows;
+
+    DualCtx x;
+    x.q = &q;
+    x.cg = lane & 7;
+    x.rg = lane >> 3;
+    x.flip1 = (uint32_t)(lane & 1) << 31;
+    x.flip2 = (uint32_t)(lane & 2) << 30;
+    x.flip4 = (uint32_t)(lane & 4) << 29;
+    x.flip8 = (uint32_t)(lane & 8) << 28;
+    x.inv_row = x.inv_col = 0.0f;
+    x.qmin_row = (float)(-(1 << (q.b_row - 1)));
+    x.qmax_row = (float)((1 << (q.b_row - 1)) - 1);
+    x.qmin_col = (float)(-(1 << (q.b_col - 1)));
+    x.qmax_col = (float)((1 << (q.b_col - 1)) - 1);
+
+    Tile cur, nxt;
+    if (live) tile_load(cur, q, x, strip_row0, col0);
+    if (QUANT) {
+        const Scaling s_row = load_scaling(q.meta_row, q.clip_row, q.b_row);
+        const Scaling s_col = load_scaling(q.meta_col, q.clip_col, q.b_col);
+        x.inv_row = s_row.inv;
+        x.inv_col = s_col.inv;
+        if (blockIdx.x == 0 && blockIdx.y == 0 && threadIdx.x == 0) {
+            q.meta_row->scale = s_row.scale;
+            q.meta_col->scale = s_col.scale;
+            if (q.scale_row_out) *q.scale_row_out = s_row.scale;
+            if (q.scale_col_out) *q.scale_col_out = s_col.scale;
+        }
+    }
+    float amax_row = 0.0f, amax_col = 0.0f;
+    if (live) {
+        // rows % (64 * SUBS) == 0: a live strip has all its SUBS tiles.  The loop stays
+        // rolled: unrolled, every tile's loads are hoisted to the top and the
+        // registers run out.
+#pragma unroll 1
+        for (int sub = 0; sub < SUBS; ++sub) {
+            const int64_t row0 = strip_row0 + sub * kTile;
+            if (sub + 1 < SUBS) tile_load(nxt, q, x, row0 + kTile, col0);
+#pragma unroll
+            for (int i = 0; i < 8; ++i) row_line<QUANT, ST_ROW>(cur, i, x, row0, col0, amax_row);
+            col_transform(cur, q.log2n_col, x.flip8);
+            if (!QUANT) {
+#pragma unroll
+                for (int h = 0; h < 2; ++h)
+#pragma unroll
+                    for (int j = 0; j < 4; ++j)
+#pragma unroll
+                        for (int i = 0; i < 8; ++i) amax_col = fmaxf(amax_col, fabsf(cur.v[h][j][i]));
+            } else {
+                col_codes<ST_COL>(cur, x, row0, col0);
+            }
+            if (sub + 1 < SUBS) cur = nxt;
+        }
+    }
+    if (!QUANT) block_atomic_max2(amax_row, amax_col, q.meta_row, q.meta_col, red);
+}
+
+template <int SUBS>
+hipError_t launch_dual(const DualArgs& q, hipStream_t stream)
+{
+    const int64_t strips = q.cols / kTile;
+    const int WC = (strips % 4 == 0) ? 4 : (strips % 2 == 0) ? 2 : 1;
+    const int WR = 4 / WC;
+    const int64_t tall = (int64_t)kTile * SUBS * WR;
+    const dim3 grid((unsigned)(strips / WC), (unsigned)((q.rows + tall - 1) / tall));
+    {
+        ProfileScope ps(K_DUAL_ABSMAX, stream);
+        hipLaunchKernelGGL((fwht_dual_kernel<false, false, false, SUBS>), grid, dim3(kThreads), 0, stream,
+                           q, WC);
+    }
+    ProfileScope ps(K_DUAL_QUANT, stream);
+    if (q.st_row && q.st_col)
+        hipLaunchKernelGGL((fwht_dual_kernel<true, true, true, SUBS>), grid, dim3(kThreads), 0, stream, q, WC);
+    else if (q.st_row)
+        hipLaunchKernelGGL((fwht_dual_kernel<true, true, false, SUBS>), grid, dim3(kThreads), 0, stream, q, WC);
+    else if (q.st_col)
+        hipLaunchKernelGGL((fwht_dual_kernel<true, false, true, SUBS>), grid, dim3(kThreads), 0, stream, q, WC);
+    else
+        hipLaunchKernelGGL((fwht_dual_kernel<true, false, false, SUBS>), grid, dim3(kThreads), 0, stream, q, WC);
+    return hipGetLastError();
+}
+
+} // namespace
+
+bool quantize_dual_eligible(const DualArgs& q)
+{
+    return (q.rows % kTile == 0) && (q.cols % kTile == 0) && q.log2n_row <= 6 && q.log2n_col <= 6 &&
+           q.b_row <= 4 && q.b_col <= 4 && q.rows / kTile < 65535;
+}
+
+// Pass 1 and pass 2; both calibration records must be zero.
+hipError_t launch_quantize_dual(const DualArgs& q, hipStream_t stream)
+{
+    // column codes leave in runs of 32*SUBS bytes: prefer long runs once there are
+    // enough wave strips to fill the chip several times over
+    // (a strip must consist of whole tiles: SUBS divides rows / 64)
+    const int64_t tall = q.rows / kTile;
+    const int64_t tiles = tall * (q.cols / kTile);
+#ifdef HDQT_EXP_SUBS
+    if (tall % HDQT_EXP_SUBS == 0) return launch_dual<HDQT_EXP_SUBS>(q, stream);
+#endif
+    (void)tiles;
+    return launch_dual<1>(q, stream);
+}
+
+} // namespace hdqt

@@ -1,0 +1,248 @@
+"""GPU parity at the benchmark configurations' full sizes.
+
+Codes and scales of both operands are compared in full (bit-exact); the
+integer accumulators and the dequantized outputs are compared on a few thousand
+sampled positions that the oracle computes one by one (the full products take
+the oracle minutes at these sizes).  The synthetic tensors stand in for the
+paper's CIFAR100 / HAR layers: same shapes, ReLU sparsity, im2col repetition,
+Kaiming weights, small Gaussian gradients, heavy-tailed outliers for the
+square sweep."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import capi
+from paper_2310_03675_amd import binding as B
+from paper_2310_03675_amd import workloads
+
+pytestmark = pytest.mark.gpu
+
+RTOL = 1e-6
+SAMPLES = 4096
+FWD, BWI, BWW = B.GEMM_FWD, B.GEMM_BWD_INPUT, B.GEMM_BWD_WEIGHT
+KIND_NAME = {FWD: "fwd", BWI: "bwd_input", BWW: "bwd_weight"}
+AXES = {FWD: (1, 0), BWI: (1, 1), BWW: (0, 0)}
+
+
+def dev(t):
+    return t.contiguous().to("cuda:0")
+
+
+def operands(kind, layer):
+    return {FWD: (layer.X, layer.W), BWI: (layer.G, layer.W), BWW: (layer.X, layer.G)}[kind]
+
+
+def step_operands(kind, b, layer_id, sr=True):
+    """Measured setting: G stochastic in both backward matmuls, the rest nearest."""
+    tid = lambda role: 16 * layer_id + {"X": 0, "W": 1, "G": 2}[role] + 4 * kind
+    NE, ST = B.ROUND_NEAREST, (B.ROUND_STOCHASTIC if sr else B.ROUND_NEAREST)
+    if kind == FWD:
+        return B.Operand(b, NE, 1.0, tid("X")), B.Operand(b, NE, 1.0, tid("W"))
+    if kind == BWI:
+        return B.Operand(b, ST, 1.0, tid("G")), B.Operand(b, NE, 1.0, tid("W"))
+    return B.Operand(b, NE, 1.0, tid("X")), B.Operand(b, ST, 1.0, tid("G"))
+
+
+def o_op(op):
+    return capi.Operand(b=op.b, round_mode=op.round, clip=op.clip, tensor_id=op.tensor_id)
+
+
+def check_layer(kind, layer, n, b, settings, layer_id=0, sr=True, seed=0):
+    """settings: list of (s, acc_bits).  The oracle quantizes once; every setting is a
+    GPU matmul whose codes, scales and sampled outputs are compared."""
+    M, K, N = layer.M, layer.K, layer.N
+    P, Q = operands(kind, layer)
+    opA, opB = step_operands(kind, b, layer_id, sr)
+    print(f"{KIND_NAME[kind]} {layer.name} n={n} b={b}: oracle quantization ...", flush=True)
+    cA, sA, nA = capi.quantize(P.numpy(), AXES[kind][0], n, o_op(opA), seed)
+    cB, sB, nB = capi.quantize(Q.numpy(), AXES[kind][1], n, o_op(opB), seed)
+    pA, pB = capi.pack_codes(cA, b), capi.pack_codes(cB, b)
+    Pd, Qd = dev(P), dev(Q)
+    rng = np.random.default_rng(1234 + kind)
+    first = True
+    for s, a in settings:
+        print(f"  s={s} a={a}", flush=True)
+        prm = B.Params(had_block=n, acc_bits=a, s=s, seed=seed, A=opA, B=opB)
+        out, acc, ws = B.gemm(kind, Pd, Qd, M, K, N, prm, want_acc=True)
+        L = B.workspace_layout(kind, M, K, N, prm)
+        torch.cuda.synchronize()
+        assert L.n_eff == nA == nB
+        if first:       # the quantization does not depend on (s, a)
+            gA = ws[L.codesA:L.codesA + pA.size].cpu().numpy().reshape(pA.shape)
+            gB = ws[L.codesB:L.codesB + pB.size].cpu().numpy().reshape(pB.shape)
+            assert np.array_equal(gA, pA), "codes of operand A differ"
+            assert np.array_equal(gB, pB), "codes of operand B differ"
+            scales = ws[:L.scaleB + 4].cpu().numpy()
+            assert scales[L.scaleA:L.scaleA + 4].view(np.float32)[0] == sA
+            assert scales[L.scaleB:L.scaleB + 4].view(np.float32)[0] == sB
+            first = False
+        ii = rng.integers(0, L.RA, size=SAMPLES)
+        jj = rng.integers(0, L.RB, size=SAMPLES)
+        # corners and last row / column always included
+        ii[:4] = [0, 0, L.RA - 1, L.RA - 1]
+        jj[:4] = [0, L.RB - 1, 0, L.RB - 1]
+        it, jt = torch.from_numpy(ii).to("cuda:0"), torch.from_numpy(jj).to("cuda:0")
+        got_acc = acc[it, jt].cpu().numpy()
+        got_out = out[it, jt].cpu().numpy()
+        want_acc = capi.tiled_matmul_sampled(cA, cB, s, a, ii, jj)
+        assert np.array_equal(got_acc, want_acc), f"{(got_acc != want_acc).sum()} sampled accumulators differ"
+        want_out = capi.dequantize(want_acc, sA, sB, nA)
+        denom = np.maximum(np.abs(want_out), np.finfo(np.float32).tiny)
+        assert np.all(np.abs(got_out.astype(np.float64) - want_out) <= RTOL * denom)
+        del out, acc, ws
+
+
+# ---------------------------------------------------------------- ResNet-style conv layers
+
+@pytest.mark.parametrize("kind", [FWD, BWI, BWW])
+def test_resnet_conv_k1152(kind):
+    layer = workloads.resnet_conv_layer(256, 128, 128, 16, seed=0)       # M=65536, K=1152, N=128
+    check_layer(kind, layer, 64, 4, [(32, 8), (64, 8)])
+
+
+@pytest.mark.parametrize("kind", [FWD, BWI, BWW])
+def test_resnet_conv_k576(kind):
+    layer = workloads.resnet_conv_layer(256, 64, 64, 32, seed=0)         # M=262144, K=576, N=64
+    check_layer(kind, layer, 64, 4, [(32, 8), (64, 8)])
+
+
+# ---------------------------------------------------------------- square sweep with outliers
+
+@pytest.mark.parametrize("n", [64, 256])
+@pytest.mark.parametrize("b", [4, 8])
+def test_square_4096_forward_sweep(n, b):
+    layer = workloads.square_layer(4096, seed=0)
+    check_layer(FWD, layer, n, b, [(s, a) for a in (8, 16) for s in (16, 64, 256)], sr=False)
+
+
+@pytest.mark.parametrize("kind", [BWI, BWW])
+def test_square_4096_backward(kind):
+    layer = workloads.square_layer(4096, seed=0)
+    check_layer(kind, layer, 64, 4, [(64, 8), (256, 16)], sr=False)
+
+
+def test_square_8192_forward():
+    layer = workloads.square_layer(8192, seed=0)
+    check_layer(FWD, layer, 64, 4, [(64, 8), (16, 16)], sr=False)
+
+
+def test_square_16384_forward():
+    layer = workloads.square_layer(16384, seed=0)
+    check_layer(FWD, layer, 64, 4, [(64, 8)], sr=False)
+
+
+# ---------------------------------------------------------------- ResNet-18 layer shapes, batch 128
+
+def _distinct_resnet18_shapes():
+    seen, out = set(), []
+    for idx, (name, M, K, N) in enumerate(workloads.resnet18_layer_table(128)):
+        if (M, K, N) not in seen:
+            seen.add((M, K, N))
+            out.append((idx, name, M, K, N))
+    return out
+
+
+@pytest.mark.parametrize("idx,name,M,K,N", _distinct_resnet18_shapes())
+def test_resnet18_layer_shapes(idx, name, M, K, N):
+    """Every distinct matmul shape of a CIFAR-width ResNet-18 training step at batch 128
+    (stem K = 27 and classifier N = 100 included), all three matmuls.  The tensors are
+    synthetic with the layer's shape: ReLU activations, Kaiming weights, Gaussian gradients."""
+    g = torch.Generator().manual_seed(5000 + idx)
+    X = torch.relu(torch.randn((M, K), generator=g))
+    W = torch.randn((K, N), generator=g) * (2.0 / K) ** 0.5
+    G = torch.randn((M, N), generator=g) * 1e-2
+    layer = workloads.Layer(name, X, W, G)
+    for kind in (FWD, BWI, BWW):
+        if name == "stem" and kind == BWI:
+            continue            # the first layer needs no input gradient
+        check_layer(kind, layer, 64, 4, [(32, 8)], layer_id=idx)
+
+
+# ---------------------------------------------------------------- degenerate shapes and settings
+
+@pytest.mark.parametrize("M,K,N", [(1, 64, 1), (1, 1, 1), (2, 2, 2), (129, 33, 65), (64, 8, 300),
+                                   (257, 256, 3)])
+def test_tiny_and_odd_shapes(M, K, N):
+    layer = workloads.fc_layer(M, K, N, seed=7)
+    for kind in (FWD, BWI, BWW):
+        for n, s, a in ((64, 32, 8), (256, 1, 4), (1, 1000, 2), (8, 3, 32)):
+            prm_ops = step_operands(kind, 4, 1)
+            prm = B.Params(had_block=n, acc_bits=a, s=s, seed=11, A=prm_ops[0], B=prm_ops[1])
+            P, Q = operands(kind, layer)
+            out, acc, _ = B.gemm(kind, dev(P), dev(Q), M, K, N, prm, want_acc=True)
+            torch.cuda.synchronize()
+            ref = capi.gemm({FWD: capi.FWD, BWI: capi.BWD_INPUT, BWW: capi.BWD_WEIGHT}[kind],
+                            P.numpy(), Q.numpy(), M, K, N,
+                            capi.Params(n, a, s, 11, o_op(prm_ops[0]), o_op(prm_ops[1])))
+            assert np.array_equal(acc.cpu().numpy(), ref["acc"]), (kind, n, s, a)
+            got = out.cpu().numpy()
+            denom = np.maximum(np.abs(ref["out"]), np.finfo(np.float32).tiny)
+            assert np.all(np.abs(got - ref["out"]) <= RTOL * denom)
+
+
+def test_constant_and_zero_operands():
+    M, K, N = 96, 128, 80
+    zeros = torch.zeros((M, K))
+    ones = torch.ones((K, N))
+    G = torch.full((M, N), -2.5)
+    layer = workloads.Layer("const", zeros, ones, G)
+    for kind in (FWD, BWI, BWW):
+        check_layer(kind, layer, 64, 4, [(32, 8)], sr=True)
+    layer = workloads.Layer("const2", torch.full((M, K), 3.0), ones, G)
+    for kind in (FWD, BWI, BWW):
+        check_layer(kind, layer, 64, 4, [(32, 8), (128, 12)], sr=True)
+
+
+# ---------------------------------------------------------------- the whole step in one call
+
+def _step_params(n, s, a, seed, layer_id=0, b=4):
+    out = []
+    for kind in (FWD, BWI, BWW):
+        opA, opB = step_operands(kind, b, layer_id)
+        out.append(B.Params(had_block=n, acc_bits=a, s=s, seed=seed + kind, A=opA, B=opB))
+    return out
+
+
+@pytest.mark.parametrize("M,K,N,n,s,a", [
+    (256, 128, 64, 64, 32, 8),          # both tensors take the fused two-axis kernels
+    (512, 1152, 128, 64, 32, 8),
+    (8192, 576, 64, 64, 64, 8),
+    (320, 192, 128, 16, 16, 6),
+    (129, 33, 65, 64, 32, 8),           # nothing aligned: single-axis kernels throughout
+    (256, 128, 72, 64, 32, 8),          # X fused, G not
+    (1024, 256, 256, 256, 64, 16),      # block order above the fused kernels' range
+    (64, 64, 64, 8, 1000, 32),
+])
+def test_layer_step_equals_three_matmuls(M, K, N, n, s, a):
+    """hdqt_layer_step against hdqt_gemm_fwd / _bwd_input / _bwd_weight (which the tests
+    above check against the oracle): every output bit-identical."""
+    layer = workloads.fc_layer(M, K, N, seed=3)
+    X, W, G = dev(layer.X), dev(layer.W), dev(layer.G)
+    pf, pi, pw = _step_params(n, s, a, seed=41)
+    print(f"layer_step M={M} K={K} N={N} n={n} s={s} a={a}", flush=True)
+    Z, dX, dW, _ = B.layer_step(X, W, G, pf, pi, pw)
+    Z3, _, _ = B.gemm(FWD, X, W, M, K, N, pf)
+    dX3, _, _ = B.gemm(BWI, G, W, M, K, N, pi)
+    dW3, _, _ = B.gemm(BWW, X, G, M, K, N, pw)
+    torch.cuda.synchronize()
+    assert torch.equal(Z, Z3) and torch.equal(dX, dX3) and torch.equal(dW, dW3)
+    # first layer of a network: no input gradient
+    Zb, none, dWb, _ = B.layer_step(X, W, G, pf, None, pw)
+    torch.cuda.synchronize()
+    assert none is None and torch.equal(Zb, Z3) and torch.equal(dWb, dW3)
+
+
+def test_layer_step_resnet_conv_k1152():
+    """The benchmark's step at full size, twice in the same workspace."""
+    layer = workloads.resnet_conv_layer(256, 128, 128, 16, seed=0)
+    M, K, N = layer.M, layer.K, layer.N
+    X, W, G = dev(layer.X), dev(layer.W), dev(layer.G)
+    pf, pi, pw = _step_params(64, 32, 8, seed=0)
+    Z3, _, _ = B.gemm(FWD, X, W, M, K, N, pf)
+    dX3, _, _ = B.gemm(BWI, G, W, M, K, N, pi)
+    dW3, _, _ = B.gemm(BWW, X, G, M, K, N, pw)
+    ws = None
+    for _ in range(2):
+        Z, dX, dW, ws = B.layer_step(X, W, G, pf, pi, pw, workspace=ws)
+        torch.cuda.synchronize()
+        assert torch.equal(Z, Z3) and torch.equal(dX, dX3) and torch.equal(dW, dW3)

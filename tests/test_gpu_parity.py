@@ -280,3 +280,40 @@ def test_ragged_layers(kind):
     check_whole_gemm(kind, layer, step_params(kind, 64, 32))
     layer = workloads.fc_layer(128, 561, 11, seed=5)      # HAR FCN widths of the paper's energy table
     check_whole_gemm(kind, layer, step_params(kind, 32, 32))
+
+
+# ------------------------------------------------------------------ both axes from one read
+
+def check_quantize_dual(T: np.ndarray, n: int, op1: B.Operand, op0: B.Operand, seed: int = 0):
+    print(f"quantize_dual shape={T.shape} n={n} b=({op1.b},{op0.b}) round=({op1.round},{op0.round})",
+          flush=True)
+    c1, s1, c0, s0 = B.quantize_dual(dev(T), n, op1, op0, seed)
+    for axis, op, cg, sg in ((1, op1, c1, s1), (0, op0, c0, s0)):
+        codes_o, scale_o, _ = capi.quantize(T, axis, n, o_operand(op), seed)
+        want = capi.pack_codes(codes_o, op.b)
+        got = host(cg)
+        assert host(sg)[0] == scale_o, (axis, host(sg)[0], scale_o)
+        if not np.array_equal(got, want):
+            bad = np.argwhere(got != want)
+            raise AssertionError(f"axis {axis}: {len(bad)} code bytes differ, first at {bad[0]}")
+
+
+@pytest.mark.parametrize("rows,cols,n", [(64, 64, 64), (128, 192, 64), (256, 64, 16), (64, 256, 32),
+                                         (320, 128, 64), (512, 1152, 64), (1024, 128, 64), (192, 64, 1),
+                                         (100, 64, 64), (64, 72, 64), (256, 256, 256), (37, 27, 64)])
+def test_quantize_dual(rows, cols, n):
+    rng = np.random.default_rng(rows * 31 + cols)
+    T = (rng.standard_normal((rows, cols)) * 0.37).astype(np.float32)
+    NE, ST = B.ROUND_NEAREST, B.ROUND_STOCHASTIC
+    check_quantize_dual(T, n, B.Operand(4, NE, 1.0, 1), B.Operand(4, NE, 1.0, 2))
+    check_quantize_dual(T, n, B.Operand(4, ST, 1.0, 3), B.Operand(4, ST, 1.0, 4), seed=77)
+    check_quantize_dual(T, n, B.Operand(4, NE, 0.975, 5), B.Operand(3, ST, 1.0, 6), seed=5)
+    check_quantize_dual(T, n, B.Operand(2, ST, 1.0, 7), B.Operand(4, NE, 1.0, 8), seed=6)
+
+
+def test_quantize_dual_wider_codes_and_zero():
+    rng = np.random.default_rng(2)
+    T = rng.standard_normal((128, 128)).astype(np.float32)
+    check_quantize_dual(T, 64, B.Operand(8), B.Operand(4))
+    check_quantize_dual(T, 64, B.Operand(4), B.Operand(6, B.ROUND_STOCHASTIC, 1.0, 9), seed=3)
+    check_quantize_dual(np.zeros((64, 128), np.float32), 64, B.Operand(4), B.Operand(4, B.ROUND_STOCHASTIC))
