@@ -27,6 +27,16 @@ if ROOT not in sys.path:
 
 METRIC = "effective int TOPS of HDQT backward GEMMs (% int8 MFMA peak); FWHT-quant GB/s"
 HBM_PEAK_GBPS = 8000.0          # MI355X HBM3E
+# HBM bytes per launch (fetch + write) of the default workload's kernels, from the
+# rocprofv3 FETCH_SIZE / WRITE_SIZE runs summarised in
+# profiles/bench_resnet_k1152_hbm_traffic.md (per-launch average over the tensors a
+# kernel family runs on); bench.py cannot collect counters itself.
+MEASURED_TRAFFIC = {
+    "fwht_dual_absmax_X": 302.2e6, "fwht_dual_quant_X": 378.6e6,
+    "fwht_dual_absmax_W": 0.8e6, "fwht_dual_quant_W": 1.1e6,
+    "fwht_dual_absmax_G": 33.8e6, "fwht_dual_quant_G": 42.6e6,
+    "gemm_i4_fwd": 74.6e6, "gemm_i4_bwd_input": 327.6e6, "gemm_i4_bwd_weight": 98.9e6,
+}
 INT8_MFMA_PEAK_TOPS = 5000.0    # MI355X dense int8
 
 WORKLOADS = {
@@ -172,47 +182,58 @@ def main():
     value = ops_step / (dt / args.steps) / 1e12
 
     # ---- per-kernel table.  Algorithmic bytes / operations of one step, per kernel:
-    #   absmax pass: 4 B read per element; quantize pass: 4 B read + 0.5 B written;
+    #   absmax pass: 4 B read per element; quantize pass: 4 B read + 0.5 B written per axis;
     #   matmul: packed operands read once (0.5 B per code) + fp32 output written once,
     #   2*M*K*N operations each.
     elems = {"X": M * K, "W": K * N, "G": M * N}
-    #   two-axis kernels: 4 B read per element per pass, 2 x 0.5 B written in the second.
-    per_elem = {"absmax": 4.0, "quant": 4.0 + 0.5}
     if args.separate:
         seen = {"fwht_row": ["X", "G", "W"],      # axis 1: X (fwd), G and W (bwd_input)
                 "fwht_col": ["W", "X", "G"]}      # axis 0: W (fwd), X and G (bwd_weight)
     else:
-        seen = {"fwht_row": ["W"], "fwht_col": ["W"], "fwht_dua": ["X", "G"]}
-    gemm_bytes_step = (0.5 * (M * K + K * N) + 4.0 * M * N) + (0.5 * (M * N + K * N) + 4.0 * M * K) \
-        + (0.5 * (M * K + M * N) + 4.0 * K * N)
+        seen = {"fwht_dua": ["X", "W", "G"]}      # both axes of each tensor from one read per pass
+    gemm_bytes = {"fwd": 0.5 * (M * K + K * N) + 4.0 * M * N,
+                  "bwd_input": 0.5 * (M * N + K * N) + 4.0 * M * K,
+                  "bwd_weight": 0.5 * (M * K + M * N) + 4.0 * K * N}
+    measured = MEASURED_TRAFFIC if (args.workload == "resnet_k1152" and args.s == 32
+                                    and args.acc_bits == 8 and not args.separate) else {}
     kernels, roof_all = {}, {}
     for name, (l, tot) in kern.items():
         avg_s = tot / l * 1e-3
-        kernels[name] = {"launches_per_step": l / args.steps, "avg_us": avg_s * 1e6,
+        per_step = l / args.steps
+        kernels[name] = {"launches_per_step": per_step, "avg_us": avg_s * 1e6,
                          "us_per_step": tot / args.steps * 1e3}
         fam = name[:8]
         if fam in seen:
-            kind = "absmax" if name.endswith("absmax") else "quant"
-            bytes_step = (per_elem[kind] + (0.5 if fam == "fwht_dua" and kind == "quant" else 0.0)) \
-                * sum(elems[t] for t in seen[fam])
-            gbps = bytes_step * args.steps / (tot * 1e-3) / 1e9
+            absmax = "absmax" in name
+            per_elem = 4.0 if absmax else 4.0 + (1.0 if fam == "fwht_dua" else 0.5)
+            # hdqt_layer_step names the tensor of each two-axis launch (..._X, _W, _G)
+            tensors = [name[-1]] if name[-2:] in ("_X", "_W", "_G") else seen[fam]
+            bytes_launch = per_elem * sum(elems[t] for t in tensors) / per_step
+            gbps = bytes_launch / avg_s / 1e9
             roof_all[name] = {"bound": "hbm", "achieved": gbps, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
-                              "frac": gbps / HBM_PEAK_GBPS, "traffic": None,
-                              "algorithmic_bytes_per_launch": bytes_step / (l / args.steps)}
-        elif name.startswith("gemm"):
-            tops = ops_step * args.steps / (tot * 1e-3) / 1e12
-            roof_all[name] = {"bound": "mfma", "achieved": tops, "peak": INT8_MFMA_PEAK_TOPS,
-                              "unit": "TOP/s", "frac": tops / INT8_MFMA_PEAK_TOPS, "traffic": None,
-                              "algorithmic_ops_per_launch": ops_step / (l / args.steps),
-                              "hbm_GBps": gemm_bytes_step * args.steps / (tot * 1e-3) / 1e9}
+                              "frac": gbps / HBM_PEAK_GBPS, "traffic": measured.get(name),
+                              "algorithmic_bytes_per_launch": bytes_launch}
+        elif name.startswith("gemm_i4_"):
+            which = name[len("gemm_i4_"):]
+            tops = ops_step / 3 / avg_s / 1e12
+            gbps = gemm_bytes[which] / avg_s / 1e9
+            f_mfma, f_hbm = tops / INT8_MFMA_PEAK_TOPS, gbps / HBM_PEAK_GBPS
+            # the roofline that binds is the one the kernel sits closer to
+            if f_hbm >= f_mfma:
+                roof_all[name] = {"bound": "hbm", "achieved": gbps, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                                  "frac": f_hbm, "traffic": measured.get(name),
+                                  "algorithmic_bytes_per_launch": gemm_bytes[which], "mfma_TOPs": tops}
+            else:
+                roof_all[name] = {"bound": "mfma", "achieved": tops, "peak": INT8_MFMA_PEAK_TOPS,
+                                  "unit": "TOP/s", "frac": f_mfma, "traffic": measured.get(name),
+                                  "algorithmic_ops_per_launch": ops_step / 3, "hbm_GBps": gbps}
     dominant = max(roof_all, key=lambda k: kern[k][1])
     roofline = dict(roof_all[dominant], kernel=dominant)
-    gemm_ms = sum(tot for name, (l, tot) in kern.items() if name.startswith("gemm") or name == "dequant")
+    gemm_ms = sum(tot for name, (l, tot) in kern.items() if name.startswith("gemm") or name == "reduce_splits")
     gemm_tops = ops_step * args.steps / (gemm_ms * 1e-3) / 1e12 if gemm_ms else None
     quant_ms = sum(tot for name, (l, tot) in kern.items() if name.startswith("fwht"))
     quant_bytes = args.steps * sum(
-        (per_elem["absmax"] + per_elem["quant"] + (0.5 if fam == "fwht_dua" else 0.0)) * elems[t]
-        for fam, ts in seen.items() for t in ts)
+        (4.0 + 4.0 + (1.0 if fam == "fwht_dua" else 0.5)) * elems[t] for fam, ts in seen.items() for t in ts)
     line = {
         "metric": METRIC, "value": value, "unit": "TOPS", "n_gpus": 1, "steps": args.steps,
         "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": True,

@@ -97,7 +97,7 @@ typedef struct {
     size_t scaleB;   /* float */
     size_t codesA;   /* packed codes [RA, D] */
     size_t codesB;   /* packed codes [RB, D] */
-    size_t acc;      /* int32 [RA, RB] */
+    size_t acc;      /* int32 slices of a split contraction (see hdqt_gemm_codes) */
     size_t total;    /* bytes required */
     int64_t RA, RB, D;
     int32_t n_eff;
@@ -175,9 +175,13 @@ int hdqt_quantize_dual(const float *T, int64_t rows, int64_t cols, int had_block
  *   scaleA, scaleB          device pointers to one float each
  *   out     fp32 [RA, RB] (device, may be NULL if acc_out is given)
  *   acc_out int32 [RA, RB] (device, may be NULL)
- *   workspace: RA*RB*4 bytes are needed only when both acc_out is NULL and the
- *   contraction is split over workgroups; hdqt_workspace_size covers it.
+ *   workspace: hdqt_gemm_codes_workspace_size(RA, RB, D, s) bytes of device memory
+ *   (0 for most shapes, then NULL is fine).  Few output tiles with a long
+ *   contraction are split over workgroups along the contraction; every part
+ *   writes its totals (sums of whole clamped tiles, so the result is the same)
+ *   to a slice of the workspace and a second pass adds the slices.
  */
+size_t hdqt_gemm_codes_workspace_size(int64_t RA, int64_t RB, int64_t D, int64_t s);
 int hdqt_gemm_codes(const void *qA, const void *qB, int bA, int bB, const float *scaleA,
                     const float *scaleB, int64_t RA, int64_t RB, int64_t D, int n_eff,
                     int acc_bits, int64_t s, float *out, int32_t *acc_out, void *workspace,

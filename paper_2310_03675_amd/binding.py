@@ -24,6 +24,7 @@ EXPORTED = [
     "hdqt_gemm_bwd_input", "hdqt_gemm_bwd_weight", "hdqt_strerror", "hdqt_last_hip_error",
     "hdqt_profile_enable", "hdqt_profile_collect", "hdqt_quantize_dual",
     "hdqt_quantize_dual_workspace_size", "hdqt_layer_step_workspace_size", "hdqt_layer_step",
+    "hdqt_gemm_codes_workspace_size",
 ]
 
 
@@ -105,6 +106,8 @@ def load() -> C.CDLL:
                                   vp, sz, vp]
     lib.hdqt_quantize_dual_workspace_size.restype = sz
     lib.hdqt_quantize_dual_workspace_size.argtypes = []
+    lib.hdqt_gemm_codes_workspace_size.restype = sz
+    lib.hdqt_gemm_codes_workspace_size.argtypes = [i64, i64, i64, i64]
     lib.hdqt_layer_step_workspace_size.restype = sz
     lib.hdqt_layer_step_workspace_size.argtypes = [i64, i64, i64] + [C.POINTER(CParams)] * 3
     lib.hdqt_layer_step.restype = i32
@@ -242,7 +245,8 @@ def gemm_codes(qA: torch.Tensor, qB: torch.Tensor, bA: int, bB: int, scaleA: tor
     if acc is None and want_acc:
         acc = torch.empty((RA, RB), dtype=torch.int32, device=qA.device)
     if workspace is None:
-        workspace = torch.empty(max(RA * RB * 4, 256), dtype=torch.uint8, device=qA.device)
+        need = load().hdqt_gemm_codes_workspace_size(RA, RB, D, s)
+        workspace = torch.empty(max(need, 256), dtype=torch.uint8, device=qA.device)
     rc = load().hdqt_gemm_codes(_ptr(qA), _ptr(qB), bA, bB, _ptr(scaleA), _ptr(scaleB), RA, RB, D,
                                 n, acc_bits, s, _ptr(out), _ptr(acc), _ptr(workspace),
                                 workspace.numel(), _stream(stream))

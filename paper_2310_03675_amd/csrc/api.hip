@@ -107,13 +107,14 @@ int hip_fail(hipError_t e)
     return HDQT_EHIP;
 }
 
-// how many workgroups share an output tile along the contraction
+// How many workgroups share an output tile along the contraction.  The matmul
+// kernels keep two workgroups per CU resident (512 on the chip): the split fills
+// those places once and never spills a few workgroups into a second round.
 int choose_splits(int64_t RA, int64_t RB, int64_t n_tiles)
 {
     const int64_t blocks = ((RA + 127) / 128) * ((RB + 127) / 128);
-    if (blocks >= 512 || n_tiles < 8) return 1;
-    // two workgroups per CU; every further split adds a full set of output atomics
-    int64_t want = (512 + blocks - 1) / blocks;
+    if (blocks > 256 || n_tiles < 8) return 1;
+    int64_t want = 512 / blocks;
     if (want > n_tiles / 4) want = n_tiles / 4;
     if (want > 1024) want = 1024;
     return want < 1 ? 1 : (int)want;
@@ -142,9 +143,10 @@ int run_quantize(const float* T, int64_t rows, int64_t cols, int axis, int n_eff
 int run_quantize_pair(const float* T, int64_t rows, int64_t cols, int n1, const hdqt_operand_t* op1,
                       uint64_t seed1, int n0, const hdqt_operand_t* op0, uint64_t seed0,
                       hdqt::QMeta* meta1, hdqt::QMeta* meta0, void* codes1, void* codes0,
-                      float* scale1_out, float* scale0_out, hipStream_t stream)
+                      float* scale1_out, float* scale0_out, hipStream_t stream, int profile_tag = 0)
 {
     hdqt::DualArgs d{};
+    d.profile_tag = profile_tag;
     d.T = T; d.rows = rows; d.cols = cols;
     d.log2n_row = log2i(n1); d.log2n_col = log2i(n0);
     d.b_row = op1->b; d.st_row = (op1->round == HDQT_ROUND_STOCHASTIC);
@@ -168,9 +170,10 @@ int run_quantize_pair(const float* T, int64_t rows, int64_t cols, int n1, const 
 // Resolve tile length, accumulator range and the split of the contraction.
 hdqt::GemmArgs plan_gemm(const void* qA, const void* qB, int bA, int bB, const float* scaleA,
                          const float* scaleB, int64_t RA, int64_t RB, int64_t D, int n_eff,
-                         int acc_bits, int64_t s, float* out, int32_t* acc_out)
+                         int acc_bits, int64_t s, float* out, int32_t* acc_out, int profile_tag = 0)
 {
     hdqt::GemmArgs g{};
+    g.profile_tag = profile_tag;
     g.qA = static_cast<const uint8_t*>(qA); g.qB = static_cast<const uint8_t*>(qB);
     g.pitchA = hdqt_codes_pitch(D, bA); g.pitchB = hdqt_codes_pitch(D, bB);
     g.bA = bA; g.bB = bB; g.RA = RA; g.RB = RB; g.D = D;
@@ -188,27 +191,27 @@ hdqt::GemmArgs plan_gemm(const void* qA, const void* qB, int bA, int bB, const f
     return g;
 }
 
-// With a split contraction the workgroups add their partial totals into an
-// int32 buffer (acc_out, or the workspace when the caller wants no accumulators)
-// that must be zero beforehand; the dequantization is then a pass of its own.
-int run_planned_gemm(hdqt::GemmArgs g, int32_t* acc_ws, bool target_is_zero, hipStream_t stream)
+// Bytes of workspace the matmul needs: with a split contraction every part writes
+// its totals to a slice of its own ([splits, RA, RB] int32), summed by a second pass.
+size_t partial_bytes(int64_t RA, int64_t RB, int64_t D, int64_t s)
+{
+    const int64_t s_eff = s < D ? s : D;
+    const int splits = choose_splits(RA, RB, (D + s_eff - 1) / s_eff);
+    return splits > 1 ? (size_t)splits * (size_t)(RA * RB) * sizeof(int32_t) : 0;
+}
+
+int run_planned_gemm(hdqt::GemmArgs g, void* ws, size_t ws_bytes, hipStream_t stream)
 {
     hipError_t e;
     if (g.splits > 1) {
-        int32_t* target = g.acc_out ? g.acc_out : acc_ws;
-        if (!target) return HDQT_EWORKSPACE;
-        g.acc_out = target;
-        if (!target_is_zero) {
-            e = hdqt::launch_zero2(reinterpret_cast<uint32_t*>(target), g.RA * g.RB, nullptr, 0, stream);
-            if (e != hipSuccess) return hip_fail(e);
-        }
+        if (!ws || ws_bytes < (size_t)g.splits * (size_t)(g.RA * g.RB) * sizeof(int32_t))
+            return HDQT_EWORKSPACE;
+        g.partial = static_cast<int32_t*>(ws);
         e = hdqt::launch_gemm(g, stream);
         if (e != hipSuccess) return hip_fail(e);
-        if (g.out) {
-            e = hdqt::launch_dequant(target, g.RA * g.RB, g.scaleA, g.scaleB, g.inv_n, g.out, stream);
-            if (e != hipSuccess) return hip_fail(e);
-        }
-        return HDQT_OK;
+        e = hdqt::launch_reduce(g.partial, g.splits, g.RA * g.RB, g.scaleA, g.scaleB, g.inv_n, g.out,
+                                g.acc_out, stream);
+        return e == hipSuccess ? HDQT_OK : hip_fail(e);
     }
     e = hdqt::launch_gemm(g, stream);
     return e == hipSuccess ? HDQT_OK : hip_fail(e);
@@ -232,14 +235,11 @@ int run_gemm(int kind, const float* P, const float* Q, float* out, int64_t M, in
     hdqt::QMeta* metaB = reinterpret_cast<hdqt::QMeta*>(base + L.scaleB);
     void* codesA = base + L.codesA;
     void* codesB = base + L.codesB;
-    int32_t* acc_ws = reinterpret_cast<int32_t*>(base + L.acc);
     hdqt::GemmArgs g = plan_gemm(codesA, codesB, prm->A.b, prm->B.b, &metaA->scale, &metaB->scale,
-                                 o.RA, o.RB, o.D, L.n_eff, prm->acc_bits, prm->s, out, acc_out);
-    // one launch clears both calibration records (they are adjacent) and, when the
-    // contraction is split, the accumulation target
-    uint32_t* acc_target = g.splits > 1 ? reinterpret_cast<uint32_t*>(acc_out ? acc_out : acc_ws) : nullptr;
+                                 o.RA, o.RB, o.D, L.n_eff, prm->acc_bits, prm->s, out, acc_out, 1 + kind);
+    // one launch clears both calibration records (they are adjacent)
     hipError_t e = hdqt::launch_zero2(reinterpret_cast<uint32_t*>(metaA), (int64_t)(2 * kMetaBytes / 4),
-                                      acc_target, acc_target ? o.RA * o.RB : 0, stream);
+                                      nullptr, 0, stream);
     if (e != hipSuccess) return hip_fail(e);
     rc = run_quantize(P, o.a_rows, o.a_cols, o.a_axis, L.n_eff, &prm->A, prm->seed, metaA, codesA,
                       nullptr, stream);
@@ -247,18 +247,18 @@ int run_gemm(int kind, const float* P, const float* Q, float* out, int64_t M, in
     rc = run_quantize(Q, o.b_rows, o.b_cols, o.b_axis, L.n_eff, &prm->B, prm->seed, metaB, codesB,
                       nullptr, stream);
     if (rc) return rc;
-    return run_planned_gemm(g, acc_ws, true, stream);
+    return run_planned_gemm(g, base + L.acc, L.total - L.acc, stream);
 }
 
 
-// Workspace of hdqt_layer_step.  Offsets in bytes; the calibration records and the
-// accumulation targets of split contractions are contiguous from offset 0, so one
-// launch clears them all.
+// Workspace of hdqt_layer_step.  Offsets in bytes; the calibration records are
+// contiguous from offset 0, so one launch clears them all.
 enum { T_X1, T_X0, T_W0, T_W1, T_G1, T_G0, T_COUNT };
 struct StepLayout {
     size_t meta[T_COUNT];
     size_t codes[T_COUNT];
-    size_t acc[3];           // per matmul; meaningful when splits[k] > 1
+    size_t acc[3];           // per matmul: slices of a split contraction
+    size_t acc_bytes[3];
     int splits[3];
     int n_eff[3];
     size_t zero_bytes;
@@ -278,15 +278,21 @@ int plan_step(int64_t M, int64_t K, int64_t N, const hdqt_params_t* const prm[3]
     for (int t = 0; t < T_COUNT; ++t) { L->meta[t] = off; off += kMetaBytes; }
     for (int k = 0; k < 3; ++k) {
         L->acc[k] = off;
+        L->acc_bytes[k] = 0;
         L->splits[k] = 1;
         L->n_eff[k] = 1;
         if (k == HDQT_GEMM_BWD_INPUT && !with_dx) continue;
         L->n_eff[k] = hdqt_n_eff(o[k].D, prm[k]->had_block);
         const int64_t s = prm[k]->s < o[k].D ? prm[k]->s : o[k].D;
         L->splits[k] = choose_splits(o[k].RA, o[k].RB, (o[k].D + s - 1) / s);
-        if (L->splits[k] > 1) off = align_up(off + (size_t)(o[k].RA * o[k].RB) * sizeof(int32_t), 256);
     }
     L->zero_bytes = off;
+    for (int k = 0; k < 3; ++k) {
+        L->acc[k] = off;
+        if (k == HDQT_GEMM_BWD_INPUT && !with_dx) continue;
+        L->acc_bytes[k] = partial_bytes(o[k].RA, o[k].RB, o[k].D, prm[k]->s);
+        off = align_up(off + L->acc_bytes[k], 256);
+    }
     const hdqt_params_t *fwd = prm[0], *bwi = prm[1], *bww = prm[2];
     const size_t bytes[T_COUNT] = {
         (size_t)(M * hdqt_codes_pitch(K, fwd->A.b)),                 // X along K
@@ -340,7 +346,7 @@ int hdqt_workspace_layout(int gemm_kind, int64_t M, int64_t K, int64_t N,
     L.codesB = off;
     off = align_up(off + (size_t)(o.RB * hdqt_codes_pitch(o.D, params->B.b)), 256);
     L.acc = off;
-    off = align_up(off + (size_t)(o.RA * o.RB) * sizeof(int32_t), 256);
+    off = align_up(off + partial_bytes(o.RA, o.RB, o.D, params->s) + 256, 256);
     L.total = off;
     if (layout) *layout = L;
     return HDQT_OK;
@@ -405,6 +411,12 @@ int hdqt_quantize_dual(const float* T, int64_t rows, int64_t cols, int had_block
                              codes_axis0, scale_axis1, scale_axis0, stream);
 }
 
+size_t hdqt_gemm_codes_workspace_size(int64_t RA, int64_t RB, int64_t D, int64_t s)
+{
+    if (RA <= 0 || RB <= 0 || D <= 0 || s < 1 || RA >= kMaxDim || RB >= kMaxDim || D >= kMaxDim) return 0;
+    return partial_bytes(RA, RB, D, s);
+}
+
 int hdqt_gemm_codes(const void* qA, const void* qB, int bA, int bB, const float* scaleA,
                     const float* scaleB, int64_t RA, int64_t RB, int64_t D, int n_eff,
                     int acc_bits, int64_t s, float* out, int32_t* acc_out, void* workspace,
@@ -423,12 +435,9 @@ int hdqt_gemm_codes(const void* qA, const void* qB, int bA, int bB, const float*
     if (misaligned(qA) || misaligned(qB) || misaligned(out) || misaligned(acc_out) ||
         misaligned(workspace))
         return HDQT_EALIGN;
-    int32_t* acc_ws = nullptr;
-    if (workspace && workspace_bytes >= (size_t)(RA * RB) * sizeof(int32_t))
-        acc_ws = static_cast<int32_t*>(workspace);
     return run_planned_gemm(plan_gemm(qA, qB, bA, bB, scaleA, scaleB, RA, RB, D, n_eff, acc_bits, s,
                                       out, acc_out),
-                            acc_ws, false, static_cast<hipStream_t>(stream));
+                            workspace, workspace_bytes, static_cast<hipStream_t>(stream));
 }
 
 size_t hdqt_layer_step_workspace_size(int64_t M, int64_t K, int64_t N, const hdqt_params_t* fwd,
@@ -459,7 +468,7 @@ int hdqt_layer_step(const float* X, const float* W, const float* G, float* Z, fl
     char* base = static_cast<char*>(workspace);
     auto meta = [&](int t) { return reinterpret_cast<hdqt::QMeta*>(base + L.meta[t]); };
     auto codes = [&](int t) { return static_cast<void*>(base + L.codes[t]); };
-    auto acc = [&](int k) { return L.splits[k] > 1 ? reinterpret_cast<int32_t*>(base + L.acc[k]) : nullptr; };
+    auto acc = [&](int k) { return static_cast<void*>(base + L.acc[k]); };
 
     hipError_t e = hdqt::launch_zero2(reinterpret_cast<uint32_t*>(base), (int64_t)(L.zero_bytes / 4),
                                       nullptr, 0, stream);
@@ -469,28 +478,32 @@ int hdqt_layer_step(const float* X, const float* W, const float* G, float* Z, fl
     const int nF = L.n_eff[HDQT_GEMM_FWD], nI = L.n_eff[HDQT_GEMM_BWD_INPUT],
               nW = L.n_eff[HDQT_GEMM_BWD_WEIGHT];
     rc = run_quantize_pair(X, M, K, nF, &fwd->A, fwd->seed, nW, &bwd_weight->A, bwd_weight->seed,
-                           meta(T_X1), meta(T_X0), codes(T_X1), codes(T_X0), nullptr, nullptr, stream);
+                           meta(T_X1), meta(T_X0), codes(T_X1), codes(T_X0), nullptr, nullptr, stream, 1);
     if (rc) return rc;
-    rc = run_quantize(W, K, N, 0, nF, &fwd->B, fwd->seed, meta(T_W0), codes(T_W0), nullptr, stream);
+    // W along K for the forward product and, when dX is wanted, along N for the input gradient
+    if (with_dx)
+        rc = run_quantize_pair(W, K, N, nI, &bwd_input->B, bwd_input->seed, nF, &fwd->B, fwd->seed,
+                               meta(T_W1), meta(T_W0), codes(T_W1), codes(T_W0), nullptr, nullptr, stream, 2);
+    else
+        rc = run_quantize(W, K, N, 0, nF, &fwd->B, fwd->seed, meta(T_W0), codes(T_W0), nullptr, stream);
     if (rc) return rc;
     rc = run_planned_gemm(plan_gemm(codes(T_X1), codes(T_W0), fwd->A.b, fwd->B.b, &meta(T_X1)->scale,
-                                    &meta(T_W0)->scale, M, N, K, nF, fwd->acc_bits, fwd->s, Z, nullptr),
-                          acc(HDQT_GEMM_FWD), true, stream);
+                                    &meta(T_W0)->scale, M, N, K, nF, fwd->acc_bits, fwd->s, Z, nullptr,
+                                    1 + HDQT_GEMM_FWD),
+                          acc(HDQT_GEMM_FWD), L.acc_bytes[HDQT_GEMM_FWD], stream);
     if (rc) return rc;
 
-    // ---- backward: G along N and along M, W along N
+    // ---- backward: G along N and along M
     if (with_dx) {
         rc = run_quantize_pair(G, M, N, nI, &bwd_input->A, bwd_input->seed, nW, &bwd_weight->B,
                                bwd_weight->seed, meta(T_G1), meta(T_G0), codes(T_G1), codes(T_G0),
-                               nullptr, nullptr, stream);
-        if (rc) return rc;
-        rc = run_quantize(W, K, N, 1, nI, &bwd_input->B, bwd_input->seed, meta(T_W1), codes(T_W1),
-                          nullptr, stream);
+                               nullptr, nullptr, stream, 3);
         if (rc) return rc;
         rc = run_planned_gemm(plan_gemm(codes(T_G1), codes(T_W1), bwd_input->A.b, bwd_input->B.b,
                                         &meta(T_G1)->scale, &meta(T_W1)->scale, M, K, N, nI,
-                                        bwd_input->acc_bits, bwd_input->s, dX, nullptr),
-                              acc(HDQT_GEMM_BWD_INPUT), true, stream);
+                                        bwd_input->acc_bits, bwd_input->s, dX, nullptr,
+                                        1 + HDQT_GEMM_BWD_INPUT),
+                              acc(HDQT_GEMM_BWD_INPUT), L.acc_bytes[HDQT_GEMM_BWD_INPUT], stream);
         if (rc) return rc;
     } else {
         rc = run_quantize(G, M, N, 0, nW, &bwd_weight->B, bwd_weight->seed, meta(T_G0), codes(T_G0),
@@ -499,8 +512,9 @@ int hdqt_layer_step(const float* X, const float* W, const float* G, float* Z, fl
     }
     return run_planned_gemm(plan_gemm(codes(T_X0), codes(T_G0), bwd_weight->A.b, bwd_weight->B.b,
                                       &meta(T_X0)->scale, &meta(T_G0)->scale, K, N, M, nW,
-                                      bwd_weight->acc_bits, bwd_weight->s, dW, nullptr),
-                          acc(HDQT_GEMM_BWD_WEIGHT), true, stream);
+                                      bwd_weight->acc_bits, bwd_weight->s, dW, nullptr,
+                                      1 + HDQT_GEMM_BWD_WEIGHT),
+                          acc(HDQT_GEMM_BWD_WEIGHT), L.acc_bytes[HDQT_GEMM_BWD_WEIGHT], stream);
 }
 
 int hdqt_gemm_fwd(const float* X, const float* W, float* Z, int64_t M, int64_t K, int64_t N,

@@ -60,6 +60,7 @@ struct DualArgs {
     uint8_t* codes_col;     // [cols, rows/2]
     float* scale_row_out;   // may be null
     float* scale_col_out;
+    int profile_tag;        // which tensor of the step this is (timing table only): 0 none, 1 X, 2 W, 3 G
 };
 
 struct GemmArgs {
@@ -77,7 +78,9 @@ struct GemmArgs {
     const float* scaleB;
     float inv_n;            // 1 / n_eff (a power of two)
     float* out;             // [RA, RB] or null
-    int32_t* acc_out;       // [RA, RB] or null; with splits > 1 it is the atomic target
+    int32_t* acc_out;       // [RA, RB] or null
+    int32_t* partial;       // [splits, RA, RB] when splits > 1: one slice per part of the contraction
+    int profile_tag;        // which matmul of the step this is (timing table only): 0 none, 1 + kind
     int splits;             // workgroups sharing one output tile along the contraction
     int64_t tiles_per_split;
 };
@@ -87,14 +90,19 @@ hipError_t launch_quantize(const QuantArgs& q, hipStream_t stream);
 hipError_t launch_gemm(const GemmArgs& g, hipStream_t stream);
 // zero a[0, na) and b[0, nb) (b may be null) in one launch
 hipError_t launch_zero2(uint32_t* a, int64_t na, uint32_t* b, int64_t nb, hipStream_t stream);
-hipError_t launch_dequant(const int32_t* acc, int64_t count, const float* scaleA,
-                          const float* scaleB, float inv_n, float* out, hipStream_t stream);
+// sum the `splits` slices of `partial` ([splits, count]); the totals go to acc_out
+// (nullable) and, dequantized, to out (nullable)
+hipError_t launch_reduce(const int32_t* partial, int splits, int64_t count, const float* scaleA,
+                         const float* scaleB, float inv_n, float* out, int32_t* acc_out,
+                         hipStream_t stream);
 
 // Optional per-kernel timing (off by default).  When enabled through the C ABI,
 // every launch is bracketed by two HIP events on its stream.
 enum KernelId {
     K_FILL = 0, K_ROW_ABSMAX, K_ROW_QUANT, K_COL_ABSMAX, K_COL_QUANT, K_PLAIN_ABSMAX,
-    K_PLAIN_QUANT, K_GEMM_ALIGNED, K_GEMM_GENERIC, K_DEQUANT, K_GEMM_I4, K_DUAL_ABSMAX, K_DUAL_QUANT,
+    K_PLAIN_QUANT, K_GEMM_ALIGNED, K_GEMM_GENERIC, K_REDUCE, K_GEMM_I4, K_DUAL_ABSMAX, K_DUAL_QUANT,
+    K_GEMM_I4_FWD, K_GEMM_I4_BWD_INPUT, K_GEMM_I4_BWD_WEIGHT,
+    K_DUAL_ABSMAX_X, K_DUAL_ABSMAX_W, K_DUAL_ABSMAX_G, K_DUAL_QUANT_X, K_DUAL_QUANT_W, K_DUAL_QUANT_G,
     K_COUNT
 };
 bool quantize_fast_eligible(const QuantArgs& q);

@@ -181,7 +181,7 @@ __global__ __launch_bounds__(kThreads) void gemm_tiled_kernel(GemmArgs g)
                 if (i < g.RA && j < g.RB) {
                     const int v = total[a][c][r];
                     if (g.splits > 1) {
-                        atomicAdd(&g.acc_out[i * g.RB + j], v);
+                        g.partial[((int64_t)blockIdx.z * g.RA + i) * g.RB + j] = v;
                     } else {
                         if (g.acc_out) g.acc_out[i * g.RB + j] = v;
                         if (g.out) g.out[i * g.RB + j] = (float)v * dq;
@@ -191,27 +191,52 @@ __global__ __launch_bounds__(kThreads) void gemm_tiled_kernel(GemmArgs g)
         }
 }
 
-__global__ __launch_bounds__(256) void dequant_kernel(const int32_t* acc, int64_t count,
-                                                      const float* scaleA, const float* scaleB,
-                                                      float inv_n, float* out)
+// Totals of a split contraction: element e of the output is the sum of element e of
+// every slice.  VEC = 4: count is a multiple of 4, so every slice is 16-byte aligned.
+template <int VEC>
+__global__ __launch_bounds__(256) void reduce_kernel(const int32_t* partial, int splits, int64_t count,
+                                                     const float* scaleA, const float* scaleB,
+                                                     float inv_n, float* out, int32_t* acc_out)
 {
     const float dq = (scaleA[0] * scaleB[0]) * inv_n;
-    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < count;
-         i += (int64_t)gridDim.x * blockDim.x)
-        out[i] = (float)acc[i] * dq;
+    for (int64_t e = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) * VEC; e < count;
+         e += (int64_t)gridDim.x * blockDim.x * VEC) {
+        int t[4] = {0, 0, 0, 0};
+        const int32_t* src = partial + e;
+#pragma unroll 4
+        for (int z = 0; z < splits; ++z, src += count) {
+            if (VEC == 4) {
+                const int4 v = *reinterpret_cast<const int4*>(src);
+                t[0] += v.x; t[1] += v.y; t[2] += v.z; t[3] += v.w;
+            } else {
+                t[0] += src[0];
+            }
+        }
+#pragma unroll
+        for (int k = 0; k < VEC; ++k) {
+            if (acc_out) acc_out[e + k] = t[k];
+            if (out) out[e + k] = (float)t[k] * dq;
+        }
+    }
 }
 
 } // namespace
 
-hipError_t launch_dequant(const int32_t* acc, int64_t count, const float* scaleA,
-                          const float* scaleB, float inv_n, float* out, hipStream_t stream)
+hipError_t launch_reduce(const int32_t* partial, int splits, int64_t count, const float* scaleA,
+                         const float* scaleB, float inv_n, float* out, int32_t* acc_out,
+                         hipStream_t stream)
 {
-    int64_t blocks = (count + 255) / 256;
+    const bool vec = (count % 4 == 0);
+    int64_t blocks = ((vec ? count / 4 : count) + 255) / 256;
     if (blocks > 4096) blocks = 4096;
     if (blocks < 1) blocks = 1;
-    ProfileScope ps(K_DEQUANT, stream);
-    hipLaunchKernelGGL(dequant_kernel, dim3((unsigned)blocks), dim3(256), 0, stream, acc, count,
-                       scaleA, scaleB, inv_n, out);
+    ProfileScope ps(K_REDUCE, stream);
+    if (vec)
+        hipLaunchKernelGGL(reduce_kernel<4>, dim3((unsigned)blocks), dim3(256), 0, stream, partial, splits,
+                           count, scaleA, scaleB, inv_n, out, acc_out);
+    else
+        hipLaunchKernelGGL(reduce_kernel<1>, dim3((unsigned)blocks), dim3(256), 0, stream, partial, splits,
+                           count, scaleA, scaleB, inv_n, out, acc_out);
     return hipGetLastError();
 }
 

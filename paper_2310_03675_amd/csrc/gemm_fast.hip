@@ -19,8 +19,8 @@
 //     of a pair are two consecutive tiles of the same output element.
 //   * any other accumulator width or tile length: v_med3_i32 against bounds
 //     scaled by 256, add, and one exact shift at the end.
-//   * LDS holds int8, double-buffered; the next stage's global loads are in
-//     flight while the current stage is multiplied.
+//   * LDS holds int8, double-buffered, and the global loads run one stage
+//     ahead of the multiplication, across output-tile boundaries.
 
 #include "common.hpp"
 
@@ -76,6 +76,18 @@ __device__ __forceinline__ int clamp3(int v, int lo, int hi)
     return r;
 }
 
+// Work of a workgroup: the output tiles (blockIdx.y, ct), ct = blockIdx.z,
+// blockIdx.z + gridDim.z, ..., each over the part [k_begin, k_end) of the
+// contraction that blockIdx.x selects, as one stream of stages of KS codes.
+// The part index is the fastest-varying block coordinate: the workgroups that
+// share an output tile run together and between them read whole rows of the
+// operands, which keeps the DRAM pages they touch open.
+// The stream is software-pipelined across tile boundaries: the global loads run
+// one stage ahead of the multiplication, LDS holds two stages, and a tile's
+// output stores are issued while the next tile's first stage is already in
+// flight.  With gridDim.z = 1 a workgroup walks along a
+// whole row strip of the output, which is how short contractions (one or two
+// stages per tile) keep loads, MFMAs and stores overlapped.
 template <int EPI>
 __global__ __launch_bounds__(kThreads, 2) void gemm_i4_kernel(GemmArgs g)
 {
@@ -86,14 +98,15 @@ __global__ __launch_bounds__(kThreads, 2) void gemm_i4_kernel(GemmArgs g)
     const int lane = tid & 63, wave = tid >> 6;
     const int wm = wave >> 1, wn = wave & 1;
     const int64_t row0 = (int64_t)blockIdx.y * BM;
-    const int64_t col0 = (int64_t)blockIdx.x * BN;
+    const int n_ct = (int)((g.RB + BN - 1) / BN);
 
-    const int64_t t_begin = (int64_t)blockIdx.z * g.tiles_per_split;
+    const int64_t t_begin = (int64_t)blockIdx.x * g.tiles_per_split;
     int64_t t_end = t_begin + g.tiles_per_split;
     if (t_end > g.n_tiles) t_end = g.n_tiles;
     const int64_t k_begin = t_begin * g.s;
     int64_t k_end = t_end * g.s;
     if (k_end > g.D) k_end = g.D;
+    if (k_begin >= k_end) return;         // not reached: every part has at least one tile
     const int steps_per_tile = (int)(g.s / KSTEP);
     const int lo = g.acc_lo_scaled, hi = g.acc_hi_scaled;
 
@@ -109,36 +122,48 @@ __global__ __launch_bounds__(kThreads, 2) void gemm_i4_kernel(GemmArgs g)
 #pragma unroll
             for (int r = 0; r < 16; ++r) { total[a][c][r] = 0; part[a][c][r] = 0; }
     const v16i zero = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
+    const float dq = (g.scaleA[0] * g.scaleB[0]) * g.inv_n;
 
-    Staged st;
-    auto fetch = [&](int64_t k0) {
+    // ---- the load stream: position of the next stage to fetch
+    int f_ct = blockIdx.z;
+    int64_t f_k = k_begin;
+    auto fetch_next = [&](Staged& st) {
+        if (f_ct >= n_ct) return;
+        const int64_t col0 = (int64_t)f_ct * BN;
 #pragma unroll
         for (int i = 0; i < 2; ++i) {
             const int r = lrow + 64 * i;
-            st.a[i] = load_unit(g.qA, g.pitchA, g.RA, row0 + r, k0 + lks * KSTEP, k_end);
-            st.b[i] = load_unit(g.qB, g.pitchB, g.RB, col0 + r, k0 + lks * KSTEP, k_end);
+            st.a[i] = load_unit(g.qA, g.pitchA, g.RA, row0 + r, f_k + lks * KSTEP, k_end);
+            st.b[i] = load_unit(g.qB, g.pitchB, g.RB, col0 + r, f_k + lks * KSTEP, k_end);
         }
+        f_k += KS;
+        if (f_k >= k_end) { f_k = k_begin; f_ct += gridDim.z; }
     };
-    auto stash = [&](int buf) {
+    auto frag = [&](const uint8_t(*lds)[LDP], int base_row, int ks) -> v4i {
+        return *reinterpret_cast<const v4i*>(&lds[base_row + (lane & 31)][ks * KSTEP + (lane >> 5) * 16]);
+    };
+
+    // ---- the multiply stream
+    const int lane_row = wm * 64 + 4 * (lane >> 5), lane_col = wn * 64 + (lane & 31);
+    const uint32_t lane_off = (uint32_t)lane_row * (uint32_t)g.RB + (uint32_t)lane_col;
+    int c_ct = blockIdx.z;
+    int64_t c_k = k_begin;
+    int step_in_tile = 0;
+
+    // One stage: registers -> LDS buffer `buf`, barrier, refill the registers with
+    // the next stage, multiply; at the end of a tile, write it out.
+    // Whole stages only: positions at or beyond k_end are zero in LDS and add nothing.
+    // One barrier per stage is enough: buffer `buf` was last read two stages ago,
+    // and every wave has passed the previous stage's barrier since.
+    auto stage = [&](Staged& st, const int buf) {
 #pragma unroll
         for (int i = 0; i < 2; ++i) {
             const int r = lrow + 64 * i;
             store_unit(&As[buf][r][lks * KSTEP], st.a[i]);
             store_unit(&Bs[buf][r][lks * KSTEP], st.b[i]);
         }
-    };
-    auto frag = [&](const uint8_t(*lds)[LDP], int base_row, int ks) -> v4i {
-        return *reinterpret_cast<const v4i*>(&lds[base_row + (lane & 31)][ks * KSTEP + (lane >> 5) * 16]);
-    };
-
-    int step_in_tile = 0;
-    int buf = 0;
-    if (k_begin < k_end) fetch(k_begin);
-    // Whole stages only: positions at or beyond k_end are zero in LDS and add nothing.
-    for (int64_t k0 = k_begin; k0 < k_end; k0 += KS, buf ^= 1) {
-        stash(buf);
         __syncthreads();
-        if (k0 + KS < k_end) fetch(k0 + KS);
+        fetch_next(st);
 
         if (EPI == EPI_SAT8_S32 || EPI == EPI_SAT8_S64) {
             // two tiles per half stage (s = 32) or per stage (s = 64)
@@ -197,39 +222,57 @@ __global__ __launch_bounds__(kThreads, 2) void gemm_i4_kernel(GemmArgs g)
                 }
             }
         }
-    }
-    if (EPI == EPI_GENERIC) {
-        // a short last tile (D not a multiple of s) ends without reaching steps_per_tile
-        if (step_in_tile != 0) {
+
+        c_k += KS;
+        if (c_k < k_end) return;
+
+        // ---- end of the output tile (row0, c_ct)
+        if (EPI == EPI_GENERIC && step_in_tile != 0) {
+            // a short last tile (D not a multiple of s) ends without reaching steps_per_tile
+            step_in_tile = 0;
 #pragma unroll
             for (int a = 0; a < 2; ++a)
 #pragma unroll
                 for (int c = 0; c < 2; ++c)
 #pragma unroll
-                    for (int r = 0; r < 16; ++r) total[a][c][r] += clamp3(part[a][c][r], lo, hi);
+                    for (int r = 0; r < 16; ++r) {
+                        total[a][c][r] += clamp3(part[a][c][r], lo, hi);
+                        part[a][c][r] = 0;
+                    }
         }
-    }
-
-    const float dq = (g.scaleA[0] * g.scaleB[0]) * g.inv_n;
+        // Element (a, c, r) of the lane lies at tile_off + (32a + 8(r/4) + r%4) RB + 32c
+        // (uniform) + lane_off (per lane, 32 bits: RB <= 2^21 on this path).
+        const int64_t col0 = (int64_t)c_ct * BN;
+        const int64_t tile_off = row0 * g.RB + col0;
+        const bool interior = (row0 + BM <= g.RA) && (col0 + BN <= g.RB);
+        float* ob = (g.splits == 1 && g.out) ? g.out + tile_off : nullptr;
+        int32_t* ab = g.splits > 1 ? g.partial + (int64_t)blockIdx.x * g.RA * g.RB + tile_off
+                                   : (g.acc_out ? g.acc_out + tile_off : nullptr);
 #pragma unroll
-    for (int a = 0; a < 2; ++a)
+        for (int a = 0; a < 2; ++a)
 #pragma unroll
-        for (int c = 0; c < 2; ++c) {
-            const int64_t j = col0 + wn * 64 + c * 32 + (lane & 31);
+            for (int c = 0; c < 2; ++c)
 #pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                const int64_t i = row0 + wm * 64 + a * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
-                if (i < g.RA && j < g.RB) {
+                for (int r = 0; r < 16; ++r) {
+                    const int rr = a * 32 + 8 * (r >> 2) + (r & 3);
+                    const int64_t uo = (int64_t)rr * g.RB + c * 32;
                     const int v = (EPI == EPI_GENERIC) ? (total[a][c][r] >> kScaleShift) : total[a][c][r];
-                    if (g.splits > 1) {
-                        atomicAdd(&g.acc_out[i * g.RB + j], v);
-                    } else {
-                        if (g.acc_out) g.acc_out[i * g.RB + j] = v;
-                        if (g.out) g.out[i * g.RB + j] = (float)v * dq;
+                    total[a][c][r] = 0;
+                    bool ok = interior;
+                    if (!interior)
+                        ok = (row0 + lane_row + rr < g.RA) && (col0 + lane_col + c * 32 < g.RB);
+                    if (ok) {
+                        if (ab) (ab + uo)[lane_off] = v;
+                        if (ob) (ob + uo)[lane_off] = (float)v * dq;
                     }
                 }
-            }
-        }
+        c_k = k_begin;
+        c_ct += gridDim.z;
+    };
+
+    Staged st;
+    fetch_next(st);
+    for (int buf = 0; c_ct < n_ct; buf ^= 1) stage(st, buf);
 }
 
 bool sat8_path(const GemmArgs& g) { return g.acc_hi == 127 && (g.s == 32 || g.s == 64); }
@@ -240,6 +283,7 @@ bool gemm_fast_eligible(const GemmArgs& g)
 {
     if (g.bA > 4 || g.bB > 4) return false;
     if (g.s % KSTEP != 0 || g.D % KSTEP != 0) return false;
+    if (g.RB > ((int64_t)1 << 21)) return false;     // 32-bit offsets inside an output tile
     if (sat8_path(g)) return true;      // unscaled int32 total: covered by the API's range check
     // generic epilogue: totals carry a factor 256 and must stay inside int32
     const int64_t tile_max = g.s * 64;                            // |code| <= 8 on both sides
@@ -255,9 +299,18 @@ hipError_t launch_gemm_fast(const GemmArgs& g_in, hipStream_t stream)
     const int64_t lo = (int64_t)g.acc_lo * 256, hi = (int64_t)g.acc_hi * 256;
     g.acc_lo_scaled = lo < INT32_MIN ? INT32_MIN : (int)lo;
     g.acc_hi_scaled = hi > INT32_MAX ? INT32_MAX : (int)hi;
-    const dim3 grid((unsigned)((g.RB + BN - 1) / BN), (unsigned)((g.RA + BM - 1) / BM),
-                    (unsigned)g.splits);
-    ProfileScope ps(K_GEMM_I4, stream);
+    // Short contractions (at most two stages per output tile): a workgroup walks along
+    // its row strip of the output as long as that leaves about two workgroups per CU.
+    const int64_t n_ct = (g.RB + BN - 1) / BN, n_rt = (g.RA + BM - 1) / BM;
+    const int64_t stages = (g.tiles_per_split * g.s + KS - 1) / KS;
+    int64_t gx = n_ct;
+    if (stages <= 2) {
+        gx = (512 + n_rt * g.splits - 1) / (n_rt * g.splits);
+        if (gx > n_ct) gx = n_ct;
+        if (gx < 1) gx = 1;
+    }
+    const dim3 grid((unsigned)g.splits, (unsigned)n_rt, (unsigned)gx);
+    ProfileScope ps(g.profile_tag ? K_GEMM_I4_FWD + (g.profile_tag - 1) : K_GEMM_I4, stream);
     if (sat8_path(g) && g.s == 32)
         hipLaunchKernelGGL(gemm_i4_kernel<EPI_SAT8_S32>, grid, dim3(kThreads), 0, stream, g);
     else if (sat8_path(g))

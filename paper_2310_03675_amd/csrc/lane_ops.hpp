@@ -36,6 +36,78 @@ __device__ __forceinline__ float stage_dpp(float own, uint32_t flip)
     return lane_xor<M>(own) + as_f(as_u(own) ^ flip);
 }
 
+// The same stage in one multiply-add: own + c * other with c = +1 in the lane that
+// holds the lower half and -1 in the other (multiplying by +-1 is exact, so the
+// rounding is that of the plain sum).  The lower lane gets lower + upper as
+// before; the upper lane gets upper - lower, the NEGATED butterfly output.  A
+// caller therefore tracks one sign per lane: with values stored as sigma * true,
+// pairs whose two lanes carry the same sigma use c = +-1 as described, and sigma
+// flips in the upper lane.  Signs do not matter to max|.|, and a quantizer
+// multiplies by sigma * (1 / step) instead of 1 / step.
+// Written as v_fmac_f32 with a DPP source, eight values per statement: the
+// compiler keeps the lane move and the multiply-add apart (two instructions per
+// value), the hardware does both in one.  A DPP source may not be read within
+// two wait states of the VALU instruction that wrote it; inside a statement the
+// eight values are independent, and the s_nop at either end covers the
+// instructions around it.
+#define HDQT_FMA8(CTRL)                                                                           \
+    asm("s_nop 1\n\t"                                                                             \
+        "v_fmac_f32_dpp %0, %0, %8 " CTRL " row_mask:0xf bank_mask:0xf\n\t"                       \
+        "v_fmac_f32_dpp %1, %1, %8 " CTRL " row_mask:0xf bank_mask:0xf\n\t"                       \
+        "v_fmac_f32_dpp %2, %2, %8 " CTRL " row_mask:0xf bank_mask:0xf\n\t"                       \
+        "v_fmac_f32_dpp %3, %3, %8 " CTRL " row_mask:0xf bank_mask:0xf\n\t"                       \
+        "v_fmac_f32_dpp %4, %4, %8 " CTRL " row_mask:0xf bank_mask:0xf\n\t"                       \
+        "v_fmac_f32_dpp %5, %5, %8 " CTRL " row_mask:0xf bank_mask:0xf\n\t"                       \
+        "v_fmac_f32_dpp %6, %6, %8 " CTRL " row_mask:0xf bank_mask:0xf\n\t"                       \
+        "v_fmac_f32_dpp %7, %7, %8 " CTRL " row_mask:0xf bank_mask:0xf\n\t"                       \
+        "s_nop 1"                                                                                 \
+        : "+v"(w[0]), "+v"(w[1]), "+v"(w[2]), "+v"(w[3]), "+v"(w[4]), "+v"(w[5]), "+v"(w[6]),     \
+          "+v"(w[7])                                                                              \
+        : "v"(c))
+
+// w[k] <- w[k] + c * (w[k] of lane ^ M), k < 8, M in {1, 2, 4, 8}
+template <int M>
+__device__ __forceinline__ void stage_fma8(float w[8], float c)
+{
+    if (M == 1) {
+        HDQT_FMA8("quad_perm:[1,0,3,2]");
+    } else if (M == 2) {
+        HDQT_FMA8("quad_perm:[2,3,0,1]");
+    } else if (M == 8) {
+        HDQT_FMA8("row_ror:8");
+    } else {
+        // lane ^ 4 = half-row mirror, then quad reverse: eight moves, then eight multiply-adds
+        float t[8];
+        asm("s_nop 1\n\t"
+            "v_mov_b32_dpp %0, %8 row_half_mirror row_mask:0xf bank_mask:0xf\n\t"
+            "v_mov_b32_dpp %1, %9 row_half_mirror row_mask:0xf bank_mask:0xf\n\t"
+            "v_mov_b32_dpp %2, %10 row_half_mirror row_mask:0xf bank_mask:0xf\n\t"
+            "v_mov_b32_dpp %3, %11 row_half_mirror row_mask:0xf bank_mask:0xf\n\t"
+            "v_mov_b32_dpp %4, %12 row_half_mirror row_mask:0xf bank_mask:0xf\n\t"
+            "v_mov_b32_dpp %5, %13 row_half_mirror row_mask:0xf bank_mask:0xf\n\t"
+            "v_mov_b32_dpp %6, %14 row_half_mirror row_mask:0xf bank_mask:0xf\n\t"
+            "v_mov_b32_dpp %7, %15 row_half_mirror row_mask:0xf bank_mask:0xf\n\t"
+            "s_nop 1"
+            : "=&v"(t[0]), "=&v"(t[1]), "=&v"(t[2]), "=&v"(t[3]), "=&v"(t[4]), "=&v"(t[5]), "=&v"(t[6]),
+              "=&v"(t[7])
+            : "v"(w[0]), "v"(w[1]), "v"(w[2]), "v"(w[3]), "v"(w[4]), "v"(w[5]), "v"(w[6]), "v"(w[7]));
+        asm("s_nop 1\n\t"
+            "v_fmac_f32_dpp %0, %8, %16 quad_perm:[3,2,1,0] row_mask:0xf bank_mask:0xf\n\t"
+            "v_fmac_f32_dpp %1, %9, %16 quad_perm:[3,2,1,0] row_mask:0xf bank_mask:0xf\n\t"
+            "v_fmac_f32_dpp %2, %10, %16 quad_perm:[3,2,1,0] row_mask:0xf bank_mask:0xf\n\t"
+            "v_fmac_f32_dpp %3, %11, %16 quad_perm:[3,2,1,0] row_mask:0xf bank_mask:0xf\n\t"
+            "v_fmac_f32_dpp %4, %12, %16 quad_perm:[3,2,1,0] row_mask:0xf bank_mask:0xf\n\t"
+            "v_fmac_f32_dpp %5, %13, %16 quad_perm:[3,2,1,0] row_mask:0xf bank_mask:0xf\n\t"
+            "v_fmac_f32_dpp %6, %14, %16 quad_perm:[3,2,1,0] row_mask:0xf bank_mask:0xf\n\t"
+            "v_fmac_f32_dpp %7, %15, %16 quad_perm:[3,2,1,0] row_mask:0xf bank_mask:0xf\n\t"
+            "s_nop 1"
+            : "+v"(w[0]), "+v"(w[1]), "+v"(w[2]), "+v"(w[3]), "+v"(w[4]), "+v"(w[5]), "+v"(w[6]),
+              "+v"(w[7])
+            : "v"(t[0]), "v"(t[1]), "v"(t[2]), "v"(t[3]), "v"(t[4]), "v"(t[5]), "v"(t[6]), "v"(t[7]),
+              "v"(c));
+    }
+}
+
 // Butterfly stage pairing lane and lane ^ 16 (W32 = false) or lane ^ 32 (true),
 // on two values at once.  The swap brings, into one lane, the two halves of a
 // pair (of `a` in the lower lanes, of `b` in the upper lanes); sum and

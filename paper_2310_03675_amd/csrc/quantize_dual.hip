@@ -18,6 +18,10 @@
 //     strides 4, 8, 16 pair lanes (lane xor 1, 2, 4), stride 32 pairs registers (h);
 //   along the rows of a column (axis 0): strides 1, 2, 4 pair registers (i),
 //     strides 8, 16, 32 pair lanes (lane xor 8, 16, 32).
+// The stages that pair lanes through DPP are single multiply-adds that leave the
+// upper lane's result negated (see stage_fma8); the sign a lane has accumulated,
+// (-1)^popcount(lane & 7) after axis 1 and (-1)^(lane bit 3) after axis 0, is
+// folded into the reciprocal step the lane quantizes with.
 // The axis-1 transform is done row by row on copies (eight values at a time),
 // the axis-0 transform then in place.  No LDS is involved.
 // Requires rows and cols multiples of 64, block orders up to 64 and codes of at
@@ -42,8 +46,8 @@ struct Tile {
 struct DualCtx {
     const DualArgs* q;
     int cg, rg;
-    uint32_t flip1, flip2, flip4, flip8;
-    float inv_row, inv_col;
+    float c1, c2, c4, c8;          // -1 where the lane bit is set, else +1
+    float inv_row, inv_col;        // reciprocal steps, times the lane's accumulated sign
     float qmin_row, qmax_row, qmin_col, qmax_col;
 };
 
@@ -105,16 +109,25 @@ __device__ __forceinline__ void row_line(const Tile& t, int i, const DualCtx& x,
             }
     }
     if (log2n >= 3) {
-#pragma unroll
-        for (int k = 0; k < 8; ++k) w[k] = stage_dpp<1>(w[k], x.flip1);
+        stage_fma8<1>(w, x.c1);
     }
     if (log2n >= 4) {
-#pragma unroll
-        for (int k = 0; k < 8; ++k) w[k] = stage_dpp<2>(w[k], x.flip2);
+        stage_fma8<2>(w, x.c2);
     }
     if (log2n >= 5) {
+        stage_fma8<4>(w, x.c4);
+    }
+    if (!QUANT) {
+        // max(|a + c|, |a - c|) = |a| + |c|, also after rounding: the last stage of
+        // pass 1 needs no differences
+        if (log2n >= 6) {
 #pragma unroll
-        for (int k = 0; k < 8; ++k) w[k] = stage_dpp<4>(w[k], x.flip4);
+            for (int k = 0; k < 4; ++k) amax = fmaxf(amax, fabsf(w[k]) + fabsf(w[k + 4]));
+        } else {
+#pragma unroll
+            for (int k = 0; k < 8; ++k) amax = fmaxf(amax, fabsf(w[k]));
+        }
+        return;
     }
     if (log2n >= 6) {
 #pragma unroll
@@ -123,11 +136,6 @@ __device__ __forceinline__ void row_line(const Tile& t, int i, const DualCtx& x,
             w[k] = a + c;
             w[k + 4] = a - c;
         }
-    }
-    if (!QUANT) {
-#pragma unroll
-        for (int k = 0; k < 8; ++k) amax = fmaxf(amax, fabsf(w[k]));
-        return;
     }
     const int64_t row = row0 + x.rg * 8 + i;
     const float magic = kMagic + 8.0f;
@@ -158,28 +166,37 @@ __device__ __forceinline__ void row_line(const Tile& t, int i, const DualCtx& x,
     *reinterpret_cast<uint32_t*>(q.codes_row + row * (q.cols >> 1) + (col0 >> 1) + byte_off) = word;
 }
 
-// Axis 0 on the whole tile, in place.
-__device__ __forceinline__ void col_transform(Tile& t, int log2n, uint32_t flip8)
+// Axis 0 on the whole tile, in place.  The two lanes of a swap stage carry the
+// same sign (it depends on lane bit 3 only), so those stages need no care.
+// MAX_ONLY (pass 1, block order 64): the last stage is replaced by |lo| + |hi| of
+// the swapped-in pairs, returned as a running maximum; the tile is then spent.
+template <bool MAX_ONLY>
+__device__ __forceinline__ float col_transform(Tile& t, int log2n, float c8)
 {
+    float m = 0.0f;
 #pragma unroll
     for (int h = 0; h < 2; ++h)
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
             float* v = t.v[h][j];
             butterfly8(v, log2n);
-            if (log2n > 3) {
-#pragma unroll
-                for (int i = 0; i < 8; ++i) v[i] = stage_dpp<8>(v[i], flip8);
-            }
+            if (log2n > 3) stage_fma8<8>(v, c8);
             if (log2n > 4) {
 #pragma unroll
                 for (int i = 0; i < 8; i += 2) stage_swap<false>(v[i], v[i + 1]);
             }
-            if (log2n > 5) {
+            if (MAX_ONLY) {
+#pragma unroll
+                for (int i = 0; i < 8; i += 2) {
+                    const v2u r = __builtin_amdgcn_permlane32_swap(as_u(v[i]), as_u(v[i + 1]), false, false);
+                    m = fmaxf(m, fabsf(as_f(r[0])) + fabsf(as_f(r[1])));
+                }
+            } else if (log2n > 5) {
 #pragma unroll
                 for (int i = 0; i < 8; i += 2) stage_swap<true>(v[i], v[i + 1]);
             }
         }
+    return m;
 }
 
 template <bool STOCH>
@@ -260,10 +277,10 @@ __global__ __launch_bounds__(kThreads) void fwht_dual_kernel(DualArgs q, int WC)
     x.q = &q;
     x.cg = lane & 7;
     x.rg = lane >> 3;
-    x.flip1 = (uint32_t)(lane & 1) << 31;
-    x.flip2 = (uint32_t)(lane & 2) << 30;
-    x.flip4 = (uint32_t)(lane & 4) << 29;
-    x.flip8 = (uint32_t)(lane & 8) << 28;
+    x.c1 = (lane & 1) ? -1.0f : 1.0f;
+    x.c2 = (lane & 2) ? -1.0f : 1.0f;
+    x.c4 = (lane & 4) ? -1.0f : 1.0f;
+    x.c8 = (lane & 8) ? -1.0f : 1.0f;
     x.inv_row = x.inv_col = 0.0f;
     x.qmin_row = (float)(-(1 << (q.b_row - 1)));
     x.qmax_row = (float)((1 << (q.b_row - 1)) - 1);
@@ -275,8 +292,13 @@ __global__ __launch_bounds__(kThreads) void fwht_dual_kernel(DualArgs q, int WC)
     if (QUANT) {
         const Scaling s_row = load_scaling(q.meta_row, q.clip_row, q.b_row);
         const Scaling s_col = load_scaling(q.meta_col, q.clip_col, q.b_col);
-        x.inv_row = s_row.inv;
-        x.inv_col = s_col.inv;
+        // signs accumulated by the stage_fma stages that actually run
+        float sg_row = 1.0f;
+        if (q.log2n_row >= 3) sg_row *= x.c1;
+        if (q.log2n_row >= 4) sg_row *= x.c2;
+        if (q.log2n_row >= 5) sg_row *= x.c4;
+        x.inv_row = s_row.inv * sg_row;
+        x.inv_col = q.log2n_col > 3 ? s_col.inv * x.c8 : s_col.inv;
         if (blockIdx.x == 0 && blockIdx.y == 0 && threadIdx.x == 0) {
             q.meta_row->scale = s_row.scale;
             q.meta_col->scale = s_col.scale;
@@ -288,16 +310,20 @@ __global__ __launch_bounds__(kThreads) void fwht_dual_kernel(DualArgs q, int WC)
     if (live) {
 #pragma unroll
         for (int i = 0; i < 8; ++i) row_line<QUANT, ST_ROW>(t, i, x, row0, col0, amax_row);
-        col_transform(t, q.log2n_col, x.flip8);
-        if (!QUANT) {
-#pragma unroll
-            for (int h = 0; h < 2; ++h)
-#pragma unroll
-                for (int j = 0; j < 4; ++j)
-#pragma unroll
-                    for (int i = 0; i < 8; ++i) amax_col = fmaxf(amax_col, fabsf(t.v[h][j][i]));
+        if (!QUANT && q.log2n_col > 5) {
+            amax_col = col_transform<true>(t, q.log2n_col, x.c8);
         } else {
-            col_codes<ST_COL>(t, x, row0, col0);
+            col_transform<false>(t, q.log2n_col, x.c8);
+            if (!QUANT) {
+#pragma unroll
+                for (int h = 0; h < 2; ++h)
+#pragma unroll
+                    for (int j = 0; j < 4; ++j)
+#pragma unroll
+                        for (int i = 0; i < 8; ++i) amax_col = fmaxf(amax_col, fabsf(t.v[h][j][i]));
+            } else {
+                col_codes<ST_COL>(t, x, row0, col0);
+            }
         }
     }
     if (!QUANT) block_atomic_max2(amax_row, amax_col, q.meta_row, q.meta_col, red);
@@ -320,10 +346,10 @@ hipError_t launch_quantize_dual(const DualArgs& q, hipStream_t stream)
     const int64_t tall = (int64_t)kTile * WR;
     const dim3 grid((unsigned)(strips / WC), (unsigned)((q.rows + tall - 1) / tall));
     {
-        ProfileScope ps(K_DUAL_ABSMAX, stream);
+        ProfileScope ps(q.profile_tag ? K_DUAL_ABSMAX_X + (q.profile_tag - 1) : K_DUAL_ABSMAX, stream);
         hipLaunchKernelGGL((fwht_dual_kernel<false, false, false>), grid, dim3(kThreads), 0, stream, q, WC);
     }
-    ProfileScope ps(K_DUAL_QUANT, stream);
+    ProfileScope ps(q.profile_tag ? K_DUAL_QUANT_X + (q.profile_tag - 1) : K_DUAL_QUANT, stream);
     if (q.st_row && q.st_col)
         hipLaunchKernelGGL((fwht_dual_kernel<true, true, true>), grid, dim3(kThreads), 0, stream, q, WC);
     else if (q.st_row)
