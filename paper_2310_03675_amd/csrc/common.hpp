@@ -80,6 +80,7 @@ struct GemmArgs {
     float* out;             // [RA, RB] or null
     int32_t* acc_out;       // [RA, RB] or null
     int32_t* partial;       // [splits, RA, RB] when splits > 1: one slice per part of the contraction
+    int stream_out;         // fp32 output too large to stay cached: written with streaming stores
     int profile_tag;        // which matmul of the step this is (timing table only): 0 none, 1 + kind
     int splits;             // workgroups sharing one output tile along the contraction
     int64_t tiles_per_split;

@@ -34,16 +34,17 @@ typedef short v2s __attribute__((ext_vector_type(2)));
 
 constexpr int kThreads = 256;
 constexpr int BM = 128, BN = 128;
-constexpr int KS = 128;               // codes per LDS stage (4 MFMA steps)
+constexpr int KS_LONG = 128;          // codes per LDS stage: 4 MFMA steps.  (Stages of 64 codes leave
+                                      // room for three workgroups per CU instead of two; measured
+                                      // slower on all three layer shapes.)
 constexpr int KSTEP = 32;             // codes per MFMA
-constexpr int NSTEP = KS / KSTEP;
-constexpr int LDP = KS + 16;          // LDS row pitch in bytes (int8 codes)
 constexpr int kScaleShift = 8;        // both operands carry a factor 16
 
 enum Epilogue { EPI_GENERIC = 0, EPI_SAT8_S32 = 1, EPI_SAT8_S64 = 2 };
 
+template <int UNITS>
 struct Staged {
-    uint4 a[2], b[2];                 // two (row, k-step) units per operand per thread
+    uint4 a[UNITS], b[UNITS];         // (row, k-step) units per operand per thread
 };
 
 __device__ __forceinline__ uint4 load_unit(const uint8_t* q, int64_t pitch, int64_t R, int64_t row,
@@ -88,9 +89,13 @@ __device__ __forceinline__ int clamp3(int v, int lo, int hi)
 // flight.  With gridDim.z = 1 a workgroup walks along a
 // whole row strip of the output, which is how short contractions (one or two
 // stages per tile) keep loads, MFMAs and stores overlapped.
-template <int EPI>
+template <int EPI, int KS, bool STREAM>
 __global__ __launch_bounds__(kThreads, 2) void gemm_i4_kernel(GemmArgs g)
 {
+    constexpr int NSTEP = KS / KSTEP;
+    constexpr int LDP = KS + 16;          // LDS row pitch in bytes (int8 codes)
+    constexpr int UNITS = NSTEP / 2;      // 16-byte units per operand and thread: 128 rows * NSTEP / 256
+    static_assert(EPI != EPI_SAT8_S64 || KS == KS_LONG, "a pair of 64-code tiles is one long stage");
     __shared__ __attribute__((aligned(16))) uint8_t As[2][BM][LDP];
     __shared__ __attribute__((aligned(16))) uint8_t Bs[2][BN][LDP];
 
@@ -110,8 +115,9 @@ __global__ __launch_bounds__(kThreads, 2) void gemm_i4_kernel(GemmArgs g)
     const int steps_per_tile = (int)(g.s / KSTEP);
     const int lo = g.acc_lo_scaled, hi = g.acc_hi_scaled;
 
-    // loader mapping: unit u = tid + 256*i -> row u/4, k-step u%4
-    const int lrow = tid >> 2, lks = tid & 3;
+    // loader mapping: unit u = tid + 256*i -> row u / NSTEP, k-step u % NSTEP
+    const int lrow = tid / NSTEP, lks = tid % NSTEP;
+    constexpr int ROWS_PER_PASS = kThreads / NSTEP;
 
     v16i total[2][2];
     v16i part[2][2];                  // EPI_GENERIC only
@@ -127,12 +133,12 @@ __global__ __launch_bounds__(kThreads, 2) void gemm_i4_kernel(GemmArgs g)
     // ---- the load stream: position of the next stage to fetch
     int f_ct = blockIdx.z;
     int64_t f_k = k_begin;
-    auto fetch_next = [&](Staged& st) {
+    auto fetch_next = [&](Staged<UNITS>& st) {
         if (f_ct >= n_ct) return;
         const int64_t col0 = (int64_t)f_ct * BN;
 #pragma unroll
-        for (int i = 0; i < 2; ++i) {
-            const int r = lrow + 64 * i;
+        for (int i = 0; i < UNITS; ++i) {
+            const int r = lrow + ROWS_PER_PASS * i;
             st.a[i] = load_unit(g.qA, g.pitchA, g.RA, row0 + r, f_k + lks * KSTEP, k_end);
             st.b[i] = load_unit(g.qB, g.pitchB, g.RB, col0 + r, f_k + lks * KSTEP, k_end);
         }
@@ -155,10 +161,10 @@ __global__ __launch_bounds__(kThreads, 2) void gemm_i4_kernel(GemmArgs g)
     // Whole stages only: positions at or beyond k_end are zero in LDS and add nothing.
     // One barrier per stage is enough: buffer `buf` was last read two stages ago,
     // and every wave has passed the previous stage's barrier since.
-    auto stage = [&](Staged& st, const int buf) {
+    auto stage = [&](Staged<UNITS>& st, const int buf) {
 #pragma unroll
-        for (int i = 0; i < 2; ++i) {
-            const int r = lrow + 64 * i;
+        for (int i = 0; i < UNITS; ++i) {
+            const int r = lrow + ROWS_PER_PASS * i;
             store_unit(&As[buf][r][lks * KSTEP], st.a[i]);
             store_unit(&Bs[buf][r][lks * KSTEP], st.b[i]);
         }
@@ -168,7 +174,7 @@ __global__ __launch_bounds__(kThreads, 2) void gemm_i4_kernel(GemmArgs g)
         if (EPI == EPI_SAT8_S32 || EPI == EPI_SAT8_S64) {
             // two tiles per half stage (s = 32) or per stage (s = 64)
 #pragma unroll
-            for (int pr = 0; pr < (EPI == EPI_SAT8_S32 ? 2 : 1); ++pr) {
+            for (int pr = 0; pr < (EPI == EPI_SAT8_S32 ? NSTEP / 2 : 1); ++pr) {
                 constexpr int SPT = (EPI == EPI_SAT8_S32) ? 1 : 2;      // steps per tile
                 v4i fa[2 * SPT][2], fb[2 * SPT][2];
 #pragma unroll
@@ -263,14 +269,19 @@ __global__ __launch_bounds__(kThreads, 2) void gemm_i4_kernel(GemmArgs g)
                         ok = (row0 + lane_row + rr < g.RA) && (col0 + lane_col + c * 32 < g.RB);
                     if (ok) {
                         if (ab) (ab + uo)[lane_off] = v;
-                        if (ob) (ob + uo)[lane_off] = (float)v * dq;
+                        if (ob) {
+                            // (a template flag, not a run-time branch: merging the two stores
+                            // would drop the streaming hint)
+                            if (STREAM) __builtin_nontemporal_store((float)v * dq, &(ob + uo)[lane_off]);
+                            else (ob + uo)[lane_off] = (float)v * dq;
+                        }
                     }
                 }
         c_k = k_begin;
         c_ct += gridDim.z;
     };
 
-    Staged st;
+    Staged<UNITS> st;
     fetch_next(st);
     for (int buf = 0; c_ct < n_ct; buf ^= 1) stage(st, buf);
 }
@@ -302,6 +313,8 @@ hipError_t launch_gemm_fast(const GemmArgs& g_in, hipStream_t stream)
     // Short contractions (at most two stages per output tile): a workgroup walks along
     // its row strip of the output as long as that leaves about two workgroups per CU.
     const int64_t n_ct = (g.RB + BN - 1) / BN, n_rt = (g.RA + BM - 1) / BM;
+    const bool s32 = sat8_path(g) && g.s == 32;
+    const int64_t KS = KS_LONG;
     const int64_t stages = (g.tiles_per_split * g.s + KS - 1) / KS;
     int64_t gx = n_ct;
     if (stages <= 2) {
@@ -311,12 +324,17 @@ hipError_t launch_gemm_fast(const GemmArgs& g_in, hipStream_t stream)
     }
     const dim3 grid((unsigned)g.splits, (unsigned)n_rt, (unsigned)gx);
     ProfileScope ps(g.profile_tag ? K_GEMM_I4_FWD + (g.profile_tag - 1) : K_GEMM_I4, stream);
-    if (sat8_path(g) && g.s == 32)
-        hipLaunchKernelGGL(gemm_i4_kernel<EPI_SAT8_S32>, grid, dim3(kThreads), 0, stream, g);
-    else if (sat8_path(g))
-        hipLaunchKernelGGL(gemm_i4_kernel<EPI_SAT8_S64>, grid, dim3(kThreads), 0, stream, g);
-    else
-        hipLaunchKernelGGL(gemm_i4_kernel<EPI_GENERIC>, grid, dim3(kThreads), 0, stream, g);
+    const dim3 block(kThreads);
+    if (s32) {
+        if (g.stream_out) hipLaunchKernelGGL((gemm_i4_kernel<EPI_SAT8_S32, KS_LONG, true>), grid, block, 0, stream, g);
+        else hipLaunchKernelGGL((gemm_i4_kernel<EPI_SAT8_S32, KS_LONG, false>), grid, block, 0, stream, g);
+    } else if (sat8_path(g)) {
+        if (g.stream_out) hipLaunchKernelGGL((gemm_i4_kernel<EPI_SAT8_S64, KS_LONG, true>), grid, block, 0, stream, g);
+        else hipLaunchKernelGGL((gemm_i4_kernel<EPI_SAT8_S64, KS_LONG, false>), grid, block, 0, stream, g);
+    } else {
+        if (g.stream_out) hipLaunchKernelGGL((gemm_i4_kernel<EPI_GENERIC, KS_LONG, true>), grid, block, 0, stream, g);
+        else hipLaunchKernelGGL((gemm_i4_kernel<EPI_GENERIC, KS_LONG, false>), grid, block, 0, stream, g);
+    }
     return hipGetLastError();
 }
 
