@@ -229,6 +229,40 @@ int hdqt_layer_step(const float *X, const float *W, const float *G, float *Z, fl
                     void *workspace, size_t workspace_bytes, void *stream);
 
 /*
+ * The same step as two calls, for training loops in which the gradient G arrives
+ * long after the forward product (Methodology: the forward and the backward
+ * matmuls of a layer):
+ *   hdqt_layer_fwd  Z = hdqt_gemm_fwd(X, W; *fwd); when bwd_weight is not NULL, X is
+ *                   also quantized along M with bwd_weight->A / had_block / seed,
+ *                   from the same reads, and those codes and their scale are left
+ *                   in `saved`: the activation is kept for the backward pass as b-bit
+ *                   codes (hdqt_layer_saved_size bytes, 1/8 of fp32 X at b = 4)
+ *                   instead of X itself.
+ *   hdqt_layer_bwd  dW = hdqt_gemm_bwd_weight(X, G; *bwd_weight) with X taken from
+ *                   `saved`, and, when dX is not NULL, dX = hdqt_gemm_bwd_input(G, W;
+ *                   *bwd_input); G is read once per pass for both.
+ * Results are bit-identical to the hdqt_gemm_* calls.  bwd_weight must be the same
+ * in both calls.  saved: device memory, 16-byte aligned, written by hdqt_layer_fwd,
+ * read by hdqt_layer_bwd, owned by the caller in between; its layout (a 256-byte
+ * header holding the scale, then packed codes [K, pitch(M)]) is private to the
+ * library.  Workspaces as for the other entry points (the *_workspace_size
+ * functions return 0 for invalid arguments); params are host pointers.
+ */
+size_t hdqt_layer_saved_size(int64_t M, int64_t K, const hdqt_params_t *bwd_weight);
+size_t hdqt_layer_fwd_workspace_size(int64_t M, int64_t K, int64_t N, const hdqt_params_t *fwd,
+                                     const hdqt_params_t *bwd_weight);
+int hdqt_layer_fwd(const float *X, const float *W, float *Z, int64_t M, int64_t K, int64_t N,
+                   const hdqt_params_t *fwd, const hdqt_params_t *bwd_weight, void *saved,
+                   size_t saved_bytes, void *workspace, size_t workspace_bytes, void *stream);
+size_t hdqt_layer_bwd_workspace_size(int64_t M, int64_t K, int64_t N,
+                                     const hdqt_params_t *bwd_input,
+                                     const hdqt_params_t *bwd_weight);
+int hdqt_layer_bwd(const float *G, const float *W, const void *saved, float *dX, float *dW,
+                   int64_t M, int64_t K, int64_t N, const hdqt_params_t *bwd_input,
+                   const hdqt_params_t *bwd_weight, void *workspace, size_t workspace_bytes,
+                   void *stream);
+
+/*
  * Optional per-kernel timing, for benchmarks.  While enabled, every kernel the
  * library launches is bracketed by two HIP events on its stream (this is the
  * only state the library keeps, and events are the only thing it creates).

@@ -1,0 +1,94 @@
+"""torch.autograd glue over the C ABI: a linear map Z = X W whose forward product and
+both gradients are the library's quantized matmuls (Methodology: forward and
+backward pass of a layer).  Nothing is computed here; the functions marshal
+tensors into hdqt_layer_fwd / hdqt_layer_bwd and hand the results to autograd.
+
+The activation is not kept in fp32 for the backward pass: hdqt_layer_fwd leaves
+X's codes along the batch dimension (what the weight gradient contracts over)
+in a byte buffer one eighth the size of X at 4 bits.
+"""
+from dataclasses import dataclass, field
+from typing import Optional
+
+import torch
+
+from . import binding as B
+
+
+@dataclass
+class LayerConfig:
+    """Quantization of one layer's three matmuls; defaults follow the paper's
+    backward-pass setting (4-bit codes, Hadamard block 64, stochastic rounding of
+    the gradient, 8-bit accumulators over tiles of 32)."""
+    had_block: int = 64
+    bits: int = 4
+    acc_bits: int = 8
+    s: int = 32
+    seed: int = 0
+    layer_id: int = 0
+    clip_fwd: float = 1.0
+    stochastic_grad: bool = True
+    need_input_grad: bool = True
+
+    def params(self, kind: int, step: int = 0) -> B.Params:
+        tid = lambda role: 16 * self.layer_id + {"X": 0, "W": 1, "G": 2}[role] + 4 * kind
+        NE = B.ROUND_NEAREST
+        ST = B.ROUND_STOCHASTIC if self.stochastic_grad else NE
+        b = self.bits
+        if kind == B.GEMM_FWD:
+            A, Bq = B.Operand(b, NE, self.clip_fwd, tid("X")), B.Operand(b, NE, self.clip_fwd, tid("W"))
+        elif kind == B.GEMM_BWD_INPUT:
+            A, Bq = B.Operand(b, ST, 1.0, tid("G")), B.Operand(b, NE, 1.0, tid("W"))
+        else:
+            A, Bq = B.Operand(b, NE, 1.0, tid("X")), B.Operand(b, ST, 1.0, tid("G"))
+        # a fresh random stream every step: the seed advances with the step counter
+        return B.Params(had_block=self.had_block, acc_bits=self.acc_bits, s=self.s,
+                        seed=self.seed + step, A=A, B=Bq)
+
+
+class HdqtMatmul(torch.autograd.Function):
+    """Z = X W with X [M, K], W [K, N] on the GPU, fp32, contiguous."""
+
+    @staticmethod
+    def forward(ctx, X, W, cfg: LayerConfig, step: int):
+        X, W = X.contiguous(), W.contiguous()
+        pf = cfg.params(B.GEMM_FWD, step)
+        pw = cfg.params(B.GEMM_BWD_WEIGHT, step)
+        Z, saved = B.layer_fwd(X, W, pf, pw)
+        ctx.save_for_backward(W, saved)
+        ctx.cfg, ctx.step, ctx.K = cfg, step, X.shape[1]
+        ctx.want_dx = cfg.need_input_grad and X.requires_grad
+        return Z
+
+    @staticmethod
+    def backward(ctx, G):
+        W, saved = ctx.saved_tensors
+        cfg = ctx.cfg
+        pi = cfg.params(B.GEMM_BWD_INPUT, ctx.step) if ctx.want_dx else None
+        pw = cfg.params(B.GEMM_BWD_WEIGHT, ctx.step)
+        dX, dW = B.layer_bwd(G.contiguous(), W, saved, ctx.K, pi, pw)
+        return dX, dW, None, None
+
+
+class HdqtLinear(torch.nn.Module):
+    """y = x W + bias with the matmul and its gradients quantized; inputs of any
+    leading shape are flattened to [M, K]."""
+
+    def __init__(self, in_features: int, out_features: int, bias: bool = True,
+                 cfg: Optional[LayerConfig] = None, device=None):
+        super().__init__()
+        self.cfg = cfg or LayerConfig()
+        w = torch.empty(in_features, out_features, device=device)
+        torch.nn.init.kaiming_normal_(w.t(), nonlinearity="relu")     # fan-in = in_features
+        self.weight = torch.nn.Parameter(w)
+        self.bias = torch.nn.Parameter(torch.zeros(out_features, device=device)) if bias else None
+        self.step = 0
+
+    def forward(self, x):
+        lead = x.shape[:-1]
+        z = HdqtMatmul.apply(x.reshape(-1, x.shape[-1]), self.weight, self.cfg, self.step)
+        if self.training:
+            self.step += 1
+        if self.bias is not None:
+            z = z + self.bias
+        return z.reshape(*lead, -1)

@@ -24,7 +24,8 @@ EXPORTED = [
     "hdqt_gemm_bwd_input", "hdqt_gemm_bwd_weight", "hdqt_strerror", "hdqt_last_hip_error",
     "hdqt_profile_enable", "hdqt_profile_collect", "hdqt_quantize_dual",
     "hdqt_quantize_dual_workspace_size", "hdqt_layer_step_workspace_size", "hdqt_layer_step",
-    "hdqt_gemm_codes_workspace_size",
+    "hdqt_gemm_codes_workspace_size", "hdqt_layer_saved_size", "hdqt_layer_fwd_workspace_size",
+    "hdqt_layer_fwd", "hdqt_layer_bwd_workspace_size", "hdqt_layer_bwd",
 ]
 
 
@@ -108,6 +109,16 @@ def load() -> C.CDLL:
     lib.hdqt_quantize_dual_workspace_size.argtypes = []
     lib.hdqt_gemm_codes_workspace_size.restype = sz
     lib.hdqt_gemm_codes_workspace_size.argtypes = [i64, i64, i64, i64]
+    lib.hdqt_layer_saved_size.restype = sz
+    lib.hdqt_layer_saved_size.argtypes = [i64, i64, C.POINTER(CParams)]
+    lib.hdqt_layer_fwd_workspace_size.restype = sz
+    lib.hdqt_layer_fwd_workspace_size.argtypes = [i64, i64, i64] + [C.POINTER(CParams)] * 2
+    lib.hdqt_layer_fwd.restype = i32
+    lib.hdqt_layer_fwd.argtypes = [vp] * 3 + [i64, i64, i64] + [C.POINTER(CParams)] * 2 + [vp, sz, vp, sz, vp]
+    lib.hdqt_layer_bwd_workspace_size.restype = sz
+    lib.hdqt_layer_bwd_workspace_size.argtypes = [i64, i64, i64] + [C.POINTER(CParams)] * 2
+    lib.hdqt_layer_bwd.restype = i32
+    lib.hdqt_layer_bwd.argtypes = [vp] * 5 + [i64, i64, i64] + [C.POINTER(CParams)] * 2 + [vp, sz, vp]
     lib.hdqt_layer_step_workspace_size.restype = sz
     lib.hdqt_layer_step_workspace_size.argtypes = [i64, i64, i64] + [C.POINTER(CParams)] * 3
     lib.hdqt_layer_step.restype = i32
@@ -334,3 +345,57 @@ def layer_step(X: torch.Tensor, W: torch.Tensor, G: torch.Tensor, fwd: Params,
     if rc:
         raise HdqtError(rc, "hdqt_layer_step")
     return Z, dX, dW, workspace
+
+
+def _byref(p):
+    return C.byref(p) if p is not None else None
+
+
+def layer_fwd(X: torch.Tensor, W: torch.Tensor, fwd: Params, bwd_weight: Optional[Params] = None,
+              out: Optional[torch.Tensor] = None, saved: Optional[torch.Tensor] = None,
+              workspace: Optional[torch.Tensor] = None, stream: Optional[torch.cuda.Stream] = None):
+    """hdqt_layer_fwd -> (Z, saved | None).  With `bwd_weight`, `saved` receives X's codes
+    along M for layer_bwd (a uint8 tensor of hdqt_layer_saved_size bytes)."""
+    _check_dev(X, W, out, saved, workspace)
+    M, K = X.shape
+    N = W.shape[1]
+    assert W.shape[0] == K
+    if out is None:
+        out = torch.empty((M, N), dtype=torch.float32, device=X.device)
+    pf = fwd.c()
+    pw = bwd_weight.c() if bwd_weight is not None else None
+    if pw is not None and saved is None:
+        saved = torch.empty(load().hdqt_layer_saved_size(M, K, C.byref(pw)), dtype=torch.uint8,
+                            device=X.device)
+    if workspace is None:
+        need = load().hdqt_layer_fwd_workspace_size(M, K, N, C.byref(pf), _byref(pw))
+        workspace = torch.empty(max(need, 256), dtype=torch.uint8, device=X.device)
+    rc = load().hdqt_layer_fwd(_ptr(X), _ptr(W), _ptr(out), M, K, N, C.byref(pf), _byref(pw),
+                               _ptr(saved), saved.numel() if saved is not None else 0,
+                               _ptr(workspace), workspace.numel(), _stream(stream))
+    if rc:
+        raise HdqtError(rc, "hdqt_layer_fwd")
+    return out, saved
+
+
+def layer_bwd(G: torch.Tensor, W: torch.Tensor, saved: torch.Tensor, K: int,
+              bwd_input: Optional[Params], bwd_weight: Params, out=None,
+              workspace: Optional[torch.Tensor] = None, stream: Optional[torch.cuda.Stream] = None):
+    """hdqt_layer_bwd -> (dX | None, dW).  dX is skipped when `bwd_input` is None.
+    `out` may carry preallocated (dX, dW)."""
+    _check_dev(G, W, saved, workspace)
+    M, N = G.shape
+    if out is None:
+        new = lambda *shape: torch.empty(shape, dtype=torch.float32, device=G.device)
+        out = (new(M, K) if bwd_input is not None else None, new(K, N))
+    dX, dW = out
+    pi = bwd_input.c() if bwd_input is not None else None
+    pw = bwd_weight.c()
+    if workspace is None:
+        need = load().hdqt_layer_bwd_workspace_size(M, K, N, _byref(pi), C.byref(pw))
+        workspace = torch.empty(max(need, 256), dtype=torch.uint8, device=G.device)
+    rc = load().hdqt_layer_bwd(_ptr(G), _ptr(W), _ptr(saved), _ptr(dX), _ptr(dW), M, K, N, _byref(pi),
+                               C.byref(pw), _ptr(workspace), workspace.numel(), _stream(stream))
+    if rc:
+        raise HdqtError(rc, "hdqt_layer_bwd")
+    return dX, dW

@@ -315,6 +315,86 @@ int plan_step(int64_t M, int64_t K, int64_t N, const hdqt_params_t* const prm[3]
     return HDQT_OK;
 }
 
+
+// ---- forward and backward halves of a layer's step, with X's codes along M handed over
+constexpr size_t kSavedHeader = 256;     // the scale (one float) of the saved codes, then padding
+
+struct FwdLayout {
+    size_t metaX1, metaX0, metaW0;       // contiguous from offset 0
+    size_t acc, acc_bytes;
+    size_t codesX1, codesW0;
+    size_t total;
+    int n_fwd, n_bww;
+};
+
+int plan_fwd(int64_t M, int64_t K, int64_t N, const hdqt_params_t* fwd, const hdqt_params_t* bww,
+             FwdLayout* L)
+{
+    Orientation o;
+    int rc = check_gemm(HDQT_GEMM_FWD, M, K, N, fwd, &o);
+    if (rc) return rc;
+    L->n_fwd = hdqt_n_eff(K, fwd->had_block);
+    L->n_bww = 1;
+    if (bww) {
+        Orientation ow;
+        if ((rc = check_gemm(HDQT_GEMM_BWD_WEIGHT, M, K, N, bww, &ow))) return rc;
+        L->n_bww = hdqt_n_eff(M, bww->had_block);
+    }
+    size_t off = 0;
+    L->metaX1 = off; off += kMetaBytes;
+    L->metaX0 = off; off += kMetaBytes;
+    L->metaW0 = off; off += kMetaBytes;
+    L->acc = off;
+    L->acc_bytes = partial_bytes(M, N, K, fwd->s);
+    off = align_up(off + L->acc_bytes, 256);
+    L->codesX1 = off;
+    off = align_up(off + (size_t)(M * hdqt_codes_pitch(K, fwd->A.b)), 256);
+    L->codesW0 = off;
+    off = align_up(off + (size_t)(N * hdqt_codes_pitch(K, fwd->B.b)), 256);
+    L->total = off;
+    return HDQT_OK;
+}
+
+struct BwdLayout {
+    size_t metaG1, metaG0, metaW1;       // contiguous from offset 0
+    size_t acc[2], acc_bytes[2];         // input gradient, weight gradient
+    size_t codesG1, codesG0, codesW1;
+    size_t total;
+    int n_bwi, n_bww;
+};
+
+int plan_bwd(int64_t M, int64_t K, int64_t N, const hdqt_params_t* bwi, const hdqt_params_t* bww,
+             BwdLayout* L)
+{
+    Orientation o;
+    int rc = check_gemm(HDQT_GEMM_BWD_WEIGHT, M, K, N, bww, &o);
+    if (rc) return rc;
+    L->n_bww = hdqt_n_eff(M, bww->had_block);
+    L->n_bwi = 1;
+    if (bwi) {
+        if ((rc = check_gemm(HDQT_GEMM_BWD_INPUT, M, K, N, bwi, &o))) return rc;
+        L->n_bwi = hdqt_n_eff(N, bwi->had_block);
+    }
+    size_t off = 0;
+    L->metaG1 = off; off += kMetaBytes;
+    L->metaG0 = off; off += kMetaBytes;
+    L->metaW1 = off; off += kMetaBytes;
+    L->acc[0] = off;
+    L->acc_bytes[0] = bwi ? partial_bytes(M, K, N, bwi->s) : 0;
+    off = align_up(off + L->acc_bytes[0], 256);
+    L->acc[1] = off;
+    L->acc_bytes[1] = partial_bytes(K, N, M, bww->s);
+    off = align_up(off + L->acc_bytes[1], 256);
+    L->codesG1 = off;
+    off = align_up(off + (bwi ? (size_t)(M * hdqt_codes_pitch(N, bwi->A.b)) : 0), 256);
+    L->codesG0 = off;
+    off = align_up(off + (size_t)(N * hdqt_codes_pitch(M, bww->B.b)), 256);
+    L->codesW1 = off;
+    off = align_up(off + (bwi ? (size_t)(K * hdqt_codes_pitch(N, bwi->B.b)) : 0), 256);
+    L->total = off;
+    return HDQT_OK;
+}
+
 } // namespace
 
 extern "C" {
@@ -520,6 +600,109 @@ int hdqt_layer_step(const float* X, const float* W, const float* G, float* Z, fl
                                       bwd_input->acc_bits, bwd_input->s, dX, nullptr,
                                       1 + HDQT_GEMM_BWD_INPUT),
                             acc(HDQT_GEMM_BWD_INPUT), L.acc_bytes[HDQT_GEMM_BWD_INPUT], stream);
+}
+
+size_t hdqt_layer_saved_size(int64_t M, int64_t K, const hdqt_params_t* bwd_weight)
+{
+    if (!bwd_weight || check_dims2(M, K) || check_operand(&bwd_weight->A)) return 0;
+    return kSavedHeader + align_up((size_t)(K * hdqt_codes_pitch(M, bwd_weight->A.b)), 256);
+}
+
+size_t hdqt_layer_fwd_workspace_size(int64_t M, int64_t K, int64_t N, const hdqt_params_t* fwd,
+                                     const hdqt_params_t* bwd_weight)
+{
+    FwdLayout L;
+    return plan_fwd(M, K, N, fwd, bwd_weight, &L) == HDQT_OK ? L.total : 0;
+}
+
+int hdqt_layer_fwd(const float* X, const float* W, float* Z, int64_t M, int64_t K, int64_t N,
+                   const hdqt_params_t* fwd, const hdqt_params_t* bwd_weight, void* saved,
+                   size_t saved_bytes, void* workspace, size_t workspace_bytes, void* stream_v)
+{
+    if (!X || !W || !Z || !fwd) return HDQT_EINVAL_NULL;
+    if (bwd_weight && !saved) return HDQT_EINVAL_NULL;
+    FwdLayout L;
+    int rc = plan_fwd(M, K, N, fwd, bwd_weight, &L);
+    if (rc) return rc;
+    if (!workspace || workspace_bytes < L.total) return HDQT_EWORKSPACE;
+    if (bwd_weight && saved_bytes < hdqt_layer_saved_size(M, K, bwd_weight)) return HDQT_EWORKSPACE;
+    if (misaligned(X) || misaligned(W) || misaligned(Z) || misaligned(saved) || misaligned(workspace))
+        return HDQT_EALIGN;
+    hipStream_t stream = static_cast<hipStream_t>(stream_v);
+    char* base = static_cast<char*>(workspace);
+    char* sv = static_cast<char*>(saved);
+    auto meta = [&](size_t off) { return reinterpret_cast<hdqt::QMeta*>(base + off); };
+    hipError_t e = hdqt::launch_zero2(reinterpret_cast<uint32_t*>(base), (int64_t)(3 * kMetaBytes / 4),
+                                      nullptr, 0, stream);
+    if (e != hipSuccess) return hip_fail(e);
+    if (bwd_weight)
+        rc = run_quantize_pair(X, M, K, L.n_fwd, &fwd->A, fwd->seed, L.n_bww, &bwd_weight->A,
+                               bwd_weight->seed, meta(L.metaX1), meta(L.metaX0), base + L.codesX1,
+                               sv + kSavedHeader, nullptr, reinterpret_cast<float*>(sv), stream, 1);
+    else
+        rc = run_quantize(X, M, K, 1, L.n_fwd, &fwd->A, fwd->seed, meta(L.metaX1), base + L.codesX1,
+                          nullptr, stream);
+    if (rc) return rc;
+    rc = run_quantize(W, K, N, 0, L.n_fwd, &fwd->B, fwd->seed, meta(L.metaW0), base + L.codesW0, nullptr,
+                      stream);
+    if (rc) return rc;
+    return run_planned_gemm(plan_gemm(base + L.codesX1, base + L.codesW0, fwd->A.b, fwd->B.b,
+                                      &meta(L.metaX1)->scale, &meta(L.metaW0)->scale, M, N, K, L.n_fwd,
+                                      fwd->acc_bits, fwd->s, Z, nullptr, 1 + HDQT_GEMM_FWD),
+                            base + L.acc, L.acc_bytes, stream);
+}
+
+size_t hdqt_layer_bwd_workspace_size(int64_t M, int64_t K, int64_t N, const hdqt_params_t* bwd_input,
+                                     const hdqt_params_t* bwd_weight)
+{
+    BwdLayout L;
+    return plan_bwd(M, K, N, bwd_input, bwd_weight, &L) == HDQT_OK ? L.total : 0;
+}
+
+int hdqt_layer_bwd(const float* G, const float* W, const void* saved, float* dX, float* dW, int64_t M,
+                   int64_t K, int64_t N, const hdqt_params_t* bwd_input,
+                   const hdqt_params_t* bwd_weight, void* workspace, size_t workspace_bytes,
+                   void* stream_v)
+{
+    if (!G || !saved || !dW || !bwd_weight) return HDQT_EINVAL_NULL;
+    const bool with_dx = dX != nullptr;
+    if (with_dx && (!bwd_input || !W)) return HDQT_EINVAL_NULL;
+    BwdLayout L;
+    int rc = plan_bwd(M, K, N, with_dx ? bwd_input : nullptr, bwd_weight, &L);
+    if (rc) return rc;
+    if (!workspace || workspace_bytes < L.total) return HDQT_EWORKSPACE;
+    if (misaligned(G) || misaligned(W) || misaligned(saved) || misaligned(dX) || misaligned(dW) ||
+        misaligned(workspace))
+        return HDQT_EALIGN;
+    hipStream_t stream = static_cast<hipStream_t>(stream_v);
+    char* base = static_cast<char*>(workspace);
+    const char* sv = static_cast<const char*>(saved);
+    auto meta = [&](size_t off) { return reinterpret_cast<hdqt::QMeta*>(base + off); };
+    hipError_t e = hdqt::launch_zero2(reinterpret_cast<uint32_t*>(base), (int64_t)(3 * kMetaBytes / 4),
+                                      nullptr, 0, stream);
+    if (e != hipSuccess) return hip_fail(e);
+    if (with_dx)
+        rc = run_quantize_pair(G, M, N, L.n_bwi, &bwd_input->A, bwd_input->seed, L.n_bww, &bwd_weight->B,
+                               bwd_weight->seed, meta(L.metaG1), meta(L.metaG0), base + L.codesG1,
+                               base + L.codesG0, nullptr, nullptr, stream, 3);
+    else
+        rc = run_quantize(G, M, N, 0, L.n_bww, &bwd_weight->B, bwd_weight->seed, meta(L.metaG0),
+                          base + L.codesG0, nullptr, stream);
+    if (rc) return rc;
+    rc = run_planned_gemm(plan_gemm(sv + kSavedHeader, base + L.codesG0, bwd_weight->A.b, bwd_weight->B.b,
+                                    reinterpret_cast<const float*>(sv), &meta(L.metaG0)->scale, K, N, M,
+                                    L.n_bww, bwd_weight->acc_bits, bwd_weight->s, dW, nullptr,
+                                    1 + HDQT_GEMM_BWD_WEIGHT),
+                          base + L.acc[1], L.acc_bytes[1], stream);
+    if (rc || !with_dx) return rc;
+    rc = run_quantize(W, K, N, 1, L.n_bwi, &bwd_input->B, bwd_input->seed, meta(L.metaW1),
+                      base + L.codesW1, nullptr, stream);
+    if (rc) return rc;
+    return run_planned_gemm(plan_gemm(base + L.codesG1, base + L.codesW1, bwd_input->A.b, bwd_input->B.b,
+                                      &meta(L.metaG1)->scale, &meta(L.metaW1)->scale, M, K, N, L.n_bwi,
+                                      bwd_input->acc_bits, bwd_input->s, dX, nullptr,
+                                      1 + HDQT_GEMM_BWD_INPUT),
+                            base + L.acc[0], L.acc_bytes[0], stream);
 }
 
 int hdqt_gemm_fwd(const float* X, const float* W, float* Z, int64_t M, int64_t K, int64_t N,

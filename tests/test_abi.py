@@ -148,3 +148,114 @@ def test_strerror_texts():
         assert B.strerror(code) and "unknown error" not in B.strerror(code)
     assert "unknown error" in B.strerror(-99)
     assert B.load().hdqt_last_hip_error() == 0
+
+
+# ---------------------------------------------------------------- the whole-step entry points
+# (argument errors only: found on the host before anything is launched)
+
+def _error_codes():
+    """name -> value of the HDQT_E* macros, parsed from the header"""
+    text = open(os.path.join(ROOT, "include", "hdqt.h")).read()
+    return {k: int(v) for k, v in re.findall(r"#define (HDQT_E[A-Z_]+) \((-\d+)\)", text)}
+
+
+E = _error_codes()
+
+
+def _cparams(n=64, a=8, s=32, bA=4, bB=4):
+    return B.Params(had_block=n, acc_bits=a, s=s, A=B.Operand(b=bA), B=B.Operand(b=bB)).c()
+
+
+def test_quantize_dual_argument_errors():
+    lib = B.load()
+    op = B.Operand(b=4).c()
+
+    def rc(T=FAKE, rows=64, cols=64, had=64, o1=op, o0=op, c1=FAKE, s1=FAKE, c0=FAKE, s0=FAKE,
+           ws=FAKE, ws_bytes=1 << 16):
+        return lib.hdqt_quantize_dual(T, rows, cols, had, C.byref(o1), C.byref(o0), 0, c1, s1, c0, s0,
+                                      ws, ws_bytes, None)
+
+    assert lib.hdqt_quantize_dual_workspace_size() >= 2 * lib.hdqt_quantize_workspace_size()
+    assert rc(T=None) == E["HDQT_EINVAL_NULL"]
+    assert rc(c0=None) == E["HDQT_EINVAL_NULL"]
+    assert rc(s1=None) == E["HDQT_EINVAL_NULL"]
+    assert rc(rows=0) == E["HDQT_EINVAL_DIM"]
+    assert rc(had=48) == E["HDQT_EINVAL_HADAMARD"]
+    assert rc(o0=B.Operand(b=9).c()) == E["HDQT_EINVAL_BITS"]
+    assert rc(o1=B.Operand(b=4, clip=0.0).c()) == E["HDQT_EINVAL_CLIP"]
+    assert rc(ws=None) == E["HDQT_EWORKSPACE"]
+    assert rc(ws_bytes=lib.hdqt_quantize_workspace_size()) == E["HDQT_EWORKSPACE"]
+    assert rc(c1=C.c_void_p(0x1008)) == E["HDQT_EALIGN"]
+    assert rc(s0=C.c_void_p(0x1002)) == E["HDQT_EALIGN"]
+
+
+def test_layer_step_argument_errors():
+    lib = B.load()
+    M, K, N = 256, 128, 64
+    pf, pi, pw = _cparams(), _cparams(), _cparams()
+    need = lib.hdqt_layer_step_workspace_size(M, K, N, C.byref(pf), C.byref(pi), C.byref(pw))
+    assert need > 0
+    # without the input gradient less is needed, never more
+    assert 0 < lib.hdqt_layer_step_workspace_size(M, K, N, C.byref(pf), None, C.byref(pw)) <= need
+    assert lib.hdqt_layer_step_workspace_size(M, K, N, C.byref(pf), C.byref(pi), C.byref(_cparams(n=3))) == 0
+
+    def rc(X=FAKE, W=FAKE, G=FAKE, Z=FAKE, dX=FAKE, dW=FAKE, m=M, f=pf, i=pi, w=pw, ws=FAKE, nbytes=need):
+        return lib.hdqt_layer_step(X, W, G, Z, dX, dW, m, K, N, C.byref(f) if f else None,
+                                   C.byref(i) if i else None, C.byref(w) if w else None, ws, nbytes, None)
+
+    assert rc(X=None) == E["HDQT_EINVAL_NULL"]
+    assert rc(dW=None) == E["HDQT_EINVAL_NULL"]
+    assert rc(w=None) == E["HDQT_EINVAL_NULL"]
+    assert rc(i=None) == E["HDQT_EINVAL_NULL"]            # dX wanted but no parameters for it
+    assert rc(m=0) == E["HDQT_EINVAL_DIM"]
+    assert rc(f=_cparams(a=1)) == E["HDQT_EINVAL_ACC"]
+    assert rc(w=_cparams(s=0)) == E["HDQT_EINVAL_TILE"]
+    assert rc(i=_cparams(bA=1)) == E["HDQT_EINVAL_BITS"]
+    assert rc(ws=None) == E["HDQT_EWORKSPACE"]
+    assert rc(nbytes=need - 1) == E["HDQT_EWORKSPACE"]
+    assert rc(G=C.c_void_p(0x1004)) == E["HDQT_EALIGN"]
+
+
+def test_layer_fwd_bwd_argument_errors():
+    lib = B.load()
+    M, K, N = 256, 128, 64
+    pf, pi, pw = _cparams(), _cparams(), _cparams()
+    saved = lib.hdqt_layer_saved_size(M, K, C.byref(pw))
+    assert saved >= K * M // 2 and lib.hdqt_layer_saved_size(M, K, None) == 0
+    nf = lib.hdqt_layer_fwd_workspace_size(M, K, N, C.byref(pf), C.byref(pw))
+    nb = lib.hdqt_layer_bwd_workspace_size(M, K, N, C.byref(pi), C.byref(pw))
+    assert nf > 0 and nb > 0
+    assert lib.hdqt_layer_bwd_workspace_size(M, K, N, C.byref(pi), None) == 0
+
+    def fwd(X=FAKE, W=FAKE, Z=FAKE, f=pf, w=pw, sv=FAKE, sv_bytes=saved, ws=FAKE, nbytes=nf):
+        return lib.hdqt_layer_fwd(X, W, Z, M, K, N, C.byref(f) if f else None, C.byref(w) if w else None,
+                                  sv, sv_bytes, ws, nbytes, None)
+
+    assert fwd(Z=None) == E["HDQT_EINVAL_NULL"]
+    assert fwd(f=None) == E["HDQT_EINVAL_NULL"]
+    assert fwd(sv=None) == E["HDQT_EINVAL_NULL"]          # codes are to be saved but there is no buffer
+    assert fwd(sv_bytes=saved - 1) == E["HDQT_EWORKSPACE"]
+    assert fwd(nbytes=nf - 1) == E["HDQT_EWORKSPACE"]
+    assert fwd(f=_cparams(n=512)) == E["HDQT_EINVAL_HADAMARD"]
+    assert fwd(sv=C.c_void_p(0x1001)) == E["HDQT_EALIGN"]
+
+    def bwd(G=FAKE, W=FAKE, sv=FAKE, dX=FAKE, dW=FAKE, i=pi, w=pw, ws=FAKE, nbytes=nb):
+        return lib.hdqt_layer_bwd(G, W, sv, dX, dW, M, K, N, C.byref(i) if i else None,
+                                  C.byref(w) if w else None, ws, nbytes, None)
+
+    assert bwd(G=None) == E["HDQT_EINVAL_NULL"]
+    assert bwd(sv=None) == E["HDQT_EINVAL_NULL"]
+    assert bwd(w=None) == E["HDQT_EINVAL_NULL"]
+    assert bwd(i=None) == E["HDQT_EINVAL_NULL"]
+    assert bwd(W=None) == E["HDQT_EINVAL_NULL"]
+    assert bwd(nbytes=nb - 1) == E["HDQT_EWORKSPACE"]
+    assert bwd(w=_cparams(a=40)) == E["HDQT_EINVAL_ACC"]
+    assert bwd(dW=C.c_void_p(0x1008)) == E["HDQT_EALIGN"]
+
+
+def test_gemm_codes_workspace_size():
+    lib = B.load()
+    assert lib.hdqt_gemm_codes_workspace_size(65536, 128, 1152, 32) == 0          # many output tiles: no split
+    need = lib.hdqt_gemm_codes_workspace_size(1152, 128, 65536, 32)               # 9 tiles, long contraction
+    assert need > 0 and need % (1152 * 128 * 4) == 0
+    assert lib.hdqt_gemm_codes_workspace_size(0, 128, 64, 32) == 0
