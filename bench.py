@@ -32,9 +32,8 @@ HBM_PEAK_GBPS = 8000.0          # MI355X HBM3E
 # profiles/bench_resnet_k1152_hbm_traffic.md (per-launch average over the tensors a
 # kernel family runs on); bench.py cannot collect counters itself.
 MEASURED_TRAFFIC = {
-    "fwht_dual_absmax_X": 302.2e6, "fwht_dual_quant_X": 378.6e6,
-    "fwht_dual_absmax_W": 0.8e6, "fwht_dual_quant_W": 1.1e6,
-    "fwht_dual_absmax_G": 33.8e6, "fwht_dual_quant_G": 42.6e6,
+    "fwht_dual_absmax_batch": 302.2e6 + 0.8e6 + 33.8e6, "fwht_dual_quant_batch": 378.6e6 + 1.1e6,
+    "fwht_dual_quant_G": 42.6e6,
     "gemm_i4_fwd": 74.6e6, "gemm_i4_bwd_input": 327.6e6, "gemm_i4_bwd_weight": 98.9e6,
 }
 INT8_MFMA_PEAK_TOPS = 5000.0    # MI355X dense int8
@@ -206,8 +205,14 @@ def main():
         if fam in seen:
             absmax = "absmax" in name
             per_elem = 4.0 if absmax else 4.0 + (1.0 if fam == "fwht_dua" else 0.5)
-            # hdqt_layer_step names the tensor of each two-axis launch (..._X, _W, _G)
-            tensors = [name[-1]] if name[-2:] in ("_X", "_W", "_G") else seen[fam]
+            # hdqt_layer_step names the tensor of each two-axis launch (..._X, _W, _G); one
+            # launch finds the maxima of all three tensors, one writes the codes of X and W
+            if name[-2:] in ("_X", "_W", "_G"):
+                tensors = [name[-1]]
+            elif name.endswith("_batch"):
+                tensors = ["X", "W", "G"] if absmax else ["X", "W"]
+            else:
+                tensors = seen[fam]
             bytes_launch = per_elem * sum(elems[t] for t in tensors) / per_step
             gbps = bytes_launch / avg_s / 1e9
             roof_all[name] = {"bound": "hbm", "achieved": gbps, "peak": HBM_PEAK_GBPS, "unit": "GB/s",

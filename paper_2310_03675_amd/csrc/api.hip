@@ -137,13 +137,11 @@ int run_quantize(const float* T, int64_t rows, int64_t cols, int axis, int n_eff
     return e == hipSuccess ? HDQT_OK : hip_fail(e);
 }
 
-// Both quantizations of one tensor (axis 1 and axis 0): from a single read per
-// pass when the fused kernel takes the shape, else one after the other.  Both
-// calibration records must be zero.
-int run_quantize_pair(const float* T, int64_t rows, int64_t cols, int n1, const hdqt_operand_t* op1,
-                      uint64_t seed1, int n0, const hdqt_operand_t* op0, uint64_t seed0,
-                      hdqt::QMeta* meta1, hdqt::QMeta* meta0, void* codes1, void* codes0,
-                      float* scale1_out, float* scale0_out, hipStream_t stream, int profile_tag = 0)
+hdqt::DualArgs make_dual_args(const float* T, int64_t rows, int64_t cols, int n1,
+                              const hdqt_operand_t* op1, uint64_t seed1, int n0,
+                              const hdqt_operand_t* op0, uint64_t seed0, hdqt::QMeta* meta1,
+                              hdqt::QMeta* meta0, void* codes1, void* codes0, float* scale1_out,
+                              float* scale0_out, int profile_tag)
 {
     hdqt::DualArgs d{};
     d.profile_tag = profile_tag;
@@ -158,6 +156,19 @@ int run_quantize_pair(const float* T, int64_t rows, int64_t cols, int n1, const 
     d.meta_row = meta1; d.meta_col = meta0;
     d.codes_row = static_cast<uint8_t*>(codes1); d.codes_col = static_cast<uint8_t*>(codes0);
     d.scale_row_out = scale1_out; d.scale_col_out = scale0_out;
+    return d;
+}
+
+// Both quantizations of one tensor (axis 1 and axis 0): from a single read per
+// pass when the fused kernel takes the shape, else one after the other.  Both
+// calibration records must be zero.
+int run_quantize_pair(const float* T, int64_t rows, int64_t cols, int n1, const hdqt_operand_t* op1,
+                      uint64_t seed1, int n0, const hdqt_operand_t* op0, uint64_t seed0,
+                      hdqt::QMeta* meta1, hdqt::QMeta* meta0, void* codes1, void* codes0,
+                      float* scale1_out, float* scale0_out, hipStream_t stream, int profile_tag = 0)
+{
+    const hdqt::DualArgs d = make_dual_args(T, rows, cols, n1, op1, seed1, n0, op0, seed0, meta1, meta0,
+                                            codes1, codes0, scale1_out, scale0_out, profile_tag);
     if (hdqt::quantize_dual_eligible(d)) {
         const hipError_t e = hdqt::launch_quantize_dual(d, stream);
         return e == hipSuccess ? HDQT_OK : hip_fail(e);
@@ -559,19 +570,49 @@ int hdqt_layer_step(const float* X, const float* W, const float* G, float* Z, fl
                                       nullptr, 0, stream);
     if (e != hipSuccess) return hip_fail(e);
 
-    // ---- forward: X along K (and along M, kept for the weight gradient), W along K
     const int nF = L.n_eff[HDQT_GEMM_FWD], nI = L.n_eff[HDQT_GEMM_BWD_INPUT],
               nW = L.n_eff[HDQT_GEMM_BWD_WEIGHT];
-    rc = run_quantize_pair(X, M, K, nF, &fwd->A, fwd->seed, nW, &bwd_weight->A, bwd_weight->seed,
-                           meta(T_X1), meta(T_X0), codes(T_X1), codes(T_X0), nullptr, nullptr, stream, 1);
-    if (rc) return rc;
-    // W along K for the forward product and, when dX is wanted, along N for the input gradient
-    if (with_dx)
-        rc = run_quantize_pair(W, K, N, nI, &bwd_input->B, bwd_input->seed, nF, &fwd->B, fwd->seed,
-                               meta(T_W1), meta(T_W0), codes(T_W1), codes(T_W0), nullptr, nullptr, stream, 2);
-    else
-        rc = run_quantize(W, K, N, 0, nF, &fwd->B, fwd->seed, meta(T_W0), codes(T_W0), nullptr, stream);
-    if (rc) return rc;
+    // X along K (forward) and along M (weight gradient); W along N (input gradient) and
+    // along K (forward); G along N (input gradient) and along M (weight gradient)
+    bool g_done = false;
+    if (with_dx) {
+        const hdqt::DualArgs dX3[3] = {
+            make_dual_args(X, M, K, nF, &fwd->A, fwd->seed, nW, &bwd_weight->A, bwd_weight->seed,
+                           meta(T_X1), meta(T_X0), codes(T_X1), codes(T_X0), nullptr, nullptr, 1),
+            make_dual_args(W, K, N, nI, &bwd_input->B, bwd_input->seed, nF, &fwd->B, fwd->seed,
+                           meta(T_W1), meta(T_W0), codes(T_W1), codes(T_W0), nullptr, nullptr, 2),
+            make_dual_args(G, M, N, nI, &bwd_input->A, bwd_input->seed, nW, &bwd_weight->B,
+                           bwd_weight->seed, meta(T_G1), meta(T_G0), codes(T_G1), codes(T_G0), nullptr,
+                           nullptr, 3)};
+        const hdqt::DualArgs &dx = dX3[0], &dw = dX3[1], &dg = dX3[2];
+        if (hdqt::quantize_dual_eligible(dx) && hdqt::quantize_dual_eligible(dw) &&
+            hdqt::quantize_dual_eligible(dg)) {
+            // all three tensors take the two-axis kernels: one launch finds all six maxima,
+            // and W's codes ride along with X's when the rounding modes agree
+            e = hdqt::launch_dual_pass1(dX3, 3, stream);
+            if (e != hipSuccess) return hip_fail(e);
+            if (dx.st_row == dw.st_row && dx.st_col == dw.st_col) {
+                e = hdqt::launch_dual_pass2(dX3, 2, stream);
+            } else {
+                e = hdqt::launch_dual_pass2(&dx, 1, stream);
+                if (e == hipSuccess) e = hdqt::launch_dual_pass2(&dw, 1, stream);
+            }
+            if (e == hipSuccess) e = hdqt::launch_dual_pass2(&dg, 1, stream);
+            if (e != hipSuccess) return hip_fail(e);
+            g_done = true;
+        }
+    }
+    if (!g_done) {
+        rc = run_quantize_pair(X, M, K, nF, &fwd->A, fwd->seed, nW, &bwd_weight->A, bwd_weight->seed,
+                               meta(T_X1), meta(T_X0), codes(T_X1), codes(T_X0), nullptr, nullptr, stream, 1);
+        if (rc) return rc;
+        if (with_dx)
+            rc = run_quantize_pair(W, K, N, nI, &bwd_input->B, bwd_input->seed, nF, &fwd->B, fwd->seed,
+                                   meta(T_W1), meta(T_W0), codes(T_W1), codes(T_W0), nullptr, nullptr, stream, 2);
+        else
+            rc = run_quantize(W, K, N, 0, nF, &fwd->B, fwd->seed, meta(T_W0), codes(T_W0), nullptr, stream);
+        if (rc) return rc;
+    }
     rc = run_planned_gemm(plan_gemm(codes(T_X1), codes(T_W0), fwd->A.b, fwd->B.b, &meta(T_X1)->scale,
                                     &meta(T_W0)->scale, M, N, K, nF, fwd->acc_bits, fwd->s, Z, nullptr,
                                     1 + HDQT_GEMM_FWD),
@@ -581,7 +622,9 @@ int hdqt_layer_step(const float* X, const float* W, const float* G, float* Z, fl
     // ---- backward: G along N and along M.  The weight gradient goes first: its
     // operand, X's codes along M, was written by the forward part and is the older
     // data in the memory-side cache; the input gradient's large output comes last.
-    if (with_dx)
+    if (g_done)
+        rc = HDQT_OK;
+    else if (with_dx)
         rc = run_quantize_pair(G, M, N, nI, &bwd_input->A, bwd_input->seed, nW, &bwd_weight->B,
                                bwd_weight->seed, meta(T_G1), meta(T_G0), codes(T_G1), codes(T_G0),
                                nullptr, nullptr, stream, 3);

@@ -89,6 +89,10 @@ struct GemmArgs {
 // Launchers (host).  Each returns the hipError_t of its last launch.
 hipError_t launch_quantize(const QuantArgs& q, hipStream_t stream);
 hipError_t launch_gemm(const GemmArgs& g, hipStream_t stream);
+constexpr int kMaxDualBatch = 3;
+// the two passes of the two-axis quantization, each for up to kMaxDualBatch tensors in one launch
+hipError_t launch_dual_pass1(const DualArgs* qs, int n, hipStream_t stream);
+hipError_t launch_dual_pass2(const DualArgs* qs, int n, hipStream_t stream);
 // zero a[0, na) and b[0, nb) (b may be null) in one launch
 hipError_t launch_zero2(uint32_t* a, int64_t na, uint32_t* b, int64_t nb, hipStream_t stream);
 // sum the `splits` slices of `partial` ([splits, count]); the totals go to acc_out
@@ -104,6 +108,7 @@ enum KernelId {
     K_PLAIN_QUANT, K_GEMM_ALIGNED, K_GEMM_GENERIC, K_REDUCE, K_GEMM_I4, K_DUAL_ABSMAX, K_DUAL_QUANT,
     K_GEMM_I4_FWD, K_GEMM_I4_BWD_INPUT, K_GEMM_I4_BWD_WEIGHT,
     K_DUAL_ABSMAX_X, K_DUAL_ABSMAX_W, K_DUAL_ABSMAX_G, K_DUAL_QUANT_X, K_DUAL_QUANT_W, K_DUAL_QUANT_G,
+    K_DUAL_ABSMAX_BATCH, K_DUAL_QUANT_BATCH,
     K_COUNT
 };
 bool quantize_fast_eligible(const QuantArgs& q);

@@ -283,7 +283,11 @@ __global__ __launch_bounds__(kThreads, 2) void gemm_i4_kernel(GemmArgs g)
 
     Staged<UNITS> st;
     fetch_next(st);
-    for (int buf = 0; c_ct < n_ct; buf ^= 1) stage(st, buf);
+    int buf = 0;
+    while (c_ct < n_ct) {       // stage() advances c_ct at the end of a tile
+        stage(st, buf);
+        buf ^= 1;
+    }
 }
 
 bool sat8_path(const GemmArgs& g) { return g.acc_hi == 127 && (g.s == 32 || g.s == 64); }

@@ -232,7 +232,7 @@ __device__ __forceinline__ void col_codes(const Tile& t, const DualCtx& x, int64
 
 // One atomicMax per workgroup and record (see block_atomic_max in common.hpp).
 __device__ __forceinline__ void block_atomic_max2(float m_row, float m_col, QMeta* meta_row,
-                                                  QMeta* meta_col, float (*smem)[2])
+                                                  QMeta* meta_col, float (*smem)[2], uint32_t block_id)
 {
     m_row = wave_max(m_row);
     m_col = wave_max(m_col);
@@ -244,7 +244,7 @@ __device__ __forceinline__ void block_atomic_max2(float m_row, float m_col, QMet
         float r = smem[0][which];
         for (int w = 1; w < kThreads / kWave; ++w) r = fmaxf(r, smem[w][which]);
         QMeta* meta = which ? meta_col : meta_row;
-        const uint32_t slot = (blockIdx.x + blockIdx.y * gridDim.x) % kAmaxSlots;
+        const uint32_t slot = block_id % kAmaxSlots;
         uint32_t* target = &meta->amax[slot * kAmaxSlotStride];
         const uint32_t bits = __float_as_uint(r);
         if (bits > __hip_atomic_load(target, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT))
@@ -252,28 +252,10 @@ __device__ __forceinline__ void block_atomic_max2(float m_row, float m_col, QMet
     }
 }
 
-// Wave w of a workgroup owns the tile at columns [64*wc, 64*wc + 64) of the
-// workgroup's strip and rows [64*wr, 64*wr + 64), (wc, wr) = (w % WC, w / WC).
-// One tile per wave and no register prefetch: what hides the memory latency is
-// the number of resident waves, and a second tile in registers halves it
-// (measured: 67 us against 85 us for pass 1 of a 65536 x 1152 tensor).
-template <bool QUANT, bool ST_ROW, bool ST_COL>
-__global__ __launch_bounds__(kThreads) void fwht_dual_kernel(DualArgs q, int WC)
+// ---- the two phases of a tile, shared by the two-launch and the one-launch kernels
+
+__device__ __forceinline__ void dual_setup(DualCtx& x, const DualArgs& q, int lane)
 {
-    __shared__ float red[kThreads / kWave][2];
-
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const int wc = wave % WC, wr = wave / WC, WR = 4 / WC;
-    // pass 2 walks the tensor from its end to its start: it begins with what pass 1
-    // read last, which is most likely still in the memory-side cache
-    const int64_t by = QUANT ? (gridDim.y - 1 - blockIdx.y) : blockIdx.y;
-    const int64_t bx = QUANT ? (gridDim.x - 1 - blockIdx.x) : blockIdx.x;
-    const int64_t col0 = (bx * WC + wc) * kTile;
-    const int64_t row0 = (by * WR + wr) * kTile;
-    // rows % 64 == cols % 64 == 0: a tile is entirely inside the tensor or entirely outside
-    const bool live = col0 < q.cols && row0 < q.rows;
-
-    DualCtx x;
     x.q = &q;
     x.cg = lane & 7;
     x.rg = lane >> 3;
@@ -286,47 +268,135 @@ __global__ __launch_bounds__(kThreads) void fwht_dual_kernel(DualArgs q, int WC)
     x.qmax_row = (float)((1 << (q.b_row - 1)) - 1);
     x.qmin_col = (float)(-(1 << (q.b_col - 1)));
     x.qmax_col = (float)((1 << (q.b_col - 1)) - 1);
+}
 
+// reciprocal steps (with the lane's accumulated signs) from the two scalings;
+// one thread of the grid publishes the scales
+__device__ __forceinline__ void dual_set_scaling(DualCtx& x, const DualArgs& q, const Scaling& s_row,
+                                                 const Scaling& s_col, bool publisher)
+{
+    // signs accumulated by the stage_fma8 stages that actually run
+    float sg_row = 1.0f;
+    if (q.log2n_row >= 3) sg_row *= x.c1;
+    if (q.log2n_row >= 4) sg_row *= x.c2;
+    if (q.log2n_row >= 5) sg_row *= x.c4;
+    x.inv_row = s_row.inv * sg_row;
+    x.inv_col = q.log2n_col > 3 ? s_col.inv * x.c8 : s_col.inv;
+    if (publisher && threadIdx.x == 0) {
+        q.meta_row->scale = s_row.scale;
+        q.meta_col->scale = s_col.scale;
+        if (q.scale_row_out) *q.scale_row_out = s_row.scale;
+        if (q.scale_col_out) *q.scale_col_out = s_col.scale;
+    }
+}
+
+// both maxima of a tile; `t` is spent afterwards
+__device__ __forceinline__ void dual_absmax(Tile& t, const DualCtx& x, int64_t row0, int64_t col0,
+                                            float& amax_row, float& amax_col)
+{
+    const DualArgs& q = *x.q;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) row_line<false, false>(t, i, x, row0, col0, amax_row);
+    if (q.log2n_col > 5) {
+        amax_col = fmaxf(amax_col, col_transform<true>(t, q.log2n_col, x.c8));
+    } else {
+        col_transform<false>(t, q.log2n_col, x.c8);
+#pragma unroll
+        for (int h = 0; h < 2; ++h)
+#pragma unroll
+            for (int j = 0; j < 4; ++j)
+#pragma unroll
+                for (int i = 0; i < 8; ++i) amax_col = fmaxf(amax_col, fabsf(t.v[h][j][i]));
+    }
+}
+
+// both code sets of a tile; `t` is spent afterwards
+template <bool ST_ROW, bool ST_COL>
+__device__ __forceinline__ void dual_codes(Tile& t, const DualCtx& x, int64_t row0, int64_t col0)
+{
+    float unused = 0.0f;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) row_line<true, ST_ROW>(t, i, x, row0, col0, unused);
+    col_transform<false>(t, x.q->log2n_col, x.c8);
+    col_codes<ST_COL>(t, x, row0, col0);
+}
+
+// One launch covers up to kMaxBatch tensors: the workgroups of tensor k are
+// [first[k], first[k+1]) of a one-dimensional grid, numbered along its columns first.
+// Small tensors (a layer's weights) ride along with a large one instead of paying
+// for a launch of their own.
+struct DualBatch {
+    DualArgs t[kMaxDualBatch];
+    int n;
+    int first[kMaxDualBatch + 1];
+    int gx[kMaxDualBatch];       // workgroups along the columns
+    int WC[kMaxDualBatch];       // waves side by side in a workgroup (1, 2 or 4)
+};
+
+// Wave w of a workgroup owns the tile at columns [64*wc, 64*wc + 64) of the
+// workgroup's strip and rows [64*wr, 64*wr + 64), (wc, wr) = (w % WC, w / WC).
+// One tile per wave and no register prefetch: what hides the memory latency is
+// the number of resident waves, and a second tile in registers halves it
+// (measured: 67 us against 85 us for pass 1 of a 65536 x 1152 tensor).
+template <bool QUANT, bool ST_ROW, bool ST_COL>
+__global__ __launch_bounds__(kThreads) void fwht_dual_kernel(DualBatch b)
+{
+    __shared__ float red[kThreads / kWave][2];
+
+    int k = 0;
+    while (k + 1 < b.n && (int)blockIdx.x >= b.first[k + 1]) ++k;
+    const DualArgs& q = b.t[k];
+    const int count = b.first[k + 1] - b.first[k];
+    // pass 2 walks a tensor from its end to its start: it begins with what pass 1
+    // read last, which is most likely still in the memory-side cache
+    int local = (int)blockIdx.x - b.first[k];
+    if (QUANT) local = count - 1 - local;
+    const int gx = b.gx[k], WC = b.WC[k];
+    const int64_t by = local / gx, bx = local - (local / gx) * gx;
+
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int wc = wave % WC, wr = wave / WC, WR = 4 / WC;
+    const int64_t col0 = (bx * WC + wc) * kTile;
+    const int64_t row0 = (by * WR + wr) * kTile;
+    // rows % 64 == cols % 64 == 0: a tile is entirely inside the tensor or entirely outside
+    const bool live = col0 < q.cols && row0 < q.rows;
+
+    DualCtx x;
+    dual_setup(x, q, lane);
     Tile t;
     if (live) tile_load(t, q, x, row0, col0);
     if (QUANT) {
         const Scaling s_row = load_scaling(q.meta_row, q.clip_row, q.b_row);
         const Scaling s_col = load_scaling(q.meta_col, q.clip_col, q.b_col);
-        // signs accumulated by the stage_fma stages that actually run
-        float sg_row = 1.0f;
-        if (q.log2n_row >= 3) sg_row *= x.c1;
-        if (q.log2n_row >= 4) sg_row *= x.c2;
-        if (q.log2n_row >= 5) sg_row *= x.c4;
-        x.inv_row = s_row.inv * sg_row;
-        x.inv_col = q.log2n_col > 3 ? s_col.inv * x.c8 : s_col.inv;
-        if (blockIdx.x == 0 && blockIdx.y == 0 && threadIdx.x == 0) {
-            q.meta_row->scale = s_row.scale;
-            q.meta_col->scale = s_col.scale;
-            if (q.scale_row_out) *q.scale_row_out = s_row.scale;
-            if (q.scale_col_out) *q.scale_col_out = s_col.scale;
-        }
+        dual_set_scaling(x, q, s_row, s_col, local == 0);
+        if (live) dual_codes<ST_ROW, ST_COL>(t, x, row0, col0);
+    } else {
+        float amax_row = 0.0f, amax_col = 0.0f;
+        if (live) dual_absmax(t, x, row0, col0, amax_row, amax_col);
+        block_atomic_max2(amax_row, amax_col, q.meta_row, q.meta_col, red, (uint32_t)local);
     }
-    float amax_row = 0.0f, amax_col = 0.0f;
-    if (live) {
-#pragma unroll
-        for (int i = 0; i < 8; ++i) row_line<QUANT, ST_ROW>(t, i, x, row0, col0, amax_row);
-        if (!QUANT && q.log2n_col > 5) {
-            amax_col = col_transform<true>(t, q.log2n_col, x.c8);
-        } else {
-            col_transform<false>(t, q.log2n_col, x.c8);
-            if (!QUANT) {
-#pragma unroll
-                for (int h = 0; h < 2; ++h)
-#pragma unroll
-                    for (int j = 0; j < 4; ++j)
-#pragma unroll
-                        for (int i = 0; i < 8; ++i) amax_col = fmaxf(amax_col, fabsf(t.v[h][j][i]));
-            } else {
-                col_codes<ST_COL>(t, x, row0, col0);
-            }
-        }
+}
+
+bool make_batch(const DualArgs* qs, int n, DualBatch* b)
+{
+    if (n < 1 || n > kMaxDualBatch) return false;
+    b->n = n;
+    int64_t total = 0;
+    for (int k = 0; k < n; ++k) {
+        const DualArgs& q = qs[k];
+        const int64_t strips = q.cols / kTile;
+        const int WC = (strips % 4 == 0) ? 4 : (strips % 2 == 0) ? 2 : 1;
+        const int64_t tall = (int64_t)kTile * (4 / WC);
+        const int64_t gx = strips / WC, gy = (q.rows + tall - 1) / tall;
+        b->t[k] = q;
+        b->first[k] = (int)total;
+        b->gx[k] = (int)gx;
+        b->WC[k] = WC;
+        total += gx * gy;
+        if (total >= ((int64_t)1 << 31)) return false;
     }
-    if (!QUANT) block_atomic_max2(amax_row, amax_col, q.meta_row, q.meta_col, red);
+    b->first[n] = (int)total;
+    return true;
 }
 
 } // namespace
@@ -334,31 +404,53 @@ __global__ __launch_bounds__(kThreads) void fwht_dual_kernel(DualArgs q, int WC)
 bool quantize_dual_eligible(const DualArgs& q)
 {
     return (q.rows % kTile == 0) && (q.cols % kTile == 0) && q.log2n_row <= 6 && q.log2n_col <= 6 &&
-           q.b_row <= 4 && q.b_col <= 4 && q.rows / kTile < 65535;
+           q.b_row <= 4 && q.b_col <= 4 && (q.rows / kTile) * (q.cols / kTile) < ((int64_t)1 << 30);
 }
 
-// Pass 1 and pass 2; both calibration records must be zero.
+// Pass 1 (both maxima) of n tensors in one launch; their calibration records must be zero.
+hipError_t launch_dual_pass1(const DualArgs* qs, int n, hipStream_t stream)
+{
+    DualBatch b;
+    if (!make_batch(qs, n, &b)) return hipErrorInvalidValue;
+    const int id = n > 1 ? K_DUAL_ABSMAX_BATCH
+                         : (qs[0].profile_tag ? K_DUAL_ABSMAX_X + (qs[0].profile_tag - 1) : K_DUAL_ABSMAX);
+    ProfileScope ps(id, stream);
+    hipLaunchKernelGGL((fwht_dual_kernel<false, false, false>), dim3((unsigned)b.first[n]), dim3(kThreads), 0,
+                       stream, b);
+    return hipGetLastError();
+}
+
+// Pass 2 (both code sets) of n tensors in one launch; the tensors of a launch share
+// their rounding modes (those select the kernel instance).
+hipError_t launch_dual_pass2(const DualArgs* qs, int n, hipStream_t stream)
+{
+    DualBatch b;
+    if (!make_batch(qs, n, &b)) return hipErrorInvalidValue;
+    for (int k = 1; k < n; ++k)
+        if (qs[k].st_row != qs[0].st_row || qs[k].st_col != qs[0].st_col) return hipErrorInvalidValue;
+    const int id = n > 1 ? K_DUAL_QUANT_BATCH
+                         : (qs[0].profile_tag ? K_DUAL_QUANT_X + (qs[0].profile_tag - 1) : K_DUAL_QUANT);
+    ProfileScope ps(id, stream);
+    const dim3 grid((unsigned)b.first[n]), block(kThreads);
+    if (qs[0].st_row && qs[0].st_col)
+        hipLaunchKernelGGL((fwht_dual_kernel<true, true, true>), grid, block, 0, stream, b);
+    else if (qs[0].st_row)
+        hipLaunchKernelGGL((fwht_dual_kernel<true, true, false>), grid, block, 0, stream, b);
+    else if (qs[0].st_col)
+        hipLaunchKernelGGL((fwht_dual_kernel<true, false, true>), grid, block, 0, stream, b);
+    else
+        hipLaunchKernelGGL((fwht_dual_kernel<true, false, false>), grid, block, 0, stream, b);
+    return hipGetLastError();
+}
+
+// Pass 1 and pass 2 of one tensor.  (A one-launch variant for small tensors -- tile
+// kept in registers across a grid-wide barrier -- was built and measured: correct,
+// but the cooperative launch it needs for a guaranteed co-resident grid costs about
+// 25 us more than an ordinary launch on this stack, more than the launch it saves.)
 hipError_t launch_quantize_dual(const DualArgs& q, hipStream_t stream)
 {
-    const int64_t strips = q.cols / kTile;
-    const int WC = (strips % 4 == 0) ? 4 : (strips % 2 == 0) ? 2 : 1;
-    const int WR = 4 / WC;
-    const int64_t tall = (int64_t)kTile * WR;
-    const dim3 grid((unsigned)(strips / WC), (unsigned)((q.rows + tall - 1) / tall));
-    {
-        ProfileScope ps(q.profile_tag ? K_DUAL_ABSMAX_X + (q.profile_tag - 1) : K_DUAL_ABSMAX, stream);
-        hipLaunchKernelGGL((fwht_dual_kernel<false, false, false>), grid, dim3(kThreads), 0, stream, q, WC);
-    }
-    ProfileScope ps(q.profile_tag ? K_DUAL_QUANT_X + (q.profile_tag - 1) : K_DUAL_QUANT, stream);
-    if (q.st_row && q.st_col)
-        hipLaunchKernelGGL((fwht_dual_kernel<true, true, true>), grid, dim3(kThreads), 0, stream, q, WC);
-    else if (q.st_row)
-        hipLaunchKernelGGL((fwht_dual_kernel<true, true, false>), grid, dim3(kThreads), 0, stream, q, WC);
-    else if (q.st_col)
-        hipLaunchKernelGGL((fwht_dual_kernel<true, false, true>), grid, dim3(kThreads), 0, stream, q, WC);
-    else
-        hipLaunchKernelGGL((fwht_dual_kernel<true, false, false>), grid, dim3(kThreads), 0, stream, q, WC);
-    return hipGetLastError();
+    const hipError_t e = launch_dual_pass1(&q, 1, stream);
+    return e != hipSuccess ? e : launch_dual_pass2(&q, 1, stream);
 }
 
 } // namespace hdqt
