@@ -64,18 +64,26 @@ __device__ __forceinline__ void tile_load(Tile& t, const DualArgs& q, const Dual
         }
 }
 
-// The two 32-bit words of random bits that cover the lane's four consecutive
-// elements e .. e+3 (e % 4 == 0): they lie in one Philox block, in its words
-// (e % 8) / 2 and (e % 8) / 2 + 1.
-__device__ __forceinline__ void random_pair(int64_t e, uint32_t tensor_id, uint32_t k0, uint32_t k1,
-                                            uint32_t w01[2])
+// Random bits of stochastic rounding for the lane's elements of one tile row: four
+// consecutive elements at h = 0 (index e, e % 4 == 0) and four at h = 1 (index
+// e + 32).  Each group lies in one Philox block (block e/8, words (e%8)/2 and
+// (e%8)/2 + 1), and lanes cg and cg ^ 1 need the same two blocks, the even lane the
+// lower words, the odd lane the upper ones.  So the even lane computes the block of
+// h = 0, the odd lane that of h = 1, and they trade the halves the other needs:
+// one Philox call per lane and row instead of two.
+__device__ __forceinline__ void random_words(int64_t e, bool odd, uint32_t tensor_id, uint32_t k0,
+                                             uint32_t k1, uint32_t w_h0[2], uint32_t w_h1[2])
 {
-    const uint64_t blk = (uint64_t)e >> 3;
-    uint32_t rnd[4];
-    philox4x32_10((uint32_t)blk, (uint32_t)(blk >> 32), tensor_id, 0u, k0, k1, rnd);
-    const bool upper = (e & 4) != 0;
-    w01[0] = upper ? rnd[2] : rnd[0];
-    w01[1] = upper ? rnd[3] : rnd[1];
+    const uint64_t blk = ((uint64_t)e >> 3) + (odd ? 4u : 0u);
+    uint32_t r[4];
+    philox4x32_10((uint32_t)blk, (uint32_t)(blk >> 32), tensor_id, 0u, k0, k1, r);
+    const uint32_t send0 = odd ? r[0] : r[2], send1 = odd ? r[1] : r[3];
+    const uint32_t recv0 = __float_as_uint(lane_xor<1>(__uint_as_float(send0)));
+    const uint32_t recv1 = __float_as_uint(lane_xor<1>(__uint_as_float(send1)));
+    w_h0[0] = odd ? recv0 : r[0];
+    w_h0[1] = odd ? recv1 : r[1];
+    w_h1[0] = odd ? r[2] : recv0;
+    w_h1[1] = odd ? r[3] : recv1;
 }
 
 // Axis 1 for the lane's row 8*rg + i of the tile: transform, then absmax (pass
@@ -140,11 +148,13 @@ __device__ __forceinline__ void row_line(const Tile& t, int i, const DualCtx& x,
     const int64_t row = row0 + x.rg * 8 + i;
     const float magic = kMagic + 8.0f;
     uint32_t both = 0;       // the lane's eight codes: low half h = 0, high half h = 1
+    uint32_t rnd[2][2] = {{0u, 0u}, {0u, 0u}};
+    if (STOCH)
+        random_words(row * q.cols + col0 + x.cg * 4, (x.cg & 1) != 0, q.tid_row, q.seed_row_lo,
+                     q.seed_row_hi, rnd[0], rnd[1]);
 #pragma unroll
     for (int h = 0; h < 2; ++h) {
-        uint32_t w01[2] = {0u, 0u};
-        if (STOCH)
-            random_pair(row * q.cols + col0 + 32 * h + x.cg * 4, q.tid_row, q.seed_row_lo, q.seed_row_hi, w01);
+        const uint32_t* w01 = rnd[h];
         // 0x4B400000 << 4j has no bits in the low 16: the low half of the sum is the
         // four offset nibbles
         uint32_t acc = 0;
@@ -205,29 +215,30 @@ __device__ __forceinline__ void col_codes(const Tile& t, const DualCtx& x, int64
     const DualArgs& q = *x.q;
     const float magic = kMagic + 8.0f;
     const int64_t pitch = q.rows >> 1;
+    uint32_t cw[2][4][8];
 #pragma unroll
-    for (int h = 0; h < 2; ++h) {
-        uint32_t cw[4][8];
+    for (int i = 0; i < 8; ++i) {
+        uint32_t rnd[2][2] = {{0u, 0u}, {0u, 0u}};
+        if (STOCH)
+            random_words((row0 + x.rg * 8 + i) * q.cols + col0 + x.cg * 4, (x.cg & 1) != 0, q.tid_col,
+                         q.seed_col_lo, q.seed_col_hi, rnd[0], rnd[1]);
 #pragma unroll
-        for (int i = 0; i < 8; ++i) {
-            uint32_t w01[2] = {0u, 0u};
-            if (STOCH)
-                random_pair((row0 + x.rg * 8 + i) * q.cols + col0 + 32 * h + x.cg * 4, q.tid_col,
-                            q.seed_col_lo, q.seed_col_hi, w01);
+        for (int h = 0; h < 2; ++h)
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
-                const uint32_t u = (w01[j >> 1] >> (16 * (j & 1))) & 0xFFFFu;
-                cw[j][i] = code_word<STOCH>(t.v[h][j][i], x.inv_col, x.qmin_col, x.qmax_col, magic, u);
+                const uint32_t u = (rnd[h][j >> 1] >> (16 * (j & 1))) & 0xFFFFu;
+                cw[h][j][i] = code_word<STOCH>(t.v[h][j][i], x.inv_col, x.qmin_col, x.qmax_col, magic, u);
             }
-        }
-        // column 32h + 4cg + j, rows 8rg .. 8rg+7: one dword; the eight rg lanes of a
-        // column write 32 consecutive bytes
+    }
+    // column 32h + 4cg + j, rows 8rg .. 8rg+7: one dword; the eight rg lanes of a
+    // column write 32 consecutive bytes
+#pragma unroll
+    for (int h = 0; h < 2; ++h)
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
             uint8_t* dst = q.codes_col + (col0 + 32 * h + x.cg * 4 + j) * pitch + (row0 >> 1) + x.rg * 4;
-            *reinterpret_cast<uint32_t*>(dst) = pack_nibbles(cw[j]);
+            *reinterpret_cast<uint32_t*>(dst) = pack_nibbles(cw[h][j]);
         }
-    }
 }
 
 // One atomicMax per workgroup and record (see block_atomic_max in common.hpp).
