@@ -92,3 +92,31 @@ class HdqtLinear(torch.nn.Module):
         if self.bias is not None:
             z = z + self.bias
         return z.reshape(*lead, -1)
+
+
+class HdqtConv2d(torch.nn.Module):
+    """3x3-style convolution (stride 1) as the paper runs it: the activation is unfolded
+    (im2col, column index = channel * kh * kw + tap) and the products of the forward and
+    the backward pass are the quantized matmuls above.  The unfolding and folding are
+    PyTorch's; only the matmuls are the library's."""
+
+    def __init__(self, in_channels: int, out_channels: int, kernel_size: int = 3, padding: int = 1,
+                 cfg: Optional[LayerConfig] = None, device=None):
+        super().__init__()
+        self.k, self.pad = kernel_size, padding
+        self.cfg = cfg or LayerConfig()
+        fan_in = in_channels * kernel_size * kernel_size
+        w = torch.empty(fan_in, out_channels, device=device)
+        torch.nn.init.kaiming_normal_(w.t(), nonlinearity="relu")
+        self.weight = torch.nn.Parameter(w)
+        self.step = 0
+
+    def forward(self, x):
+        Bn, Cin, H, W = x.shape
+        Ho, Wo = H + 2 * self.pad - self.k + 1, W + 2 * self.pad - self.k + 1
+        cols = torch.nn.functional.unfold(x, kernel_size=self.k, padding=self.pad)   # [B, C*k*k, Ho*Wo]
+        X = cols.transpose(1, 2).reshape(Bn * Ho * Wo, Cin * self.k * self.k)
+        Z = HdqtMatmul.apply(X, self.weight, self.cfg, self.step)
+        if self.training:
+            self.step += 1
+        return Z.reshape(Bn, Ho * Wo, -1).transpose(1, 2).reshape(Bn, -1, Ho, Wo)

@@ -128,3 +128,53 @@ def test_training_reduces_the_loss():
         losses.append(loss.item())
     print("loss", losses[0], "->", losses[-1], flush=True)
     assert losses[-1] < 0.5 * losses[0]
+
+
+def test_conv_block_trains_and_matches_oracle():
+    """A small ResNet-style stack (conv 3x3 - ReLU - conv 3x3 - pool - linear) on 16x16
+    inputs: the first convolution's three matmuls against the oracle on the operands
+    autograd actually passed, and a few SGD steps that must reduce the loss."""
+    torch.manual_seed(2)
+    conv1 = A.HdqtConv2d(8, 16, cfg=A.LayerConfig(layer_id=0, seed=9), device="cuda:0")
+    conv2 = A.HdqtConv2d(16, 32, cfg=A.LayerConfig(layer_id=1, seed=9), device="cuda:0")
+    head = A.HdqtLinear(32, 10, cfg=A.LayerConfig(layer_id=2, seed=9), device="cuda:0")
+    params = list(conv1.parameters()) + list(conv2.parameters()) + list(head.parameters())
+    x = torch.randn(16, 8, 16, 16, device="cuda:0")
+    y = torch.randint(0, 10, (16,), device="cuda:0")
+
+    def forward(inp):
+        h = torch.relu(conv1(inp))
+        h = torch.relu(conv2(h))
+        return head(h.mean(dim=(2, 3)))
+
+    # ---- one step with the first convolution's operands captured
+    captured = {}
+    orig_apply = A.HdqtMatmul.apply
+
+    xin = x.clone().requires_grad_(True)
+    cols = torch.nn.functional.unfold(xin, kernel_size=3, padding=1).transpose(1, 2).reshape(16 * 256, 72)
+    cols.retain_grad()
+    Z = orig_apply(cols, conv1.weight, conv1.cfg, 0)
+    Z.retain_grad()
+    h = torch.relu(Z.reshape(16, 256, 16).transpose(1, 2).reshape(16, 16, 16, 16))
+    h = torch.relu(conv2(h))
+    loss = torch.nn.functional.cross_entropy(head(h.mean(dim=(2, 3))), y)
+    loss.backward()
+    torch.cuda.synchronize()
+    M, K, N = 16 * 256, 72, 16
+    cfg, W = conv1.cfg, conv1.weight.detach()
+    assert_matches_oracle(FWD, cols.detach(), W, M, K, N, cfg.params(FWD, 0), Z)
+    assert_matches_oracle(BWW, cols.detach(), Z.grad, M, K, N, cfg.params(BWW, 0), conv1.weight.grad)
+    assert_matches_oracle(BWI, Z.grad, W, M, K, N, cfg.params(BWI, 0), cols.grad)
+
+    # ---- a few optimisation steps
+    opt = torch.optim.SGD(params, lr=0.05, momentum=0.9)
+    losses = []
+    for _ in range(60):
+        opt.zero_grad()
+        loss = torch.nn.functional.cross_entropy(forward(x), y)
+        loss.backward()
+        opt.step()
+        losses.append(loss.item())
+    print("loss", losses[0], "->", losses[-1], flush=True)
+    assert losses[-1] < 0.85 * losses[0]
