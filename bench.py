@@ -104,6 +104,9 @@ def main():
     ap.add_argument("--acc-bits", type=int, default=8)
     ap.add_argument("--cpu-rows", type=int, default=65536, help="rows of the oracle's sample")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--graph", action="store_true",
+                    help="capture one step into a HIP graph and time its replays (measured: no faster than "
+                         "launching from the host, the step is bound by its kernels)")
     ap.add_argument("--separate", action="store_true",
                     help="run the step as the three per-matmul entry points instead of hdqt_layer_step")
     ap.add_argument("--calib-copy", action="store_true",
@@ -127,7 +130,6 @@ def main():
     prm = {k: step_params(B, k, n, args.s, args.acc_bits) for k in kinds}
     srcs = {B.GEMM_FWD: (X, W), B.GEMM_BWD_INPUT: (G, W), B.GEMM_BWD_WEIGHT: (X, G)}
     outs = {k: torch.empty(B.out_shape(k, M, K, N), dtype=torch.float32, device=dev) for k in kinds}
-    stream = torch.cuda.current_stream()
     if args.separate:
         ws_bytes = max(B.workspace_size(k, M, K, N, prm[k]) for k in kinds)
     else:
@@ -136,14 +138,39 @@ def main():
     step_out = tuple(outs[k] for k in kinds)
 
     def step():
+        # (enqueued on torch's current stream: the capture stream while a graph is recorded)
         if args.separate:
             for k in kinds:
-                B.gemm(k, srcs[k][0], srcs[k][1], M, K, N, prm[k], out=outs[k], workspace=ws, stream=stream)
+                B.gemm(k, srcs[k][0], srcs[k][1], M, K, N, prm[k], out=outs[k], workspace=ws)
         else:
             # Z, dX, dW bit-identical to the three calls above; X and G are read once
             # per quantization pass for both of their Hadamard domains
             B.layer_step(X, W, G, prm[kinds[0]], prm[kinds[1]], prm[kinds[2]], out=step_out,
-                         workspace=ws, stream=stream)
+                         workspace=ws)
+
+    # One step is a fixed sequence of kernel launches (no host decisions, no memsets, no
+    # allocation), so it can be captured once into a HIP graph and replayed; the replayed
+    # step must reproduce the eagerly launched one bit for bit.
+    run, launch = step, "eager"
+    if args.graph:
+        step()
+        torch.cuda.synchronize()
+        eager = [o.clone() for o in step_out]
+        try:
+            graph = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(graph):
+                step()
+            for _ in range(2):
+                for o in step_out:
+                    o.fill_(float("nan"))
+                graph.replay()
+                torch.cuda.synchronize()
+                assert all(torch.equal(o, e) for o, e in zip(step_out, eager)), "graph replay differs"
+            run, launch = graph.replay, "hip graph replay"
+        except Exception as exc:            # capture unsupported: keep launching from the host
+            print(f"bench.py: graph capture failed ({exc}); launching eagerly", file=sys.stderr)
+            torch.cuda.synchronize()
+        del eager
 
     if args.calib_copy:
         a = torch.empty(256 << 20, dtype=torch.uint8, device=dev)
@@ -154,11 +181,11 @@ def main():
 
     # ---- timed region: K steps, no instrumentation
     for _ in range(args.warmup):
-        step()
+        run()
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for _ in range(args.steps):
-        step()
+        run()
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
 
@@ -245,6 +272,7 @@ def main():
         "config": {"workload": f"{args.workload}: {layer.name} (M={M}, K={K}, N={N}), one training "
                                f"step = fwd + bwd_input + bwd_weight",
                    "entry": "3 x hdqt_gemm_*" if args.separate else "hdqt_layer_step",
+                   "launch": launch,
                    "had_block": n, "input_bits": 4, "acc_bits": args.acc_bits, "s": args.s,
                    "rounding": "G stochastic, X and W nearest"},
         "roofline": roofline,

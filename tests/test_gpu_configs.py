@@ -246,3 +246,30 @@ def test_layer_step_resnet_conv_k1152():
         Z, dX, dW, ws = B.layer_step(X, W, G, pf, pi, pw, workspace=ws)
         torch.cuda.synchronize()
         assert torch.equal(Z, Z3) and torch.equal(dX, dX3) and torch.equal(dW, dW3)
+
+
+def test_layer_step_in_a_hip_graph():
+    """The step is a fixed sequence of kernel launches: captured into a HIP graph and
+    replayed several times, with eager work and synchronisation in between, every
+    replay must reproduce the eagerly launched step bit for bit."""
+    layer = workloads.resnet_conv_layer(32, 128, 128, 16, seed=1)        # M=8192, K=1152, N=128
+    M, K, N = layer.M, layer.K, layer.N
+    X, W, G = dev(layer.X), dev(layer.W), dev(layer.G)
+    pf, pi, pw = _step_params(64, 32, 8, seed=5)
+    Z0, dX0, dW0, _ = B.layer_step(X, W, G, pf, pi, pw)
+    torch.cuda.synchronize()
+    out = tuple(torch.empty_like(t) for t in (Z0, dX0, dW0))
+    ws = torch.empty(B.layer_step_workspace_size(M, K, N, pf, pi, pw), dtype=torch.uint8, device="cuda:0")
+    B.layer_step(X, W, G, pf, pi, pw, out=out, workspace=ws)               # warm-up outside the capture
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        B.layer_step(X, W, G, pf, pi, pw, out=out, workspace=ws)
+    for rep in range(4):
+        for o in out:
+            o.fill_(float("nan"))
+        ws.random_(0, 255)                      # the workspace's contents are undefined on entry
+        _ = (X * 2.0).sum().item()              # unrelated eager work and a synchronisation
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(out[0], Z0) and torch.equal(out[1], dX0) and torch.equal(out[2], dW0), rep
