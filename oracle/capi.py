@@ -173,6 +173,31 @@ def tiled_matmul_sampled(qA, qB, s: int, a: int, ii, jj) -> np.ndarray:
     return acc
 
 
+def tiled_matmul_requant(qA, qB, s: int, a: int):
+    """Second reading of the accumulator -> (acc int64 [RA, RB], tile_max int32 [tiles]);
+    value = acc / 2^(a-1)."""
+    qA = np.ascontiguousarray(qA, dtype=np.int8)
+    qB = np.ascontiguousarray(qB, dtype=np.int8)
+    RA, D = qA.shape
+    RB, D2 = qB.shape
+    assert D == D2
+    tiles = (D + s - 1) // s
+    acc = np.empty((RA, RB), dtype=np.int64)
+    tmax = np.empty(tiles, dtype=np.int32)
+    lib().orc_tiled_matmul_requant(_p(qA, C.c_int8), _p(qB, C.c_int8), C.c_int64(RA), C.c_int64(RB),
+                                   C.c_int64(D), C.c_int64(s), C.c_int(a), _p(acc, C.c_int64),
+                                   _p(tmax, C.c_int32))
+    return acc, tmax
+
+
+def dequantize_requant(acc, scaleA, scaleB, n: int, a: int) -> np.ndarray:
+    acc = np.ascontiguousarray(acc, dtype=np.int64)
+    out = np.empty(acc.shape, dtype=np.float32)
+    lib().orc_dequantize_requant(_p(acc, C.c_int64), C.c_int64(acc.size), C.c_float(scaleA),
+                                 C.c_float(scaleB), C.c_int(n), C.c_int(a), _p(out, C.c_float))
+    return out
+
+
 def dequant_factor(scaleA, scaleB, n: int) -> np.float32:
     return np.float32(lib().orc_dequant_factor(C.c_float(scaleA), C.c_float(scaleB), n))
 

@@ -119,3 +119,36 @@ def tiled_matmul(qA: np.ndarray, qB: np.ndarray, s: int, a: int) -> np.ndarray:
 def dequantize(acc: np.ndarray, scaleA, scaleB, n: int) -> np.ndarray:
     dq = F(F(F(scaleA) * F(scaleB)) * F(1.0 / n))
     return (acc.astype(F) * dq).astype(F)
+
+
+def tiled_matmul_requant(qA: np.ndarray, qB: np.ndarray, s: int, a: int):
+    """Second reading of the low-bit accumulator (Methodology, tiled quantization): every
+    tile's partial-sum tensor is quantized to a bits with its own max and the tile results
+    are added.  Pure Python over tiles and elements; exact rational arithmetic decides the
+    rounding wherever binary32 cannot be trusted to show it.
+    -> (acc as Python ints [RA][RB] with value acc / 2^(a-1), [m_t])."""
+    from fractions import Fraction
+    RA, D = qA.shape
+    RB = qB.shape[0]
+    qmax, qmin = (1 << (a - 1)) - 1, -(1 << (a - 1))
+    acc = [[0] * RB for _ in range(RA)]
+    maxima = []
+    for t0 in range(0, D, s):
+        t1 = min(t0 + s, D)
+        P = [[sum(int(qA[i, d]) * int(qB[j, d]) for d in range(t0, t1)) for j in range(RB)] for i in range(RA)]
+        m = max(abs(v) for row in P for v in row)
+        maxima.append(m)
+        if m == 0:
+            continue
+        inv = np.float32(np.float64(1 << (a - 1)) / np.float64(m))      # one correctly rounded division
+        for i in range(RA):
+            for j in range(RB):
+                v = np.float32(np.float32(P[i][j]) * inv)                # one binary32 multiplication
+                # nearest integer, ties to even, decided exactly on the binary32 value v
+                f = Fraction(float(v))
+                lo = f.numerator // f.denominator
+                frac = f - lo
+                c = lo if frac < Fraction(1, 2) else lo + 1 if frac > Fraction(1, 2) else lo + (lo & 1)
+                c = max(qmin, min(qmax, c))
+                acc[i][j] += c * m
+    return acc, maxima

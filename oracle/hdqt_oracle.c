@@ -30,6 +30,10 @@
  * the code is one multiplication and one rounding.  Build with
  * -ffp-contract=off so that no fused multiply-add replaces these.
  *
+ *   5'. second reading of step 5 (orc_tiled_matmul_requant): every tile's
+ *                     partial-sum tensor goes through Q with a bits and its own
+ *                     max, and the tile results are added
+ *
  * Parity pins live in tests/ (H H^T = n I, scipy's Hadamard matrix, fp64
  * transform, grid inputs with known codes, hand-computed saturation cases,
  * exact int64 matmul when nothing saturates, an independent Philox engine).
@@ -358,6 +362,74 @@ void orc_dequantize(const int32_t *acc, int64_t count, float scaleA, float scale
                     float *out)
 {
     float dq = orc_dequant_factor(scaleA, scaleB, n_eff);
+    for (int64_t p = 0; p < count; ++p)
+        out[p] = (float)acc[p] * dq;
+}
+
+/* ------------------------------------------------------------------ */
+/* Second reading of the low-bit accumulator: tiled quantization        */
+/* ------------------------------------------------------------------ */
+
+/* Methodology, "tiled quantization ... limiting computations to tiles of size s",
+ * read through the paper's own emulation device, the quantizer Q: the partial-sum
+ * tensor of every tile t,
+ *     P_t[i,j] = sum_{d in tile t} qA[i,d] qB[j,d]        (exact integers),
+ * is passed through Q with a bits and its own max calibration, and the tile
+ * results are added:
+ *     m_t      = max_{i,j} |P_t[i,j]|                      (over the whole tensor)
+ *     inv_t    = fl(2^(a-1) / m_t)                         (binary32, correctly rounded)
+ *     c_t[i,j] = clamp(RNE(fl(float(P_t[i,j]) * inv_t)), -2^(a-1), 2^(a-1) - 1)
+ *     acc[i,j] = sum_t c_t[i,j] * m_t                      (exact; value = acc / 2^(a-1))
+ * A tile whose partial sums are all zero contributes nothing.  Same conventions as
+ * the operand quantizer above (scale by 2^(b-1), two's-complement clamp, nearest-even).
+ * tile_max (nullable) receives m_t for every tile. */
+void orc_tiled_matmul_requant(const int8_t *qA, const int8_t *qB, int64_t RA, int64_t RB,
+                              int64_t D, int64_t s, int a, int64_t *acc, int32_t *tile_max)
+{
+    int32_t *P = (int32_t *)malloc((size_t)(RA * RB) * sizeof(int32_t));
+    const int32_t qmax = (int32_t)(((int64_t)1 << (a - 1)) - 1), qmin = -qmax - 1;
+    for (int64_t p = 0; p < RA * RB; ++p) acc[p] = 0;
+    int64_t t = 0;
+    for (int64_t t0 = 0; t0 < D; t0 += s, ++t) {
+        int64_t t1 = t0 + s < D ? t0 + s : D;
+        int32_t m = 0;
+#pragma omp parallel for schedule(static) reduction(max : m)
+        for (int64_t i = 0; i < RA; ++i)
+            for (int64_t j = 0; j < RB; ++j) {
+                int32_t sum = 0;
+                for (int64_t d = t0; d < t1; ++d)
+                    sum += (int32_t)qA[i * D + d] * (int32_t)qB[j * D + d];
+                P[i * RB + j] = sum;
+                int32_t mag = sum < 0 ? -sum : sum;
+                if (mag > m) m = mag;
+            }
+        if (tile_max) tile_max[t] = m;
+        if (m == 0) continue;
+        /* a binary64 quotient of two integers below 2^31 rounds to binary32 without
+         * double-rounding error only if both are binary32 values; m < 2^24 here */
+        float inv = (float)((double)((int64_t)1 << (a - 1)) / (double)m);
+#pragma omp parallel for schedule(static)
+        for (int64_t p = 0; p < RA * RB; ++p) {
+            float v = (float)P[p] * inv;
+            float r = rintf(v); /* round half to even */
+            int32_t c = r > (float)qmax ? qmax : (r < (float)qmin ? qmin : (int32_t)r);
+            acc[p] += (int64_t)c * (int64_t)m;
+        }
+    }
+    free(P);
+}
+
+/* value = acc * 2^-(a-1) * (scaleA * scaleB) / n: the factor is the three binary32
+ * operations of orc_dequant_factor followed by an exact scaling by a power of two. */
+float orc_requant_factor(float scaleA, float scaleB, int n_eff, int a)
+{
+    return ldexpf(orc_dequant_factor(scaleA, scaleB, n_eff), -(a - 1));
+}
+
+void orc_dequantize_requant(const int64_t *acc, int64_t count, float scaleA, float scaleB,
+                            int n_eff, int a, float *out)
+{
+    float dq = orc_requant_factor(scaleA, scaleB, n_eff, a);
     for (int64_t p = 0; p < count; ++p)
         out[p] = (float)acc[p] * dq;
 }

@@ -196,3 +196,87 @@ def test_hadamard_domain_uses_levels_better_on_outliers():
                   np.linalg.norm(r["out"] - ref) / np.linalg.norm(ref))
     assert res[64][0] > res[1][0]
     assert res[64][1] < res[1][1]
+
+
+# ---------------------------------------------------------------- second reading of the accumulator
+# (Methodology, tiled quantization: every tile's partial-sum tensor through Q with a bits)
+
+def _codes(rng, rows, D, b=4):
+    return rng.integers(-(1 << (b - 1)), 1 << (b - 1), size=(rows, D)).astype(np.int8)
+
+
+def test_requant_brute_force_against_definitional():
+    rng = np.random.default_rng(11)
+    for RA, RB, D, s, a in [(5, 4, 12, 4, 8), (3, 6, 20, 8, 5), (4, 4, 7, 3, 3), (2, 2, 64, 32, 8), (6, 3, 9, 100, 12)]:
+        qA, qB = _codes(rng, RA, D), _codes(rng, RB, D)
+        acc, tmax = capi.tiled_matmul_requant(qA, qB, s, a)
+        ref, maxima = definitional.tiled_matmul_requant(qA, qB, s, a)
+        assert tmax.tolist() == maxima
+        assert acc.tolist() == ref
+
+
+def test_requant_tile_maxima_are_the_maxima_of_the_integer_products():
+    rng = np.random.default_rng(12)
+    qA, qB = _codes(rng, 17, 96), _codes(rng, 9, 96)
+    _, tmax = capi.tiled_matmul_requant(qA, qB, 32, 8)
+    for t in range(3):
+        P = qA[:, 32 * t:32 * t + 32].astype(np.int64) @ qB[:, 32 * t:32 * t + 32].astype(np.int64).T
+        assert tmax[t] == np.abs(P).max()
+
+
+def test_requant_with_power_of_two_maxima_is_the_exact_matmul():
+    """If every tile's maximum is a power of two not above 2^(a-1) and is reached only by a
+    negative partial sum, Q is the identity on that tile (the scale is a power of two, nothing
+    rounds, nothing clamps): acc / 2^(a-1) is the plain integer product."""
+    rng = np.random.default_rng(13)
+    RA, RB, s, tiles, a = 6, 5, 8, 4, 8
+    qA = rng.integers(-2, 3, size=(RA, s * tiles)).astype(np.int8)
+    qB = rng.integers(-2, 3, size=(RB, s * tiles)).astype(np.int8)
+    for t in range(tiles):          # plant the maximum: row 0 x col 0 of each tile sums to -64
+        qA[0, s * t:s * t + s] = -8
+        qB[0, s * t:s * t + s] = 1
+        qA[1:, s * t:s * t + s] = np.clip(qA[1:, s * t:s * t + s], -1, 1)
+    acc, tmax = capi.tiled_matmul_requant(qA, qB, s, a)
+    P = qA.astype(np.int64) @ qB.astype(np.int64).T
+    assert tmax.tolist() == [64] * tiles
+    assert np.array_equal(acc, P * 128)
+
+
+def test_requant_error_is_within_half_a_step_per_tile():
+    """|acc / 2^(a-1) - exact| <= sum_t m_t / 2^a, plus one step m_t / 2^(a-1) where the
+    positive maximum itself is clamped to 2^(a-1) - 1."""
+    rng = np.random.default_rng(14)
+    qA, qB = _codes(rng, 40, 256), _codes(rng, 24, 256)
+    exact = qA.astype(np.int64) @ qB.astype(np.int64).T
+    for s, a in [(32, 8), (64, 6), (16, 4), (256, 8)]:
+        acc, tmax = capi.tiled_matmul_requant(qA, qB, s, a)
+        err = np.abs(acc / float(1 << (a - 1)) - exact)
+        bound = float(np.sum(tmax.astype(np.float64)) / (1 << a) + np.sum(tmax.astype(np.float64)) / (1 << (a - 1)))
+        assert err.max() <= bound
+        # typical error is far below the bound and shrinks with the accumulator width
+        acc_wide, _ = capi.tiled_matmul_requant(qA, qB, s, a + 4)
+        assert np.abs(acc_wide / float(1 << (a + 3)) - exact).mean() < err.mean()
+
+
+def test_requant_single_tile_is_the_quantizer_on_the_product():
+    """One tile (s >= D): the reading reduces to Q_a applied to the integer product."""
+    rng = np.random.default_rng(15)
+    qA, qB = _codes(rng, 12, 48), _codes(rng, 10, 48)
+    a = 6
+    acc, tmax = capi.tiled_matmul_requant(qA, qB, 1000, a)
+    P = qA.astype(np.int64) @ qB.astype(np.int64).T
+    m = int(np.abs(P).max())
+    assert tmax.tolist() == [m]
+    inv = np.float32(np.float64(1 << (a - 1)) / np.float64(m))
+    codes = np.clip(np.rint(P.astype(np.float32) * inv), -(1 << (a - 1)), (1 << (a - 1)) - 1).astype(np.int64)
+    assert np.array_equal(acc, codes * m)
+    # an all-zero operand: every tile's maximum is zero, nothing is added
+    acc0, tmax0 = capi.tiled_matmul_requant(np.zeros_like(qA), qB, 16, a)
+    assert not acc0.any() and not tmax0.any()
+
+
+def test_requant_dequantization():
+    acc = np.array([[3, -5], [1 << 40, 0]], dtype=np.int64)
+    out = capi.dequantize_requant(acc, np.float32(0.5), np.float32(0.25), 64, 8)
+    f = np.float32(np.float32(np.float32(0.5) * np.float32(0.25)) * np.float32(1 / 64)) * np.float32(2.0 ** -7)
+    assert np.array_equal(out, (acc.astype(np.float32) * f).astype(np.float32))
