@@ -107,6 +107,9 @@ def main():
     ap.add_argument("--graph", action="store_true",
                     help="capture one step into a HIP graph and time its replays (measured: no faster than "
                          "launching from the host, the step is bound by its kernels)")
+    ap.add_argument("--requant", action="store_true",
+                    help="also time the forward matmul under the second reading of the accumulator "
+                         "(hdqt_gemm_requant) and report it as 'requant_fwd'")
     ap.add_argument("--separate", action="store_true",
                     help="run the step as the three per-matmul entry points instead of hdqt_layer_step")
     ap.add_argument("--calib-copy", action="store_true",
@@ -283,6 +286,30 @@ def main():
         "kernels": kernels,
         "roofline_all": roof_all,
     }
+    if args.requant:
+        k = kinds[0]
+        need = B.load().hdqt_gemm_requant_workspace_size(k, M, K, N, prm[k].c())
+        ws2 = torch.empty(need, dtype=torch.uint8, device=dev)
+        for _ in range(2):
+            B.gemm_requant(k, X, W, M, K, N, prm[k], workspace=ws2)
+        torch.cuda.synchronize()
+        B.profile_enable(True)
+        B.profile_collect()
+        t2 = time.perf_counter()
+        for _ in range(5):
+            B.gemm_requant(k, X, W, M, K, N, prm[k], workspace=ws2)
+        torch.cuda.synchronize()
+        dt2 = (time.perf_counter() - t2) / 5
+        B.profile_enable(False)
+        kern2 = B.profile_collect()
+        tiles = (K + args.s - 1) // args.s
+        slab = 4.0 * tiles * M * N                 # all tile sums, written once and read once
+        line["requant_fwd"] = {
+            "ms": dt2 * 1e3, "tiles": tiles, "tile_sum_bytes": slab,
+            "kernels_us": {n_: tot / l * 1e3 for n_, (l, tot) in kern2.items() if n_.startswith("requant")},
+            "tile_sums_write_GBps": slab / (kern2["requant_tile_sums"][1] / kern2["requant_tile_sums"][0] * 1e-3) / 1e9,
+            "quantize_sum_read_GBps": slab / (kern2["requant_quantize_sum"][1] / kern2["requant_quantize_sum"][0] * 1e-3) / 1e9}
+        del ws2
     if not args.no_cpu_baseline:
         line["cpu_baseline"] = cpu_baseline(layer, n, args.s, min(args.cpu_rows, M))
     print(json.dumps(line))

@@ -188,6 +188,33 @@ int hdqt_gemm_codes(const void *qA, const void *qB, int bA, int bB, const float 
                     size_t workspace_bytes, void *stream);
 
 /*
+ * The second reading of "tiled quantization" (Methodology: tiles of size s reduce
+ * the partial sums an a-bit accumulator has to hold): instead of a saturating
+ * register, every tile's partial-sum tensor goes through the paper's quantizer Q
+ * with a bits and its own max calibration, and the tile results are added:
+ *   P_t[i,j] = sum_{d in tile t} qA[i,d] qB[j,d]           m_t = max_{i,j} |P_t[i,j]|
+ *   c_t[i,j] = clamp(RNE(fl(float(P_t[i,j]) * fl(2^(a-1) / m_t))), -2^(a-1), 2^(a-1)-1)
+ *   acc[i,j] = sum_t c_t[i,j] * m_t     (exact)      out = (float)acc * 2^-(a-1) * scaleA*scaleB / n_eff
+ * Arguments as for hdqt_gemm_codes; acc_bits 2..24; acc_out (nullable) receives acc.
+ * HDQT_EINVAL_TILE if a tile sum may not be exact in binary32 (s * 2^(bA+bB-2) >= 2^24),
+ * HDQT_EINVAL_ACC if acc may leave int32.  This is an emulation of the reading, not a
+ * fast path: all tile sums are materialised (workspace
+ * hdqt_gemm_codes_requant_workspace_size = ceil(D/s) * RA*RB*4 bytes plus the maxima).
+ * hdqt_gemm_requant is the same for one of the three matmuls of a step, from the fp32
+ * tensors (P, Q = X, W / G, W / X, G for the three kinds).
+ */
+size_t hdqt_gemm_codes_requant_workspace_size(int64_t RA, int64_t RB, int64_t D, int64_t s);
+int hdqt_gemm_codes_requant(const void *qA, const void *qB, int bA, int bB, const float *scaleA,
+                            const float *scaleB, int64_t RA, int64_t RB, int64_t D, int n_eff,
+                            int acc_bits, int64_t s, float *out, int32_t *acc_out,
+                            void *workspace, size_t workspace_bytes, void *stream);
+size_t hdqt_gemm_requant_workspace_size(int gemm_kind, int64_t M, int64_t K, int64_t N,
+                                        const hdqt_params_t *params);
+int hdqt_gemm_requant(int gemm_kind, const float *P, const float *Q, float *out, int64_t M,
+                      int64_t K, int64_t N, const hdqt_params_t *params, int32_t *acc_out,
+                      void *workspace, size_t workspace_bytes, void *stream);
+
+/*
  * The three matmuls of a training step.  X, W, G, the outputs: fp32 device
  * tensors with the shapes at the top of this file.  `acc_out` (nullable)
  * receives the int32 accumulators of the output's shape.  `params` is a host

@@ -26,6 +26,8 @@ EXPORTED = [
     "hdqt_quantize_dual_workspace_size", "hdqt_layer_step_workspace_size", "hdqt_layer_step",
     "hdqt_gemm_codes_workspace_size", "hdqt_layer_saved_size", "hdqt_layer_fwd_workspace_size",
     "hdqt_layer_fwd", "hdqt_layer_bwd_workspace_size", "hdqt_layer_bwd",
+    "hdqt_gemm_codes_requant_workspace_size", "hdqt_gemm_codes_requant",
+    "hdqt_gemm_requant_workspace_size", "hdqt_gemm_requant",
 ]
 
 
@@ -109,6 +111,15 @@ def load() -> C.CDLL:
     lib.hdqt_quantize_dual_workspace_size.argtypes = []
     lib.hdqt_gemm_codes_workspace_size.restype = sz
     lib.hdqt_gemm_codes_workspace_size.argtypes = [i64, i64, i64, i64]
+    lib.hdqt_gemm_codes_requant_workspace_size.restype = sz
+    lib.hdqt_gemm_codes_requant_workspace_size.argtypes = [i64, i64, i64, i64]
+    lib.hdqt_gemm_codes_requant.restype = i32
+    lib.hdqt_gemm_codes_requant.argtypes = [vp, vp, i32, i32, vp, vp, i64, i64, i64, i32, i32, i64, vp, vp,
+                                            vp, sz, vp]
+    lib.hdqt_gemm_requant_workspace_size.restype = sz
+    lib.hdqt_gemm_requant_workspace_size.argtypes = [i32, i64, i64, i64, C.POINTER(CParams)]
+    lib.hdqt_gemm_requant.restype = i32
+    lib.hdqt_gemm_requant.argtypes = [i32, vp, vp, vp, i64, i64, i64, C.POINTER(CParams), vp, vp, sz, vp]
     lib.hdqt_layer_saved_size.restype = sz
     lib.hdqt_layer_saved_size.argtypes = [i64, i64, C.POINTER(CParams)]
     lib.hdqt_layer_fwd_workspace_size.restype = sz
@@ -399,3 +410,45 @@ def layer_bwd(G: torch.Tensor, W: torch.Tensor, saved: torch.Tensor, K: int,
     if rc:
         raise HdqtError(rc, "hdqt_layer_bwd")
     return dX, dW
+
+
+def gemm_codes_requant(qA: torch.Tensor, qB: torch.Tensor, bA: int, bB: int, scaleA: torch.Tensor,
+                       scaleB: torch.Tensor, D: int, n: int, acc_bits: int, s: int,
+                       want_acc: bool = True, workspace: Optional[torch.Tensor] = None,
+                       stream: Optional[torch.cuda.Stream] = None):
+    """hdqt_gemm_codes_requant -> (out fp32 [RA, RB], acc int32 [RA, RB] | None)."""
+    _check_dev(qA, qB, scaleA, scaleB, workspace)
+    RA, RB = qA.shape[0], qB.shape[0]
+    out = torch.empty((RA, RB), dtype=torch.float32, device=qA.device)
+    acc = torch.empty((RA, RB), dtype=torch.int32, device=qA.device) if want_acc else None
+    if workspace is None:
+        need = load().hdqt_gemm_codes_requant_workspace_size(RA, RB, D, s)
+        workspace = torch.empty(max(need, 256), dtype=torch.uint8, device=qA.device)
+    rc = load().hdqt_gemm_codes_requant(_ptr(qA), _ptr(qB), bA, bB, _ptr(scaleA), _ptr(scaleB), RA, RB, D,
+                                        n, acc_bits, s, _ptr(out), _ptr(acc), _ptr(workspace),
+                                        workspace.numel(), _stream(stream))
+    if rc:
+        raise HdqtError(rc, "hdqt_gemm_codes_requant")
+    return out, acc
+
+
+def gemm_requant(kind: int, P: torch.Tensor, Q: torch.Tensor, M: int, K: int, N: int, params: Params,
+                 want_acc: bool = False, workspace: Optional[torch.Tensor] = None,
+                 stream: Optional[torch.cuda.Stream] = None):
+    """hdqt_gemm_requant -> (out, acc | None, workspace); the workspace starts with the
+    layout hdqt_workspace_layout describes (scales and codes of both operands)."""
+    _check_dev(P, Q, workspace)
+    shape = out_shape(kind, M, K, N)
+    out = torch.empty(shape, dtype=torch.float32, device=P.device)
+    acc = torch.empty(shape, dtype=torch.int32, device=P.device) if want_acc else None
+    p = params.c()
+    if workspace is None:
+        need = load().hdqt_gemm_requant_workspace_size(kind, M, K, N, C.byref(p))
+        if need == 0:
+            raise HdqtError(-5, "hdqt_gemm_requant_workspace_size")
+        workspace = torch.empty(need, dtype=torch.uint8, device=P.device)
+    rc = load().hdqt_gemm_requant(kind, _ptr(P), _ptr(Q), _ptr(out), M, K, N, C.byref(p), _ptr(acc),
+                                  _ptr(workspace), workspace.numel(), _stream(stream))
+    if rc:
+        raise HdqtError(rc, "hdqt_gemm_requant")
+    return out, acc, workspace

@@ -406,6 +406,47 @@ int plan_bwd(int64_t M, int64_t K, int64_t N, const hdqt_params_t* bwi, const hd
     return HDQT_OK;
 }
 
+// ---- second reading of the low-bit accumulator (tiled quantization of the partial sums)
+
+int check_requant(int64_t RA, int64_t RB, int64_t D, int64_t s, int acc_bits, int bA, int bB)
+{
+    if (s < 1) return HDQT_EINVAL_TILE;
+    if (acc_bits < 2 || acc_bits > 24) return HDQT_EINVAL_ACC;
+    const int64_t s_eff = s < D ? s : D;
+    const int64_t max_prod = ((int64_t)1 << (bA - 1)) * ((int64_t)1 << (bB - 1));
+    // a tile sum must be exact in binary32 ...
+    if (s_eff > (((int64_t)1 << 24) - 1) / max_prod) return HDQT_EINVAL_TILE;
+    // ... and the sum over tiles of code * maximum must stay inside int32
+    const int64_t n_tiles = (D + s_eff - 1) / s_eff;
+    const int64_t per_tile = ((int64_t)1 << (acc_bits - 1)) * s_eff * max_prod;
+    if (n_tiles > (((int64_t)1 << 31) - 1) / per_tile) return HDQT_EINVAL_ACC;
+    (void)RA; (void)RB;
+    return HDQT_OK;
+}
+
+size_t requant_bytes(int64_t RA, int64_t RB, int64_t D, int64_t s)
+{
+    const int64_t s_eff = s < D ? s : D;
+    const int64_t n_tiles = (D + s_eff - 1) / s_eff;
+    return align_up((size_t)n_tiles * sizeof(uint32_t), 256) +
+           (size_t)n_tiles * (size_t)(RA * RB) * sizeof(int32_t);
+}
+
+int run_requant(const void* qA, const void* qB, int bA, int bB, const float* scaleA, const float* scaleB,
+                int64_t RA, int64_t RB, int64_t D, int n_eff, int acc_bits, int64_t s, float* out,
+                int32_t* acc_out, void* ws, size_t ws_bytes, hipStream_t stream)
+{
+    if (!ws || ws_bytes < requant_bytes(RA, RB, D, s)) return HDQT_EWORKSPACE;
+    hdqt::GemmArgs g = plan_gemm(qA, qB, bA, bB, scaleA, scaleB, RA, RB, D, n_eff, 32, s, out, acc_out);
+    char* base = static_cast<char*>(ws);
+    g.tile_max = reinterpret_cast<uint32_t*>(base);
+    g.partial = reinterpret_cast<int32_t*>(base + align_up((size_t)g.n_tiles * sizeof(uint32_t), 256));
+    hipError_t e = hdqt::launch_zero2(g.tile_max, g.n_tiles, nullptr, 0, stream);
+    if (e != hipSuccess) return hip_fail(e);
+    e = hdqt::launch_gemm_requant(g, acc_bits, stream);
+    return e == hipSuccess ? HDQT_OK : hip_fail(e);
+}
+
 } // namespace
 
 extern "C" {
@@ -534,6 +575,74 @@ int hdqt_gemm_codes(const void* qA, const void* qB, int bA, int bB, const float*
     return run_planned_gemm(plan_gemm(qA, qB, bA, bB, scaleA, scaleB, RA, RB, D, n_eff, acc_bits, s,
                                       out, acc_out),
                             workspace, workspace_bytes, static_cast<hipStream_t>(stream));
+}
+
+size_t hdqt_gemm_codes_requant_workspace_size(int64_t RA, int64_t RB, int64_t D, int64_t s)
+{
+    if (RA <= 0 || RB <= 0 || D <= 0 || s < 1 || RA >= kMaxDim || RB >= kMaxDim || D >= kMaxDim) return 0;
+    return requant_bytes(RA, RB, D, s);
+}
+
+int hdqt_gemm_codes_requant(const void* qA, const void* qB, int bA, int bB, const float* scaleA,
+                            const float* scaleB, int64_t RA, int64_t RB, int64_t D, int n_eff,
+                            int acc_bits, int64_t s, float* out, int32_t* acc_out, void* workspace,
+                            size_t workspace_bytes, void* stream)
+{
+    if (!qA || !qB || !scaleA || !scaleB || (!out && !acc_out)) return HDQT_EINVAL_NULL;
+    if (RA <= 0 || RB <= 0 || D <= 0 || RA >= kMaxDim || RB >= kMaxDim || D >= kMaxDim)
+        return HDQT_EINVAL_DIM;
+    int rc;
+    if ((rc = check_dims2(RA, D)) || (rc = check_dims2(RB, D)) || (rc = check_dims2(RA, RB))) return rc;
+    if (bA < 2 || bA > 8 || bB < 2 || bB > 8) return HDQT_EINVAL_BITS;
+    if (!is_pow2(n_eff) || n_eff > hdqt::kMaxHadamard || D % n_eff != 0) return HDQT_EINVAL_HADAMARD;
+    if ((rc = check_requant(RA, RB, D, s, acc_bits, bA, bB))) return rc;
+    if (misaligned(qA) || misaligned(qB) || misaligned(out) || misaligned(acc_out) || misaligned(workspace))
+        return HDQT_EALIGN;
+    return run_requant(qA, qB, bA, bB, scaleA, scaleB, RA, RB, D, n_eff, acc_bits, s, out, acc_out,
+                       workspace, workspace_bytes, static_cast<hipStream_t>(stream));
+}
+
+size_t hdqt_gemm_requant_workspace_size(int gemm_kind, int64_t M, int64_t K, int64_t N,
+                                        const hdqt_params_t* params)
+{
+    hdqt_ws_layout_t L;
+    if (hdqt_workspace_layout(gemm_kind, M, K, N, params, &L) != HDQT_OK) return 0;
+    if (check_requant(L.RA, L.RB, L.D, params->s, params->acc_bits, params->A.b, params->B.b)) return 0;
+    return L.acc + requant_bytes(L.RA, L.RB, L.D, params->s);
+}
+
+int hdqt_gemm_requant(int gemm_kind, const float* P, const float* Q, float* out, int64_t M, int64_t K,
+                      int64_t N, const hdqt_params_t* params, int32_t* acc_out, void* workspace,
+                      size_t workspace_bytes, void* stream_v)
+{
+    hdqt_ws_layout_t L;
+    int rc = hdqt_workspace_layout(gemm_kind, M, K, N, params, &L);
+    if (rc) return rc;
+    if ((rc = check_requant(L.RA, L.RB, L.D, params->s, params->acc_bits, params->A.b, params->B.b)))
+        return rc;
+    if (!P || !Q || (!out && !acc_out)) return HDQT_EINVAL_NULL;
+    if (!workspace || workspace_bytes < L.acc + requant_bytes(L.RA, L.RB, L.D, params->s))
+        return HDQT_EWORKSPACE;
+    if (misaligned(P) || misaligned(Q) || misaligned(out) || misaligned(acc_out) || misaligned(workspace))
+        return HDQT_EALIGN;
+    Orientation o;
+    orient(gemm_kind, M, K, N, &o);
+    hipStream_t stream = static_cast<hipStream_t>(stream_v);
+    char* base = static_cast<char*>(workspace);
+    hdqt::QMeta* metaA = reinterpret_cast<hdqt::QMeta*>(base + L.scaleA);
+    hdqt::QMeta* metaB = reinterpret_cast<hdqt::QMeta*>(base + L.scaleB);
+    hipError_t e = hdqt::launch_zero2(reinterpret_cast<uint32_t*>(metaA), (int64_t)(2 * kMetaBytes / 4),
+                                      nullptr, 0, stream);
+    if (e != hipSuccess) return hip_fail(e);
+    rc = run_quantize(P, o.a_rows, o.a_cols, o.a_axis, L.n_eff, &params->A, params->seed, metaA,
+                      base + L.codesA, nullptr, stream);
+    if (rc) return rc;
+    rc = run_quantize(Q, o.b_rows, o.b_cols, o.b_axis, L.n_eff, &params->B, params->seed, metaB,
+                      base + L.codesB, nullptr, stream);
+    if (rc) return rc;
+    return run_requant(base + L.codesA, base + L.codesB, params->A.b, params->B.b, &metaA->scale,
+                       &metaB->scale, L.RA, L.RB, L.D, L.n_eff, params->acc_bits, params->s, out, acc_out,
+                       base + L.acc, workspace_bytes - L.acc, stream);
 }
 
 size_t hdqt_layer_step_workspace_size(int64_t M, int64_t K, int64_t N, const hdqt_params_t* fwd,

@@ -79,7 +79,9 @@ struct GemmArgs {
     float inv_n;            // 1 / n_eff (a power of two)
     float* out;             // [RA, RB] or null
     int32_t* acc_out;       // [RA, RB] or null
-    int32_t* partial;       // [splits, RA, RB] when splits > 1: one slice per part of the contraction
+    int32_t* partial;       // [splits, RA, RB] when splits > 1: one slice per part of the contraction;
+                            // second reading of the accumulator: [n_tiles, RA, RB], every tile's sums
+    uint32_t* tile_max;     // second reading only: max |tile sum| per tile, zero beforehand
     int stream_out;         // fp32 output too large to stay cached: written with streaming stores
     int profile_tag;        // which matmul of the step this is (timing table only): 0 none, 1 + kind
     int splits;             // workgroups sharing one output tile along the contraction
@@ -89,6 +91,9 @@ struct GemmArgs {
 // Launchers (host).  Each returns the hipError_t of its last launch.
 hipError_t launch_quantize(const QuantArgs& q, hipStream_t stream);
 hipError_t launch_gemm(const GemmArgs& g, hipStream_t stream);
+// Second reading of the low-bit accumulator: every tile's partial sums to g.partial and their
+// maxima to g.tile_max, then Q with acc_bits per tile and the sum over tiles (see gemm.hip).
+hipError_t launch_gemm_requant(const GemmArgs& g, int acc_bits, hipStream_t stream);
 constexpr int kMaxDualBatch = 3;
 // the two passes of the two-axis quantization, each for up to kMaxDualBatch tensors in one launch
 hipError_t launch_dual_pass1(const DualArgs* qs, int n, hipStream_t stream);
@@ -108,7 +113,7 @@ enum KernelId {
     K_PLAIN_QUANT, K_GEMM_ALIGNED, K_GEMM_GENERIC, K_REDUCE, K_GEMM_I4, K_DUAL_ABSMAX, K_DUAL_QUANT,
     K_GEMM_I4_FWD, K_GEMM_I4_BWD_INPUT, K_GEMM_I4_BWD_WEIGHT,
     K_DUAL_ABSMAX_X, K_DUAL_ABSMAX_W, K_DUAL_ABSMAX_G, K_DUAL_QUANT_X, K_DUAL_QUANT_W, K_DUAL_QUANT_G,
-    K_DUAL_ABSMAX_BATCH, K_DUAL_QUANT_BATCH,
+    K_DUAL_ABSMAX_BATCH, K_DUAL_QUANT_BATCH, K_REQUANT_TILES, K_REQUANT_SUM,
     K_COUNT
 };
 bool quantize_fast_eligible(const QuantArgs& q);

@@ -27,6 +27,13 @@ constexpr int KC = 64;          // virtual contraction positions per LDS stage
 constexpr int KG = 16;          // contraction depth of one MFMA
 constexpr int LDP = KC + 16;    // LDS row pitch in bytes
 
+__device__ __forceinline__ int wave_max_int(int v)
+{
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) v = max(v, __shfl_xor(v, off, kWave));
+    return v;
+}
+
 __device__ __forceinline__ int sext_nibble(uint32_t nib)
 {
     return ((int)(nib << 28)) >> 28;
@@ -100,7 +107,10 @@ __device__ __forceinline__ void load_operand(uint8_t (*lds)[LDP], const uint8_t*
     }
 }
 
-template <bool ALIGNED>
+// REQUANT (second reading of the accumulator, Methodology: tiled quantization): instead of
+// clamping and adding, every finished tile's sums are written to g.partial[t] and their
+// largest magnitude is folded into g.tile_max[t]; requant_sum_kernel does the rest.
+template <bool ALIGNED, bool REQUANT>
 __global__ __launch_bounds__(kThreads) void gemm_tiled_kernel(GemmArgs g)
 {
     __shared__ __attribute__((aligned(16))) uint8_t As[BM][LDP];
@@ -150,7 +160,31 @@ __global__ __launch_bounds__(kThreads) void gemm_tiled_kernel(GemmArgs g)
 #pragma unroll
                 for (int c = 0; c < 2; ++c)
                     part[a][c] = __builtin_amdgcn_mfma_i32_32x32x16_i8(fa[a], fb[c], part[a][c], 0, 0, 0);
-            if (++step_in_tile == steps_per_tile) {
+            if (REQUANT && step_in_tile + 1 == steps_per_tile) {
+                step_in_tile = 0;
+                const int64_t t = (kv0 + ks * KG) / g.s_pad;
+                int32_t* slice = g.partial + t * g.RA * g.RB;
+                int m = 0;
+#pragma unroll
+                for (int a = 0; a < 2; ++a)
+#pragma unroll
+                    for (int c = 0; c < 2; ++c) {
+                        const int64_t j = col0 + wn * 64 + c * 32 + (lane & 31);
+#pragma unroll
+                        for (int r = 0; r < 16; ++r) {
+                            const int64_t i = row0 + wm * 64 + a * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
+                            const int pv = part[a][c][r];
+                            part[a][c][r] = 0;
+                            if (i < g.RA && j < g.RB) {
+                                slice[i * g.RB + j] = pv;
+                                m = max(m, pv < 0 ? -pv : pv);
+                            }
+                        }
+                    }
+                m = wave_max_int(m);
+                if (lane == 0 && (uint32_t)m > __hip_atomic_load(&g.tile_max[t], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT))
+                    atomicMax(&g.tile_max[t], (uint32_t)m);
+            } else if (++step_in_tile == steps_per_tile) {
                 step_in_tile = 0;
 #pragma unroll
                 for (int a = 0; a < 2; ++a)
@@ -167,6 +201,7 @@ __global__ __launch_bounds__(kThreads) void gemm_tiled_kernel(GemmArgs g)
         }
     }
 
+    if (REQUANT) return;
     // ---- store.  32x32 block: lane holds column (lane & 31); register r is
     // row 8*(r/4) + 4*(lane/32) + (r%4).
     const float dq = (g.scaleA[0] * g.scaleB[0]) * g.inv_n;
@@ -220,6 +255,53 @@ __global__ __launch_bounds__(256) void reduce_kernel(const int32_t* partial, int
     }
 }
 
+// Second reading, second step: Q with `a` bits on every tile's partial sums, with the
+// tile's own maximum, and the sum over tiles.  Per element e and tile t:
+//   inv_t = fl(2^(a-1) / m_t),  c = clamp(RNE(fl(float(P_t[e]) * inv_t))),  acc += c * m_t
+// (exact integers); value = acc * 2^-(a-1), dequantized like any other total.
+constexpr int kTileChunk = 2048;
+__global__ __launch_bounds__(256) void requant_sum_kernel(const int32_t* partial, const uint32_t* tile_max,
+                                                          int64_t n_tiles, int64_t count, int a,
+                                                          const float* scaleA, const float* scaleB,
+                                                          float inv_n, float pow2, float* out,
+                                                          int32_t* acc_out)
+{
+    __shared__ float inv_s[kTileChunk];
+    __shared__ int m_s[kTileChunk];
+    const float qmax = (float)((1 << (a - 1)) - 1), qmin = -(float)(1 << (a - 1));
+    const float dq = ((scaleA[0] * scaleB[0]) * inv_n) * pow2;     // pow2 = 2^-(a-1): exact scaling
+    const int64_t per_block = (int64_t)blockDim.x;
+    const int64_t rounds = (count + per_block * gridDim.x - 1) / (per_block * gridDim.x);
+    // every thread of a block walks the same tiles, so the chunk tables are filled once per round
+    for (int64_t round = 0; round < rounds; ++round) {
+        const int64_t e = (round * gridDim.x + blockIdx.x) * per_block + threadIdx.x;
+        int acc = 0;
+        for (int64_t t0 = 0; t0 < n_tiles; t0 += kTileChunk) {
+            const int chunk = (int)(n_tiles - t0 < kTileChunk ? n_tiles - t0 : kTileChunk);
+            __syncthreads();
+            for (int k = threadIdx.x; k < chunk; k += blockDim.x) {
+                const uint32_t m = tile_max[t0 + k];
+                m_s[k] = (int)m;
+                // binary64 quotient of two binary32-exact integers, rounded once more to binary32
+                inv_s[k] = m ? (float)((double)(1 << (a - 1)) / (double)m) : 0.0f;
+            }
+            __syncthreads();
+            if (e < count) {
+                const int32_t* src = partial + t0 * count + e;
+                for (int k = 0; k < chunk; ++k, src += count) {
+                    const float v = (float)src[0] * inv_s[k];
+                    const float r = fminf(fmaxf(rintf(v), qmin), qmax);
+                    acc += (int)r * m_s[k];
+                }
+            }
+        }
+        if (e < count) {
+            if (acc_out) acc_out[e] = acc;
+            if (out) out[e] = (float)acc * dq;
+        }
+    }
+}
+
 } // namespace
 
 hipError_t launch_reduce(const int32_t* partial, int splits, int64_t count, const float* scaleA,
@@ -248,9 +330,40 @@ hipError_t launch_gemm(const GemmArgs& g, hipStream_t stream)
     const bool aligned = (g.s % 16 == 0) && (g.D % 16 == 0) && (g.s_pad == g.s);
     ProfileScope ps(aligned ? K_GEMM_ALIGNED : K_GEMM_GENERIC, stream);
     if (aligned)
-        hipLaunchKernelGGL(gemm_tiled_kernel<true>, grid, dim3(kThreads), 0, stream, g);
+        hipLaunchKernelGGL((gemm_tiled_kernel<true, false>), grid, dim3(kThreads), 0, stream, g);
     else
-        hipLaunchKernelGGL(gemm_tiled_kernel<false>, grid, dim3(kThreads), 0, stream, g);
+        hipLaunchKernelGGL((gemm_tiled_kernel<false, false>), grid, dim3(kThreads), 0, stream, g);
+    return hipGetLastError();
+}
+
+hipError_t launch_gemm_requant(const GemmArgs& g_in, int acc_bits, hipStream_t stream)
+{
+    GemmArgs g = g_in;
+    const int64_t blocks = ((g.RB + BN - 1) / BN) * ((g.RA + BM - 1) / BM);
+    // the tiles are independent: spread them over enough workgroups to fill the chip
+    int64_t parts = (1024 + blocks - 1) / blocks;
+    if (parts > g.n_tiles) parts = g.n_tiles;
+    if (parts > 65535) parts = 65535;
+    g.tiles_per_split = (g.n_tiles + parts - 1) / parts;
+    g.splits = (int)((g.n_tiles + g.tiles_per_split - 1) / g.tiles_per_split);
+    const dim3 grid((unsigned)((g.RB + BN - 1) / BN), (unsigned)((g.RA + BM - 1) / BM), (unsigned)g.splits);
+    const bool aligned = (g.s % 16 == 0) && (g.D % 16 == 0) && (g.s_pad == g.s);
+    {
+        ProfileScope ps(K_REQUANT_TILES, stream);
+        if (aligned)
+            hipLaunchKernelGGL((gemm_tiled_kernel<true, true>), grid, dim3(kThreads), 0, stream, g);
+        else
+            hipLaunchKernelGGL((gemm_tiled_kernel<false, true>), grid, dim3(kThreads), 0, stream, g);
+    }
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    const int64_t count = g.RA * g.RB;
+    int64_t nb = (count + 255) / 256;
+    if (nb > 8192) nb = 8192;
+    ProfileScope ps(K_REQUANT_SUM, stream);
+    hipLaunchKernelGGL(requant_sum_kernel, dim3((unsigned)nb), dim3(256), 0, stream, g.partial, g.tile_max,
+                       g.n_tiles, count, acc_bits, g.scaleA, g.scaleB, g.inv_n,
+                       ldexpf(1.0f, -(acc_bits - 1)), g.out, g.acc_out);
     return hipGetLastError();
 }
 

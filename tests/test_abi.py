@@ -259,3 +259,32 @@ def test_gemm_codes_workspace_size():
     need = lib.hdqt_gemm_codes_workspace_size(1152, 128, 65536, 32)               # 9 tiles, long contraction
     assert need > 0 and need % (1152 * 128 * 4) == 0
     assert lib.hdqt_gemm_codes_workspace_size(0, 128, 64, 32) == 0
+
+
+def test_gemm_codes_requant_argument_errors():
+    lib = B.load()
+    assert lib.hdqt_gemm_codes_requant_workspace_size(8, 8, 64, 32) >= 2 * 8 * 8 * 4 + 2 * 4
+    assert lib.hdqt_gemm_codes_requant_workspace_size(8, 0, 64, 32) == 0
+
+    def rc(qA=FAKE, bA=4, bB=4, RA=8, D=64, n=64, a=8, s=32, out=FAKE, ws=FAKE, nbytes=1 << 20):
+        return lib.hdqt_gemm_codes_requant(qA, FAKE, bA, bB, FAKE, FAKE, RA, 8, D, n, a, s, out, None, ws,
+                                           nbytes, None)
+
+    assert rc(qA=None) == E["HDQT_EINVAL_NULL"]
+    assert rc(out=None) == E["HDQT_EINVAL_NULL"]
+    assert rc(RA=0) == E["HDQT_EINVAL_DIM"]
+    assert rc(bA=1) == E["HDQT_EINVAL_BITS"]
+    assert rc(n=3) == E["HDQT_EINVAL_HADAMARD"]
+    assert rc(a=25) == E["HDQT_EINVAL_ACC"]
+    assert rc(s=0) == E["HDQT_EINVAL_TILE"]
+    assert rc(bA=8, bB=8, D=4096, s=4096) == E["HDQT_EINVAL_TILE"]     # 4096 * 2^14 = 2^26: not exact in binary32
+    assert rc(D=1 << 20, n=64, a=16) == E["HDQT_EINVAL_ACC"]           # the sum over 32768 tiles may leave int32
+    assert rc(ws=None) == E["HDQT_EWORKSPACE"]
+    assert rc(nbytes=64) == E["HDQT_EWORKSPACE"]
+    p = _cparams()
+    assert lib.hdqt_gemm_requant_workspace_size(0, 256, 128, 64, C.byref(p)) > 0
+    assert lib.hdqt_gemm_requant_workspace_size(5, 256, 128, 64, C.byref(p)) == 0
+    assert lib.hdqt_gemm_requant(0, None, FAKE, FAKE, 256, 128, 64, C.byref(p), None, FAKE, 1 << 30, None) \
+        == E["HDQT_EINVAL_NULL"]
+    assert lib.hdqt_gemm_requant(0, FAKE, FAKE, FAKE, 256, 128, 64, C.byref(p), None, FAKE, 1024, None) \
+        == E["HDQT_EWORKSPACE"]

@@ -273,3 +273,24 @@ def test_layer_step_in_a_hip_graph():
         graph.replay()
         torch.cuda.synchronize()
         assert torch.equal(out[0], Z0) and torch.equal(out[1], dX0) and torch.equal(out[2], dW0), rep
+
+
+def test_requant_forward_resnet_conv_k1152():
+    """The bench layer's forward product under the second reading of the accumulator
+    (36 tiles of 32, each re-quantized to 8 bits with its own maximum), full size, every
+    total against the oracle."""
+    layer = workloads.resnet_conv_layer(256, 128, 128, 16, seed=0)
+    M, K, N = layer.M, layer.K, layer.N
+    opA, opB = step_operands(FWD, 4, 0)
+    prm = B.Params(had_block=64, acc_bits=8, s=32, seed=0, A=opA, B=opB)
+    print("oracle quantization and second-reading matmul ...", flush=True)
+    cA, sA, nA = capi.quantize(layer.X.numpy(), 1, 64, o_op(opA), 0)
+    cB, sB, _ = capi.quantize(layer.W.numpy(), 0, 64, o_op(opB), 0)
+    want_acc, tmax = capi.tiled_matmul_requant(cA, cB, 32, 8)
+    out, acc, _ = B.gemm_requant(FWD, dev(layer.X), dev(layer.W), M, K, N, prm, want_acc=True)
+    torch.cuda.synchronize()
+    assert np.array_equal(acc.cpu().numpy().astype(np.int64), want_acc)
+    want_out = capi.dequantize_requant(want_acc, sA, sB, nA, 8)
+    got = out.cpu().numpy()
+    denom = np.maximum(np.abs(want_out), np.finfo(np.float32).tiny)
+    assert np.all(np.abs(got.astype(np.float64) - want_out) <= RTOL * denom)

@@ -317,3 +317,66 @@ def test_quantize_dual_wider_codes_and_zero():
     check_quantize_dual(T, 64, B.Operand(8), B.Operand(4))
     check_quantize_dual(T, 64, B.Operand(4), B.Operand(6, B.ROUND_STOCHASTIC, 1.0, 9), seed=3)
     check_quantize_dual(np.zeros((64, 128), np.float32), 64, B.Operand(4), B.Operand(4, B.ROUND_STOCHASTIC))
+
+
+# ------------------------------------------------------------------ second reading of the accumulator
+
+def check_requant_codes(RA, RB, D, bA, bB, s, a, n=1, seed=0, extreme=0.0):
+    print(f"requant RA={RA} RB={RB} D={D} bA={bA} bB={bB} s={s} a={a}", flush=True)
+    rng = np.random.default_rng(seed + RA * 3 + RB * 5 + D)
+    cA = random_codes(rng, RA, D, bA, extreme)
+    cB = random_codes(rng, RB, D, bB, extreme)
+    sA, sB = np.float32(0.0123), np.float32(3.21e-4)
+    want_acc, _ = capi.tiled_matmul_requant(cA, cB, s, a)
+    want_out = capi.dequantize_requant(want_acc, sA, sB, n, a)
+    out, acc = B.gemm_codes_requant(dev(capi.pack_codes(cA, bA)), dev(capi.pack_codes(cB, bB)), bA, bB,
+                                    dev(np.array([sA])), dev(np.array([sB])), D, n, a, s)
+    got_acc, got_out = host(acc), host(out)
+    assert np.array_equal(got_acc.astype(np.int64), want_acc), \
+        f"{(got_acc != want_acc).sum()} of {want_acc.size} totals differ"
+    assert_close_f32(got_out, want_out)
+
+
+@pytest.mark.parametrize("s", [16, 32, 64, 256])
+@pytest.mark.parametrize("a", [4, 8, 12])
+def test_requant_codes_aligned(s, a):
+    check_requant_codes(200, 136, 512, 4, 4, s, a, n=64)
+    check_requant_codes(200, 136, 512, 4, 4, s, a, n=64, extreme=0.5)
+
+
+@pytest.mark.parametrize("s", [1, 5, 27, 48, 100, 1000])
+def test_requant_codes_ragged(s):
+    check_requant_codes(37, 29, 100, 4, 4, s, 8, n=4)
+    check_requant_codes(130, 5, 27, 4, 4, s, 8)
+    check_requant_codes(9, 300, 144, 3, 5, s, 6, n=16, extreme=0.3)
+
+
+def test_requant_codes_wide_inputs_and_many_tiles():
+    check_requant_codes(96, 72, 512, 8, 8, 32, 8, n=64, extreme=0.2)
+    check_requant_codes(96, 72, 512, 6, 5, 64, 12, n=64, extreme=0.2)
+    check_requant_codes(64, 64, 8192, 4, 4, 32, 8, n=64)            # 256 tiles
+    check_requant_codes(16, 16, 4096, 4, 4, 1, 8)                   # 4096 tiles of one code: tables in chunks
+    zeros = np.zeros((32, 64), np.int8)
+    out, acc = B.gemm_codes_requant(dev(capi.pack_codes(zeros, 4)), dev(capi.pack_codes(zeros, 4)), 4, 4,
+                                    dev(np.ones(1, np.float32)), dev(np.ones(1, np.float32)), 64, 64, 8, 32)
+    assert not host(acc).any() and not host(out).any()
+
+
+@pytest.mark.parametrize("kind", [B.GEMM_FWD, B.GEMM_BWD_INPUT, B.GEMM_BWD_WEIGHT])
+def test_requant_matmul_from_tensors(kind):
+    """The paper's forward setting (tiles of 32, 8-bit accumulators) under the second reading,
+    and the two backward matmuls, from the fp32 tensors: quantization as everywhere else, then
+    the oracle's second-reading matmul on the oracle's codes."""
+    layer = workloads.fc_layer(320, 256, 192, seed=2)
+    M, K, N = layer.M, layer.K, layer.N
+    P, Q = {B.GEMM_FWD: (layer.X, layer.W), B.GEMM_BWD_INPUT: (layer.G, layer.W),
+            B.GEMM_BWD_WEIGHT: (layer.X, layer.G)}[kind]
+    axes = {B.GEMM_FWD: (1, 0), B.GEMM_BWD_INPUT: (1, 1), B.GEMM_BWD_WEIGHT: (0, 0)}[kind]
+    prm = B.Params(had_block=64, acc_bits=8, s=32, seed=4, A=B.Operand(4, B.ROUND_NEAREST, 0.975, 1),
+                   B=B.Operand(4, B.ROUND_STOCHASTIC, 1.0, 2))
+    out, acc, _ = B.gemm_requant(kind, dev(P), dev(Q), M, K, N, prm, want_acc=True)
+    cA, sA, nA = capi.quantize(P.numpy(), axes[0], 64, o_operand(prm.A), 4)
+    cB, sB, nB = capi.quantize(Q.numpy(), axes[1], 64, o_operand(prm.B), 4)
+    want_acc, _ = capi.tiled_matmul_requant(cA, cB, 32, 8)
+    assert np.array_equal(host(acc).astype(np.int64), want_acc)
+    assert_close_f32(host(out), capi.dequantize_requant(want_acc, sA, sB, nA, 8))
