@@ -4,6 +4,10 @@
 // H = BlockDiag(H_k,..,H_k) in Sylvester form; Q(y) with alpha calibrated on
 // the maximum of the tensor; nearest or stochastic rounding.
 //
+// This file holds the kernels for the shapes the tuned kernels (quantize_fast.hip,
+// quantize_dual.hip) do not take -- odd contraction lengths, block orders 128 and
+// 256 along axis 0, column counts that are not multiples of 4 -- and the fill kernel.
+//
 // Two passes over the source tensor, both HBM-bound:
 //   pass 1  transform in registers, reduce max|y|, one atomicMax per workgroup
 //   pass 2  transform again, scale, round, clamp, pack, store codes
@@ -58,92 +62,6 @@ __device__ __forceinline__ float pair_lanes(float own, int lane, int mask)
 {
     const float other = __shfl_xor(own, mask, kWave);
     return (lane & mask) ? (other - own) : (own + other);
-}
-
-// ---------------------------------------------------------------------------
-// Contraction along rows of the source (axis 1).  Blocks of n consecutive
-// elements never straddle a row (n | cols), so the tensor is one flat array
-// cut into chunks of 8; a wave covers 512 consecutive elements.
-// Requires: cols even when b <= 4 (codes of a row fill whole bytes).
-// ---------------------------------------------------------------------------
-template <bool QUANT>
-__global__ __launch_bounds__(kThreads) void fwht_row_kernel(QuantArgs q)
-{
-    __shared__ float red[kThreads / kWave];
-    const int64_t total = q.rows * q.cols;
-    const int64_t nchunks = (total + 7) >> 3;
-    const int lane = threadIdx.x & 63;
-    const int log2n = q.log2n;
-    const int qmin = -(1 << (q.b - 1)), qmax = (1 << (q.b - 1)) - 1;
-
-    Scaling sc{};
-    if (QUANT) {
-        sc = load_scaling(q.meta, q.clip, q.b);
-        publish_scale(q, sc);
-    }
-    float amax = 0.0f;
-
-    for (int64_t base = (int64_t)blockIdx.x * kThreads; base < nchunks;
-         base += (int64_t)gridDim.x * kThreads) {
-        const int64_t c = base + threadIdx.x;
-        const int64_t e0 = c << 3;
-        float v[8];
-        if (e0 + 8 <= total) {
-            const float4 lo = *reinterpret_cast<const float4*>(q.T + e0);
-            const float4 hi = *reinterpret_cast<const float4*>(q.T + e0 + 4);
-            v[0] = lo.x; v[1] = lo.y; v[2] = lo.z; v[3] = lo.w;
-            v[4] = hi.x; v[5] = hi.y; v[6] = hi.z; v[7] = hi.w;
-        } else {
-#pragma unroll
-            for (int i = 0; i < 8; ++i) v[i] = (e0 + i < total) ? q.T[e0 + i] : 0.0f;
-        }
-        butterfly8(v, log2n);
-        for (int st = 3; st < log2n; ++st) {
-            const int mask = 1 << (st - 3);
-#pragma unroll
-            for (int i = 0; i < 8; ++i) v[i] = pair_lanes(v[i], lane, mask);
-        }
-        if (!QUANT) {
-#pragma unroll
-            for (int i = 0; i < 8; ++i) amax = fmaxf(amax, fabsf(v[i]));
-            continue;
-        }
-        if (e0 >= total) continue;
-        uint32_t rnd[4] = {0, 0, 0, 0};
-        if (q.stochastic)
-            philox4x32_10((uint32_t)c, (uint32_t)(c >> 32), q.tensor_id, 0u, q.seed_lo, q.seed_hi,
-                          rnd);
-        int code[8];
-#pragma unroll
-        for (int i = 0; i < 8; ++i)
-            code[i] = quantize_value(v[i], sc.inv, qmin, qmax, q.stochastic != 0,
-                                               sr_halfword(rnd, (uint32_t)i));
-        const bool full = (e0 + 8 <= total);
-        if (q.b <= 4) {
-            uint32_t w = 0;
-#pragma unroll
-            for (int i = 0; i < 8; ++i) w |= ((uint32_t)code[i] & 0xFu) << (4 * i);
-            if (full) {
-                reinterpret_cast<uint32_t*>(q.codes)[c] = w;
-            } else {
-                for (int i = 0; i < 8 && e0 + i < total; i += 2)
-                    q.codes[(e0 + i) >> 1] = (uint8_t)(w >> (4 * i));
-            }
-        } else {
-            uint32_t w0 = 0, w1 = 0;
-#pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                w0 |= ((uint32_t)code[i] & 0xFFu) << (8 * i);
-                w1 |= ((uint32_t)code[i + 4] & 0xFFu) << (8 * i);
-            }
-            if (full) {
-                reinterpret_cast<uint2*>(q.codes)[c] = make_uint2(w0, w1);
-            } else {
-                for (int i = 0; i < 8 && e0 + i < total; ++i) q.codes[e0 + i] = (uint8_t)code[i];
-            }
-        }
-    }
-    if (!QUANT) block_atomic_max(amax, q.meta, red);
 }
 
 // ---------------------------------------------------------------------------
@@ -392,17 +310,9 @@ hipError_t launch_quantize(const QuantArgs& q, hipStream_t stream)
         hipLaunchKernelGGL(quant_plain_kernel, dim3(grid2), dim3(kThreads), 0, stream, q);
         return hipGetLastError();
     }
-    if (q.axis == 1) {
-        const int64_t nchunks = (total + 7) >> 3;
-        const int grid = clamp_grid((nchunks + kThreads - 1) / kThreads, 256 * 16);
-        {
-            ProfileScope ps(K_ROW_ABSMAX, stream);
-            hipLaunchKernelGGL(fwht_row_kernel<false>, dim3(grid), dim3(kThreads), 0, stream, q);
-        }
-        ProfileScope ps(K_ROW_QUANT, stream);
-        hipLaunchKernelGGL(fwht_row_kernel<true>, dim3(grid), dim3(kThreads), 0, stream, q);
-        return hipGetLastError();
-    }
+    // (axis 1 with an even row length is always taken by the tuned kernel: what is left
+    // here is axis 0 with a block order above 64 or a column count that is not a
+    // multiple of 4)
     const dim3 grid((unsigned)((q.cols + kColTileCols - 1) / kColTileCols),
                     (unsigned)((D + kColTileRows - 1) / kColTileRows));
     {
