@@ -107,6 +107,8 @@ def main():
     ap.add_argument("--graph", action="store_true",
                     help="capture one step into a HIP graph and time its replays (measured: no faster than "
                          "launching from the host, the step is bound by its kernels)")
+    ap.add_argument("--no-large-quantize", action="store_true",
+                    help="skip the 1 GiB hdqt_quantize measurement ('quantize_1GiB')")
     ap.add_argument("--requant", action="store_true",
                     help="also time the forward matmul under the second reading of the accumulator "
                          "(hdqt_gemm_requant) and report it as 'requant_fwd'")
@@ -286,6 +288,29 @@ def main():
         "kernels": kernels,
         "roofline_all": roof_all,
     }
+    if not args.no_large_quantize:
+        # The quantizer alone on a tensor far larger than any cache (1 GiB, axis 1, n = 64,
+        # b = 4, nearest): per-pass HBM rate of hdqt_quantize, algorithmic bytes 4 B per
+        # element for pass 1 and 4.5 B for pass 2.
+        big = torch.randn((16384, 16384), device=dev)
+        op = B.Operand(4, B.ROUND_NEAREST, 1.0, 0)
+        B.quantize(big, 1, 64, op, 0)
+        torch.cuda.synchronize()
+        B.profile_enable(True)
+        B.profile_collect()
+        for _ in range(5):
+            B.quantize(big, 1, 64, op, 0)
+        torch.cuda.synchronize()
+        B.profile_enable(False)
+        kq = B.profile_collect()
+        elems_big = 16384.0 * 16384.0
+        p1 = kq["fwht_row_absmax"][1] / kq["fwht_row_absmax"][0] * 1e-3
+        p2 = kq["fwht_row_quant"][1] / kq["fwht_row_quant"][0] * 1e-3
+        line["quantize_1GiB"] = {
+            "pass1_GBps": 4.0 * elems_big / p1 / 1e9, "pass1_frac_of_hbm_peak": 4.0 * elems_big / p1 / 1e9 / HBM_PEAK_GBPS,
+            "pass2_GBps": 4.5 * elems_big / p2 / 1e9, "pass2_frac_of_hbm_peak": 4.5 * elems_big / p2 / 1e9 / HBM_PEAK_GBPS,
+            "both_GBps": 8.5 * elems_big / (p1 + p2) / 1e9}
+        del big
     if args.requant:
         k = kinds[0]
         need = B.load().hdqt_gemm_requant_workspace_size(k, M, K, N, prm[k].c())
