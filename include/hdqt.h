@@ -58,7 +58,8 @@ typedef enum { HDQT_GEMM_FWD = 0, HDQT_GEMM_BWD_INPUT = 1, HDQT_GEMM_BWD_WEIGHT 
 /* ---- error codes ---- */
 #define HDQT_OK 0
 #define HDQT_EINVAL_NULL (-1)     /* a required pointer is NULL */
-#define HDQT_EINVAL_DIM (-2)      /* a dimension is <= 0 or too large */
+#define HDQT_EINVAL_DIM (-2)      /* a dimension is <= 0 or above 4 194 240 (65535 * 64), or a
+                                     tensor has 2^40 elements or more */
 #define HDQT_EINVAL_HADAMARD (-3) /* had_block is not a power of two in [1, 256] */
 #define HDQT_EINVAL_BITS (-4)     /* b outside [2, 8] */
 #define HDQT_EINVAL_ACC (-5)      /* acc_bits outside [2, 32], or the sum of all tiles may leave int32 */

@@ -31,7 +31,9 @@ int check_hadamard(int had_block)
     return HDQT_OK;
 }
 
-constexpr int64_t kMaxDim = (int64_t)1 << 31;        // per dimension
+// Per dimension: the kernels put up to one workgroup per 64 rows on the y axis of the
+// grid, which holds 65535.
+constexpr int64_t kMaxDim = (int64_t)65535 * 64 + 1;
 constexpr int64_t kMaxElems = (int64_t)1 << 40;      // per tensor
 
 int check_dims2(int64_t rows, int64_t cols)

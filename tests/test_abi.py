@@ -93,8 +93,8 @@ def test_accumulation_range_errors():
     # 8-bit codes, one tile of 2^20: tile sum up to 2^34 does not fit int32
     big = dict(A=B.Operand(b=8), B=B.Operand(b=8))
     assert _gemm_rc(B.GEMM_FWD, M=64, K=1 << 20, N=64, s=1 << 20, acc_bits=32, ws_bytes=1 << 40, **big) == -6
-    # 2^24 tiles of one element clamped to 2^15: total up to 2^39
-    assert _gemm_rc(B.GEMM_FWD, M=16, K=1 << 24, N=16, s=1, acc_bits=16, ws_bytes=1 << 40, **big) == -5
+    # about 2^22 tiles of one element, each up to 2^14: total up to 2^36
+    assert _gemm_rc(B.GEMM_FWD, M=16, K=65535 * 64, N=16, s=1, acc_bits=16, ws_bytes=1 << 40, **big) == -5
 
 
 def test_unknown_kind():
@@ -288,3 +288,13 @@ def test_gemm_codes_requant_argument_errors():
         == E["HDQT_EINVAL_NULL"]
     assert lib.hdqt_gemm_requant(0, FAKE, FAKE, FAKE, 256, 128, 64, C.byref(p), None, FAKE, 1024, None) \
         == E["HDQT_EWORKSPACE"]
+
+
+def test_dimension_limit():
+    """A dimension above 65535 * 64 is refused: the grids could not hold it."""
+    p = _cparams()
+    lim = 65535 * 64
+    assert B.load().hdqt_workspace_size(0, lim, 64, 64, C.byref(p)) > 0
+    assert B.load().hdqt_workspace_size(0, lim + 1, 64, 64, C.byref(p)) == 0
+    assert _quant_rc(rows=lim + 1) == E["HDQT_EINVAL_DIM"]
+    assert _quant_rc(cols=lim + 64, had=64) == E["HDQT_EINVAL_DIM"]
