@@ -294,3 +294,20 @@ def test_requant_forward_resnet_conv_k1152():
     got = out.cpu().numpy()
     denom = np.maximum(np.abs(want_out), np.finfo(np.float32).tiny)
     assert np.all(np.abs(got.astype(np.float64) - want_out) <= RTOL * denom)
+
+
+@pytest.mark.parametrize("which", ["X", "G"])
+def test_quantize_dual_full_size_against_oracle(which):
+    """The two-axis kernels on the bench layer's activation (nearest) and gradient
+    (stochastic) tensors at full size: every code byte and both scales against the oracle."""
+    layer = workloads.resnet_conv_layer(256, 128, 128, 16, seed=0)
+    T = layer.X if which == "X" else layer.G
+    rnd = B.ROUND_NEAREST if which == "X" else B.ROUND_STOCHASTIC
+    op1, op0 = B.Operand(4, rnd, 1.0, 3), B.Operand(4, rnd, 1.0, 9)
+    c1, s1, c0, s0 = B.quantize_dual(dev(T), 64, op1, op0, seed=0x5eed)
+    torch.cuda.synchronize()
+    for axis, op, cg, sg in ((1, op1, c1, s1), (0, op0, c0, s0)):
+        print(f"{which} axis {axis}: oracle ...", flush=True)
+        codes, scale, _ = capi.quantize(T.numpy(), axis, 64, o_op(op), 0x5eed)
+        assert sg.cpu().numpy()[0] == scale
+        assert np.array_equal(cg.cpu().numpy(), capi.pack_codes(codes, 4)), f"{which} axis {axis}: codes differ"
