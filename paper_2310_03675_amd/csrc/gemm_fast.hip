@@ -6,6 +6,9 @@
 //
 // What differs from the generic kernel:
 //   * v_mfma_i32_32x32x32_i8: one MFMA consumes 32 contraction positions.
+//   * eight waves per 128 x 128 workgroup tile, each 64 rows x 32 columns: 106-124
+//     VGPRs, so four waves share a SIMD and fill each other's MFMA / LDS / barrier
+//     latencies (four waves of 64 x 64 need 168-198 VGPRs: two per SIMD).
 //   * Nibble unpack without sign extension: a code in the high nibble of a
 //     byte IS 16*code as int8, so (w << 4) & 0xF0F0F0F0 and w & 0xF0F0F0F0 give
 //     the even and the odd codes of a dword, each scaled by 16.  Both operands
@@ -32,7 +35,8 @@ typedef int v4i __attribute__((ext_vector_type(4)));
 typedef int v16i __attribute__((ext_vector_type(16)));
 typedef short v2s __attribute__((ext_vector_type(2)));
 
-constexpr int kThreads = 256;
+constexpr int kWaves = 8;             // waves per workgroup: 8 measured 3-7 % faster than 4 on the layer
+                                      // shapes and on 4096^3 (see the kernel)
 constexpr int BM = 128, BN = 128;
 constexpr int KS_LONG = 128;          // codes per LDS stage: 4 MFMA steps.  (Stages of 64 codes leave
                                       // room for three workgroups per CU instead of two; measured
@@ -89,19 +93,26 @@ __device__ __forceinline__ int clamp3(int v, int lo, int hi)
 // flight.  With gridDim.z = 1 a workgroup walks along a
 // whole row strip of the output, which is how short contractions (one or two
 // stages per tile) keep loads, MFMAs and stores overlapped.
-template <int EPI, int KS, bool STREAM>
-__global__ __launch_bounds__(kThreads, 2) void gemm_i4_kernel(GemmArgs g)
+template <int EPI, int KS, bool STREAM, int WAVES>
+__global__ __launch_bounds__(64 * WAVES, WAVES == 8 ? 4 : 2) void gemm_i4_kernel(GemmArgs g)
 {
+    // WAVES = 4: each wave a 64 x 64 quarter (2 x 2 MFMA blocks).  WAVES = 8: each wave
+    // 64 rows x 32 columns (2 x 1 MFMA blocks): half the accumulators per wave, so four
+    // waves fit a SIMD instead of two, at 1.5 LDS fragment reads per MFMA instead of 1.
+    constexpr int NTHREADS = 64 * WAVES;
+    constexpr int WN = WAVES / 2;         // waves side by side
+    constexpr int CS = 4 / WN;            // 32-column MFMA blocks per wave: 2 or 1
+    constexpr int WCOLS = 32 * CS;
     constexpr int NSTEP = KS / KSTEP;
     constexpr int LDP = KS + 16;          // LDS row pitch in bytes (int8 codes)
-    constexpr int UNITS = NSTEP / 2;      // 16-byte units per operand and thread: 128 rows * NSTEP / 256
+    constexpr int UNITS = 128 * NSTEP / NTHREADS;   // 16-byte units per operand and thread
     static_assert(EPI != EPI_SAT8_S64 || KS == KS_LONG, "a pair of 64-code tiles is one long stage");
     __shared__ __attribute__((aligned(16))) uint8_t As[2][BM][LDP];
     __shared__ __attribute__((aligned(16))) uint8_t Bs[2][BN][LDP];
 
     const int tid = threadIdx.x;
     const int lane = tid & 63, wave = tid >> 6;
-    const int wm = wave >> 1, wn = wave & 1;
+    const int wm = wave / WN, wn = wave % WN;
     const int64_t row0 = (int64_t)blockIdx.y * BM;
     const int n_ct = (int)((g.RB + BN - 1) / BN);
 
@@ -115,16 +126,16 @@ __global__ __launch_bounds__(kThreads, 2) void gemm_i4_kernel(GemmArgs g)
     const int steps_per_tile = (int)(g.s / KSTEP);
     const int lo = g.acc_lo_scaled, hi = g.acc_hi_scaled;
 
-    // loader mapping: unit u = tid + 256*i -> row u / NSTEP, k-step u % NSTEP
+    // loader mapping: unit u = tid + NTHREADS*i -> row u / NSTEP, k-step u % NSTEP
     const int lrow = tid / NSTEP, lks = tid % NSTEP;
-    constexpr int ROWS_PER_PASS = kThreads / NSTEP;
+    constexpr int ROWS_PER_PASS = NTHREADS / NSTEP;
 
-    v16i total[2][2];
-    v16i part[2][2];                  // EPI_GENERIC only
+    v16i total[2][CS];
+    v16i part[2][CS];                 // EPI_GENERIC only
 #pragma unroll
     for (int a = 0; a < 2; ++a)
 #pragma unroll
-        for (int c = 0; c < 2; ++c)
+        for (int c = 0; c < CS; ++c)
 #pragma unroll
             for (int r = 0; r < 16; ++r) { total[a][c][r] = 0; part[a][c][r] = 0; }
     const v16i zero = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
@@ -150,7 +161,7 @@ __global__ __launch_bounds__(kThreads, 2) void gemm_i4_kernel(GemmArgs g)
     };
 
     // ---- the multiply stream
-    const int lane_row = wm * 64 + 4 * (lane >> 5), lane_col = wn * 64 + (lane & 31);
+    const int lane_row = wm * 64 + 4 * (lane >> 5), lane_col = wn * WCOLS + (lane & 31);
     const uint32_t lane_off = (uint32_t)lane_row * (uint32_t)g.RB + (uint32_t)lane_col;
     int c_ct = blockIdx.z;
     int64_t c_k = k_begin;
@@ -176,18 +187,18 @@ __global__ __launch_bounds__(kThreads, 2) void gemm_i4_kernel(GemmArgs g)
 #pragma unroll
             for (int pr = 0; pr < (EPI == EPI_SAT8_S32 ? NSTEP / 2 : 1); ++pr) {
                 constexpr int SPT = (EPI == EPI_SAT8_S32) ? 1 : 2;      // steps per tile
-                v4i fa[2 * SPT][2], fb[2 * SPT][2];
+                v4i fa[2 * SPT][2], fb[2 * SPT][CS];
 #pragma unroll
                 for (int q = 0; q < 2 * SPT; ++q)
 #pragma unroll
                     for (int h = 0; h < 2; ++h) {
                         fa[q][h] = frag(As[buf], wm * 64 + h * 32, pr * 2 * SPT + q);
-                        fb[q][h] = frag(Bs[buf], wn * 64 + h * 32, pr * 2 * SPT + q);
+                        if (h < CS) fb[q][h] = frag(Bs[buf], wn * WCOLS + h * 32, pr * 2 * SPT + q);
                     }
 #pragma unroll
                 for (int a = 0; a < 2; ++a)
 #pragma unroll
-                    for (int c = 0; c < 2; ++c) {
+                    for (int c = 0; c < CS; ++c) {
                         v16i p0 = __builtin_amdgcn_mfma_i32_32x32x32_i8(fa[0][a], fb[0][c], zero, 0, 0, 0);
                         if (SPT == 2)
                             p0 = __builtin_amdgcn_mfma_i32_32x32x32_i8(fa[1][a], fb[1][c], p0, 0, 0, 0);
@@ -202,16 +213,16 @@ __global__ __launch_bounds__(kThreads, 2) void gemm_i4_kernel(GemmArgs g)
         } else {
 #pragma unroll
             for (int ks = 0; ks < NSTEP; ++ks) {
-                v4i fa[2], fb[2];
+                v4i fa[2], fb[CS];
 #pragma unroll
                 for (int h = 0; h < 2; ++h) {
                     fa[h] = frag(As[buf], wm * 64 + h * 32, ks);
-                    fb[h] = frag(Bs[buf], wn * 64 + h * 32, ks);
+                    if (h < CS) fb[h] = frag(Bs[buf], wn * WCOLS + h * 32, ks);
                 }
 #pragma unroll
                 for (int a = 0; a < 2; ++a)
 #pragma unroll
-                    for (int c = 0; c < 2; ++c)
+                    for (int c = 0; c < CS; ++c)
                         part[a][c] =
                             __builtin_amdgcn_mfma_i32_32x32x32_i8(fa[a], fb[c], part[a][c], 0, 0, 0);
                 if (++step_in_tile == steps_per_tile) {
@@ -219,7 +230,7 @@ __global__ __launch_bounds__(kThreads, 2) void gemm_i4_kernel(GemmArgs g)
 #pragma unroll
                     for (int a = 0; a < 2; ++a)
 #pragma unroll
-                        for (int c = 0; c < 2; ++c)
+                        for (int c = 0; c < CS; ++c)
 #pragma unroll
                             for (int r = 0; r < 16; ++r) {
                                 total[a][c][r] += clamp3(part[a][c][r], lo, hi);
@@ -239,7 +250,7 @@ __global__ __launch_bounds__(kThreads, 2) void gemm_i4_kernel(GemmArgs g)
 #pragma unroll
             for (int a = 0; a < 2; ++a)
 #pragma unroll
-                for (int c = 0; c < 2; ++c)
+                for (int c = 0; c < CS; ++c)
 #pragma unroll
                     for (int r = 0; r < 16; ++r) {
                         total[a][c][r] += clamp3(part[a][c][r], lo, hi);
@@ -257,7 +268,7 @@ __global__ __launch_bounds__(kThreads, 2) void gemm_i4_kernel(GemmArgs g)
 #pragma unroll
         for (int a = 0; a < 2; ++a)
 #pragma unroll
-            for (int c = 0; c < 2; ++c)
+            for (int c = 0; c < CS; ++c)
 #pragma unroll
                 for (int r = 0; r < 16; ++r) {
                     const int rr = a * 32 + 8 * (r >> 2) + (r & 3);
@@ -328,16 +339,16 @@ hipError_t launch_gemm_fast(const GemmArgs& g_in, hipStream_t stream)
     }
     const dim3 grid((unsigned)g.splits, (unsigned)n_rt, (unsigned)gx);
     ProfileScope ps(g.profile_tag ? K_GEMM_I4_FWD + (g.profile_tag - 1) : K_GEMM_I4, stream);
-    const dim3 block(kThreads);
+    const dim3 block(64 * kWaves);
     if (s32) {
-        if (g.stream_out) hipLaunchKernelGGL((gemm_i4_kernel<EPI_SAT8_S32, KS_LONG, true>), grid, block, 0, stream, g);
-        else hipLaunchKernelGGL((gemm_i4_kernel<EPI_SAT8_S32, KS_LONG, false>), grid, block, 0, stream, g);
+        if (g.stream_out) hipLaunchKernelGGL((gemm_i4_kernel<EPI_SAT8_S32, KS_LONG, true, kWaves>), grid, block, 0, stream, g);
+        else hipLaunchKernelGGL((gemm_i4_kernel<EPI_SAT8_S32, KS_LONG, false, kWaves>), grid, block, 0, stream, g);
     } else if (sat8_path(g)) {
-        if (g.stream_out) hipLaunchKernelGGL((gemm_i4_kernel<EPI_SAT8_S64, KS_LONG, true>), grid, block, 0, stream, g);
-        else hipLaunchKernelGGL((gemm_i4_kernel<EPI_SAT8_S64, KS_LONG, false>), grid, block, 0, stream, g);
+        if (g.stream_out) hipLaunchKernelGGL((gemm_i4_kernel<EPI_SAT8_S64, KS_LONG, true, kWaves>), grid, block, 0, stream, g);
+        else hipLaunchKernelGGL((gemm_i4_kernel<EPI_SAT8_S64, KS_LONG, false, kWaves>), grid, block, 0, stream, g);
     } else {
-        if (g.stream_out) hipLaunchKernelGGL((gemm_i4_kernel<EPI_GENERIC, KS_LONG, true>), grid, block, 0, stream, g);
-        else hipLaunchKernelGGL((gemm_i4_kernel<EPI_GENERIC, KS_LONG, false>), grid, block, 0, stream, g);
+        if (g.stream_out) hipLaunchKernelGGL((gemm_i4_kernel<EPI_GENERIC, KS_LONG, true, kWaves>), grid, block, 0, stream, g);
+        else hipLaunchKernelGGL((gemm_i4_kernel<EPI_GENERIC, KS_LONG, false, kWaves>), grid, block, 0, stream, g);
     }
     return hipGetLastError();
 }
