@@ -32,8 +32,8 @@ HBM_PEAK_GBPS = 8000.0          # MI355X HBM3E
 # profiles/bench_resnet_k1152_hbm_traffic.md (per-launch average over the tensors a
 # kernel family runs on); bench.py cannot collect counters itself.
 MEASURED_TRAFFIC = {
-    "fwht_dual_absmax_batch": 336.4e6, "fwht_dual_quant_batch": 382.4e6, "fwht_dual_quant_G": 42.5e6,
-    "gemm_i4_fwd": 74.6e6, "gemm_i4_bwd_input": 307.2e6, "gemm_i4_bwd_weight": 99.7e6,
+    "fwht_dual_absmax_batch": 336.4e6, "fwht_dual_quant_batch": 382.6e6, "fwht_dual_quant_G": 42.5e6,
+    "gemm_i4_fwd": 74.4e6, "gemm_i4_bwd_input": 307.3e6, "gemm_i4_bwd_weight": 98.0e6,
 }
 INT8_MFMA_PEAK_TOPS = 5000.0    # MI355X dense int8
 
