@@ -29,6 +29,9 @@ class LayerConfig:
     clip_fwd: float = 1.0
     stochastic_grad: bool = True
     need_input_grad: bool = True
+    # when set to a dict, every matmul of the layer leaves its operands and results there
+    # (X, W, Z in the forward pass; G, dX, dW in the backward pass) for inspection
+    capture: Optional[dict] = field(default=None, repr=False, compare=False)
 
     def params(self, kind: int, step: int = 0) -> B.Params:
         tid = lambda role: 16 * self.layer_id + {"X": 0, "W": 1, "G": 2}[role] + 4 * kind
@@ -58,6 +61,8 @@ class HdqtMatmul(torch.autograd.Function):
         ctx.save_for_backward(W, saved)
         ctx.cfg, ctx.step, ctx.K = cfg, step, X.shape[1]
         ctx.want_dx = cfg.need_input_grad and X.requires_grad
+        if cfg.capture is not None:
+            cfg.capture.update(X=X.detach(), W=W.detach().clone(), Z=Z.detach(), step=step)
         return Z
 
     @staticmethod
@@ -66,7 +71,10 @@ class HdqtMatmul(torch.autograd.Function):
         cfg = ctx.cfg
         pi = cfg.params(B.GEMM_BWD_INPUT, ctx.step) if ctx.want_dx else None
         pw = cfg.params(B.GEMM_BWD_WEIGHT, ctx.step)
-        dX, dW = B.layer_bwd(G.contiguous(), W, saved, ctx.K, pi, pw)
+        G = G.contiguous()
+        dX, dW = B.layer_bwd(G, W, saved, ctx.K, pi, pw)
+        if cfg.capture is not None:
+            cfg.capture.update(G=G.detach(), dX=dX, dW=dW)
         return dX, dW, None, None
 
 
@@ -95,15 +103,15 @@ class HdqtLinear(torch.nn.Module):
 
 
 class HdqtConv2d(torch.nn.Module):
-    """3x3-style convolution (stride 1) as the paper runs it: the activation is unfolded
-    (im2col, column index = channel * kh * kw + tap) and the products of the forward and
-    the backward pass are the quantized matmuls above.  The unfolding and folding are
-    PyTorch's; only the matmuls are the library's."""
+    """Convolution as the paper runs it: the activation is unfolded (im2col, column index =
+    channel * kh * kw + tap) and the products of the forward and the backward pass are the
+    quantized matmuls above.  The unfolding and folding are PyTorch's; only the matmuls are
+    the library's."""
 
     def __init__(self, in_channels: int, out_channels: int, kernel_size: int = 3, padding: int = 1,
-                 cfg: Optional[LayerConfig] = None, device=None):
+                 stride: int = 1, cfg: Optional[LayerConfig] = None, device=None):
         super().__init__()
-        self.k, self.pad = kernel_size, padding
+        self.k, self.pad, self.stride = kernel_size, padding, stride
         self.cfg = cfg or LayerConfig()
         fan_in = in_channels * kernel_size * kernel_size
         w = torch.empty(fan_in, out_channels, device=device)
@@ -113,8 +121,10 @@ class HdqtConv2d(torch.nn.Module):
 
     def forward(self, x):
         Bn, Cin, H, W = x.shape
-        Ho, Wo = H + 2 * self.pad - self.k + 1, W + 2 * self.pad - self.k + 1
-        cols = torch.nn.functional.unfold(x, kernel_size=self.k, padding=self.pad)   # [B, C*k*k, Ho*Wo]
+        Ho = (H + 2 * self.pad - self.k) // self.stride + 1
+        Wo = (W + 2 * self.pad - self.k) // self.stride + 1
+        cols = torch.nn.functional.unfold(x, kernel_size=self.k, padding=self.pad,
+                                          stride=self.stride)                 # [B, C*k*k, Ho*Wo]
         X = cols.transpose(1, 2).reshape(Bn * Ho * Wo, Cin * self.k * self.k)
         Z = HdqtMatmul.apply(X, self.weight, self.cfg, self.step)
         if self.training:
