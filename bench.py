@@ -241,7 +241,8 @@ def main():
             if name[-2:] in ("_X", "_W", "_G"):
                 tensors = [name[-1]]
             elif name.endswith("_batch"):
-                tensors = ["X", "W", "G"] if absmax else ["X", "W"]
+                # G's codes come from the same launch unless it ran on its own
+                tensors = ["X", "W"] if (not absmax and "fwht_dual_quant_G" in kern) else ["X", "W", "G"]
             else:
                 tensors = seen[fam]
             bytes_launch = per_elem * sum(elems[t] for t in tensors) / per_step

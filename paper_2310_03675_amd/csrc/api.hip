@@ -702,13 +702,19 @@ int hdqt_layer_step(const float* X, const float* W, const float* G, float* Z, fl
             // and W's codes ride along with X's when the rounding modes agree
             e = hdqt::launch_dual_pass1(dX3, 3, stream);
             if (e != hipSuccess) return hip_fail(e);
-            if (dx.st_row == dw.st_row && dx.st_col == dw.st_col) {
-                e = hdqt::launch_dual_pass2(dX3, 2, stream);
+            // G first: its tiles take longest (two random streams) and start while the chip fills
+            const hdqt::DualArgs gxw[3] = {dg, dx, dw};
+            if (hdqt::dual_pass2_batchable(gxw, 3)) {
+                e = hdqt::launch_dual_pass2(gxw, 3, stream);
             } else {
-                e = hdqt::launch_dual_pass2(&dx, 1, stream);
-                if (e == hipSuccess) e = hdqt::launch_dual_pass2(&dw, 1, stream);
+                if (hdqt::dual_pass2_batchable(dX3, 2)) {
+                    e = hdqt::launch_dual_pass2(dX3, 2, stream);
+                } else {
+                    e = hdqt::launch_dual_pass2(&dx, 1, stream);
+                    if (e == hipSuccess) e = hdqt::launch_dual_pass2(&dw, 1, stream);
+                }
+                if (e == hipSuccess) e = hdqt::launch_dual_pass2(&dg, 1, stream);
             }
-            if (e == hipSuccess) e = hdqt::launch_dual_pass2(&dg, 1, stream);
             if (e != hipSuccess) return hip_fail(e);
             g_done = true;
         }

@@ -98,6 +98,7 @@ constexpr int kMaxDualBatch = 3;
 // the two passes of the two-axis quantization, each for up to kMaxDualBatch tensors in one launch
 hipError_t launch_dual_pass1(const DualArgs* qs, int n, hipStream_t stream);
 hipError_t launch_dual_pass2(const DualArgs* qs, int n, hipStream_t stream);
+bool dual_pass2_batchable(const DualArgs* qs, int n);
 // zero a[0, na) and b[0, nb) (b may be null) in one launch
 hipError_t launch_zero2(uint32_t* a, int64_t na, uint32_t* b, int64_t nb, hipStream_t stream);
 // sum the `splits` slices of `partial` ([splits, count]); the totals go to acc_out

@@ -354,7 +354,15 @@ struct DualBatch {
 // One tile per wave and no register prefetch: what hides the memory latency is
 // the number of resident waves, and a second tile in registers halves it
 // (measured: 67 us against 85 us for pass 1 of a 65536 x 1152 tensor).
-template <bool QUANT, bool ST_ROW, bool ST_COL, bool N64>
+//
+// ROUND selects the rounding of pass 2: bit 0 = stochastic along the rows, bit 1 =
+// along the columns; kRoundPerTensor = every tensor of the launch is either nearest on
+// both axes or stochastic on both, told by its own flags (a layer's X and W next to
+// its G), so that the short, arithmetic-heavy stochastic tensor shares a launch with
+// the long, memory-bound ones instead of running after them on a half-empty chip.
+constexpr int kRoundPerTensor = 4;
+
+template <bool QUANT, int ROUND, bool N64>
 __global__ __launch_bounds__(kThreads) void fwht_dual_kernel(DualBatch b)
 {
     __shared__ float red[kThreads / kWave][2];
@@ -385,7 +393,14 @@ __global__ __launch_bounds__(kThreads) void fwht_dual_kernel(DualBatch b)
         const Scaling s_row = load_scaling(q.meta_row, q.clip_row, q.b_row);
         const Scaling s_col = load_scaling(q.meta_col, q.clip_col, q.b_col);
         dual_set_scaling(x, q, s_row, s_col, local == 0);
-        if (live) dual_codes<ST_ROW, ST_COL>(t, x, row0, col0);
+        if constexpr (ROUND == kRoundPerTensor) {
+            if (live) {
+                if (q.st_row) dual_codes<true, true>(t, x, row0, col0);
+                else dual_codes<false, false>(t, x, row0, col0);
+            }
+        } else {
+            if (live) dual_codes<(ROUND & 1) != 0, (ROUND & 2) != 0>(t, x, row0, col0);
+        }
     } else {
         float amax_row = 0.0f, amax_col = 0.0f;
         if (live) dual_absmax(t, x, row0, col0, amax_row, amax_col);
@@ -440,34 +455,47 @@ hipError_t launch_dual_pass1(const DualArgs* qs, int n, hipStream_t stream)
     ProfileScope ps(id, stream);
     const dim3 grid((unsigned)b.first[n]), block(kThreads);
     if (all_order_64(qs, n))
-        hipLaunchKernelGGL((fwht_dual_kernel<false, false, false, true>), grid, block, 0, stream, b);
+        hipLaunchKernelGGL((fwht_dual_kernel<false, 0, true>), grid, block, 0, stream, b);
     else
-        hipLaunchKernelGGL((fwht_dual_kernel<false, false, false, false>), grid, block, 0, stream, b);
+        hipLaunchKernelGGL((fwht_dual_kernel<false, 0, false>), grid, block, 0, stream, b);
     return hipGetLastError();
 }
 
-// Pass 2 (both code sets) of n tensors in one launch; the tensors of a launch share
-// their rounding modes (those select the kernel instance).
+// Whether the tensors can share a pass-2 launch: same rounding modes everywhere, or each
+// tensor nearest on both axes or stochastic on both.
+bool dual_pass2_batchable(const DualArgs* qs, int n)
+{
+    bool same = true, paired = true;
+    for (int k = 0; k < n; ++k) {
+        if (qs[k].st_row != qs[0].st_row || qs[k].st_col != qs[0].st_col) same = false;
+        if (qs[k].st_row != qs[k].st_col) paired = false;
+    }
+    return same || paired;
+}
+
+// Pass 2 (both code sets) of n tensors in one launch (see dual_pass2_batchable).
 hipError_t launch_dual_pass2(const DualArgs* qs, int n, hipStream_t stream)
 {
     DualBatch b;
-    if (!make_batch(qs, n, &b)) return hipErrorInvalidValue;
+    if (!make_batch(qs, n, &b) || !dual_pass2_batchable(qs, n)) return hipErrorInvalidValue;
+    bool same = true;
     for (int k = 1; k < n; ++k)
-        if (qs[k].st_row != qs[0].st_row || qs[k].st_col != qs[0].st_col) return hipErrorInvalidValue;
+        if (qs[k].st_row != qs[0].st_row || qs[k].st_col != qs[0].st_col) same = false;
     const int id = n > 1 ? K_DUAL_QUANT_BATCH
                          : (qs[0].profile_tag ? K_DUAL_QUANT_X + (qs[0].profile_tag - 1) : K_DUAL_QUANT);
     ProfileScope ps(id, stream);
     const dim3 grid((unsigned)b.first[n]), block(kThreads);
     const bool n64 = all_order_64(qs, n);
-#define HDQT_LAUNCH_PASS2(SR, SC)                                                                     \
-    do {                                                                                              \
-        if (n64) hipLaunchKernelGGL((fwht_dual_kernel<true, SR, SC, true>), grid, block, 0, stream, b); \
-        else hipLaunchKernelGGL((fwht_dual_kernel<true, SR, SC, false>), grid, block, 0, stream, b);   \
+#define HDQT_LAUNCH_PASS2(ROUND)                                                                     \
+    do {                                                                                            \
+        if (n64) hipLaunchKernelGGL((fwht_dual_kernel<true, ROUND, true>), grid, block, 0, stream, b); \
+        else hipLaunchKernelGGL((fwht_dual_kernel<true, ROUND, false>), grid, block, 0, stream, b);  \
     } while (0)
-    if (qs[0].st_row && qs[0].st_col) HDQT_LAUNCH_PASS2(true, true);
-    else if (qs[0].st_row) HDQT_LAUNCH_PASS2(true, false);
-    else if (qs[0].st_col) HDQT_LAUNCH_PASS2(false, true);
-    else HDQT_LAUNCH_PASS2(false, false);
+    if (!same) HDQT_LAUNCH_PASS2(kRoundPerTensor);
+    else if (qs[0].st_row && qs[0].st_col) HDQT_LAUNCH_PASS2(3);
+    else if (qs[0].st_row) HDQT_LAUNCH_PASS2(1);
+    else if (qs[0].st_col) HDQT_LAUNCH_PASS2(2);
+    else HDQT_LAUNCH_PASS2(0);
 #undef HDQT_LAUNCH_PASS2
     return hipGetLastError();
 }
