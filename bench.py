@@ -32,8 +32,8 @@ HBM_PEAK_GBPS = 8000.0          # MI355X HBM3E
 # profiles/bench_resnet_k1152_hbm_traffic.md (per-launch average over the tensors a
 # kernel family runs on); bench.py cannot collect counters itself.
 MEASURED_TRAFFIC = {
-    "fwht_dual_absmax_batch": 336.4e6, "fwht_dual_quant_batch": 382.6e6, "fwht_dual_quant_G": 42.5e6,
-    "gemm_i4_fwd": 74.4e6, "gemm_i4_bwd_input": 307.3e6, "gemm_i4_bwd_weight": 98.0e6,
+    "fwht_dual_absmax_batch": 336.4e6, "fwht_dual_quant_batch": 421.7e6,
+    "gemm_i4_fwd": 74.4e6, "gemm_i4_bwd_input": 307.2e6, "gemm_i4_bwd_weight": 98.2e6,
 }
 INT8_MFMA_PEAK_TOPS = 5000.0    # MI355X dense int8
 
@@ -109,6 +109,8 @@ def main():
                          "launching from the host, the step is bound by its kernels)")
     ap.add_argument("--no-large-quantize", action="store_true",
                     help="skip the 1 GiB hdqt_quantize measurement ('quantize_1GiB')")
+    ap.add_argument("--no-square", action="store_true",
+                    help="skip the 4096^3 matmul measurement ('gemm_square_4096')")
     ap.add_argument("--requant", action="store_true",
                     help="also time the forward matmul under the second reading of the accumulator "
                          "(hdqt_gemm_requant) and report it as 'requant_fwd'")
@@ -312,6 +314,36 @@ def main():
             "pass2_GBps": 4.5 * elems_big / p2 / 1e9, "pass2_frac_of_hbm_peak": 4.5 * elems_big / p2 / 1e9 / HBM_PEAK_GBPS,
             "both_GBps": 8.5 * elems_big / (p1 + p2) / 1e9}
         del big
+    if not args.no_square:
+        # The integer matmul alone where the matrix pipe is the roofline: 4096^3 on the codes
+        # of the square sweep's operands (N(0,1) with 1 % outliers at +-20, Hadamard block 64,
+        # 4-bit nearest), 8-bit accumulators, tiles of 32 and 64.
+        from paper_2310_03675_amd import workloads
+        sq = workloads.square_layer(4096, seed=0)
+        opn = B.Operand(4, B.ROUND_NEAREST, 1.0, 0)
+        qa, sa = B.quantize(sq.X.to(dev), 1, 64, opn, 0)
+        qb, sb = B.quantize(sq.W.to(dev), 0, 64, opn, 0)
+        o_sq = torch.empty((4096, 4096), dtype=torch.float32, device=dev)
+        ws_sq = torch.empty(max(B.load().hdqt_gemm_codes_workspace_size(4096, 4096, 4096, 32), 256),
+                            dtype=torch.uint8, device=dev)
+        line["gemm_square_4096"] = {}
+        for s_sq in (32, 64):
+            for _ in range(3):
+                B.gemm_codes(qa, qb, 4, 4, sa, sb, 4096, 64, 8, s_sq, want_acc=False, out=o_sq, workspace=ws_sq)
+            torch.cuda.synchronize()
+            B.profile_enable(True)
+            B.profile_collect()
+            for _ in range(10):
+                B.gemm_codes(qa, qb, 4, 4, sa, sb, 4096, 64, 8, s_sq, want_acc=False, out=o_sq, workspace=ws_sq)
+            torch.cuda.synchronize()
+            B.profile_enable(False)
+            kg = B.profile_collect()
+            us = sum(v[1] for k_, v in kg.items() if k_.startswith("gemm") or k_ == "reduce_splits") * 1e3 / 10
+            tops = 2.0 * 4096.0 ** 3 / us / 1e6
+            line["gemm_square_4096"][f"s{s_sq}"] = {
+                "us": us, "bound": "mfma", "achieved": tops, "peak": INT8_MFMA_PEAK_TOPS, "unit": "TOP/s",
+                "frac": tops / INT8_MFMA_PEAK_TOPS}
+        del sq, qa, qb, o_sq, ws_sq
     if args.requant:
         k = kinds[0]
         need = B.load().hdqt_gemm_requant_workspace_size(k, M, K, N, prm[k].c())

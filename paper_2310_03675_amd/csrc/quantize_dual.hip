@@ -363,12 +363,8 @@ struct DualBatch {
 constexpr int kRoundPerTensor = 4;
 
 template <bool QUANT, int ROUND, bool N64>
-__global__ __launch_bounds__(kThreads) void fwht_dual_kernel(DualBatch b)
+__device__ __forceinline__ void dual_block(const DualBatch& b, int k, float (*red)[2])
 {
-    __shared__ float red[kThreads / kWave][2];
-
-    int k = 0;
-    while (k + 1 < b.n && (int)blockIdx.x >= b.first[k + 1]) ++k;
     const DualArgs& q = b.t[k];
     const int count = b.first[k + 1] - b.first[k];
     // pass 2 walks a tensor from its end to its start: it begins with what pass 1
@@ -393,18 +389,28 @@ __global__ __launch_bounds__(kThreads) void fwht_dual_kernel(DualBatch b)
         const Scaling s_row = load_scaling(q.meta_row, q.clip_row, q.b_row);
         const Scaling s_col = load_scaling(q.meta_col, q.clip_col, q.b_col);
         dual_set_scaling(x, q, s_row, s_col, local == 0);
-        if constexpr (ROUND == kRoundPerTensor) {
-            if (live) {
-                if (q.st_row) dual_codes<true, true>(t, x, row0, col0);
-                else dual_codes<false, false>(t, x, row0, col0);
-            }
-        } else {
-            if (live) dual_codes<(ROUND & 1) != 0, (ROUND & 2) != 0>(t, x, row0, col0);
-        }
+        if (live) dual_codes<(ROUND & 1) != 0, (ROUND & 2) != 0>(t, x, row0, col0);
     } else {
         float amax_row = 0.0f, amax_col = 0.0f;
         if (live) dual_absmax(t, x, row0, col0, amax_row, amax_col);
         block_atomic_max2(amax_row, amax_col, q.meta_row, q.meta_col, red, (uint32_t)local);
+    }
+}
+
+template <bool QUANT, int ROUND, bool N64>
+__global__ __launch_bounds__(kThreads) void fwht_dual_kernel(DualBatch b)
+{
+    __shared__ float red[kThreads / kWave][2];
+
+    int k = 0;
+    while (k + 1 < b.n && (int)blockIdx.x >= b.first[k + 1]) ++k;
+    if constexpr (ROUND == kRoundPerTensor) {
+        // two complete bodies, chosen per workgroup: sharing anything between them
+        // (one load, one setup) lets the compiler keep both paths' registers alive
+        if (b.t[k].st_row) dual_block<QUANT, 3, N64>(b, k, red);
+        else dual_block<QUANT, 0, N64>(b, k, red);
+    } else {
+        dual_block<QUANT, ROUND, N64>(b, k, red);
     }
 }
 
