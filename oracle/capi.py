@@ -210,6 +210,23 @@ def dequantize(acc, scaleA, scaleB, n: int) -> np.ndarray:
     return out
 
 
+def bf16_bits(x) -> np.ndarray:
+    """binary32 values -> bfloat16 bit patterns (uint16), nearest, ties to even."""
+    x = np.ascontiguousarray(x, dtype=np.float32)
+    f = lib().orc_bf16_bits
+    f.restype, f.argtypes = C.c_uint16, [C.c_float]
+    return np.array([f(float(v)) for v in x.ravel()], dtype=np.uint16).reshape(x.shape)
+
+
+def dequantize_bf16(acc, scaleA, scaleB, n: int) -> np.ndarray:
+    """Step 6 with the narrow output: uint16 bfloat16 patterns."""
+    acc = np.ascontiguousarray(acc, dtype=np.int32)
+    out = np.empty(acc.shape, dtype=np.uint16)
+    lib().orc_dequantize_bf16(_p(acc, C.c_int32), C.c_int64(acc.size), C.c_float(scaleA),
+                              C.c_float(scaleB), C.c_int(n), _p(out, C.c_uint16))
+    return out
+
+
 def gemm_shapes(kind: int, M: int, K: int, N: int):
     """-> (RA, RB, D): output is [RA, RB], contraction length D."""
     return {FWD: (M, N, K), BWD_INPUT: (M, K, N), BWD_WEIGHT: (K, N, M)}[kind]

@@ -33,6 +33,10 @@
  *   5'. second reading of step 5 (orc_tiled_matmul_requant): every tile's
  *                     partial-sum tensor goes through Q with a bits and its own
  *                     max, and the tile results are added
+ *   6'. narrow output (orc_dequantize_bf16, an extension that is not in the
+ *                     paper): step 6's binary32 value rounded to bfloat16,
+ *                     nearest, ties to even; pinned by hand-built ties and a
+ *                     library conversion
  *
  * Parity pins live in tests/ (H H^T = n I, scipy's Hadamard matrix, fp64
  * transform, grid inputs with known codes, hand-computed saturation cases,
@@ -364,6 +368,30 @@ void orc_dequantize(const int32_t *acc, int64_t count, float scaleA, float scale
     float dq = orc_dequant_factor(scaleA, scaleB, n_eff);
     for (int64_t p = 0; p < count; ++p)
         out[p] = (float)acc[p] * dq;
+}
+
+/* Narrow output (an engineering extension, not a step of the paper, whose layers hand
+ * binary32 on): the dequantized binary32 value of step 6 rounded once more, to bfloat16
+ * (1 sign, 8 exponent, 7 fraction bits: the upper half of a binary32), round to nearest,
+ * ties to even.  Returned as the 16-bit pattern.  Finite inputs; a value beyond the
+ * largest finite bfloat16 rounds to infinity, as IEEE rounding prescribes. */
+uint16_t orc_bf16_bits(float x)
+{
+    uint32_t u;
+    memcpy(&u, &x, sizeof u);
+    uint32_t keep = u >> 16;      /* sign, exponent, 7 fraction bits */
+    uint32_t rest = u & 0xFFFFu;  /* the 16 fraction bits that go */
+    if (rest > 0x8000u || (rest == 0x8000u && (keep & 1u)))
+        keep += 1u; /* magnitude up by one unit; a carry into the exponent is the right result */
+    return (uint16_t)keep;
+}
+
+void orc_dequantize_bf16(const int32_t *acc, int64_t count, float scaleA, float scaleB, int n_eff,
+                         uint16_t *out)
+{
+    float dq = orc_dequant_factor(scaleA, scaleB, n_eff);
+    for (int64_t p = 0; p < count; ++p)
+        out[p] = orc_bf16_bits((float)acc[p] * dq);
 }
 
 /* ------------------------------------------------------------------ */

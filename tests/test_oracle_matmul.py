@@ -280,3 +280,53 @@ def test_requant_dequantization():
     out = capi.dequantize_requant(acc, np.float32(0.5), np.float32(0.25), 64, 8)
     f = np.float32(np.float32(np.float32(0.5) * np.float32(0.25)) * np.float32(1 / 64)) * np.float32(2.0 ** -7)
     assert np.array_equal(out, (acc.astype(np.float32) * f).astype(np.float32))
+
+
+# ---------------------------------------------------------------- narrow (bfloat16) output
+
+def test_bf16_narrowing_hand_cases():
+    """Values whose bfloat16 neighbours are known by construction.  bfloat16 has 7 fraction
+    bits, so 1 + 2^-8 is exactly half way between 1 and 1 + 2^-7 and goes to the even one
+    (1.0); 1 + 3*2^-8 is half way between 1 + 2^-7 (odd) and 1 + 2^-6 (even) and goes up."""
+    cases = [
+        (1.0, 0x3F80),
+        (1.0 + 2.0 ** -8, 0x3F80),                  # tie, down to even
+        (1.0 + 2.0 ** -8 + 2.0 ** -20, 0x3F81),     # just above the tie
+        (1.0 + 3 * 2.0 ** -8, 0x3F82),              # tie, up to even
+        (1.0 + 2.0 ** -7, 0x3F81),                  # representable
+        (-(1.0 + 2.0 ** -8), 0xBF80),               # sign-symmetric
+        (2.0 - 2.0 ** -9, 0x4000),                  # rounds up into the next binade
+        (0.0, 0x0000),
+        (2.0 ** -130, 0x0008),                      # subnormal, representable (2^-133 is the unit)
+    ]
+    xs = np.array([c[0] for c in cases], dtype=np.float32)
+    assert [int(v) for v in capi.bf16_bits(xs)] == [c[1] for c in cases]
+
+
+def test_bf16_narrowing_against_library_conversion_and_error_bound():
+    """Random and adversarial binary32 values against PyTorch's float32 -> bfloat16
+    conversion (a library routine for the same IEEE rounding), and the half-unit bound."""
+    import torch
+    rng = np.random.default_rng(3)
+    x = np.concatenate([
+        rng.standard_normal(4000).astype(np.float32) * np.float32(1e-3),
+        (rng.standard_normal(2000) * 1e4).astype(np.float32),
+        # every tie pattern around a few exponents: fraction bits 0x8000 below the cut
+        (np.arange(0x3F800000, 0x3F800000 + 256 * 0x10000, 0x8000, dtype=np.uint32)).view(np.float32),
+        np.array([3.3895314e38, -3.3895314e38, 1e-40, -1e-40], dtype=np.float32),
+    ])
+    got = capi.bf16_bits(x)
+    want = torch.from_numpy(x.copy()).to(torch.bfloat16).view(torch.int16).numpy().view(np.uint16)
+    assert np.array_equal(got, want)
+    back = (got.astype(np.uint32) << 16).view(np.float32).astype(np.float64)
+    fin = np.isfinite(back)
+    ulp = 2.0 ** (np.floor(np.log2(np.maximum(np.abs(x[fin].astype(np.float64)), 2.0 ** -126))) - 7)
+    assert np.all(np.abs(back[fin] - x[fin]) <= 0.5 * ulp)
+
+
+def test_dequantize_bf16_is_narrowing_of_the_fp32_output():
+    rng = np.random.default_rng(4)
+    acc = rng.integers(-5000, 5000, size=(37, 19)).astype(np.int32)
+    sA, sB, n = np.float32(0.0123), np.float32(3.1e-4), 64
+    full = capi.dequantize(acc, sA, sB, n)
+    assert np.array_equal(capi.dequantize_bf16(acc, sA, sB, n), capi.bf16_bits(full))
