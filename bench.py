@@ -344,6 +344,33 @@ def main():
                 "us": us, "bound": "mfma", "achieved": tops, "peak": INT8_MFMA_PEAK_TOPS, "unit": "TOP/s",
                 "frac": tops / INT8_MFMA_PEAK_TOPS}
         del sq, qa, qb, o_sq, ws_sq
+        # The input gradient with its output narrowed to bfloat16 (hdqt_gemm_codes_bf16 on the
+        # layer's own codes): the fp32 matmul is bound by the 4*M*K bytes it writes, this one
+        # writes half of them.  Not part of `value`: the step hands fp32 on, as the paper does.
+        opg = B.Operand(4, B.ROUND_STOCHASTIC, 1.0, 6)
+        qg, sg = B.quantize(G, 1, n, opg, 0)
+        qw, sw = B.quantize(W, 1, n, opn, 0)
+        line["bwd_input_bf16"] = {}
+        for tag, bf in (("fp32", False), ("bf16", True)):
+            o_dx = torch.empty((M, K), dtype=torch.bfloat16 if bf else torch.float32, device=dev)
+            for _ in range(3):
+                B.gemm_codes(qg, qw, 4, 4, sg, sw, N, n, args.acc_bits, args.s, want_acc=False, out=o_dx, bf16=bf)
+            torch.cuda.synchronize()
+            B.profile_enable(True)
+            B.profile_collect()
+            for _ in range(10):
+                B.gemm_codes(qg, qw, 4, 4, sg, sw, N, n, args.acc_bits, args.s, want_acc=False, out=o_dx, bf16=bf)
+            torch.cuda.synchronize()
+            B.profile_enable(False)
+            kg = B.profile_collect()
+            us = sum(v[1] for k_, v in kg.items() if k_.startswith("gemm")) * 1e3 / 10
+            nbytes = 0.5 * (M * N + K * N) + (2.0 if bf else 4.0) * M * K
+            line["bwd_input_bf16"][tag] = {"us": us, "bound": "hbm", "achieved": nbytes / us / 1e3,
+                                           "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                                           "frac": nbytes / us / 1e3 / HBM_PEAK_GBPS,
+                                           "algorithmic_bytes_per_launch": nbytes}
+            del o_dx
+        del qg, qw
     if args.requant:
         k = kinds[0]
         need = B.load().hdqt_gemm_requant_workspace_size(k, M, K, N, prm[k].c())

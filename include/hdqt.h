@@ -189,6 +189,19 @@ int hdqt_gemm_codes(const void *qA, const void *qB, int bA, int bB, const float 
                     size_t workspace_bytes, void *stream);
 
 /*
+ * The same matmul with a narrow output (not a step of the paper, whose layers hand
+ * fp32 on; it halves what the input gradient of a wide layer writes, which is the one
+ * thing that bounds that matmul): out[i,j] is the fp32 value above rounded to
+ * bfloat16 (nearest, ties to even) and stored as its 16-bit pattern.
+ *   out     bfloat16 [RA, RB] (device, 16-byte aligned, may be NULL if acc_out is given)
+ * Everything else, the workspace included, as for hdqt_gemm_codes.
+ */
+int hdqt_gemm_codes_bf16(const void *qA, const void *qB, int bA, int bB, const float *scaleA,
+                         const float *scaleB, int64_t RA, int64_t RB, int64_t D, int n_eff,
+                         int acc_bits, int64_t s, uint16_t *out, int32_t *acc_out,
+                         void *workspace, size_t workspace_bytes, void *stream);
+
+/*
  * The second reading of "tiled quantization" (Methodology: tiles of size s reduce
  * the partial sums an a-bit accumulator has to hold): instead of a saturating
  * register, every tile's partial-sum tensor goes through the paper's quantizer Q
@@ -230,6 +243,11 @@ int hdqt_gemm_bwd_input(const float *G, const float *W, float *dX, int64_t M, in
 int hdqt_gemm_bwd_weight(const float *X, const float *G, float *dW, int64_t M, int64_t K,
                          int64_t N, const hdqt_params_t *params, int32_t *acc_out,
                          void *workspace, size_t workspace_bytes, void *stream);
+/* hdqt_gemm_bwd_input with dX narrowed to bfloat16 (see hdqt_gemm_codes_bf16); same
+ * workspace, same errors. */
+int hdqt_gemm_bwd_input_bf16(const float *G, const float *W, uint16_t *dX, int64_t M, int64_t K,
+                             int64_t N, const hdqt_params_t *params, int32_t *acc_out,
+                             void *workspace, size_t workspace_bytes, void *stream);
 
 /*
  * All three matmuls of one layer's training step in one call (Methodology: every

@@ -27,7 +27,8 @@ EXPORTED = [
     "hdqt_gemm_codes_workspace_size", "hdqt_layer_saved_size", "hdqt_layer_fwd_workspace_size",
     "hdqt_layer_fwd", "hdqt_layer_bwd_workspace_size", "hdqt_layer_bwd",
     "hdqt_gemm_codes_requant_workspace_size", "hdqt_gemm_codes_requant",
-    "hdqt_gemm_requant_workspace_size", "hdqt_gemm_requant",
+    "hdqt_gemm_requant_workspace_size", "hdqt_gemm_requant", "hdqt_gemm_codes_bf16",
+    "hdqt_gemm_bwd_input_bf16",
 ]
 
 
@@ -140,7 +141,9 @@ def load() -> C.CDLL:
     lib.hdqt_gemm_codes.restype = i32
     lib.hdqt_gemm_codes.argtypes = [vp, vp, i32, i32, vp, vp, i64, i64, i64, i32, i32, i64, vp, vp,
                                     vp, sz, vp]
-    for name in ("hdqt_gemm_fwd", "hdqt_gemm_bwd_input", "hdqt_gemm_bwd_weight"):
+    lib.hdqt_gemm_codes_bf16.restype = i32
+    lib.hdqt_gemm_codes_bf16.argtypes = lib.hdqt_gemm_codes.argtypes
+    for name in ("hdqt_gemm_fwd", "hdqt_gemm_bwd_input", "hdqt_gemm_bwd_weight", "hdqt_gemm_bwd_input_bf16"):
         fn = getattr(lib, name)
         fn.restype = i32
         fn.argtypes = [vp, vp, vp, i64, i64, i64, C.POINTER(CParams), vp, vp, sz, vp]
@@ -258,22 +261,25 @@ def gemm_codes(qA: torch.Tensor, qB: torch.Tensor, bA: int, bB: int, scaleA: tor
                want_out: bool = True, want_acc: bool = True,
                workspace: Optional[torch.Tensor] = None,
                out: Optional[torch.Tensor] = None, acc: Optional[torch.Tensor] = None,
-               stream: Optional[torch.cuda.Stream] = None):
-    """hdqt_gemm_codes -> (out fp32 [RA, RB] | None, acc int32 [RA, RB] | None)."""
+               stream: Optional[torch.cuda.Stream] = None, bf16: bool = False):
+    """hdqt_gemm_codes -> (out fp32 [RA, RB] | None, acc int32 [RA, RB] | None);
+    with bf16=True hdqt_gemm_codes_bf16 and `out` is a torch.bfloat16 tensor."""
     _check_dev(qA, qB, scaleA, scaleB)
     RA, RB = qA.shape[0], qB.shape[0]
+    fn = "hdqt_gemm_codes_bf16" if bf16 else "hdqt_gemm_codes"
     if out is None and want_out:
-        out = torch.empty((RA, RB), dtype=torch.float32, device=qA.device)
+        out = torch.empty((RA, RB), dtype=torch.bfloat16 if bf16 else torch.float32, device=qA.device)
+    assert out is None or out.dtype == (torch.bfloat16 if bf16 else torch.float32)
     if acc is None and want_acc:
         acc = torch.empty((RA, RB), dtype=torch.int32, device=qA.device)
     if workspace is None:
         need = load().hdqt_gemm_codes_workspace_size(RA, RB, D, s)
         workspace = torch.empty(max(need, 256), dtype=torch.uint8, device=qA.device)
-    rc = load().hdqt_gemm_codes(_ptr(qA), _ptr(qB), bA, bB, _ptr(scaleA), _ptr(scaleB), RA, RB, D,
-                                n, acc_bits, s, _ptr(out), _ptr(acc), _ptr(workspace),
-                                workspace.numel(), _stream(stream))
+    rc = getattr(load(), fn)(_ptr(qA), _ptr(qB), bA, bB, _ptr(scaleA), _ptr(scaleB), RA, RB, D,
+                             n, acc_bits, s, _ptr(out), _ptr(acc), _ptr(workspace),
+                             workspace.numel(), _stream(stream))
     if rc:
-        raise HdqtError(rc, "hdqt_gemm_codes")
+        raise HdqtError(rc, fn)
     return out, acc
 
 
@@ -288,24 +294,27 @@ def out_shape(kind: int, M: int, K: int, N: int):
 def gemm(kind: int, P: torch.Tensor, Q: torch.Tensor, M: int, K: int, N: int, params: Params,
          out: Optional[torch.Tensor] = None, acc: Optional[torch.Tensor] = None,
          want_acc: bool = False, workspace: Optional[torch.Tensor] = None,
-         stream: Optional[torch.cuda.Stream] = None):
+         stream: Optional[torch.cuda.Stream] = None, bf16: bool = False):
     """hdqt_gemm_{fwd,bwd_input,bwd_weight}.  P, Q are the two source tensors of
-    `kind`: (X, W), (G, W), (X, G).  -> (out, acc | None, workspace)."""
+    `kind`: (X, W), (G, W), (X, G).  -> (out, acc | None, workspace).  bf16=True (input
+    gradient only): hdqt_gemm_bwd_input_bf16, `out` is a torch.bfloat16 tensor."""
     _check_dev(P, Q, out, acc, workspace)
     shape = out_shape(kind, M, K, N)
+    assert not bf16 or kind == GEMM_BWD_INPUT
+    fn = "hdqt_gemm_bwd_input_bf16" if bf16 else _GEMM_FN[kind]
     if out is None:
-        out = torch.empty(shape, dtype=torch.float32, device=P.device)
+        out = torch.empty(shape, dtype=torch.bfloat16 if bf16 else torch.float32, device=P.device)
+    assert out.dtype == (torch.bfloat16 if bf16 else torch.float32)
     if acc is None and want_acc:
         acc = torch.empty(shape, dtype=torch.int32, device=P.device)
     p = params.c()
     need = load().hdqt_workspace_size(kind, M, K, N, C.byref(p))
     if workspace is None:
         workspace = torch.empty(max(need, 256), dtype=torch.uint8, device=P.device)
-    rc = getattr(load(), _GEMM_FN[kind])(_ptr(P), _ptr(Q), _ptr(out), M, K, N, C.byref(p),
-                                         _ptr(acc), _ptr(workspace), workspace.numel(),
-                                         _stream(stream))
+    rc = getattr(load(), fn)(_ptr(P), _ptr(Q), _ptr(out), M, K, N, C.byref(p),
+                             _ptr(acc), _ptr(workspace), workspace.numel(), _stream(stream))
     if rc:
-        raise HdqtError(rc, _GEMM_FN[kind])
+        raise HdqtError(rc, fn)
     return out, acc, workspace
 
 

@@ -183,7 +183,8 @@ int run_quantize_pair(const float* T, int64_t rows, int64_t cols, int n1, const 
 // Resolve tile length, accumulator range and the split of the contraction.
 hdqt::GemmArgs plan_gemm(const void* qA, const void* qB, int bA, int bB, const float* scaleA,
                          const float* scaleB, int64_t RA, int64_t RB, int64_t D, int n_eff,
-                         int acc_bits, int64_t s, float* out, int32_t* acc_out, int profile_tag = 0)
+                         int acc_bits, int64_t s, float* out, int32_t* acc_out, int profile_tag = 0,
+                         uint16_t* out_bf16 = nullptr)
 {
     hdqt::GemmArgs g{};
     g.profile_tag = profile_tag;
@@ -197,12 +198,13 @@ hdqt::GemmArgs plan_gemm(const void* qA, const void* qB, int bA, int bB, const f
     g.acc_hi = acc_bits >= 32 ? INT_MAX : (1 << (acc_bits - 1)) - 1;
     g.scaleA = scaleA; g.scaleB = scaleB;
     g.inv_n = 1.0f / (float)n_eff;
-    g.out = out; g.acc_out = acc_out;
+    g.out = out; g.acc_out = acc_out; g.out_bf16 = out_bf16;
     // An output larger than half the 256 MB memory-side cache cannot stay there until
     // someone reads it; written normally it would sit there dirty and be written back
     // in the middle of the next kernel's reads (measured: the pass over X that follows
     // the input gradient of the 65536 x 1152 layer takes 90 us instead of 53 us).
-    g.stream_out = (RA * RB * (int64_t)sizeof(float) >= ((int64_t)128 << 20)) ? 1 : 0;
+    const int64_t out_elem = out ? (int64_t)sizeof(float) : (int64_t)sizeof(uint16_t);
+    g.stream_out = (RA * RB * out_elem >= ((int64_t)128 << 20)) ? 1 : 0;
     g.splits = choose_splits(RA, RB, g.n_tiles);
     g.tiles_per_split = (g.n_tiles + g.splits - 1) / g.splits;
     g.splits = (int)((g.n_tiles + g.tiles_per_split - 1) / g.tiles_per_split);
@@ -228,22 +230,47 @@ int run_planned_gemm(hdqt::GemmArgs g, void* ws, size_t ws_bytes, hipStream_t st
         e = hdqt::launch_gemm(g, stream);
         if (e != hipSuccess) return hip_fail(e);
         e = hdqt::launch_reduce(g.partial, g.splits, g.RA * g.RB, g.scaleA, g.scaleB, g.inv_n, g.out,
-                                g.acc_out, stream);
+                                g.out_bf16, g.acc_out, stream);
         return e == hipSuccess ? HDQT_OK : hip_fail(e);
     }
     e = hdqt::launch_gemm(g, stream);
     return e == hipSuccess ? HDQT_OK : hip_fail(e);
 }
 
+int run_gemm_codes(const void* qA, const void* qB, int bA, int bB, const float* scaleA,
+                   const float* scaleB, int64_t RA, int64_t RB, int64_t D, int n_eff, int acc_bits,
+                   int64_t s, float* out, uint16_t* out_bf16, int32_t* acc_out, void* workspace,
+                   size_t workspace_bytes, void* stream)
+{
+    if (!qA || !qB || !scaleA || !scaleB || (!out && !out_bf16 && !acc_out)) return HDQT_EINVAL_NULL;
+    if (RA <= 0 || RB <= 0 || D <= 0 || RA >= kMaxDim || RB >= kMaxDim || D >= kMaxDim)
+        return HDQT_EINVAL_DIM;
+    int rc;
+    if ((rc = check_dims2(RA, D)) || (rc = check_dims2(RB, D)) || (rc = check_dims2(RA, RB)))
+        return rc;
+    if (bA < 2 || bA > 8 || bB < 2 || bB > 8) return HDQT_EINVAL_BITS;
+    if (!is_pow2(n_eff) || n_eff > hdqt::kMaxHadamard || D % n_eff != 0)
+        return HDQT_EINVAL_HADAMARD;
+    if ((rc = check_accumulation(D, s, acc_bits, bA, bB))) return rc;
+    if (misaligned(qA) || misaligned(qB) || misaligned(out) || misaligned(out_bf16) ||
+        misaligned(acc_out) || misaligned(workspace))
+        return HDQT_EALIGN;
+    return run_planned_gemm(plan_gemm(qA, qB, bA, bB, scaleA, scaleB, RA, RB, D, n_eff, acc_bits, s,
+                                      out, acc_out, 0, out_bf16),
+                            workspace, workspace_bytes, static_cast<hipStream_t>(stream));
+}
+
 int run_gemm(int kind, const float* P, const float* Q, float* out, int64_t M, int64_t K, int64_t N,
-             const hdqt_params_t* prm, int32_t* acc_out, void* ws, size_t ws_bytes, void* stream_v)
+             const hdqt_params_t* prm, int32_t* acc_out, void* ws, size_t ws_bytes, void* stream_v,
+             uint16_t* out_bf16 = nullptr)
 {
     hdqt_ws_layout_t L;
     int rc = hdqt_workspace_layout(kind, M, K, N, prm, &L);
     if (rc) return rc;
-    if (!P || !Q || (!out && !acc_out)) return HDQT_EINVAL_NULL;
+    if (!P || !Q || (!out && !out_bf16 && !acc_out)) return HDQT_EINVAL_NULL;
     if (!ws || ws_bytes < L.total) return HDQT_EWORKSPACE;
-    if (misaligned(P) || misaligned(Q) || misaligned(out) || misaligned(acc_out) || misaligned(ws))
+    if (misaligned(P) || misaligned(Q) || misaligned(out) || misaligned(out_bf16) || misaligned(acc_out) ||
+        misaligned(ws))
         return HDQT_EALIGN;
     Orientation o;
     orient(kind, M, K, N, &o);
@@ -254,7 +281,8 @@ int run_gemm(int kind, const float* P, const float* Q, float* out, int64_t M, in
     void* codesA = base + L.codesA;
     void* codesB = base + L.codesB;
     hdqt::GemmArgs g = plan_gemm(codesA, codesB, prm->A.b, prm->B.b, &metaA->scale, &metaB->scale,
-                                 o.RA, o.RB, o.D, L.n_eff, prm->acc_bits, prm->s, out, acc_out, 1 + kind);
+                                 o.RA, o.RB, o.D, L.n_eff, prm->acc_bits, prm->s, out, acc_out, 1 + kind,
+                                 out_bf16);
     // one launch clears both calibration records (they are adjacent)
     hipError_t e = hdqt::launch_zero2(reinterpret_cast<uint32_t*>(metaA), (int64_t)(2 * kMetaBytes / 4),
                                       nullptr, 0, stream);
@@ -561,22 +589,17 @@ int hdqt_gemm_codes(const void* qA, const void* qB, int bA, int bB, const float*
                     int acc_bits, int64_t s, float* out, int32_t* acc_out, void* workspace,
                     size_t workspace_bytes, void* stream)
 {
-    if (!qA || !qB || !scaleA || !scaleB || (!out && !acc_out)) return HDQT_EINVAL_NULL;
-    if (RA <= 0 || RB <= 0 || D <= 0 || RA >= kMaxDim || RB >= kMaxDim || D >= kMaxDim)
-        return HDQT_EINVAL_DIM;
-    int rc;
-    if ((rc = check_dims2(RA, D)) || (rc = check_dims2(RB, D)) || (rc = check_dims2(RA, RB)))
-        return rc;
-    if (bA < 2 || bA > 8 || bB < 2 || bB > 8) return HDQT_EINVAL_BITS;
-    if (!is_pow2(n_eff) || n_eff > hdqt::kMaxHadamard || D % n_eff != 0)
-        return HDQT_EINVAL_HADAMARD;
-    if ((rc = check_accumulation(D, s, acc_bits, bA, bB))) return rc;
-    if (misaligned(qA) || misaligned(qB) || misaligned(out) || misaligned(acc_out) ||
-        misaligned(workspace))
-        return HDQT_EALIGN;
-    return run_planned_gemm(plan_gemm(qA, qB, bA, bB, scaleA, scaleB, RA, RB, D, n_eff, acc_bits, s,
-                                      out, acc_out),
-                            workspace, workspace_bytes, static_cast<hipStream_t>(stream));
+    return run_gemm_codes(qA, qB, bA, bB, scaleA, scaleB, RA, RB, D, n_eff, acc_bits, s, out, nullptr,
+                          acc_out, workspace, workspace_bytes, stream);
+}
+
+int hdqt_gemm_codes_bf16(const void* qA, const void* qB, int bA, int bB, const float* scaleA,
+                         const float* scaleB, int64_t RA, int64_t RB, int64_t D, int n_eff,
+                         int acc_bits, int64_t s, uint16_t* out, int32_t* acc_out, void* workspace,
+                         size_t workspace_bytes, void* stream)
+{
+    return run_gemm_codes(qA, qB, bA, bB, scaleA, scaleB, RA, RB, D, n_eff, acc_bits, s, nullptr, out,
+                          acc_out, workspace, workspace_bytes, stream);
 }
 
 size_t hdqt_gemm_codes_requant_workspace_size(int64_t RA, int64_t RB, int64_t D, int64_t s)
@@ -879,6 +902,14 @@ int hdqt_gemm_bwd_input(const float* G, const float* W, float* dX, int64_t M, in
 {
     return run_gemm(HDQT_GEMM_BWD_INPUT, G, W, dX, M, K, N, params, acc_out, workspace,
                     workspace_bytes, stream);
+}
+
+int hdqt_gemm_bwd_input_bf16(const float* G, const float* W, uint16_t* dX, int64_t M, int64_t K,
+                             int64_t N, const hdqt_params_t* params, int32_t* acc_out, void* workspace,
+                             size_t workspace_bytes, void* stream)
+{
+    return run_gemm(HDQT_GEMM_BWD_INPUT, G, W, nullptr, M, K, N, params, acc_out, workspace,
+                    workspace_bytes, stream, dX);
 }
 
 int hdqt_gemm_bwd_weight(const float* X, const float* G, float* dW, int64_t M, int64_t K,

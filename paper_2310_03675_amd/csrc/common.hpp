@@ -78,6 +78,7 @@ struct GemmArgs {
     const float* scaleB;
     float inv_n;            // 1 / n_eff (a power of two)
     float* out;             // [RA, RB] or null
+    uint16_t* out_bf16;     // [RA, RB] bfloat16 patterns or null: the same values, narrowed (nearest even)
     int32_t* acc_out;       // [RA, RB] or null
     int32_t* partial;       // [splits, RA, RB] when splits > 1: one slice per part of the contraction;
                             // second reading of the accumulator: [n_tiles, RA, RB], every tile's sums
@@ -103,9 +104,10 @@ bool dual_pass2_batchable(const DualArgs* qs, int n);
 hipError_t launch_zero2(uint32_t* a, int64_t na, uint32_t* b, int64_t nb, hipStream_t stream);
 // sum the `splits` slices of `partial` ([splits, count]); the totals go to acc_out
 // (nullable) and, dequantized, to out (nullable)
+// out_bf16 (nullable): the dequantized totals narrowed to bfloat16
 hipError_t launch_reduce(const int32_t* partial, int splits, int64_t count, const float* scaleA,
-                         const float* scaleB, float inv_n, float* out, int32_t* acc_out,
-                         hipStream_t stream);
+                         const float* scaleB, float inv_n, float* out, uint16_t* out_bf16,
+                         int32_t* acc_out, hipStream_t stream);
 
 // Optional per-kernel timing (off by default).  When enabled through the C ABI,
 // every launch is bracketed by two HIP events on its stream.
@@ -165,6 +167,14 @@ __device__ __forceinline__ uint32_t sr_halfword(const uint32_t blk[4], uint32_t 
 
 // alpha * 2^(b-1): one correctly rounded division.  A binary64 quotient of two
 // binary32 values rounds to binary32 without double-rounding error (53 >= 2*24+2).
+// binary32 -> bfloat16 pattern, nearest, ties to even (finite values; a carry out of the
+// fraction moves to the next binade or to infinity, which is the correctly rounded result)
+__device__ __forceinline__ uint32_t bf16_bits(float x)
+{
+    const uint32_t u = __float_as_uint(x);
+    return (u + 0x7FFFu + ((u >> 16) & 1u)) >> 16;
+}
+
 __device__ __forceinline__ float inverse_step(float amax_clipped, int b)
 {
     const double levels = (double)(1 << (b - 1));

@@ -220,6 +220,7 @@ __global__ __launch_bounds__(kThreads) void gemm_tiled_kernel(GemmArgs g)
                     } else {
                         if (g.acc_out) g.acc_out[i * g.RB + j] = v;
                         if (g.out) g.out[i * g.RB + j] = (float)v * dq;
+                        if (g.out_bf16) g.out_bf16[i * g.RB + j] = (uint16_t)bf16_bits((float)v * dq);
                     }
                 }
             }
@@ -231,7 +232,8 @@ __global__ __launch_bounds__(kThreads) void gemm_tiled_kernel(GemmArgs g)
 template <int VEC>
 __global__ __launch_bounds__(256) void reduce_kernel(const int32_t* partial, int splits, int64_t count,
                                                      const float* scaleA, const float* scaleB,
-                                                     float inv_n, float* out, int32_t* acc_out)
+                                                     float inv_n, float* out, uint16_t* out_bf16,
+                                                     int32_t* acc_out)
 {
     const float dq = (scaleA[0] * scaleB[0]) * inv_n;
     for (int64_t e = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) * VEC; e < count;
@@ -251,6 +253,7 @@ __global__ __launch_bounds__(256) void reduce_kernel(const int32_t* partial, int
         for (int k = 0; k < VEC; ++k) {
             if (acc_out) acc_out[e + k] = t[k];
             if (out) out[e + k] = (float)t[k] * dq;
+            if (out_bf16) out_bf16[e + k] = (uint16_t)bf16_bits((float)t[k] * dq);
         }
     }
 }
@@ -305,8 +308,8 @@ __global__ __launch_bounds__(256) void requant_sum_kernel(const int32_t* partial
 } // namespace
 
 hipError_t launch_reduce(const int32_t* partial, int splits, int64_t count, const float* scaleA,
-                         const float* scaleB, float inv_n, float* out, int32_t* acc_out,
-                         hipStream_t stream)
+                         const float* scaleB, float inv_n, float* out, uint16_t* out_bf16,
+                         int32_t* acc_out, hipStream_t stream)
 {
     const bool vec = (count % 4 == 0);
     int64_t blocks = ((vec ? count / 4 : count) + 255) / 256;
@@ -315,10 +318,10 @@ hipError_t launch_reduce(const int32_t* partial, int splits, int64_t count, cons
     ProfileScope ps(K_REDUCE, stream);
     if (vec)
         hipLaunchKernelGGL(reduce_kernel<4>, dim3((unsigned)blocks), dim3(256), 0, stream, partial, splits,
-                           count, scaleA, scaleB, inv_n, out, acc_out);
+                           count, scaleA, scaleB, inv_n, out, out_bf16, acc_out);
     else
         hipLaunchKernelGGL(reduce_kernel<1>, dim3((unsigned)blocks), dim3(256), 0, stream, partial, splits,
-                           count, scaleA, scaleB, inv_n, out, acc_out);
+                           count, scaleA, scaleB, inv_n, out, out_bf16, acc_out);
     return hipGetLastError();
 }
 

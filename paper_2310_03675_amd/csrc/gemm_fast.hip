@@ -34,6 +34,8 @@ namespace {
 typedef int v4i __attribute__((ext_vector_type(4)));
 typedef int v16i __attribute__((ext_vector_type(16)));
 typedef short v2s __attribute__((ext_vector_type(2)));
+typedef float f2 __attribute__((ext_vector_type(2)));
+typedef __bf16 bf2 __attribute__((ext_vector_type(2)));
 
 constexpr int kWaves = 8;             // waves per workgroup: 8 measured 3-7 % faster than 4 on the layer
                                       // shapes and on 4096^3 (see the kernel)
@@ -93,7 +95,7 @@ __device__ __forceinline__ int clamp3(int v, int lo, int hi)
 // flight.  With gridDim.z = 1 a workgroup walks along a
 // whole row strip of the output, which is how short contractions (one or two
 // stages per tile) keep loads, MFMAs and stores overlapped.
-template <int EPI, int KS, bool STREAM, int WAVES>
+template <int EPI, int KS, bool STREAM, int WAVES, bool BF16>
 __global__ __launch_bounds__(64 * WAVES, WAVES == 8 ? 4 : 2) void gemm_i4_kernel(GemmArgs g)
 {
     // WAVES = 4: each wave a 64 x 64 quarter (2 x 2 MFMA blocks).  WAVES = 8: each wave
@@ -263,8 +265,61 @@ __global__ __launch_bounds__(64 * WAVES, WAVES == 8 ? 4 : 2) void gemm_i4_kernel
         const int64_t tile_off = row0 * g.RB + col0;
         const bool interior = (row0 + BM <= g.RA) && (col0 + BN <= g.RB);
         float* ob = (g.splits == 1 && g.out) ? g.out + tile_off : nullptr;
+        // (the narrow output has kernel instances of its own: its epilogue costs the others registers)
+        uint16_t* hb = (BF16 && g.splits == 1 && g.out_bf16) ? g.out_bf16 + tile_off : nullptr;
+        // bfloat16 output of an interior tile with an even row length: lanes l and l ^ 1 hold
+        // neighbouring columns and trade their values, so that every lane stores one dword
+        const bool pair_bf16 = hb && interior && (g.RB % 2 == 0);
         int32_t* ab = g.splits > 1 ? g.partial + (int64_t)blockIdx.x * g.RA * g.RB + tile_off
                                    : (g.acc_out ? g.acc_out + tile_off : nullptr);
+        if constexpr (BF16) if (pair_bf16) {
+            const bool odd = lane & 1;
+            auto value = [&](int t) -> float {
+                return (float)((EPI == EPI_GENERIC) ? (t >> kScaleShift) : t) * dq;
+            };
+            // quad_perm [1,0,3,2]: the value of lane ^ 1
+            auto neighbour = [](float f) -> float {
+                return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(f), 0xB1, 0xF, 0xF, true));
+            };
+            // two binary32 values -> two bfloat16 in one dword (v_cvt_pk_bf16_f32: nearest even)
+            auto pack = [](float lo, float hi) -> uint32_t {
+                const f2 v = {lo, hi};
+                return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf2));
+            };
+#pragma unroll
+            for (int a = 0; a < 2; ++a) {
+                if constexpr (CS == 2) {
+                    // 64 columns per wave: the even lanes store the pairs of the left 32-column
+                    // block, the odd lanes those of the right one, so the 32 lanes that share a
+                    // row write its whole 128-byte line with one instruction
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) {
+                        const float f0 = value(total[a][0][r]), f1 = value(total[a][CS - 1][r]);
+                        const float n0 = neighbour(f0), n1 = neighbour(f1);
+                        const uint32_t word = pack(odd ? n1 : f0, odd ? f1 : n0);
+                        const int rr = a * 32 + 8 * (r >> 2) + (r & 3);
+                        const uint32_t off = lane_off + (odd ? 31u : 0u);
+                        uint32_t* dst = reinterpret_cast<uint32_t*>(hb + (int64_t)rr * g.RB + off);
+                        if (STREAM) __builtin_nontemporal_store(word, dst);
+                        else *dst = word;
+                    }
+                } else {
+                    // 32 columns per wave: the even lane stores both columns of row r, the odd
+                    // lane both columns of row r + 1 (r even): 64-byte pieces of four rows
+#pragma unroll
+                    for (int r = 0; r < 16; r += 2) {
+                        const float f0 = value(total[a][0][r]), f1 = value(total[a][0][r + 1]);
+                        const float n0 = neighbour(f0), n1 = neighbour(f1);
+                        const uint32_t word = pack(odd ? n1 : f0, odd ? f1 : n0);
+                        const int rr = a * 32 + 8 * (r >> 2) + (r & 3);
+                        const uint32_t off = lane_off + (odd ? (uint32_t)g.RB - 1u : 0u);
+                        uint32_t* dst = reinterpret_cast<uint32_t*>(hb + (int64_t)rr * g.RB + off);
+                        if (STREAM) __builtin_nontemporal_store(word, dst);
+                        else *dst = word;
+                    }
+                }
+            }
+        }
 #pragma unroll
         for (int a = 0; a < 2; ++a)
 #pragma unroll
@@ -278,6 +333,7 @@ __global__ __launch_bounds__(64 * WAVES, WAVES == 8 ? 4 : 2) void gemm_i4_kernel
                     bool ok = interior;
                     if (!interior)
                         ok = (row0 + lane_row + rr < g.RA) && (col0 + lane_col + c * 32 < g.RB);
+                    if (BF16 && hb && !pair_bf16 && ok) (hb + uo)[lane_off] = (uint16_t)bf16_bits((float)v * dq);
                     if (ok) {
                         if (ab) (ab + uo)[lane_off] = v;
                         if (ob) {
@@ -339,17 +395,21 @@ hipError_t launch_gemm_fast(const GemmArgs& g_in, hipStream_t stream)
     }
     const dim3 grid((unsigned)g.splits, (unsigned)n_rt, (unsigned)gx);
     ProfileScope ps(g.profile_tag ? K_GEMM_I4_FWD + (g.profile_tag - 1) : K_GEMM_I4, stream);
-    const dim3 block(64 * kWaves);
-    if (s32) {
-        if (g.stream_out) hipLaunchKernelGGL((gemm_i4_kernel<EPI_SAT8_S32, KS_LONG, true, kWaves>), grid, block, 0, stream, g);
-        else hipLaunchKernelGGL((gemm_i4_kernel<EPI_SAT8_S32, KS_LONG, false, kWaves>), grid, block, 0, stream, g);
-    } else if (sat8_path(g)) {
-        if (g.stream_out) hipLaunchKernelGGL((gemm_i4_kernel<EPI_SAT8_S64, KS_LONG, true, kWaves>), grid, block, 0, stream, g);
-        else hipLaunchKernelGGL((gemm_i4_kernel<EPI_SAT8_S64, KS_LONG, false, kWaves>), grid, block, 0, stream, g);
-    } else {
-        if (g.stream_out) hipLaunchKernelGGL((gemm_i4_kernel<EPI_GENERIC, KS_LONG, true, kWaves>), grid, block, 0, stream, g);
-        else hipLaunchKernelGGL((gemm_i4_kernel<EPI_GENERIC, KS_LONG, false, kWaves>), grid, block, 0, stream, g);
-    }
+#define HDQT_LAUNCH_I4(EPI)                                                                          \
+    do {                                                                                             \
+        const dim3 block(64 * kWaves);                                                               \
+        if (g.out_bf16) {                                                                            \
+            if (g.stream_out) hipLaunchKernelGGL((gemm_i4_kernel<EPI, KS_LONG, true, kWaves, true>), grid, block, 0, stream, g); \
+            else hipLaunchKernelGGL((gemm_i4_kernel<EPI, KS_LONG, false, kWaves, true>), grid, block, 0, stream, g); \
+        } else if (g.stream_out)                                                                     \
+            hipLaunchKernelGGL((gemm_i4_kernel<EPI, KS_LONG, true, kWaves, false>), grid, block, 0, stream, g); \
+        else                                                                                         \
+            hipLaunchKernelGGL((gemm_i4_kernel<EPI, KS_LONG, false, kWaves, false>), grid, block, 0, stream, g); \
+    } while (0)
+    if (s32) HDQT_LAUNCH_I4(EPI_SAT8_S32);
+    else if (sat8_path(g)) HDQT_LAUNCH_I4(EPI_SAT8_S64);
+    else HDQT_LAUNCH_I4(EPI_GENERIC);
+#undef HDQT_LAUNCH_I4
     return hipGetLastError();
 }
 

@@ -298,3 +298,26 @@ def test_dimension_limit():
     assert B.load().hdqt_workspace_size(0, lim + 1, 64, 64, C.byref(p)) == 0
     assert _quant_rc(rows=lim + 1) == E["HDQT_EINVAL_DIM"]
     assert _quant_rc(cols=lim + 64, had=64) == E["HDQT_EINVAL_DIM"]
+
+
+def test_bf16_output_argument_errors():
+    """The narrow-output entry points check their arguments like the fp32 ones."""
+    lib = B.load()
+
+    def rc(qA=FAKE, bA=4, RA=8, D=64, n=64, a=8, s=32, out=FAKE, acc=None):
+        return lib.hdqt_gemm_codes_bf16(qA, FAKE, bA, 4, FAKE, FAKE, RA, 8, D, n, a, s, out, acc, None, 0,
+                                        None)
+    assert rc(qA=None) == E["HDQT_EINVAL_NULL"]
+    assert rc(out=None, acc=None) == E["HDQT_EINVAL_NULL"]
+    assert rc(RA=0) == E["HDQT_EINVAL_DIM"]
+    assert rc(bA=9) == E["HDQT_EINVAL_BITS"]
+    assert rc(n=48) == E["HDQT_EINVAL_HADAMARD"]
+    assert rc(a=40) == E["HDQT_EINVAL_ACC"]
+    assert rc(s=0) == E["HDQT_EINVAL_TILE"]
+    assert rc(out=C.c_void_p(0x10002)) == E["HDQT_EALIGN"]
+    p = _cparams()
+    f = lib.hdqt_gemm_bwd_input_bf16
+    assert f(None, FAKE, FAKE, 64, 64, 64, C.byref(p), None, FAKE, 1 << 30, None) == E["HDQT_EINVAL_NULL"]
+    assert f(FAKE, FAKE, None, 64, 64, 64, C.byref(p), None, FAKE, 1 << 30, None) == E["HDQT_EINVAL_NULL"]
+    assert f(FAKE, FAKE, FAKE, 64, 64, 64, C.byref(p), None, FAKE, 16, None) == E["HDQT_EWORKSPACE"]
+    assert f(FAKE, FAKE, FAKE, 0, 64, 64, C.byref(p), None, FAKE, 1 << 30, None) == E["HDQT_EINVAL_DIM"]
