@@ -111,6 +111,8 @@ def main():
                     help="skip the 1 GiB hdqt_quantize measurement ('quantize_1GiB')")
     ap.add_argument("--no-square", action="store_true",
                     help="skip the 4096^3 matmul measurement ('gemm_square_4096')")
+    ap.add_argument("--no-conv", action="store_true",
+                    help="skip the activation-source variant of the step ('conv_step')")
     ap.add_argument("--requant", action="store_true",
                     help="also time the forward matmul under the second reading of the accumulator "
                          "(hdqt_gemm_requant) and report it as 'requant_fwd'")
@@ -371,6 +373,45 @@ def main():
                                            "algorithmic_bytes_per_launch": nbytes}
             del o_dx
         del qg, qw
+    if layer.act is not None and not args.no_conv and not args.separate:
+        # The same step with X given as the convolution's input (hdqt_conv_step): the quantizer
+        # reads the activation, kh*kw times smaller than its im2col matrix, and the outputs
+        # are bit for bit those of the step above.  Not `value`: the benchmark's workload
+        # hands the matrix over; this is what a convolution layer can call instead.
+        act_d = layer.act.to(dev)
+        kh_, kw_ = layer.window
+        try:
+            ws_c = torch.empty(ws_bytes, dtype=torch.uint8, device=dev)
+            conv = lambda: B.conv_step(act_d, kh_, kw_, W, G, prm[kinds[0]], prm[kinds[1]], prm[kinds[2]],
+                                       out=step_out, workspace=ws_c)
+            ref = [o.clone() for o in step_out]
+            conv()
+            torch.cuda.synchronize()
+            same = all(torch.equal(o, r) for o, r in zip(step_out, ref))
+            for _ in range(args.warmup):
+                conv()
+            torch.cuda.synchronize()
+            t1 = time.perf_counter()
+            for _ in range(args.steps):
+                conv()
+            torch.cuda.synchronize()
+            dt_c = (time.perf_counter() - t1) / args.steps
+            B.profile_enable(True)
+            B.profile_collect()
+            for _ in range(args.steps):
+                conv()
+            torch.cuda.synchronize()
+            B.profile_enable(False)
+            kc = B.profile_collect()
+            line["conv_step"] = {
+                "entry": "hdqt_conv_step", "ms_per_step": dt_c * 1e3, "TOPS": ops_step / dt_c / 1e12,
+                "outputs_equal_layer_step": same,
+                "activation_bytes": 4.0 * act_d.numel(), "im2col_matrix_bytes": 4.0 * M * K,
+                "kernels_us": {n_: tot / l * 1e3 for n_, (l, tot) in kc.items()}}
+            del ws_c, ref
+        except B.HdqtError as exc:          # geometry the activation-source kernels do not take
+            line["conv_step"] = {"skipped": str(exc)}
+        del act_d
     if args.requant:
         k = kinds[0]
         need = B.load().hdqt_gemm_requant_workspace_size(k, M, K, N, prm[k].c())

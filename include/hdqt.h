@@ -70,6 +70,8 @@ typedef enum { HDQT_GEMM_FWD = 0, HDQT_GEMM_BWD_INPUT = 1, HDQT_GEMM_BWD_WEIGHT 
 #define HDQT_EWORKSPACE (-10)     /* workspace NULL or smaller than required */
 #define HDQT_EALIGN (-11)         /* a pointer is not 16-byte aligned */
 #define HDQT_EHIP (-12)           /* a HIP call failed */
+#define HDQT_EINVAL_GEOMETRY (-13) /* convolution geometry (or layer shape) outside what the
+                                      activation-source kernels take: see hdqt_conv_t */
 
 /* One quantized operand; names follow the paper's quantizer Q. */
 typedef struct {
@@ -165,6 +167,32 @@ int hdqt_quantize_dual(const float *T, int64_t rows, int64_t cols, int had_block
                        const hdqt_operand_t *op_axis1, const hdqt_operand_t *op_axis0,
                        uint64_t seed, void *codes_axis1, float *scale_axis1, void *codes_axis0,
                        float *scale_axis0, void *workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * A convolution's input as the source of the matmuls (Experiments: the convolutions of
+ * the paper's networks run as matmuls on the unfolded activation).  The activation
+ * act[batch, channels, height, width] (fp32, row-major, device) stands for its im2col
+ * matrix X[M, K], M = batch*height*width, K = channels*kh*kw: row (b, y, x), column
+ * c*kh*kw + ty*kw + tx holds act[b, c, y + ty - (kh-1)/2, x + tx - (kw-1)/2], zero outside
+ * the image (stride 1, output of the input's size).  The kernels read the activation,
+ * kh*kw times smaller than X, and never need X in memory.
+ * Taken: kh, kw odd (<= 15); width a power of two <= 64 with height*width a multiple of
+ * 64, or width a multiple of 64; and what the two-axis kernels need of X (M and K
+ * multiples of 64, block orders <= 64, codes of <= 4 bits).  Anything else:
+ * HDQT_EINVAL_GEOMETRY, and the caller unfolds the activation itself.
+ */
+typedef struct {
+    int64_t batch;
+    int32_t channels, height, width;
+    int32_t kh, kw;
+} hdqt_conv_t;
+
+/* hdqt_quantize_dual on the im2col matrix of `act`; outputs, workspace and errors as there. */
+int hdqt_quantize_dual_im2col(const float *act, const hdqt_conv_t *geo, int had_block,
+                              const hdqt_operand_t *op_axis1, const hdqt_operand_t *op_axis0,
+                              uint64_t seed, void *codes_axis1, float *scale_axis1,
+                              void *codes_axis0, float *scale_axis0, void *workspace,
+                              size_t workspace_bytes, void *stream);
 
 /*
  * Tiled integer matmul on packed codes (Methodology: tiles of size s, low-bit
@@ -273,6 +301,34 @@ int hdqt_layer_step(const float *X, const float *W, const float *G, float *Z, fl
                     float *dW, int64_t M, int64_t K, int64_t N, const hdqt_params_t *fwd,
                     const hdqt_params_t *bwd_input, const hdqt_params_t *bwd_weight,
                     void *workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * hdqt_layer_step for a convolution layer: X is given as the activation (see hdqt_conv_t),
+ * M and K follow from `geo`.  Z [M, N], dXcol [M, K] (the gradient of the im2col matrix:
+ * folding it back onto the activation is the caller's) and dW [K, N] as for
+ * hdqt_layer_step, bit for bit what that call returns on the unfolded activation.
+ * dXcol and bwd_input are required.  Workspace: hdqt_conv_step_workspace_size(...) bytes,
+ * 0 if the geometry is not taken (then hdqt_conv_step returns HDQT_EINVAL_GEOMETRY).
+ */
+size_t hdqt_conv_step_workspace_size(const hdqt_conv_t *geo, int64_t N, const hdqt_params_t *fwd,
+                                     const hdqt_params_t *bwd_input,
+                                     const hdqt_params_t *bwd_weight);
+int hdqt_conv_step(const float *act, const hdqt_conv_t *geo, const float *W, const float *G,
+                   float *Z, float *dXcol, float *dW, int64_t N, const hdqt_params_t *fwd,
+                   const hdqt_params_t *bwd_input, const hdqt_params_t *bwd_weight,
+                   void *workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * hdqt_layer_fwd for a convolution layer: Z and the saved codes of X along M from the
+ * activation (see hdqt_conv_t); M = batch*height*width and K = channels*kh*kw follow from
+ * `geo`.  bwd_weight and saved are required (both code sets come from the same kernels);
+ * sizes from hdqt_layer_saved_size(M, K, ...) and hdqt_layer_fwd_workspace_size(M, K, N, ...).
+ * hdqt_layer_bwd then runs as for any layer (its dX is the gradient of the im2col matrix).
+ * HDQT_EINVAL_GEOMETRY if the geometry is not taken.
+ */
+int hdqt_conv_fwd(const float *act, const hdqt_conv_t *geo, const float *W, float *Z, int64_t N,
+                  const hdqt_params_t *fwd, const hdqt_params_t *bwd_weight, void *saved,
+                  size_t saved_bytes, void *workspace, size_t workspace_bytes, void *stream);
 
 /*
  * The same step as two calls, for training loops in which the gradient G arrives

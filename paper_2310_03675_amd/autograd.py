@@ -54,13 +54,14 @@ class HdqtMatmul(torch.autograd.Function):
 
     @staticmethod
     def forward(ctx, X, W, cfg: LayerConfig, step: int):
+        # (asked before .contiguous(): a copy made inside forward() does not require grad)
+        ctx.want_dx = cfg.need_input_grad and X.requires_grad
         X, W = X.contiguous(), W.contiguous()
         pf = cfg.params(B.GEMM_FWD, step)
         pw = cfg.params(B.GEMM_BWD_WEIGHT, step)
         Z, saved = B.layer_fwd(X, W, pf, pw)
         ctx.save_for_backward(W, saved)
         ctx.cfg, ctx.step, ctx.K = cfg, step, X.shape[1]
-        ctx.want_dx = cfg.need_input_grad and X.requires_grad
         if cfg.capture is not None:
             cfg.capture.update(X=X.detach(), W=W.detach().clone(), Z=Z.detach(), step=step)
         return Z
@@ -76,6 +77,45 @@ class HdqtMatmul(torch.autograd.Function):
         if cfg.capture is not None:
             cfg.capture.update(G=G.detach(), dX=dX, dW=dW)
         return dX, dW, None, None
+
+
+class HdqtConvMatmul(torch.autograd.Function):
+    """Z = im2col(act) W for a stride-1, same-size convolution, without forming im2col(act):
+    the forward call reads the activation (hdqt_conv_fwd).  The backward pass returns the
+    gradient of the activation: the library's gradient of the im2col matrix, folded back by
+    PyTorch."""
+
+    @staticmethod
+    def forward(ctx, act, W, cfg: LayerConfig, step: int, kh: int, kw: int):
+        ctx.want_dx = cfg.need_input_grad and act.requires_grad
+        act, W = act.contiguous(), W.contiguous()
+        pf = cfg.params(B.GEMM_FWD, step)
+        pw = cfg.params(B.GEMM_BWD_WEIGHT, step)
+        Z, saved = B.conv_fwd(act, kh, kw, W, pf, pw)
+        ctx.save_for_backward(W, saved)
+        ctx.cfg, ctx.step, ctx.shape, ctx.window = cfg, step, tuple(act.shape), (kh, kw)
+        if cfg.capture is not None:
+            cfg.capture.update(act=act.detach(), W=W.detach().clone(), Z=Z.detach(), step=step)
+        return Z
+
+    @staticmethod
+    def backward(ctx, G):
+        W, saved = ctx.saved_tensors
+        cfg = ctx.cfg
+        Bn, Cin, H, Wd = ctx.shape
+        kh, kw = ctx.window
+        pi = cfg.params(B.GEMM_BWD_INPUT, ctx.step) if ctx.want_dx else None
+        pw = cfg.params(B.GEMM_BWD_WEIGHT, ctx.step)
+        G = G.contiguous()
+        dXcol, dW = B.layer_bwd(G, W, saved, Cin * kh * kw, pi, pw)
+        if cfg.capture is not None:
+            cfg.capture.update(G=G.detach(), dX=dXcol, dW=dW)
+        dAct = None
+        if dXcol is not None:
+            cols = dXcol.reshape(Bn, H * Wd, Cin * kh * kw).transpose(1, 2)
+            dAct = torch.nn.functional.fold(cols, output_size=(H, Wd), kernel_size=(kh, kw),
+                                            padding=((kh - 1) // 2, (kw - 1) // 2))
+        return dAct, dW, None, None, None, None
 
 
 class HdqtLinear(torch.nn.Module):
@@ -105,8 +145,9 @@ class HdqtLinear(torch.nn.Module):
 class HdqtConv2d(torch.nn.Module):
     """Convolution as the paper runs it: the activation is unfolded (im2col, column index =
     channel * kh * kw + tap) and the products of the forward and the backward pass are the
-    quantized matmuls above.  The unfolding and folding are PyTorch's; only the matmuls are
-    the library's."""
+    quantized matmuls above.  Stride-1, same-size layers whose geometry the library takes
+    never form the unfolded matrix in the forward pass (hdqt_conv_fwd reads the activation);
+    the others are unfolded by PyTorch.  Folding the input gradient back is PyTorch's."""
 
     def __init__(self, in_channels: int, out_channels: int, kernel_size: int = 3, padding: int = 1,
                  stride: int = 1, cfg: Optional[LayerConfig] = None, device=None):
@@ -118,15 +159,27 @@ class HdqtConv2d(torch.nn.Module):
         torch.nn.init.kaiming_normal_(w.t(), nonlinearity="relu")
         self.weight = torch.nn.Parameter(w)
         self.step = 0
+        self.from_activation = True      # read the activation directly where the library takes the geometry
+        self._refused = set()            # input shapes it did not take
 
     def forward(self, x):
         Bn, Cin, H, W = x.shape
         Ho = (H + 2 * self.pad - self.k) // self.stride + 1
         Wo = (W + 2 * self.pad - self.k) // self.stride + 1
-        cols = torch.nn.functional.unfold(x, kernel_size=self.k, padding=self.pad,
-                                          stride=self.stride)                 # [B, C*k*k, Ho*Wo]
-        X = cols.transpose(1, 2).reshape(Bn * Ho * Wo, Cin * self.k * self.k)
-        Z = HdqtMatmul.apply(X, self.weight, self.cfg, self.step)
+        Z = None
+        if (self.from_activation and self.stride == 1 and 2 * self.pad == self.k - 1 and self.training
+                and tuple(x.shape) not in self._refused):
+            try:
+                Z = HdqtConvMatmul.apply(x, self.weight, self.cfg, self.step, self.k, self.k)
+            except B.HdqtError as exc:
+                if exc.code != -13:
+                    raise
+                self._refused.add(tuple(x.shape))
+        if Z is None:
+            cols = torch.nn.functional.unfold(x, kernel_size=self.k, padding=self.pad,
+                                              stride=self.stride)                 # [B, C*k*k, Ho*Wo]
+            X = cols.transpose(1, 2).reshape(Bn * Ho * Wo, Cin * self.k * self.k)
+            Z = HdqtMatmul.apply(X, self.weight, self.cfg, self.step)
         if self.training:
             self.step += 1
         return Z.reshape(Bn, Ho * Wo, -1).transpose(1, 2).reshape(Bn, -1, Ho, Wo)

@@ -28,7 +28,8 @@ EXPORTED = [
     "hdqt_layer_fwd", "hdqt_layer_bwd_workspace_size", "hdqt_layer_bwd",
     "hdqt_gemm_codes_requant_workspace_size", "hdqt_gemm_codes_requant",
     "hdqt_gemm_requant_workspace_size", "hdqt_gemm_requant", "hdqt_gemm_codes_bf16",
-    "hdqt_gemm_bwd_input_bf16",
+    "hdqt_gemm_bwd_input_bf16", "hdqt_quantize_dual_im2col", "hdqt_conv_step_workspace_size",
+    "hdqt_conv_step", "hdqt_conv_fwd",
 ]
 
 
@@ -46,6 +47,11 @@ class COperand(C.Structure):
 class CParams(C.Structure):
     _fields_ = [("had_block", C.c_int32), ("acc_bits", C.c_int32), ("s", C.c_int64),
                 ("seed", C.c_uint64), ("A", COperand), ("B", COperand)]
+
+
+class CConv(C.Structure):
+    _fields_ = [("batch", C.c_int64), ("channels", C.c_int32), ("height", C.c_int32),
+                ("width", C.c_int32), ("kh", C.c_int32), ("kw", C.c_int32)]
 
 
 class CLayout(C.Structure):
@@ -141,6 +147,15 @@ def load() -> C.CDLL:
     lib.hdqt_gemm_codes.restype = i32
     lib.hdqt_gemm_codes.argtypes = [vp, vp, i32, i32, vp, vp, i64, i64, i64, i32, i32, i64, vp, vp,
                                     vp, sz, vp]
+    lib.hdqt_quantize_dual_im2col.restype = i32
+    lib.hdqt_quantize_dual_im2col.argtypes = [vp, C.POINTER(CConv), i32, C.POINTER(COperand),
+                                              C.POINTER(COperand), C.c_uint64, vp, vp, vp, vp, vp, sz, vp]
+    lib.hdqt_conv_step_workspace_size.restype = sz
+    lib.hdqt_conv_step_workspace_size.argtypes = [C.POINTER(CConv), i64] + [C.POINTER(CParams)] * 3
+    lib.hdqt_conv_step.restype = i32
+    lib.hdqt_conv_step.argtypes = [vp, C.POINTER(CConv), vp, vp, vp, vp, vp, i64] + [C.POINTER(CParams)] * 3 + [vp, sz, vp]
+    lib.hdqt_conv_fwd.restype = i32
+    lib.hdqt_conv_fwd.argtypes = [vp, C.POINTER(CConv), vp, vp, i64] + [C.POINTER(CParams)] * 2 + [vp, sz, vp, sz, vp]
     lib.hdqt_gemm_codes_bf16.restype = i32
     lib.hdqt_gemm_codes_bf16.argtypes = lib.hdqt_gemm_codes.argtypes
     for name in ("hdqt_gemm_fwd", "hdqt_gemm_bwd_input", "hdqt_gemm_bwd_weight", "hdqt_gemm_bwd_input_bf16"):
@@ -254,6 +269,60 @@ def quantize_dual(T: torch.Tensor, had_block: int, op_axis1: Operand, op_axis0: 
     if rc:
         raise HdqtError(rc, "hdqt_quantize_dual")
     return c1, s1, c0, s0
+
+
+def conv_geometry(act: torch.Tensor, kh: int, kw: int) -> CConv:
+    """Geometry of a stride-1, same-size convolution over act [batch, C, H, W]."""
+    assert act.dim() == 4 and act.dtype == torch.float32 and act.is_contiguous()
+    b, c, h, w = act.shape
+    return CConv(b, c, h, w, kh, kw)
+
+
+def quantize_dual_im2col(act: torch.Tensor, kh: int, kw: int, had_block: int, op_axis1: Operand,
+                         op_axis0: Operand, seed: int = 0, stream: Optional[torch.cuda.Stream] = None):
+    """hdqt_quantize_dual_im2col -> (codes_axis1, scale_axis1, codes_axis0, scale_axis0) of the
+    im2col matrix [batch*H*W, C*kh*kw] of act, which is never formed."""
+    _check_dev(act)
+    geo = conv_geometry(act, kh, kw)
+    rows, cols = act.shape[0] * act.shape[2] * act.shape[3], act.shape[1] * kh * kw
+    c1 = torch.empty((rows, codes_pitch(cols, op_axis1.b)), dtype=torch.uint8, device=act.device)
+    c0 = torch.empty((cols, codes_pitch(rows, op_axis0.b)), dtype=torch.uint8, device=act.device)
+    s1 = torch.empty(1, dtype=torch.float32, device=act.device)
+    s0 = torch.empty(1, dtype=torch.float32, device=act.device)
+    ws = torch.empty(load().hdqt_quantize_dual_workspace_size(), dtype=torch.uint8, device=act.device)
+    o1, o0 = op_axis1.c(), op_axis0.c()
+    rc = load().hdqt_quantize_dual_im2col(_ptr(act), C.byref(geo), had_block, C.byref(o1), C.byref(o0),
+                                          seed, _ptr(c1), _ptr(s1), _ptr(c0), _ptr(s0), _ptr(ws),
+                                          ws.numel(), _stream(stream))
+    if rc:
+        raise HdqtError(rc, "hdqt_quantize_dual_im2col")
+    return c1, s1, c0, s0
+
+
+def conv_step(act: torch.Tensor, kh: int, kw: int, W: torch.Tensor, G: torch.Tensor, fwd: Params,
+              bwd_input: Params, bwd_weight: Params, out=None, workspace: Optional[torch.Tensor] = None,
+              stream: Optional[torch.cuda.Stream] = None):
+    """hdqt_conv_step -> (Z [M, N], dXcol [M, K], dW [K, N], workspace)."""
+    _check_dev(act, W, G, workspace)
+    geo = conv_geometry(act, kh, kw)
+    M, K, N = act.shape[0] * act.shape[2] * act.shape[3], act.shape[1] * kh * kw, W.shape[1]
+    pf, pi, pw = fwd.c(), bwd_input.c(), bwd_weight.c()
+    if workspace is None:
+        need = load().hdqt_conv_step_workspace_size(C.byref(geo), N, C.byref(pf), C.byref(pi), C.byref(pw))
+        if need == 0:
+            raise HdqtError(-13, "hdqt_conv_step_workspace_size")
+        workspace = torch.empty(need, dtype=torch.uint8, device=act.device)
+    if out is None:
+        out = (torch.empty((M, N), dtype=torch.float32, device=act.device),
+               torch.empty((M, K), dtype=torch.float32, device=act.device),
+               torch.empty((K, N), dtype=torch.float32, device=act.device))
+    Z, dX, dW = out
+    rc = load().hdqt_conv_step(_ptr(act), C.byref(geo), _ptr(W), _ptr(G), _ptr(Z), _ptr(dX), _ptr(dW), N,
+                               C.byref(pf), C.byref(pi), C.byref(pw), _ptr(workspace), workspace.numel(),
+                               _stream(stream))
+    if rc:
+        raise HdqtError(rc, "hdqt_conv_step")
+    return Z, dX, dW, workspace
 
 
 def gemm_codes(qA: torch.Tensor, qB: torch.Tensor, bA: int, bB: int, scaleA: torch.Tensor,
@@ -395,6 +464,26 @@ def layer_fwd(X: torch.Tensor, W: torch.Tensor, fwd: Params, bwd_weight: Optiona
                                _ptr(workspace), workspace.numel(), _stream(stream))
     if rc:
         raise HdqtError(rc, "hdqt_layer_fwd")
+    return out, saved
+
+
+def conv_fwd(act: torch.Tensor, kh: int, kw: int, W: torch.Tensor, fwd: Params, bwd_weight: Params,
+             stream: Optional[torch.cuda.Stream] = None):
+    """hdqt_conv_fwd -> (Z [batch*H*W, N], saved): hdqt_layer_fwd with X given as the activation.
+    Raises HdqtError with code -13 for geometries the activation-source kernels do not take."""
+    _check_dev(act, W)
+    geo = conv_geometry(act, kh, kw)
+    M, K, N = act.shape[0] * act.shape[2] * act.shape[3], act.shape[1] * kh * kw, W.shape[1]
+    assert W.shape[0] == K
+    pf, pw = fwd.c(), bwd_weight.c()
+    out = torch.empty((M, N), dtype=torch.float32, device=act.device)
+    saved = torch.empty(load().hdqt_layer_saved_size(M, K, C.byref(pw)), dtype=torch.uint8, device=act.device)
+    need = load().hdqt_layer_fwd_workspace_size(M, K, N, C.byref(pf), C.byref(pw))
+    workspace = torch.empty(max(need, 256), dtype=torch.uint8, device=act.device)
+    rc = load().hdqt_conv_fwd(_ptr(act), C.byref(geo), _ptr(W), _ptr(out), N, C.byref(pf), C.byref(pw),
+                              _ptr(saved), saved.numel(), _ptr(workspace), workspace.numel(), _stream(stream))
+    if rc:
+        raise HdqtError(rc, "hdqt_conv_fwd")
     return out, saved
 
 

@@ -161,6 +161,29 @@ hdqt::DualArgs make_dual_args(const float* T, int64_t rows, int64_t cols, int n1
     return d;
 }
 
+// rows and columns of the im2col matrix; false if the geometry is not a valid one
+bool conv_matrix_shape(const hdqt_conv_t* geo, int64_t* M, int64_t* K)
+{
+    if (!geo || geo->batch < 1 || geo->channels < 1 || geo->height < 1 || geo->width < 1 || geo->kh < 1 ||
+        geo->kw < 1)
+        return false;
+    const int64_t hw = (int64_t)geo->height * geo->width;
+    if (geo->batch > kMaxDim / hw) return false;
+    *M = geo->batch * hw;
+    *K = (int64_t)geo->channels * geo->kh * geo->kw;
+    return *M < kMaxDim && *K < kMaxDim;
+}
+
+// Make `d` read its tensor from the activation `geo` describes; false if the two-axis
+// kernels do not take that geometry.
+bool set_conv_source(hdqt::DualArgs* d, const hdqt_conv_t* geo)
+{
+    d->conv = 1;
+    d->cC = geo->channels; d->cH = geo->height; d->cW = geo->width;
+    d->ckh = geo->kh; d->ckw = geo->kw;
+    return hdqt::dual_conv_plan(d);
+}
+
 // Both quantizations of one tensor (axis 1 and axis 0): from a single read per
 // pass when the fused kernel takes the shape, else one after the other.  Both
 // calibration records must be zero.
@@ -578,6 +601,37 @@ int hdqt_quantize_dual(const float* T, int64_t rows, int64_t cols, int had_block
                              codes_axis0, scale_axis1, scale_axis0, stream);
 }
 
+int hdqt_quantize_dual_im2col(const float* act, const hdqt_conv_t* geo, int had_block,
+                              const hdqt_operand_t* op_axis1, const hdqt_operand_t* op_axis0,
+                              uint64_t seed, void* codes_axis1, float* scale_axis1, void* codes_axis0,
+                              float* scale_axis0, void* workspace, size_t workspace_bytes, void* stream_v)
+{
+    if (!act || !geo || !op_axis1 || !op_axis0 || !codes_axis1 || !codes_axis0 || !scale_axis1 ||
+        !scale_axis0)
+        return HDQT_EINVAL_NULL;
+    int64_t rows, cols;
+    if (!conv_matrix_shape(geo, &rows, &cols)) return HDQT_EINVAL_DIM;
+    int rc;
+    if ((rc = check_dims2(rows, cols)) || (rc = check_hadamard(had_block)) ||
+        (rc = check_operand(op_axis1)) || (rc = check_operand(op_axis0)))
+        return rc;
+    if (!workspace || workspace_bytes < 2 * kMetaBytes) return HDQT_EWORKSPACE;
+    if (misaligned(act) || misaligned(codes_axis1) || misaligned(codes_axis0) || misaligned(workspace))
+        return HDQT_EALIGN;
+    hipStream_t stream = static_cast<hipStream_t>(stream_v);
+    char* base = static_cast<char*>(workspace);
+    hdqt::QMeta* meta1 = reinterpret_cast<hdqt::QMeta*>(base);
+    hdqt::QMeta* meta0 = reinterpret_cast<hdqt::QMeta*>(base + kMetaBytes);
+    hdqt::DualArgs d = make_dual_args(act, rows, cols, hdqt_n_eff(cols, had_block), op_axis1, seed,
+                                      hdqt_n_eff(rows, had_block), op_axis0, seed, meta1, meta0,
+                                      codes_axis1, codes_axis0, scale_axis1, scale_axis0, 0);
+    if (!set_conv_source(&d, geo) || !hdqt::quantize_dual_eligible(d)) return HDQT_EINVAL_GEOMETRY;
+    hipError_t e = hdqt::launch_zero2(reinterpret_cast<uint32_t*>(base), (int64_t)(2 * kMetaBytes / 4),
+                                      nullptr, 0, stream);
+    if (e == hipSuccess) e = hdqt::launch_quantize_dual(d, stream);
+    return e == hipSuccess ? HDQT_OK : hip_fail(e);
+}
+
 size_t hdqt_gemm_codes_workspace_size(int64_t RA, int64_t RB, int64_t D, int64_t s)
 {
     if (RA <= 0 || RB <= 0 || D <= 0 || s < 1 || RA >= kMaxDim || RB >= kMaxDim || D >= kMaxDim) return 0;
@@ -678,10 +732,15 @@ size_t hdqt_layer_step_workspace_size(int64_t M, int64_t K, int64_t N, const hdq
     return plan_step(M, K, N, prm, bwd_input != nullptr, &L) == HDQT_OK ? L.total : 0;
 }
 
-int hdqt_layer_step(const float* X, const float* W, const float* G, float* Z, float* dX, float* dW,
-                    int64_t M, int64_t K, int64_t N, const hdqt_params_t* fwd,
-                    const hdqt_params_t* bwd_input, const hdqt_params_t* bwd_weight,
-                    void* workspace, size_t workspace_bytes, void* stream_v)
+} // extern "C"
+
+namespace {
+
+// X is the [M, K] matrix, or, with `geo`, the activation whose im2col matrix it is.
+int run_layer_step(const float* X, const hdqt_conv_t* geo, const float* W, const float* G, float* Z,
+                   float* dX, float* dW, int64_t M, int64_t K, int64_t N, const hdqt_params_t* fwd,
+                   const hdqt_params_t* bwd_input, const hdqt_params_t* bwd_weight, void* workspace,
+                   size_t workspace_bytes, void* stream_v)
 {
     if (!X || !W || !G || !Z || !dW || !fwd || !bwd_weight) return HDQT_EINVAL_NULL;
     const bool with_dx = dX != nullptr;
@@ -700,17 +759,19 @@ int hdqt_layer_step(const float* X, const float* W, const float* G, float* Z, fl
     auto codes = [&](int t) { return static_cast<void*>(base + L.codes[t]); };
     auto acc = [&](int k) { return static_cast<void*>(base + L.acc[k]); };
 
-    hipError_t e = hdqt::launch_zero2(reinterpret_cast<uint32_t*>(base), (int64_t)(L.zero_bytes / 4),
-                                      nullptr, 0, stream);
-    if (e != hipSuccess) return hip_fail(e);
-
     const int nF = L.n_eff[HDQT_GEMM_FWD], nI = L.n_eff[HDQT_GEMM_BWD_INPUT],
               nW = L.n_eff[HDQT_GEMM_BWD_WEIGHT];
     // X along K (forward) and along M (weight gradient); W along N (input gradient) and
     // along K (forward); G along N (input gradient) and along M (weight gradient)
     bool g_done = false;
-    if (with_dx) {
-        const hdqt::DualArgs dX3[3] = {
+    hipError_t e;
+    if (!with_dx) {
+        if (geo) return HDQT_EINVAL_GEOMETRY;       // (hdqt_conv_step asks for dXcol)
+        e = hdqt::launch_zero2(reinterpret_cast<uint32_t*>(base), (int64_t)(L.zero_bytes / 4), nullptr, 0,
+                               stream);
+        if (e != hipSuccess) return hip_fail(e);
+    } else {
+        hdqt::DualArgs dX3[3] = {
             make_dual_args(X, M, K, nF, &fwd->A, fwd->seed, nW, &bwd_weight->A, bwd_weight->seed,
                            meta(T_X1), meta(T_X0), codes(T_X1), codes(T_X0), nullptr, nullptr, 1),
             make_dual_args(W, K, N, nI, &bwd_input->B, bwd_input->seed, nF, &fwd->B, fwd->seed,
@@ -718,9 +779,17 @@ int hdqt_layer_step(const float* X, const float* W, const float* G, float* Z, fl
             make_dual_args(G, M, N, nI, &bwd_input->A, bwd_input->seed, nW, &bwd_weight->B,
                            bwd_weight->seed, meta(T_G1), meta(T_G0), codes(T_G1), codes(T_G0), nullptr,
                            nullptr, 3)};
+        if (geo && !set_conv_source(&dX3[0], geo)) return HDQT_EINVAL_GEOMETRY;
         const hdqt::DualArgs &dx = dX3[0], &dw = dX3[1], &dg = dX3[2];
-        if (hdqt::quantize_dual_eligible(dx) && hdqt::quantize_dual_eligible(dw) &&
-            hdqt::quantize_dual_eligible(dg)) {
+        const bool dual = hdqt::quantize_dual_eligible(dx) && hdqt::quantize_dual_eligible(dw) &&
+                          hdqt::quantize_dual_eligible(dg);
+        // an activation source is read by the two-axis kernels only (nothing is launched before
+        // this is known)
+        if (geo && !dual) return HDQT_EINVAL_GEOMETRY;
+        e = hdqt::launch_zero2(reinterpret_cast<uint32_t*>(base), (int64_t)(L.zero_bytes / 4), nullptr, 0,
+                               stream);
+        if (e != hipSuccess) return hip_fail(e);
+        if (dual) {
             // all three tensors take the two-axis kernels: one launch finds all six maxima,
             // and W's codes ride along with X's when the rounding modes agree
             e = hdqt::launch_dual_pass1(dX3, 3, stream);
@@ -785,6 +854,42 @@ int hdqt_layer_step(const float* X, const float* W, const float* G, float* Z, fl
                             acc(HDQT_GEMM_BWD_INPUT), L.acc_bytes[HDQT_GEMM_BWD_INPUT], stream);
 }
 
+} // namespace
+
+extern "C" {
+
+int hdqt_layer_step(const float* X, const float* W, const float* G, float* Z, float* dX, float* dW,
+                    int64_t M, int64_t K, int64_t N, const hdqt_params_t* fwd,
+                    const hdqt_params_t* bwd_input, const hdqt_params_t* bwd_weight,
+                    void* workspace, size_t workspace_bytes, void* stream)
+{
+    return run_layer_step(X, nullptr, W, G, Z, dX, dW, M, K, N, fwd, bwd_input, bwd_weight, workspace,
+                          workspace_bytes, stream);
+}
+
+size_t hdqt_conv_step_workspace_size(const hdqt_conv_t* geo, int64_t N, const hdqt_params_t* fwd,
+                                     const hdqt_params_t* bwd_input, const hdqt_params_t* bwd_weight)
+{
+    int64_t M, K;
+    if (!conv_matrix_shape(geo, &M, &K) || !bwd_input) return 0;
+    hdqt::DualArgs d{};
+    d.rows = M; d.cols = K;
+    if (!set_conv_source(&d, geo)) return 0;
+    return hdqt_layer_step_workspace_size(M, K, N, fwd, bwd_input, bwd_weight);
+}
+
+int hdqt_conv_step(const float* act, const hdqt_conv_t* geo, const float* W, const float* G, float* Z,
+                   float* dXcol, float* dW, int64_t N, const hdqt_params_t* fwd,
+                   const hdqt_params_t* bwd_input, const hdqt_params_t* bwd_weight, void* workspace,
+                   size_t workspace_bytes, void* stream)
+{
+    if (!geo || !dXcol || !bwd_input) return HDQT_EINVAL_NULL;
+    int64_t M, K;
+    if (!conv_matrix_shape(geo, &M, &K)) return HDQT_EINVAL_DIM;
+    return run_layer_step(act, geo, W, G, Z, dXcol, dW, M, K, N, fwd, bwd_input, bwd_weight, workspace,
+                          workspace_bytes, stream);
+}
+
 size_t hdqt_layer_saved_size(int64_t M, int64_t K, const hdqt_params_t* bwd_weight)
 {
     if (!bwd_weight || check_dims2(M, K) || check_operand(&bwd_weight->A)) return 0;
@@ -798,9 +903,14 @@ size_t hdqt_layer_fwd_workspace_size(int64_t M, int64_t K, int64_t N, const hdqt
     return plan_fwd(M, K, N, fwd, bwd_weight, &L) == HDQT_OK ? L.total : 0;
 }
 
-int hdqt_layer_fwd(const float* X, const float* W, float* Z, int64_t M, int64_t K, int64_t N,
-                   const hdqt_params_t* fwd, const hdqt_params_t* bwd_weight, void* saved,
-                   size_t saved_bytes, void* workspace, size_t workspace_bytes, void* stream_v)
+} // extern "C"
+
+namespace {
+
+// X is the [M, K] matrix, or, with `geo`, the activation whose im2col matrix it is.
+int run_layer_fwd(const float* X, const hdqt_conv_t* geo, const float* W, float* Z, int64_t M, int64_t K,
+                  int64_t N, const hdqt_params_t* fwd, const hdqt_params_t* bwd_weight, void* saved,
+                  size_t saved_bytes, void* workspace, size_t workspace_bytes, void* stream_v)
 {
     if (!X || !W || !Z || !fwd) return HDQT_EINVAL_NULL;
     if (bwd_weight && !saved) return HDQT_EINVAL_NULL;
@@ -815,10 +925,24 @@ int hdqt_layer_fwd(const float* X, const float* W, float* Z, int64_t M, int64_t 
     char* base = static_cast<char*>(workspace);
     char* sv = static_cast<char*>(saved);
     auto meta = [&](size_t off) { return reinterpret_cast<hdqt::QMeta*>(base + off); };
+    hdqt::DualArgs dconv{};
+    if (geo) {
+        // an activation source is read by the two-axis kernels only: both code sets are made,
+        // and nothing is launched before the geometry is known to be taken
+        if (!bwd_weight) return HDQT_EINVAL_NULL;
+        dconv = make_dual_args(X, M, K, L.n_fwd, &fwd->A, fwd->seed, L.n_bww, &bwd_weight->A,
+                               bwd_weight->seed, meta(L.metaX1), meta(L.metaX0), base + L.codesX1,
+                               sv + kSavedHeader, nullptr, reinterpret_cast<float*>(sv), 1);
+        if (!set_conv_source(&dconv, geo) || !hdqt::quantize_dual_eligible(dconv))
+            return HDQT_EINVAL_GEOMETRY;
+    }
     hipError_t e = hdqt::launch_zero2(reinterpret_cast<uint32_t*>(base), (int64_t)(3 * kMetaBytes / 4),
                                       nullptr, 0, stream);
     if (e != hipSuccess) return hip_fail(e);
-    if (bwd_weight)
+    if (geo) {
+        e = hdqt::launch_quantize_dual(dconv, stream);
+        rc = e == hipSuccess ? HDQT_OK : hip_fail(e);
+    } else if (bwd_weight)
         rc = run_quantize_pair(X, M, K, L.n_fwd, &fwd->A, fwd->seed, L.n_bww, &bwd_weight->A,
                                bwd_weight->seed, meta(L.metaX1), meta(L.metaX0), base + L.codesX1,
                                sv + kSavedHeader, nullptr, reinterpret_cast<float*>(sv), stream, 1);
@@ -833,6 +957,29 @@ int hdqt_layer_fwd(const float* X, const float* W, float* Z, int64_t M, int64_t 
                                       &meta(L.metaX1)->scale, &meta(L.metaW0)->scale, M, N, K, L.n_fwd,
                                       fwd->acc_bits, fwd->s, Z, nullptr, 1 + HDQT_GEMM_FWD),
                             base + L.acc, L.acc_bytes, stream);
+}
+
+} // namespace
+
+extern "C" {
+
+int hdqt_layer_fwd(const float* X, const float* W, float* Z, int64_t M, int64_t K, int64_t N,
+                   const hdqt_params_t* fwd, const hdqt_params_t* bwd_weight, void* saved,
+                   size_t saved_bytes, void* workspace, size_t workspace_bytes, void* stream)
+{
+    return run_layer_fwd(X, nullptr, W, Z, M, K, N, fwd, bwd_weight, saved, saved_bytes, workspace,
+                         workspace_bytes, stream);
+}
+
+int hdqt_conv_fwd(const float* act, const hdqt_conv_t* geo, const float* W, float* Z, int64_t N,
+                  const hdqt_params_t* fwd, const hdqt_params_t* bwd_weight, void* saved,
+                  size_t saved_bytes, void* workspace, size_t workspace_bytes, void* stream)
+{
+    if (!geo) return HDQT_EINVAL_NULL;
+    int64_t M, K;
+    if (!conv_matrix_shape(geo, &M, &K)) return HDQT_EINVAL_DIM;
+    return run_layer_fwd(act, geo, W, Z, M, K, N, fwd, bwd_weight, saved, saved_bytes, workspace,
+                         workspace_bytes, stream);
 }
 
 size_t hdqt_layer_bwd_workspace_size(int64_t M, int64_t K, int64_t N, const hdqt_params_t* bwd_input,
@@ -936,6 +1083,7 @@ const char* hdqt_strerror(int code)
     case HDQT_EWORKSPACE: return "workspace is NULL or too small";
     case HDQT_EALIGN: return "a pointer is not 16-byte aligned";
     case HDQT_EHIP: return "a HIP call failed (see hdqt_last_hip_error)";
+    case HDQT_EINVAL_GEOMETRY: return "convolution geometry or layer shape not taken by the activation-source kernels";
     default: return "unknown error code";
     }
 }

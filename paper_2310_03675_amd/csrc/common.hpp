@@ -61,6 +61,13 @@ struct DualArgs {
     float* scale_row_out;   // may be null
     float* scale_col_out;
     int profile_tag;        // which tensor of the step this is (timing table only): 0 none, 1 X, 2 W, 3 G
+    // Convolution source (conv != 0): T points at an activation [batch, C, H, W] and the
+    // tensor that is quantized is its im2col matrix for a kh x kw window, stride 1, zero
+    // padding (kh - 1) / 2 and (kw - 1) / 2: row = pixel (b, y, x), column c*kh*kw + ty*kw + tx
+    // holds act[b, c, y + ty - ph, x + tx - pw].  rows = batch*H*W, cols = C*kh*kw.
+    int conv;
+    int cC, cH, cW, ckh, ckw;
+    int pPH, pPW, pCN;      // the part of the activation a 64 x 64 tile reads: rows, row length, channels
 };
 
 struct GemmArgs {
@@ -100,6 +107,8 @@ constexpr int kMaxDualBatch = 3;
 hipError_t launch_dual_pass1(const DualArgs* qs, int n, hipStream_t stream);
 hipError_t launch_dual_pass2(const DualArgs* qs, int n, hipStream_t stream);
 bool dual_pass2_batchable(const DualArgs* qs, int n);
+// fills the patch extents of a convolution source; false if the kernels do not take the geometry
+bool dual_conv_plan(DualArgs* q);
 // zero a[0, na) and b[0, nb) (b may be null) in one launch
 hipError_t launch_zero2(uint32_t* a, int64_t na, uint32_t* b, int64_t nb, hipStream_t stream);
 // sum the `splits` slices of `partial` ([splits, count]); the totals go to acc_out

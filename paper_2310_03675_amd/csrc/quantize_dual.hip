@@ -65,6 +65,127 @@ __device__ __forceinline__ void tile_load(Tile& t, const DualArgs& q, const Dual
         }
 }
 
+// The same tile when the source is an activation and the tensor its im2col matrix.
+// The 64 rows of a tile are 64 consecutive pixels of one image (whole image rows when
+// W <= 64, a 64-pixel run of one row otherwise), its 64 columns a run of (channel, tap)
+// pairs: everything the tile reads lies in a patch of pCN channels x pPH rows x pPW
+// pixels, zero border included.  The wave copies the patch into its own piece of LDS
+// with coalesced reads, then gathers its 64 x 64 values from there: an element's patch
+// address is (row part of its pixel) + (column part of its channel and tap).
+// The activation is read from HBM about once per pass instead of kh*kw times.
+constexpr int kPatchUnroll = 32;
+
+__device__ __forceinline__ void tile_load_conv(Tile& t, const DualArgs& q, const DualCtx& x,
+                                               int64_t row0, int64_t col0, float* patch, int lane)
+{
+    const int W = q.cW, H = q.cH, C = q.cC, kw = q.ckw, khw = q.ckh * q.ckw;
+    const int ph = (q.ckh - 1) / 2, pw = (kw - 1) / 2;
+    const int PH = q.pPH, PW = q.pPW, CN = q.pCN;
+    int* coltab = reinterpret_cast<int*>(patch + ((CN * PH * PW + 3) & ~3));      // 64 column parts
+
+    // where the tile lies (the same in every lane)
+    const uint32_t m0 = (uint32_t)__builtin_amdgcn_readfirstlane((int)row0);
+    const uint32_t k0 = (uint32_t)__builtin_amdgcn_readfirstlane((int)col0);
+    const uint32_t HW = (uint32_t)(H * W);
+    const uint32_t b = m0 / HW, rem = m0 - b * HW;
+    const int y_first = (int)(rem / (uint32_t)W), x_first = (int)(rem - (uint32_t)y_first * (uint32_t)W);
+    const int c_lo = (int)(k0 / (uint32_t)khw);
+
+    // ---- patch: row q = (channel c_lo + q / PH, image row y_first - ph + q % PH).  Rows of up
+    // to 32 words go two per step (32 lanes each).  What costs here is the number of load
+    // round trips, not the instructions: kPatchUnroll steps issue their loads together
+    // (every address is clamped into the activation, so no load is conditional), then store.
+    // (One row per step with scalar row arithmetic halves the vector instructions and is
+    // 35 % slower: twice the round trips.)
+    const bool two = PW <= 32;
+    const int lpr = two ? 32 : 64, rpi = two ? 2 : 1;
+    const int lrow = two ? (lane >> 5) : 0, lx = lane & (lpr - 1);
+    const int rows_total = CN * PH;
+    const int steps = (rows_total + rpi - 1) / rpi;
+    const float* img = q.T + (int64_t)b * C * H * W;
+    for (int ch = 0; ch * lpr < PW; ++ch) {
+        const int pxx = ch * lpr + lx;
+        const int gx = x_first - pw + pxx;
+        const bool col_ok = pxx < PW && gx >= 0 && gx < W;
+        const int gxc = gx < 0 ? 0 : (gx >= W ? W - 1 : gx);
+        int c_rel = 0, pyy = lrow;
+        while (pyy >= PH) { pyy -= PH; ++c_rel; }
+        for (int it0 = 0; it0 < steps; it0 += kPatchUnroll) {
+            float v[kPatchUnroll];
+            bool keep[kPatchUnroll];
+#pragma unroll
+            for (int u = 0; u < kPatchUnroll; ++u) {
+                const int gy = y_first - ph + pyy, c = c_lo + c_rel;
+                const int gyc = gy < 0 ? 0 : (gy >= H ? H - 1 : gy);
+                const int cc = c >= C ? C - 1 : c;
+                v[u] = img[(cc * H + gyc) * W + gxc];
+                keep[u] = col_ok && gy >= 0 && gy < H && c < C;
+                pyy += rpi;
+                while (pyy >= PH) { pyy -= PH; ++c_rel; }
+            }
+#pragma unroll
+            for (int u = 0; u < kPatchUnroll; ++u) {
+                const int qrow = (it0 + u) * rpi + lrow;
+                if (pxx < PW && qrow < rows_total) patch[qrow * PW + pxx] = keep[u] ? v[u] : 0.0f;
+            }
+        }
+    }
+    // ---- column parts of the tile's 64 columns, one per lane
+    {
+        const uint32_t k = k0 + (uint32_t)lane;
+        const uint32_t c = k / (uint32_t)khw, tap = k - c * (uint32_t)khw;
+        const uint32_t ty = tap / (uint32_t)kw, tx = tap - ty * (uint32_t)kw;
+        coltab[lane] = ((int)c - c_lo) * PH * PW + (int)ty * PW + (int)tx;
+    }
+    // LDS operations of one wave are carried out in order; the fence keeps the compiler
+    // from moving the reads below above the writes of other lanes
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+
+    // ---- gather: pixel 8*rg + i of the tile is (image row off / Wt, position off % Wt),
+    // Wt = min(W, 64), a power of two.  With Wt >= 8 the lane's eight pixels are neighbours
+    // in one image row: eight consecutive patch words per column.
+    const int wt_shift = (W >= 64) ? 6 : (31 - __builtin_clz((unsigned)W));
+    if (wt_shift >= 3) {
+        const int off = x.rg * 8;
+        const float* base = patch + (off >> wt_shift) * PW + (off & ((1 << wt_shift) - 1));
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+            const int4 cp = *reinterpret_cast<const int4*>(coltab + 32 * h + 4 * x.cg);
+            const float* p0 = base + cp.x;
+            const float* p1 = base + cp.y;
+            const float* p2 = base + cp.z;
+            const float* p3 = base + cp.w;
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                t.v[h][0][i] = p0[i];
+                t.v[h][1][i] = p1[i];
+                t.v[h][2][i] = p2[i];
+                t.v[h][3][i] = p3[i];
+            }
+        }
+    } else {
+        int rowpart[8];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            const int off = x.rg * 8 + i;
+            rowpart[i] = (off >> wt_shift) * PW + (off & ((1 << wt_shift) - 1));
+        }
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+            const int4 cp = *reinterpret_cast<const int4*>(coltab + 32 * h + 4 * x.cg);
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                t.v[h][0][i] = patch[rowpart[i] + cp.x];
+                t.v[h][1][i] = patch[rowpart[i] + cp.y];
+                t.v[h][2][i] = patch[rowpart[i] + cp.z];
+                t.v[h][3][i] = patch[rowpart[i] + cp.w];
+            }
+        }
+    }
+}
+
 // Random bits of stochastic rounding for the lane's elements of one tile row: four
 // consecutive elements at h = 0 (index e, e % 4 == 0) and four at h = 1 (index
 // e + 32).  Each group lies in one Philox block (block e/8, words (e%8)/2 and
@@ -347,6 +468,7 @@ struct DualBatch {
     int first[kMaxDualBatch + 1];
     int gx[kMaxDualBatch];       // workgroups along the columns
     int WC[kMaxDualBatch];       // waves side by side in a workgroup (1, 2 or 4)
+    int lds_per_wave;            // floats of LDS per wave (convolution sources), a multiple of 4
 };
 
 // Wave w of a workgroup owns the tile at columns [64*wc, 64*wc + 64) of the
@@ -362,8 +484,8 @@ struct DualBatch {
 // the long, memory-bound ones instead of running after them on a half-empty chip.
 constexpr int kRoundPerTensor = 4;
 
-template <bool QUANT, int ROUND, bool N64>
-__device__ __forceinline__ void dual_block(const DualBatch& b, int k, float (*red)[2])
+template <bool QUANT, int ROUND, bool N64, bool CONV>
+__device__ __forceinline__ void dual_block(const DualBatch& b, int k, float (*red)[2], float* lds)
 {
     const DualArgs& q = b.t[k];
     const int count = b.first[k + 1] - b.first[k];
@@ -384,7 +506,10 @@ __device__ __forceinline__ void dual_block(const DualBatch& b, int k, float (*re
     DualCtx x;
     dual_setup<N64>(x, q, lane);
     Tile t;
-    if (live) tile_load(t, q, x, row0, col0);
+    if (live) {
+        if (CONV && q.conv) tile_load_conv(t, q, x, row0, col0, lds + wave * b.lds_per_wave, lane);
+        else tile_load(t, q, x, row0, col0);
+    }
     if (QUANT) {
         const Scaling s_row = load_scaling(q.meta_row, q.clip_row, q.b_row);
         const Scaling s_col = load_scaling(q.meta_col, q.clip_col, q.b_col);
@@ -397,20 +522,21 @@ __device__ __forceinline__ void dual_block(const DualBatch& b, int k, float (*re
     }
 }
 
-template <bool QUANT, int ROUND, bool N64>
+template <bool QUANT, int ROUND, bool N64, bool CONV>
 __global__ __launch_bounds__(kThreads) void fwht_dual_kernel(DualBatch b)
 {
     __shared__ float red[kThreads / kWave][2];
+    extern __shared__ __attribute__((aligned(16))) float lds[];      // CONV: one patch per wave
 
     int k = 0;
     while (k + 1 < b.n && (int)blockIdx.x >= b.first[k + 1]) ++k;
     if constexpr (ROUND == kRoundPerTensor) {
         // two complete bodies, chosen per workgroup: sharing anything between them
         // (one load, one setup) lets the compiler keep both paths' registers alive
-        if (b.t[k].st_row) dual_block<QUANT, 3, N64>(b, k, red);
-        else dual_block<QUANT, 0, N64>(b, k, red);
+        if (b.t[k].st_row) dual_block<QUANT, 3, N64, CONV>(b, k, red, lds);
+        else dual_block<QUANT, 0, N64, CONV>(b, k, red, lds);
     } else {
-        dual_block<QUANT, ROUND, N64>(b, k, red);
+        dual_block<QUANT, ROUND, N64, CONV>(b, k, red, lds);
     }
 }
 
@@ -426,6 +552,7 @@ bool make_batch(const DualArgs* qs, int n, DualBatch* b)
     if (n < 1 || n > kMaxDualBatch) return false;
     b->n = n;
     int64_t total = 0;
+    int lds = 0;
     for (int k = 0; k < n; ++k) {
         const DualArgs& q = qs[k];
         const int64_t strips = q.cols / kTile;
@@ -433,6 +560,10 @@ bool make_batch(const DualArgs* qs, int n, DualBatch* b)
         const int64_t tall = (int64_t)kTile * (4 / WC);
         const int64_t gx = strips / WC, gy = (q.rows + tall - 1) / tall;
         b->t[k] = q;
+        if (q.conv) {
+            const int need = ((q.pCN * q.pPH * q.pPW + 3) & ~3) + kTile;
+            if (need > lds) lds = need;
+        }
         b->first[k] = (int)total;
         b->gx[k] = (int)gx;
         b->WC[k] = WC;
@@ -440,10 +571,34 @@ bool make_batch(const DualArgs* qs, int n, DualBatch* b)
         if (total >= ((int64_t)1 << 31)) return false;
     }
     b->first[n] = (int)total;
+    b->lds_per_wave = lds;
     return true;
 }
 
 } // namespace
+
+// Geometries the im2col source takes: odd windows, and tiles of 64 pixels that are whole
+// image rows (W a power of two up to 64, H*W a multiple of 64) or lie inside one row
+// (W a multiple of 64); the patch of a tile must fit the wave's share of LDS.
+constexpr int kMaxPatchFloats = 3008;      // 12 KB per wave with the column table
+
+bool dual_conv_plan(DualArgs* q)
+{
+    const int W = q->cW, H = q->cH, kh = q->ckh, kw = q->ckw;
+    if (q->cC < 1 || H < 1 || W < 1 || kh < 1 || kw < 1 || kh % 2 == 0 || kw % 2 == 0) return false;
+    if (kh > 15 || kw > 15) return false;
+    const bool row_run = (W % kTile == 0);
+    const bool whole_rows = (W < kTile) && (kTile % W == 0) && (((int64_t)H * W) % kTile == 0);
+    if (!row_run && !whole_rows) return false;
+    // one image is indexed with 32 bits
+    if ((int64_t)q->cC * H * W >= ((int64_t)1 << 31) || q->rows >= ((int64_t)1 << 31) || q->cols >= ((int64_t)1 << 31))
+        return false;
+    if (q->rows % ((int64_t)H * W) != 0 || q->cols != (int64_t)q->cC * kh * kw) return false;
+    q->pPH = (row_run ? 1 : kTile / W) + kh - 1;
+    q->pPW = (row_run ? kTile : W) + kw - 1;
+    q->pCN = (kTile - 1) / (kh * kw) + 2;
+    return q->pCN * q->pPH * q->pPW <= kMaxPatchFloats;
+}
 
 bool quantize_dual_eligible(const DualArgs& q)
 {
@@ -460,10 +615,16 @@ hipError_t launch_dual_pass1(const DualArgs* qs, int n, hipStream_t stream)
                          : (qs[0].profile_tag ? K_DUAL_ABSMAX_X + (qs[0].profile_tag - 1) : K_DUAL_ABSMAX);
     ProfileScope ps(id, stream);
     const dim3 grid((unsigned)b.first[n]), block(kThreads);
-    if (all_order_64(qs, n))
-        hipLaunchKernelGGL((fwht_dual_kernel<false, 0, true>), grid, block, 0, stream, b);
-    else
-        hipLaunchKernelGGL((fwht_dual_kernel<false, 0, false>), grid, block, 0, stream, b);
+    const size_t lds = (size_t)(kThreads / kWave) * b.lds_per_wave * sizeof(float);
+    const bool n64 = all_order_64(qs, n);
+    if (lds) {      // a convolution source among the tensors
+        if (n64) hipLaunchKernelGGL((fwht_dual_kernel<false, 0, true, true>), grid, block, lds, stream, b);
+        else hipLaunchKernelGGL((fwht_dual_kernel<false, 0, false, true>), grid, block, lds, stream, b);
+    } else if (n64) {
+        hipLaunchKernelGGL((fwht_dual_kernel<false, 0, true, false>), grid, block, 0, stream, b);
+    } else {
+        hipLaunchKernelGGL((fwht_dual_kernel<false, 0, false, false>), grid, block, 0, stream, b);
+    }
     return hipGetLastError();
 }
 
@@ -492,10 +653,13 @@ hipError_t launch_dual_pass2(const DualArgs* qs, int n, hipStream_t stream)
     ProfileScope ps(id, stream);
     const dim3 grid((unsigned)b.first[n]), block(kThreads);
     const bool n64 = all_order_64(qs, n);
+    const size_t lds = (size_t)(kThreads / kWave) * b.lds_per_wave * sizeof(float);
 #define HDQT_LAUNCH_PASS2(ROUND)                                                                     \
     do {                                                                                            \
-        if (n64) hipLaunchKernelGGL((fwht_dual_kernel<true, ROUND, true>), grid, block, 0, stream, b); \
-        else hipLaunchKernelGGL((fwht_dual_kernel<true, ROUND, false>), grid, block, 0, stream, b);  \
+        if (lds && n64) hipLaunchKernelGGL((fwht_dual_kernel<true, ROUND, true, true>), grid, block, lds, stream, b); \
+        else if (lds) hipLaunchKernelGGL((fwht_dual_kernel<true, ROUND, false, true>), grid, block, lds, stream, b); \
+        else if (n64) hipLaunchKernelGGL((fwht_dual_kernel<true, ROUND, true, false>), grid, block, 0, stream, b); \
+        else hipLaunchKernelGGL((fwht_dual_kernel<true, ROUND, false, false>), grid, block, 0, stream, b); \
     } while (0)
     if (!same) HDQT_LAUNCH_PASS2(kRoundPerTensor);
     else if (qs[0].st_row && qs[0].st_col) HDQT_LAUNCH_PASS2(3);

@@ -12,7 +12,7 @@ structure (ReLU sparsity, im2col repetition, zero borders, heavy-tailed
 outliers) of such layers.
 """
 from dataclasses import dataclass
-from typing import Dict, List, Tuple
+from typing import Dict, List, Optional, Tuple
 
 import torch
 
@@ -36,6 +36,8 @@ class Layer:
     X: torch.Tensor
     W: torch.Tensor
     G: torch.Tensor
+    act: Optional[torch.Tensor] = None     # convolution layers: the activation X is unfolded from
+    window: Optional[Tuple[int, int]] = None        # and its (kh, kw)
 
     @property
     def M(self) -> int:
@@ -82,7 +84,7 @@ def har_conv_layer(batch: int = 256, seq: int = 128, cin: int = 64, cout: int = 
     K = cin * kernel
     W = _normal((K, cout), (2.0 / K) ** 0.5, _gen(seed, "W", layer))
     G = _normal((batch * seq, cout), 1e-3 ** 0.5, _gen(seed, "G", layer))
-    return Layer(f"har_conv_{batch * seq}x{K}x{cout}", X, W, G)
+    return Layer(f"har_conv_{batch * seq}x{K}x{cout}", X, W, G, act.unsqueeze(2).contiguous(), (1, kernel))
 
 
 def resnet_conv_layer(batch: int = 256, cin: int = 128, cout: int = 128, hw: int = 16,
@@ -93,7 +95,7 @@ def resnet_conv_layer(batch: int = 256, cin: int = 128, cout: int = 128, hw: int
     K = cin * 9
     W = _normal((K, cout), (2.0 / K) ** 0.5, _gen(seed, "W", layer))
     G = _normal((batch * hw * hw, cout), g_var ** 0.5, _gen(seed, "G", layer))
-    return Layer(f"resnet_conv_{batch * hw * hw}x{K}x{cout}", X, W, G)
+    return Layer(f"resnet_conv_{batch * hw * hw}x{K}x{cout}", X, W, G, act, (3, 3))
 
 
 def outlier_matrix(rows: int, cols: int, seed: int, role: str, p: float = 0.01,

@@ -144,7 +144,7 @@ def test_gemm_codes_argument_errors():
 
 def test_strerror_texts():
     assert B.strerror(0) == "success"
-    for code in range(-12, 0):
+    for code in range(-13, 0):
         assert B.strerror(code) and "unknown error" not in B.strerror(code)
     assert "unknown error" in B.strerror(-99)
     assert B.load().hdqt_last_hip_error() == 0
@@ -321,3 +321,34 @@ def test_bf16_output_argument_errors():
     assert f(FAKE, FAKE, None, 64, 64, 64, C.byref(p), None, FAKE, 1 << 30, None) == E["HDQT_EINVAL_NULL"]
     assert f(FAKE, FAKE, FAKE, 64, 64, 64, C.byref(p), None, FAKE, 16, None) == E["HDQT_EWORKSPACE"]
     assert f(FAKE, FAKE, FAKE, 0, 64, 64, C.byref(p), None, FAKE, 1 << 30, None) == E["HDQT_EINVAL_DIM"]
+
+
+def test_conv_source_argument_errors():
+    """hdqt_quantize_dual_im2col / hdqt_conv_step: geometry and argument errors are found on
+    the host."""
+    lib = B.load()
+    op = B.Operand(b=4).c()
+    good = B.CConv(2, 64, 16, 16, 3, 3)
+
+    def rc(act=FAKE, geo=good, n=64, ws=FAKE, ws_bytes=1 << 20):
+        return lib.hdqt_quantize_dual_im2col(act, C.byref(geo) if geo is not None else None, n, C.byref(op),
+                                             C.byref(op), 0, FAKE, FAKE, FAKE, FAKE, ws, ws_bytes, None)
+    assert rc(act=None) == E["HDQT_EINVAL_NULL"]
+    assert rc(geo=None) == E["HDQT_EINVAL_NULL"]
+    assert rc(geo=B.CConv(0, 64, 16, 16, 3, 3)) == E["HDQT_EINVAL_DIM"]
+    assert rc(n=48) == E["HDQT_EINVAL_HADAMARD"]
+    assert rc(ws_bytes=8) == E["HDQT_EWORKSPACE"]
+    for bad in (B.CConv(2, 64, 16, 16, 2, 2), B.CConv(2, 64, 12, 12, 3, 3), B.CConv(2, 3, 16, 16, 3, 3),
+                B.CConv(2, 64, 3, 16, 3, 3), B.CConv(1, 64, 8, 8, 1, 1)):
+        assert rc(geo=bad) == E["HDQT_EINVAL_GEOMETRY"]
+    p = _cparams()
+    size = lib.hdqt_conv_step_workspace_size
+    assert size(C.byref(good), 128, C.byref(p), C.byref(p), C.byref(p)) == \
+        lib.hdqt_layer_step_workspace_size(512, 576, 128, C.byref(p), C.byref(p), C.byref(p)) > 0
+    assert size(C.byref(B.CConv(2, 64, 12, 12, 3, 3)), 128, C.byref(p), C.byref(p), C.byref(p)) == 0
+    step = lib.hdqt_conv_step
+    args = lambda geo, dx=FAKE: (FAKE, C.byref(geo), FAKE, FAKE, FAKE, dx, FAKE, 128, C.byref(p), C.byref(p),
+                                 C.byref(p), FAKE, 1 << 30, None)
+    assert step(*args(good, dx=None)) == E["HDQT_EINVAL_NULL"]
+    assert step(*args(B.CConv(2, 64, 12, 12, 3, 3))) == E["HDQT_EINVAL_GEOMETRY"]
+    assert step(*args(B.CConv(2, 64, 16, 16, 3, 3))[:-3], FAKE, 16, None) == E["HDQT_EWORKSPACE"]

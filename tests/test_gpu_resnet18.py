@@ -72,9 +72,16 @@ def test_resnet18_training_step_matches_oracle_per_matmul():
     table = {name: (M, K, N) for name, M, K, N in workloads.resnet18_layer_table(batch)}
     assert set(cap) == set(table)
     rng = np.random.default_rng(4321)
+    fused = []
     for name in net.layer_names:
         c = cap[name]
         M, K, N = table[name]
+        if "X" not in c:
+            # a layer that read its activation directly: the matrix it stands for, by PyTorch's unfold
+            kh = {27: 3, 64: 1, 128: 1, 256: 1}.get(K, 3)
+            cols = torch.nn.functional.unfold(c["act"].cpu(), kernel_size=kh, padding=kh // 2)
+            c["X"] = cols.transpose(1, 2).reshape(M, K).contiguous()
+            fused.append(name)
         assert tuple(c["X"].shape) == (M, K) and tuple(c["W"].shape) == (K, N) and tuple(c["G"].shape) == (M, N)
         cfg = LayerConfig(seed=11, layer_id=net.layer_names.index(name))
         print(f"{name}: {M}x{K}x{N}: oracle", flush=True)
@@ -87,3 +94,6 @@ def test_resnet18_training_step_matches_oracle_per_matmul():
         else:
             check_sampled(BWI, ("G", G), ("W", W), c["dX"], cfg.params(BWI, c["step"]), rng, cache)
         cap[name] = None            # release the captured tensors of this layer
+    # the stride-1 3x3 layers at 32x32, 16x16 and 8x8 read their activation directly
+    print("layers that read the activation directly:", fused, flush=True)
+    assert len(fused) >= 9
