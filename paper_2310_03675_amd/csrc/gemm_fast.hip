@@ -22,8 +22,9 @@
 //     of a pair are two consecutive tiles of the same output element.
 //   * any other accumulator width or tile length: v_med3_i32 against bounds
 //     scaled by 256, add, and one exact shift at the end.
-//   * LDS holds int8, double-buffered, and the global loads run one stage
-//     ahead of the multiplication, across output-tile boundaries.
+//   * LDS holds int8, double-buffered, and the global loads run two stages
+//     (one in the s = 64 instance) ahead of the multiplication, across
+//     output-tile boundaries.
 
 #include "common.hpp"
 
@@ -46,7 +47,10 @@ constexpr int KS_LONG = 128;          // codes per LDS stage: 4 MFMA steps.  (St
 constexpr int KSTEP = 32;             // codes per MFMA
 constexpr int kScaleShift = 8;        // both operands carry a factor 16
 
-enum Epilogue { EPI_GENERIC = 0, EPI_SAT8_S32 = 1, EPI_SAT8_S64 = 2 };
+enum Epilogue { EPI_GENERIC = 0, EPI_SAT8_S32 = 1, EPI_SAT8_S64 = 2, EPI_STAGES = 3 };
+// EPI_STAGES: the generic clamp for tiles that are whole stages (s a multiple of KS_LONG): the
+// tile ends are tested once per stage, so nothing branches between the MFMAs of a stage and
+// the fragment loads of its four steps can run ahead of them.
 
 template <int UNITS>
 struct Staged {
@@ -212,6 +216,46 @@ __global__ __launch_bounds__(64 * WAVES, WAVES == 8 ? 4 : 2) void gemm_i4_kernel
                             total[a][c][r] = add_sat8_pair(total[a][c][r], p0[r], p1[r]);
                     }
             }
+        } else if (EPI == EPI_STAGES) {
+            v4i fa[NSTEP][2], fb[NSTEP][CS];
+#pragma unroll
+            for (int ks = 0; ks < NSTEP; ++ks)
+#pragma unroll
+                for (int h = 0; h < 2; ++h) {
+                    fa[ks][h] = frag(As[buf], wm * 64 + h * 32, ks);
+                    if (h < CS) fb[ks][h] = frag(Bs[buf], wn * WCOLS + h * 32, ks);
+                }
+#pragma unroll
+            for (int ks = 0; ks < NSTEP; ++ks)
+#pragma unroll
+                for (int a = 0; a < 2; ++a)
+#pragma unroll
+                    for (int c = 0; c < CS; ++c)
+                        part[a][c] =
+                            __builtin_amdgcn_mfma_i32_32x32x32_i8(fa[ks][a], fb[ks][c], part[a][c], 0, 0, 0);
+            // issue order: the fragments of step ks + 1 are requested before the MFMAs of step ks
+            // (left alone, the scheduler puts every read right in front of its use to save
+            // registers, and each MFMA pair then waits a whole LDS round trip)
+            constexpr int kReads = 2 + CS, kMfmas = 2 * CS;
+            __builtin_amdgcn_sched_group_barrier(0x100, 2 * kReads, 0);
+#pragma unroll
+            for (int ks = 0; ks < NSTEP; ++ks) {
+                __builtin_amdgcn_sched_group_barrier(0x008, kMfmas, 0);
+                if (ks + 2 < NSTEP) __builtin_amdgcn_sched_group_barrier(0x100, kReads, 0);
+            }
+            step_in_tile += NSTEP;
+            if (step_in_tile >= steps_per_tile) {
+                step_in_tile = 0;
+#pragma unroll
+                for (int a = 0; a < 2; ++a)
+#pragma unroll
+                    for (int c = 0; c < CS; ++c)
+#pragma unroll
+                        for (int r = 0; r < 16; ++r) {
+                            total[a][c][r] += clamp3(part[a][c][r], lo, hi);
+                            part[a][c][r] = 0;
+                        }
+            }
         } else {
 #pragma unroll
             for (int ks = 0; ks < NSTEP; ++ks) {
@@ -246,7 +290,7 @@ __global__ __launch_bounds__(64 * WAVES, WAVES == 8 ? 4 : 2) void gemm_i4_kernel
         if (c_k < k_end) return;
 
         // ---- end of the output tile (row0, c_ct)
-        if (EPI == EPI_GENERIC && step_in_tile != 0) {
+        if ((EPI == EPI_GENERIC || EPI == EPI_STAGES) && step_in_tile != 0) {
             // a short last tile (D not a multiple of s) ends without reaching steps_per_tile
             step_in_tile = 0;
 #pragma unroll
@@ -275,7 +319,7 @@ __global__ __launch_bounds__(64 * WAVES, WAVES == 8 ? 4 : 2) void gemm_i4_kernel
         if constexpr (BF16) if (pair_bf16) {
             const bool odd = lane & 1;
             auto value = [&](int t) -> float {
-                return (float)((EPI == EPI_GENERIC) ? (t >> kScaleShift) : t) * dq;
+                return (float)((EPI == EPI_GENERIC || EPI == EPI_STAGES) ? (t >> kScaleShift) : t) * dq;
             };
             // quad_perm [1,0,3,2]: the value of lane ^ 1
             auto neighbour = [](float f) -> float {
@@ -328,7 +372,7 @@ __global__ __launch_bounds__(64 * WAVES, WAVES == 8 ? 4 : 2) void gemm_i4_kernel
                 for (int r = 0; r < 16; ++r) {
                     const int rr = a * 32 + 8 * (r >> 2) + (r & 3);
                     const int64_t uo = (int64_t)rr * g.RB + c * 32;
-                    const int v = (EPI == EPI_GENERIC) ? (total[a][c][r] >> kScaleShift) : total[a][c][r];
+                    const int v = (EPI == EPI_GENERIC || EPI == EPI_STAGES) ? (total[a][c][r] >> kScaleShift) : total[a][c][r];
                     total[a][c][r] = 0;
                     bool ok = interior;
                     if (!interior)
@@ -348,12 +392,28 @@ __global__ __launch_bounds__(64 * WAVES, WAVES == 8 ? 4 : 2) void gemm_i4_kernel
         c_ct += gridDim.z;
     };
 
-    Staged<UNITS> st;
-    fetch_next(st);
-    int buf = 0;
-    while (c_ct < n_ct) {       // stage() advances c_ct at the end of a tile
-        stage(st, buf);
-        buf ^= 1;
+    // The global loads run two stages ahead of the multiplication where the registers allow
+    // it (one stage of 128 codes is 8 MFMAs per wave, about 0.5 us of matrix time per SIMD,
+    // less than a trip to L2 under load), one stage ahead in the s = 64 instance, which has
+    // no eight registers to spare at four waves per SIMD.
+    constexpr bool kDeep = (EPI != EPI_SAT8_S64);
+    if constexpr (kDeep) {
+        Staged<UNITS> st0, st1;
+        fetch_next(st0);
+        fetch_next(st1);
+        while (c_ct < n_ct) {       // stage() advances c_ct at the end of a tile
+            stage(st0, 0);
+            if (c_ct >= n_ct) break;
+            stage(st1, 1);
+        }
+    } else {
+        Staged<UNITS> st;
+        fetch_next(st);
+        int buf = 0;
+        while (c_ct < n_ct) {
+            stage(st, buf);
+            buf ^= 1;
+        }
     }
 }
 
@@ -408,6 +468,7 @@ hipError_t launch_gemm_fast(const GemmArgs& g_in, hipStream_t stream)
     } while (0)
     if (s32) HDQT_LAUNCH_I4(EPI_SAT8_S32);
     else if (sat8_path(g)) HDQT_LAUNCH_I4(EPI_SAT8_S64);
+    else if (g.s % KS_LONG == 0) HDQT_LAUNCH_I4(EPI_STAGES);
     else HDQT_LAUNCH_I4(EPI_GENERIC);
 #undef HDQT_LAUNCH_I4
     return hipGetLastError();
