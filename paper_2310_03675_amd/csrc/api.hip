@@ -112,13 +112,21 @@ int hip_fail(hipError_t e)
 // How many workgroups share an output tile along the contraction.  The matmul
 // kernels keep two workgroups per CU resident (512 on the chip): the split fills
 // those places once and never spills a few workgroups into a second round.
-int choose_splits(int64_t RA, int64_t RB, int64_t n_tiles)
+// Parts the contraction is split into when the output has too few tiles to fill the chip.
+// Every part writes an int32 slice of the output that a second pass reads back, so parts
+// are only worth their traffic while the slices cost no more than about twice what the
+// operands cost to read (a weight gradient: yes; a forward product with one workgroup per
+// CU: no).
+int choose_splits(int64_t RA, int64_t RB, int64_t D, int64_t n_tiles)
 {
     const int64_t blocks = ((RA + 127) / 128) * ((RB + 127) / 128);
     if (blocks > 256 || n_tiles < 8) return 1;
     int64_t want = 512 / blocks;
     if (want > n_tiles / 4) want = n_tiles / 4;
     if (want > 1024) want = 1024;
+    // slices: 4 * RA * RB bytes each, twice (written, read back); operands: about (RA + RB) * D / 2
+    const int64_t cap = ((RA + RB) * D) / (8 * RA * RB);
+    if (want > cap) want = cap;
     return want < 1 ? 1 : (int)want;
 }
 
@@ -228,7 +236,7 @@ hdqt::GemmArgs plan_gemm(const void* qA, const void* qB, int bA, int bB, const f
     // the input gradient of the 65536 x 1152 layer takes 90 us instead of 53 us).
     const int64_t out_elem = out ? (int64_t)sizeof(float) : (int64_t)sizeof(uint16_t);
     g.stream_out = (RA * RB * out_elem >= ((int64_t)128 << 20)) ? 1 : 0;
-    g.splits = choose_splits(RA, RB, g.n_tiles);
+    g.splits = choose_splits(RA, RB, D, g.n_tiles);
     g.tiles_per_split = (g.n_tiles + g.splits - 1) / g.splits;
     g.splits = (int)((g.n_tiles + g.tiles_per_split - 1) / g.tiles_per_split);
     return g;
@@ -239,7 +247,7 @@ hdqt::GemmArgs plan_gemm(const void* qA, const void* qB, int bA, int bB, const f
 size_t partial_bytes(int64_t RA, int64_t RB, int64_t D, int64_t s)
 {
     const int64_t s_eff = s < D ? s : D;
-    const int splits = choose_splits(RA, RB, (D + s_eff - 1) / s_eff);
+    const int splits = choose_splits(RA, RB, D, (D + s_eff - 1) / s_eff);
     return splits > 1 ? (size_t)splits * (size_t)(RA * RB) * sizeof(int32_t) : 0;
 }
 
@@ -353,7 +361,7 @@ int plan_step(int64_t M, int64_t K, int64_t N, const hdqt_params_t* const prm[3]
         if (k == HDQT_GEMM_BWD_INPUT && !with_dx) continue;
         L->n_eff[k] = hdqt_n_eff(o[k].D, prm[k]->had_block);
         const int64_t s = prm[k]->s < o[k].D ? prm[k]->s : o[k].D;
-        L->splits[k] = choose_splits(o[k].RA, o[k].RB, (o[k].D + s - 1) / s);
+        L->splits[k] = choose_splits(o[k].RA, o[k].RB, o[k].D, (o[k].D + s - 1) / s);
     }
     L->zero_bytes = off;
     for (int k = 0; k < 3; ++k) {
