@@ -227,6 +227,16 @@ def dequantize_bf16(acc, scaleA, scaleB, n: int) -> np.ndarray:
     return out
 
 
+def col2im_acc(acc, batch: int, channels: int, H: int, W: int, kh: int, kw: int) -> np.ndarray:
+    """Integer accumulators of dX [batch*H*W, C*kh*kw] folded back onto the layer's input:
+    int32 [batch, C, H, W] (dequantize() of it is the input gradient)."""
+    acc = np.ascontiguousarray(acc, dtype=np.int32)
+    assert acc.shape == (batch * H * W, channels * kh * kw)
+    out = np.empty((batch, channels, H, W), dtype=np.int32)
+    lib().orc_col2im_acc(_p(acc, C.c_int32), C.c_int64(batch), channels, H, W, kh, kw, _p(out, C.c_int32))
+    return out
+
+
 def gemm_shapes(kind: int, M: int, K: int, N: int):
     """-> (RA, RB, D): output is [RA, RB], contraction length D."""
     return {FWD: (M, N, K), BWD_INPUT: (M, K, N), BWD_WEIGHT: (K, N, M)}[kind]

@@ -33,6 +33,9 @@
  *   5'. second reading of step 5 (orc_tiled_matmul_requant): every tile's
  *                     partial-sum tensor goes through Q with a bits and its own
  *                     max, and the tile results are added
+ *   5''. input gradient of a convolution (orc_col2im_acc, an extension): the
+ *                     accumulators of dX = G W^T folded back onto the layer's input
+ *                     (the transpose of im2col) as exact integer sums, then step 6
  *   6'. narrow output (orc_dequantize_bf16, an extension that is not in the
  *                     paper): step 6's binary32 value rounded to bfloat16,
  *                     nearest, ties to even; pinned by hand-built ties and a
@@ -392,6 +395,41 @@ void orc_dequantize_bf16(const int32_t *acc, int64_t count, float scaleA, float 
     float dq = orc_dequant_factor(scaleA, scaleB, n_eff);
     for (int64_t p = 0; p < count; ++p)
         out[p] = orc_bf16_bits((float)acc[p] * dq);
+}
+
+/* Input gradient of a convolution layer (an engineering extension: the paper's layers
+ * stop at the gradient of the im2col matrix and leave the fold to the framework).
+ * The layer's input act[batch, C, H, W] enters the matmuls as X[M, K], M = batch*H*W,
+ * K = C*kh*kw, with X[(b,y,x), c*kh*kw + ty*kw + tx] = act[b, c, y + ty - ph, x + tx - pw]
+ * (zero outside the image; ph = (kh-1)/2, pw = (kw-1)/2; stride 1).  The gradient of act is
+ * the transpose of that map applied to dX = G W^T:
+ *     dAct[b,c,y,x] = sum over taps (ty,tx) of dX[(b, y - ty + ph, x - tx + pw), c*kh*kw + ty*kw + tx]
+ * over the taps whose source pixel lies in the image.  Here the sum is taken on the
+ * integer accumulators of step 5, which is exact, and step 6 is applied once to the sum:
+ *     accAct = sum of acc[...]  (int32),   dAct = fl(float(accAct) * dq)
+ * (dequantization is linear, so this is the fold of the dequantized dX up to rounding,
+ * and it does not depend on the order of the sum). */
+void orc_col2im_acc(const int32_t *acc, int64_t batch, int C, int H, int W, int kh, int kw,
+                    int32_t *acc_act)
+{
+    const int ph = (kh - 1) / 2, pw = (kw - 1) / 2;
+    const int64_t K = (int64_t)C * kh * kw;
+#pragma omp parallel for schedule(static)
+    for (int64_t b = 0; b < batch; ++b)
+        for (int c = 0; c < C; ++c)
+            for (int y = 0; y < H; ++y)
+                for (int x = 0; x < W; ++x) {
+                    int64_t sum = 0;
+                    for (int ty = 0; ty < kh; ++ty)
+                        for (int tx = 0; tx < kw; ++tx) {
+                            const int yp = y - ty + ph, xp = x - tx + pw;
+                            if (yp < 0 || yp >= H || xp < 0 || xp >= W)
+                                continue;
+                            const int64_t m = (b * H + yp) * W + xp;
+                            sum += acc[m * K + ((int64_t)c * kh + ty) * kw + tx];
+                        }
+                    acc_act[((b * C + c) * H + y) * W + x] = (int32_t)sum;
+                }
 }
 
 /* ------------------------------------------------------------------ */

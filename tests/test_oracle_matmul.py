@@ -330,3 +330,59 @@ def test_dequantize_bf16_is_narrowing_of_the_fp32_output():
     sA, sB, n = np.float32(0.0123), np.float32(3.1e-4), 64
     full = capi.dequantize(acc, sA, sB, n)
     assert np.array_equal(capi.dequantize_bf16(acc, sA, sB, n), capi.bf16_bits(full))
+
+
+# ---------------------------------------------------------------- fold of the input gradient
+
+def _brute_col2im(acc, batch, C, H, W, kh, kw):
+    """The transpose of im2col written as a scatter: every entry of dX goes to the input
+    element it was read from."""
+    out = np.zeros((batch, C, H, W), dtype=np.int64)
+    ph, pw = (kh - 1) // 2, (kw - 1) // 2
+    for b in range(batch):
+        for yp in range(H):
+            for xp in range(W):
+                m = (b * H + yp) * W + xp
+                for c in range(C):
+                    for ty in range(kh):
+                        for tx in range(kw):
+                            y, x = yp + ty - ph, xp + tx - pw
+                            if 0 <= y < H and 0 <= x < W:
+                                out[b, c, y, x] += acc[m, (c * kh + ty) * kw + tx]
+    return out
+
+
+@pytest.mark.parametrize("batch,C,H,W,kh,kw", [(2, 3, 4, 5, 3, 3), (1, 2, 1, 9, 1, 5), (3, 1, 6, 2, 5, 1),
+                                               (2, 2, 3, 3, 1, 1)])
+def test_col2im_acc_against_scatter_and_library_fold(batch, C, H, W, kh, kw):
+    import torch
+    rng = np.random.default_rng(batch * 100 + H * 10 + W)
+    acc = rng.integers(-500, 500, size=(batch * H * W, C * kh * kw)).astype(np.int32)
+    got = capi.col2im_acc(acc, batch, C, H, W, kh, kw)
+    assert np.array_equal(got, _brute_col2im(acc, batch, C, H, W, kh, kw))
+    # PyTorch's fold (the adjoint of unfold), exact in float64 on small integers
+    cols = torch.from_numpy(acc.astype(np.float64)).reshape(batch, H * W, C * kh * kw).transpose(1, 2)
+    ref = torch.nn.functional.fold(cols, output_size=(H, W), kernel_size=(kh, kw),
+                                   padding=((kh - 1) // 2, (kw - 1) // 2)).numpy()
+    assert np.array_equal(got.astype(np.float64), ref)
+
+
+def test_col2im_acc_is_the_adjoint_of_im2col():
+    """<unfold(a), d> = <a, col2im(d)> for integer tensors: the defining property."""
+    import torch
+    rng = np.random.default_rng(9)
+    batch, C, H, W, kh, kw = 2, 3, 5, 4, 3, 3
+    a = rng.integers(-9, 9, size=(batch, C, H, W)).astype(np.float64)
+    d = rng.integers(-9, 9, size=(batch * H * W, C * kh * kw)).astype(np.int32)
+    X = torch.nn.functional.unfold(torch.from_numpy(a), kernel_size=(kh, kw), padding=1)
+    X = X.transpose(1, 2).reshape(batch * H * W, C * kh * kw).numpy()
+    lhs = float((X * d).sum())
+    rhs = float((a * capi.col2im_acc(d, batch, C, H, W, kh, kw)).sum())
+    assert lhs == rhs
+
+
+def test_col2im_of_a_1x1_window_is_a_transpose():
+    rng = np.random.default_rng(10)
+    acc = rng.integers(-100, 100, size=(2 * 3 * 4, 5)).astype(np.int32)
+    got = capi.col2im_acc(acc, 2, 5, 3, 4, 1, 1)
+    assert np.array_equal(got, acc.reshape(2, 12, 5).transpose(0, 2, 1).reshape(2, 5, 3, 4))
