@@ -331,6 +331,35 @@ int hdqt_conv_fwd(const float *act, const hdqt_conv_t *geo, const float *W, floa
                   size_t saved_bytes, void *workspace, size_t workspace_bytes, void *stream);
 
 /*
+ * hdqt_layer_bwd for a convolution layer, with the input gradient folded back onto the
+ * activation inside the matmul: dAct[batch, channels, height, width] (fp32, device) instead
+ * of the [M, K] gradient of the im2col matrix, which is never written.
+ *   dAct[b,c,y,x] = float( sum over the window's taps (ty,tx) whose source pixel
+ *                   (y - ty + (kh-1)/2, x - tx + (kw-1)/2) lies in the image of
+ *                   acc[(b, that pixel), c*kh*kw + ty*kw + tx] ) * scaleG * scaleW / n_eff
+ * with acc the integer accumulators of dX = G W^T: the taps are added as integers (exact,
+ * order-free) and dequantized once.  dW as for hdqt_layer_bwd.  dAct, bwd_input and W are
+ * required.  Workspace: hdqt_layer_bwd_workspace_size(M, K, N, ...) with M = batch*height*width,
+ * K = channels*kh*kw.
+ * Taken: 4-bit codes, s and N multiples of 32, ceil(N/s) * 2^(acc_bits-1) <= 32767 (the
+ * folded tile is kept as 16-bit integers); kh, kw odd; width a power
+ * of two <= 128; height*width a power of two <= 128, or 128/width >= kh image rows per
+ * strip.  Anything else: HDQT_EINVAL_GEOMETRY (before anything is launched), and the caller
+ * takes hdqt_layer_bwd and folds its dX.
+ */
+int hdqt_conv_bwd(const float *G, const float *W, const void *saved, const hdqt_conv_t *geo,
+                  float *dAct, float *dW, int64_t N, const hdqt_params_t *bwd_input,
+                  const hdqt_params_t *bwd_weight, void *workspace, size_t workspace_bytes,
+                  void *stream);
+
+/* The folded input gradient alone, on packed codes: qG [M, N] codes of G along N, qW [K, N]
+ * codes of W along N (as hdqt_quantize writes them), their scales (device), the contraction
+ * length N and its block order n_eff; dAct as for hdqt_conv_bwd.  No workspace. */
+int hdqt_gemm_codes_fold(const void *qG, const void *qW, int bG, int bW, const float *scaleG,
+                         const float *scaleW, const hdqt_conv_t *geo, int64_t N, int n_eff,
+                         int acc_bits, int64_t s, float *dAct, void *stream);
+
+/*
  * The same step as two calls, for training loops in which the gradient G arrives
  * long after the forward product (Methodology: the forward and the backward
  * matmuls of a layer):

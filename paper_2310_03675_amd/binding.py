@@ -29,7 +29,7 @@ EXPORTED = [
     "hdqt_gemm_codes_requant_workspace_size", "hdqt_gemm_codes_requant",
     "hdqt_gemm_requant_workspace_size", "hdqt_gemm_requant", "hdqt_gemm_codes_bf16",
     "hdqt_gemm_bwd_input_bf16", "hdqt_quantize_dual_im2col", "hdqt_conv_step_workspace_size",
-    "hdqt_conv_step", "hdqt_conv_fwd",
+    "hdqt_conv_step", "hdqt_conv_fwd", "hdqt_conv_bwd", "hdqt_gemm_codes_fold",
 ]
 
 
@@ -156,6 +156,10 @@ def load() -> C.CDLL:
     lib.hdqt_conv_step.argtypes = [vp, C.POINTER(CConv), vp, vp, vp, vp, vp, i64] + [C.POINTER(CParams)] * 3 + [vp, sz, vp]
     lib.hdqt_conv_fwd.restype = i32
     lib.hdqt_conv_fwd.argtypes = [vp, C.POINTER(CConv), vp, vp, i64] + [C.POINTER(CParams)] * 2 + [vp, sz, vp, sz, vp]
+    lib.hdqt_conv_bwd.restype = i32
+    lib.hdqt_conv_bwd.argtypes = [vp, vp, vp, C.POINTER(CConv), vp, vp, i64] + [C.POINTER(CParams)] * 2 + [vp, sz, vp]
+    lib.hdqt_gemm_codes_fold.restype = i32
+    lib.hdqt_gemm_codes_fold.argtypes = [vp, vp, i32, i32, vp, vp, C.POINTER(CConv), i64, i32, i32, i64, vp, vp]
     lib.hdqt_gemm_codes_bf16.restype = i32
     lib.hdqt_gemm_codes_bf16.argtypes = lib.hdqt_gemm_codes.argtypes
     for name in ("hdqt_gemm_fwd", "hdqt_gemm_bwd_input", "hdqt_gemm_bwd_weight", "hdqt_gemm_bwd_input_bf16"):
@@ -485,6 +489,44 @@ def conv_fwd(act: torch.Tensor, kh: int, kw: int, W: torch.Tensor, fwd: Params, 
     if rc:
         raise HdqtError(rc, "hdqt_conv_fwd")
     return out, saved
+
+
+def conv_bwd(G: torch.Tensor, W: torch.Tensor, saved: torch.Tensor, act_shape, kh: int, kw: int,
+             bwd_input: Params, bwd_weight: Params, stream: Optional[torch.cuda.Stream] = None):
+    """hdqt_conv_bwd -> (dAct [batch, C, H, W], dW [K, N]): hdqt_layer_bwd with the input gradient
+    folded back onto the activation inside the matmul.  HdqtError -13 for geometries not taken."""
+    _check_dev(G, W, saved)
+    batch, Cin, H, Wd = act_shape
+    geo = CConv(batch, Cin, H, Wd, kh, kw)
+    M, K, N = batch * H * Wd, Cin * kh * kw, G.shape[1]
+    assert tuple(G.shape) == (M, N) and tuple(W.shape) == (K, N)
+    pi, pw = bwd_input.c(), bwd_weight.c()
+    dAct = torch.empty((batch, Cin, H, Wd), dtype=torch.float32, device=G.device)
+    dW = torch.empty((K, N), dtype=torch.float32, device=G.device)
+    need = load().hdqt_layer_bwd_workspace_size(M, K, N, C.byref(pi), C.byref(pw))
+    workspace = torch.empty(max(need, 256), dtype=torch.uint8, device=G.device)
+    rc = load().hdqt_conv_bwd(_ptr(G), _ptr(W), _ptr(saved), C.byref(geo), _ptr(dAct), _ptr(dW), N,
+                              C.byref(pi), C.byref(pw), _ptr(workspace), workspace.numel(), _stream(stream))
+    if rc:
+        raise HdqtError(rc, "hdqt_conv_bwd")
+    return dAct, dW
+
+
+def gemm_codes_fold(qG: torch.Tensor, qW: torch.Tensor, bG: int, bW: int, scaleG: torch.Tensor,
+                    scaleW: torch.Tensor, act_shape, kh: int, kw: int, n: int, acc_bits: int, s: int,
+                    out: Optional[torch.Tensor] = None, stream: Optional[torch.cuda.Stream] = None):
+    """hdqt_gemm_codes_fold -> dAct [batch, C, H, W]."""
+    _check_dev(qG, qW, scaleG, scaleW)
+    batch, Cin, H, Wd = act_shape
+    geo = CConv(batch, Cin, H, Wd, kh, kw)
+    N = qG.shape[1] * (2 if bG <= 4 else 1)
+    if out is None:
+        out = torch.empty((batch, Cin, H, Wd), dtype=torch.float32, device=qG.device)
+    rc = load().hdqt_gemm_codes_fold(_ptr(qG), _ptr(qW), bG, bW, _ptr(scaleG), _ptr(scaleW), C.byref(geo), N,
+                                     n, acc_bits, s, _ptr(out), _stream(stream))
+    if rc:
+        raise HdqtError(rc, "hdqt_gemm_codes_fold")
+    return out
 
 
 def layer_bwd(G: torch.Tensor, W: torch.Tensor, saved: torch.Tensor, K: int,

@@ -997,10 +997,15 @@ size_t hdqt_layer_bwd_workspace_size(int64_t M, int64_t K, int64_t N, const hdqt
     return plan_bwd(M, K, N, bwd_input, bwd_weight, &L) == HDQT_OK ? L.total : 0;
 }
 
-int hdqt_layer_bwd(const float* G, const float* W, const void* saved, float* dX, float* dW, int64_t M,
-                   int64_t K, int64_t N, const hdqt_params_t* bwd_input,
-                   const hdqt_params_t* bwd_weight, void* workspace, size_t workspace_bytes,
-                   void* stream_v)
+} // extern "C"
+
+namespace {
+
+// dX is the gradient of the [M, K] matrix, or, with `geo`, of the activation it was unfolded from.
+int run_layer_bwd(const float* G, const float* W, const void* saved, const hdqt_conv_t* geo, float* dX,
+                  float* dW, int64_t M, int64_t K, int64_t N, const hdqt_params_t* bwd_input,
+                  const hdqt_params_t* bwd_weight, void* workspace, size_t workspace_bytes,
+                  void* stream_v)
 {
     if (!G || !saved || !dW || !bwd_weight) return HDQT_EINVAL_NULL;
     const bool with_dx = dX != nullptr;
@@ -1016,6 +1021,18 @@ int hdqt_layer_bwd(const float* G, const float* W, const void* saved, float* dX,
     char* base = static_cast<char*>(workspace);
     const char* sv = static_cast<const char*>(saved);
     auto meta = [&](size_t off) { return reinterpret_cast<hdqt::QMeta*>(base + off); };
+    hdqt::GemmArgs g_dx{};
+    if (with_dx) {
+        g_dx = plan_gemm(base + L.codesG1, base + L.codesW1, bwd_input->A.b, bwd_input->B.b,
+                         &meta(L.metaG1)->scale, &meta(L.metaW1)->scale, M, K, N, L.n_bwi,
+                         bwd_input->acc_bits, bwd_input->s, dX, nullptr, 1 + HDQT_GEMM_BWD_INPUT);
+        // (nothing is launched before the geometry is known to be taken)
+        if (geo && !hdqt::gemm_fold_plan(&g_dx, geo->batch, geo->channels, geo->height, geo->width, geo->kh,
+                                         geo->kw))
+            return HDQT_EINVAL_GEOMETRY;
+    } else if (geo) {
+        return HDQT_EINVAL_NULL;
+    }
     hipError_t e = hdqt::launch_zero2(reinterpret_cast<uint32_t*>(base), (int64_t)(3 * kMetaBytes / 4),
                                       nullptr, 0, stream);
     if (e != hipSuccess) return hip_fail(e);
@@ -1036,12 +1053,53 @@ int hdqt_layer_bwd(const float* G, const float* W, const void* saved, float* dX,
     rc = run_quantize(W, K, N, 1, L.n_bwi, &bwd_input->B, bwd_input->seed, meta(L.metaW1),
                       base + L.codesW1, nullptr, stream);
     if (rc) return rc;
-    return run_planned_gemm(plan_gemm(base + L.codesG1, base + L.codesW1, bwd_input->A.b, bwd_input->B.b,
-                                      &meta(L.metaG1)->scale, &meta(L.metaW1)->scale, M, K, N, L.n_bwi,
-                                      bwd_input->acc_bits, bwd_input->s, dX, nullptr,
-                                      1 + HDQT_GEMM_BWD_INPUT),
-                            base + L.acc[0], L.acc_bytes[0], stream);
+    return run_planned_gemm(g_dx, base + L.acc[0], L.acc_bytes[0], stream);
 }
+
+} // namespace
+
+extern "C" {
+
+int hdqt_layer_bwd(const float* G, const float* W, const void* saved, float* dX, float* dW, int64_t M,
+                   int64_t K, int64_t N, const hdqt_params_t* bwd_input,
+                   const hdqt_params_t* bwd_weight, void* workspace, size_t workspace_bytes,
+                   void* stream)
+{
+    return run_layer_bwd(G, W, saved, nullptr, dX, dW, M, K, N, bwd_input, bwd_weight, workspace,
+                         workspace_bytes, stream);
+}
+
+int hdqt_conv_bwd(const float* G, const float* W, const void* saved, const hdqt_conv_t* geo, float* dAct,
+                  float* dW, int64_t N, const hdqt_params_t* bwd_input, const hdqt_params_t* bwd_weight,
+                  void* workspace, size_t workspace_bytes, void* stream)
+{
+    if (!geo || !dAct) return HDQT_EINVAL_NULL;
+    int64_t M, K;
+    if (!conv_matrix_shape(geo, &M, &K)) return HDQT_EINVAL_DIM;
+    return run_layer_bwd(G, W, saved, geo, dAct, dW, M, K, N, bwd_input, bwd_weight, workspace,
+                         workspace_bytes, stream);
+}
+
+int hdqt_gemm_codes_fold(const void* qG, const void* qW, int bG, int bW, const float* scaleG,
+                         const float* scaleW, const hdqt_conv_t* geo, int64_t N, int n_eff, int acc_bits,
+                         int64_t s, float* dAct, void* stream)
+{
+    if (!qG || !qW || !scaleG || !scaleW || !geo || !dAct) return HDQT_EINVAL_NULL;
+    int64_t M, K;
+    if (!conv_matrix_shape(geo, &M, &K) || N <= 0 || N >= kMaxDim) return HDQT_EINVAL_DIM;
+    int rc;
+    if ((rc = check_dims2(M, N)) || (rc = check_dims2(K, N)) || (rc = check_dims2(M, K))) return rc;
+    if (bG < 2 || bG > 8 || bW < 2 || bW > 8) return HDQT_EINVAL_BITS;
+    if (!is_pow2(n_eff) || n_eff > hdqt::kMaxHadamard || N % n_eff != 0) return HDQT_EINVAL_HADAMARD;
+    if ((rc = check_accumulation(N, s, acc_bits, bG, bW))) return rc;
+    if (misaligned(qG) || misaligned(qW) || misaligned(dAct)) return HDQT_EALIGN;
+    hdqt::GemmArgs g = plan_gemm(qG, qW, bG, bW, scaleG, scaleW, M, K, N, n_eff, acc_bits, s, dAct, nullptr,
+                                 1 + HDQT_GEMM_BWD_INPUT);
+    if (!hdqt::gemm_fold_plan(&g, geo->batch, geo->channels, geo->height, geo->width, geo->kh, geo->kw))
+        return HDQT_EINVAL_GEOMETRY;
+    return run_planned_gemm(g, nullptr, 0, static_cast<hipStream_t>(stream));
+}
+
 
 int hdqt_gemm_fwd(const float* X, const float* W, float* Z, int64_t M, int64_t K, int64_t N,
                   const hdqt_params_t* params, int32_t* acc_out, void* workspace,

@@ -94,7 +94,22 @@ struct GemmArgs {
     int profile_tag;        // which matmul of the step this is (timing table only): 0 none, 1 + kind
     int splits;             // workgroups sharing one output tile along the contraction
     int64_t tiles_per_split;
+    // Fold (fold != 0): the product is the gradient of an im2col matrix, qA holds the codes of
+    // G [batch*H*W pixels, D], qB those of W [C*kh*kw, D], and what is written is the gradient
+    // of the activation, out[batch, C, H, W]: the accumulators of a pixel's kh*kw taps are
+    // added up inside the workgroup (exact integers) and dequantized once.
+    int fold;
+    int fC, fH, fW, fkh, fkw;
+    int64_t fbatch;
+    int f_log2w, f_log2hw;  // W and (image mode) H*W are powers of two
+    int f_imgs;             // images per 128-pixel row tile (H*W <= 128), else 0: strips of one image
+    int f_rows_c;           // strip mode: image rows a row tile computes (128 / W), kh - 1 of them halo
+    int f_rows_out;         // strip mode: image rows a row tile writes
+    int f_strips;           // strip mode: row tiles per image
+    int f_cg;               // channels per column tile: 128 / (kh*kw)
 };
+// fills the fold fields from the geometry; false if the fast kernel does not take it
+bool gemm_fold_plan(GemmArgs* g, int64_t batch, int C, int H, int W, int kh, int kw);
 
 // Launchers (host).  Each returns the hipError_t of its last launch.
 hipError_t launch_quantize(const QuantArgs& q, hipStream_t stream);

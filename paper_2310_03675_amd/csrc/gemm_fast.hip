@@ -60,7 +60,7 @@ struct Staged {
 __device__ __forceinline__ uint4 load_unit(const uint8_t* q, int64_t pitch, int64_t R, int64_t row,
                                            int64_t k, int64_t k_end)
 {
-    if (row < R && k < k_end) return *reinterpret_cast<const uint4*>(q + row * pitch + (k >> 1));
+    if (row >= 0 && row < R && k < k_end) return *reinterpret_cast<const uint4*>(q + row * pitch + (k >> 1));
     return make_uint4(0u, 0u, 0u, 0u);
 }
 
@@ -80,11 +80,14 @@ __device__ __forceinline__ int add_sat8_pair(int total, int p0, int p1)
     return __builtin_amdgcn_sdot4(__builtin_bit_cast(int, pk), 0x01000100, total, false);
 }
 
+// clamp(v, lo, hi), lo <= hi.  Plain C++ on purpose: written as inline assembly (one
+// v_med3_i32) the compiler does not see that the instruction reads an MFMA result and leaves
+// out the wait states the hardware needs between the two (found as a lost tile sum in the
+// first element of a block).
 __device__ __forceinline__ int clamp3(int v, int lo, int hi)
 {
-    int r;
-    asm("v_med3_i32 %0, %1, %2, %3" : "=v"(r) : "v"(v), "v"(lo), "v"(hi));
-    return r;
+    const int t = v < lo ? lo : v;
+    return t > hi ? hi : t;
 }
 
 // Work of a workgroup: the output tiles (blockIdx.y, ct), ct = blockIdx.z,
@@ -99,7 +102,7 @@ __device__ __forceinline__ int clamp3(int v, int lo, int hi)
 // flight.  With gridDim.z = 1 a workgroup walks along a
 // whole row strip of the output, which is how short contractions (one or two
 // stages per tile) keep loads, MFMAs and stores overlapped.
-template <int EPI, int KS, bool STREAM, int WAVES, bool BF16>
+template <int EPI, int KS, bool STREAM, int WAVES, bool BF16, bool FOLD>
 __global__ __launch_bounds__(64 * WAVES, WAVES == 8 ? 4 : 2) void gemm_i4_kernel(GemmArgs g)
 {
     // WAVES = 4: each wave a 64 x 64 quarter (2 x 2 MFMA blocks).  WAVES = 8: each wave
@@ -120,7 +123,20 @@ __global__ __launch_bounds__(64 * WAVES, WAVES == 8 ? 4 : 2) void gemm_i4_kernel
     const int lane = tid & 63, wave = tid >> 6;
     const int wm = wave / WN, wn = wave % WN;
     const int64_t row0 = (int64_t)blockIdx.y * BM;
-    const int n_ct = (int)((g.RB + BN - 1) / BN);
+    // fold: a column tile is f_cg whole channels (f_cg * kh * kw <= 128 columns)
+    const int col_stride = FOLD ? g.f_cg * g.fkh * g.fkw : BN;
+    const int n_ct = FOLD ? (g.fC + g.f_cg - 1) / g.f_cg : (int)((g.RB + BN - 1) / BN);
+    // fold, strip mode: row tile = f_rows_c image rows of one image starting (kh-1)/2 rows above
+    // the rows it writes; rows outside the image are zero
+    const int f_ph = FOLD ? (g.fkh - 1) / 2 : 0, f_pw = FOLD ? (g.fkw - 1) / 2 : 0;
+    const int f_img = (FOLD && !g.f_imgs) ? (int)blockIdx.y / g.f_strips : 0;
+    const int f_y0 = (FOLD && !g.f_imgs) ? ((int)blockIdx.y % g.f_strips) * g.f_rows_out - f_ph : 0;
+    auto a_row = [&](int r) -> int64_t {          // source row of qA for row r of the tile, -1: zero
+        if (!FOLD || g.f_imgs) return row0 + r;
+        const int yy = f_y0 + (r >> g.f_log2w);
+        if (yy < 0 || yy >= g.fH) return -1;
+        return ((int64_t)f_img * g.fH + yy) * g.fW + (r & (g.fW - 1));
+    };
 
     const int64_t t_begin = (int64_t)blockIdx.x * g.tiles_per_split;
     int64_t t_end = t_begin + g.tiles_per_split;
@@ -152,11 +168,11 @@ __global__ __launch_bounds__(64 * WAVES, WAVES == 8 ? 4 : 2) void gemm_i4_kernel
     int64_t f_k = k_begin;
     auto fetch_next = [&](Staged<UNITS>& st) {
         if (f_ct >= n_ct) return;
-        const int64_t col0 = (int64_t)f_ct * BN;
+        const int64_t col0 = (int64_t)f_ct * col_stride;
 #pragma unroll
         for (int i = 0; i < UNITS; ++i) {
             const int r = lrow + ROWS_PER_PASS * i;
-            st.a[i] = load_unit(g.qA, g.pitchA, g.RA, row0 + r, f_k + lks * KSTEP, k_end);
+            st.a[i] = load_unit(g.qA, g.pitchA, g.RA, a_row(r), f_k + lks * KSTEP, k_end);
             st.b[i] = load_unit(g.qB, g.pitchB, g.RB, col0 + r, f_k + lks * KSTEP, k_end);
         }
         f_k += KS;
@@ -303,6 +319,68 @@ __global__ __launch_bounds__(64 * WAVES, WAVES == 8 ? 4 : 2) void gemm_i4_kernel
                         part[a][c][r] = 0;
                     }
         }
+        if constexpr (FOLD) {
+            // ---- fold: the tile's accumulators go to LDS (int16: at most 255 tiles of +-128),
+            // then every thread adds up the kh*kw taps of its pixels and channels.  Both operand
+            // buffers are free here: the stages still to come are in registers.
+            constexpr int AP = 130;      // pitch in int16 (65 dwords: neighbouring pixels, neighbouring banks)
+            static_assert(sizeof(As) >= (size_t)BM * AP * sizeof(int16_t), "accumulator tile must fit the A buffers");
+            int16_t* accT = reinterpret_cast<int16_t*>(&As[0][0][0]);
+            __syncthreads();             // every wave is done reading this stage's operands
+#pragma unroll
+            for (int a = 0; a < 2; ++a)
+#pragma unroll
+                for (int c = 0; c < CS; ++c)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) {
+                        const int rr = a * 32 + 8 * (r >> 2) + (r & 3);
+                        const int v = (EPI == EPI_GENERIC || EPI == EPI_STAGES) ? (total[a][c][r] >> kScaleShift)
+                                                                                 : total[a][c][r];
+                        total[a][c][r] = 0;
+                        accT[(lane_row + rr) * AP + lane_col + c * 32] = (int16_t)v;
+                    }
+            __syncthreads();
+            const int W = g.fW, H = g.fH, kw = g.fkw, khw = g.fkh * g.fkw;
+            const int q = tid & (BM - 1);                 // pixel of the tile
+            int il = 0, ry, rows_part, y;
+            int64_t b;
+            bool out_ok;
+            const int x = q & (W - 1);
+            if (g.f_imgs) {                               // whole images: q = (image, row, position)
+                il = q >> g.f_log2hw;
+                ry = (q & ((1 << g.f_log2hw) - 1)) >> g.f_log2w;
+                rows_part = H;
+                b = (int64_t)blockIdx.y * g.f_imgs + il;
+                y = ry;
+                out_ok = b < g.fbatch;
+            } else {                                      // a strip of one image, halo rows first and last
+                ry = q >> g.f_log2w;
+                rows_part = g.f_rows_c;
+                b = f_img;
+                y = f_y0 + ry;
+                out_ok = ry >= f_ph && ry < f_ph + g.f_rows_out && y < H;
+            }
+            const int cbase = c_ct * g.f_cg;
+            const int16_t* img_part = accT + (il << g.f_log2hw) * AP;      // (il = 0 in strip mode)
+            for (int c = tid / BM; c < g.f_cg; c += NTHREADS / BM) {
+                if (!out_ok || cbase + c >= g.fC) continue;
+                int sum = 0;
+                for (int ty = 0; ty < g.fkh; ++ty) {
+                    const int ryp = ry - ty + f_ph;
+                    if (ryp < 0 || ryp >= rows_part) continue;
+                    for (int tx = 0; tx < kw; ++tx) {
+                        const int xp = x - tx + f_pw;
+                        if (xp < 0 || xp >= W) continue;
+                        sum += img_part[((ryp << g.f_log2w) + xp) * AP + c * khw + ty * kw + tx];
+                    }
+                }
+                g.out[(((int64_t)b * g.fC + cbase + c) * H + y) * W + x] = (float)sum * dq;
+            }
+            __syncthreads();             // the next stage overwrites the buffers the sums were read from
+            c_k = k_begin;
+            c_ct += gridDim.z;
+            return;
+        }
         // Element (a, c, r) of the lane lies at tile_off + (32a + 8(r/4) + r%4) RB + 32c
         // (uniform) + lane_off (per lane, 32 bits: RB <= 2^21 on this path).
         const int64_t col0 = (int64_t)c_ct * BN;
@@ -396,7 +474,7 @@ __global__ __launch_bounds__(64 * WAVES, WAVES == 8 ? 4 : 2) void gemm_i4_kernel
     // it (one stage of 128 codes is 8 MFMAs per wave, about 0.5 us of matrix time per SIMD,
     // less than a trip to L2 under load), one stage ahead in the s = 64 instance, which has
     // no eight registers to spare at four waves per SIMD.
-    constexpr bool kDeep = (EPI != EPI_SAT8_S64);
+    constexpr bool kDeep = (EPI != EPI_SAT8_S64) && !FOLD;      // (the fold epilogue needs the registers)
     if constexpr (kDeep) {
         Staged<UNITS> st0, st1;
         fetch_next(st0);
@@ -421,6 +499,45 @@ bool sat8_path(const GemmArgs& g) { return g.acc_hi == 127 && (g.s == 32 || g.s 
 
 } // namespace
 
+// Geometries the fold epilogue takes: W a power of two up to 128; either whole images per
+// 128-pixel row tile (H*W a power of two up to 128) or strips of 128 / W image rows of which
+// kh - 1 are halo (recomputed by the neighbouring strips); odd windows of at most 128 taps.
+bool gemm_fold_plan(GemmArgs* g, int64_t batch, int C, int H, int W, int kh, int kw)
+{
+    auto pow2 = [](int v) { return v > 0 && (v & (v - 1)) == 0; };
+    auto log2i = [](int v) { int l = 0; while ((1 << l) < v) ++l; return l; };
+    if (batch < 1 || C < 1 || H < 1 || W < 1 || kh < 1 || kw < 1 || kh % 2 == 0 || kw % 2 == 0) return false;
+    if (!pow2(W) || W > BM || kh * kw > BN || kh > 15 || kw > 15) return false;
+    if (g->RA != batch * (int64_t)H * W || g->RB != (int64_t)C * kh * kw) return false;
+    g->splits = 1;                        // short contractions; the fold needs whole totals
+    g->tiles_per_split = g->n_tiles;
+    if (batch * (int64_t)C * H * W >= ((int64_t)1 << 40) || false) return false;
+    g->fold = 1;
+    g->fbatch = batch; g->fC = C; g->fH = H; g->fW = W; g->fkh = kh; g->fkw = kw;
+    g->f_log2w = log2i(W);
+    g->f_cg = BN / (kh * kw);
+    const int64_t hw = (int64_t)H * W;
+    if (hw <= BM) {
+        if (!pow2((int)hw)) return false;
+        g->f_imgs = BM / (int)hw;
+        g->f_log2hw = log2i((int)hw);
+        g->f_rows_c = H; g->f_rows_out = H; g->f_strips = 1;
+    } else {
+        g->f_imgs = 0;
+        g->f_log2hw = 7;                  // unused: one image part per tile
+        g->f_rows_c = BM / W;
+        g->f_rows_out = g->f_rows_c - (kh - 1);
+        if (g->f_rows_out < 1) return false;
+        g->f_strips = (H + g->f_rows_out - 1) / g->f_rows_out;
+        if (batch * g->f_strips > 65535) return false;      // grid.y
+    }
+    if (g->f_imgs && (batch + g->f_imgs - 1) / g->f_imgs > 65535) return false;
+    // int16 accumulator tile: |total| <= tiles * 2^(a-1)
+    const int64_t per_tile = (int64_t)g->acc_hi + 1;
+    if (per_tile > 32767 || per_tile * g->n_tiles > 32767) return false;
+    return gemm_fast_eligible(*g);
+}
+
 bool gemm_fast_eligible(const GemmArgs& g)
 {
     if (g.bA > 4 || g.bB > 4) return false;
@@ -443,7 +560,11 @@ hipError_t launch_gemm_fast(const GemmArgs& g_in, hipStream_t stream)
     g.acc_hi_scaled = hi > INT32_MAX ? INT32_MAX : (int)hi;
     // Short contractions (at most two stages per output tile): a workgroup walks along
     // its row strip of the output as long as that leaves about two workgroups per CU.
-    const int64_t n_ct = (g.RB + BN - 1) / BN, n_rt = (g.RA + BM - 1) / BM;
+    int64_t n_ct = (g.RB + BN - 1) / BN, n_rt = (g.RA + BM - 1) / BM;
+    if (g.fold) {
+        n_ct = (g.fC + g.f_cg - 1) / g.f_cg;
+        n_rt = g.f_imgs ? (g.fbatch + g.f_imgs - 1) / g.f_imgs : g.fbatch * g.f_strips;
+    }
     const bool s32 = sat8_path(g) && g.s == 32;
     const int64_t KS = KS_LONG;
     const int64_t stages = (g.tiles_per_split * g.s + KS - 1) / KS;
@@ -458,13 +579,15 @@ hipError_t launch_gemm_fast(const GemmArgs& g_in, hipStream_t stream)
 #define HDQT_LAUNCH_I4(EPI)                                                                          \
     do {                                                                                             \
         const dim3 block(64 * kWaves);                                                               \
-        if (g.out_bf16) {                                                                            \
-            if (g.stream_out) hipLaunchKernelGGL((gemm_i4_kernel<EPI, KS_LONG, true, kWaves, true>), grid, block, 0, stream, g); \
-            else hipLaunchKernelGGL((gemm_i4_kernel<EPI, KS_LONG, false, kWaves, true>), grid, block, 0, stream, g); \
+        if (g.fold)                                                                                  \
+            hipLaunchKernelGGL((gemm_i4_kernel<EPI, KS_LONG, false, kWaves, false, true>), grid, block, 0, stream, g); \
+        else if (g.out_bf16) {                                                                       \
+            if (g.stream_out) hipLaunchKernelGGL((gemm_i4_kernel<EPI, KS_LONG, true, kWaves, true, false>), grid, block, 0, stream, g); \
+            else hipLaunchKernelGGL((gemm_i4_kernel<EPI, KS_LONG, false, kWaves, true, false>), grid, block, 0, stream, g); \
         } else if (g.stream_out)                                                                     \
-            hipLaunchKernelGGL((gemm_i4_kernel<EPI, KS_LONG, true, kWaves, false>), grid, block, 0, stream, g); \
+            hipLaunchKernelGGL((gemm_i4_kernel<EPI, KS_LONG, true, kWaves, false, false>), grid, block, 0, stream, g); \
         else                                                                                         \
-            hipLaunchKernelGGL((gemm_i4_kernel<EPI, KS_LONG, false, kWaves, false>), grid, block, 0, stream, g); \
+            hipLaunchKernelGGL((gemm_i4_kernel<EPI, KS_LONG, false, kWaves, false, false>), grid, block, 0, stream, g); \
     } while (0)
     if (s32) HDQT_LAUNCH_I4(EPI_SAT8_S32);
     else if (sat8_path(g)) HDQT_LAUNCH_I4(EPI_SAT8_S64);
