@@ -372,6 +372,33 @@ def main():
                                            "frac": nbytes / us / 1e3 / HBM_PEAK_GBPS,
                                            "algorithmic_bytes_per_launch": nbytes}
             del o_dx
+        if layer.act is not None:
+            # and with the gradient folded back onto the convolution's input inside the matmul
+            # (hdqt_gemm_codes_fold): what is written is the activation's gradient, kh*kw times
+            # smaller than the gradient of the im2col matrix
+            kh_, kw_ = layer.window
+            shape_ = tuple(layer.act.shape)
+            try:
+                o_act = torch.empty(shape_, dtype=torch.float32, device=dev)
+                for _ in range(3):
+                    B.gemm_codes_fold(qg, qw, 4, 4, sg, sw, shape_, kh_, kw_, n, args.acc_bits, args.s, out=o_act)
+                torch.cuda.synchronize()
+                B.profile_enable(True)
+                B.profile_collect()
+                for _ in range(10):
+                    B.gemm_codes_fold(qg, qw, 4, 4, sg, sw, shape_, kh_, kw_, n, args.acc_bits, args.s, out=o_act)
+                torch.cuda.synchronize()
+                B.profile_enable(False)
+                kg = B.profile_collect()
+                us = sum(v[1] for k_, v in kg.items() if k_.startswith("gemm")) * 1e3 / 10
+                nbytes = 0.5 * (M * N + K * N) + 4.0 * o_act.numel()
+                line["bwd_input_bf16"]["folded_fp32"] = {
+                    "us": us, "bound": "hbm", "achieved": nbytes / us / 1e3, "peak": HBM_PEAK_GBPS,
+                    "unit": "GB/s", "frac": nbytes / us / 1e3 / HBM_PEAK_GBPS,
+                    "algorithmic_bytes_per_launch": nbytes}
+                del o_act
+            except B.HdqtError as exc:
+                line["bwd_input_bf16"]["folded_fp32"] = {"skipped": str(exc)}
         del qg, qw
     if layer.act is not None and not args.no_conv and not args.separate:
         # The same step with X given as the convolution's input (hdqt_conv_step): the quantizer
@@ -408,6 +435,31 @@ def main():
                 "outputs_equal_layer_step": same,
                 "activation_bytes": 4.0 * act_d.numel(), "im2col_matrix_bytes": 4.0 * M * K,
                 "kernels_us": {n_: tot / l * 1e3 for n_, (l, tot) in kc.items()}}
+            # the whole layer from its input to its input's gradient: hdqt_conv_fwd + hdqt_conv_bwd
+            # (the gradient folded back inside the matmul), against what the matrix path needs
+            # around it: PyTorch's unfold before and fold after
+            try:
+                pf_, pi_, pw_ = prm[kinds[0]], prm[kinds[1]], prm[kinds[2]]
+                def whole():
+                    _, sv = B.conv_fwd(act_d, kh_, kw_, W, pf_, pw_)
+                    B.conv_bwd(G, W, sv, tuple(act_d.shape), kh_, kw_, pi_, pw_)
+                def glue():
+                    xs = torch.nn.functional.unfold(act_d, (kh_, kw_), padding=((kh_ - 1) // 2, (kw_ - 1) // 2))
+                    xs = xs.transpose(1, 2).reshape(M, K).contiguous()
+                    torch.nn.functional.fold(step_out[1].reshape(act_d.shape[0], -1, K).transpose(1, 2),
+                                             output_size=tuple(act_d.shape[2:]), kernel_size=(kh_, kw_),
+                                             padding=((kh_ - 1) // 2, (kw_ - 1) // 2))
+                for name_, fn_ in (("conv_fwd_plus_conv_bwd_ms", whole), ("pytorch_unfold_plus_fold_ms", glue)):
+                    for _ in range(3):
+                        fn_()
+                    torch.cuda.synchronize()
+                    t1 = time.perf_counter()
+                    for _ in range(10):
+                        fn_()
+                    torch.cuda.synchronize()
+                    line["conv_step"][name_] = (time.perf_counter() - t1) / 10 * 1e3
+            except B.HdqtError as exc:
+                line["conv_step"]["conv_bwd"] = f"skipped: {exc}"
             del ws_c, ref
         except B.HdqtError as exc:          # geometry the activation-source kernels do not take
             line["conv_step"] = {"skipped": str(exc)}

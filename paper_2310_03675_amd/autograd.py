@@ -29,6 +29,7 @@ class LayerConfig:
     clip_fwd: float = 1.0
     stochastic_grad: bool = True
     need_input_grad: bool = True
+    fold_in_matmul: bool = True      # convolution layers: hdqt_conv_bwd where the geometry is taken
     # when set to a dict, every matmul of the layer leaves its operands and results there
     # (X, W, Z in the forward pass; G, dX, dW in the backward pass) for inspection
     capture: Optional[dict] = field(default=None, repr=False, compare=False)
@@ -79,6 +80,9 @@ class HdqtMatmul(torch.autograd.Function):
         return dX, dW, None, None
 
 
+_FOLD_REFUSED = set()        # activation shapes hdqt_conv_bwd did not take (with the window used)
+
+
 class HdqtConvMatmul(torch.autograd.Function):
     """Z = im2col(act) W for a stride-1, same-size convolution, without forming im2col(act):
     the forward call reads the activation (hdqt_conv_fwd).  The backward pass returns the
@@ -107,14 +111,25 @@ class HdqtConvMatmul(torch.autograd.Function):
         pi = cfg.params(B.GEMM_BWD_INPUT, ctx.step) if ctx.want_dx else None
         pw = cfg.params(B.GEMM_BWD_WEIGHT, ctx.step)
         G = G.contiguous()
-        dXcol, dW = B.layer_bwd(G, W, saved, Cin * kh * kw, pi, pw)
+        dAct = dXcol = None
+        key = (ctx.shape, kh, kw)
+        if pi is not None and cfg.fold_in_matmul and key not in _FOLD_REFUSED:
+            # the input gradient folded onto the activation inside the matmul: the gradient of
+            # the im2col matrix is never written
+            try:
+                dAct, dW = B.conv_bwd(G, W, saved, ctx.shape, kh, kw, pi, pw)
+            except B.HdqtError as exc:
+                if exc.code != -13:
+                    raise
+                _FOLD_REFUSED.add(key)
+        if dAct is None:
+            dXcol, dW = B.layer_bwd(G, W, saved, Cin * kh * kw, pi, pw)
+            if dXcol is not None:
+                cols = dXcol.reshape(Bn, H * Wd, Cin * kh * kw).transpose(1, 2)
+                dAct = torch.nn.functional.fold(cols, output_size=(H, Wd), kernel_size=(kh, kw),
+                                                padding=((kh - 1) // 2, (kw - 1) // 2))
         if cfg.capture is not None:
-            cfg.capture.update(G=G.detach(), dX=dXcol, dW=dW)
-        dAct = None
-        if dXcol is not None:
-            cols = dXcol.reshape(Bn, H * Wd, Cin * kh * kw).transpose(1, 2)
-            dAct = torch.nn.functional.fold(cols, output_size=(H, Wd), kernel_size=(kh, kw),
-                                            padding=((kh - 1) // 2, (kw - 1) // 2))
+            cfg.capture.update(G=G.detach(), dX=dXcol, dAct=dAct, dW=dW)
         return dAct, dW, None, None, None, None
 
 

@@ -352,3 +352,33 @@ def test_conv_source_argument_errors():
     assert step(*args(good, dx=None)) == E["HDQT_EINVAL_NULL"]
     assert step(*args(B.CConv(2, 64, 12, 12, 3, 3))) == E["HDQT_EINVAL_GEOMETRY"]
     assert step(*args(B.CConv(2, 64, 16, 16, 3, 3))[:-3], FAKE, 16, None) == E["HDQT_EWORKSPACE"]
+
+
+def test_folded_input_gradient_argument_errors():
+    lib = B.load()
+    good = B.CConv(2, 64, 16, 16, 3, 3)
+
+    def rc(qG=FAKE, geo=good, N=128, n=64, a=8, s=32, out=FAKE, bG=4):
+        return lib.hdqt_gemm_codes_fold(qG, FAKE, bG, 4, FAKE, FAKE, C.byref(geo) if geo is not None else None,
+                                        N, n, a, s, out, None)
+    assert rc(qG=None) == E["HDQT_EINVAL_NULL"]
+    assert rc(out=None) == E["HDQT_EINVAL_NULL"]
+    assert rc(geo=None) == E["HDQT_EINVAL_NULL"]
+    assert rc(N=0) == E["HDQT_EINVAL_DIM"]
+    assert rc(n=48) == E["HDQT_EINVAL_HADAMARD"]
+    assert rc(a=40) == E["HDQT_EINVAL_ACC"]
+    assert rc(out=C.c_void_p(0x10004)) == E["HDQT_EALIGN"]
+    # geometries and settings the fold does not take: refused before anything is launched
+    assert rc(geo=B.CConv(2, 64, 12, 12, 3, 3)) == E["HDQT_EINVAL_GEOMETRY"]
+    assert rc(geo=B.CConv(2, 64, 16, 16, 2, 2)) == E["HDQT_EINVAL_GEOMETRY"]
+    assert rc(geo=B.CConv(2, 64, 2, 128, 3, 3)) == E["HDQT_EINVAL_GEOMETRY"]
+    assert rc(a=16) == E["HDQT_EINVAL_GEOMETRY"]           # totals beyond 16 bits
+    assert rc(bG=8) == E["HDQT_EINVAL_GEOMETRY"]           # 8-bit codes: not the 4-bit kernel
+    assert rc(s=48) == E["HDQT_EINVAL_GEOMETRY"]           # tile length not a multiple of 32
+    p = _cparams()
+    f = lib.hdqt_conv_bwd
+    args = lambda geo=good, dact=FAKE, ws=1 << 30: (FAKE, FAKE, FAKE, C.byref(geo), dact, FAKE, 128, C.byref(p),
+                                                   C.byref(p), FAKE, ws, None)
+    assert f(*args(dact=None)) == E["HDQT_EINVAL_NULL"]
+    assert f(*args(geo=B.CConv(2, 64, 12, 12, 3, 3))) == E["HDQT_EINVAL_GEOMETRY"]
+    assert f(*args(ws=16)) == E["HDQT_EWORKSPACE"]

@@ -139,11 +139,15 @@ def test_conv_module_from_activation_equals_unfolded():
     torch.manual_seed(4)
     x = torch.relu(torch.randn(4, 64, 16, 16, device="cuda:0"))
     mods = []
-    for fused in (True, False):
-        m = A.HdqtConv2d(64, 128, cfg=A.LayerConfig(layer_id=3, seed=2), device="cuda:0")
+    for fused in (True, False, True):
+        # (the third module also folds its input gradient inside the matmul: integer sums,
+        # dequantized once, so its input gradient is close to the others', not identical)
+        m = A.HdqtConv2d(64, 128, cfg=A.LayerConfig(layer_id=3, seed=2, fold_in_matmul=len(mods) == 2),
+                         device="cuda:0")
         m.from_activation = fused
         mods.append(m)
     mods[1].weight.data.copy_(mods[0].weight.data)
+    mods[2].weight.data.copy_(mods[0].weight.data)
     res = []
     for m in mods:
         xi = x.clone().requires_grad_(True)
@@ -153,5 +157,7 @@ def test_conv_module_from_activation_equals_unfolded():
         torch.cuda.synchronize()
         res.append((z.detach(), m.weight.grad, xi.grad))
     assert not mods[0]._refused and mods[0].step == 1
-    for a, b in zip(*res):
+    for a, b in zip(res[0], res[1]):
         assert torch.equal(a, b)
+    assert torch.equal(res[2][0], res[0][0]) and torch.equal(res[2][1], res[0][1])
+    assert torch.allclose(res[2][2], res[0][2], rtol=1e-5, atol=9 * 2.0 ** -22 * float(res[0][2].abs().max()))

@@ -48,6 +48,40 @@ def check_sampled(kind, P, Q, got, prm, rng, cache):
     assert not bad.any(), f"kind {kind}: {bad.sum()} of {bad.size} sampled outputs differ"
 
 
+def check_fold_sampled(G, W, dAct, shape, kh, prm, rng, cache):
+    """The folded input gradient at sampled positions: the oracle's accumulators of the (at most
+    kh*kh) entries of dX that fold onto each position, added as integers, dequantized once."""
+    batch, C, H, Wd = shape
+    def codes(role, T, op):
+        key = (role, 1, op.round, op.tensor_id)
+        if key not in cache:
+            cache[key] = capi.quantize(T, 1, prm.had_block, o_op(op), prm.seed)
+        return cache[key]
+    cA, sA, nA = codes("G", G, prm.A)
+    cB, sB, nB = codes("W", W, prm.B)
+    n = 512
+    bb, cc = rng.integers(0, batch, n), rng.integers(0, C, n)
+    yy, xx = rng.integers(0, H, n), rng.integers(0, Wd, n)
+    yy[:4], xx[:4] = [0, 0, H - 1, H - 1], [0, Wd - 1, 0, Wd - 1]
+    ph = (kh - 1) // 2
+    rows, cols, owner = [], [], []
+    for i in range(n):
+        for ty in range(kh):
+            for tx in range(kh):
+                yp, xp = yy[i] - ty + ph, xx[i] - tx + ph
+                if 0 <= yp < H and 0 <= xp < Wd:
+                    rows.append((bb[i] * H + yp) * Wd + xp)
+                    cols.append((cc[i] * kh + ty) * kh + tx)
+                    owner.append(i)
+    acc = capi.tiled_matmul_sampled(cA, cB, prm.s, prm.acc_bits, np.array(rows), np.array(cols))
+    total = np.zeros(n, dtype=np.int64)
+    np.add.at(total, np.array(owner), acc.astype(np.int64))
+    want = capi.dequantize(total.astype(np.int32), sA, sB, nA)
+    idx = [torch.from_numpy(v).to(dAct.device) for v in (bb, cc, yy, xx)]
+    have = dAct[idx[0], idx[1], idx[2], idx[3]].cpu().numpy()
+    assert np.array_equal(have, want), f"{(have != want).sum()} of {n} folded input gradients differ"
+
+
 def test_resnet18_training_step_matches_oracle_per_matmul():
     torch.manual_seed(0)
     batch = 128
@@ -72,7 +106,7 @@ def test_resnet18_training_step_matches_oracle_per_matmul():
     table = {name: (M, K, N) for name, M, K, N in workloads.resnet18_layer_table(batch)}
     assert set(cap) == set(table)
     rng = np.random.default_rng(4321)
-    fused = []
+    fused, folded = [], []
     for name in net.layer_names:
         c = cap[name]
         M, K, N = table[name]
@@ -91,9 +125,15 @@ def test_resnet18_training_step_matches_oracle_per_matmul():
         check_sampled(BWW, ("X", X), ("G", G), c["dW"], cfg.params(BWW, c["step"]), rng, cache)
         if name == "stem":
             assert c["dX"] is None
-        else:
+        elif c.get("dX") is not None:
             check_sampled(BWI, ("G", G), ("W", W), c["dX"], cfg.params(BWI, c["step"]), rng, cache)
+        else:
+            # the input gradient was folded onto the activation inside the matmul
+            check_fold_sampled(G, W, c["dAct"], tuple(c["act"].shape), 3, cfg.params(BWI, c["step"]), rng, cache)
+            folded.append(name)
         cap[name] = None            # release the captured tensors of this layer
     # the stride-1 3x3 layers at 32x32, 16x16 and 8x8 read their activation directly
     print("layers that read the activation directly:", fused, flush=True)
     assert len(fused) >= 9
+    print("layers whose input gradient was folded inside the matmul:", folded, flush=True)
+    assert len(folded) >= 9
