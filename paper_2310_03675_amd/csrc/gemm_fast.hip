@@ -324,7 +324,7 @@ __global__ __launch_bounds__(64 * WAVES, WAVES == 8 ? 4 : 2) void gemm_i4_kernel
             // then every thread adds up the kh*kw taps of its pixels and channels.  Both operand
             // buffers are free here: the stages still to come are in registers.
             constexpr int AP = 130;      // pitch in int16 (65 dwords: neighbouring pixels, neighbouring banks)
-            static_assert(sizeof(As) >= (size_t)BM * AP * sizeof(int16_t), "accumulator tile must fit the A buffers");
+            static_assert(sizeof(As) >= ((size_t)BM * AP + BN) * sizeof(int16_t), "accumulator tile must fit the A buffers");
             int16_t* accT = reinterpret_cast<int16_t*>(&As[0][0][0]);
             __syncthreads();             // every wave is done reading this stage's operands
 #pragma unroll
@@ -339,6 +339,9 @@ __global__ __launch_bounds__(64 * WAVES, WAVES == 8 ? 4 : 2) void gemm_i4_kernel
                         total[a][c][r] = 0;
                         accT[(lane_row + rr) * AP + lane_col + c * 32] = (int16_t)v;
                     }
+            // the word behind the tile, read for taps outside the image; c * khw + BM * AP stays
+            // inside the A buffers for every channel of a column tile
+            if (tid < BN) accT[BM * AP + tid] = 0;
             __syncthreads();
             const int W = g.fW, H = g.fH, kw = g.fkw, khw = g.fkh * g.fkw;
             const int q = tid & (BM - 1);                 // pixel of the tile
@@ -362,19 +365,42 @@ __global__ __launch_bounds__(64 * WAVES, WAVES == 8 ? 4 : 2) void gemm_i4_kernel
             }
             const int cbase = c_ct * g.f_cg;
             const int16_t* img_part = accT + (il << g.f_log2hw) * AP;      // (il = 0 in strip mode)
-            for (int c = tid / BM; c < g.f_cg; c += NTHREADS / BM) {
-                if (!out_ok || cbase + c >= g.fC) continue;
-                int sum = 0;
-                for (int ty = 0; ty < g.fkh; ++ty) {
-                    const int ryp = ry - ty + f_ph;
-                    if (ryp < 0 || ryp >= rows_part) continue;
-                    for (int tx = 0; tx < kw; ++tx) {
-                        const int xp = x - tx + f_pw;
-                        if (xp < 0 || xp >= W) continue;
-                        sum += img_part[((ryp << g.f_log2w) + xp) * AP + c * khw + ty * kw + tx];
-                    }
+            if (khw <= 9) {
+                // up to nine taps: where each one reads, worked out once for the pixel (a tap whose
+                // source pixel lies outside reads the zero word behind the tile), then three
+                // instructions per tap and channel
+                int off[9];
+                int ty = 0, tx = 0;
+#pragma unroll
+                for (int t = 0; t < 9; ++t) {
+                    const int ryp = ry - ty + f_ph, xp = x - tx + f_pw;
+                    const bool ok = t < khw && ryp >= 0 && ryp < rows_part && xp >= 0 && xp < W;
+                    off[t] = ok ? ((il << g.f_log2hw) + (ryp << g.f_log2w) + xp) * AP + t : BM * AP;
+                    if (++tx == kw) { tx = 0; ++ty; }
                 }
-                g.out[(((int64_t)b * g.fC + cbase + c) * H + y) * W + x] = (float)sum * dq;
+                for (int c = tid / BM; c < g.f_cg; c += NTHREADS / BM) {
+                    if (!out_ok || cbase + c >= g.fC) continue;
+                    const int16_t* col = accT + c * khw;
+                    int sum = 0;
+#pragma unroll
+                    for (int t = 0; t < 9; ++t) sum += col[off[t]];
+                    g.out[(((int64_t)b * g.fC + cbase + c) * H + y) * W + x] = (float)sum * dq;
+                }
+            } else {
+                for (int c = tid / BM; c < g.f_cg; c += NTHREADS / BM) {
+                    if (!out_ok || cbase + c >= g.fC) continue;
+                    int sum = 0;
+                    for (int ty = 0; ty < g.fkh; ++ty) {
+                        const int ryp = ry - ty + f_ph;
+                        if (ryp < 0 || ryp >= rows_part) continue;
+                        for (int tx = 0; tx < kw; ++tx) {
+                            const int xp = x - tx + f_pw;
+                            if (xp < 0 || xp >= W) continue;
+                            sum += img_part[((ryp << g.f_log2w) + xp) * AP + c * khw + ty * kw + tx];
+                        }
+                    }
+                    g.out[(((int64_t)b * g.fC + cbase + c) * H + y) * W + x] = (float)sum * dq;
+                }
             }
             __syncthreads();             // the next stage overwrites the buffers the sums were read from
             c_k = k_begin;
