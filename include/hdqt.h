@@ -195,6 +195,16 @@ int hdqt_quantize_dual_im2col(const float *act, const hdqt_conv_t *geo, int had_
                               size_t workspace_bytes, void *stream);
 
 /*
+ * The im2col matrix itself, for the layers the activation-source entry points refuse
+ * (strides, K off a multiple of 64, tiny images): X[(b, yo, xo), c*kh*kw + ty*kw + tx] =
+ * act[b, c, yo*stride + ty - pad_h, xo*stride + tx - pad_w], zero outside the image;
+ * X is [batch*Ho*Wo, channels*kh*kw] with Ho = (height + 2*pad_h - kh)/stride + 1 and Wo
+ * alike (fp32, device, 16-byte aligned).  Pure data movement, one launch.
+ */
+int hdqt_im2col(const float *act, int64_t batch, int channels, int height, int width, int kh,
+                int kw, int stride, int pad_h, int pad_w, float *X, void *stream);
+
+/*
  * Tiled integer matmul on packed codes (Methodology: tiles of size s, low-bit
  * accumulators) followed by dequantization:
  *   acc[i,j] = sum_t sat_a( sum_{d in tile t} qA[i,d] qB[j,d] )

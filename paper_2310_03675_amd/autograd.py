@@ -133,6 +133,24 @@ class HdqtConvMatmul(torch.autograd.Function):
         return dAct, dW, None, None, None, None
 
 
+class Unfold(torch.autograd.Function):
+    """act [B, C, H, W] -> its im2col matrix [B*Ho*Wo, C*k*k] by the library's one-launch kernel
+    (the layers whose geometry the activation-source kernels do not read directly); the
+    backward pass folds the matrix gradient back with PyTorch."""
+
+    @staticmethod
+    def forward(ctx, act, k: int, stride: int, pad: int):
+        ctx.geo = (tuple(act.shape), k, stride, pad)
+        return B.im2col(act, k, k, stride, pad, pad)
+
+    @staticmethod
+    def backward(ctx, dX):
+        (Bn, Cin, H, W), k, stride, pad = ctx.geo
+        cols = dX.reshape(Bn, -1, Cin * k * k).transpose(1, 2)
+        return torch.nn.functional.fold(cols, output_size=(H, W), kernel_size=k, padding=pad,
+                                        stride=stride), None, None, None
+
+
 class HdqtLinear(torch.nn.Module):
     """y = x W + bias with the matmul and its gradients quantized; inputs of any
     leading shape are flattened to [M, K]."""
@@ -161,8 +179,9 @@ class HdqtConv2d(torch.nn.Module):
     """Convolution as the paper runs it: the activation is unfolded (im2col, column index =
     channel * kh * kw + tap) and the products of the forward and the backward pass are the
     quantized matmuls above.  Stride-1, same-size layers whose geometry the library takes
-    never form the unfolded matrix in the forward pass (hdqt_conv_fwd reads the activation);
-    the others are unfolded by PyTorch.  Folding the input gradient back is PyTorch's."""
+    never form the unfolded matrix (hdqt_conv_fwd reads the activation, hdqt_conv_bwd folds the
+    input gradient back inside the matmul); the others are unfolded by hdqt_im2col and their
+    input gradient is folded back by PyTorch."""
 
     def __init__(self, in_channels: int, out_channels: int, kernel_size: int = 3, padding: int = 1,
                  stride: int = 1, cfg: Optional[LayerConfig] = None, device=None):
@@ -191,9 +210,7 @@ class HdqtConv2d(torch.nn.Module):
                     raise
                 self._refused.add(tuple(x.shape))
         if Z is None:
-            cols = torch.nn.functional.unfold(x, kernel_size=self.k, padding=self.pad,
-                                              stride=self.stride)                 # [B, C*k*k, Ho*Wo]
-            X = cols.transpose(1, 2).reshape(Bn * Ho * Wo, Cin * self.k * self.k)
+            X = Unfold.apply(x, self.k, self.stride, self.pad)                     # [B*Ho*Wo, C*k*k]
             Z = HdqtMatmul.apply(X, self.weight, self.cfg, self.step)
         if self.training:
             self.step += 1

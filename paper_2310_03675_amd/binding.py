@@ -29,7 +29,7 @@ EXPORTED = [
     "hdqt_gemm_codes_requant_workspace_size", "hdqt_gemm_codes_requant",
     "hdqt_gemm_requant_workspace_size", "hdqt_gemm_requant", "hdqt_gemm_codes_bf16",
     "hdqt_gemm_bwd_input_bf16", "hdqt_quantize_dual_im2col", "hdqt_conv_step_workspace_size",
-    "hdqt_conv_step", "hdqt_conv_fwd", "hdqt_conv_bwd", "hdqt_gemm_codes_fold",
+    "hdqt_conv_step", "hdqt_conv_fwd", "hdqt_conv_bwd", "hdqt_gemm_codes_fold", "hdqt_im2col",
 ]
 
 
@@ -160,6 +160,8 @@ def load() -> C.CDLL:
     lib.hdqt_conv_bwd.argtypes = [vp, vp, vp, C.POINTER(CConv), vp, vp, i64] + [C.POINTER(CParams)] * 2 + [vp, sz, vp]
     lib.hdqt_gemm_codes_fold.restype = i32
     lib.hdqt_gemm_codes_fold.argtypes = [vp, vp, i32, i32, vp, vp, C.POINTER(CConv), i64, i32, i32, i64, vp, vp]
+    lib.hdqt_im2col.restype = i32
+    lib.hdqt_im2col.argtypes = [vp, i64] + [i32] * 8 + [vp, vp]
     lib.hdqt_gemm_codes_bf16.restype = i32
     lib.hdqt_gemm_codes_bf16.argtypes = lib.hdqt_gemm_codes.argtypes
     for name in ("hdqt_gemm_fwd", "hdqt_gemm_bwd_input", "hdqt_gemm_bwd_weight", "hdqt_gemm_bwd_input_bf16"):
@@ -273,6 +275,21 @@ def quantize_dual(T: torch.Tensor, had_block: int, op_axis1: Operand, op_axis0: 
     if rc:
         raise HdqtError(rc, "hdqt_quantize_dual")
     return c1, s1, c0, s0
+
+
+def im2col(act: torch.Tensor, kh: int, kw: int, stride: int = 1, pad_h: int = 0, pad_w: int = 0,
+           stream: Optional[torch.cuda.Stream] = None) -> torch.Tensor:
+    """hdqt_im2col -> X [batch*Ho*Wo, C*kh*kw] (column index c*kh*kw + ty*kw + tx)."""
+    assert act.dim() == 4 and act.dtype == torch.float32
+    act = act.contiguous()
+    _check_dev(act)
+    b, c, h, w = act.shape
+    Ho, Wo = (h + 2 * pad_h - kh) // stride + 1, (w + 2 * pad_w - kw) // stride + 1
+    X = torch.empty((b * Ho * Wo, c * kh * kw), dtype=torch.float32, device=act.device)
+    rc = load().hdqt_im2col(_ptr(act), b, c, h, w, kh, kw, stride, pad_h, pad_w, _ptr(X), _stream(stream))
+    if rc:
+        raise HdqtError(rc, "hdqt_im2col")
+    return X
 
 
 def conv_geometry(act: torch.Tensor, kh: int, kw: int) -> CConv:

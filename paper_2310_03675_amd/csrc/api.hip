@@ -640,6 +640,27 @@ int hdqt_quantize_dual_im2col(const float* act, const hdqt_conv_t* geo, int had_
     return e == hipSuccess ? HDQT_OK : hip_fail(e);
 }
 
+int hdqt_im2col(const float* act, int64_t batch, int channels, int height, int width, int kh, int kw,
+                int stride, int pad_h, int pad_w, float* X, void* stream)
+{
+    if (!act || !X) return HDQT_EINVAL_NULL;
+    if (batch < 1 || channels < 1 || height < 1 || width < 1 || kh < 1 || kw < 1 || stride < 1 || pad_h < 0 ||
+        pad_w < 0 || kh > 255 || kw > 255 || height + 2 * pad_h < kh || width + 2 * pad_w < kw)
+        return HDQT_EINVAL_DIM;
+    const int Ho = (height + 2 * pad_h - kh) / stride + 1, Wo = (width + 2 * pad_w - kw) / stride + 1;
+    const int64_t per_image = (int64_t)Ho * Wo, K = (int64_t)channels * kh * kw;
+    if (batch > kMaxDim / per_image) return HDQT_EINVAL_DIM;
+    const int64_t M = batch * per_image;
+    int rc = check_dims2(M, K);
+    if (rc) return rc;
+    if ((int64_t)channels * height * width >= ((int64_t)1 << 31) || (M + 3) / 4 >= ((int64_t)1 << 31))
+        return HDQT_EINVAL_DIM;
+    if (misaligned(act) || misaligned(X)) return HDQT_EALIGN;
+    hdqt::Im2colArgs a{act, X, M, channels, height, width, kh, kw, stride, pad_h, pad_w, Ho, Wo};
+    const hipError_t e = hdqt::launch_im2col(a, static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? HDQT_OK : hip_fail(e);
+}
+
 size_t hdqt_gemm_codes_workspace_size(int64_t RA, int64_t RB, int64_t D, int64_t s)
 {
     if (RA <= 0 || RB <= 0 || D <= 0 || s < 1 || RA >= kMaxDim || RB >= kMaxDim || D >= kMaxDim) return 0;

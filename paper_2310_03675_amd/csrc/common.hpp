@@ -111,6 +111,15 @@ struct GemmArgs {
 // fills the fold fields from the geometry; false if the fast kernel does not take it
 bool gemm_fold_plan(GemmArgs* g, int64_t batch, int C, int H, int W, int kh, int kw);
 
+// Unfolding of an activation [batch, C, H, W] into X [M = batch*Ho*Wo, K = C*kh*kw] (im2col.hip)
+struct Im2colArgs {
+    const float* act;
+    float* X;
+    int64_t M;
+    int C, H, W, kh, kw, stride, ph, pw, Ho, Wo;
+};
+hipError_t launch_im2col(const Im2colArgs& a, hipStream_t stream);
+
 // Launchers (host).  Each returns the hipError_t of its last launch.
 hipError_t launch_quantize(const QuantArgs& q, hipStream_t stream);
 hipError_t launch_gemm(const GemmArgs& g, hipStream_t stream);
@@ -140,7 +149,7 @@ enum KernelId {
     K_PLAIN_QUANT, K_GEMM_ALIGNED, K_GEMM_GENERIC, K_REDUCE, K_GEMM_I4, K_DUAL_ABSMAX, K_DUAL_QUANT,
     K_GEMM_I4_FWD, K_GEMM_I4_BWD_INPUT, K_GEMM_I4_BWD_WEIGHT,
     K_DUAL_ABSMAX_X, K_DUAL_ABSMAX_W, K_DUAL_ABSMAX_G, K_DUAL_QUANT_X, K_DUAL_QUANT_W, K_DUAL_QUANT_G,
-    K_DUAL_ABSMAX_BATCH, K_DUAL_QUANT_BATCH, K_REQUANT_TILES, K_REQUANT_SUM,
+    K_DUAL_ABSMAX_BATCH, K_DUAL_QUANT_BATCH, K_REQUANT_TILES, K_REQUANT_SUM, K_IM2COL,
     K_COUNT
 };
 bool quantize_fast_eligible(const QuantArgs& q);

@@ -382,3 +382,15 @@ def test_folded_input_gradient_argument_errors():
     assert f(*args(dact=None)) == E["HDQT_EINVAL_NULL"]
     assert f(*args(geo=B.CConv(2, 64, 12, 12, 3, 3))) == E["HDQT_EINVAL_GEOMETRY"]
     assert f(*args(ws=16)) == E["HDQT_EWORKSPACE"]
+
+
+def test_im2col_argument_errors():
+    f = B.load().hdqt_im2col
+    ok = (FAKE, 2, 3, 8, 8, 3, 3, 1, 1, 1, FAKE, None)
+    bad = lambda i, v: f(*(ok[:i] + (v,) + ok[i + 1:]))
+    assert bad(0, None) == E["HDQT_EINVAL_NULL"] and bad(10, None) == E["HDQT_EINVAL_NULL"]
+    assert bad(1, 0) == E["HDQT_EINVAL_DIM"]          # batch
+    assert bad(7, 0) == E["HDQT_EINVAL_DIM"]          # stride
+    assert bad(5, 12) == E["HDQT_EINVAL_DIM"]         # window taller than the padded image
+    assert bad(8, -1) == E["HDQT_EINVAL_DIM"]         # negative padding
+    assert bad(10, C.c_void_p(0x10008)) == E["HDQT_EALIGN"]

@@ -161,3 +161,18 @@ def test_conv_module_from_activation_equals_unfolded():
         assert torch.equal(a, b)
     assert torch.equal(res[2][0], res[0][0]) and torch.equal(res[2][1], res[0][1])
     assert torch.allclose(res[2][2], res[0][2], rtol=1e-5, atol=9 * 2.0 ** -22 * float(res[0][2].abs().max()))
+
+
+@pytest.mark.parametrize("shape,k,stride,pad", [((3, 5, 9, 7), 3, 1, 1), ((2, 3, 32, 32), 3, 1, 1),
+                                                 ((2, 16, 16, 16), 3, 2, 1), ((2, 8, 8, 8), 1, 2, 0),
+                                                 ((1, 4, 7, 5), 5, 2, 2), ((2, 6, 4, 4), 3, 1, 0),
+                                                 ((1, 2, 1, 40), 1, 1, 0)])
+def test_im2col_kernel_against_library_unfold(shape, k, stride, pad):
+    """hdqt_im2col is data movement: identical to PyTorch's unfold, re-laid out row by pixel."""
+    g = torch.Generator().manual_seed(sum(shape) + k)
+    act = torch.randn(shape, generator=g)
+    want = torch.nn.functional.unfold(act, kernel_size=k, padding=pad, stride=stride)
+    want = want.transpose(1, 2).reshape(-1, shape[1] * k * k)
+    got = B.im2col(act.to("cuda:0"), k, k, stride, pad, pad)
+    torch.cuda.synchronize()
+    assert got.shape == want.shape and torch.equal(got.cpu(), want)
