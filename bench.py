@@ -113,6 +113,8 @@ def main():
                     help="skip the 4096^3 matmul measurement ('gemm_square_4096')")
     ap.add_argument("--no-conv", action="store_true",
                     help="skip the activation-source variant of the step ('conv_step')")
+    ap.add_argument("--no-sweep", action="store_true",
+                    help="skip the sweep of input and accumulator widths on the same layer")
     ap.add_argument("--requant", action="store_true",
                     help="also time the forward matmul under the second reading of the accumulator "
                          "(hdqt_gemm_requant) and report it as 'requant_fwd'")
@@ -464,6 +466,24 @@ def main():
         except B.HdqtError as exc:          # geometry the activation-source kernels do not take
             line["conv_step"] = {"skipped": str(exc)}
         del act_d
+    if not args.no_sweep and not args.separate:
+        # The same step over the input and accumulator widths of the paper's Fig. 4 (inputs of
+        # 3 to 8 bits, accumulators of 8 to 32): wall time per step and the rate at the
+        # headline metric's operation count.  Not `value`: that is the 4-bit / 8-bit point.
+        line["width_sweep"] = {"unit": "ms_per_step", "s": args.s}
+        for b_in, a_acc in ((3, 8), (4, 8), (4, 10), (4, 12), (4, 16), (5, 12), (6, 12), (6, 16), (8, 16), (8, 32)):
+            prm_w = [step_params(B, k, n, args.s, a_acc, b_in) for k in kinds]
+            ws_w = torch.empty(B.layer_step_workspace_size(M, K, N, *prm_w), dtype=torch.uint8, device=dev)
+            for _ in range(3):
+                B.layer_step(X, W, G, *prm_w, out=step_out, workspace=ws_w)
+            torch.cuda.synchronize()
+            t_w = time.perf_counter()
+            for _ in range(10):
+                B.layer_step(X, W, G, *prm_w, out=step_out, workspace=ws_w)
+            torch.cuda.synchronize()
+            ms_w = (time.perf_counter() - t_w) / 10 * 1e3
+            line["width_sweep"][f"b{b_in}_a{a_acc}"] = {"ms": ms_w, "TOPS": 3 * 2.0 * M * K * N / (ms_w * 1e-3) / 1e12}
+            del ws_w
     if args.requant:
         k = kinds[0]
         need = B.load().hdqt_gemm_requant_workspace_size(k, M, K, N, prm[k].c())

@@ -215,7 +215,7 @@ int run_quantize_pair(const float* T, int64_t rows, int64_t cols, int n1, const 
 hdqt::GemmArgs plan_gemm(const void* qA, const void* qB, int bA, int bB, const float* scaleA,
                          const float* scaleB, int64_t RA, int64_t RB, int64_t D, int n_eff,
                          int acc_bits, int64_t s, float* out, int32_t* acc_out, int profile_tag = 0,
-                         uint16_t* out_bf16 = nullptr)
+                         uint16_t* out_bf16 = nullptr, bool keep_tiles = false)
 {
     hdqt::GemmArgs g{};
     g.profile_tag = profile_tag;
@@ -223,10 +223,23 @@ hdqt::GemmArgs plan_gemm(const void* qA, const void* qB, int bA, int bB, const f
     g.pitchA = hdqt_codes_pitch(D, bA); g.pitchB = hdqt_codes_pitch(D, bB);
     g.bA = bA; g.bB = bB; g.RA = RA; g.RB = RB; g.D = D;
     g.s = s < D ? s : D;
-    g.s_pad = (int)((g.s + 15) / 16 * 16);
-    g.n_tiles = (D + g.s - 1) / g.s;
     g.acc_lo = acc_bits >= 32 ? INT_MIN : -(1 << (acc_bits - 1));
     g.acc_hi = acc_bits >= 32 ? INT_MAX : (1 << (acc_bits - 1)) - 1;
+    if (!keep_tiles) {
+        // Tiles that cannot saturate need not be kept apart: while m * s products of the
+        // largest magnitude, 2^(bA-1) * 2^(bB-1) each, fit the accumulator, the clamp of a
+        // group of m tiles changes nothing and the sum over the group is the sum of its
+        // tiles' sums.  Groups of 256 or 128 codes are whole stages of the matrix-core kernel
+        // (16-bit accumulators with 4-bit inputs, 32-bit ones with any inputs).
+        const int64_t max_prod = ((int64_t)1 << (bA - 1)) * ((int64_t)1 << (bB - 1));
+        for (int64_t grp = 256; grp >= 128; grp /= 2)
+            if (g.s < grp && grp % g.s == 0 && grp <= D && grp * max_prod <= (int64_t)g.acc_hi) {
+                g.s = grp;
+                break;
+            }
+    }
+    g.s_pad = (int)((g.s + 15) / 16 * 16);
+    g.n_tiles = (D + g.s - 1) / g.s;
     g.scaleA = scaleA; g.scaleB = scaleB;
     g.inv_n = 1.0f / (float)n_eff;
     g.out = out; g.acc_out = acc_out; g.out_bf16 = out_bf16;
@@ -498,7 +511,9 @@ int run_requant(const void* qA, const void* qB, int bA, int bB, const float* sca
                 int32_t* acc_out, void* ws, size_t ws_bytes, hipStream_t stream)
 {
     if (!ws || ws_bytes < requant_bytes(RA, RB, D, s)) return HDQT_EWORKSPACE;
-    hdqt::GemmArgs g = plan_gemm(qA, qB, bA, bB, scaleA, scaleB, RA, RB, D, n_eff, 32, s, out, acc_out);
+    // (the tiles are what this reading quantizes: they stay as given)
+    hdqt::GemmArgs g = plan_gemm(qA, qB, bA, bB, scaleA, scaleB, RA, RB, D, n_eff, 32, s, out, acc_out, 0,
+                                 nullptr, true);
     char* base = static_cast<char*>(ws);
     g.tile_max = reinterpret_cast<uint32_t*>(base);
     g.partial = reinterpret_cast<int32_t*>(base + align_up((size_t)g.n_tiles * sizeof(uint32_t), 256));

@@ -81,6 +81,7 @@ struct GemmArgs {
     int64_t n_tiles;        // ceil(D / s)
     int acc_lo, acc_hi;     // accumulator range [-2^(a-1), 2^(a-1)-1]
     int acc_lo_scaled, acc_hi_scaled;   // the same bounds times 256 (set by the 4-bit fast path)
+    int jA, jB, fin_shift;              // 16-bit saturation path: operand factors 2^jA, 2^jB; 16 - acc_bits
     const float* scaleA;    // device scalars
     const float* scaleB;
     float inv_n;            // 1 / n_eff (a power of two)

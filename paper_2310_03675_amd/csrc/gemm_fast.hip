@@ -1,8 +1,10 @@
-// Fast path of the tiled integer matmul for 4-bit codes (gfx950).
+// Fast path of the tiled integer matmul (gfx950).
 //
 // Same result as the generic kernel (tiles of size s along the contraction,
 // each tile's sum clamped to the a-bit accumulator range, 32-bit total), for
-//   both operands packed 4-bit, s a multiple of 32, D a multiple of 32.
+//   both operands packed 4-bit, or both with a byte per code (the WIDE instances: the
+//   bytes go to LDS as they are, nothing is scaled, generic clamp only);
+//   s a multiple of 32, D a multiple of 32.
 //
 // What differs from the generic kernel:
 //   * v_mfma_i32_32x32x32_i8: one MFMA consumes 32 contraction positions.
@@ -47,7 +49,15 @@ constexpr int KS_LONG = 128;          // codes per LDS stage: 4 MFMA steps.  (St
 constexpr int KSTEP = 32;             // codes per MFMA
 constexpr int kScaleShift = 8;        // both operands carry a factor 16
 
-enum Epilogue { EPI_GENERIC = 0, EPI_SAT8_S32 = 1, EPI_SAT8_S64 = 2, EPI_STAGES = 3 };
+enum Epilogue { EPI_GENERIC = 0, EPI_SAT8_S32 = 1, EPI_SAT8_S64 = 2, EPI_STAGES = 3, EPI_SAT16_S32 = 4,
+                EPI_SAT16_S64 = 5 };
+// EPI_SAT16: accumulators of a bits, bA + bB <= a <= 16, tiles of 32 or 64.  The operands go to
+// LDS scaled by 2^jA and 2^jB, jA + jB = 16 - a (a code of b bits times 2^(8-b) still fits a
+// byte), so a tile's sum arrives times 2^(16-a) and saturating it to int16 is the a-bit clamp,
+// still times 2^(16-a) once the low 16 - a bits are cleared (32767 is not a multiple);
+// v_dot2c_i32_i16 adds the two halves of a pair to the total, and one exact shift at the
+// end takes the factor out.  (EPI_SAT8 is the case a = 8 with 4-bit
+// operands, whose unpacking gives the factor 256 for free.)
 // EPI_STAGES: the generic clamp for tiles that are whole stages (s a multiple of KS_LONG): the
 // tile ends are tested once per stage, so nothing branches between the MFMAs of a stage and
 // the fragment loads of its four steps can run ahead of them.
@@ -61,6 +71,14 @@ __device__ __forceinline__ uint4 load_unit(const uint8_t* q, int64_t pitch, int6
                                            int64_t k, int64_t k_end)
 {
     if (row >= 0 && row < R && k < k_end) return *reinterpret_cast<const uint4*>(q + row * pitch + (k >> 1));
+    return make_uint4(0u, 0u, 0u, 0u);
+}
+
+// a byte per code: the 32 codes of a unit are two of these, at byte offsets k and k + 16
+__device__ __forceinline__ uint4 load_unit_wide(const uint8_t* q, int64_t pitch, int64_t R, int64_t row,
+                                                int64_t k, int64_t k_end, int half)
+{
+    if (row >= 0 && row < R && k < k_end) return *reinterpret_cast<const uint4*>(q + row * pitch + k + 16 * half);
     return make_uint4(0u, 0u, 0u, 0u);
 }
 
@@ -78,6 +96,53 @@ __device__ __forceinline__ int add_sat8_pair(int total, int p0, int p1)
 {
     const v2s pk = __builtin_amdgcn_cvt_pk_i16(p0, p1);
     return __builtin_amdgcn_sdot4(__builtin_bit_cast(int, pk), 0x01000100, total, false);
+}
+
+// total += floor_f(clamp(p0, -32768, 32767)) + floor_f(clamp(p1, -32768, 32767)), floor_f =
+// down to a multiple of the factor 2^need the sums carry (`low_clear` has the low `need` bits
+// of both halves clear): a sum that saturates upwards becomes 32767, which is
+// (2^(a-1) - 1) * 2^need plus a remainder that must not add up over the tiles.
+__device__ __forceinline__ int add_sat16_pair(int total, int p0, int p1, uint32_t low_clear)
+{
+    const v2s pk = __builtin_amdgcn_cvt_pk_i16(p0, p1);
+    const v2s ones = {1, 1};
+    return __builtin_amdgcn_sdot2(__builtin_bit_cast(v2s, __builtin_bit_cast(uint32_t, pk) & low_clear), ones,
+                                  total, false);
+}
+
+// Four bytes, each holding code * 16 (a nibble in its high half), to code * 2^j, j < 4:
+// a shift right by k = 4 - j inside every byte, then sign extension from bit 7 - k.  Bit 7
+// is set before the subtraction so that no byte borrows from its neighbour, and cleared
+// (or, for a negative code, set) by the last exclusive or.
+__device__ __forceinline__ uint32_t rescale_bytes(uint32_t hi_form, int k, uint32_t keep, uint32_t sign)
+{
+    const uint32_t t = (hi_form >> k) & keep;
+    return (((t ^ sign) | 0x80808080u) - sign) ^ 0x80808080u;
+}
+
+// 32 packed 4-bit codes -> LDS as bytes code * 2^j (even codes first, then odd ones)
+__device__ __forceinline__ void store_unit_scaled(uint8_t* lds_row_k, const uint4& w, int j)
+{
+    const uint32_t m = 0xF0F0F0F0u;
+    uint4 even = make_uint4((w.x << 4) & m, (w.y << 4) & m, (w.z << 4) & m, (w.w << 4) & m);
+    uint4 odd = make_uint4(w.x & m, w.y & m, w.z & m, w.w & m);
+    if (j < 4) {
+        const int k = 4 - j;
+        const uint32_t keep = (0xFFu >> k) * 0x01010101u, sign = (0x80u >> k) * 0x01010101u;
+        even = make_uint4(rescale_bytes(even.x, k, keep, sign), rescale_bytes(even.y, k, keep, sign),
+                          rescale_bytes(even.z, k, keep, sign), rescale_bytes(even.w, k, keep, sign));
+        odd = make_uint4(rescale_bytes(odd.x, k, keep, sign), rescale_bytes(odd.y, k, keep, sign),
+                         rescale_bytes(odd.z, k, keep, sign), rescale_bytes(odd.w, k, keep, sign));
+    }
+    *reinterpret_cast<uint4*>(lds_row_k) = even;
+    *reinterpret_cast<uint4*>(lds_row_k + 16) = odd;
+}
+
+// 16 codes, a byte each, times 2^j (the caller guarantees that they still fit)
+__device__ __forceinline__ uint4 scale_bytes(const uint4& w, int j)
+{
+    const uint32_t keep = ((0xFFu << j) & 0xFFu) * 0x01010101u;
+    return make_uint4((w.x << j) & keep, (w.y << j) & keep, (w.z << j) & keep, (w.w << j) & keep);
 }
 
 // clamp(v, lo, hi), lo <= hi.  Plain C++ on purpose: written as inline assembly (one
@@ -102,9 +167,19 @@ __device__ __forceinline__ int clamp3(int v, int lo, int hi)
 // flight.  With gridDim.z = 1 a workgroup walks along a
 // whole row strip of the output, which is how short contractions (one or two
 // stages per tile) keep loads, MFMAs and stores overlapped.
-template <int EPI, int KS, bool STREAM, int WAVES, bool BF16, bool FOLD>
+template <int EPI, int KS, bool STREAM, int WAVES, bool BF16, bool FOLD, bool WIDE = false>
 __global__ __launch_bounds__(64 * WAVES, WAVES == 8 ? 4 : 2) void gemm_i4_kernel(GemmArgs g)
 {
+    constexpr bool kSat16 = (EPI == EPI_SAT16_S32 || EPI == EPI_SAT16_S64);
+    constexpr bool kSat8 = (EPI == EPI_SAT8_S32 || EPI == EPI_SAT8_S64);
+    constexpr bool kPairs32 = (EPI == EPI_SAT8_S32 || EPI == EPI_SAT16_S32);      // pairs of 32-code tiles
+    constexpr bool kPairs64 = (EPI == EPI_SAT8_S64 || EPI == EPI_SAT16_S64);      // pairs of 64-code tiles
+    static_assert(!WIDE || !kSat8, "the 8-bit clamp trick needs the factor 256 of the nibble unpack");
+    constexpr int SHIFT = WIDE ? 0 : kScaleShift;      // factor the totals carry, as a shift
+    // factor left in a finished total, as a shift: none after the 8-bit trick
+    const int fin_shift = kSat16 ? g.fin_shift : (kSat8 ? 0 : SHIFT);
+    const uint32_t low_clear = kSat16 ? (0xFFFFu & (0xFFFFu << g.fin_shift)) * 0x00010001u : 0u;
+    constexpr int REGS = WIDE ? 2 : 1;                 // 16-byte registers per unit in flight
     // WAVES = 4: each wave a 64 x 64 quarter (2 x 2 MFMA blocks).  WAVES = 8: each wave
     // 64 rows x 32 columns (2 x 1 MFMA blocks): half the accumulators per wave, so four
     // waves fit a SIMD instead of two, at 1.5 LDS fragment reads per MFMA instead of 1.
@@ -115,7 +190,7 @@ __global__ __launch_bounds__(64 * WAVES, WAVES == 8 ? 4 : 2) void gemm_i4_kernel
     constexpr int NSTEP = KS / KSTEP;
     constexpr int LDP = KS + 16;          // LDS row pitch in bytes (int8 codes)
     constexpr int UNITS = 128 * NSTEP / NTHREADS;   // 16-byte units per operand and thread
-    static_assert(EPI != EPI_SAT8_S64 || KS == KS_LONG, "a pair of 64-code tiles is one long stage");
+    static_assert(!kPairs64 || KS == KS_LONG, "a pair of 64-code tiles is one long stage");
     __shared__ __attribute__((aligned(16))) uint8_t As[2][BM][LDP];
     __shared__ __attribute__((aligned(16))) uint8_t Bs[2][BN][LDP];
 
@@ -166,14 +241,22 @@ __global__ __launch_bounds__(64 * WAVES, WAVES == 8 ? 4 : 2) void gemm_i4_kernel
     // ---- the load stream: position of the next stage to fetch
     int f_ct = blockIdx.z;
     int64_t f_k = k_begin;
-    auto fetch_next = [&](Staged<UNITS>& st) {
+    auto fetch_next = [&](Staged<UNITS * REGS>& st) {
         if (f_ct >= n_ct) return;
         const int64_t col0 = (int64_t)f_ct * col_stride;
 #pragma unroll
         for (int i = 0; i < UNITS; ++i) {
             const int r = lrow + ROWS_PER_PASS * i;
-            st.a[i] = load_unit(g.qA, g.pitchA, g.RA, a_row(r), f_k + lks * KSTEP, k_end);
-            st.b[i] = load_unit(g.qB, g.pitchB, g.RB, col0 + r, f_k + lks * KSTEP, k_end);
+            if constexpr (WIDE) {
+#pragma unroll
+                for (int hf = 0; hf < 2; ++hf) {
+                    st.a[2 * i + hf] = load_unit_wide(g.qA, g.pitchA, g.RA, a_row(r), f_k + lks * KSTEP, k_end, hf);
+                    st.b[2 * i + hf] = load_unit_wide(g.qB, g.pitchB, g.RB, col0 + r, f_k + lks * KSTEP, k_end, hf);
+                }
+            } else {
+                st.a[i] = load_unit(g.qA, g.pitchA, g.RA, a_row(r), f_k + lks * KSTEP, k_end);
+                st.b[i] = load_unit(g.qB, g.pitchB, g.RB, col0 + r, f_k + lks * KSTEP, k_end);
+            }
         }
         f_k += KS;
         if (f_k >= k_end) { f_k = k_begin; f_ct += gridDim.z; }
@@ -194,21 +277,34 @@ __global__ __launch_bounds__(64 * WAVES, WAVES == 8 ? 4 : 2) void gemm_i4_kernel
     // Whole stages only: positions at or beyond k_end are zero in LDS and add nothing.
     // One barrier per stage is enough: buffer `buf` was last read two stages ago,
     // and every wave has passed the previous stage's barrier since.
-    auto stage = [&](Staged<UNITS>& st, const int buf) {
+    auto stage = [&](Staged<UNITS * REGS>& st, const int buf) {
 #pragma unroll
         for (int i = 0; i < UNITS; ++i) {
             const int r = lrow + ROWS_PER_PASS * i;
-            store_unit(&As[buf][r][lks * KSTEP], st.a[i]);
-            store_unit(&Bs[buf][r][lks * KSTEP], st.b[i]);
+            if constexpr (WIDE) {
+#pragma unroll
+                for (int hf = 0; hf < 2; ++hf) {
+                    *reinterpret_cast<uint4*>(&As[buf][r][lks * KSTEP + 16 * hf]) =
+                        kSat16 ? scale_bytes(st.a[2 * i + hf], g.jA) : st.a[2 * i + hf];
+                    *reinterpret_cast<uint4*>(&Bs[buf][r][lks * KSTEP + 16 * hf]) =
+                        kSat16 ? scale_bytes(st.b[2 * i + hf], g.jB) : st.b[2 * i + hf];
+                }
+            } else if constexpr (kSat16) {
+                store_unit_scaled(&As[buf][r][lks * KSTEP], st.a[i], g.jA);
+                store_unit_scaled(&Bs[buf][r][lks * KSTEP], st.b[i], g.jB);
+            } else {
+                store_unit(&As[buf][r][lks * KSTEP], st.a[i]);
+                store_unit(&Bs[buf][r][lks * KSTEP], st.b[i]);
+            }
         }
         __syncthreads();
         fetch_next(st);
 
-        if (EPI == EPI_SAT8_S32 || EPI == EPI_SAT8_S64) {
+        if (kPairs32 || kPairs64) {
             // two tiles per half stage (s = 32) or per stage (s = 64)
 #pragma unroll
-            for (int pr = 0; pr < (EPI == EPI_SAT8_S32 ? NSTEP / 2 : 1); ++pr) {
-                constexpr int SPT = (EPI == EPI_SAT8_S32) ? 1 : 2;      // steps per tile
+            for (int pr = 0; pr < (kPairs32 ? NSTEP / 2 : 1); ++pr) {
+                constexpr int SPT = kPairs32 ? 1 : 2;      // steps per tile
                 v4i fa[2 * SPT][2], fb[2 * SPT][CS];
 #pragma unroll
                 for (int q = 0; q < 2 * SPT; ++q)
@@ -229,7 +325,8 @@ __global__ __launch_bounds__(64 * WAVES, WAVES == 8 ? 4 : 2) void gemm_i4_kernel
                             p1 = __builtin_amdgcn_mfma_i32_32x32x32_i8(fa[SPT + 1][a], fb[SPT + 1][c], p1, 0, 0, 0);
 #pragma unroll
                         for (int r = 0; r < 16; ++r)
-                            total[a][c][r] = add_sat8_pair(total[a][c][r], p0[r], p1[r]);
+                            total[a][c][r] = kSat16 ? add_sat16_pair(total[a][c][r], p0[r], p1[r], low_clear)
+                                                    : add_sat8_pair(total[a][c][r], p0[r], p1[r]);
                     }
             }
         } else if (EPI == EPI_STAGES) {
@@ -334,8 +431,7 @@ __global__ __launch_bounds__(64 * WAVES, WAVES == 8 ? 4 : 2) void gemm_i4_kernel
 #pragma unroll
                     for (int r = 0; r < 16; ++r) {
                         const int rr = a * 32 + 8 * (r >> 2) + (r & 3);
-                        const int v = (EPI == EPI_GENERIC || EPI == EPI_STAGES) ? (total[a][c][r] >> kScaleShift)
-                                                                                 : total[a][c][r];
+                        const int v = total[a][c][r] >> fin_shift;
                         total[a][c][r] = 0;
                         accT[(lane_row + rr) * AP + lane_col + c * 32] = (int16_t)v;
                     }
@@ -423,7 +519,7 @@ __global__ __launch_bounds__(64 * WAVES, WAVES == 8 ? 4 : 2) void gemm_i4_kernel
         if constexpr (BF16) if (pair_bf16) {
             const bool odd = lane & 1;
             auto value = [&](int t) -> float {
-                return (float)((EPI == EPI_GENERIC || EPI == EPI_STAGES) ? (t >> kScaleShift) : t) * dq;
+                return (float)(t >> fin_shift) * dq;
             };
             // quad_perm [1,0,3,2]: the value of lane ^ 1
             auto neighbour = [](float f) -> float {
@@ -476,7 +572,7 @@ __global__ __launch_bounds__(64 * WAVES, WAVES == 8 ? 4 : 2) void gemm_i4_kernel
                 for (int r = 0; r < 16; ++r) {
                     const int rr = a * 32 + 8 * (r >> 2) + (r & 3);
                     const int64_t uo = (int64_t)rr * g.RB + c * 32;
-                    const int v = (EPI == EPI_GENERIC || EPI == EPI_STAGES) ? (total[a][c][r] >> kScaleShift) : total[a][c][r];
+                    const int v = total[a][c][r] >> fin_shift;
                     total[a][c][r] = 0;
                     bool ok = interior;
                     if (!interior)
@@ -500,9 +596,10 @@ __global__ __launch_bounds__(64 * WAVES, WAVES == 8 ? 4 : 2) void gemm_i4_kernel
     // it (one stage of 128 codes is 8 MFMAs per wave, about 0.5 us of matrix time per SIMD,
     // less than a trip to L2 under load), one stage ahead in the s = 64 instance, which has
     // no eight registers to spare at four waves per SIMD.
-    constexpr bool kDeep = (EPI != EPI_SAT8_S64) && !FOLD;      // (the fold epilogue needs the registers)
+    // (the fold epilogue needs the registers; with a byte per code a stage in flight is twice as many)
+    constexpr bool kDeep = !kPairs64 && !FOLD && !WIDE;
     if constexpr (kDeep) {
-        Staged<UNITS> st0, st1;
+        Staged<UNITS * REGS> st0, st1;
         fetch_next(st0);
         fetch_next(st1);
         while (c_ct < n_ct) {       // stage() advances c_ct at the end of a tile
@@ -511,7 +608,7 @@ __global__ __launch_bounds__(64 * WAVES, WAVES == 8 ? 4 : 2) void gemm_i4_kernel
             stage(st1, 1);
         }
     } else {
-        Staged<UNITS> st;
+        Staged<UNITS * REGS> st;
         fetch_next(st);
         int buf = 0;
         while (c_ct < n_ct) {
@@ -522,6 +619,28 @@ __global__ __launch_bounds__(64 * WAVES, WAVES == 8 ? 4 : 2) void gemm_i4_kernel
 }
 
 bool sat8_path(const GemmArgs& g) { return g.acc_hi == 127 && (g.s == 32 || g.s == 64); }
+
+// Saturation through the int16 conversion (EPI_SAT16): accumulators of bA + bB to 16 bits,
+// tiles of 32 or 64 codes.  Fills in the operand factors when `plan` is given.
+bool sat16_path(const GemmArgs& g, GemmArgs* plan = nullptr)
+{
+    if ((g.s != 32 && g.s != 64) || g.fold || g.out_bf16 || g.acc_hi > 32767) return false;
+    if ((g.bA > 4) != (g.bB > 4)) return false;
+    if (g.bA <= 4 && sat8_path(g)) return false;      // has its own, cheaper instances
+    int a = 1;
+    while (((int64_t)1 << (a - 1)) - 1 < g.acc_hi) ++a;
+    // a code of b bits times 2^(8 - b) still fits a byte; packed codes are unpacked as 4-bit ones
+    const int capA = g.bA > 4 ? 8 - g.bA : 4, capB = g.bB > 4 ? 8 - g.bB : 4;
+    const int need = 16 - a;
+    if (need > capA + capB) return false;
+    if (g.tiles_per_split >= 65536) return false;     // totals carry the factor 2^need: |.| <= tiles * 2^15
+    if (plan) {
+        plan->jA = need < capA ? need : capA;
+        plan->jB = need - plan->jA;
+        plan->fin_shift = need;
+    }
+    return true;
+}
 
 } // namespace
 
@@ -566,9 +685,19 @@ bool gemm_fold_plan(GemmArgs* g, int64_t batch, int C, int H, int W, int kh, int
 
 bool gemm_fast_eligible(const GemmArgs& g)
 {
-    if (g.bA > 4 || g.bB > 4) return false;
+    if ((g.bA > 4) != (g.bB > 4)) return false;      // packed or bytes, the same on both sides
     if (g.s % KSTEP != 0 || g.D % KSTEP != 0) return false;
     if (g.RB > ((int64_t)1 << 21)) return false;     // 32-bit offsets inside an output tile
+    if (sat16_path(g)) return true;
+    if (g.bA > 4) {
+        // a byte per code: nothing is scaled; a tile's sum (|code| <= 128 on both sides) and
+        // a part's total must stay inside int32
+        if (g.fold || g.out_bf16) return false;
+        const int64_t tile_max = g.s << 14, acc_max = (int64_t)g.acc_hi + 1;
+        const int64_t per_tile = tile_max < acc_max ? tile_max : acc_max;
+        if (g.s >= ((int64_t)1 << 16)) return false;
+        return per_tile * g.tiles_per_split < ((int64_t)1 << 31);
+    }
     if (sat8_path(g)) return true;      // unscaled int32 total: covered by the API's range check
     // generic epilogue: totals carry a factor 256 and must stay inside int32
     const int64_t tile_max = g.s * 64;                            // |code| <= 8 on both sides
@@ -581,7 +710,8 @@ bool gemm_fast_eligible(const GemmArgs& g)
 hipError_t launch_gemm_fast(const GemmArgs& g_in, hipStream_t stream)
 {
     GemmArgs g = g_in;
-    const int64_t lo = (int64_t)g.acc_lo * 256, hi = (int64_t)g.acc_hi * 256;
+    const bool wide = g.bA > 4;
+    const int64_t lo = (int64_t)g.acc_lo * (wide ? 1 : 256), hi = (int64_t)g.acc_hi * (wide ? 1 : 256);
     g.acc_lo_scaled = lo < INT32_MIN ? INT32_MIN : (int)lo;
     g.acc_hi_scaled = hi > INT32_MAX ? INT32_MAX : (int)hi;
     // Short contractions (at most two stages per output tile): a workgroup walks along
@@ -592,6 +722,7 @@ hipError_t launch_gemm_fast(const GemmArgs& g_in, hipStream_t stream)
         n_rt = g.f_imgs ? (g.fbatch + g.f_imgs - 1) / g.f_imgs : g.fbatch * g.f_strips;
     }
     const bool s32 = sat8_path(g) && g.s == 32;
+    const bool sat16 = sat16_path(g, &g);
     const int64_t KS = KS_LONG;
     const int64_t stages = (g.tiles_per_split * g.s + KS - 1) / KS;
     int64_t gx = n_ct;
@@ -615,11 +746,32 @@ hipError_t launch_gemm_fast(const GemmArgs& g_in, hipStream_t stream)
         else                                                                                         \
             hipLaunchKernelGGL((gemm_i4_kernel<EPI, KS_LONG, false, kWaves, false, false>), grid, block, 0, stream, g); \
     } while (0)
-    if (s32) HDQT_LAUNCH_I4(EPI_SAT8_S32);
+#define HDQT_LAUNCH_SAT16(EPI, WIDE)                                                                  \
+    do {                                                                                             \
+        const dim3 block(64 * kWaves);                                                               \
+        if (g.stream_out) hipLaunchKernelGGL((gemm_i4_kernel<EPI, KS_LONG, true, kWaves, false, false, WIDE>), grid, block, 0, stream, g); \
+        else hipLaunchKernelGGL((gemm_i4_kernel<EPI, KS_LONG, false, kWaves, false, false, WIDE>), grid, block, 0, stream, g); \
+    } while (0)
+    if (sat16) {
+        if (wide && g.s == 32) HDQT_LAUNCH_SAT16(EPI_SAT16_S32, true);
+        else if (wide) HDQT_LAUNCH_SAT16(EPI_SAT16_S64, true);
+        else if (g.s == 32) HDQT_LAUNCH_SAT16(EPI_SAT16_S32, false);
+        else HDQT_LAUNCH_SAT16(EPI_SAT16_S64, false);
+    } else if (wide) {
+        const dim3 block(64 * kWaves);
+        if (g.s % KS_LONG == 0) {
+            if (g.stream_out) hipLaunchKernelGGL((gemm_i4_kernel<EPI_STAGES, KS_LONG, true, kWaves, false, false, true>), grid, block, 0, stream, g);
+            else hipLaunchKernelGGL((gemm_i4_kernel<EPI_STAGES, KS_LONG, false, kWaves, false, false, true>), grid, block, 0, stream, g);
+        } else {
+            if (g.stream_out) hipLaunchKernelGGL((gemm_i4_kernel<EPI_GENERIC, KS_LONG, true, kWaves, false, false, true>), grid, block, 0, stream, g);
+            else hipLaunchKernelGGL((gemm_i4_kernel<EPI_GENERIC, KS_LONG, false, kWaves, false, false, true>), grid, block, 0, stream, g);
+        }
+    } else if (s32) HDQT_LAUNCH_I4(EPI_SAT8_S32);
     else if (sat8_path(g)) HDQT_LAUNCH_I4(EPI_SAT8_S64);
     else if (g.s % KS_LONG == 0) HDQT_LAUNCH_I4(EPI_STAGES);
     else HDQT_LAUNCH_I4(EPI_GENERIC);
 #undef HDQT_LAUNCH_I4
+#undef HDQT_LAUNCH_SAT16
     return hipGetLastError();
 }
 

@@ -24,8 +24,9 @@
 // folded into the reciprocal step the lane quantizes with.
 // The axis-1 transform is done row by row on copies (eight values at a time),
 // the axis-0 transform then in place.  No LDS is involved.
-// Requires rows and cols multiples of 64, block orders up to 64 and codes of at
-// most 4 bits.
+// Requires rows and cols multiples of 64 and block orders up to 64.  Codes of up to
+// 4 bits are packed two per byte; the WIDE instances write codes of 5 to 8 bits, one
+// per byte (both axes of a tensor, and all tensors of a launch, on the same side).
 
 #include "common.hpp"
 #include "lane_ops.hpp"
@@ -210,7 +211,7 @@ __device__ __forceinline__ void random_words(int64_t e, bool odd, uint32_t tenso
 
 // Axis 1 for the lane's row 8*rg + i of the tile: transform, then absmax (pass
 // 1) or codes (pass 2).
-template <bool QUANT, bool STOCH>
+template <bool QUANT, bool STOCH, bool WIDE>
 __device__ __forceinline__ void row_line(const Tile& t, int i, const DualCtx& x, int64_t row0,
                                          int64_t col0, float& amax)
 {
@@ -268,12 +269,34 @@ __device__ __forceinline__ void row_line(const Tile& t, int i, const DualCtx& x,
         }
     }
     const int64_t row = row0 + x.rg * 8 + i;
-    const float magic = kMagic + 8.0f;
+    const float magic = kMagic + (WIDE ? 128.0f : 8.0f);
     uint32_t both = 0;       // the lane's eight codes: low half h = 0, high half h = 1
     uint32_t rnd[2][2] = {{0u, 0u}, {0u, 0u}};
     if (STOCH)
         random_words(row * q.cols + col0 + x.cg * 4, (x.cg & 1) != 0, q.tid_row, q.seed_row_lo,
                      q.seed_row_hi, rnd[0], rnd[1]);
+    if constexpr (WIDE) {
+        // one byte per code: the lane's four codes of each half are a dword.  Lanes cg and
+        // cg ^ 1 trade one of them: the even lane ends up with columns 4cg .. 4cg+7, the odd
+        // one with columns 32+4(cg-1) .. 32+4cg+3, eight bytes per lane and store.
+        uint32_t word[2];
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+            uint32_t cw[4];
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const uint32_t u = (rnd[h][j >> 1] >> (16 * (j & 1))) & 0xFFFFu;
+                cw[j] = code_word<STOCH>(w[4 * h + j], x.inv_row, x.qmin_row, x.qmax_row, magic, u);
+            }
+            word[h] = pack_bytes(cw);
+        }
+        const bool odd = (x.cg & 1) != 0;
+        const uint32_t other = __float_as_uint(lane_xor<1>(__uint_as_float(odd ? word[0] : word[1])));
+        const uint2 pair = odd ? make_uint2(other, word[1]) : make_uint2(word[0], other);
+        const int byte_off = odd ? 32 + 4 * (x.cg - 1) : 4 * x.cg;
+        *reinterpret_cast<uint2*>(q.codes_row + row * q.cols + col0 + byte_off) = pair;
+        return;
+    }
 #pragma unroll
     for (int h = 0; h < 2; ++h) {
         const uint32_t* w01 = rnd[h];
@@ -331,12 +354,12 @@ __device__ __forceinline__ float col_transform(Tile& t, int log2n, float c8)
     return m;
 }
 
-template <bool STOCH>
+template <bool STOCH, bool WIDE>
 __device__ __forceinline__ void col_codes(const Tile& t, const DualCtx& x, int64_t row0, int64_t col0)
 {
     const DualArgs& q = *x.q;
-    const float magic = kMagic + 8.0f;
-    const int64_t pitch = q.rows >> 1;
+    const float magic = kMagic + (WIDE ? 128.0f : 8.0f);
+    const int64_t pitch = WIDE ? q.rows : q.rows >> 1;
     uint32_t cw[2][4][8];
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
@@ -352,14 +375,19 @@ __device__ __forceinline__ void col_codes(const Tile& t, const DualCtx& x, int64
                 cw[h][j][i] = code_word<STOCH>(t.v[h][j][i], x.inv_col, x.qmin_col, x.qmax_col, magic, u);
             }
     }
-    // column 32h + 4cg + j, rows 8rg .. 8rg+7: one dword; the eight rg lanes of a
-    // column write 32 consecutive bytes
+    // column 32h + 4cg + j, rows 8rg .. 8rg+7: one dword (two with a byte per code); the
+    // eight rg lanes of a column write 32 (64) consecutive bytes
 #pragma unroll
     for (int h = 0; h < 2; ++h)
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
-            uint8_t* dst = q.codes_col + (col0 + 32 * h + x.cg * 4 + j) * pitch + (row0 >> 1) + x.rg * 4;
-            *reinterpret_cast<uint32_t*>(dst) = pack_nibbles(cw[h][j]);
+            if constexpr (WIDE) {
+                uint8_t* dst = q.codes_col + (col0 + 32 * h + x.cg * 4 + j) * pitch + row0 + x.rg * 8;
+                *reinterpret_cast<uint2*>(dst) = make_uint2(pack_bytes(cw[h][j]), pack_bytes(cw[h][j] + 4));
+            } else {
+                uint8_t* dst = q.codes_col + (col0 + 32 * h + x.cg * 4 + j) * pitch + (row0 >> 1) + x.rg * 4;
+                *reinterpret_cast<uint32_t*>(dst) = pack_nibbles(cw[h][j]);
+            }
         }
 }
 
@@ -433,7 +461,7 @@ __device__ __forceinline__ void dual_absmax(Tile& t, const DualCtx& x, int64_t r
                                             float& amax_row, float& amax_col)
 {
 #pragma unroll
-    for (int i = 0; i < 8; ++i) row_line<false, false>(t, i, x, row0, col0, amax_row);
+    for (int i = 0; i < 8; ++i) row_line<false, false, false>(t, i, x, row0, col0, amax_row);
     if (x.log2n_col > 5) {
         amax_col = fmaxf(amax_col, col_transform<true>(t, x.log2n_col, x.c8));
     } else {
@@ -448,14 +476,14 @@ __device__ __forceinline__ void dual_absmax(Tile& t, const DualCtx& x, int64_t r
 }
 
 // both code sets of a tile; `t` is spent afterwards
-template <bool ST_ROW, bool ST_COL>
+template <bool ST_ROW, bool ST_COL, bool WIDE>
 __device__ __forceinline__ void dual_codes(Tile& t, const DualCtx& x, int64_t row0, int64_t col0)
 {
     float unused = 0.0f;
 #pragma unroll
-    for (int i = 0; i < 8; ++i) row_line<true, ST_ROW>(t, i, x, row0, col0, unused);
+    for (int i = 0; i < 8; ++i) row_line<true, ST_ROW, WIDE>(t, i, x, row0, col0, unused);
     col_transform<false>(t, x.log2n_col, x.c8);
-    col_codes<ST_COL>(t, x, row0, col0);
+    col_codes<ST_COL, WIDE>(t, x, row0, col0);
 }
 
 // One launch covers up to kMaxBatch tensors: the workgroups of tensor k are
@@ -483,6 +511,7 @@ struct DualBatch {
 // its G), so that the short, arithmetic-heavy stochastic tensor shares a launch with
 // the long, memory-bound ones instead of running after them on a half-empty chip.
 constexpr int kRoundPerTensor = 4;
+constexpr int kRoundWide = 8;        // added to ROUND: codes of 5 to 8 bits, one per byte
 
 template <bool QUANT, int ROUND, bool N64, bool CONV>
 __device__ __forceinline__ void dual_block(const DualBatch& b, int k, float (*red)[2], float* lds)
@@ -514,7 +543,7 @@ __device__ __forceinline__ void dual_block(const DualBatch& b, int k, float (*re
         const Scaling s_row = load_scaling(q.meta_row, q.clip_row, q.b_row);
         const Scaling s_col = load_scaling(q.meta_col, q.clip_col, q.b_col);
         dual_set_scaling(x, q, s_row, s_col, local == 0);
-        if (live) dual_codes<(ROUND & 1) != 0, (ROUND & 2) != 0>(t, x, row0, col0);
+        if (live) dual_codes<(ROUND & 1) != 0, (ROUND & 2) != 0, (ROUND & kRoundWide) != 0>(t, x, row0, col0);
     } else {
         float amax_row = 0.0f, amax_col = 0.0f;
         if (live) dual_absmax(t, x, row0, col0, amax_row, amax_col);
@@ -530,11 +559,11 @@ __global__ __launch_bounds__(kThreads) void fwht_dual_kernel(DualBatch b)
 
     int k = 0;
     while (k + 1 < b.n && (int)blockIdx.x >= b.first[k + 1]) ++k;
-    if constexpr (ROUND == kRoundPerTensor) {
+    if constexpr ((ROUND & 7) == kRoundPerTensor) {
         // two complete bodies, chosen per workgroup: sharing anything between them
         // (one load, one setup) lets the compiler keep both paths' registers alive
-        if (b.t[k].st_row) dual_block<QUANT, 3, N64, CONV>(b, k, red, lds);
-        else dual_block<QUANT, 0, N64, CONV>(b, k, red, lds);
+        if (b.t[k].st_row) dual_block<QUANT, 3 | (ROUND & kRoundWide), N64, CONV>(b, k, red, lds);
+        else dual_block<QUANT, ROUND & kRoundWide, N64, CONV>(b, k, red, lds);
     } else {
         dual_block<QUANT, ROUND, N64, CONV>(b, k, red, lds);
     }
@@ -603,7 +632,8 @@ bool dual_conv_plan(DualArgs* q)
 bool quantize_dual_eligible(const DualArgs& q)
 {
     return (q.rows % kTile == 0) && (q.cols % kTile == 0) && q.log2n_row <= 6 && q.log2n_col <= 6 &&
-           q.b_row <= 4 && q.b_col <= 4 && (q.rows / kTile) * (q.cols / kTile) < ((int64_t)1 << 30);
+           q.b_row <= 8 && q.b_col <= 8 && (q.b_row <= 4) == (q.b_col <= 4) &&
+           (q.rows / kTile) * (q.cols / kTile) < ((int64_t)1 << 30);
 }
 
 // Pass 1 (both maxima) of n tensors in one launch; their calibration records must be zero.
@@ -629,11 +659,13 @@ hipError_t launch_dual_pass1(const DualArgs* qs, int n, hipStream_t stream)
 }
 
 // Whether the tensors can share a pass-2 launch: same rounding modes everywhere, or each
-// tensor nearest on both axes or stochastic on both.
+// tensor nearest on both axes or stochastic on both; and all of them with packed 4-bit
+// codes or all with a byte per code.
 bool dual_pass2_batchable(const DualArgs* qs, int n)
 {
     bool same = true, paired = true;
     for (int k = 0; k < n; ++k) {
+        if ((qs[k].b_row <= 4) != (qs[0].b_row <= 4)) return false;
         if (qs[k].st_row != qs[0].st_row || qs[k].st_col != qs[0].st_col) same = false;
         if (qs[k].st_row != qs[k].st_col) paired = false;
     }
@@ -661,11 +693,24 @@ hipError_t launch_dual_pass2(const DualArgs* qs, int n, hipStream_t stream)
         else if (n64) hipLaunchKernelGGL((fwht_dual_kernel<true, ROUND, true, false>), grid, block, 0, stream, b); \
         else hipLaunchKernelGGL((fwht_dual_kernel<true, ROUND, false, false>), grid, block, 0, stream, b); \
     } while (0)
-    if (!same) HDQT_LAUNCH_PASS2(kRoundPerTensor);
-    else if (qs[0].st_row && qs[0].st_col) HDQT_LAUNCH_PASS2(3);
-    else if (qs[0].st_row) HDQT_LAUNCH_PASS2(1);
-    else if (qs[0].st_col) HDQT_LAUNCH_PASS2(2);
-    else HDQT_LAUNCH_PASS2(0);
+    const int mode = !same ? kRoundPerTensor : (qs[0].st_row ? 1 : 0) | (qs[0].st_col ? 2 : 0);
+    if (qs[0].b_row > 4) {
+        switch (mode) {
+        case kRoundPerTensor: HDQT_LAUNCH_PASS2(kRoundPerTensor | kRoundWide); break;
+        case 3: HDQT_LAUNCH_PASS2(3 | kRoundWide); break;
+        case 1: HDQT_LAUNCH_PASS2(1 | kRoundWide); break;
+        case 2: HDQT_LAUNCH_PASS2(2 | kRoundWide); break;
+        default: HDQT_LAUNCH_PASS2(0 | kRoundWide); break;
+        }
+    } else {
+        switch (mode) {
+        case kRoundPerTensor: HDQT_LAUNCH_PASS2(kRoundPerTensor); break;
+        case 3: HDQT_LAUNCH_PASS2(3); break;
+        case 1: HDQT_LAUNCH_PASS2(1); break;
+        case 2: HDQT_LAUNCH_PASS2(2); break;
+        default: HDQT_LAUNCH_PASS2(0); break;
+        }
+    }
 #undef HDQT_LAUNCH_PASS2
     return hipGetLastError();
 }

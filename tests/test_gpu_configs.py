@@ -232,6 +232,46 @@ def test_layer_step_equals_three_matmuls(M, K, N, n, s, a):
     assert none is None and torch.equal(Zb, Z3) and torch.equal(dWb, dW3)
 
 
+@pytest.mark.parametrize("M,K,N,n,s,a,b", [
+    (512, 1152, 128, 64, 32, 12, 8),     # a byte per code: two-axis kernels and matrix-core matmul
+    (512, 1152, 128, 64, 32, 12, 5),
+    (8192, 576, 64, 64, 128, 16, 6),
+    (256, 128, 64, 16, 64, 32, 8),
+    (129, 33, 65, 64, 32, 16, 8),        # nothing aligned
+])
+def test_layer_step_byte_codes(M, K, N, n, s, a, b):
+    layer = workloads.fc_layer(M, K, N, seed=5)
+    X, W, G = dev(layer.X), dev(layer.W), dev(layer.G)
+    pf, pi, pw = _step_params(n, s, a, seed=43, b=b)
+    print(f"layer_step M={M} K={K} N={N} n={n} s={s} a={a} b={b}", flush=True)
+    Z, dX, dW, _ = B.layer_step(X, W, G, pf, pi, pw)
+    Z3, _, _ = B.gemm(FWD, X, W, M, K, N, pf)
+    dX3, _, _ = B.gemm(BWI, G, W, M, K, N, pi)
+    dW3, _, _ = B.gemm(BWW, X, G, M, K, N, pw)
+    torch.cuda.synchronize()
+    assert torch.equal(Z, Z3) and torch.equal(dX, dX3) and torch.equal(dW, dW3)
+
+
+@pytest.mark.parametrize("kind", [FWD, BWI, BWW])
+def test_resnet_conv_k1152_8bit_inputs(kind):
+    """The benchmark layer with 8-bit inputs and the accumulators that go with them (Fig. 4)."""
+    layer = workloads.resnet_conv_layer(256, 128, 128, 16, seed=0)
+    check_layer(kind, layer, 64, 8, [(32, 16), (128, 32)])
+
+
+def test_layer_step_resnet_conv_k1152_8bit_inputs():
+    layer = workloads.resnet_conv_layer(256, 128, 128, 16, seed=0)
+    M, K, N = layer.M, layer.K, layer.N
+    X, W, G = dev(layer.X), dev(layer.W), dev(layer.G)
+    pf, pi, pw = _step_params(64, 32, 16, seed=0, b=8)
+    Z3, _, _ = B.gemm(FWD, X, W, M, K, N, pf)
+    dX3, _, _ = B.gemm(BWI, G, W, M, K, N, pi)
+    dW3, _, _ = B.gemm(BWW, X, G, M, K, N, pw)
+    Z, dX, dW, _ = B.layer_step(X, W, G, pf, pi, pw)
+    torch.cuda.synchronize()
+    assert torch.equal(Z, Z3) and torch.equal(dX, dX3) and torch.equal(dW, dW3)
+
+
 def test_layer_step_resnet_conv_k1152():
     """The benchmark's step at full size, twice in the same workspace."""
     layer = workloads.resnet_conv_layer(256, 128, 128, 16, seed=0)

@@ -170,6 +170,65 @@ def test_gemm_codes_widths(bA, bB):
         check_gemm_codes(33, 47, 77, bA, bB, s, a, n=1, extreme=0.2)
 
 
+@pytest.mark.parametrize("bA,bB", [(8, 8), (5, 6), (6, 8), (7, 5)])
+def test_gemm_codes_byte_codes_matrix_path(bA, bB):
+    """Both operands with a byte per code, tiles that are multiples of 32: the matrix-core
+    kernel's instances for unpacked codes (whole stages when 128 divides s)."""
+    for s, a in ((32, 8), (32, 12), (64, 16), (96, 32), (128, 12), (128, 32), (256, 16), (384, 32)):
+        check_gemm_codes(200, 136, 768, bA, bB, s, a, n=64, extreme=0.3)
+    check_gemm_codes(128, 256, 64, bA, bB, 32, 12, n=64, extreme=0.2)      # one short stage
+    check_gemm_codes(1, 1, 4096, bA, bB, 32, 10, n=64, extreme=0.9)
+    # all codes at the negative end: the largest tile sums there are
+    D = 256
+    cA = np.full((130, D), -(1 << (bA - 1)), np.int8)
+    cB = np.full((70, D), -(1 << (bB - 1)), np.int8)
+    one = dev(np.array([1.0], np.float32))
+    for s, a in ((32, 32), (128, 32), (64, 16)):
+        out, acc = B.gemm_codes(dev(capi.pack_codes(cA, bA)), dev(capi.pack_codes(cB, bB)), bA, bB, one, one,
+                                D, 1, a, s)
+        assert np.array_equal(host(acc), capi.tiled_matmul(cA, cB, s, a))
+
+
+@pytest.mark.parametrize("bA,bB,accs", [
+    (4, 4, (9, 10, 11, 12, 13, 16)), (3, 4, (8, 9, 12)), (2, 3, (8, 10)), (4, 2, (11,)),
+    (5, 5, (10, 12, 14, 16)), (5, 6, (11, 12, 13)), (6, 6, (12, 15)), (7, 8, (15, 16)), (8, 8, (16,)),
+    (8, 5, (13, 14)),
+])
+def test_gemm_codes_saturation_through_int16(bA, bB, accs):
+    """Accumulators of bA + bB to 16 bits with tiles of 32 and 64: the operands are scaled on
+    their way to LDS so that the int16 conversion is the clamp.  Half the codes sit at the
+    ends of their range, so most tile sums saturate."""
+    for a in accs:
+        for s in (32, 64):
+            check_gemm_codes(200, 136, 768, bA, bB, s, a, n=64, extreme=0.5)
+            check_gemm_codes(130, 70, 64, bA, bB, s, a, n=64, extreme=0.9)
+            check_gemm_codes(96, 40, 96, bA, bB, s, a, n=32, extreme=0.05)
+    # every code at the negative end, every code at the positive end, and mixed signs
+    D = 256
+    lo = lambda b: -(1 << (b - 1))
+    hi = lambda b: (1 << (b - 1)) - 1
+    one = dev(np.array([1.0], np.float32))
+    for va, vb in ((lo(bA), lo(bB)), (hi(bA), hi(bB)), (lo(bA), hi(bB)), (hi(bA), lo(bB))):
+        cA = np.full((64, D), va, np.int8)
+        cB = np.full((64, D), vb, np.int8)
+        for s in (32, 64):
+            out, acc = B.gemm_codes(dev(capi.pack_codes(cA, bA)), dev(capi.pack_codes(cB, bB)), bA, bB,
+                                    one, one, D, 1, accs[0], s)
+            assert np.array_equal(host(acc), capi.tiled_matmul(cA, cB, s, accs[0])), (va, vb, s)
+
+
+def test_gemm_codes_saturation_through_int16_split_contraction():
+    check_gemm_codes(128, 128, 16384, 4, 4, 32, 12, n=64, extreme=0.6)
+    check_gemm_codes(100, 60, 8192 + 64, 8, 8, 64, 16, n=64, extreme=0.5)
+    check_gemm_codes(64, 64, 4096 + 32, 5, 6, 32, 11, n=32, extreme=0.5)
+
+
+def test_gemm_codes_byte_codes_split_contraction():
+    check_gemm_codes(128, 128, 16384, 8, 8, 32, 12, n=64, extreme=0.1)
+    check_gemm_codes(100, 60, 8192 + 64, 8, 6, 128, 16, n=64, extreme=0.5)
+    check_gemm_codes(64, 64, 4096, 5, 8, 64, 32, n=64, extreme=0.5)
+
+
 def test_gemm_codes_split_contraction():
     # few output tiles and a long contraction: several workgroups share a tile
     check_gemm_codes(128, 128, 16384, 4, 4, 32, 8, n=64, extreme=0.1)
@@ -265,6 +324,15 @@ def test_fc_layer_step(kind):
         check_whole_gemm(kind, layer, step_params(kind, 64, 10 ** 6, a=12, sr_x=True))
 
 
+@pytest.mark.parametrize("b,a", [(8, 16), (5, 12), (6, 12), (3, 8)])
+@pytest.mark.parametrize("kind", [B.GEMM_FWD, B.GEMM_BWD_INPUT, B.GEMM_BWD_WEIGHT])
+def test_fc_layer_step_other_input_widths(kind, b, a):
+    # input widths and accumulators of the paper's Fig. 4 ranges
+    layer = workloads.fc_layer(128, 256, 128, seed=1)
+    check_whole_gemm(kind, layer, step_params(kind, 64, 32, a=a, b=b))
+    check_whole_gemm(kind, layer, step_params(kind, 64, 128, a=a, b=b, sr_x=True))
+
+
 @pytest.mark.parametrize("kind", [B.GEMM_FWD, B.GEMM_BWD_INPUT, B.GEMM_BWD_WEIGHT])
 def test_har_conv_layer_step(kind):
     layer = workloads.har_conv_layer(seed=0)
@@ -309,6 +377,19 @@ def test_quantize_dual(rows, cols, n):
     check_quantize_dual(T, n, B.Operand(4, ST, 1.0, 3), B.Operand(4, ST, 1.0, 4), seed=77)
     check_quantize_dual(T, n, B.Operand(4, NE, 0.975, 5), B.Operand(3, ST, 1.0, 6), seed=5)
     check_quantize_dual(T, n, B.Operand(2, ST, 1.0, 7), B.Operand(4, NE, 1.0, 8), seed=6)
+
+
+@pytest.mark.parametrize("rows,cols,n", [(64, 64, 64), (128, 192, 64), (256, 64, 16), (512, 1152, 64),
+                                         (192, 64, 1), (64, 256, 32)])
+def test_quantize_dual_byte_codes(rows, cols, n):
+    """Both axes with 5 to 8 bits: the two-axis kernels' instances that write a byte per code."""
+    rng = np.random.default_rng(rows * 17 + cols)
+    T = (rng.standard_normal((rows, cols)) * 2.1).astype(np.float32)
+    NE, ST = B.ROUND_NEAREST, B.ROUND_STOCHASTIC
+    check_quantize_dual(T, n, B.Operand(8, NE, 1.0, 1), B.Operand(8, NE, 1.0, 2))
+    check_quantize_dual(T, n, B.Operand(8, ST, 1.0, 3), B.Operand(8, ST, 1.0, 4), seed=78)
+    check_quantize_dual(T, n, B.Operand(5, NE, 0.975, 5), B.Operand(8, ST, 1.0, 6), seed=5)
+    check_quantize_dual(T, n, B.Operand(6, ST, 1.0, 7), B.Operand(7, NE, 1.0, 8), seed=6)
 
 
 def test_quantize_dual_wider_codes_and_zero():
