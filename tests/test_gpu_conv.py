@@ -64,6 +64,25 @@ def test_quantize_dual_im2col(batch, C, H, W, kh, kw, n, rounding):
         assert np.array_equal(got, want), f"axis {axis}: {(got != want).sum()} code bytes differ"
 
 
+@pytest.mark.parametrize("batch,C,H,W,kh,kw,n", GEOMETRIES[:4])
+@pytest.mark.parametrize("b1,b0", [(8, 8), (5, 7)])
+def test_quantize_dual_im2col_byte_codes(batch, C, H, W, kh, kw, n, b1, b0):
+    """Codes of 5 to 8 bits from the activation: the byte-writing instances with the patch load."""
+    act = relu_act((batch, C, H, W), seed=batch * 999 + C + H * 5 + W)
+    X = unfold(act, kh, kw)
+    for r in (NE, ST):
+        op1, op0 = B.Operand(b1, r, 1.0, 3), B.Operand(b0, r, 0.975, 9)
+        c1, s1, c0, s0 = B.quantize_dual_im2col(act.to("cuda:0"), kh, kw, n, op1, op0, seed=6)
+        torch.cuda.synchronize()
+        for axis, got_c, got_s, op in ((1, c1, s1, op1), (0, c0, s0, op0)):
+            codes, scale, _ = capi.quantize(X.numpy(), axis, n, o_op(op), 6)
+            want = capi.pack_codes(codes, op.b)
+            got = got_c.cpu().numpy()
+            assert got.shape == want.shape
+            assert got_s.cpu().numpy()[0] == scale
+            assert np.array_equal(got, want), f"axis {axis}: {(got != want).sum()} code bytes differ"
+
+
 def test_unsupported_geometries_are_refused():
     op = B.Operand(4, NE, 1.0, 0)
     for shape, kh, kw in (((1, 64, 16, 16), 2, 2),        # even window
@@ -78,26 +97,27 @@ def test_unsupported_geometries_are_refused():
         assert e.value.code == -13, (shape, kh, kw, e.value.code)
 
 
-def step_params(layer_id=0, n=64, s=32, seed=0):
+def step_params(layer_id=0, n=64, s=32, seed=0, b=4, a=8):
     tid = lambda role, kind: 16 * layer_id + {"X": 0, "W": 1, "G": 2}[role] + 4 * kind
     F, I, Wk = B.GEMM_FWD, B.GEMM_BWD_INPUT, B.GEMM_BWD_WEIGHT
-    mk = lambda A, Bq: B.Params(had_block=n, acc_bits=8, s=s, seed=seed, A=A, B=Bq)
-    return (mk(B.Operand(4, NE, 1.0, tid("X", F)), B.Operand(4, NE, 1.0, tid("W", F))),
-            mk(B.Operand(4, ST, 1.0, tid("G", I)), B.Operand(4, NE, 1.0, tid("W", I))),
-            mk(B.Operand(4, NE, 1.0, tid("X", Wk)), B.Operand(4, ST, 1.0, tid("G", Wk))))
+    mk = lambda A, Bq: B.Params(had_block=n, acc_bits=a, s=s, seed=seed, A=A, B=Bq)
+    return (mk(B.Operand(b, NE, 1.0, tid("X", F)), B.Operand(b, NE, 1.0, tid("W", F))),
+            mk(B.Operand(b, ST, 1.0, tid("G", I)), B.Operand(b, NE, 1.0, tid("W", I))),
+            mk(B.Operand(b, NE, 1.0, tid("X", Wk)), B.Operand(b, ST, 1.0, tid("G", Wk))))
 
 
+@pytest.mark.parametrize("b,a", [(4, 8), (8, 16), (6, 12)])
 @pytest.mark.parametrize("batch,C,H,W,kh,kw,N", [(2, 64, 16, 16, 3, 3, 128), (4, 64, 1, 128, 1, 5, 64)])
-def test_conv_step_equals_layer_step_on_the_unfolded_activation(batch, C, H, W, kh, kw, N):
+def test_conv_step_equals_layer_step_on_the_unfolded_activation(batch, C, H, W, kh, kw, N, b, a):
     act = relu_act((batch, C, H, W), seed=11)
     X = unfold(act, kh, kw)
     M, K = X.shape
     g = torch.Generator().manual_seed(12)
     Wt = torch.randn((K, N), generator=g) * (2.0 / K) ** 0.5
     G = torch.randn((M, N), generator=g) * 1e-2
-    pf, pi, pw = step_params(layer_id=1, n=64 if K % 64 == 0 else 32)
+    pf, pi, pw = step_params(layer_id=1, n=64 if K % 64 == 0 else 32, b=b, a=a)
     d = lambda t: t.contiguous().to("cuda:0")
-    print(f"conv_step act {tuple(act.shape)} -> M={M} K={K} N={N}", flush=True)
+    print(f"conv_step act {tuple(act.shape)} -> M={M} K={K} N={N} b={b} a={a}", flush=True)
     Z, dX, dW, _ = B.conv_step(d(act), kh, kw, d(Wt), d(G), pf, pi, pw)
     Z2, dX2, dW2, _ = B.layer_step(d(X), d(Wt), d(G), pf, pi, pw)
     torch.cuda.synchronize()
