@@ -251,6 +251,8 @@ hdqt::GemmArgs plan_gemm(const void* qA, const void* qB, int bA, int bB, const f
     g.stream_out = (RA * RB * out_elem >= ((int64_t)128 << 20)) ? 1 : 0;
     g.splits = choose_splits(RA, RB, D, g.n_tiles);
     g.tiles_per_split = (g.n_tiles + g.splits - 1) / g.splits;
+    // (tiles of 16 codes: the matrix-core kernel loads 32 codes at a time, parts start on those)
+    if (g.s == 16 && g.splits > 1 && g.tiles_per_split % 2 != 0) ++g.tiles_per_split;
     g.splits = (int)((g.n_tiles + g.tiles_per_split - 1) / g.tiles_per_split);
     return g;
 }

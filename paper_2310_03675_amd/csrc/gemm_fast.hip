@@ -34,6 +34,7 @@ namespace hdqt {
 
 namespace {
 
+typedef int v2i __attribute__((ext_vector_type(2)));
 typedef int v4i __attribute__((ext_vector_type(4)));
 typedef int v16i __attribute__((ext_vector_type(16)));
 typedef short v2s __attribute__((ext_vector_type(2)));
@@ -50,7 +51,12 @@ constexpr int KSTEP = 32;             // codes per MFMA
 constexpr int kScaleShift = 8;        // both operands carry a factor 16
 
 enum Epilogue { EPI_GENERIC = 0, EPI_SAT8_S32 = 1, EPI_SAT8_S64 = 2, EPI_STAGES = 3, EPI_SAT16_S32 = 4,
-                EPI_SAT16_S64 = 5 };
+                EPI_SAT16_S64 = 5, EPI_SAT8_S16 = 6, EPI_SAT16_S16 = 7 };
+// The _S16 instances (tiles of 16 codes) split every 32-code step into two
+// v_mfma_i32_32x32x16_i8: the 16-byte LDS fragment of a lane already holds, in its low and
+// high halves, what that instruction wants from the lane for the first and the second tile
+// of the step (packed codes: even positions first, then odd ones; byte codes: the loader
+// stores the 8-byte quarters of a step in the order 0, 2, 1, 3).
 // EPI_SAT16: accumulators of a bits, bA + bB <= a <= 16, tiles of 32 or 64.  The operands go to
 // LDS scaled by 2^jA and 2^jB, jA + jB = 16 - a (a code of b bits times 2^(8-b) still fits a
 // byte), so a tile's sum arrives times 2^(16-a) and saturating it to int16 is the a-bit clamp,
@@ -170,8 +176,9 @@ __device__ __forceinline__ int clamp3(int v, int lo, int hi)
 template <int EPI, int KS, bool STREAM, int WAVES, bool BF16, bool FOLD, bool WIDE = false>
 __global__ __launch_bounds__(64 * WAVES, WAVES == 8 ? 4 : 2) void gemm_i4_kernel(GemmArgs g)
 {
-    constexpr bool kSat16 = (EPI == EPI_SAT16_S32 || EPI == EPI_SAT16_S64);
-    constexpr bool kSat8 = (EPI == EPI_SAT8_S32 || EPI == EPI_SAT8_S64);
+    constexpr bool kSat16 = (EPI == EPI_SAT16_S32 || EPI == EPI_SAT16_S64 || EPI == EPI_SAT16_S16);
+    constexpr bool kSat8 = (EPI == EPI_SAT8_S32 || EPI == EPI_SAT8_S64 || EPI == EPI_SAT8_S16);
+    constexpr bool kPairs16 = (EPI == EPI_SAT8_S16 || EPI == EPI_SAT16_S16);      // pairs of 16-code tiles
     constexpr bool kPairs32 = (EPI == EPI_SAT8_S32 || EPI == EPI_SAT16_S32);      // pairs of 32-code tiles
     constexpr bool kPairs64 = (EPI == EPI_SAT8_S64 || EPI == EPI_SAT16_S64);      // pairs of 64-code tiles
     static_assert(!WIDE || !kSat8, "the 8-bit clamp trick needs the factor 256 of the nibble unpack");
@@ -281,7 +288,16 @@ __global__ __launch_bounds__(64 * WAVES, WAVES == 8 ? 4 : 2) void gemm_i4_kernel
 #pragma unroll
         for (int i = 0; i < UNITS; ++i) {
             const int r = lrow + ROWS_PER_PASS * i;
-            if constexpr (WIDE) {
+            if constexpr (WIDE && kPairs16) {
+                // quarters 0, 2 | 1, 3 of the step: a lane's fragment then holds its share of
+                // the first 16 positions in its low half and of the second 16 in its high half
+                const uint4 a0 = scale_bytes(st.a[2 * i], g.jA), a1 = scale_bytes(st.a[2 * i + 1], g.jA);
+                const uint4 b0 = scale_bytes(st.b[2 * i], g.jB), b1 = scale_bytes(st.b[2 * i + 1], g.jB);
+                *reinterpret_cast<uint4*>(&As[buf][r][lks * KSTEP]) = make_uint4(a0.x, a0.y, a1.x, a1.y);
+                *reinterpret_cast<uint4*>(&As[buf][r][lks * KSTEP + 16]) = make_uint4(a0.z, a0.w, a1.z, a1.w);
+                *reinterpret_cast<uint4*>(&Bs[buf][r][lks * KSTEP]) = make_uint4(b0.x, b0.y, b1.x, b1.y);
+                *reinterpret_cast<uint4*>(&Bs[buf][r][lks * KSTEP + 16]) = make_uint4(b0.z, b0.w, b1.z, b1.w);
+            } else if constexpr (WIDE) {
 #pragma unroll
                 for (int hf = 0; hf < 2; ++hf) {
                     *reinterpret_cast<uint4*>(&As[buf][r][lks * KSTEP + 16 * hf]) =
@@ -300,7 +316,33 @@ __global__ __launch_bounds__(64 * WAVES, WAVES == 8 ? 4 : 2) void gemm_i4_kernel
         __syncthreads();
         fetch_next(st);
 
-        if (kPairs32 || kPairs64) {
+        if constexpr (kPairs16) {
+            // two tiles per step
+#pragma unroll
+            for (int ks = 0; ks < NSTEP; ++ks) {
+                v4i fa[2], fb[CS];
+#pragma unroll
+                for (int h = 0; h < 2; ++h) {
+                    fa[h] = frag(As[buf], wm * 64 + h * 32, ks);
+                    if (h < CS) fb[h] = frag(Bs[buf], wn * WCOLS + h * 32, ks);
+                }
+                auto half = [](const v4i& f, int hi) -> long {
+                    const v2i p = hi ? v2i{f.z, f.w} : v2i{f.x, f.y};
+                    return __builtin_bit_cast(long, p);
+                };
+#pragma unroll
+                for (int a = 0; a < 2; ++a)
+#pragma unroll
+                    for (int c = 0; c < CS; ++c) {
+                        const v16i p0 = __builtin_amdgcn_mfma_i32_32x32x16_i8(half(fa[a], 0), half(fb[c], 0), zero, 0, 0, 0);
+                        const v16i p1 = __builtin_amdgcn_mfma_i32_32x32x16_i8(half(fa[a], 1), half(fb[c], 1), zero, 0, 0, 0);
+#pragma unroll
+                        for (int r = 0; r < 16; ++r)
+                            total[a][c][r] = kSat16 ? add_sat16_pair(total[a][c][r], p0[r], p1[r], low_clear)
+                                                    : add_sat8_pair(total[a][c][r], p0[r], p1[r]);
+                    }
+            }
+        } else if (kPairs32 || kPairs64) {
             // two tiles per half stage (s = 32) or per stage (s = 64)
 #pragma unroll
             for (int pr = 0; pr < (kPairs32 ? NSTEP / 2 : 1); ++pr) {
@@ -618,13 +660,13 @@ __global__ __launch_bounds__(64 * WAVES, WAVES == 8 ? 4 : 2) void gemm_i4_kernel
     }
 }
 
-bool sat8_path(const GemmArgs& g) { return g.acc_hi == 127 && (g.s == 32 || g.s == 64); }
+bool sat8_path(const GemmArgs& g) { return g.acc_hi == 127 && (g.s == 16 || g.s == 32 || g.s == 64); }
 
 // Saturation through the int16 conversion (EPI_SAT16): accumulators of bA + bB to 16 bits,
 // tiles of 32 or 64 codes.  Fills in the operand factors when `plan` is given.
 bool sat16_path(const GemmArgs& g, GemmArgs* plan = nullptr)
 {
-    if ((g.s != 32 && g.s != 64) || g.fold || g.out_bf16 || g.acc_hi > 32767) return false;
+    if ((g.s != 16 && g.s != 32 && g.s != 64) || g.fold || g.out_bf16 || g.acc_hi > 32767) return false;
     if ((g.bA > 4) != (g.bB > 4)) return false;
     if (g.bA <= 4 && sat8_path(g)) return false;      // has its own, cheaper instances
     int a = 1;
@@ -686,8 +728,14 @@ bool gemm_fold_plan(GemmArgs* g, int64_t batch, int C, int H, int W, int kh, int
 bool gemm_fast_eligible(const GemmArgs& g)
 {
     if ((g.bA > 4) != (g.bB > 4)) return false;      // packed or bytes, the same on both sides
-    if (g.s % KSTEP != 0 || g.D % KSTEP != 0) return false;
+    if (g.D % KSTEP != 0) return false;
     if (g.RB > ((int64_t)1 << 21)) return false;     // 32-bit offsets inside an output tile
+    if (g.s == 16) {
+        // two tiles per 32-code step: saturating epilogues only, parts that start on a step
+        if (g.fold || g.out_bf16 || (g.splits > 1 && g.tiles_per_split % 2 != 0)) return false;
+        return sat16_path(g) || (g.bA <= 4 && sat8_path(g));
+    }
+    if (g.s % KSTEP != 0) return false;
     if (sat16_path(g)) return true;
     if (g.bA > 4) {
         // a byte per code: nothing is scaled; a tile's sum (|code| <= 128 on both sides) and
@@ -752,7 +800,11 @@ hipError_t launch_gemm_fast(const GemmArgs& g_in, hipStream_t stream)
         if (g.stream_out) hipLaunchKernelGGL((gemm_i4_kernel<EPI, KS_LONG, true, kWaves, false, false, WIDE>), grid, block, 0, stream, g); \
         else hipLaunchKernelGGL((gemm_i4_kernel<EPI, KS_LONG, false, kWaves, false, false, WIDE>), grid, block, 0, stream, g); \
     } while (0)
-    if (sat16) {
+    if (g.s == 16) {
+        if (!sat16) HDQT_LAUNCH_SAT16(EPI_SAT8_S16, false);
+        else if (wide) HDQT_LAUNCH_SAT16(EPI_SAT16_S16, true);
+        else HDQT_LAUNCH_SAT16(EPI_SAT16_S16, false);
+    } else if (sat16) {
         if (wide && g.s == 32) HDQT_LAUNCH_SAT16(EPI_SAT16_S32, true);
         else if (wide) HDQT_LAUNCH_SAT16(EPI_SAT16_S64, true);
         else if (g.s == 32) HDQT_LAUNCH_SAT16(EPI_SAT16_S32, false);

@@ -199,7 +199,7 @@ def test_gemm_codes_saturation_through_int16(bA, bB, accs):
     their way to LDS so that the int16 conversion is the clamp.  Half the codes sit at the
     ends of their range, so most tile sums saturate."""
     for a in accs:
-        for s in (32, 64):
+        for s in (16, 32, 64):
             check_gemm_codes(200, 136, 768, bA, bB, s, a, n=64, extreme=0.5)
             check_gemm_codes(130, 70, 64, bA, bB, s, a, n=64, extreme=0.9)
             check_gemm_codes(96, 40, 96, bA, bB, s, a, n=32, extreme=0.05)
@@ -211,10 +211,23 @@ def test_gemm_codes_saturation_through_int16(bA, bB, accs):
     for va, vb in ((lo(bA), lo(bB)), (hi(bA), hi(bB)), (lo(bA), hi(bB)), (hi(bA), lo(bB))):
         cA = np.full((64, D), va, np.int8)
         cB = np.full((64, D), vb, np.int8)
-        for s in (32, 64):
+        for s in (16, 32, 64):
             out, acc = B.gemm_codes(dev(capi.pack_codes(cA, bA)), dev(capi.pack_codes(cB, bB)), bA, bB,
                                     one, one, D, 1, accs[0], s)
             assert np.array_equal(host(acc), capi.tiled_matmul(cA, cB, s, accs[0])), (va, vb, s)
+
+
+def test_gemm_codes_tiles_of_16_codes():
+    """Two tiles per 32-code step of the matrix-core kernel, 8-bit and wider accumulators,
+    split contractions whose parts would start in the middle of a step."""
+    for a in (8, 9, 11):
+        check_gemm_codes(200, 136, 768, 4, 4, 16, a, n=16, extreme=0.4)
+        check_gemm_codes(70, 130, 32, 4, 4, 16, a, n=16, extreme=0.9)
+    check_gemm_codes(200, 136, 768, 3, 3, 16, 8, n=16, extreme=0.4)
+    check_gemm_codes(128, 128, 16384, 4, 4, 16, 8, n=64, extreme=0.4)
+    check_gemm_codes(64, 64, 4096 + 32, 4, 4, 16, 9, n=32, extreme=0.5)
+    check_gemm_codes(100, 60, 8192 + 64, 8, 8, 16, 16, n=64, extreme=0.5)
+    check_gemm_codes(64, 64, 16 * 31 * 8 + 32, 5, 5, 16, 12, n=32, extreme=0.5)
 
 
 def test_gemm_codes_saturation_through_int16_split_contraction():
