@@ -251,8 +251,14 @@ hdqt::GemmArgs plan_gemm(const void* qA, const void* qB, int bA, int bB, const f
     g.stream_out = (RA * RB * out_elem >= ((int64_t)128 << 20)) ? 1 : 0;
     g.splits = choose_splits(RA, RB, D, g.n_tiles);
     g.tiles_per_split = (g.n_tiles + g.splits - 1) / g.splits;
-    // (tiles of 16 codes: the matrix-core kernel loads 32 codes at a time, parts start on those)
-    if (g.s == 16 && g.splits > 1 && g.tiles_per_split % 2 != 0) ++g.tiles_per_split;
+    // Parts begin on a stage of the matrix-core kernel (128 codes) when the tile length
+    // divides one: every 16-byte load of a part then lies inside one 64-byte run of its row
+    // (measured on the benchmark layer's weight gradient: 37 -> 40 tiles per part, 35.7 ->
+    // 33.1 us), and a tile of 16 codes never starts in the middle of a 32-code step.
+    if (g.splits > 1 && g.s < 128 && 128 % g.s == 0) {
+        const int64_t q = 128 / g.s;
+        g.tiles_per_split = (g.tiles_per_split + q - 1) / q * q;
+    }
     g.splits = (int)((g.n_tiles + g.tiles_per_split - 1) / g.tiles_per_split);
     return g;
 }
