@@ -33,7 +33,7 @@ HBM_PEAK_GBPS = 8000.0          # MI355X HBM3E
 # kernel family runs on); bench.py cannot collect counters itself.
 MEASURED_TRAFFIC = {
     "fwht_dual_absmax_batch": 336.4e6, "fwht_dual_quant_batch": 421.7e6,
-    "gemm_i4_fwd": 74.4e6, "gemm_i4_bwd_input": 307.2e6, "gemm_i4_bwd_weight": 98.2e6,
+    "gemm_i4_fwd": 74.8e6, "gemm_i4_bwd_input": 307.4e6, "gemm_i4_bwd_weight": 77.6e6,
 }
 INT8_MFMA_PEAK_TOPS = 5000.0    # MI355X dense int8
 
