@@ -68,9 +68,9 @@ enum Epilogue { EPI_GENERIC = 0, EPI_SAT8_S32 = 1, EPI_SAT8_S64 = 2, EPI_STAGES 
 // tile ends are tested once per stage, so nothing branches between the MFMAs of a stage and
 // the fragment loads of its four steps can run ahead of them.
 
-template <int UNITS>
+template <int UNITS_A, int UNITS_B>
 struct Staged {
-    uint4 a[UNITS], b[UNITS];         // (row, k-step) units per operand per thread
+    uint4 a[UNITS_A], b[UNITS_B];     // (row, k-step) units per operand per thread
 };
 
 __device__ __forceinline__ uint4 load_unit(const uint8_t* q, int64_t pitch, int64_t R, int64_t row,
@@ -173,9 +173,17 @@ __device__ __forceinline__ int clamp3(int v, int lo, int hi)
 // flight.  With gridDim.z = 1 a workgroup walks along a
 // whole row strip of the output, which is how short contractions (one or two
 // stages per tile) keep loads, MFMAs and stores overlapped.
-template <int EPI, int KS, bool STREAM, int WAVES, bool BF16, bool FOLD, bool WIDE = false>
+// NARROW: workgroup tile of 128 rows x 64 columns instead of 128 x 128, the eight waves four
+// high and two wide with one 32 x 32 block each, for outputs of at most 64 columns, which
+// would leave half of every 128-column tile -- half the MFMAs and half the tile sums -- to
+// nothing.
+template <int EPI, int KS, bool STREAM, int WAVES, bool BF16, bool FOLD, bool WIDE = false, bool NARROW = false>
 __global__ __launch_bounds__(64 * WAVES, WAVES == 8 ? 4 : 2) void gemm_i4_kernel(GemmArgs g)
 {
+    static_assert(!NARROW || (WAVES == 8 && !BF16 && !FOLD && !WIDE), "narrow tiles: plain packed instances only");
+    constexpr int TM = BM, TN = NARROW ? 64 : BN;   // the workgroup's tile
+    constexpr int RS = NARROW ? 1 : 2;              // 32-row MFMA blocks per wave
+    constexpr int WROWS = 32 * RS;
     constexpr bool kSat16 = (EPI == EPI_SAT16_S32 || EPI == EPI_SAT16_S64 || EPI == EPI_SAT16_S16);
     constexpr bool kSat8 = (EPI == EPI_SAT8_S32 || EPI == EPI_SAT8_S64 || EPI == EPI_SAT8_S16);
     constexpr bool kPairs16 = (EPI == EPI_SAT8_S16 || EPI == EPI_SAT16_S16);      // pairs of 16-code tiles
@@ -191,23 +199,24 @@ __global__ __launch_bounds__(64 * WAVES, WAVES == 8 ? 4 : 2) void gemm_i4_kernel
     // 64 rows x 32 columns (2 x 1 MFMA blocks): half the accumulators per wave, so four
     // waves fit a SIMD instead of two, at 1.5 LDS fragment reads per MFMA instead of 1.
     constexpr int NTHREADS = 64 * WAVES;
-    constexpr int WN = WAVES / 2;         // waves side by side
-    constexpr int CS = 4 / WN;            // 32-column MFMA blocks per wave: 2 or 1
+    constexpr int WN = NARROW ? 2 : WAVES / 2;      // waves side by side
+    constexpr int CS = NARROW ? 1 : 4 / WN;         // 32-column MFMA blocks per wave: 2 or 1
     constexpr int WCOLS = 32 * CS;
     constexpr int NSTEP = KS / KSTEP;
     constexpr int LDP = KS + 16;          // LDS row pitch in bytes (int8 codes)
-    constexpr int UNITS = 128 * NSTEP / NTHREADS;   // 16-byte units per operand and thread
+    constexpr int UNITS = TM * NSTEP / NTHREADS;    // 16-byte units of A per thread
+    constexpr int UNITS_B = UNITS;                  // of B (narrow: only the threads of rows < TN)
     static_assert(!kPairs64 || KS == KS_LONG, "a pair of 64-code tiles is one long stage");
-    __shared__ __attribute__((aligned(16))) uint8_t As[2][BM][LDP];
-    __shared__ __attribute__((aligned(16))) uint8_t Bs[2][BN][LDP];
+    __shared__ __attribute__((aligned(16))) uint8_t As[2][TM][LDP];
+    __shared__ __attribute__((aligned(16))) uint8_t Bs[2][TN][LDP];
 
     const int tid = threadIdx.x;
     const int lane = tid & 63, wave = tid >> 6;
     const int wm = wave / WN, wn = wave % WN;
-    const int64_t row0 = (int64_t)blockIdx.y * BM;
+    const int64_t row0 = (int64_t)blockIdx.y * TM;
     // fold: a column tile is f_cg whole channels (f_cg * kh * kw <= 128 columns)
-    const int col_stride = FOLD ? g.f_cg * g.fkh * g.fkw : BN;
-    const int n_ct = FOLD ? (g.fC + g.f_cg - 1) / g.f_cg : (int)((g.RB + BN - 1) / BN);
+    const int col_stride = FOLD ? g.f_cg * g.fkh * g.fkw : TN;
+    const int n_ct = FOLD ? (g.fC + g.f_cg - 1) / g.f_cg : (int)((g.RB + TN - 1) / TN);
     // fold, strip mode: row tile = f_rows_c image rows of one image starting (kh-1)/2 rows above
     // the rows it writes; rows outside the image are zero
     const int f_ph = FOLD ? (g.fkh - 1) / 2 : 0, f_pw = FOLD ? (g.fkw - 1) / 2 : 0;
@@ -234,10 +243,10 @@ __global__ __launch_bounds__(64 * WAVES, WAVES == 8 ? 4 : 2) void gemm_i4_kernel
     const int lrow = tid / NSTEP, lks = tid % NSTEP;
     constexpr int ROWS_PER_PASS = NTHREADS / NSTEP;
 
-    v16i total[2][CS];
-    v16i part[2][CS];                 // EPI_GENERIC only
+    v16i total[RS][CS];
+    v16i part[RS][CS];                // EPI_GENERIC only
 #pragma unroll
-    for (int a = 0; a < 2; ++a)
+    for (int a = 0; a < RS; ++a)
 #pragma unroll
         for (int c = 0; c < CS; ++c)
 #pragma unroll
@@ -248,7 +257,7 @@ __global__ __launch_bounds__(64 * WAVES, WAVES == 8 ? 4 : 2) void gemm_i4_kernel
     // ---- the load stream: position of the next stage to fetch
     int f_ct = blockIdx.z;
     int64_t f_k = k_begin;
-    auto fetch_next = [&](Staged<UNITS * REGS>& st) {
+    auto fetch_next = [&](Staged<UNITS * REGS, UNITS_B * REGS>& st) {
         if (f_ct >= n_ct) return;
         const int64_t col0 = (int64_t)f_ct * col_stride;
 #pragma unroll
@@ -262,7 +271,9 @@ __global__ __launch_bounds__(64 * WAVES, WAVES == 8 ? 4 : 2) void gemm_i4_kernel
                 }
             } else {
                 st.a[i] = load_unit(g.qA, g.pitchA, g.RA, a_row(r), f_k + lks * KSTEP, k_end);
-                st.b[i] = load_unit(g.qB, g.pitchB, g.RB, col0 + r, f_k + lks * KSTEP, k_end);
+                // (narrow: the threads of rows 64 .. 127 of the pass have no unit of B)
+                if (i < UNITS_B && (!NARROW || r < TN))
+                    st.b[i] = load_unit(g.qB, g.pitchB, g.RB, col0 + r, f_k + lks * KSTEP, k_end);
             }
         }
         f_k += KS;
@@ -273,7 +284,7 @@ __global__ __launch_bounds__(64 * WAVES, WAVES == 8 ? 4 : 2) void gemm_i4_kernel
     };
 
     // ---- the multiply stream
-    const int lane_row = wm * 64 + 4 * (lane >> 5), lane_col = wn * WCOLS + (lane & 31);
+    const int lane_row = wm * WROWS + 4 * (lane >> 5), lane_col = wn * WCOLS + (lane & 31);
     const uint32_t lane_off = (uint32_t)lane_row * (uint32_t)g.RB + (uint32_t)lane_col;
     int c_ct = blockIdx.z;
     int64_t c_k = k_begin;
@@ -284,7 +295,7 @@ __global__ __launch_bounds__(64 * WAVES, WAVES == 8 ? 4 : 2) void gemm_i4_kernel
     // Whole stages only: positions at or beyond k_end are zero in LDS and add nothing.
     // One barrier per stage is enough: buffer `buf` was last read two stages ago,
     // and every wave has passed the previous stage's barrier since.
-    auto stage = [&](Staged<UNITS * REGS>& st, const int buf) {
+    auto stage = [&](Staged<UNITS * REGS, UNITS_B * REGS>& st, const int buf) {
 #pragma unroll
         for (int i = 0; i < UNITS; ++i) {
             const int r = lrow + ROWS_PER_PASS * i;
@@ -307,10 +318,10 @@ __global__ __launch_bounds__(64 * WAVES, WAVES == 8 ? 4 : 2) void gemm_i4_kernel
                 }
             } else if constexpr (kSat16) {
                 store_unit_scaled(&As[buf][r][lks * KSTEP], st.a[i], g.jA);
-                store_unit_scaled(&Bs[buf][r][lks * KSTEP], st.b[i], g.jB);
+                if (i < UNITS_B && (!NARROW || r < TN)) store_unit_scaled(&Bs[buf][r][lks * KSTEP], st.b[i], g.jB);
             } else {
                 store_unit(&As[buf][r][lks * KSTEP], st.a[i]);
-                store_unit(&Bs[buf][r][lks * KSTEP], st.b[i]);
+                if (i < UNITS_B && (!NARROW || r < TN)) store_unit(&Bs[buf][r][lks * KSTEP], st.b[i]);
             }
         }
         __syncthreads();
@@ -320,10 +331,10 @@ __global__ __launch_bounds__(64 * WAVES, WAVES == 8 ? 4 : 2) void gemm_i4_kernel
             // two tiles per step
 #pragma unroll
             for (int ks = 0; ks < NSTEP; ++ks) {
-                v4i fa[2], fb[CS];
+                v4i fa[RS], fb[CS];
 #pragma unroll
-                for (int h = 0; h < 2; ++h) {
-                    fa[h] = frag(As[buf], wm * 64 + h * 32, ks);
+                for (int h = 0; h < RS; ++h) {
+                    fa[h] = frag(As[buf], wm * WROWS + h * 32, ks);
                     if (h < CS) fb[h] = frag(Bs[buf], wn * WCOLS + h * 32, ks);
                 }
                 auto half = [](const v4i& f, int hi) -> long {
@@ -331,7 +342,7 @@ __global__ __launch_bounds__(64 * WAVES, WAVES == 8 ? 4 : 2) void gemm_i4_kernel
                     return __builtin_bit_cast(long, p);
                 };
 #pragma unroll
-                for (int a = 0; a < 2; ++a)
+                for (int a = 0; a < RS; ++a)
 #pragma unroll
                     for (int c = 0; c < CS; ++c) {
                         const v16i p0 = __builtin_amdgcn_mfma_i32_32x32x16_i8(half(fa[a], 0), half(fb[c], 0), zero, 0, 0, 0);
@@ -347,16 +358,16 @@ __global__ __launch_bounds__(64 * WAVES, WAVES == 8 ? 4 : 2) void gemm_i4_kernel
 #pragma unroll
             for (int pr = 0; pr < (kPairs32 ? NSTEP / 2 : 1); ++pr) {
                 constexpr int SPT = kPairs32 ? 1 : 2;      // steps per tile
-                v4i fa[2 * SPT][2], fb[2 * SPT][CS];
+                v4i fa[2 * SPT][RS], fb[2 * SPT][CS];
 #pragma unroll
                 for (int q = 0; q < 2 * SPT; ++q)
 #pragma unroll
-                    for (int h = 0; h < 2; ++h) {
-                        fa[q][h] = frag(As[buf], wm * 64 + h * 32, pr * 2 * SPT + q);
+                    for (int h = 0; h < RS; ++h) {
+                        fa[q][h] = frag(As[buf], wm * WROWS + h * 32, pr * 2 * SPT + q);
                         if (h < CS) fb[q][h] = frag(Bs[buf], wn * WCOLS + h * 32, pr * 2 * SPT + q);
                     }
 #pragma unroll
-                for (int a = 0; a < 2; ++a)
+                for (int a = 0; a < RS; ++a)
 #pragma unroll
                     for (int c = 0; c < CS; ++c) {
                         v16i p0 = __builtin_amdgcn_mfma_i32_32x32x32_i8(fa[0][a], fb[0][c], zero, 0, 0, 0);
@@ -372,18 +383,18 @@ __global__ __launch_bounds__(64 * WAVES, WAVES == 8 ? 4 : 2) void gemm_i4_kernel
                     }
             }
         } else if (EPI == EPI_STAGES) {
-            v4i fa[NSTEP][2], fb[NSTEP][CS];
+            v4i fa[NSTEP][RS], fb[NSTEP][CS];
 #pragma unroll
             for (int ks = 0; ks < NSTEP; ++ks)
 #pragma unroll
-                for (int h = 0; h < 2; ++h) {
-                    fa[ks][h] = frag(As[buf], wm * 64 + h * 32, ks);
+                for (int h = 0; h < RS; ++h) {
+                    fa[ks][h] = frag(As[buf], wm * WROWS + h * 32, ks);
                     if (h < CS) fb[ks][h] = frag(Bs[buf], wn * WCOLS + h * 32, ks);
                 }
 #pragma unroll
             for (int ks = 0; ks < NSTEP; ++ks)
 #pragma unroll
-                for (int a = 0; a < 2; ++a)
+                for (int a = 0; a < RS; ++a)
 #pragma unroll
                     for (int c = 0; c < CS; ++c)
                         part[a][c] =
@@ -391,7 +402,7 @@ __global__ __launch_bounds__(64 * WAVES, WAVES == 8 ? 4 : 2) void gemm_i4_kernel
             // issue order: the fragments of step ks + 1 are requested before the MFMAs of step ks
             // (left alone, the scheduler puts every read right in front of its use to save
             // registers, and each MFMA pair then waits a whole LDS round trip)
-            constexpr int kReads = 2 + CS, kMfmas = 2 * CS;
+            constexpr int kReads = RS + CS, kMfmas = RS * CS;
             __builtin_amdgcn_sched_group_barrier(0x100, 2 * kReads, 0);
 #pragma unroll
             for (int ks = 0; ks < NSTEP; ++ks) {
@@ -402,7 +413,7 @@ __global__ __launch_bounds__(64 * WAVES, WAVES == 8 ? 4 : 2) void gemm_i4_kernel
             if (step_in_tile >= steps_per_tile) {
                 step_in_tile = 0;
 #pragma unroll
-                for (int a = 0; a < 2; ++a)
+                for (int a = 0; a < RS; ++a)
 #pragma unroll
                     for (int c = 0; c < CS; ++c)
 #pragma unroll
@@ -414,14 +425,14 @@ __global__ __launch_bounds__(64 * WAVES, WAVES == 8 ? 4 : 2) void gemm_i4_kernel
         } else {
 #pragma unroll
             for (int ks = 0; ks < NSTEP; ++ks) {
-                v4i fa[2], fb[CS];
+                v4i fa[RS], fb[CS];
 #pragma unroll
-                for (int h = 0; h < 2; ++h) {
-                    fa[h] = frag(As[buf], wm * 64 + h * 32, ks);
+                for (int h = 0; h < RS; ++h) {
+                    fa[h] = frag(As[buf], wm * WROWS + h * 32, ks);
                     if (h < CS) fb[h] = frag(Bs[buf], wn * WCOLS + h * 32, ks);
                 }
 #pragma unroll
-                for (int a = 0; a < 2; ++a)
+                for (int a = 0; a < RS; ++a)
 #pragma unroll
                     for (int c = 0; c < CS; ++c)
                         part[a][c] =
@@ -429,7 +440,7 @@ __global__ __launch_bounds__(64 * WAVES, WAVES == 8 ? 4 : 2) void gemm_i4_kernel
                 if (++step_in_tile == steps_per_tile) {
                     step_in_tile = 0;
 #pragma unroll
-                    for (int a = 0; a < 2; ++a)
+                    for (int a = 0; a < RS; ++a)
 #pragma unroll
                         for (int c = 0; c < CS; ++c)
 #pragma unroll
@@ -449,7 +460,7 @@ __global__ __launch_bounds__(64 * WAVES, WAVES == 8 ? 4 : 2) void gemm_i4_kernel
             // a short last tile (D not a multiple of s) ends without reaching steps_per_tile
             step_in_tile = 0;
 #pragma unroll
-            for (int a = 0; a < 2; ++a)
+            for (int a = 0; a < RS; ++a)
 #pragma unroll
                 for (int c = 0; c < CS; ++c)
 #pragma unroll
@@ -467,7 +478,7 @@ __global__ __launch_bounds__(64 * WAVES, WAVES == 8 ? 4 : 2) void gemm_i4_kernel
             int16_t* accT = reinterpret_cast<int16_t*>(&As[0][0][0]);
             __syncthreads();             // every wave is done reading this stage's operands
 #pragma unroll
-            for (int a = 0; a < 2; ++a)
+            for (int a = 0; a < RS; ++a)
 #pragma unroll
                 for (int c = 0; c < CS; ++c)
 #pragma unroll
@@ -547,9 +558,9 @@ __global__ __launch_bounds__(64 * WAVES, WAVES == 8 ? 4 : 2) void gemm_i4_kernel
         }
         // Element (a, c, r) of the lane lies at tile_off + (32a + 8(r/4) + r%4) RB + 32c
         // (uniform) + lane_off (per lane, 32 bits: RB <= 2^21 on this path).
-        const int64_t col0 = (int64_t)c_ct * BN;
+        const int64_t col0 = (int64_t)c_ct * TN;
         const int64_t tile_off = row0 * g.RB + col0;
-        const bool interior = (row0 + BM <= g.RA) && (col0 + BN <= g.RB);
+        const bool interior = (row0 + TM <= g.RA) && (col0 + TN <= g.RB);
         float* ob = (g.splits == 1 && g.out) ? g.out + tile_off : nullptr;
         // (the narrow output has kernel instances of its own: its epilogue costs the others registers)
         uint16_t* hb = (BF16 && g.splits == 1 && g.out_bf16) ? g.out_bf16 + tile_off : nullptr;
@@ -573,7 +584,7 @@ __global__ __launch_bounds__(64 * WAVES, WAVES == 8 ? 4 : 2) void gemm_i4_kernel
                 return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf2));
             };
 #pragma unroll
-            for (int a = 0; a < 2; ++a) {
+            for (int a = 0; a < RS; ++a) {
                 if constexpr (CS == 2) {
                     // 64 columns per wave: the even lanes store the pairs of the left 32-column
                     // block, the odd lanes those of the right one, so the 32 lanes that share a
@@ -607,7 +618,7 @@ __global__ __launch_bounds__(64 * WAVES, WAVES == 8 ? 4 : 2) void gemm_i4_kernel
             }
         }
 #pragma unroll
-        for (int a = 0; a < 2; ++a)
+        for (int a = 0; a < RS; ++a)
 #pragma unroll
             for (int c = 0; c < CS; ++c)
 #pragma unroll
@@ -641,7 +652,7 @@ __global__ __launch_bounds__(64 * WAVES, WAVES == 8 ? 4 : 2) void gemm_i4_kernel
     // (the fold epilogue needs the registers; with a byte per code a stage in flight is twice as many)
     constexpr bool kDeep = !kPairs64 && !FOLD && !WIDE;
     if constexpr (kDeep) {
-        Staged<UNITS * REGS> st0, st1;
+        Staged<UNITS * REGS, UNITS_B * REGS> st0, st1;
         fetch_next(st0);
         fetch_next(st1);
         while (c_ct < n_ct) {       // stage() advances c_ct at the end of a tile
@@ -650,7 +661,7 @@ __global__ __launch_bounds__(64 * WAVES, WAVES == 8 ? 4 : 2) void gemm_i4_kernel
             stage(st1, 1);
         }
     } else {
-        Staged<UNITS * REGS> st;
+        Staged<UNITS * REGS, UNITS_B * REGS> st;
         fetch_next(st);
         int buf = 0;
         while (c_ct < n_ct) {
@@ -755,6 +766,14 @@ bool gemm_fast_eligible(const GemmArgs& g)
     return per_tile * g.tiles_per_split < ((int64_t)1 << 22);
 }
 
+// Outputs of at most 64 columns take the 128 x 64 workgroup tile where such instances exist
+// (packed codes, fp32 / int32 output, the epilogues of the paper's settings).
+static bool narrow_tiles(const GemmArgs& g)
+{
+    if (g.RB > 64 || g.fold || g.out_bf16 || g.bA > 4 || g.s == 16) return false;
+    return !sat16_path(g);
+}
+
 hipError_t launch_gemm_fast(const GemmArgs& g_in, hipStream_t stream)
 {
     GemmArgs g = g_in;
@@ -764,7 +783,9 @@ hipError_t launch_gemm_fast(const GemmArgs& g_in, hipStream_t stream)
     g.acc_hi_scaled = hi > INT32_MAX ? INT32_MAX : (int)hi;
     // Short contractions (at most two stages per output tile): a workgroup walks along
     // its row strip of the output as long as that leaves about two workgroups per CU.
+    const bool narrow = narrow_tiles(g);
     int64_t n_ct = (g.RB + BN - 1) / BN, n_rt = (g.RA + BM - 1) / BM;
+    if (narrow) n_ct = (g.RB + 63) / 64;
     if (g.fold) {
         n_ct = (g.fC + g.f_cg - 1) / g.f_cg;
         n_rt = g.f_imgs ? (g.fbatch + g.f_imgs - 1) / g.f_imgs : g.fbatch * g.f_strips;
@@ -786,7 +807,10 @@ hipError_t launch_gemm_fast(const GemmArgs& g_in, hipStream_t stream)
         const dim3 block(64 * kWaves);                                                               \
         if (g.fold)                                                                                  \
             hipLaunchKernelGGL((gemm_i4_kernel<EPI, KS_LONG, false, kWaves, false, true>), grid, block, 0, stream, g); \
-        else if (g.out_bf16) {                                                                       \
+        else if (narrow) {                                                                           \
+            if (g.stream_out) hipLaunchKernelGGL((gemm_i4_kernel<EPI, KS_LONG, true, kWaves, false, false, false, true>), grid, block, 0, stream, g); \
+            else hipLaunchKernelGGL((gemm_i4_kernel<EPI, KS_LONG, false, kWaves, false, false, false, true>), grid, block, 0, stream, g); \
+        } else if (g.out_bf16) {                                                                     \
             if (g.stream_out) hipLaunchKernelGGL((gemm_i4_kernel<EPI, KS_LONG, true, kWaves, true, false>), grid, block, 0, stream, g); \
             else hipLaunchKernelGGL((gemm_i4_kernel<EPI, KS_LONG, false, kWaves, true, false>), grid, block, 0, stream, g); \
         } else if (g.stream_out)                                                                     \

@@ -217,6 +217,16 @@ def test_gemm_codes_saturation_through_int16(bA, bB, accs):
             assert np.array_equal(host(acc), capi.tiled_matmul(cA, cB, s, accs[0])), (va, vb, s)
 
 
+@pytest.mark.parametrize("RA,RB", [(300, 64), (128, 33), (1000, 1), (50, 60), (513, 64)])
+def test_gemm_codes_outputs_of_at_most_64_columns(RA, RB):
+    """The 128 x 64 workgroup tile: every epilogue that has such instances, ragged rows and
+    columns, one stage and many, a split contraction."""
+    for s, a in ((32, 8), (64, 8), (128, 8), (256, 16), (96, 6), (32, 32), (64, 7)):
+        check_gemm_codes(RA, RB, 768, 4, 4, s, a, n=64, extreme=0.4)
+    check_gemm_codes(RA, RB, 64, 4, 3, 32, 8, n=64, extreme=0.9)
+    check_gemm_codes(RA, RB, 16384 + 96, 4, 4, 32, 8, n=32, extreme=0.3)
+
+
 def test_gemm_codes_tiles_of_16_codes():
     """Two tiles per 32-code step of the matrix-core kernel, 8-bit and wider accumulators,
     split contractions whose parts would start in the middle of a step."""
