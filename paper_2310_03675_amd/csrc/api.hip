@@ -109,25 +109,33 @@ int hip_fail(hipError_t e)
     return HDQT_EHIP;
 }
 
-// How many workgroups share an output tile along the contraction.  The matmul
-// kernels keep two workgroups per CU resident (512 on the chip): the split fills
-// those places once and never spills a few workgroups into a second round.
 // Parts the contraction is split into when the output has too few tiles to fill the chip.
-// Every part writes an int32 slice of the output that a second pass reads back, so parts
-// are only worth their traffic while the slices cost no more than about twice what the
-// operands cost to read (a weight gradient: yes; a forward product with one workgroup per
-// CU: no).
+// The matmul kernels keep two workgroups per CU resident (512 on the chip); every part
+// writes an int32 slice of the output that a second pass reads back.  The number of parts is
+// the one a simple cost model likes best: the multiplication at the rate the kernels reach
+// on a full chip (0.8 POP/s on whole 128 x 128 tiles), slowed down in proportion when
+// fewer than 512 workgroups exist, plus one more launch and the slices written and read at
+// the 8 TB/s that data of this size gets from the caches.  (A weight gradient with nine
+// output tiles takes all the parts it can get; a forward product that already has one
+// workgroup per CU takes none; a 2048 x 4608 x 512 product with 64 tiles takes eight.)
 int choose_splits(int64_t RA, int64_t RB, int64_t D, int64_t n_tiles)
 {
     const int64_t blocks = ((RA + 127) / 128) * ((RB + 127) / 128);
-    if (blocks > 256 || n_tiles < 8) return 1;
-    int64_t want = 512 / blocks;
-    if (want > n_tiles / 4) want = n_tiles / 4;
-    if (want > 1024) want = 1024;
-    // slices: 4 * RA * RB bytes each, twice (written, read back); operands: about (RA + RB) * D / 2
-    const int64_t cap = ((RA + RB) * D) / (8 * RA * RB);
-    if (want > cap) want = cap;
-    return want < 1 ? 1 : (int)want;
+    if (blocks >= 512 || n_tiles < 8) return 1;
+    int64_t most = 512 / blocks;
+    if (most > n_tiles / 4) most = n_tiles / 4;
+    if (most > 1024) most = 1024;
+    const double ops = 2.0 * 128.0 * 128.0 * (double)blocks * (double)D;      // what the tiles cost, padding included
+    const double slice_us = 8.0 * (double)RA * (double)RB / 8.0e6;            // one slice, written and read
+    double best_t = 0.0;
+    int best = 1;
+    for (int64_t c = 1; c <= most; ++c) {
+        const double fill = (double)(blocks * c) / 512.0;
+        double t = ops / (0.8e9 * (fill < 1.0 ? fill : 1.0));
+        if (c > 1) t += 4.0 + slice_us * (double)c;
+        if (c == 1 || t < best_t) { best_t = t; best = (int)c; }
+    }
+    return best;
 }
 
 constexpr size_t kMetaBytes = (sizeof(hdqt::QMeta) + 255) / 256 * 256;
@@ -268,7 +276,13 @@ hdqt::GemmArgs plan_gemm(const void* qA, const void* qB, int bA, int bB, const f
 size_t partial_bytes(int64_t RA, int64_t RB, int64_t D, int64_t s)
 {
     const int64_t s_eff = s < D ? s : D;
-    const int splits = choose_splits(RA, RB, D, (D + s_eff - 1) / s_eff);
+    int splits = choose_splits(RA, RB, D, (D + s_eff - 1) / s_eff);
+    // plan_gemm may merge tiles into groups of 128 or 256 codes; whatever it decides fits
+    for (int64_t grp = 128; grp <= 256; grp *= 2)
+        if (s_eff < grp && grp % s_eff == 0 && grp <= D) {
+            const int alt = choose_splits(RA, RB, D, (D + grp - 1) / grp);
+            if (alt > splits) splits = alt;
+        }
     return splits > 1 ? (size_t)splits * (size_t)(RA * RB) * sizeof(int32_t) : 0;
 }
 

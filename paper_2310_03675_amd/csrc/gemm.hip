@@ -258,6 +258,49 @@ __global__ __launch_bounds__(256) void reduce_kernel(const int32_t* partial, int
     }
 }
 
+// The same for many slices: sixteen threads share an element (a group of VEC), each adds up
+// every sixteenth slice, and the first of them adds the sixteen sums from LDS.  A thread of
+// the kernel above walks all slices one after the other, which is latency, not bandwidth,
+// once there are more than a few dozen.
+template <int VEC>
+__global__ __launch_bounds__(256) void reduce_many_kernel(const int32_t* partial, int splits, int64_t count,
+                                                          const float* scaleA, const float* scaleB,
+                                                          float inv_n, float* out, uint16_t* out_bf16,
+                                                          int32_t* acc_out)
+{
+    constexpr int SG = 16, EPB = 256 / SG;      // slice groups, elements per block
+    __shared__ int red[SG][EPB][4];
+    const int el = threadIdx.x % EPB, sg = threadIdx.x / EPB;
+    const int64_t e = ((int64_t)blockIdx.x * EPB + el) * VEC;
+    int t[4] = {0, 0, 0, 0};
+    if (e < count) {
+        const int32_t* src = partial + (int64_t)sg * count + e;
+#pragma unroll 4
+        for (int z = sg; z < splits; z += SG, src += (int64_t)SG * count) {
+            if (VEC == 4) {
+                const int4 v = *reinterpret_cast<const int4*>(src);
+                t[0] += v.x; t[1] += v.y; t[2] += v.z; t[3] += v.w;
+            } else {
+                t[0] += src[0];
+            }
+        }
+    }
+#pragma unroll
+    for (int k = 0; k < 4; ++k) red[sg][el][k] = t[k];
+    __syncthreads();
+    if (sg != 0 || e >= count) return;
+    const float dq = (scaleA[0] * scaleB[0]) * inv_n;
+#pragma unroll
+    for (int k = 0; k < VEC; ++k) {
+        int sum = 0;
+#pragma unroll
+        for (int j = 0; j < SG; ++j) sum += red[j][el][k];
+        if (acc_out) acc_out[e + k] = sum;
+        if (out) out[e + k] = (float)sum * dq;
+        if (out_bf16) out_bf16[e + k] = (uint16_t)bf16_bits((float)sum * dq);
+    }
+}
+
 // Second reading, second step: Q with `a` bits on every tile's partial sums, with the
 // tile's own maximum, and the sum over tiles.  Per element e and tile t:
 //   inv_t = fl(2^(a-1) / m_t),  c = clamp(RNE(fl(float(P_t[e]) * inv_t))),  acc += c * m_t
@@ -312,6 +355,18 @@ hipError_t launch_reduce(const int32_t* partial, int splits, int64_t count, cons
                          int32_t* acc_out, hipStream_t stream)
 {
     const bool vec = (count % 4 == 0);
+    const int64_t groups = vec ? count / 4 : count;
+    if (splits >= 32 && (groups + 15) / 16 < ((int64_t)1 << 31)) {
+        ProfileScope ps(K_REDUCE, stream);
+        const dim3 grid((unsigned)((groups + 15) / 16));
+        if (vec)
+            hipLaunchKernelGGL(reduce_many_kernel<4>, grid, dim3(256), 0, stream, partial, splits, count, scaleA,
+                               scaleB, inv_n, out, out_bf16, acc_out);
+        else
+            hipLaunchKernelGGL(reduce_many_kernel<1>, grid, dim3(256), 0, stream, partial, splits, count, scaleA,
+                               scaleB, inv_n, out, out_bf16, acc_out);
+        return hipGetLastError();
+    }
     int64_t blocks = ((vec ? count / 4 : count) + 255) / 256;
     if (blocks > 4096) blocks = 4096;
     if (blocks < 1) blocks = 1;
