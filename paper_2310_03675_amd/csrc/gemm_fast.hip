@@ -709,7 +709,7 @@ bool gemm_fold_plan(GemmArgs* g, int64_t batch, int C, int H, int W, int kh, int
     if (g->RA != batch * (int64_t)H * W || g->RB != (int64_t)C * kh * kw) return false;
     g->splits = 1;                        // short contractions; the fold needs whole totals
     g->tiles_per_split = g->n_tiles;
-    if (batch * (int64_t)C * H * W >= ((int64_t)1 << 40) || false) return false;
+    if (batch * (int64_t)C * H * W >= ((int64_t)1 << 40)) return false;
     g->fold = 1;
     g->fbatch = batch; g->fC = C; g->fH = H; g->fW = W; g->fkh = kh; g->fkw = kw;
     g->f_log2w = log2i(W);
