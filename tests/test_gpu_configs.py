@@ -121,14 +121,19 @@ def test_square_4096_backward(kind):
     check_layer(kind, layer, 64, 4, [(64, 8), (256, 16)], sr=False)
 
 
-def test_square_8192_forward():
+@pytest.mark.parametrize("n", [64, 256])
+@pytest.mark.parametrize("b", [4, 8])
+def test_square_8192_forward_sweep(n, b):
     layer = workloads.square_layer(8192, seed=0)
-    check_layer(FWD, layer, 64, 4, [(64, 8), (16, 16)], sr=False)
+    check_layer(FWD, layer, n, b, [(s, a) for a in (8, 16) for s in (16, 64, 256)], sr=False)
 
 
-def test_square_16384_forward():
+@pytest.mark.parametrize("b", [4, 8])
+def test_square_16384_forward_sweep(b):
+    # (block order 256 at this size is left out: the oracle's O(n) work per element would keep
+    # one test silent for minutes; the 4096 and 8192 sweeps cover it)
     layer = workloads.square_layer(16384, seed=0)
-    check_layer(FWD, layer, 64, 4, [(64, 8)], sr=False)
+    check_layer(FWD, layer, 64, b, [(s, a) for a in (8, 16) for s in (16, 64, 256)], sr=False)
 
 
 # ---------------------------------------------------------------- ResNet-18 layer shapes, batch 128
