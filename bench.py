@@ -348,6 +348,30 @@ def main():
                 "us": us, "bound": "mfma", "achieved": tops, "peak": INT8_MFMA_PEAK_TOPS, "unit": "TOP/s",
                 "frac": tops / INT8_MFMA_PEAK_TOPS}
         del sq, qa, qb, o_sq, ws_sq
+        # and 8192^3, where the loop, not the tile boundaries, is what is measured:
+        # tiles of 64 with 8-bit accumulators and tiles of 256 with 16-bit ones
+        sq = workloads.square_layer(8192, seed=0)
+        qa, sa = B.quantize(sq.X.to(dev), 1, 64, opn, 0)
+        qb, sb = B.quantize(sq.W.to(dev), 0, 64, opn, 0)
+        o_sq = torch.empty((8192, 8192), dtype=torch.float32, device=dev)
+        line["gemm_square_8192"] = {}
+        for s_sq, a_sq in ((64, 8), (256, 16)):
+            for _ in range(2):
+                B.gemm_codes(qa, qb, 4, 4, sa, sb, 8192, 64, a_sq, s_sq, want_acc=False, out=o_sq)
+            torch.cuda.synchronize()
+            B.profile_enable(True)
+            B.profile_collect()
+            for _ in range(5):
+                B.gemm_codes(qa, qb, 4, 4, sa, sb, 8192, 64, a_sq, s_sq, want_acc=False, out=o_sq)
+            torch.cuda.synchronize()
+            B.profile_enable(False)
+            kg = B.profile_collect()
+            us = sum(v[1] for k_, v in kg.items() if k_.startswith("gemm")) * 1e3 / 5
+            tops = 2.0 * 8192.0 ** 3 / us / 1e6
+            line["gemm_square_8192"][f"s{s_sq}_a{a_sq}"] = {
+                "us": us, "bound": "mfma", "achieved": tops, "peak": INT8_MFMA_PEAK_TOPS, "unit": "TOP/s",
+                "frac": tops / INT8_MFMA_PEAK_TOPS}
+        del sq, qa, qb, o_sq
         # The input gradient with its output narrowed to bfloat16 (hdqt_gemm_codes_bf16 on the
         # layer's own codes): the fp32 matmul is bound by the 4*M*K bytes it writes, this one
         # writes half of them.  Not part of `value`: the step hands fp32 on, as the paper does.
