@@ -178,7 +178,8 @@ int hdqt_quantize_dual(const float *T, int64_t rows, int64_t cols, int had_block
  * kh*kw times smaller than X, and never need X in memory.
  * Taken: kh, kw odd (<= 15); width a power of two <= 64 with height*width a multiple of
  * 64, or width a multiple of 64; and what the two-axis kernels need of X (M and K
- * multiples of 64, block orders <= 64, codes of <= 4 bits).  Anything else:
+ * multiples of 64, block orders <= 64, both axes' codes of at most 4 bits or both of 5 to
+ * 8).  Anything else:
  * HDQT_EINVAL_GEOMETRY, and the caller unfolds the activation itself.
  */
 typedef struct {
