@@ -326,6 +326,10 @@ __global__ __launch_bounds__(64 * WAVES, WAVES == 8 ? 4 : 2) void gemm_i4_kernel
         }
         __syncthreads();
         fetch_next(st);
+        // Tiles of 16 and 32 codes: the waves that are multiplying and clamping go first
+        // (measured on 4096^3 with tiles of 32: 156 -> 146 us; nothing for tiles of 64, and
+        // the whole-stage loop loses 5 %, so it is left alone)
+        if constexpr (kPairs32 || kPairs16) __builtin_amdgcn_s_setprio(1);
 
         if constexpr (kPairs16) {
             // two tiles per step
@@ -452,6 +456,7 @@ __global__ __launch_bounds__(64 * WAVES, WAVES == 8 ? 4 : 2) void gemm_i4_kernel
             }
         }
 
+        if constexpr (kPairs32 || kPairs16) __builtin_amdgcn_s_setprio(0);
         c_k += KS;
         if (c_k < k_end) return;
 
