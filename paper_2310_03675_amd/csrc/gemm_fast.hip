@@ -73,19 +73,35 @@ struct Staged {
     uint4 a[UNITS_A], b[UNITS_B];     // (row, k-step) units per operand per thread
 };
 
-__device__ __forceinline__ uint4 load_unit(const uint8_t* q, int64_t pitch, int64_t R, int64_t row,
+// Operands are read through buffer descriptors that cover exactly their bytes: a unit that
+// lies outside (a row beyond the last one, a position beyond the part's end, a halo row of
+// the fold) is given an offset beyond the descriptor's range and comes back as zeros from
+// the hardware's range check.  No branch surrounds the load, so the compiler can count the
+// loads in flight: with the load inside an `if` it waited for all of them at the top of
+// every stage, the ones just issued for the stage after next included.
+typedef unsigned int u4v __attribute__((ext_vector_type(4)));
+constexpr uint32_t kOutside = 0x80000000u;      // operands are smaller than 2 GiB (gemm_fast_eligible)
+
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t operand_rsrc(const uint8_t* q, int64_t bytes)
+{
+    return __builtin_amdgcn_make_buffer_rsrc(const_cast<uint8_t*>(q), 0, (int)bytes, 0x00020000);
+}
+
+__device__ __forceinline__ uint4 load_unit(__amdgpu_buffer_rsrc_t rs, int64_t pitch, int64_t R, int64_t row,
                                            int64_t k, int64_t k_end)
 {
-    if (row >= 0 && row < R && k < k_end) return *reinterpret_cast<const uint4*>(q + row * pitch + (k >> 1));
-    return make_uint4(0u, 0u, 0u, 0u);
+    const bool ok = row >= 0 && row < R && k < k_end;
+    const uint32_t off = ok ? (uint32_t)(row * pitch + (k >> 1)) : kOutside;
+    return __builtin_bit_cast(uint4, __builtin_amdgcn_raw_buffer_load_b128(rs, off, 0, 0));
 }
 
 // a byte per code: the 32 codes of a unit are two of these, at byte offsets k and k + 16
-__device__ __forceinline__ uint4 load_unit_wide(const uint8_t* q, int64_t pitch, int64_t R, int64_t row,
+__device__ __forceinline__ uint4 load_unit_wide(__amdgpu_buffer_rsrc_t rs, int64_t pitch, int64_t R, int64_t row,
                                                 int64_t k, int64_t k_end, int half)
 {
-    if (row >= 0 && row < R && k < k_end) return *reinterpret_cast<const uint4*>(q + row * pitch + k + 16 * half);
-    return make_uint4(0u, 0u, 0u, 0u);
+    const bool ok = row >= 0 && row < R && k < k_end;
+    const uint32_t off = ok ? (uint32_t)(row * pitch + k + 16 * half) : kOutside;
+    return __builtin_bit_cast(uint4, __builtin_amdgcn_raw_buffer_load_b128(rs, off, 0, 0));
 }
 
 __device__ __forceinline__ void store_unit(uint8_t* lds_row_k, const uint4& w)
@@ -254,11 +270,16 @@ __global__ __launch_bounds__(64 * WAVES, WAVES == 8 ? 4 : 2) void gemm_i4_kernel
     const v16i zero = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
     const float dq = (g.scaleA[0] * g.scaleB[0]) * g.inv_n;
 
+    const __amdgpu_buffer_rsrc_t rsA = operand_rsrc(g.qA, g.RA * g.pitchA), rsB = operand_rsrc(g.qB, g.RB * g.pitchB);
+
     // ---- the load stream: position of the next stage to fetch
     int f_ct = blockIdx.z;
     int64_t f_k = k_begin;
     auto fetch_next = [&](Staged<UNITS * REGS, UNITS_B * REGS>& st) {
-        if (f_ct >= n_ct) return;
+        // (past the end of the stream the loads are still issued, with offsets outside the
+        // operands: the number of loads in flight then does not depend on the path taken, and
+        // the wait at the top of a stage can leave the newer stage's loads in flight)
+        const int64_t ke = f_ct < n_ct ? k_end : 0;
         const int64_t col0 = (int64_t)f_ct * col_stride;
 #pragma unroll
         for (int i = 0; i < UNITS; ++i) {
@@ -266,14 +287,15 @@ __global__ __launch_bounds__(64 * WAVES, WAVES == 8 ? 4 : 2) void gemm_i4_kernel
             if constexpr (WIDE) {
 #pragma unroll
                 for (int hf = 0; hf < 2; ++hf) {
-                    st.a[2 * i + hf] = load_unit_wide(g.qA, g.pitchA, g.RA, a_row(r), f_k + lks * KSTEP, k_end, hf);
-                    st.b[2 * i + hf] = load_unit_wide(g.qB, g.pitchB, g.RB, col0 + r, f_k + lks * KSTEP, k_end, hf);
+                    st.a[2 * i + hf] = load_unit_wide(rsA, g.pitchA, g.RA, a_row(r), f_k + lks * KSTEP, ke, hf);
+                    st.b[2 * i + hf] = load_unit_wide(rsB, g.pitchB, g.RB, col0 + r, f_k + lks * KSTEP, ke, hf);
                 }
             } else {
-                st.a[i] = load_unit(g.qA, g.pitchA, g.RA, a_row(r), f_k + lks * KSTEP, k_end);
-                // (narrow: the threads of rows 64 .. 127 of the pass have no unit of B)
-                if (i < UNITS_B && (!NARROW || r < TN))
-                    st.b[i] = load_unit(g.qB, g.pitchB, g.RB, col0 + r, f_k + lks * KSTEP, k_end);
+                st.a[i] = load_unit(rsA, g.pitchA, g.RA, a_row(r), f_k + lks * KSTEP, ke);
+                // (narrow: the threads of rows 64 .. 127 of the pass have no unit of B: row -1)
+                if (i < UNITS_B)
+                    st.b[i] = load_unit(rsB, g.pitchB, g.RB, (!NARROW || r < TN) ? col0 + r : -1,
+                                        f_k + lks * KSTEP, ke);
             }
         }
         f_k += KS;
@@ -746,6 +768,8 @@ bool gemm_fast_eligible(const GemmArgs& g)
     if ((g.bA > 4) != (g.bB > 4)) return false;      // packed or bytes, the same on both sides
     if (g.D % KSTEP != 0) return false;
     if (g.RB > ((int64_t)1 << 21)) return false;     // 32-bit offsets inside an output tile
+    // 32-bit offsets into the operands, with room for the "outside" offset
+    if ((g.RA + 256) * g.pitchA >= ((int64_t)1 << 31) || (g.RB + 256) * g.pitchB >= ((int64_t)1 << 31)) return false;
     if (g.s == 16) {
         // two tiles per 32-code step: saturating epilogues only, parts that start on a step
         if (g.fold || g.out_bf16 || (g.splits > 1 && g.tiles_per_split % 2 != 0)) return false;
