@@ -51,7 +51,9 @@ constexpr int KSTEP = 32;             // codes per MFMA
 constexpr int kScaleShift = 8;        // both operands carry a factor 16
 
 enum Epilogue { EPI_GENERIC = 0, EPI_SAT8_S32 = 1, EPI_SAT8_S64 = 2, EPI_STAGES = 3, EPI_SAT16_S32 = 4,
-                EPI_SAT16_S64 = 5, EPI_SAT8_S16 = 6, EPI_SAT16_S16 = 7 };
+                EPI_SAT16_S64 = 5, EPI_SAT8_S16 = 6, EPI_SAT16_S16 = 7, EPI_CLAMP_S16 = 8 };
+// EPI_CLAMP_S16: tiles of 16 codes with the compare-select clamp, for the accumulator widths
+// neither conversion trick covers (fewer bits than bA + bB).
 // The _S16 instances (tiles of 16 codes) split every 32-code step into two
 // v_mfma_i32_32x32x16_i8: the 16-byte LDS fragment of a lane already holds, in its low and
 // high halves, what that instruction wants from the lane for the first and the second tile
@@ -202,7 +204,7 @@ __global__ __launch_bounds__(64 * WAVES, WAVES == 8 ? 4 : 2) void gemm_i4_kernel
     constexpr int WROWS = 32 * RS;
     constexpr bool kSat16 = (EPI == EPI_SAT16_S32 || EPI == EPI_SAT16_S64 || EPI == EPI_SAT16_S16);
     constexpr bool kSat8 = (EPI == EPI_SAT8_S32 || EPI == EPI_SAT8_S64 || EPI == EPI_SAT8_S16);
-    constexpr bool kPairs16 = (EPI == EPI_SAT8_S16 || EPI == EPI_SAT16_S16);      // pairs of 16-code tiles
+    constexpr bool kPairs16 = (EPI == EPI_SAT8_S16 || EPI == EPI_SAT16_S16 || EPI == EPI_CLAMP_S16);      // pairs of 16-code tiles
     constexpr bool kPairs32 = (EPI == EPI_SAT8_S32 || EPI == EPI_SAT16_S32);      // pairs of 32-code tiles
     constexpr bool kPairs64 = (EPI == EPI_SAT8_S64 || EPI == EPI_SAT16_S64);      // pairs of 64-code tiles
     static_assert(!WIDE || !kSat8, "the 8-bit clamp trick needs the factor 256 of the nibble unpack");
@@ -374,9 +376,13 @@ __global__ __launch_bounds__(64 * WAVES, WAVES == 8 ? 4 : 2) void gemm_i4_kernel
                         const v16i p0 = __builtin_amdgcn_mfma_i32_32x32x16_i8(half(fa[a], 0), half(fb[c], 0), zero, 0, 0, 0);
                         const v16i p1 = __builtin_amdgcn_mfma_i32_32x32x16_i8(half(fa[a], 1), half(fb[c], 1), zero, 0, 0, 0);
 #pragma unroll
-                        for (int r = 0; r < 16; ++r)
-                            total[a][c][r] = kSat16 ? add_sat16_pair(total[a][c][r], p0[r], p1[r], low_clear)
-                                                    : add_sat8_pair(total[a][c][r], p0[r], p1[r]);
+                        for (int r = 0; r < 16; ++r) {
+                            if constexpr (EPI == EPI_CLAMP_S16)
+                                total[a][c][r] += clamp3(p0[r], lo, hi) + clamp3(p1[r], lo, hi);
+                            else
+                                total[a][c][r] = kSat16 ? add_sat16_pair(total[a][c][r], p0[r], p1[r], low_clear)
+                                                        : add_sat8_pair(total[a][c][r], p0[r], p1[r]);
+                        }
                     }
             }
         } else if (kPairs32 || kPairs64) {
@@ -773,7 +779,12 @@ bool gemm_fast_eligible(const GemmArgs& g)
     if (g.s == 16) {
         // two tiles per 32-code step: saturating epilogues only, parts that start on a step
         if (g.fold || g.out_bf16 || (g.splits > 1 && g.tiles_per_split % 2 != 0)) return false;
-        return sat16_path(g) || (g.bA <= 4 && sat8_path(g));
+        if (sat16_path(g) || (g.bA <= 4 && sat8_path(g))) return true;
+        // compare-select clamp: totals (times 256 with packed codes) must stay inside int32
+        const int64_t max_prod = ((int64_t)1 << (g.bA - 1)) * ((int64_t)1 << (g.bB - 1));
+        const int64_t tile_max = 16 * max_prod, acc_max = (int64_t)g.acc_hi + 1;
+        const int64_t per_tile = tile_max < acc_max ? tile_max : acc_max;
+        return per_tile * g.tiles_per_split < ((int64_t)1 << (g.bA > 4 ? 31 : 22));
     }
     if (g.s % KSTEP != 0) return false;
     if (sat16_path(g)) return true;
@@ -854,9 +865,11 @@ hipError_t launch_gemm_fast(const GemmArgs& g_in, hipStream_t stream)
         else hipLaunchKernelGGL((gemm_i4_kernel<EPI, KS_LONG, false, kWaves, false, false, WIDE>), grid, block, 0, stream, g); \
     } while (0)
     if (g.s == 16) {
-        if (!sat16) HDQT_LAUNCH_SAT16(EPI_SAT8_S16, false);
-        else if (wide) HDQT_LAUNCH_SAT16(EPI_SAT16_S16, true);
-        else HDQT_LAUNCH_SAT16(EPI_SAT16_S16, false);
+        if (sat16 && wide) HDQT_LAUNCH_SAT16(EPI_SAT16_S16, true);
+        else if (sat16) HDQT_LAUNCH_SAT16(EPI_SAT16_S16, false);
+        else if (!wide && sat8_path(g)) HDQT_LAUNCH_SAT16(EPI_SAT8_S16, false);
+        else if (wide) HDQT_LAUNCH_SAT16(EPI_CLAMP_S16, true);
+        else HDQT_LAUNCH_SAT16(EPI_CLAMP_S16, false);
     } else if (sat16) {
         if (wide && g.s == 32) HDQT_LAUNCH_SAT16(EPI_SAT16_S32, true);
         else if (wide) HDQT_LAUNCH_SAT16(EPI_SAT16_S64, true);

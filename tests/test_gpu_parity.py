@@ -238,6 +238,12 @@ def test_gemm_codes_tiles_of_16_codes():
     check_gemm_codes(64, 64, 4096 + 32, 4, 4, 16, 9, n=32, extreme=0.5)
     check_gemm_codes(100, 60, 8192 + 64, 8, 8, 16, 16, n=64, extreme=0.5)
     check_gemm_codes(64, 64, 16 * 31 * 8 + 32, 5, 5, 16, 12, n=32, extreme=0.5)
+    # accumulators narrower than bA + bB bits: the compare-select clamp on the same loop
+    for bA, bB, a in ((4, 4, 6), (4, 3, 5), (8, 8, 8), (5, 8, 10), (8, 8, 12)):
+        check_gemm_codes(200, 136, 768, bA, bB, 16, a, n=16, extreme=0.4)
+        check_gemm_codes(70, 130, 32, bA, bB, 16, a, n=16, extreme=0.9)
+    check_gemm_codes(128, 128, 16384, 8, 8, 16, 8, n=64, extreme=0.4)
+    check_gemm_codes(64, 64, 4096 + 32, 4, 4, 16, 6, n=32, extreme=0.5)
 
 
 def test_gemm_codes_saturation_through_int16_split_contraction():
