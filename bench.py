@@ -36,6 +36,11 @@ MEASURED_TRAFFIC = {
     "gemm_i4_fwd": 74.8e6, "gemm_i4_bwd_input": 307.4e6, "gemm_i4_bwd_weight": 77.6e6,
 }
 INT8_MFMA_PEAK_TOPS = 5000.0    # MI355X dense int8
+# Wave-wide vector-ALU instructions per launch of the two quantizer kernels on this workload
+# (rocprofv3 --pmc SQ_INSTS_VALU, profiles/bench_resnet_k1152_valu_issue.md), and the chip's
+# issue peak: one such instruction per SIMD every four cycles, 256 CUs x 4 SIMDs x 2.4 GHz / 4.
+MEASURED_VALU_INSTS = {"fwht_dual_absmax_batch": 21.00e6, "fwht_dual_quant_batch": 40.78e6}
+VALU_ISSUE_PEAK = 256 * 4 * 2.4e9 / 4
 
 WORKLOADS = {
     # name: (constructor kwargs, Hadamard block)
@@ -256,6 +261,13 @@ def main():
             roof_all[name] = {"bound": "hbm", "achieved": gbps, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                               "frac": gbps / HBM_PEAK_GBPS, "traffic": measured.get(name),
                               "algorithmic_bytes_per_launch": bytes_launch}
+            if measured and name in MEASURED_VALU_INSTS:
+                # the same kernel against the vector ALU's instruction issue rate: pass 2 is
+                # limited by it as much as by memory
+                rate = MEASURED_VALU_INSTS[name] / avg_s
+                roof_all[name]["valu_issue"] = {"wave_instructions_per_launch": MEASURED_VALU_INSTS[name],
+                                                "achieved": rate / 1e9, "peak": VALU_ISSUE_PEAK / 1e9,
+                                                "unit": "G wave-instructions/s", "frac": rate / VALU_ISSUE_PEAK}
         elif name.startswith("gemm_i4_"):
             which = name[len("gemm_i4_"):]
             tops = ops_step / 3 / avg_s / 1e12
