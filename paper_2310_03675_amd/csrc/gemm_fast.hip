@@ -200,7 +200,13 @@ __global__ __launch_bounds__(64 * WAVES, WAVES == 8 ? 4 : 2) void gemm_i4_kernel
 {
     static_assert(!NARROW || (WAVES == 8 && !BF16 && !FOLD && !WIDE), "narrow tiles: plain packed instances only");
     constexpr int TM = BM, TN = NARROW ? 64 : BN;   // the workgroup's tile
-    constexpr int RS = NARROW ? 1 : 2;              // 32-row MFMA blocks per wave
+    // ROWWIDE (streamed outputs, i.e. at least 128 MB): a wave is one block high and two wide
+    // instead of two high and one wide, so that its two stores of a row are neighbours (256
+    // bytes; streaming stores of 256-byte pieces reach 5.0 TB/s where 128-byte pieces reach
+    // 4.6).  Same fragment reads per MFMA.  The benchmark layer's input gradient inside the
+    // step: 73.3 -> 70.6 us; its bfloat16 variant 57.7 -> 55.4 us.
+    constexpr bool ROWWIDE = STREAM && !NARROW && !FOLD && WAVES == 8;
+    constexpr int RS = (NARROW || ROWWIDE) ? 1 : 2; // 32-row MFMA blocks per wave
     constexpr int WROWS = 32 * RS;
     constexpr bool kSat16 = (EPI == EPI_SAT16_S32 || EPI == EPI_SAT16_S64 || EPI == EPI_SAT16_S16);
     constexpr bool kSat8 = (EPI == EPI_SAT8_S32 || EPI == EPI_SAT8_S64 || EPI == EPI_SAT8_S16);
@@ -217,8 +223,9 @@ __global__ __launch_bounds__(64 * WAVES, WAVES == 8 ? 4 : 2) void gemm_i4_kernel
     // 64 rows x 32 columns (2 x 1 MFMA blocks): half the accumulators per wave, so four
     // waves fit a SIMD instead of two, at 1.5 LDS fragment reads per MFMA instead of 1.
     constexpr int NTHREADS = 64 * WAVES;
-    constexpr int WN = NARROW ? 2 : WAVES / 2;      // waves side by side
+    constexpr int WN = (NARROW || ROWWIDE) ? 2 : WAVES / 2;      // waves side by side
     constexpr int CS = NARROW ? 1 : 4 / WN;         // 32-column MFMA blocks per wave: 2 or 1
+    constexpr int HS = RS > CS ? RS : CS;
     constexpr int WCOLS = 32 * CS;
     constexpr int NSTEP = KS / KSTEP;
     constexpr int LDP = KS + 16;          // LDS row pitch in bytes (int8 codes)
@@ -361,8 +368,8 @@ __global__ __launch_bounds__(64 * WAVES, WAVES == 8 ? 4 : 2) void gemm_i4_kernel
             for (int ks = 0; ks < NSTEP; ++ks) {
                 v4i fa[RS], fb[CS];
 #pragma unroll
-                for (int h = 0; h < RS; ++h) {
-                    fa[h] = frag(As[buf], wm * WROWS + h * 32, ks);
+                for (int h = 0; h < HS; ++h) {
+                    if (h < RS) fa[h] = frag(As[buf], wm * WROWS + h * 32, ks);
                     if (h < CS) fb[h] = frag(Bs[buf], wn * WCOLS + h * 32, ks);
                 }
                 auto half = [](const v4i& f, int hi) -> long {
@@ -394,8 +401,8 @@ __global__ __launch_bounds__(64 * WAVES, WAVES == 8 ? 4 : 2) void gemm_i4_kernel
 #pragma unroll
                 for (int q = 0; q < 2 * SPT; ++q)
 #pragma unroll
-                    for (int h = 0; h < RS; ++h) {
-                        fa[q][h] = frag(As[buf], wm * WROWS + h * 32, pr * 2 * SPT + q);
+                    for (int h = 0; h < HS; ++h) {
+                        if (h < RS) fa[q][h] = frag(As[buf], wm * WROWS + h * 32, pr * 2 * SPT + q);
                         if (h < CS) fb[q][h] = frag(Bs[buf], wn * WCOLS + h * 32, pr * 2 * SPT + q);
                     }
 #pragma unroll
@@ -419,8 +426,8 @@ __global__ __launch_bounds__(64 * WAVES, WAVES == 8 ? 4 : 2) void gemm_i4_kernel
 #pragma unroll
             for (int ks = 0; ks < NSTEP; ++ks)
 #pragma unroll
-                for (int h = 0; h < RS; ++h) {
-                    fa[ks][h] = frag(As[buf], wm * WROWS + h * 32, ks);
+                for (int h = 0; h < HS; ++h) {
+                    if (h < RS) fa[ks][h] = frag(As[buf], wm * WROWS + h * 32, ks);
                     if (h < CS) fb[ks][h] = frag(Bs[buf], wn * WCOLS + h * 32, ks);
                 }
 #pragma unroll
@@ -459,8 +466,8 @@ __global__ __launch_bounds__(64 * WAVES, WAVES == 8 ? 4 : 2) void gemm_i4_kernel
             for (int ks = 0; ks < NSTEP; ++ks) {
                 v4i fa[RS], fb[CS];
 #pragma unroll
-                for (int h = 0; h < RS; ++h) {
-                    fa[h] = frag(As[buf], wm * WROWS + h * 32, ks);
+                for (int h = 0; h < HS; ++h) {
+                    if (h < RS) fa[h] = frag(As[buf], wm * WROWS + h * 32, ks);
                     if (h < CS) fb[h] = frag(Bs[buf], wn * WCOLS + h * 32, ks);
                 }
 #pragma unroll
