@@ -106,9 +106,9 @@ typedef struct {
     int32_t n_eff;
 } hdqt_ws_layout_t;
 
-/* Block order used for a contraction of length D when n is requested: the
- * largest power of two <= n that divides D ("the highest k delivering a valid
- * block-diagonal matrix for the given dimension").  Host function. */
+/* Block order used for a contraction of length D when n is requested
+ * (Methodology, H = BlockDiag(H_k, ..., H_k): the blocks must tile D exactly):
+ * the largest power of two <= n that divides D.  Host function. */
 int hdqt_n_eff(int64_t D, int had_block);
 
 /* Row pitch in bytes of packed codes: ceil(D/2) for b <= 4, D for b > 4. */
@@ -268,8 +268,12 @@ int hdqt_gemm_requant(int gemm_kind, const float *P, const float *Q, float *out,
                       void *workspace, size_t workspace_bytes, void *stream);
 
 /*
- * The three matmuls of a training step.  X, W, G, the outputs: fp32 device
- * tensors with the shapes at the top of this file.  `acc_out` (nullable)
+ * The three matmuls of a training step (Methodology, problem statement Z = X W "needed
+ * in the forward and the backward pass": forward Z = X W, input gradient dX = G W^T,
+ * weight gradient dW = X^T G; each with both operands in the Hadamard domain of its
+ * contraction dimension, quantized by Q, multiplied in tiles of size s with a-bit
+ * accumulators -- Experiments: 4-bit inputs, 8-bit accumulators, tile 32).  X, W, G, the
+ * outputs: fp32 device tensors with the shapes at the top of this file.  `acc_out` (nullable)
  * receives the int32 accumulators of the output's shape.  `params` is a host
  * pointer.  Workspace: hdqt_workspace_size(kind, ...) bytes.
  */
@@ -411,7 +415,9 @@ int hdqt_layer_bwd(const float *G, const float *W, const void *saved, float *dX,
  * hdqt_profile_collect waits for all recorded events, writes one row per
  * kernel that ran (name, number of launches, summed elapsed milliseconds) into
  * rows[0 .. max_rows) (host memory), clears the record and returns the number
- * of kernels that ran.  Not for use under graph capture.
+ * of kernels that ran.  Not for use under graph capture.  The switch and the record are
+ * process-wide: while it is on, launches from every thread and stream are recorded, and
+ * one collect returns them all (thread-safe, but two threads' launches are not kept apart).
  */
 typedef struct {
     char name[48];

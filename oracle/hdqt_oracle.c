@@ -81,9 +81,9 @@ void orc_hadamard_matrix(int k, int8_t *H)
     }
 }
 
-/* "the highest k is chosen to deliver a valid block-diagonal matrix for the
- * given tensor dimension": the block order actually used is the requested
- * order n, lowered to the largest power of two that divides D. */
+/* Block order (Methodology, block-diagonal H = BlockDiag(H_k, ..., H_k)): the
+ * blocks must tile the contraction length exactly, so the order actually used
+ * is the requested order n lowered to the largest power of two dividing D. */
 int orc_n_eff(int64_t D, int n)
 {
     int m = 1;

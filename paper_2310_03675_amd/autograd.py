@@ -17,9 +17,12 @@ from . import binding as B
 
 @dataclass
 class LayerConfig:
-    """Quantization of one layer's three matmuls; defaults follow the paper's
-    backward-pass setting (4-bit codes, Hadamard block 64, stochastic rounding of
-    the gradient, 8-bit accumulators over tiles of 32)."""
+    """Quantization of one layer's three matmuls.  The defaults are the benchmark
+    configurations' setting: 4-bit codes, Hadamard block 64, 8-bit accumulators over
+    tiles of 32, the gradient G rounded stochastically in both backward matmuls and
+    everything else to nearest.  The paper's own backward setting (Methodology,
+    stochastic-rounding paragraph; Fig. 2 ablation) also rounds the activation
+    stochastically in the weight-gradient matmul: `stochastic_act=True`."""
     had_block: int = 64
     bits: int = 4
     acc_bits: int = 8
@@ -28,6 +31,7 @@ class LayerConfig:
     layer_id: int = 0
     clip_fwd: float = 1.0
     stochastic_grad: bool = True
+    stochastic_act: bool = False     # X in dW = X^T G rounded stochastically (the paper's setting)
     need_input_grad: bool = True
     fold_in_matmul: bool = True      # convolution layers: hdqt_conv_bwd where the geometry is taken
     # when set to a dict, every matmul of the layer leaves its operands and results there
@@ -44,7 +48,8 @@ class LayerConfig:
         elif kind == B.GEMM_BWD_INPUT:
             A, Bq = B.Operand(b, ST, 1.0, tid("G")), B.Operand(b, NE, 1.0, tid("W"))
         else:
-            A, Bq = B.Operand(b, NE, 1.0, tid("X")), B.Operand(b, ST, 1.0, tid("G"))
+            SA = B.ROUND_STOCHASTIC if self.stochastic_act else NE
+            A, Bq = B.Operand(b, SA, 1.0, tid("X")), B.Operand(b, ST, 1.0, tid("G"))
         # a fresh random stream every step: the seed advances with the step counter
         return B.Params(had_block=self.had_block, acc_bits=self.acc_bits, s=self.s,
                         seed=self.seed + step, A=A, B=Bq)

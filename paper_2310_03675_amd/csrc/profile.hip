@@ -4,10 +4,15 @@
 // bracketed by two events recorded on the launch stream; hdqt_profile_collect
 // waits for them, sums the elapsed times per kernel and clears the list.  This
 // is the only state the library keeps, and only while the caller asked for it.
+// The switch and the event lists are process-wide: launches from any thread and on any
+// stream are recorded while it is on (the lists are guarded by one mutex, the switch is
+// atomic), and hdqt_profile_collect returns all of them.  Turn it on around a region that
+// one thread controls; the events of two threads' launches are not kept apart.
 
 #include "../../include/hdqt.h"
 #include "common.hpp"
 
+#include <atomic>
 #include <mutex>
 #include <string.h>
 #include <vector>
@@ -17,7 +22,7 @@ namespace hdqt {
 namespace {
 struct Pending { int id; hipEvent_t start, stop; };
 std::mutex g_mu;
-bool g_enabled = false;
+std::atomic<bool> g_enabled{false};
 std::vector<Pending> g_pending;
 std::vector<Pending> g_open;     // begun, not yet ended (per launch, LIFO)
 } // namespace
@@ -34,13 +39,14 @@ const char* kernel_name(int id)
     return (id >= 0 && id < K_COUNT) ? names[id] : "?";
 }
 
-bool profiling_enabled() { return g_enabled; }
+bool profiling_enabled() { return g_enabled.load(std::memory_order_relaxed); }
 
 void profile_begin(int id, hipStream_t stream)
 {
     std::lock_guard<std::mutex> lock(g_mu);
     Pending p{id, nullptr, nullptr};
-    if (hipEventCreate(&p.start) != hipSuccess || hipEventCreate(&p.stop) != hipSuccess) return;
+    if (hipEventCreate(&p.start) != hipSuccess) return;
+    if (hipEventCreate(&p.stop) != hipSuccess) { (void)hipEventDestroy(p.start); return; }
     (void)hipEventRecord(p.start, stream);
     g_open.push_back(p);
 }
@@ -66,7 +72,7 @@ extern "C" {
 int hdqt_profile_enable(int on)
 {
     std::lock_guard<std::mutex> lock(hdqt::g_mu);
-    hdqt::g_enabled = (on != 0);
+    hdqt::g_enabled.store(on != 0, std::memory_order_relaxed);
     return HDQT_OK;
 }
 

@@ -128,12 +128,14 @@ def test_square_8192_forward_sweep(n, b):
     check_layer(FWD, layer, n, b, [(s, a) for a in (8, 16) for s in (16, 64, 256)], sr=False)
 
 
+@pytest.mark.parametrize("n", [64, 256])
 @pytest.mark.parametrize("b", [4, 8])
-def test_square_16384_forward_sweep(b):
-    # (block order 256 at this size is left out: the oracle's O(n) work per element would keep
-    # one test silent for minutes; the 4096 and 8192 sweeps cover it)
+def test_square_16384_forward_sweep(n, b):
+    # (block order 256: the oracle's plain O(n) work per element takes about a minute per
+    # operand at this size; it quantizes once per (operand, b) and the six accumulator
+    # settings reuse those codes)
     layer = workloads.square_layer(16384, seed=0)
-    check_layer(FWD, layer, 64, b, [(s, a) for a in (8, 16) for s in (16, 64, 256)], sr=False)
+    check_layer(FWD, layer, n, b, [(s, a) for a in (8, 16) for s in (16, 64, 256)], sr=False)
 
 
 # ---------------------------------------------------------------- ResNet-18 layer shapes, batch 128
@@ -291,6 +293,44 @@ def test_layer_step_resnet_conv_k1152():
         Z, dX, dW, ws = B.layer_step(X, W, G, pf, pi, pw, workspace=ws)
         torch.cuda.synchronize()
         assert torch.equal(Z, Z3) and torch.equal(dX, dX3) and torch.equal(dW, dW3)
+
+
+def _sample_positions(rng, RA, RB):
+    ii = rng.integers(0, RA, size=SAMPLES)
+    jj = rng.integers(0, RB, size=SAMPLES)
+    ii[:4] = [0, 0, RA - 1, RA - 1]
+    jj[:4] = [0, RB - 1, 0, RB - 1]
+    return ii, jj
+
+
+@pytest.mark.parametrize("s", [32, 64])
+def test_layer_step_resnet_conv_k1152_against_oracle(s):
+    """The entry point the benchmark times, at the benchmark's size and settings, against the
+    oracle directly: Z, dX and dW of one hdqt_layer_step call on 4096 sampled positions each
+    (corners included), the oracle quantizing every operand in its own Hadamard domain."""
+    layer = workloads.resnet_conv_layer(256, 128, 128, 16, seed=0)
+    M, K, N = layer.M, layer.K, layer.N
+    X, W, G = dev(layer.X), dev(layer.W), dev(layer.G)
+    params = _step_params(64, s, 8, seed=0)
+    Z, dX, dW, _ = B.layer_step(X, W, G, *params)
+    torch.cuda.synchronize()
+    rng = np.random.default_rng(99)
+    for kind, got_t in ((FWD, Z), (BWI, dX), (BWW, dW)):
+        prm = params[kind]
+        P, Q = operands(kind, layer)
+        print(f"{KIND_NAME[kind]}: oracle quantization ...", flush=True)
+        cA, sA, nA = capi.quantize(P.numpy(), AXES[kind][0], 64, o_op(prm.A), prm.seed)
+        cB, sB, nB = capi.quantize(Q.numpy(), AXES[kind][1], 64, o_op(prm.B), prm.seed)
+        assert nA == nB
+        ii, jj = _sample_positions(rng, cA.shape[0], cB.shape[0])
+        assert tuple(got_t.shape) == (cA.shape[0], cB.shape[0])
+        want_acc = capi.tiled_matmul_sampled(cA, cB, s, 8, ii, jj)
+        want = capi.dequantize(want_acc, sA, sB, nA)
+        got = got_t[torch.from_numpy(ii).to("cuda:0"), torch.from_numpy(jj).to("cuda:0")].cpu().numpy()
+        denom = np.maximum(np.abs(want), np.finfo(np.float32).tiny)
+        bad = np.abs(got.astype(np.float64) - want) > RTOL * denom
+        assert not bad.any(), f"{KIND_NAME[kind]}: {bad.sum()} sampled outputs differ"
+        assert np.count_nonzero(want) > SAMPLES // 2      # the comparison is not one of zeros
 
 
 def test_layer_step_in_a_hip_graph():

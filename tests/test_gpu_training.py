@@ -66,14 +66,18 @@ def test_layer_fwd_bwd_equals_three_matmuls(M, K, N, n, s, a):
     assert none is None and none_dx is None and torch.equal(Zi, Z3) and torch.equal(dWb, dW3)
 
 
-def test_autograd_three_layer_network_matches_oracle():
+@pytest.mark.parametrize("stochastic_act", [False, True])
+def test_autograd_three_layer_network_matches_oracle(stochastic_act):
     """Three fully connected layers of width 561 at batch 128 (the paper's continual-
     learning network shape), ReLU between them: every matmul that autograd sees, in
-    the forward and in the backward pass, against the oracle on the same operands."""
+    the forward and in the backward pass, against the oracle on the same operands.
+    stochastic_act: the paper's own backward setting, in which the activation of the
+    weight-gradient matmul is rounded stochastically as well as the gradient."""
     torch.manual_seed(0)
     widths = [561, 561, 561, 12]
     layers = [A.HdqtLinear(widths[i], widths[i + 1], bias=False,
-                           cfg=A.LayerConfig(layer_id=i, seed=3, need_input_grad=(i > 0)),
+                           cfg=A.LayerConfig(layer_id=i, seed=3, need_input_grad=(i > 0),
+                                             stochastic_act=stochastic_act),
                            device="cuda:0") for i in range(3)]
     x = torch.randn(128, 561, device="cuda:0")
     target = torch.randint(0, 12, (128,), device="cuda:0")
