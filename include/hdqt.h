@@ -72,6 +72,8 @@ typedef enum { HDQT_GEMM_FWD = 0, HDQT_GEMM_BWD_INPUT = 1, HDQT_GEMM_BWD_WEIGHT 
 #define HDQT_EHIP (-12)           /* a HIP call failed */
 #define HDQT_EINVAL_GEOMETRY (-13) /* convolution geometry (or layer shape) outside what the
                                       activation-source kernels take: see hdqt_conv_t */
+#define HDQT_ESCRATCH (-14)        /* hdqt_gemm_fwd_static: the shape needs more scratch than the
+                                      library's fixed device array holds */
 
 /* One quantized operand; names follow the paper's quantizer Q. */
 typedef struct {
@@ -291,6 +293,24 @@ int hdqt_gemm_bwd_weight(const float *X, const float *G, float *dW, int64_t M, i
 int hdqt_gemm_bwd_input_bf16(const float *G, const float *W, uint16_t *dX, int64_t M, int64_t K,
                              int64_t N, const hdqt_params_t *params, int32_t *acc_out,
                              void *workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * hdqt_gemm_fwd for callers that cannot allocate and have no workspace to hand over: code
+ * under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same
+ * arguments without the workspace, same results bit for bit.  The calibration records and
+ * the codes of both operands live in a fixed device array inside the library
+ * (hdqt_gemm_fwd_static_max_bytes() = 8 MiB per GPU the library has run on, held until the
+ * process ends); the call allocates nothing, on the host or the device (as long as the
+ * optional profiling is off).
+ *   HDQT_ESCRATCH   hdqt_workspace_size(HDQT_GEMM_FWD, M, K, N, params) exceeds the array
+ *                   (nothing is launched); other errors as for hdqt_gemm_fwd
+ * All calls on one GPU share that GPU's array: two calls whose work overlaps in time on the
+ * same GPU (different streams or threads) race.  Calls on one stream, one after the other,
+ * are fine: every call clears and rewrites what it reads.
+ */
+size_t hdqt_gemm_fwd_static_max_bytes(void);
+int hdqt_gemm_fwd_static(const float *X, const float *W, float *Z, int64_t M, int64_t K, int64_t N,
+                         const hdqt_params_t *params, int32_t *acc_out, void *stream);
 
 /*
  * All three matmuls of one layer's training step in one call (Methodology: every

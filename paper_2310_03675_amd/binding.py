@@ -30,6 +30,7 @@ EXPORTED = [
     "hdqt_gemm_requant_workspace_size", "hdqt_gemm_requant", "hdqt_gemm_codes_bf16",
     "hdqt_gemm_bwd_input_bf16", "hdqt_quantize_dual_im2col", "hdqt_conv_step_workspace_size",
     "hdqt_conv_step", "hdqt_conv_fwd", "hdqt_conv_bwd", "hdqt_gemm_codes_fold", "hdqt_im2col",
+    "hdqt_gemm_fwd_static", "hdqt_gemm_fwd_static_max_bytes",
 ]
 
 
@@ -168,6 +169,10 @@ def load() -> C.CDLL:
         fn = getattr(lib, name)
         fn.restype = i32
         fn.argtypes = [vp, vp, vp, i64, i64, i64, C.POINTER(CParams), vp, vp, sz, vp]
+    lib.hdqt_gemm_fwd_static.restype = i32
+    lib.hdqt_gemm_fwd_static.argtypes = [vp, vp, vp, i64, i64, i64, C.POINTER(CParams), vp, vp]
+    lib.hdqt_gemm_fwd_static_max_bytes.restype = sz
+    lib.hdqt_gemm_fwd_static_max_bytes.argtypes = []
     lib.hdqt_strerror.restype = C.c_char_p
     lib.hdqt_strerror.argtypes = [i32]
     lib.hdqt_last_hip_error.restype = i32
@@ -406,6 +411,22 @@ def gemm(kind: int, P: torch.Tensor, Q: torch.Tensor, M: int, K: int, N: int, pa
     if rc:
         raise HdqtError(rc, fn)
     return out, acc, workspace
+
+
+def gemm_fwd_static(X: torch.Tensor, W: torch.Tensor, params: Params, out: torch.Tensor,
+                    acc: Optional[torch.Tensor] = None, stream: Optional[torch.cuda.Stream] = None):
+    """hdqt_gemm_fwd_static: the forward matmul without a workspace; the caller brings the
+    output (nothing is allocated here either)."""
+    _check_dev(X, W, out, acc)
+    M, K = X.shape
+    N = W.shape[1]
+    assert tuple(out.shape) == (M, N) and out.dtype == torch.float32
+    p = params.c()
+    rc = load().hdqt_gemm_fwd_static(_ptr(X), _ptr(W), _ptr(out), M, K, N, C.byref(p), _ptr(acc),
+                                     _stream(stream))
+    if rc:
+        raise HdqtError(rc, "hdqt_gemm_fwd_static")
+    return out
 
 
 def gemm_fwd(X, W, params: Params, **kw):

@@ -6,6 +6,7 @@
 #include "common.hpp"
 
 #include <limits.h>
+#include <mutex>
 
 namespace {
 
@@ -1191,6 +1192,64 @@ int hdqt_gemm_bwd_weight(const float* X, const float* G, float* dW, int64_t M, i
                     workspace_bytes, stream);
 }
 
+// ---- hdqt_gemm_fwd without a workspace argument and without any allocation ----
+//
+// The calibration records and the codes of both operands, which hdqt_gemm_fwd keeps in the
+// caller's workspace, live in a file-scope device array instead.  Every GPU the library runs
+// on holds its own copy of the array at its own address: the address is asked for once per
+// device (hipGetSymbolAddress with that device current) and only that pointer is ever handed
+// to a kernel -- in host code the array's name is a stand-in, not a device address.
+} // extern "C"
+
+namespace {
+constexpr size_t kStaticScratchBytes = (size_t)8 << 20;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+constexpr int kMaxDevices = 64;
+void* g_scratch_ptr[kMaxDevices] = {nullptr};
+std::mutex g_scratch_mu;
+
+// device pointer of `scratch` on the current device; nullptr (and the HIP error recorded) on failure
+void* static_scratch()
+{
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess || dev < 0 || dev >= kMaxDevices) {
+        g_last_hip_error = (int)(e != hipSuccess ? e : hipErrorInvalidDevice);
+        return nullptr;
+    }
+    std::lock_guard<std::mutex> lock(g_scratch_mu);
+    if (!g_scratch_ptr[dev]) {
+        void* ptr = nullptr;
+        e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));
+        if (e != hipSuccess || !ptr) {
+            g_last_hip_error = (int)(e != hipSuccess ? e : hipErrorInvalidSymbol);
+            return nullptr;
+        }
+        g_scratch_ptr[dev] = ptr;
+    }
+    return g_scratch_ptr[dev];
+}
+} // namespace
+
+extern "C" {
+
+size_t hdqt_gemm_fwd_static_max_bytes(void) { return kStaticScratchBytes; }
+
+int hdqt_gemm_fwd_static(const float* X, const float* W, float* Z, int64_t M, int64_t K, int64_t N,
+                         const hdqt_params_t* params, int32_t* acc_out, void* stream)
+{
+    hdqt_ws_layout_t L;
+    const int rc = hdqt_workspace_layout(HDQT_GEMM_FWD, M, K, N, params, &L);
+    if (rc) return rc;
+    if (L.total > kStaticScratchBytes) return HDQT_ESCRATCH;
+    void* ptr = static_scratch();
+    if (!ptr) return HDQT_EHIP;
+    // run_gemm clears the calibration records with a kernel before anything reads them, and
+    // writes every code byte that the matmul reads: what an earlier call left behind in the
+    // array is never seen.
+    return run_gemm(HDQT_GEMM_FWD, X, W, Z, M, K, N, params, acc_out, ptr, kStaticScratchBytes, stream);
+}
+
 const char* hdqt_strerror(int code)
 {
     switch (code) {
@@ -1207,6 +1266,7 @@ const char* hdqt_strerror(int code)
     case HDQT_EWORKSPACE: return "workspace is NULL or too small";
     case HDQT_EALIGN: return "a pointer is not 16-byte aligned";
     case HDQT_EHIP: return "a HIP call failed (see hdqt_last_hip_error)";
+    case HDQT_ESCRATCH: return "the shape needs more scratch than the library's fixed device array holds";
     case HDQT_EINVAL_GEOMETRY: return "convolution geometry or layer shape not taken by the activation-source kernels";
     default: return "unknown error code";
     }
