@@ -31,6 +31,8 @@ HBM_PEAK_GBPS = 8000.0          # MI355X HBM3E
 # rocprofv3 FETCH_SIZE / WRITE_SIZE runs summarised in
 # profiles/bench_resnet_k1152_hbm_traffic.md (per-launch average over the tensors a
 # kernel family runs on); bench.py cannot collect counters itself.
+TRAFFIC_SOURCE = "profiles/bench_resnet_k1152_hbm_traffic.md (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, not measured in this run)"
+VALU_SOURCE = "profiles/bench_resnet_k1152_valu_issue.md (rocprofv3 --pmc SQ_INSTS_VALU, not measured in this run)"
 MEASURED_TRAFFIC = {
     "fwht_dual_absmax_batch": 336.4e6, "fwht_dual_quant_batch": 421.7e6,
     "gemm_i4_fwd": 74.8e6, "gemm_i4_bwd_input": 307.4e6, "gemm_i4_bwd_weight": 77.6e6,
@@ -109,6 +111,10 @@ def main():
     ap.add_argument("--acc-bits", type=int, default=8)
     ap.add_argument("--cpu-rows", type=int, default=65536, help="rows of the oracle's sample")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--dist-steps", type=int, default=100,
+                    help="steps timed one by one (HIP events around each) for the median / min and the cold variant")
+    ap.add_argument("--no-others", action="store_true",
+                    help="skip the step lines of the other layer workloads ('other_workloads')")
     ap.add_argument("--graph", action="store_true",
                     help="capture one step into a HIP graph and time its replays (measured: no faster than "
                          "launching from the host, the step is bound by its kernels)")
@@ -205,6 +211,30 @@ def main():
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
 
+    # ---- the distribution: --dist-steps steps timed one by one (an event pair around each, on
+    # the stream the step is launched on), warm (back to back) and cold (a 512 MiB device fill
+    # between steps, twice the 256 MB memory-side cache: nothing of the inputs, the workspace or
+    # the previous step's outputs is left in any cache)
+    def timed_one_by_one(count, flush):
+        ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(count)]
+        for a, b_ in ev:
+            if flush is not None:
+                flush.fill_(1)
+            a.record()
+            run()
+            b_.record()
+        torch.cuda.synchronize()
+        ts = sorted(a.elapsed_time(b_) for a, b_ in ev)
+        return {"steps": count, "median_ms": ts[len(ts) // 2], "min_ms": ts[0], "max_ms": ts[-1],
+                "mean_ms": sum(ts) / len(ts)}
+    step_dist = None
+    if args.dist_steps > 0:
+        step_dist = {"warm": timed_one_by_one(args.dist_steps, None)}
+        flush_buf = torch.empty(512 << 20, dtype=torch.uint8, device=dev)
+        step_dist["cold"] = timed_one_by_one(min(args.dist_steps, 100), flush_buf)
+        step_dist["cold"]["flush"] = "512 MiB device fill before every step"
+        del flush_buf
+
     # ---- the same K steps again with the library's per-kernel HIP events switched on
     # (two events per launch on the launch stream; they cost a few microseconds per
     # launch, which is why the figure above is taken without them)
@@ -282,6 +312,11 @@ def main():
                 roof_all[name] = {"bound": "mfma", "achieved": tops, "peak": INT8_MFMA_PEAK_TOPS,
                                   "unit": "TOP/s", "frac": f_mfma, "traffic": measured.get(name),
                                   "algorithmic_ops_per_launch": ops_step / 3, "hbm_GBps": gbps}
+    for r_ in roof_all.values():
+        if r_.get("traffic") is not None:
+            r_["traffic_source"] = TRAFFIC_SOURCE
+        if "valu_issue" in r_:
+            r_["valu_issue"]["source"] = VALU_SOURCE
     dominant = max(roof_all, key=lambda k: kern[k][1])
     roofline = dict(roof_all[dominant], kernel=dominant)
     gemm_ms = sum(tot for name, (l, tot) in kern.items() if name.startswith("gemm") or name == "reduce_splits")
@@ -304,31 +339,42 @@ def main():
                  "us_per_step": gemm_ms / args.steps * 1e3},
         "fwht_quant_GBps": quant_bytes / (quant_ms * 1e-3) / 1e9 if quant_ms else None,
         "ms_per_step_with_kernel_events": dt_events / args.steps * 1e3,
+        "step_time_distribution": step_dist,
         "kernels": kernels,
         "roofline_all": roof_all,
     }
     if not args.no_large_quantize:
-        # The quantizer alone on a tensor far larger than any cache (1 GiB, axis 1, n = 64,
-        # b = 4, nearest): per-pass HBM rate of hdqt_quantize, algorithmic bytes 4 B per
-        # element for pass 1 and 4.5 B for pass 2.
+        # The quantizer alone on a tensor far larger than any cache (1 GiB, b = 4, nearest):
+        # per-pass HBM rate of hdqt_quantize, algorithmic bytes 4 B per element for pass 1 and
+        # 4.5 B for pass 2.  Legs: contraction along a row (axis 1) and along a column (axis 0,
+        # the transposing write), Hadamard block 64 (registers and lane exchanges only) and
+        # 256 (axis 1: more lane stages; axis 0: the fallback kernel that pairs waves through LDS).
         big = torch.randn((16384, 16384), device=dev)
         op = B.Operand(4, B.ROUND_NEAREST, 1.0, 0)
-        B.quantize(big, 1, 64, op, 0)
-        torch.cuda.synchronize()
-        B.profile_enable(True)
-        B.profile_collect()
-        for _ in range(5):
-            B.quantize(big, 1, 64, op, 0)
-        torch.cuda.synchronize()
-        B.profile_enable(False)
-        kq = B.profile_collect()
         elems_big = 16384.0 * 16384.0
-        p1 = kq["fwht_row_absmax"][1] / kq["fwht_row_absmax"][0] * 1e-3
-        p2 = kq["fwht_row_quant"][1] / kq["fwht_row_quant"][0] * 1e-3
-        line["quantize_1GiB"] = {
-            "pass1_GBps": 4.0 * elems_big / p1 / 1e9, "pass1_frac_of_hbm_peak": 4.0 * elems_big / p1 / 1e9 / HBM_PEAK_GBPS,
-            "pass2_GBps": 4.5 * elems_big / p2 / 1e9, "pass2_frac_of_hbm_peak": 4.5 * elems_big / p2 / 1e9 / HBM_PEAK_GBPS,
-            "both_GBps": 8.5 * elems_big / (p1 + p2) / 1e9}
+        line["quantize_1GiB"] = {}
+        for axis_q, n_q in ((1, 64), (0, 64), (1, 256), (0, 256)):
+            B.quantize(big, axis_q, n_q, op, 0)
+            torch.cuda.synchronize()
+            B.profile_enable(True)
+            B.profile_collect()
+            for _ in range(5):
+                B.quantize(big, axis_q, n_q, op, 0)
+            torch.cuda.synchronize()
+            B.profile_enable(False)
+            kq = B.profile_collect()
+            k1 = [k_ for k_ in kq if k_.endswith("absmax")]
+            k2 = [k_ for k_ in kq if k_.endswith("quant")]
+            p1 = sum(kq[k_][1] for k_ in k1) / 5 * 1e-3
+            p2 = sum(kq[k_][1] for k_ in k2) / 5 * 1e-3
+            leg = {
+                "kernels": sorted(kq),
+                "pass1_GBps": 4.0 * elems_big / p1 / 1e9, "pass1_frac_of_hbm_peak": 4.0 * elems_big / p1 / 1e9 / HBM_PEAK_GBPS,
+                "pass2_GBps": 4.5 * elems_big / p2 / 1e9, "pass2_frac_of_hbm_peak": 4.5 * elems_big / p2 / 1e9 / HBM_PEAK_GBPS,
+                "both_GBps": 8.5 * elems_big / (p1 + p2) / 1e9}
+            line["quantize_1GiB"][f"axis{axis_q}_n{n_q}"] = leg
+        # (the figures of the first leg at the top level too, where earlier runs had them)
+        line["quantize_1GiB"].update({k_: v_ for k_, v_ in line["quantize_1GiB"]["axis1_n64"].items() if k_ != "kernels"})
         del big
     if not args.no_square:
         # The integer matmul alone where the matrix pipe is the roofline: 4096^3 on the codes
@@ -544,6 +590,41 @@ def main():
             "tile_sums_write_GBps": slab / (kern2["requant_tile_sums"][1] / kern2["requant_tile_sums"][0] * 1e-3) / 1e9,
             "quantize_sum_read_GBps": slab / (kern2["requant_quantize_sum"][1] / kern2["requant_quantize_sum"][0] * 1e-3) / 1e9}
         del ws2
+    if not args.no_others and not args.separate:
+        # One step of the other layer workloads (not `value`): the HAR-style 1-D convolution layer
+        # and the 32 x 32 ResNet layer, each with its own Hadamard block, tile length = block
+        # for the first (as its configuration says) and the headline's tile length for the second.
+        line["other_workloads"] = {}
+        for name_o, s_o in (("har", 32), ("resnet_k576", args.s)):
+            lay_o, n_o = make_layer(name_o)
+            Mo, Ko, No = lay_o.M, lay_o.K, lay_o.N
+            Xo, Wo, Go = (t.to(dev) for t in (lay_o.X, lay_o.W, lay_o.G))
+            prm_o = [step_params(B, k, n_o, s_o, args.acc_bits) for k in kinds]
+            ws_o = torch.empty(B.layer_step_workspace_size(Mo, Ko, No, *prm_o), dtype=torch.uint8, device=dev)
+            out_o = tuple(torch.empty(B.out_shape(k, Mo, Ko, No), dtype=torch.float32, device=dev) for k in kinds)
+            f_o = lambda: B.layer_step(Xo, Wo, Go, *prm_o, out=out_o, workspace=ws_o)
+            for _ in range(args.warmup):
+                f_o()
+            torch.cuda.synchronize()
+            t_o = time.perf_counter()
+            for _ in range(args.steps):
+                f_o()
+            torch.cuda.synchronize()
+            dt_o = (time.perf_counter() - t_o) / args.steps
+            B.profile_enable(True)
+            B.profile_collect()
+            for _ in range(args.steps):
+                f_o()
+            torch.cuda.synchronize()
+            B.profile_enable(False)
+            k_o = B.profile_collect()
+            line["other_workloads"][name_o] = {
+                "workload": f"{lay_o.name} (M={Mo}, K={Ko}, N={No})", "had_block": n_o, "s": s_o,
+                "ms_per_step": dt_o * 1e3, "TOPS": 3 * 2.0 * Mo * Ko * No / dt_o / 1e12,
+                "algorithmic_bytes_per_step": 8.0 * (Mo * Ko + Ko * No + Mo * No) + 2.0 * (Mo * Ko + Ko * No + Mo * No)
+                                              + 4.0 * (Mo * No + Mo * Ko + Ko * No),
+                "kernels_us": {n_: tot / l * 1e3 for n_, (l, tot) in k_o.items()}}
+            del Xo, Wo, Go, ws_o, out_o, lay_o
     if not args.no_cpu_baseline:
         line["cpu_baseline"] = cpu_baseline(layer, n, args.s, min(args.cpu_rows, M))
     print(json.dumps(line))

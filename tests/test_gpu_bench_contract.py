@@ -18,7 +18,7 @@ def run_bench(*flags):
 @pytest.mark.gpu
 def test_bench_line_has_the_contract_fields():
     r = run_bench("--steps", "3", "--warmup", "1", "--no-large-quantize", "--no-square", "--no-conv",
-                  "--no-sweep", "--cpu-rows", "2048")
+                  "--no-sweep", "--no-others", "--dist-steps", "20", "--cpu-rows", "2048")
     assert r.returncode == 0, r.stderr[-2000:]
     lines = [ln for ln in r.stdout.splitlines() if ln.strip()]
     assert len(lines) == 1, "exactly one line on stdout"
@@ -34,7 +34,12 @@ def test_bench_line_has_the_contract_fields():
     assert roof["bound"] in ("hbm", "mfma", "alu") and roof["unit"] in ("GB/s", "TFLOP/s", "TOP/s")
     assert roof["peak"] == 8000.0 and 0 < roof["frac"] < 1
     assert abs(roof["frac"] - roof["achieved"] / roof["peak"]) < 1e-9
-    assert "traffic" in roof
+    assert "traffic" in roof and ("traffic_source" in roof or roof["traffic"] is None)
+    dist = d["step_time_distribution"]
+    for leg in ("warm", "cold"):
+        assert dist[leg]["steps"] == 20
+        assert 0 < dist[leg]["min_ms"] <= dist[leg]["median_ms"] <= dist[leg]["max_ms"]
+    assert dist["cold"]["median_ms"] >= dist["warm"]["min_ms"]
     cpu = d["cpu_baseline"]
     assert cpu["kind"] == "oracle" and cpu["value"] > 0 and cpu["cores"] >= 1 and cpu["sample"]
 
@@ -43,3 +48,22 @@ def test_more_than_one_gpu_is_refused():
     r = run_bench("--gpus", "2")
     assert r.returncode != 0
     assert "one GPU" in r.stderr
+
+
+@pytest.mark.gpu
+def test_bench_line_has_the_extra_legs():
+    """The standalone quantizer legs (both axes, block orders 64 and 256) and the step lines of
+    the other layer workloads."""
+    r = run_bench("--steps", "2", "--warmup", "1", "--no-square", "--no-conv", "--no-sweep",
+                  "--dist-steps", "0", "--no-cpu-baseline")
+    assert r.returncode == 0, r.stderr[-2000:]
+    d = json.loads([ln for ln in r.stdout.splitlines() if ln.strip()][0])
+    assert d["step_time_distribution"] is None
+    q = d["quantize_1GiB"]
+    for leg in ("axis1_n64", "axis0_n64", "axis1_n256", "axis0_n256"):
+        assert 0 < q[leg]["pass1_frac_of_hbm_peak"] < 1 and 0 < q[leg]["pass2_frac_of_hbm_peak"] < 1
+    assert q["pass1_GBps"] == q["axis1_n64"]["pass1_GBps"]
+    others = d["other_workloads"]
+    assert set(others) == {"har", "resnet_k576"}
+    for o in others.values():
+        assert o["ms_per_step"] > 0 and o["TOPS"] > 0 and o["kernels_us"]
