@@ -210,6 +210,16 @@ def dequantize(acc, scaleA, scaleB, n: int) -> np.ndarray:
     return out
 
 
+def relu_mask(dX, x) -> np.ndarray:
+    """dX where x > 0, +0 elsewhere (the rectifier's backward pass applied to an input gradient)."""
+    dX = np.ascontiguousarray(dX, dtype=np.float32)
+    x = np.ascontiguousarray(x, dtype=np.float32)
+    assert dX.shape == x.shape
+    out = np.empty(dX.shape, dtype=np.float32)
+    lib().orc_relu_mask(_p(dX, C.c_float), _p(x, C.c_float), C.c_int64(dX.size), _p(out, C.c_float))
+    return out
+
+
 def bf16_bits(x) -> np.ndarray:
     """binary32 values -> bfloat16 bit patterns (uint16), nearest, ties to even."""
     x = np.ascontiguousarray(x, dtype=np.float32)

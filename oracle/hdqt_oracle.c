@@ -36,6 +36,8 @@
  *   5''. input gradient of a convolution (orc_col2im_acc, an extension): the
  *                     accumulators of dX = G W^T folded back onto the layer's input
  *                     (the transpose of im2col) as exact integer sums, then step 6
+ *   6''. input gradient behind a rectifier (orc_relu_mask, an extension): step 6's
+ *                     values where the layer's input is positive, zero elsewhere
  *   6'. narrow output (orc_dequantize_bf16, an extension that is not in the
  *                     paper): step 6's binary32 value rounded to bfloat16,
  *                     nearest, ties to even; pinned by hand-built ties and a
@@ -371,6 +373,18 @@ void orc_dequantize(const int32_t *acc, int64_t count, float scaleA, float scale
     float dq = orc_dequant_factor(scaleA, scaleB, n_eff);
     for (int64_t p = 0; p < count; ++p)
         out[p] = (float)acc[p] * dq;
+}
+
+/* Input gradient behind a rectifier (an engineering extension: a framework applies this
+ * as a separate pass over dX).  When the layer's input is x = max(pre, 0), the gradient of
+ * `pre` is the layer's input gradient where x is positive and zero elsewhere:
+ *     masked[p] = x[p] > 0 ? dX[p] : +0
+ * x has dX's shape (the im2col matrix for the matrix path, the activation for the folded
+ * path).  Entries that are masked out are +0.0f whatever the sign of dX[p]. */
+void orc_relu_mask(const float *dX, const float *x, int64_t count, float *masked)
+{
+    for (int64_t p = 0; p < count; ++p)
+        masked[p] = x[p] > 0.0f ? dX[p] : 0.0f;
 }
 
 /* Narrow output (an engineering extension, not a step of the paper, whose layers hand

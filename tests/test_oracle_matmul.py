@@ -386,3 +386,31 @@ def test_col2im_of_a_1x1_window_is_a_transpose():
     acc = rng.integers(-100, 100, size=(2 * 3 * 4, 5)).astype(np.int32)
     got = capi.col2im_acc(acc, 2, 5, 3, 4, 1, 1)
     assert np.array_equal(got, acc.reshape(2, 12, 5).transpose(0, 2, 1).reshape(2, 5, 3, 4))
+
+
+# ---------------------------------------------------------------- the rectifier's mask on an input gradient
+
+def test_relu_mask_hand_cases():
+    """Written out by hand: kept where the layer's input is positive, +0 elsewhere (also
+    where the gradient is negative, where the input is -0, the smallest positive number, or
+    negative)."""
+    tiny = np.float32(1e-45)            # the smallest positive binary32 (a denormal)
+    x = np.array([1.0, -1.0, 0.0, -0.0, tiny, -tiny, 3.5, 2.0], dtype=np.float32)
+    dX = np.array([2.5, 2.5, -7.0, 4.0, -3.0, 9.0, -0.0, 1e30], dtype=np.float32)
+    want = np.array([2.5, 0.0, 0.0, 0.0, -3.0, 0.0, -0.0, 1e30], dtype=np.float32)
+    got = capi.relu_mask(dX, x)
+    assert got.tobytes() == want.tobytes()          # bit patterns: masked entries are +0, kept ones untouched
+
+
+def test_relu_mask_is_the_backward_pass_of_a_rectifier():
+    """Against PyTorch's autograd: d/d(pre) of sum(g * max(pre, 0)) is g where max(pre, 0) > 0."""
+    import torch
+    gen = torch.Generator().manual_seed(3)
+    pre = torch.randn((37, 29), generator=gen, requires_grad=True)
+    g = torch.randn((37, 29), generator=gen)
+    x = torch.relu(pre)
+    (x * g).sum().backward()
+    got = capi.relu_mask(g.numpy(), x.detach().numpy())
+    assert np.array_equal(got, pre.grad.numpy())
+    # and it commutes with nothing being masked: an all-positive input leaves the gradient as it is
+    assert np.array_equal(capi.relu_mask(g.numpy(), np.ones((37, 29), np.float32)), g.numpy())
