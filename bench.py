@@ -456,6 +456,31 @@ def main():
                                            "frac": nbytes / us / 1e3 / HBM_PEAK_GBPS,
                                            "algorithmic_bytes_per_launch": nbytes}
             del o_dx
+        # The input gradient behind a rectifier (hdqt_gemm_bwd_input_masked's kernel): dX written
+        # where the layer's input is positive, zero elsewhere; reads X once more (4*M*K bytes)
+        # where a framework's own pass over dX reads dX and X and writes dX again.
+        try:
+            ws_m = torch.empty(B.workspace_size(B.GEMM_BWD_INPUT, M, K, N, prm[B.GEMM_BWD_INPUT]), dtype=torch.uint8, device=dev)
+            o_dx = torch.empty((M, K), dtype=torch.float32, device=dev)
+            f_m = lambda: B.gemm(B.GEMM_BWD_INPUT, G, W, M, K, N, prm[B.GEMM_BWD_INPUT], out=o_dx, workspace=ws_m, mask=X)
+            for _ in range(3):
+                f_m()
+            torch.cuda.synchronize()
+            B.profile_enable(True)
+            B.profile_collect()
+            for _ in range(10):
+                f_m()
+            torch.cuda.synchronize()
+            B.profile_enable(False)
+            kg = B.profile_collect()
+            us = sum(v[1] for k_, v in kg.items() if k_.startswith("gemm") or k_ == "relu_mask") * 1e3 / 10
+            nbytes = 0.5 * (M * N + K * N) + 8.0 * M * K
+            line["bwd_input_bf16"]["relu_masked_fp32"] = {
+                "us": us, "bound": "hbm", "achieved": nbytes / us / 1e3, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                "frac": nbytes / us / 1e3 / HBM_PEAK_GBPS, "algorithmic_bytes_per_launch": nbytes}
+            del ws_m, o_dx
+        except B.HdqtError as exc:
+            line["bwd_input_bf16"]["relu_masked_fp32"] = {"skipped": str(exc)}
         if layer.act is not None:
             # and with the gradient folded back onto the convolution's input inside the matmul
             # (hdqt_gemm_codes_fold): what is written is the activation's gradient, kh*kw times

@@ -387,6 +387,33 @@ int hdqt_conv_bwd(const float *G, const float *W, const void *saved, const hdqt_
                   const hdqt_params_t *bwd_weight, void *workspace, size_t workspace_bytes,
                   void *stream);
 
+/*
+ * The input gradient behind a rectifier (not a step of the paper, whose layers hand dX on; a
+ * framework applies this as a pass of its own over dX).  When the layer's input is
+ * x = max(pre, 0), the gradient of `pre` is dX where x > 0 and zero elsewhere; these variants
+ * write that instead of dX, from inside the matmul's epilogue where the kernel has one
+ * (otherwise in the pass that finishes a split contraction, or in one more pass):
+ *     out[p] = x_mask[p] > 0 ? dX[p] : +0
+ *   x_mask    fp32, the shape of the output it masks (device, 16-byte aligned): the layer's
+ *             input X [M, K] for hdqt_gemm_bwd_input_masked and hdqt_layer_bwd_masked, the
+ *             activation [batch, C, H, W] for hdqt_conv_bwd_masked (its folded gradient is
+ *             what is masked)
+ * Everything else -- the other arguments, the workspace, the errors, dW -- as for
+ * hdqt_gemm_bwd_input, hdqt_layer_bwd and hdqt_conv_bwd; dX / dAct is required; acc_out
+ * (hdqt_gemm_bwd_input_masked) receives the accumulators unmasked.
+ */
+int hdqt_gemm_bwd_input_masked(const float *G, const float *W, const float *x_mask, float *dX, int64_t M,
+                               int64_t K, int64_t N, const hdqt_params_t *params, int32_t *acc_out,
+                               void *workspace, size_t workspace_bytes, void *stream);
+int hdqt_layer_bwd_masked(const float *G, const float *W, const void *saved, const float *x_mask,
+                          float *dX, float *dW, int64_t M, int64_t K, int64_t N,
+                          const hdqt_params_t *bwd_input, const hdqt_params_t *bwd_weight,
+                          void *workspace, size_t workspace_bytes, void *stream);
+int hdqt_conv_bwd_masked(const float *G, const float *W, const void *saved, const hdqt_conv_t *geo,
+                         const float *act_mask, float *dAct, float *dW, int64_t N,
+                         const hdqt_params_t *bwd_input, const hdqt_params_t *bwd_weight,
+                         void *workspace, size_t workspace_bytes, void *stream);
+
 /* The folded input gradient alone, on packed codes: qG [M, N] codes of G along N, qW [K, N]
  * codes of W along N (as hdqt_quantize writes them), their scales (device), the contraction
  * length N and its block order n_eff; dAct as for hdqt_conv_bwd.  No workspace. */

@@ -85,6 +85,39 @@ class HdqtMatmul(torch.autograd.Function):
         return dX, dW, None, None
 
 
+class HdqtReluMatmul(torch.autograd.Function):
+    """Z = max(pre, 0) W: the rectifier in front of a layer and the layer's matmul as one
+    autograd node.  The backward pass returns the gradient of `pre`: the library writes the
+    input gradient where the layer's input is positive and zero elsewhere, in the matmul's own
+    epilogue (hdqt_layer_bwd_masked), instead of a pass over dX by the framework.  The layer's
+    input is kept in fp32 for that (a framework's own rectifier keeps it too)."""
+
+    @staticmethod
+    def forward(ctx, pre, W, cfg: LayerConfig, step: int):
+        ctx.want_dx = cfg.need_input_grad and pre.requires_grad
+        X, W = torch.clamp_min(pre, 0.0).contiguous(), W.contiguous()
+        pf = cfg.params(B.GEMM_FWD, step)
+        pw = cfg.params(B.GEMM_BWD_WEIGHT, step)
+        Z, saved = B.layer_fwd(X, W, pf, pw)
+        ctx.save_for_backward(W, saved, X)
+        ctx.cfg, ctx.step, ctx.K = cfg, step, X.shape[1]
+        if cfg.capture is not None:
+            cfg.capture.update(X=X.detach(), W=W.detach().clone(), Z=Z.detach(), step=step)
+        return Z
+
+    @staticmethod
+    def backward(ctx, G):
+        W, saved, X = ctx.saved_tensors
+        cfg = ctx.cfg
+        pi = cfg.params(B.GEMM_BWD_INPUT, ctx.step) if ctx.want_dx else None
+        pw = cfg.params(B.GEMM_BWD_WEIGHT, ctx.step)
+        G = G.contiguous()
+        dPre, dW = B.layer_bwd(G, W, saved, ctx.K, pi, pw, mask=X if ctx.want_dx else None)
+        if cfg.capture is not None:
+            cfg.capture.update(G=G.detach(), dX=dPre, dW=dW)
+        return dPre, dW, None, None
+
+
 _FOLD_REFUSED = set()        # activation shapes hdqt_conv_bwd did not take (with the window used)
 
 
@@ -161,9 +194,10 @@ class HdqtLinear(torch.nn.Module):
     leading shape are flattened to [M, K]."""
 
     def __init__(self, in_features: int, out_features: int, bias: bool = True,
-                 cfg: Optional[LayerConfig] = None, device=None):
+                 cfg: Optional[LayerConfig] = None, device=None, relu_input: bool = False):
         super().__init__()
         self.cfg = cfg or LayerConfig()
+        self.relu_input = relu_input      # y = max(x, 0) W + bias, the rectifier's backward pass inside the matmul
         w = torch.empty(in_features, out_features, device=device)
         torch.nn.init.kaiming_normal_(w.t(), nonlinearity="relu")     # fan-in = in_features
         self.weight = torch.nn.Parameter(w)
@@ -172,7 +206,8 @@ class HdqtLinear(torch.nn.Module):
 
     def forward(self, x):
         lead = x.shape[:-1]
-        z = HdqtMatmul.apply(x.reshape(-1, x.shape[-1]), self.weight, self.cfg, self.step)
+        fn = HdqtReluMatmul if self.relu_input else HdqtMatmul
+        z = fn.apply(x.reshape(-1, x.shape[-1]), self.weight, self.cfg, self.step)
         if self.training:
             self.step += 1
         if self.bias is not None:

@@ -31,6 +31,7 @@ EXPORTED = [
     "hdqt_gemm_bwd_input_bf16", "hdqt_quantize_dual_im2col", "hdqt_conv_step_workspace_size",
     "hdqt_conv_step", "hdqt_conv_fwd", "hdqt_conv_bwd", "hdqt_gemm_codes_fold", "hdqt_im2col",
     "hdqt_gemm_fwd_static", "hdqt_gemm_fwd_static_max_bytes",
+    "hdqt_gemm_bwd_input_masked", "hdqt_layer_bwd_masked", "hdqt_conv_bwd_masked",
 ]
 
 
@@ -169,6 +170,12 @@ def load() -> C.CDLL:
         fn = getattr(lib, name)
         fn.restype = i32
         fn.argtypes = [vp, vp, vp, i64, i64, i64, C.POINTER(CParams), vp, vp, sz, vp]
+    lib.hdqt_gemm_bwd_input_masked.restype = i32
+    lib.hdqt_gemm_bwd_input_masked.argtypes = [vp, vp, vp, vp, i64, i64, i64, C.POINTER(CParams), vp, vp, sz, vp]
+    lib.hdqt_layer_bwd_masked.restype = i32
+    lib.hdqt_layer_bwd_masked.argtypes = [vp] * 6 + [i64, i64, i64] + [C.POINTER(CParams)] * 2 + [vp, sz, vp]
+    lib.hdqt_conv_bwd_masked.restype = i32
+    lib.hdqt_conv_bwd_masked.argtypes = [vp, vp, vp, C.POINTER(CConv), vp, vp, vp, i64] + [C.POINTER(CParams)] * 2 + [vp, sz, vp]
     lib.hdqt_gemm_fwd_static.restype = i32
     lib.hdqt_gemm_fwd_static.argtypes = [vp, vp, vp, i64, i64, i64, C.POINTER(CParams), vp, vp]
     lib.hdqt_gemm_fwd_static_max_bytes.restype = sz
@@ -389,11 +396,13 @@ def out_shape(kind: int, M: int, K: int, N: int):
 def gemm(kind: int, P: torch.Tensor, Q: torch.Tensor, M: int, K: int, N: int, params: Params,
          out: Optional[torch.Tensor] = None, acc: Optional[torch.Tensor] = None,
          want_acc: bool = False, workspace: Optional[torch.Tensor] = None,
-         stream: Optional[torch.cuda.Stream] = None, bf16: bool = False):
+         stream: Optional[torch.cuda.Stream] = None, bf16: bool = False,
+         mask: Optional[torch.Tensor] = None):
     """hdqt_gemm_{fwd,bwd_input,bwd_weight}.  P, Q are the two source tensors of
     `kind`: (X, W), (G, W), (X, G).  -> (out, acc | None, workspace).  bf16=True (input
-    gradient only): hdqt_gemm_bwd_input_bf16, `out` is a torch.bfloat16 tensor."""
-    _check_dev(P, Q, out, acc, workspace)
+    gradient only): hdqt_gemm_bwd_input_bf16, `out` is a torch.bfloat16 tensor.  mask (input
+    gradient only): hdqt_gemm_bwd_input_masked, the layer's input X [M, K]."""
+    _check_dev(P, Q, out, acc, workspace, mask)
     shape = out_shape(kind, M, K, N)
     assert not bf16 or kind == GEMM_BWD_INPUT
     fn = "hdqt_gemm_bwd_input_bf16" if bf16 else _GEMM_FN[kind]
@@ -406,8 +415,14 @@ def gemm(kind: int, P: torch.Tensor, Q: torch.Tensor, M: int, K: int, N: int, pa
     need = load().hdqt_workspace_size(kind, M, K, N, C.byref(p))
     if workspace is None:
         workspace = torch.empty(max(need, 256), dtype=torch.uint8, device=P.device)
-    rc = getattr(load(), fn)(_ptr(P), _ptr(Q), _ptr(out), M, K, N, C.byref(p),
-                             _ptr(acc), _ptr(workspace), workspace.numel(), _stream(stream))
+    if mask is not None:
+        assert kind == GEMM_BWD_INPUT and not bf16 and tuple(mask.shape) == tuple(shape) and mask.dtype == torch.float32
+        fn = "hdqt_gemm_bwd_input_masked"
+        rc = load().hdqt_gemm_bwd_input_masked(_ptr(P), _ptr(Q), _ptr(mask), _ptr(out), M, K, N, C.byref(p),
+                                               _ptr(acc), _ptr(workspace), workspace.numel(), _stream(stream))
+    else:
+        rc = getattr(load(), fn)(_ptr(P), _ptr(Q), _ptr(out), M, K, N, C.byref(p),
+                                 _ptr(acc), _ptr(workspace), workspace.numel(), _stream(stream))
     if rc:
         raise HdqtError(rc, fn)
     return out, acc, workspace
@@ -530,10 +545,12 @@ def conv_fwd(act: torch.Tensor, kh: int, kw: int, W: torch.Tensor, fwd: Params, 
 
 
 def conv_bwd(G: torch.Tensor, W: torch.Tensor, saved: torch.Tensor, act_shape, kh: int, kw: int,
-             bwd_input: Params, bwd_weight: Params, stream: Optional[torch.cuda.Stream] = None):
+             bwd_input: Params, bwd_weight: Params, stream: Optional[torch.cuda.Stream] = None,
+             mask: Optional[torch.Tensor] = None):
     """hdqt_conv_bwd -> (dAct [batch, C, H, W], dW [K, N]): hdqt_layer_bwd with the input gradient
-    folded back onto the activation inside the matmul.  HdqtError -13 for geometries not taken."""
-    _check_dev(G, W, saved)
+    folded back onto the activation inside the matmul.  HdqtError -13 for geometries not taken.
+    mask: hdqt_conv_bwd_masked, the activation itself (dAct is written where it is positive)."""
+    _check_dev(G, W, saved, mask)
     batch, Cin, H, Wd = act_shape
     geo = CConv(batch, Cin, H, Wd, kh, kw)
     M, K, N = batch * H * Wd, Cin * kh * kw, G.shape[1]
@@ -543,8 +560,14 @@ def conv_bwd(G: torch.Tensor, W: torch.Tensor, saved: torch.Tensor, act_shape, k
     dW = torch.empty((K, N), dtype=torch.float32, device=G.device)
     need = load().hdqt_layer_bwd_workspace_size(M, K, N, C.byref(pi), C.byref(pw))
     workspace = torch.empty(max(need, 256), dtype=torch.uint8, device=G.device)
-    rc = load().hdqt_conv_bwd(_ptr(G), _ptr(W), _ptr(saved), C.byref(geo), _ptr(dAct), _ptr(dW), N,
-                              C.byref(pi), C.byref(pw), _ptr(workspace), workspace.numel(), _stream(stream))
+    if mask is not None:
+        assert tuple(mask.shape) == tuple(dAct.shape) and mask.dtype == torch.float32 and mask.is_contiguous()
+        rc = load().hdqt_conv_bwd_masked(_ptr(G), _ptr(W), _ptr(saved), C.byref(geo), _ptr(mask), _ptr(dAct),
+                                         _ptr(dW), N, C.byref(pi), C.byref(pw), _ptr(workspace),
+                                         workspace.numel(), _stream(stream))
+    else:
+        rc = load().hdqt_conv_bwd(_ptr(G), _ptr(W), _ptr(saved), C.byref(geo), _ptr(dAct), _ptr(dW), N,
+                                  C.byref(pi), C.byref(pw), _ptr(workspace), workspace.numel(), _stream(stream))
     if rc:
         raise HdqtError(rc, "hdqt_conv_bwd")
     return dAct, dW
@@ -569,10 +592,12 @@ def gemm_codes_fold(qG: torch.Tensor, qW: torch.Tensor, bG: int, bW: int, scaleG
 
 def layer_bwd(G: torch.Tensor, W: torch.Tensor, saved: torch.Tensor, K: int,
               bwd_input: Optional[Params], bwd_weight: Params, out=None,
-              workspace: Optional[torch.Tensor] = None, stream: Optional[torch.cuda.Stream] = None):
+              workspace: Optional[torch.Tensor] = None, stream: Optional[torch.cuda.Stream] = None,
+              mask: Optional[torch.Tensor] = None):
     """hdqt_layer_bwd -> (dX | None, dW).  dX is skipped when `bwd_input` is None.
-    `out` may carry preallocated (dX, dW)."""
-    _check_dev(G, W, saved, workspace)
+    `out` may carry preallocated (dX, dW).  mask: hdqt_layer_bwd_masked, the layer's input
+    X [M, K] (dX is written where it is positive, zero elsewhere)."""
+    _check_dev(G, W, saved, workspace, mask)
     M, N = G.shape
     if out is None:
         new = lambda *shape: torch.empty(shape, dtype=torch.float32, device=G.device)
@@ -583,8 +608,14 @@ def layer_bwd(G: torch.Tensor, W: torch.Tensor, saved: torch.Tensor, K: int,
     if workspace is None:
         need = load().hdqt_layer_bwd_workspace_size(M, K, N, _byref(pi), C.byref(pw))
         workspace = torch.empty(max(need, 256), dtype=torch.uint8, device=G.device)
-    rc = load().hdqt_layer_bwd(_ptr(G), _ptr(W), _ptr(saved), _ptr(dX), _ptr(dW), M, K, N, _byref(pi),
-                               C.byref(pw), _ptr(workspace), workspace.numel(), _stream(stream))
+    if mask is not None:
+        assert dX is not None and tuple(mask.shape) == (M, K) and mask.dtype == torch.float32 and mask.is_contiguous()
+        rc = load().hdqt_layer_bwd_masked(_ptr(G), _ptr(W), _ptr(saved), _ptr(mask), _ptr(dX), _ptr(dW), M, K, N,
+                                          _byref(pi), C.byref(pw), _ptr(workspace), workspace.numel(),
+                                          _stream(stream))
+    else:
+        rc = load().hdqt_layer_bwd(_ptr(G), _ptr(W), _ptr(saved), _ptr(dX), _ptr(dW), M, K, N, _byref(pi),
+                                   C.byref(pw), _ptr(workspace), workspace.numel(), _stream(stream))
     if rc:
         raise HdqtError(rc, "hdqt_layer_bwd")
     return dX, dW

@@ -297,10 +297,16 @@ int run_planned_gemm(hdqt::GemmArgs g, void* ws, size_t ws_bytes, hipStream_t st
         e = hdqt::launch_gemm(g, stream);
         if (e != hipSuccess) return hip_fail(e);
         e = hdqt::launch_reduce(g.partial, g.splits, g.RA * g.RB, g.scaleA, g.scaleB, g.inv_n, g.out,
-                                g.out_bf16, g.acc_out, stream);
+                                g.out_bf16, g.acc_out, stream, g.mask_src);
         return e == hipSuccess ? HDQT_OK : hip_fail(e);
     }
     e = hdqt::launch_gemm(g, stream);
+    if (e != hipSuccess) return hip_fail(e);
+    // the rectifier's mask, where the matmul's own epilogue does not apply it
+    if (g.mask_src && g.out && !hdqt::gemm_fast_masks(g)) {
+        const int64_t count = g.fold ? g.fbatch * g.fC * g.fH * g.fW : g.RA * g.RB;
+        e = hdqt::launch_relu_mask(g.out, g.mask_src, count, stream);
+    }
     return e == hipSuccess ? HDQT_OK : hip_fail(e);
 }
 
@@ -329,7 +335,7 @@ int run_gemm_codes(const void* qA, const void* qB, int bA, int bB, const float* 
 
 int run_gemm(int kind, const float* P, const float* Q, float* out, int64_t M, int64_t K, int64_t N,
              const hdqt_params_t* prm, int32_t* acc_out, void* ws, size_t ws_bytes, void* stream_v,
-             uint16_t* out_bf16 = nullptr)
+             uint16_t* out_bf16 = nullptr, const float* mask_src = nullptr)
 {
     hdqt_ws_layout_t L;
     int rc = hdqt_workspace_layout(kind, M, K, N, prm, &L);
@@ -350,6 +356,8 @@ int run_gemm(int kind, const float* P, const float* Q, float* out, int64_t M, in
     hdqt::GemmArgs g = plan_gemm(codesA, codesB, prm->A.b, prm->B.b, &metaA->scale, &metaB->scale,
                                  o.RA, o.RB, o.D, L.n_eff, prm->acc_bits, prm->s, out, acc_out, 1 + kind,
                                  out_bf16);
+    if (mask_src && (misaligned(mask_src) || !out)) return out ? HDQT_EALIGN : HDQT_EINVAL_NULL;
+    g.mask_src = mask_src;
     // one launch clears both calibration records (they are adjacent)
     hipError_t e = hdqt::launch_zero2(reinterpret_cast<uint32_t*>(metaA), (int64_t)(2 * kMetaBytes / 4),
                                       nullptr, 0, stream);
@@ -1064,10 +1072,12 @@ namespace {
 int run_layer_bwd(const float* G, const float* W, const void* saved, const hdqt_conv_t* geo, float* dX,
                   float* dW, int64_t M, int64_t K, int64_t N, const hdqt_params_t* bwd_input,
                   const hdqt_params_t* bwd_weight, void* workspace, size_t workspace_bytes,
-                  void* stream_v)
+                  void* stream_v, const float* mask_src = nullptr)
 {
     if (!G || !saved || !dW || !bwd_weight) return HDQT_EINVAL_NULL;
     const bool with_dx = dX != nullptr;
+    if (mask_src && !with_dx) return HDQT_EINVAL_NULL;
+    if (misaligned(mask_src)) return HDQT_EALIGN;
     if (with_dx && (!bwd_input || !W)) return HDQT_EINVAL_NULL;
     BwdLayout L;
     int rc = plan_bwd(M, K, N, with_dx ? bwd_input : nullptr, bwd_weight, &L);
@@ -1089,6 +1099,7 @@ int run_layer_bwd(const float* G, const float* W, const void* saved, const hdqt_
         if (geo && !hdqt::gemm_fold_plan(&g_dx, geo->batch, geo->channels, geo->height, geo->width, geo->kh,
                                          geo->kw))
             return HDQT_EINVAL_GEOMETRY;
+        g_dx.mask_src = mask_src;
     } else if (geo) {
         return HDQT_EINVAL_NULL;
     }
@@ -1137,6 +1148,37 @@ int hdqt_conv_bwd(const float* G, const float* W, const void* saved, const hdqt_
     if (!conv_matrix_shape(geo, &M, &K)) return HDQT_EINVAL_DIM;
     return run_layer_bwd(G, W, saved, geo, dAct, dW, M, K, N, bwd_input, bwd_weight, workspace,
                          workspace_bytes, stream);
+}
+
+int hdqt_layer_bwd_masked(const float* G, const float* W, const void* saved, const float* x_mask,
+                          float* dX, float* dW, int64_t M, int64_t K, int64_t N,
+                          const hdqt_params_t* bwd_input, const hdqt_params_t* bwd_weight, void* workspace,
+                          size_t workspace_bytes, void* stream)
+{
+    if (!x_mask || !dX) return HDQT_EINVAL_NULL;
+    return run_layer_bwd(G, W, saved, nullptr, dX, dW, M, K, N, bwd_input, bwd_weight, workspace,
+                         workspace_bytes, stream, x_mask);
+}
+
+int hdqt_conv_bwd_masked(const float* G, const float* W, const void* saved, const hdqt_conv_t* geo,
+                         const float* act_mask, float* dAct, float* dW, int64_t N,
+                         const hdqt_params_t* bwd_input, const hdqt_params_t* bwd_weight, void* workspace,
+                         size_t workspace_bytes, void* stream)
+{
+    if (!geo || !dAct || !act_mask) return HDQT_EINVAL_NULL;
+    int64_t M, K;
+    if (!conv_matrix_shape(geo, &M, &K)) return HDQT_EINVAL_DIM;
+    return run_layer_bwd(G, W, saved, geo, dAct, dW, M, K, N, bwd_input, bwd_weight, workspace,
+                         workspace_bytes, stream, act_mask);
+}
+
+int hdqt_gemm_bwd_input_masked(const float* G, const float* W, const float* x_mask, float* dX, int64_t M,
+                               int64_t K, int64_t N, const hdqt_params_t* params, int32_t* acc_out,
+                               void* workspace, size_t workspace_bytes, void* stream)
+{
+    if (!x_mask || !dX) return HDQT_EINVAL_NULL;
+    return run_gemm(HDQT_GEMM_BWD_INPUT, G, W, dX, M, K, N, params, acc_out, workspace, workspace_bytes,
+                    stream, nullptr, x_mask);
 }
 
 int hdqt_gemm_codes_fold(const void* qG, const void* qW, int bG, int bW, const float* scaleG,

@@ -87,6 +87,9 @@ struct GemmArgs {
     float inv_n;            // 1 / n_eff (a power of two)
     float* out;             // [RA, RB] or null
     uint16_t* out_bf16;     // [RA, RB] bfloat16 patterns or null: the same values, narrowed (nearest even)
+    const float* mask_src;  // null, or a tensor of the fp32 output's shape: the output is written
+                            // where mask_src > 0 and +0 elsewhere (the rectifier's backward pass
+                            // behind an input gradient); the integer outputs are not masked
     int32_t* acc_out;       // [RA, RB] or null
     int32_t* partial;       // [splits, RA, RB] when splits > 1: one slice per part of the contraction;
                             // second reading of the accumulator: [n_tiles, RA, RB], every tile's sums
@@ -141,7 +144,11 @@ hipError_t launch_zero2(uint32_t* a, int64_t na, uint32_t* b, int64_t nb, hipStr
 // out_bf16 (nullable): the dequantized totals narrowed to bfloat16
 hipError_t launch_reduce(const int32_t* partial, int splits, int64_t count, const float* scaleA,
                          const float* scaleB, float inv_n, float* out, uint16_t* out_bf16,
-                         int32_t* acc_out, hipStream_t stream);
+                         int32_t* acc_out, hipStream_t stream, const float* mask_src = nullptr);
+// out[e] = mask_src[e] > 0 ? out[e] : +0 (for the matmul paths that do not mask in their epilogue)
+hipError_t launch_relu_mask(float* out, const float* mask_src, int64_t count, hipStream_t stream);
+// whether the matrix-core kernel applies g.mask_src in its own epilogue
+bool gemm_fast_masks(const GemmArgs& g);
 
 // Optional per-kernel timing (off by default).  When enabled through the C ABI,
 // every launch is bracketed by two HIP events on its stream.
@@ -150,7 +157,7 @@ enum KernelId {
     K_PLAIN_QUANT, K_GEMM_ALIGNED, K_GEMM_GENERIC, K_REDUCE, K_GEMM_I4, K_DUAL_ABSMAX, K_DUAL_QUANT,
     K_GEMM_I4_FWD, K_GEMM_I4_BWD_INPUT, K_GEMM_I4_BWD_WEIGHT,
     K_DUAL_ABSMAX_X, K_DUAL_ABSMAX_W, K_DUAL_ABSMAX_G, K_DUAL_QUANT_X, K_DUAL_QUANT_W, K_DUAL_QUANT_G,
-    K_DUAL_ABSMAX_BATCH, K_DUAL_QUANT_BATCH, K_REQUANT_TILES, K_REQUANT_SUM, K_IM2COL,
+    K_DUAL_ABSMAX_BATCH, K_DUAL_QUANT_BATCH, K_REQUANT_TILES, K_REQUANT_SUM, K_IM2COL, K_RELU_MASK,
     K_COUNT
 };
 bool quantize_fast_eligible(const QuantArgs& q);

@@ -233,7 +233,7 @@ template <int VEC>
 __global__ __launch_bounds__(256) void reduce_kernel(const int32_t* partial, int splits, int64_t count,
                                                      const float* scaleA, const float* scaleB,
                                                      float inv_n, float* out, uint16_t* out_bf16,
-                                                     int32_t* acc_out)
+                                                     int32_t* acc_out, const float* mask_src)
 {
     const float dq = (scaleA[0] * scaleB[0]) * inv_n;
     for (int64_t e = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) * VEC; e < count;
@@ -252,7 +252,7 @@ __global__ __launch_bounds__(256) void reduce_kernel(const int32_t* partial, int
 #pragma unroll
         for (int k = 0; k < VEC; ++k) {
             if (acc_out) acc_out[e + k] = t[k];
-            if (out) out[e + k] = (float)t[k] * dq;
+            if (out) out[e + k] = (mask_src && !(mask_src[e + k] > 0.0f)) ? 0.0f : (float)t[k] * dq;
             if (out_bf16) out_bf16[e + k] = (uint16_t)bf16_bits((float)t[k] * dq);
         }
     }
@@ -266,7 +266,7 @@ template <int VEC>
 __global__ __launch_bounds__(256) void reduce_many_kernel(const int32_t* partial, int splits, int64_t count,
                                                           const float* scaleA, const float* scaleB,
                                                           float inv_n, float* out, uint16_t* out_bf16,
-                                                          int32_t* acc_out)
+                                                          int32_t* acc_out, const float* mask_src)
 {
     constexpr int SG = 16, EPB = 256 / SG;      // slice groups, elements per block
     __shared__ int red[SG][EPB][4];
@@ -296,7 +296,7 @@ __global__ __launch_bounds__(256) void reduce_many_kernel(const int32_t* partial
 #pragma unroll
         for (int j = 0; j < SG; ++j) sum += red[j][el][k];
         if (acc_out) acc_out[e + k] = sum;
-        if (out) out[e + k] = (float)sum * dq;
+        if (out) out[e + k] = (mask_src && !(mask_src[e + k] > 0.0f)) ? 0.0f : (float)sum * dq;
         if (out_bf16) out_bf16[e + k] = (uint16_t)bf16_bits((float)sum * dq);
     }
 }
@@ -348,11 +348,26 @@ __global__ __launch_bounds__(256) void requant_sum_kernel(const int32_t* partial
     }
 }
 
+__global__ __launch_bounds__(256) void relu_mask_kernel(float* out, const float* mask_src, int64_t count)
+{
+    for (int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; e < count; e += (int64_t)gridDim.x * blockDim.x)
+        if (!(mask_src[e] > 0.0f)) out[e] = 0.0f;
+}
+
 } // namespace
+
+hipError_t launch_relu_mask(float* out, const float* mask_src, int64_t count, hipStream_t stream)
+{
+    int64_t blocks = (count + 255) / 256;
+    if (blocks > 16384) blocks = 16384;
+    ProfileScope ps(K_RELU_MASK, stream);
+    hipLaunchKernelGGL(relu_mask_kernel, dim3((unsigned)blocks), dim3(256), 0, stream, out, mask_src, count);
+    return hipGetLastError();
+}
 
 hipError_t launch_reduce(const int32_t* partial, int splits, int64_t count, const float* scaleA,
                          const float* scaleB, float inv_n, float* out, uint16_t* out_bf16,
-                         int32_t* acc_out, hipStream_t stream)
+                         int32_t* acc_out, hipStream_t stream, const float* mask_src)
 {
     const bool vec = (count % 4 == 0);
     const int64_t groups = vec ? count / 4 : count;
@@ -361,10 +376,10 @@ hipError_t launch_reduce(const int32_t* partial, int splits, int64_t count, cons
         const dim3 grid((unsigned)((groups + 15) / 16));
         if (vec)
             hipLaunchKernelGGL(reduce_many_kernel<4>, grid, dim3(256), 0, stream, partial, splits, count, scaleA,
-                               scaleB, inv_n, out, out_bf16, acc_out);
+                               scaleB, inv_n, out, out_bf16, acc_out, mask_src);
         else
             hipLaunchKernelGGL(reduce_many_kernel<1>, grid, dim3(256), 0, stream, partial, splits, count, scaleA,
-                               scaleB, inv_n, out, out_bf16, acc_out);
+                               scaleB, inv_n, out, out_bf16, acc_out, mask_src);
         return hipGetLastError();
     }
     int64_t blocks = ((vec ? count / 4 : count) + 255) / 256;
@@ -373,10 +388,10 @@ hipError_t launch_reduce(const int32_t* partial, int splits, int64_t count, cons
     ProfileScope ps(K_REDUCE, stream);
     if (vec)
         hipLaunchKernelGGL(reduce_kernel<4>, dim3((unsigned)blocks), dim3(256), 0, stream, partial, splits,
-                           count, scaleA, scaleB, inv_n, out, out_bf16, acc_out);
+                           count, scaleA, scaleB, inv_n, out, out_bf16, acc_out, mask_src);
     else
         hipLaunchKernelGGL(reduce_kernel<1>, dim3((unsigned)blocks), dim3(256), 0, stream, partial, splits,
-                           count, scaleA, scaleB, inv_n, out, out_bf16, acc_out);
+                           count, scaleA, scaleB, inv_n, out, out_bf16, acc_out, mask_src);
     return hipGetLastError();
 }
 

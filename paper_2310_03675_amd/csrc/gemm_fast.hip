@@ -195,9 +195,15 @@ __device__ __forceinline__ int clamp3(int v, int lo, int hi)
 // high and two wide with one 32 x 32 block each, for outputs of at most 64 columns, which
 // would leave half of every 128-column tile -- half the MFMAs and half the tile sums -- to
 // nothing.
-template <int EPI, int KS, bool STREAM, int WAVES, bool BF16, bool FOLD, bool WIDE = false, bool NARROW = false>
-__global__ __launch_bounds__(64 * WAVES, WAVES == 8 ? 4 : 2) void gemm_i4_kernel(GemmArgs g)
+// MASK (plain fp32 output only): g.mask_src, a tensor of the output's shape, is read at the end
+// of a tile (all of a wave's values in flight together) and the output is written where it is
+// positive, +0 elsewhere.  An instance of its own: the 32 values cost registers.  (The fold
+// epilogue masks with a run-time test: it reads one value per output element anyway.)
+template <int EPI, int KS, bool STREAM, int WAVES, bool BF16, bool FOLD, bool WIDE = false, bool NARROW = false,
+          bool MASK = false>
+__global__ __launch_bounds__(64 * WAVES, WAVES == 8 ? (MASK ? 3 : 4) : 2) void gemm_i4_kernel(GemmArgs g)
 {
+    static_assert(!MASK || (!BF16 && !FOLD && !WIDE && !NARROW), "masked output: plain packed instances only");
     static_assert(!NARROW || (WAVES == 8 && !BF16 && !FOLD && !WIDE), "narrow tiles: plain packed instances only");
     constexpr int TM = BM, TN = NARROW ? 64 : BN;   // the workgroup's tile
     // ROWWIDE (streamed outputs, i.e. at least 128 MB): a wave is one block high and two wide
@@ -320,6 +326,29 @@ __global__ __launch_bounds__(64 * WAVES, WAVES == 8 ? 4 : 2) void gemm_i4_kernel
     int c_ct = blockIdx.z;
     int64_t c_k = k_begin;
     int step_in_tile = 0;
+
+    // MASK: the values of g.mask_src at the wave's output positions of tile `ct`, requested a
+    // whole tile ahead of the epilogue that tests them (read there, right before the stores,
+    // their latency stood in front of every tile: 245 us instead of 71 us for the benchmark
+    // layer's input gradient)
+    float mk[MASK ? RS : 1][MASK ? CS : 1][MASK ? 16 : 1];
+    auto prefetch_mask = [&](const int ct) {
+        if (ct >= n_ct) return;
+        const int64_t col0 = (int64_t)ct * TN;
+        const float* mb = g.mask_src + row0 * g.RB + col0;
+        const bool interior = (row0 + TM <= g.RA) && (col0 + TN <= g.RB);
+#pragma unroll
+        for (int a = 0; a < (MASK ? RS : 1); ++a)
+#pragma unroll
+            for (int c = 0; c < (MASK ? CS : 1); ++c)
+#pragma unroll
+                for (int r = 0; r < (MASK ? 16 : 1); ++r) {
+                    const int rr = a * 32 + 8 * (r >> 2) + (r & 3);
+                    const int64_t uo = (int64_t)rr * g.RB + c * 32;
+                    const bool ok = interior || ((row0 + lane_row + rr < g.RA) && (col0 + lane_col + c * 32 < g.RB));
+                    mk[a][c][r] = ok ? __builtin_nontemporal_load(&(mb + uo)[lane_off]) : 0.0f;
+                }
+    };
 
     // One stage: registers -> LDS buffer `buf`, barrier, refill the registers with
     // the next stage, multiply; at the end of a tile, write it out.
@@ -573,7 +602,8 @@ __global__ __launch_bounds__(64 * WAVES, WAVES == 8 ? 4 : 2) void gemm_i4_kernel
                     int sum = 0;
 #pragma unroll
                     for (int t = 0; t < 9; ++t) sum += col[off[t]];
-                    g.out[(((int64_t)b * g.fC + cbase + c) * H + y) * W + x] = (float)sum * dq;
+                    const int64_t o = (((int64_t)b * g.fC + cbase + c) * H + y) * W + x;
+                    g.out[o] = (g.mask_src && !(g.mask_src[o] > 0.0f)) ? 0.0f : (float)sum * dq;
                 }
             } else {
                 for (int c = tid / BM; c < g.f_cg; c += NTHREADS / BM) {
@@ -588,7 +618,8 @@ __global__ __launch_bounds__(64 * WAVES, WAVES == 8 ? 4 : 2) void gemm_i4_kernel
                             sum += img_part[((ryp << g.f_log2w) + xp) * AP + c * khw + ty * kw + tx];
                         }
                     }
-                    g.out[(((int64_t)b * g.fC + cbase + c) * H + y) * W + x] = (float)sum * dq;
+                    const int64_t o = (((int64_t)b * g.fC + cbase + c) * H + y) * W + x;
+                    g.out[o] = (g.mask_src && !(g.mask_src[o] > 0.0f)) ? 0.0f : (float)sum * dq;
                 }
             }
             __syncthreads();             // the next stage overwrites the buffers the sums were read from
@@ -676,14 +707,19 @@ __global__ __launch_bounds__(64 * WAVES, WAVES == 8 ? 4 : 2) void gemm_i4_kernel
                         if (ob) {
                             // (a template flag, not a run-time branch: merging the two stores
                             // would drop the streaming hint)
-                            if (STREAM) __builtin_nontemporal_store((float)v * dq, &(ob + uo)[lane_off]);
-                            else (ob + uo)[lane_off] = (float)v * dq;
+                            float f = (float)v * dq;
+                            if constexpr (MASK) f = mk[a][c][r] > 0.0f ? f : 0.0f;
+                            if (STREAM) __builtin_nontemporal_store(f, &(ob + uo)[lane_off]);
+                            else (ob + uo)[lane_off] = f;
                         }
                     }
                 }
+        // the next tile's mask values set out now: a tile's worth of time to arrive
+        if constexpr (MASK) prefetch_mask(c_ct + (int)gridDim.z);
         c_k = k_begin;
         c_ct += gridDim.z;
     };
+    if constexpr (MASK) prefetch_mask(c_ct);
 
     // The global loads run two stages ahead of the multiplication where the registers allow
     // it (one stage of 128 codes is 8 MFMAs per wave, about 0.5 us of matrix time per SIMD,
@@ -813,11 +849,23 @@ bool gemm_fast_eligible(const GemmArgs& g)
     return per_tile * g.tiles_per_split < ((int64_t)1 << 22);
 }
 
+// Whether the kernel applies g.mask_src itself: the fold epilogue, and the instances of the
+// packed-code epilogues HDQT_LAUNCH_I4 covers with a whole, unsplit output.  Everything else
+// is masked by a pass of its own after the matmul (or by the pass that adds a split
+// contraction's slices).
+bool gemm_fast_masks(const GemmArgs& g)
+{
+    if (!g.mask_src || !g.out || !gemm_fast_eligible(g)) return false;
+    if (g.fold) return true;
+    if (g.splits > 1 || g.out_bf16 || g.bA > 4 || g.s == 16) return false;
+    return !sat16_path(g);
+}
+
 // Outputs of at most 64 columns take the 128 x 64 workgroup tile where such instances exist
 // (packed codes, fp32 / int32 output, the epilogues of the paper's settings).
 static bool narrow_tiles(const GemmArgs& g)
 {
-    if (g.RB > 64 || g.fold || g.out_bf16 || g.bA > 4 || g.s == 16) return false;
+    if (g.RB > 64 || g.fold || g.out_bf16 || g.bA > 4 || g.s == 16 || g.mask_src) return false;
     return !sat16_path(g);
 }
 
@@ -839,6 +887,7 @@ hipError_t launch_gemm_fast(const GemmArgs& g_in, hipStream_t stream)
     }
     const bool s32 = sat8_path(g) && g.s == 32;
     const bool sat16 = sat16_path(g, &g);
+    const bool masked = gemm_fast_masks(g) && !g.fold;
     const int64_t KS = KS_LONG;
     const int64_t stages = (g.tiles_per_split * g.s + KS - 1) / KS;
     int64_t gx = n_ct;
@@ -852,7 +901,10 @@ hipError_t launch_gemm_fast(const GemmArgs& g_in, hipStream_t stream)
 #define HDQT_LAUNCH_I4(EPI)                                                                          \
     do {                                                                                             \
         const dim3 block(64 * kWaves);                                                               \
-        if (g.fold)                                                                                  \
+        if (masked) {                                                                                \
+            if (g.stream_out) hipLaunchKernelGGL((gemm_i4_kernel<EPI, KS_LONG, true, kWaves, false, false, false, false, true>), grid, block, 0, stream, g); \
+            else hipLaunchKernelGGL((gemm_i4_kernel<EPI, KS_LONG, false, kWaves, false, false, false, false, true>), grid, block, 0, stream, g); \
+        } else if (g.fold)                                                                           \
             hipLaunchKernelGGL((gemm_i4_kernel<EPI, KS_LONG, false, kWaves, false, true>), grid, block, 0, stream, g); \
         else if (narrow) {                                                                           \
             if (g.stream_out) hipLaunchKernelGGL((gemm_i4_kernel<EPI, KS_LONG, true, kWaves, false, false, false, true>), grid, block, 0, stream, g); \

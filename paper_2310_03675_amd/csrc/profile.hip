@@ -35,7 +35,7 @@ const char* kernel_name(int id)
         "gemm_i4", "fwht_dual_absmax", "fwht_dual_quant", "gemm_i4_fwd", "gemm_i4_bwd_input",
         "gemm_i4_bwd_weight", "fwht_dual_absmax_X", "fwht_dual_absmax_W", "fwht_dual_absmax_G",
         "fwht_dual_quant_X", "fwht_dual_quant_W", "fwht_dual_quant_G", "fwht_dual_absmax_batch",
-        "fwht_dual_quant_batch", "requant_tile_sums", "requant_quantize_sum", "im2col"};
+        "fwht_dual_quant_batch", "requant_tile_sums", "requant_quantize_sum", "im2col", "relu_mask"};
     return (id >= 0 && id < K_COUNT) ? names[id] : "?";
 }
 
