@@ -377,6 +377,17 @@ def main():
         line["quantize_1GiB"].update({k_: v_ for k_, v_ in line["quantize_1GiB"]["axis1_n64"].items() if k_ != "kernels"})
         del big
     if not args.no_square:
+        # The matrix pipe's own rate and the shader clock under that load, for three kinds of
+        # operands (hdqt_probe_matrix_clock: independent MFMAs on fragments held in registers,
+        # nothing else running): the rooflines above are priced at the published 2.4 GHz peak,
+        # the chip's power management sets the clock by what the operands make the pipe switch.
+        line["matrix_clock_probe"] = {}
+        gen_p = torch.Generator(device="cpu").manual_seed(7)
+        codes_p = torch.clamp(torch.round(torch.randn(8192, generator=gen_p) * 1.5), -8, 7).to(torch.int8)
+        for kind_p, frag_p in (("zeros", torch.zeros(8192, dtype=torch.uint8)),
+                               ("codes_times_16", (codes_p * 16).view(torch.uint8)),
+                               ("random_bytes", torch.randint(0, 256, (8192,), generator=gen_p, dtype=torch.uint8))):
+            line["matrix_clock_probe"][kind_p] = B.probe_matrix_clock(frag_p.to(dev))
         # The integer matmul alone where the matrix pipe is the roofline: 4096^3 on the codes
         # of the square sweep's operands (N(0,1) with 1 % outliers at +-20, Hadamard block 64,
         # 4-bit nearest), 8-bit accumulators, tiles of 32 and 64.

@@ -32,6 +32,7 @@ EXPORTED = [
     "hdqt_conv_step", "hdqt_conv_fwd", "hdqt_conv_bwd", "hdqt_gemm_codes_fold", "hdqt_im2col",
     "hdqt_gemm_fwd_static", "hdqt_gemm_fwd_static_max_bytes",
     "hdqt_gemm_bwd_input_masked", "hdqt_layer_bwd_masked", "hdqt_conv_bwd_masked",
+    "hdqt_probe_matrix_clock", "hdqt_wall_clock_khz",
 ]
 
 
@@ -176,6 +177,10 @@ def load() -> C.CDLL:
     lib.hdqt_layer_bwd_masked.argtypes = [vp] * 6 + [i64, i64, i64] + [C.POINTER(CParams)] * 2 + [vp, sz, vp]
     lib.hdqt_conv_bwd_masked.restype = i32
     lib.hdqt_conv_bwd_masked.argtypes = [vp, vp, vp, C.POINTER(CConv), vp, vp, vp, i64] + [C.POINTER(CParams)] * 2 + [vp, sz, vp]
+    lib.hdqt_wall_clock_khz.restype = i32
+    lib.hdqt_wall_clock_khz.argtypes = []
+    lib.hdqt_probe_matrix_clock.restype = i32
+    lib.hdqt_probe_matrix_clock.argtypes = [vp, i32, vp, vp, sz, vp]
     lib.hdqt_gemm_fwd_static.restype = i32
     lib.hdqt_gemm_fwd_static.argtypes = [vp, vp, vp, i64, i64, i64, C.POINTER(CParams), vp, vp]
     lib.hdqt_gemm_fwd_static_max_bytes.restype = sz
@@ -426,6 +431,35 @@ def gemm(kind: int, P: torch.Tensor, Q: torch.Tensor, M: int, K: int, N: int, pa
     if rc:
         raise HdqtError(rc, fn)
     return out, acc, workspace
+
+
+def probe_matrix_clock(fragments: torch.Tensor, iters: int = 4000):
+    """hdqt_probe_matrix_clock -> dict: the matrix pipe's rate on the given operand fragments
+    (8 KiB uint8 on the device) and the shader clock under that load.  The rate is taken from
+    the whole launch's duration (HIP events): 1024 workgroups x 4 waves x 16 * iters MFMAs over
+    the chip's 1024 SIMDs; the clock from one wave's cycle and wall-clock counters."""
+    _check_dev(fragments)
+    assert fragments.dtype == torch.uint8 and fragments.numel() >= 8192
+    result = torch.zeros(2, dtype=torch.int64, device=fragments.device)
+    scratch = torch.empty(1 << 20, dtype=torch.uint8, device=fragments.device)
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    for rep in range(2):       # the first launch warms the clock up
+        if rep == 1:
+            e0.record()
+        rc = load().hdqt_probe_matrix_clock(_ptr(fragments), iters, _ptr(result), _ptr(scratch), scratch.numel(),
+                                            _stream(None))
+        if rc:
+            raise HdqtError(rc, "hdqt_probe_matrix_clock")
+    e1.record()
+    torch.cuda.synchronize()
+    cycles, ticks = (int(v) for v in result.cpu())
+    wall_khz = load().hdqt_wall_clock_khz() or 100000
+    mhz = cycles / (ticks * 1e3 / wall_khz)
+    ns_per_mfma = e0.elapsed_time(e1) * 1e6 / (4.0 * 16.0 * iters)       # per SIMD
+    return {"shader_clock_mhz": mhz, "ns_per_mfma_per_simd": ns_per_mfma,
+            "cycles_per_mfma_per_simd": ns_per_mfma * mhz * 1e-3,
+            "TOPs": 65536.0 * 1024.0 / ns_per_mfma / 1e3,
+            "frac_of_published_peak": 65536.0 * 1024.0 / ns_per_mfma / 1e3 / 5000.0}
 
 
 def gemm_fwd_static(X: torch.Tensor, W: torch.Tensor, params: Params, out: torch.Tensor,

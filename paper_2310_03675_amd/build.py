@@ -9,7 +9,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libhdqt.so")
 OBJ_DIR = os.path.join(HERE, "_build")
-SOURCES = ["api.hip", "quantize.hip", "quantize_fast.hip", "quantize_dual.hip", "gemm.hip", "gemm_fast.hip", "im2col.hip", "profile.hip"]
+SOURCES = ["api.hip", "quantize.hip", "quantize_fast.hip", "quantize_dual.hip", "gemm.hip", "gemm_fast.hip", "im2col.hip", "profile.hip", "probe.hip"]
 
 # -ffp-contract=off: every binary32 operation of the quantizer rounds on its own,
 # as in the definition the results are checked against.
