@@ -387,7 +387,8 @@ def main():
         for kind_p, frag_p in (("zeros", torch.zeros(8192, dtype=torch.uint8)),
                                ("codes_times_16", (codes_p * 16).view(torch.uint8)),
                                ("random_bytes", torch.randint(0, 256, (8192,), generator=gen_p, dtype=torch.uint8))):
-            line["matrix_clock_probe"][kind_p] = B.probe_matrix_clock(frag_p.to(dev))
+            line["matrix_clock_probe"][kind_p] = {f"{w_}_waves_per_simd": B.probe_matrix_clock(frag_p.to(dev), waves_per_simd=w_)
+                                                  for w_ in (2, 4)}
         # The integer matmul alone where the matrix pipe is the roofline: 4096^3 on the codes
         # of the square sweep's operands (N(0,1) with 1 % outliers at +-20, Hadamard block 64,
         # 4-bit nearest), 8-bit accumulators, tiles of 32 and 64.

@@ -477,18 +477,19 @@ int hdqt_profile_collect(hdqt_kernel_time_t *rows, int max_rows);
 /*
  * Measurement aid for benchmarks (no step of the paper): the rate of the int8 matrix pipe and
  * the shader clock under that load, which on this chip depends on the operands' switching
- * activity.  1024 workgroups of 4 waves loop `iters` times over 16 independent
+ * activity.  256 * waves_per_simd workgroups of 4 waves (waves_per_simd in 1..4: that many
+ * waves share every SIMD of the chip's 256 CUs) loop `iters` times over 16 independent
  * v_mfma_i32_32x32x32_i8 on the operand fragments in `fragments` (8 KiB, device: eight
  * fragments of 64 lanes x 16 int8), registers only.
  *   result   two int64 (device, 8-byte aligned): shader-clock cycles and wall-clock ticks
  *            (hipDeviceAttributeWallClockRate) that one wave spent in its loop, i.e. on
- *            16 * iters MFMAs sharing a SIMD with three other waves doing the same
+ *            16 * iters MFMAs (the launch's duration, timed by the caller, gives the rate)
  *   scratch  1 MiB of device memory the kernel may overwrite
- * HDQT_EINVAL_DIM for iters outside [1, 2^20].
+ * HDQT_EINVAL_DIM for iters outside [1, 2^20] or waves_per_simd outside [1, 4].
  */
 int hdqt_wall_clock_khz(void);      /* rate of those ticks on the current device, 0 if unknown (host) */
-int hdqt_probe_matrix_clock(const void *fragments, int iters, long long *result, void *scratch,
-                            size_t scratch_bytes, void *stream);
+int hdqt_probe_matrix_clock(const void *fragments, int iters, int waves_per_simd, long long *result,
+                            void *scratch, size_t scratch_bytes, void *stream);
 
 /* Text for an error code (static string, host). */
 const char *hdqt_strerror(int code);

@@ -180,7 +180,7 @@ def load() -> C.CDLL:
     lib.hdqt_wall_clock_khz.restype = i32
     lib.hdqt_wall_clock_khz.argtypes = []
     lib.hdqt_probe_matrix_clock.restype = i32
-    lib.hdqt_probe_matrix_clock.argtypes = [vp, i32, vp, vp, sz, vp]
+    lib.hdqt_probe_matrix_clock.argtypes = [vp, i32, i32, vp, vp, sz, vp]
     lib.hdqt_gemm_fwd_static.restype = i32
     lib.hdqt_gemm_fwd_static.argtypes = [vp, vp, vp, i64, i64, i64, C.POINTER(CParams), vp, vp]
     lib.hdqt_gemm_fwd_static_max_bytes.restype = sz
@@ -433,10 +433,10 @@ def gemm(kind: int, P: torch.Tensor, Q: torch.Tensor, M: int, K: int, N: int, pa
     return out, acc, workspace
 
 
-def probe_matrix_clock(fragments: torch.Tensor, iters: int = 4000):
+def probe_matrix_clock(fragments: torch.Tensor, iters: int = 4000, waves_per_simd: int = 2):
     """hdqt_probe_matrix_clock -> dict: the matrix pipe's rate on the given operand fragments
     (8 KiB uint8 on the device) and the shader clock under that load.  The rate is taken from
-    the whole launch's duration (HIP events): 1024 workgroups x 4 waves x 16 * iters MFMAs over
+    the whole launch's duration (HIP events): waves_per_simd waves x 16 * iters MFMAs on each of
     the chip's 1024 SIMDs; the clock from one wave's cycle and wall-clock counters."""
     _check_dev(fragments)
     assert fragments.dtype == torch.uint8 and fragments.numel() >= 8192
@@ -446,8 +446,8 @@ def probe_matrix_clock(fragments: torch.Tensor, iters: int = 4000):
     for rep in range(2):       # the first launch warms the clock up
         if rep == 1:
             e0.record()
-        rc = load().hdqt_probe_matrix_clock(_ptr(fragments), iters, _ptr(result), _ptr(scratch), scratch.numel(),
-                                            _stream(None))
+        rc = load().hdqt_probe_matrix_clock(_ptr(fragments), iters, waves_per_simd, _ptr(result), _ptr(scratch),
+                                            scratch.numel(), _stream(None))
         if rc:
             raise HdqtError(rc, "hdqt_probe_matrix_clock")
     e1.record()
@@ -455,8 +455,8 @@ def probe_matrix_clock(fragments: torch.Tensor, iters: int = 4000):
     cycles, ticks = (int(v) for v in result.cpu())
     wall_khz = load().hdqt_wall_clock_khz() or 100000
     mhz = cycles / (ticks * 1e3 / wall_khz)
-    ns_per_mfma = e0.elapsed_time(e1) * 1e6 / (4.0 * 16.0 * iters)       # per SIMD
-    return {"shader_clock_mhz": mhz, "ns_per_mfma_per_simd": ns_per_mfma,
+    ns_per_mfma = e0.elapsed_time(e1) * 1e6 / (waves_per_simd * 16.0 * iters)       # per SIMD
+    return {"waves_per_simd": waves_per_simd, "shader_clock_mhz": mhz, "ns_per_mfma_per_simd": ns_per_mfma,
             "cycles_per_mfma_per_simd": ns_per_mfma * mhz * 1e-3,
             "TOPs": 65536.0 * 1024.0 / ns_per_mfma / 1e3,
             "frac_of_published_peak": 65536.0 * 1024.0 / ns_per_mfma / 1e3 / 5000.0}

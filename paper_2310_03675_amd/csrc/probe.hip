@@ -6,7 +6,9 @@
 // cycles run at falls with the switching activity of the operands (power management):
 // all-zero operands, quantizer-like codes and random bytes give different clocks.  This
 // kernel measures it: every wave loops over independent MFMAs on operand fragments read once
-// from a caller-supplied buffer (registers only, nothing else competes), and one wave reports
+// from a caller-supplied buffer (registers only, nothing else competes; one to four waves per
+// SIMD: with one or two the pipe takes an MFMA every 32 cycles, with four waves taking turns
+// it took 46 to 53 cycles per MFMA on the machines measured), and one wave reports
 // its shader-clock cycles (s_memtime) and the constant-rate wall clock (s_memrealtime) around
 // the loop.  bench.py prints the result next to the rooflines that are priced at 2.4 GHz.
 
@@ -64,12 +66,13 @@ int hdqt_wall_clock_khz(void)
     return khz;
 }
 
-int hdqt_probe_matrix_clock(const void* fragments, int iters, long long* result, void* scratch,
-                            size_t scratch_bytes, void* stream)
+int hdqt_probe_matrix_clock(const void* fragments, int iters, int waves_per_simd, long long* result,
+                            void* scratch, size_t scratch_bytes, void* stream)
 {
-    constexpr int kBlocks = 1024, kThreads = 256;       // four waves per SIMD on 256 CUs
+    constexpr int kThreads = 256;                       // a workgroup is one wave on each SIMD of a CU
     if (!fragments || !result || !scratch) return HDQT_EINVAL_NULL;
-    if (iters < 1 || iters > (1 << 20)) return HDQT_EINVAL_DIM;
+    if (iters < 1 || iters > (1 << 20) || waves_per_simd < 1 || waves_per_simd > 4) return HDQT_EINVAL_DIM;
+    const int kBlocks = 256 * waves_per_simd;           // 256 CUs
     if (scratch_bytes < (size_t)kBlocks * kThreads * sizeof(int)) return HDQT_EWORKSPACE;
     if ((reinterpret_cast<uintptr_t>(fragments) & 15u) || (reinterpret_cast<uintptr_t>(result) & 7u)) return HDQT_EALIGN;
     hipLaunchKernelGGL(hdqt::matrix_clock_kernel, dim3(kBlocks), dim3(kThreads), 0, static_cast<hipStream_t>(stream),
