@@ -620,12 +620,15 @@ def main():
         B.profile_enable(False)
         kern2 = B.profile_collect()
         tiles = (K + args.s - 1) // args.s
-        slab = 4.0 * tiles * M * N                 # all tile sums, written once and read once
+        kus = {n_: tot / l * 1e3 for n_, (l, tot) in kern2.items()}
         line["requant_fwd"] = {
-            "ms": dt2 * 1e3, "tiles": tiles, "tile_sum_bytes": slab,
-            "kernels_us": {n_: tot / l * 1e3 for n_, (l, tot) in kern2.items() if n_.startswith("requant")},
-            "tile_sums_write_GBps": slab / (kern2["requant_tile_sums"][1] / kern2["requant_tile_sums"][0] * 1e-3) / 1e9,
-            "quantize_sum_read_GBps": slab / (kern2["requant_quantize_sum"][1] / kern2["requant_quantize_sum"][0] * 1e-3) / 1e9}
+            # the whole call from the fp32 tensors (quantization of X and W included), and the
+            # matmul's own launches: pass 1 (tile maxima), pass 2 (quantize and add the tile sums)
+            "ms": dt2 * 1e3, "tiles": tiles, "workspace_bytes": need,
+            "tile_sums_materialised_bytes": 0 if need < 4.0 * tiles * M * N else 4.0 * tiles * M * N,
+            "kernels_us": kus,
+            "matmul_us": sum(v for n_, v in kus.items() if n_.startswith("requant") or n_ == "reduce"),
+            "matmul_TOPs_two_passes": 2 * 2.0 * M * K * N / (sum(v for n_, v in kus.items() if n_.startswith("requant")) * 1e-6) / 1e12}
         del ws2
     if not args.no_others and not args.separate:
         # One step of the other layer workloads (not `value`): the HAR-style 1-D convolution layer

@@ -252,13 +252,22 @@ int hdqt_gemm_codes_bf16(const void *qA, const void *qB, int bA, int bB, const f
  *   acc[i,j] = sum_t c_t[i,j] * m_t     (exact)      out = (float)acc * 2^-(a-1) * scaleA*scaleB / n_eff
  * Arguments as for hdqt_gemm_codes; acc_bits 2..24; acc_out (nullable) receives acc.
  * HDQT_EINVAL_TILE if a tile sum may not be exact in binary32 (s * 2^(bA+bB-2) >= 2^24),
- * HDQT_EINVAL_ACC if acc may leave int32.  This is an emulation of the reading, not a
- * fast path: all tile sums are materialised (workspace
- * hdqt_gemm_codes_requant_workspace_size = ceil(D/s) * RA*RB*4 bytes plus the maxima).
+ * HDQT_EINVAL_ACC if acc may leave int32.
+ * Packed 4-bit codes on both sides, D and s multiples of 32, acc_bits <= 16 (and at most
+ * 512 tiles per part of a split contraction): two passes through the matrix-core kernel,
+ * the first keeping only the maxima m_t, the second quantizing every tile sum as it is
+ * produced; no tile sum is stored, and the workspace holds the maxima and, for a split
+ * contraction, one int32 slice of the output per part.  Everything else: an emulation that
+ * materialises all tile sums (ceil(D/s) * RA*RB*4 bytes plus the maxima).
+ * hdqt_gemm_codes_requant_workspace_size is the latter, an upper bound for every operand
+ * width; hdqt_gemm_codes_requant_workspace_size_for is what the call with these widths
+ * needs (0 for arguments the call would reject), and the call accepts either.
  * hdqt_gemm_requant is the same for one of the three matmuls of a step, from the fp32
  * tensors (P, Q = X, W / G, W / X, G for the three kinds).
  */
 size_t hdqt_gemm_codes_requant_workspace_size(int64_t RA, int64_t RB, int64_t D, int64_t s);
+size_t hdqt_gemm_codes_requant_workspace_size_for(int64_t RA, int64_t RB, int64_t D, int64_t s,
+                                                  int bA, int bB, int acc_bits);
 int hdqt_gemm_codes_requant(const void *qA, const void *qB, int bA, int bB, const float *scaleA,
                             const float *scaleB, int64_t RA, int64_t RB, int64_t D, int n_eff,
                             int acc_bits, int64_t s, float *out, int32_t *acc_out,

@@ -26,7 +26,8 @@ EXPORTED = [
     "hdqt_quantize_dual_workspace_size", "hdqt_layer_step_workspace_size", "hdqt_layer_step",
     "hdqt_gemm_codes_workspace_size", "hdqt_layer_saved_size", "hdqt_layer_fwd_workspace_size",
     "hdqt_layer_fwd", "hdqt_layer_bwd_workspace_size", "hdqt_layer_bwd",
-    "hdqt_gemm_codes_requant_workspace_size", "hdqt_gemm_codes_requant",
+    "hdqt_gemm_codes_requant_workspace_size", "hdqt_gemm_codes_requant_workspace_size_for",
+    "hdqt_gemm_codes_requant",
     "hdqt_gemm_requant_workspace_size", "hdqt_gemm_requant", "hdqt_gemm_codes_bf16",
     "hdqt_gemm_bwd_input_bf16", "hdqt_quantize_dual_im2col", "hdqt_conv_step_workspace_size",
     "hdqt_conv_step", "hdqt_conv_fwd", "hdqt_conv_bwd", "hdqt_gemm_codes_fold", "hdqt_im2col",
@@ -123,6 +124,8 @@ def load() -> C.CDLL:
     lib.hdqt_gemm_codes_workspace_size.argtypes = [i64, i64, i64, i64]
     lib.hdqt_gemm_codes_requant_workspace_size.restype = sz
     lib.hdqt_gemm_codes_requant_workspace_size.argtypes = [i64, i64, i64, i64]
+    lib.hdqt_gemm_codes_requant_workspace_size_for.restype = sz
+    lib.hdqt_gemm_codes_requant_workspace_size_for.argtypes = [i64, i64, i64, i64, i32, i32, i32]
     lib.hdqt_gemm_codes_requant.restype = i32
     lib.hdqt_gemm_codes_requant.argtypes = [vp, vp, i32, i32, vp, vp, i64, i64, i64, i32, i32, i64, vp, vp,
                                             vp, sz, vp]
@@ -665,7 +668,7 @@ def gemm_codes_requant(qA: torch.Tensor, qB: torch.Tensor, bA: int, bB: int, sca
     out = torch.empty((RA, RB), dtype=torch.float32, device=qA.device)
     acc = torch.empty((RA, RB), dtype=torch.int32, device=qA.device) if want_acc else None
     if workspace is None:
-        need = load().hdqt_gemm_codes_requant_workspace_size(RA, RB, D, s)
+        need = load().hdqt_gemm_codes_requant_workspace_size_for(RA, RB, D, s, bA, bB, acc_bits)
         workspace = torch.empty(max(need, 256), dtype=torch.uint8, device=qA.device)
     rc = load().hdqt_gemm_codes_requant(_ptr(qA), _ptr(qB), bA, bB, _ptr(scaleA), _ptr(scaleB), RA, RB, D,
                                         n, acc_bits, s, _ptr(out), _ptr(acc), _ptr(workspace),

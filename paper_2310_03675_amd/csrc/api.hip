@@ -529,6 +529,7 @@ int check_requant(int64_t RA, int64_t RB, int64_t D, int64_t s, int acc_bits, in
     return HDQT_OK;
 }
 
+// workspace of the emulation: the maxima and every tile's sums ([n_tiles, RA, RB] int32)
 size_t requant_bytes(int64_t RA, int64_t RB, int64_t D, int64_t s)
 {
     const int64_t s_eff = s < D ? s : D;
@@ -537,19 +538,47 @@ size_t requant_bytes(int64_t RA, int64_t RB, int64_t D, int64_t s)
            (size_t)n_tiles * (size_t)(RA * RB) * sizeof(int32_t);
 }
 
+hdqt::GemmArgs plan_requant(const void* qA, const void* qB, int bA, int bB, const float* scaleA,
+                            const float* scaleB, int64_t RA, int64_t RB, int64_t D, int n_eff, int64_t s,
+                            float* out, int32_t* acc_out)
+{
+    // (the tiles are what this reading quantizes: they stay as given)
+    return plan_gemm(qA, qB, bA, bB, scaleA, scaleB, RA, RB, D, n_eff, 32, s, out, acc_out, 0, nullptr, true);
+}
+
+// workspace of the path that will run: the two passes through the matrix-core kernel keep
+// only the maxima (and, with a split contraction, one int32 slice per part)
+size_t requant_bytes_for(int64_t RA, int64_t RB, int64_t D, int64_t s, int bA, int bB, int acc_bits)
+{
+    const hdqt::GemmArgs g = plan_requant(nullptr, nullptr, bA, bB, nullptr, nullptr, RA, RB, D, 1, s, nullptr, nullptr);
+    if (!hdqt::gemm_requant_fast_eligible(g, acc_bits)) return requant_bytes(RA, RB, D, s);
+    return align_up((size_t)g.n_tiles * sizeof(uint32_t), 256) +
+           (g.splits > 1 ? (size_t)g.splits * (size_t)(RA * RB) * sizeof(int32_t) : 0);
+}
+
 int run_requant(const void* qA, const void* qB, int bA, int bB, const float* scaleA, const float* scaleB,
                 int64_t RA, int64_t RB, int64_t D, int n_eff, int acc_bits, int64_t s, float* out,
                 int32_t* acc_out, void* ws, size_t ws_bytes, hipStream_t stream)
 {
-    if (!ws || ws_bytes < requant_bytes(RA, RB, D, s)) return HDQT_EWORKSPACE;
-    // (the tiles are what this reading quantizes: they stay as given)
-    hdqt::GemmArgs g = plan_gemm(qA, qB, bA, bB, scaleA, scaleB, RA, RB, D, n_eff, 32, s, out, acc_out, 0,
-                                 nullptr, true);
+    if (!ws || ws_bytes < requant_bytes_for(RA, RB, D, s, bA, bB, acc_bits)) return HDQT_EWORKSPACE;
+    hdqt::GemmArgs g = plan_requant(qA, qB, bA, bB, scaleA, scaleB, RA, RB, D, n_eff, s, out, acc_out);
     char* base = static_cast<char*>(ws);
     g.tile_max = reinterpret_cast<uint32_t*>(base);
     g.partial = reinterpret_cast<int32_t*>(base + align_up((size_t)g.n_tiles * sizeof(uint32_t), 256));
     hipError_t e = hdqt::launch_zero2(g.tile_max, g.n_tiles, nullptr, 0, stream);
     if (e != hipSuccess) return hip_fail(e);
+    if (hdqt::gemm_requant_fast_eligible(g, acc_bits)) {
+        // value = acc * 2^-(a-1) * (scaleA * scaleB) / n_eff: both trailing factors are powers of two
+        g.inv_n = g.inv_n * ldexpf(1.0f, -(acc_bits - 1));
+        e = hdqt::launch_gemm_requant_fast(g, acc_bits, 1, stream);
+        if (e != hipSuccess) return hip_fail(e);
+        e = hdqt::launch_gemm_requant_fast(g, acc_bits, 2, stream);
+        if (e != hipSuccess) return hip_fail(e);
+        if (g.splits > 1)
+            e = hdqt::launch_reduce(g.partial, g.splits, g.RA * g.RB, g.scaleA, g.scaleB, g.inv_n, g.out, nullptr,
+                                    g.acc_out, stream);
+        return e == hipSuccess ? HDQT_OK : hip_fail(e);
+    }
     e = hdqt::launch_gemm_requant(g, acc_bits, stream);
     return e == hipSuccess ? HDQT_OK : hip_fail(e);
 }
@@ -737,6 +766,15 @@ size_t hdqt_gemm_codes_requant_workspace_size(int64_t RA, int64_t RB, int64_t D,
     return requant_bytes(RA, RB, D, s);
 }
 
+size_t hdqt_gemm_codes_requant_workspace_size_for(int64_t RA, int64_t RB, int64_t D, int64_t s, int bA,
+                                                  int bB, int acc_bits)
+{
+    if (RA <= 0 || RB <= 0 || D <= 0 || s < 1 || RA >= kMaxDim || RB >= kMaxDim || D >= kMaxDim) return 0;
+    if (bA < 2 || bA > 8 || bB < 2 || bB > 8) return 0;
+    if (check_requant(RA, RB, D, s, acc_bits, bA, bB)) return 0;
+    return requant_bytes_for(RA, RB, D, s, bA, bB, acc_bits);
+}
+
 int hdqt_gemm_codes_requant(const void* qA, const void* qB, int bA, int bB, const float* scaleA,
                             const float* scaleB, int64_t RA, int64_t RB, int64_t D, int n_eff,
                             int acc_bits, int64_t s, float* out, int32_t* acc_out, void* workspace,
@@ -762,7 +800,7 @@ size_t hdqt_gemm_requant_workspace_size(int gemm_kind, int64_t M, int64_t K, int
     hdqt_ws_layout_t L;
     if (hdqt_workspace_layout(gemm_kind, M, K, N, params, &L) != HDQT_OK) return 0;
     if (check_requant(L.RA, L.RB, L.D, params->s, params->acc_bits, params->A.b, params->B.b)) return 0;
-    return L.acc + requant_bytes(L.RA, L.RB, L.D, params->s);
+    return L.acc + requant_bytes_for(L.RA, L.RB, L.D, params->s, params->A.b, params->B.b, params->acc_bits);
 }
 
 int hdqt_gemm_requant(int gemm_kind, const float* P, const float* Q, float* out, int64_t M, int64_t K,
@@ -775,7 +813,8 @@ int hdqt_gemm_requant(int gemm_kind, const float* P, const float* Q, float* out,
     if ((rc = check_requant(L.RA, L.RB, L.D, params->s, params->acc_bits, params->A.b, params->B.b)))
         return rc;
     if (!P || !Q || (!out && !acc_out)) return HDQT_EINVAL_NULL;
-    if (!workspace || workspace_bytes < L.acc + requant_bytes(L.RA, L.RB, L.D, params->s))
+    if (!workspace || workspace_bytes < L.acc + requant_bytes_for(L.RA, L.RB, L.D, params->s, params->A.b,
+                                                                  params->B.b, params->acc_bits))
         return HDQT_EWORKSPACE;
     if (misaligned(P) || misaligned(Q) || misaligned(out) || misaligned(acc_out) || misaligned(workspace))
         return HDQT_EALIGN;

@@ -94,6 +94,8 @@ struct GemmArgs {
     int32_t* partial;       // [splits, RA, RB] when splits > 1: one slice per part of the contraction;
                             // second reading of the accumulator: [n_tiles, RA, RB], every tile's sums
     uint32_t* tile_max;     // second reading only: max |tile sum| per tile, zero beforehand
+    int req_bits;           // second reading in the matrix-core kernel: a, and the clamp bounds
+    float req_lo, req_hi;   // -2^(a-1) and 2^(a-1) - 1, each plus 1.5 * 2^23
     int stream_out;         // fp32 output too large to stay cached: written with streaming stores
     int profile_tag;        // which matmul of the step this is (timing table only): 0 none, 1 + kind
     int splits;             // workgroups sharing one output tile along the contraction
@@ -130,6 +132,13 @@ hipError_t launch_gemm(const GemmArgs& g, hipStream_t stream);
 // Second reading of the low-bit accumulator: every tile's partial sums to g.partial and their
 // maxima to g.tile_max, then Q with acc_bits per tile and the sum over tiles (see gemm.hip).
 hipError_t launch_gemm_requant(const GemmArgs& g, int acc_bits, hipStream_t stream);
+// The same result without storing a tile sum, for the shapes the matrix-core kernel takes
+// (gemm_requant_fast_eligible): pass 1 multiplies and keeps only g.tile_max, pass 2 multiplies
+// again and quantizes every tile sum with its tile's maximum as it leaves the matrix core.
+// With a split contraction pass 2 writes its parts' totals to g.partial ([splits, RA, RB]),
+// which launch_reduce then adds; g.inv_n carries the factor 2^-(a-1) in that case and here.
+bool gemm_requant_fast_eligible(const GemmArgs& g, int acc_bits);
+hipError_t launch_gemm_requant_fast(const GemmArgs& g, int acc_bits, int pass, hipStream_t stream);
 constexpr int kMaxDualBatch = 3;
 // the two passes of the two-axis quantization, each for up to kMaxDualBatch tensors in one launch
 hipError_t launch_dual_pass1(const DualArgs* qs, int n, hipStream_t stream);

@@ -51,7 +51,23 @@ constexpr int KSTEP = 32;             // codes per MFMA
 constexpr int kScaleShift = 8;        // both operands carry a factor 16
 
 enum Epilogue { EPI_GENERIC = 0, EPI_SAT8_S32 = 1, EPI_SAT8_S64 = 2, EPI_STAGES = 3, EPI_SAT16_S32 = 4,
-                EPI_SAT16_S64 = 5, EPI_SAT8_S16 = 6, EPI_SAT16_S16 = 7, EPI_CLAMP_S16 = 8 };
+                EPI_SAT16_S64 = 5, EPI_SAT8_S16 = 6, EPI_SAT16_S16 = 7, EPI_CLAMP_S16 = 8,
+                EPI_REQ_MAX = 9, EPI_REQ_SUM = 10, EPI_REQ_MAX_S32 = 11, EPI_REQ_SUM_S32 = 12 };
+// EPI_REQ_MAX / EPI_REQ_SUM: the second reading of the low-bit accumulator (Methodology, tiled
+// quantization: every tile's partial-sum tensor through Q with a bits and its own maximum) as
+// two passes over the same product, neither of which stores a tile sum.  The first keeps, per
+// tile of the contraction, the largest magnitude over the whole output (registers -> wave ->
+// a table in LDS -> one atomic per workgroup and tile into g.tile_max); the second repeats the
+// multiplication and, with m_t known, quantizes each tile sum where it leaves the matrix core:
+//     c = clamp(RNE(fl(float(P) * fl(2^(a-1) / m_t)))),   total += c * m_t.
+// Five vector instructions per tile sum: conversion, multiplication, the addition of 1.5 * 2^23
+// (whose rounding is the round-to-nearest-even, and whose low mantissa bits are then 2^22 + c),
+// the clamp against bounds carrying the same offset, and a 24-bit multiply-add with m_t; the
+// offsets' contribution, 2^22 * sum of m_t, is subtracted once per output element (modulo
+// 2^32, like every step; the true total fits, which the caller has checked).
+// The _S32 instances are those for tiles of one 32-code step (no running tile sum to keep).
+constexpr int kReqTable = 512;         // tiles of one part of the contraction (table entries in LDS)
+constexpr float kReqMagic = 12582912.0f;   // 1.5 * 2^23
 // EPI_CLAMP_S16: tiles of 16 codes with the compare-select clamp, for the accumulator widths
 // neither conversion trick covers (fewer bits than bA + bB).
 // The _S16 instances (tiles of 16 codes) split every 32-code step into two
@@ -222,7 +238,11 @@ __global__ __launch_bounds__(64 * WAVES, WAVES == 8 ? (MASK ? 3 : 4) : 2) void g
     static_assert(!WIDE || !kSat8, "the 8-bit clamp trick needs the factor 256 of the nibble unpack");
     constexpr int SHIFT = WIDE ? 0 : kScaleShift;      // factor the totals carry, as a shift
     // factor left in a finished total, as a shift: none after the 8-bit trick
-    const int fin_shift = kSat16 ? g.fin_shift : (kSat8 ? 0 : SHIFT);
+    constexpr bool kReqMax = (EPI == EPI_REQ_MAX || EPI == EPI_REQ_MAX_S32);
+    constexpr bool kReqSum = (EPI == EPI_REQ_SUM || EPI == EPI_REQ_SUM_S32), kReq = kReqMax || kReqSum;
+    constexpr bool kReqS32 = (EPI == EPI_REQ_MAX_S32 || EPI == EPI_REQ_SUM_S32);
+    static_assert(!kReq || (!BF16 && !FOLD && !WIDE && !NARROW && !MASK), "second reading: plain packed instances only");
+    const int fin_shift = kSat16 ? g.fin_shift : ((kSat8 || kReq) ? 0 : SHIFT);
     const uint32_t low_clear = kSat16 ? (0xFFFFu & (0xFFFFu << g.fin_shift)) * 0x00010001u : 0u;
     constexpr int REGS = WIDE ? 2 : 1;                 // 16-byte registers per unit in flight
     // WAVES = 4: each wave a 64 x 64 quarter (2 x 2 MFMA blocks).  WAVES = 8: each wave
@@ -240,6 +260,10 @@ __global__ __launch_bounds__(64 * WAVES, WAVES == 8 ? (MASK ? 3 : 4) : 2) void g
     static_assert(!kPairs64 || KS == KS_LONG, "a pair of 64-code tiles is one long stage");
     __shared__ __attribute__((aligned(16))) uint8_t As[2][TM][LDP];
     __shared__ __attribute__((aligned(16))) uint8_t Bs[2][TN][LDP];
+    // second reading: per tile of this part, the running maximum (times 256) in the first pass,
+    // m_t and fl(2^(a-1) / m_t) / 256 in the second
+    __shared__ int req_m[kReq ? kReqTable : 1];
+    __shared__ float req_inv[kReqSum ? kReqTable : 1];
 
     const int tid = threadIdx.x;
     const int lane = tid & 63, wave = tid >> 6;
@@ -269,6 +293,20 @@ __global__ __launch_bounds__(64 * WAVES, WAVES == 8 ? (MASK ? 3 : 4) : 2) void g
     if (k_begin >= k_end) return;         // not reached: every part has at least one tile
     const int steps_per_tile = (int)(g.s / KSTEP);
     const int lo = g.acc_lo_scaled, hi = g.acc_hi_scaled;
+    if constexpr (kReq) {
+        // (ordered before the first use by the barrier of the first stage)
+        const int n_local = (int)(t_end - t_begin);      // <= kReqTable (gemm_requant_fast_eligible)
+        for (int i = tid; i < kReqTable; i += NTHREADS) {
+            if constexpr (kReqMax) req_m[i] = 0;
+            else {
+                const uint32_t m = i < n_local ? g.tile_max[t_begin + i] : 0u;
+                req_m[i] = (int)m;
+                // binary64 quotient of two binary32-exact integers, rounded once more to binary32;
+                // the factor 2^-8 (exact) takes out the 256 the tile sums carry
+                req_inv[i] = m ? (float)((double)(1 << (g.req_bits - 1)) / (double)m) * 0.00390625f : 0.0f;
+            }
+        }
+    }
 
     // loader mapping: unit u = tid + NTHREADS*i -> row u / NSTEP, k-step u % NSTEP
     const int lrow = tid / NSTEP, lks = tid % NSTEP;
@@ -348,6 +386,47 @@ __global__ __launch_bounds__(64 * WAVES, WAVES == 8 ? (MASK ? 3 : 4) : 2) void g
                     const bool ok = interior || ((row0 + lane_row + rr < g.RA) && (col0 + lane_col + c * 32 < g.RB));
                     mk[a][c][r] = ok ? __builtin_nontemporal_load(&(mb + uo)[lane_off]) : 0.0f;
                 }
+    };
+
+    // ---- second reading: what happens to a finished tile's sums (p, times 256)
+    int req_tile = 0;                 // index of the tile inside this part
+    uint32_t req_corr = 0;            // second pass: sum of m_t over the tiles so far
+    auto req_finish = [&](v16i (&p)[RS][CS]) {
+        if constexpr (kReqMax) {
+            int mx = 0, mn = 0;
+#pragma unroll
+            for (int a = 0; a < RS; ++a)
+#pragma unroll
+                for (int c = 0; c < CS; ++c)
+#pragma unroll
+                    for (int r = 0; r < 16; r += 2) {
+                        mx = max(max(mx, p[a][c][r]), p[a][c][r + 1]);
+                        mn = min(min(mn, p[a][c][r]), p[a][c][r + 1]);
+                    }
+            int v = max(mx, -mn);      // >= 0: lanes the data-parallel moves fill with 0 change nothing
+            v = max(v, __builtin_amdgcn_update_dpp(0, v, 0xB1, 0xF, 0xF, true));      // quad_perm [1,0,3,2]
+            v = max(v, __builtin_amdgcn_update_dpp(0, v, 0x4E, 0xF, 0xF, true));      // quad_perm [2,3,0,1]
+            v = max(v, __builtin_amdgcn_update_dpp(0, v, 0x141, 0xF, 0xF, true));     // row_half_mirror
+            v = max(v, __builtin_amdgcn_update_dpp(0, v, 0x140, 0xF, 0xF, true));     // row_mirror
+            const int w = max(max(__builtin_amdgcn_readlane(v, 0), __builtin_amdgcn_readlane(v, 16)),
+                              max(__builtin_amdgcn_readlane(v, 32), __builtin_amdgcn_readlane(v, 48)));
+            if (lane == 0) atomicMax(&req_m[req_tile], w);
+        } else if constexpr (kReqSum) {
+            const uint32_t m = (uint32_t)__builtin_amdgcn_readfirstlane(req_m[req_tile]);
+            const float inv = __int_as_float(__builtin_amdgcn_readfirstlane(__float_as_int(req_inv[req_tile])));
+            req_corr += m;
+#pragma unroll
+            for (int a = 0; a < RS; ++a)
+#pragma unroll
+                for (int c = 0; c < CS; ++c)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) {
+                        const float v = (float)p[a][c][r] * inv;
+                        const float u = __builtin_amdgcn_fmed3f(v + kReqMagic, g.req_lo, g.req_hi);
+                        total[a][c][r] += (int)__umul24(__float_as_uint(u), m);
+                    }
+        }
+        ++req_tile;
     };
 
     // One stage: registers -> LDS buffer `buf`, barrier, refill the registers with
@@ -450,6 +529,47 @@ __global__ __launch_bounds__(64 * WAVES, WAVES == 8 ? (MASK ? 3 : 4) : 2) void g
                                                     : add_sat8_pair(total[a][c][r], p0[r], p1[r]);
                     }
             }
+        } else if (kReq) {
+#pragma unroll
+            for (int ks = 0; ks < NSTEP; ++ks) {
+                v4i fa[RS], fb[CS];
+#pragma unroll
+                for (int h = 0; h < HS; ++h) {
+                    if (h < RS) fa[h] = frag(As[buf], wm * WROWS + h * 32, ks);
+                    if (h < CS) fb[h] = frag(Bs[buf], wn * WCOLS + h * 32, ks);
+                }
+                // (positions at or beyond k_end are zero in LDS: such a step lies beyond the
+                // part's last tile and must not be counted as one)
+                const bool inside = c_k + ks * KSTEP < k_end;
+                if constexpr (kReqS32) {
+                    // every step is a tile: the matrix core starts from zero each time
+                    v16i p[RS][CS];
+#pragma unroll
+                    for (int a = 0; a < RS; ++a)
+#pragma unroll
+                        for (int c = 0; c < CS; ++c)
+                            p[a][c] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fa[a], fb[c], zero, 0, 0, 0);
+                    if (inside) req_finish(p);
+                } else {
+                    if (step_in_tile == 0) {
+#pragma unroll
+                        for (int a = 0; a < RS; ++a)
+#pragma unroll
+                            for (int c = 0; c < CS; ++c)
+                                part[a][c] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fa[a], fb[c], zero, 0, 0, 0);
+                    } else {
+#pragma unroll
+                        for (int a = 0; a < RS; ++a)
+#pragma unroll
+                            for (int c = 0; c < CS; ++c)
+                                part[a][c] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fa[a], fb[c], part[a][c], 0, 0, 0);
+                    }
+                    if (inside && ++step_in_tile == steps_per_tile) {
+                        step_in_tile = 0;
+                        req_finish(part);
+                    }
+                }
+            }
         } else if (EPI == EPI_STAGES) {
             v4i fa[NSTEP][RS], fb[NSTEP][CS];
 #pragma unroll
@@ -537,6 +657,27 @@ __global__ __launch_bounds__(64 * WAVES, WAVES == 8 ? (MASK ? 3 : 4) : 2) void g
                         total[a][c][r] += clamp3(part[a][c][r], lo, hi);
                         part[a][c][r] = 0;
                     }
+        }
+        if constexpr (kReq) {
+            if (step_in_tile != 0) {      // a short last tile (D not a multiple of s)
+                step_in_tile = 0;
+                req_finish(part);
+            }
+            req_tile = 0;
+            if constexpr (kReqMax) {      // the first pass writes nothing but the maxima, at the very end
+                c_k = k_begin;
+                c_ct += gridDim.z;
+                return;
+            }
+            // the second pass: take out the offsets 2^22 * m_t that came along with the codes
+            const uint32_t corr = req_corr << 22;
+            req_corr = 0;
+#pragma unroll
+            for (int a = 0; a < RS; ++a)
+#pragma unroll
+                for (int c = 0; c < CS; ++c)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) total[a][c][r] = (int)((uint32_t)total[a][c][r] - corr);
         }
         if constexpr (FOLD) {
             // ---- fold: the tile's accumulators go to LDS (int16: at most 255 tiles of +-128),
@@ -745,6 +886,14 @@ __global__ __launch_bounds__(64 * WAVES, WAVES == 8 ? (MASK ? 3 : 4) : 2) void g
             buf ^= 1;
         }
     }
+    if constexpr (kReqMax) {
+        // this workgroup's maxima (every output tile it walked) into the tensor's
+        __syncthreads();
+        for (int i = tid; i < (int)(t_end - t_begin); i += NTHREADS) {
+            const uint32_t m = (uint32_t)req_m[i] >> kScaleShift;
+            if (m) atomicMax(&g.tile_max[t_begin + i], m);
+        }
+    }
 }
 
 bool sat8_path(const GemmArgs& g) { return g.acc_hi == 127 && (g.s == 16 || g.s == 32 || g.s == 64); }
@@ -867,6 +1016,53 @@ static bool narrow_tiles(const GemmArgs& g)
 {
     if (g.RB > 64 || g.fold || g.out_bf16 || g.bA > 4 || g.s == 16 || g.mask_src) return false;
     return !sat16_path(g);
+}
+
+// Second reading of the accumulator in this kernel: packed 4-bit codes on both sides, tiles that
+// are whole 32-code steps, accumulators of at most 16 bits (the rounding by addition needs
+// |value| < 2^22), at most kReqTable tiles per part, tile sums times 256 inside int32.
+bool gemm_requant_fast_eligible(const GemmArgs& g, int acc_bits)
+{
+    if (g.bA > 4 || g.bB > 4 || g.fold || g.out_bf16 || g.mask_src) return false;
+    if (g.D % KSTEP != 0 || g.s % KSTEP != 0) return false;
+    if (acc_bits < 2 || acc_bits > 16) return false;
+    if (g.RB > ((int64_t)1 << 21)) return false;
+    if ((g.RA + 256) * g.pitchA >= ((int64_t)1 << 31) || (g.RB + 256) * g.pitchB >= ((int64_t)1 << 31)) return false;
+    if (g.tiles_per_split > kReqTable) return false;
+    return g.s * 64 < ((int64_t)1 << 22);
+}
+
+hipError_t launch_gemm_requant_fast(const GemmArgs& g_in, int acc_bits, int pass, hipStream_t stream)
+{
+    GemmArgs g = g_in;
+    g.req_bits = acc_bits;
+    g.req_lo = kReqMagic - (float)(1 << (acc_bits - 1));
+    g.req_hi = kReqMagic + (float)((1 << (acc_bits - 1)) - 1);
+    const int64_t n_ct = (g.RB + BN - 1) / BN, n_rt = (g.RA + BM - 1) / BM;
+    const int64_t stages = (g.tiles_per_split * g.s + KS_LONG - 1) / KS_LONG;
+    int64_t gx = n_ct;
+    if (stages <= 2) {
+        gx = (512 + n_rt * g.splits - 1) / (n_rt * g.splits);
+        if (gx > n_ct) gx = n_ct;
+        if (gx < 1) gx = 1;
+    }
+    const dim3 grid((unsigned)g.splits, (unsigned)n_rt, (unsigned)gx), block(64 * kWaves);
+    ProfileScope ps(pass == 1 ? K_REQUANT_TILES : K_REQUANT_SUM, stream);
+#define HDQT_LAUNCH_REQ(EPI, STREAM) \
+    hipLaunchKernelGGL((gemm_i4_kernel<EPI, KS_LONG, STREAM, kWaves, false, false>), grid, block, 0, stream, g)
+    const bool s32 = g.s == KSTEP;
+    if (pass == 1) {
+        if (s32) HDQT_LAUNCH_REQ(EPI_REQ_MAX_S32, false);
+        else HDQT_LAUNCH_REQ(EPI_REQ_MAX, false);
+    } else if (g.stream_out) {
+        if (s32) HDQT_LAUNCH_REQ(EPI_REQ_SUM_S32, true);
+        else HDQT_LAUNCH_REQ(EPI_REQ_SUM, true);
+    } else {
+        if (s32) HDQT_LAUNCH_REQ(EPI_REQ_SUM_S32, false);
+        else HDQT_LAUNCH_REQ(EPI_REQ_SUM, false);
+    }
+#undef HDQT_LAUNCH_REQ
+    return hipGetLastError();
 }
 
 hipError_t launch_gemm_fast(const GemmArgs& g_in, hipStream_t stream)

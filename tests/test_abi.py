@@ -265,6 +265,12 @@ def test_gemm_codes_requant_argument_errors():
     lib = B.load()
     assert lib.hdqt_gemm_codes_requant_workspace_size(8, 8, 64, 32) >= 2 * 8 * 8 * 4 + 2 * 4
     assert lib.hdqt_gemm_codes_requant_workspace_size(8, 0, 64, 32) == 0
+    # the exact size for given widths: no tile sums where the two-pass path runs, the bound elsewhere
+    assert 0 < lib.hdqt_gemm_codes_requant_workspace_size_for(8, 8, 64, 32, 4, 4, 8) < 2 * 8 * 8 * 4
+    assert lib.hdqt_gemm_codes_requant_workspace_size_for(8, 8, 64, 32, 8, 8, 8) == \
+        lib.hdqt_gemm_codes_requant_workspace_size(8, 8, 64, 32)
+    assert lib.hdqt_gemm_codes_requant_workspace_size_for(8, 8, 64, 32, 4, 4, 40) == 0
+    assert lib.hdqt_gemm_codes_requant_workspace_size_for(8, 8, 64, 32, 9, 4, 8) == 0
 
     def rc(qA=FAKE, bA=4, bB=4, RA=8, D=64, n=64, a=8, s=32, out=FAKE, ws=FAKE, nbytes=1 << 20):
         return lib.hdqt_gemm_codes_requant(qA, FAKE, bA, bB, FAKE, FAKE, RA, 8, D, n, a, s, out, None, ws,

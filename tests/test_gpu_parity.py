@@ -472,6 +472,38 @@ def test_requant_codes_wide_inputs_and_many_tiles():
     assert not host(acc).any() and not host(out).any()
 
 
+@pytest.mark.parametrize("RA,RB,D,s,a", [
+    (300, 200, 1152, 256, 14),      # a short last tile (1152 = 4 * 256 + 128), ragged edge tiles
+    (300, 200, 960, 96, 8),         # tiles of three steps that straddle the 128-code stages
+    (130, 260, 4128, 32, 8),        # 129 tiles, several column tiles per workgroup
+    (256, 128, 16384, 32, 8),       # a long contraction under a small output: split, slices, reduce
+    (256, 128, 16384, 128, 11),
+    (1152, 128, 65536, 32, 8),      # the weight gradient's shape on the benchmark layer
+    (64, 40, 64, 32, 2),            # the narrowest accumulator, two tiles
+    (200, 136, 512, 32, 16),
+    (200, 136, 512, 64, 3),
+    (64, 64, 32768, 32, 8),         # 1024 tiles in one part: beyond the table, the emulation runs
+])
+def test_requant_codes_two_pass(RA, RB, D, s, a):
+    """Shapes the matrix-core kernel takes in two passes (packed 4-bit codes, tiles of whole
+    32-code steps, accumulators up to 16 bits), every total against the oracle; the workspace
+    is the exact one, which holds no tile sums."""
+    lib = B.load()
+    exact = lib.hdqt_gemm_codes_requant_workspace_size_for(RA, RB, D, s, 4, 4, a)
+    bound = lib.hdqt_gemm_codes_requant_workspace_size(RA, RB, D, s)
+    assert 0 < exact <= bound
+    if D // s <= 512:
+        assert exact < bound / 2 or D // s <= 2, (exact, bound)
+    check_requant_codes(RA, RB, D, 4, 4, s, a, n=32, extreme=0.1)
+
+
+def test_requant_codes_two_pass_streamed_output():
+    """The input gradient's shape on the benchmark layer: an output large enough to be written
+    with streaming stores (waves one block high and two wide), one stage per output tile."""
+    check_requant_codes(65536, 1152, 128, 4, 4, 32, 8, n=64)
+    check_requant_codes(65536, 1152, 128, 4, 4, 64, 6, n=64, extreme=0.05)
+
+
 @pytest.mark.parametrize("kind", [B.GEMM_FWD, B.GEMM_BWD_INPUT, B.GEMM_BWD_WEIGHT])
 def test_requant_matmul_from_tensors(kind):
     """The paper's forward setting (tiles of 32, 8-bit accumulators) under the second reading,
