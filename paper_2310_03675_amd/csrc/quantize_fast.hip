@@ -12,8 +12,10 @@
 //     step; the four waves of a workgroup sit side by side, so a workgroup
 //     reads 512 contiguous bytes of every row; the packed codes of up to 256
 //     rows are gathered in LDS and leave as runs of 128 bytes per column.
-// Covers block orders up to 256 (axis 1) and 64 (axis 0); everything else
-// stays with the generic kernels.
+//     Block orders 128 and 256 hold all 256 rows of the strip at once: the last one or
+//     two butterfly stages pair the registers of different 64-row steps.
+// Covers block orders up to 256 on both axes (axis 0: column counts that are multiples of
+// 4); everything else stays with the generic kernels.
 
 #include "common.hpp"
 #include "lane_ops.hpp"
@@ -248,6 +250,103 @@ __device__ __forceinline__ void col_transform(ColStep& s, int log2n, uint32_t fl
     }
 }
 
+// Quantize one 64-row step of the wave's strip (already transformed) and put its packed codes
+// into the wave's LDS staging area: the step's 8 codes of a lane and column are one dword
+// (b <= 4) or two.
+template <bool STOCH, bool B4>
+__device__ __forceinline__ void col_emit(const ColStep& cur, const QuantArgs& q, float inv, float qminf,
+                                         float qmaxf, float magic, int64_t row0, int64_t col0, int sub,
+                                         int rg, int cg, uint32_t* stage_w, int stage_pitch)
+{
+    const int64_t cols = q.cols;
+    uint32_t cw[4][8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        // the lane's four elements of this row, e .. e+3 with e % 4 == 0, lie in
+        // one Philox block: its words (e%8)/2 and (e%8)/2 + 1
+        uint32_t w01[2] = {0u, 0u};
+        if (STOCH) {
+            const int64_t e = (row0 + i) * cols + col0;
+            const uint64_t blk = (uint64_t)e >> 3;
+            uint32_t rnd[4];
+            philox4x32_10((uint32_t)blk, (uint32_t)(blk >> 32), q.tensor_id, 0u, q.seed_lo,
+                          q.seed_hi, rnd);
+            const bool upper = (e & 4) != 0;
+            w01[0] = upper ? rnd[2] : rnd[0];
+            w01[1] = upper ? rnd[3] : rnd[1];
+        }
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const uint32_t u = (w01[j >> 1] >> (16 * (j & 1))) & 0xFFFFu;
+            cw[j][i] = code_word<STOCH>(cur.v[j][i], inv, qminf, qmaxf, magic, u);
+        }
+    }
+    // dword index inside the column's run: 8 codes are 1 (b <= 4) or 2 dwords
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        uint32_t* dst = stage_w + (cg * 4 + j) * stage_pitch;
+        if (B4) {
+            dst[sub * 8 + rg] = pack_nibbles(cw[j]);
+        } else {
+            dst[(sub * 8 + rg) * 2] = pack_bytes(cw[j]);
+            dst[(sub * 8 + rg) * 2 + 1] = pack_bytes(cw[j] + 4);
+        }
+    }
+}
+
+// Block orders 128 and 256: the wave's 256 rows are loaded whole (the same lane holds the same
+// row of every 64-row step, so strides 64 and 128 pair registers), each step is transformed
+// up to stride 32 as above, and the last one or two stages run across the steps.  No
+// prefetch inside the wave: 128 registers of loads are in flight from the start, and the
+// other waves of the SIMD cover the arithmetic.
+template <bool QUANT, bool STOCH, bool B4, bool GUARD>
+__device__ __forceinline__ float col_strip_wide(const QuantArgs& q, float inv, int64_t tile_row0,
+                                                int64_t col0, int lane, uint32_t* stage_w, int stage_pitch)
+{
+    const int64_t D = q.rows, cols = q.cols;
+    const int cg = lane & 7, rg = lane >> 3;
+    const float qminf = (float)(-(1 << (q.b - 1))), qmaxf = (float)((1 << (q.b - 1)) - 1);
+    const float magic = kMagic + (B4 ? 8.0f : 128.0f);
+    const uint32_t flip8 = (uint32_t)(lane & 8) << 28;
+    float amax = 0.0f;
+
+    ColStep st[4];
+#pragma unroll
+    for (int sub = 0; sub < 4; ++sub)
+        col_load<GUARD>(st[sub], q.T, D, cols, tile_row0 + sub * 64 + rg * 8, col0);
+#pragma unroll
+    for (int sub = 0; sub < 4; ++sub) col_transform(st[sub], 6, flip8);
+    const bool order256 = q.log2n > 7;
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            // stride 64: steps (0, 1) and (2, 3); stride 128: steps (0, 2) and (1, 3)
+            float a0 = st[0].v[j][i], a1 = st[1].v[j][i], a2 = st[2].v[j][i], a3 = st[3].v[j][i];
+            const float s01 = a0 + a1, d01 = a0 - a1, s23 = a2 + a3, d23 = a2 - a3;
+            a0 = s01; a1 = d01; a2 = s23; a3 = d23;
+            if (order256) {
+                const float s02 = a0 + a2, d02 = a0 - a2, s13 = a1 + a3, d13 = a1 - a3;
+                a0 = s02; a2 = d02; a1 = s13; a3 = d13;
+            }
+            st[0].v[j][i] = a0; st[1].v[j][i] = a1; st[2].v[j][i] = a2; st[3].v[j][i] = a3;
+        }
+    if (!QUANT) {
+#pragma unroll
+        for (int sub = 0; sub < 4; ++sub)
+#pragma unroll
+            for (int j = 0; j < 4; ++j)
+#pragma unroll
+                for (int i = 0; i < 8; ++i) amax = fmaxf(amax, fabsf(st[sub].v[j][i]));
+    } else {
+#pragma unroll
+        for (int sub = 0; sub < 4; ++sub)
+            col_emit<STOCH, B4>(st[sub], q, inv, qminf, qmaxf, magic, tile_row0 + sub * 64 + rg * 8, col0, sub, rg,
+                                cg, stage_w, stage_pitch);
+    }
+    return amax;
+}
+
 // Load, transform and (QUANT) quantize the wave's strip; packed codes go to the
 // wave's LDS staging area `stage_w` ([32 columns][pitch dwords]); returns max|y|.
 template <bool QUANT, bool STOCH, bool B4, int SUBS, bool GUARD>
@@ -275,48 +374,17 @@ __device__ __forceinline__ float col_strip(const QuantArgs& q, float inv, int64_
 #pragma unroll
                 for (int i = 0; i < 8; ++i) amax = fmaxf(amax, fabsf(cur.v[j][i]));
         } else {
-            uint32_t cw[4][8];
-#pragma unroll
-            for (int i = 0; i < 8; ++i) {
-                // the lane's four elements of this row, e .. e+3 with e % 4 == 0, lie in
-                // one Philox block: its words (e%8)/2 and (e%8)/2 + 1
-                uint32_t w01[2] = {0u, 0u};
-                if (STOCH) {
-                    const int64_t e = (row0 + i) * cols + col0;
-                    const uint64_t blk = (uint64_t)e >> 3;
-                    uint32_t rnd[4];
-                    philox4x32_10((uint32_t)blk, (uint32_t)(blk >> 32), q.tensor_id, 0u, q.seed_lo,
-                                  q.seed_hi, rnd);
-                    const bool upper = (e & 4) != 0;
-                    w01[0] = upper ? rnd[2] : rnd[0];
-                    w01[1] = upper ? rnd[3] : rnd[1];
-                }
-#pragma unroll
-                for (int j = 0; j < 4; ++j) {
-                    const uint32_t u = (w01[j >> 1] >> (16 * (j & 1))) & 0xFFFFu;
-                    cw[j][i] = code_word<STOCH>(cur.v[j][i], inv, qminf, qmaxf, magic, u);
-                }
-            }
-            // dword index inside the column's run: 8 codes are 1 (b <= 4) or 2 dwords
-#pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                uint32_t* dst = stage_w + (cg * 4 + j) * stage_pitch;
-                if (B4) {
-                    dst[sub * 8 + rg] = pack_nibbles(cw[j]);
-                } else {
-                    dst[(sub * 8 + rg) * 2] = pack_bytes(cw[j]);
-                    dst[(sub * 8 + rg) * 2 + 1] = pack_bytes(cw[j] + 4);
-                }
-            }
+            col_emit<STOCH, B4>(cur, q, inv, qminf, qmaxf, magic, row0, col0, sub, rg, cg, stage_w, stage_pitch);
         }
         if (sub + 1 < SUBS) cur = nxt;
     }
     return amax;
 }
 
-template <bool QUANT, bool STOCH, bool B4, int SUBS>
+template <bool QUANT, bool STOCH, bool B4, int SUBS, bool WIDEN = false>
 __global__ __launch_bounds__(kThreads) void fwht_col_fast_kernel(QuantArgs q, int WC)
 {
+    static_assert(!WIDEN || SUBS == 4, "block orders 128 and 256 span the strip's 256 rows");
     __shared__ float red[kThreads / kWave];
     constexpr int kDw = B4 ? 1 : 2;          // dwords per 8 codes
     constexpr int kPitch = SUBS * 8 * kDw + 1;
@@ -341,10 +409,14 @@ __global__ __launch_bounds__(kThreads) void fwht_col_fast_kernel(QuantArgs q, in
     }
     uint32_t* stage_w = QUANT ? stage[wave] : nullptr;
     float amax;
-    if (tile_row0 + 64 * SUBS <= D && strip_col0 + 32 <= cols)
-        amax = col_strip<QUANT, STOCH, B4, SUBS, false>(q, inv, tile_row0, col0, lane, stage_w, kPitch);
-    else
-        amax = col_strip<QUANT, STOCH, B4, SUBS, true>(q, inv, tile_row0, col0, lane, stage_w, kPitch);
+    const bool inside = tile_row0 + 64 * SUBS <= D && strip_col0 + 32 <= cols;
+    if constexpr (WIDEN) {
+        if (inside) amax = col_strip_wide<QUANT, STOCH, B4, false>(q, inv, tile_row0, col0, lane, stage_w, kPitch);
+        else amax = col_strip_wide<QUANT, STOCH, B4, true>(q, inv, tile_row0, col0, lane, stage_w, kPitch);
+    } else {
+        if (inside) amax = col_strip<QUANT, STOCH, B4, SUBS, false>(q, inv, tile_row0, col0, lane, stage_w, kPitch);
+        else amax = col_strip<QUANT, STOCH, B4, SUBS, true>(q, inv, tile_row0, col0, lane, stage_w, kPitch);
+    }
 
     if (!QUANT) {
         block_atomic_max(amax, q.meta, red);
@@ -384,7 +456,7 @@ int clamp_grid(int64_t blocks, int64_t cap)
     return (int)(blocks < cap ? blocks : cap);
 }
 
-template <int SUBS, bool STOCH>
+template <int SUBS, bool STOCH, bool WIDEN = false>
 hipError_t launch_col(const QuantArgs& q, hipStream_t stream)
 {
     const int64_t D = q.rows;
@@ -395,15 +467,15 @@ hipError_t launch_col(const QuantArgs& q, hipStream_t stream)
                     (unsigned)((D + 64 * SUBS * WR - 1) / (64 * SUBS * WR)));
     {
         ProfileScope ps(K_COL_ABSMAX, stream);
-        hipLaunchKernelGGL((fwht_col_fast_kernel<false, false, true, SUBS>), grid, dim3(kThreads), 0,
+        hipLaunchKernelGGL((fwht_col_fast_kernel<false, false, true, SUBS, WIDEN>), grid, dim3(kThreads), 0,
                            stream, q, WC);
     }
     ProfileScope ps(K_COL_QUANT, stream);
     if (q.b <= 4)
-        hipLaunchKernelGGL((fwht_col_fast_kernel<true, STOCH, true, SUBS>), grid, dim3(kThreads), 0,
+        hipLaunchKernelGGL((fwht_col_fast_kernel<true, STOCH, true, SUBS, WIDEN>), grid, dim3(kThreads), 0,
                            stream, q, WC);
     else
-        hipLaunchKernelGGL((fwht_col_fast_kernel<true, STOCH, false, SUBS>), grid, dim3(kThreads), 0,
+        hipLaunchKernelGGL((fwht_col_fast_kernel<true, STOCH, false, SUBS, WIDEN>), grid, dim3(kThreads), 0,
                            stream, q, WC);
     return hipGetLastError();
 }
@@ -432,7 +504,7 @@ bool quantize_fast_eligible(const QuantArgs& q)
     const int64_t D = q.axis ? q.cols : q.rows;
     if (D & 1) return false;
     if (q.axis == 1) return q.log2n <= 8;
-    return q.log2n <= 6 && (q.cols & 3) == 0;
+    return q.log2n <= 8 && (q.cols & 3) == 0;
 }
 
 // Pass 1 and pass 2 of one tensor (the calibration record must already be zero).
@@ -444,6 +516,8 @@ hipError_t launch_quantize_fast(const QuantArgs& q, hipStream_t stream)
         if (nchunks >= (int64_t)kThreads * 4 * 4096) return launch_row<4>(q, nchunks, stream);
         return launch_row<1>(q, nchunks, stream);
     }
+    // block orders 128 and 256: strips of 256 rows, held whole
+    if (q.log2n > 6) return q.stochastic ? launch_col<4, true, true>(q, stream) : launch_col<4, false, true>(q, stream);
     // long strips (256 rows per wave) when that still gives every CU several waves
     const int64_t waves_long = ((q.cols + 31) / 32) * ((q.rows + 255) / 256);
     if (waves_long >= 4096)

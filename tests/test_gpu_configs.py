@@ -11,6 +11,7 @@ import numpy as np
 import pytest
 import torch
 
+from conftest import progress
 from oracle import capi
 from paper_2310_03675_amd import binding as B
 from paper_2310_03675_amd import workloads
@@ -54,8 +55,13 @@ def check_layer(kind, layer, n, b, settings, layer_id=0, sr=True, seed=0):
     P, Q = operands(kind, layer)
     opA, opB = step_operands(kind, b, layer_id, sr)
     print(f"{KIND_NAME[kind]} {layer.name} n={n} b={b}: oracle quantization ...", flush=True)
+    heavy = P.numel() + Q.numel() >= 1 << 27
     cA, sA, nA = capi.quantize(P.numpy(), AXES[kind][0], n, o_op(opA), seed)
+    if heavy:
+        progress(f"{KIND_NAME[kind]} {layer.name} n={n} b={b}: oracle codes of operand A done")
     cB, sB, nB = capi.quantize(Q.numpy(), AXES[kind][1], n, o_op(opB), seed)
+    if heavy:
+        progress(f"{KIND_NAME[kind]} {layer.name} n={n} b={b}: oracle codes of operand B done")
     pA, pB = capi.pack_codes(cA, b), capi.pack_codes(cB, b)
     Pd, Qd = dev(P), dev(Q)
     rng = np.random.default_rng(1234 + kind)

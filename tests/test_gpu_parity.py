@@ -68,6 +68,9 @@ QUANT_SHAPES = [
     (64, 101, 0, 64), (7, 6, 1, 8), (6, 7, 0, 8), (1, 8, 1, 8), (8, 1, 0, 8),
     (300, 96, 0, 64), (2048, 48, 0, 64), (48, 2048, 1, 64), (520, 33, 0, 8),
     (129, 64, 1, 1), (64, 129, 0, 1),
+    # axis 0, block orders 128 and 256: whole strips, a strip that ends early, ragged column strips
+    (384, 36, 0, 128), (768, 132, 0, 256), (256, 64, 0, 256), (1280, 32, 0, 256), (640, 68, 0, 128),
+    (2304, 260, 0, 256),
 ]
 
 
@@ -87,7 +90,8 @@ def test_quantize_stochastic_4bit(rows, cols, axis, n):
 
 @pytest.mark.parametrize("b", [2, 3, 5, 6, 8])
 @pytest.mark.parametrize("rows,cols,axis,n", [(40, 192, 1, 64), (192, 40, 0, 64), (9, 27, 1, 64),
-                                              (27, 9, 0, 64), (3, 100, 1, 4)])
+                                              (27, 9, 0, 64), (3, 100, 1, 4), (512, 40, 0, 256),
+                                              (384, 36, 0, 128)])
 def test_quantize_other_widths(b, rows, cols, axis, n):
     rng = np.random.default_rng(b * 77 + rows)
     T = rng.standard_normal((rows, cols)).astype(np.float32)
