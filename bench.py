@@ -126,9 +126,10 @@ def main():
                     help="skip the activation-source variant of the step ('conv_step')")
     ap.add_argument("--no-sweep", action="store_true",
                     help="skip the sweep of input and accumulator widths on the same layer")
-    ap.add_argument("--requant", action="store_true",
-                    help="also time the forward matmul under the second reading of the accumulator "
-                         "(hdqt_gemm_requant) and report it as 'requant_fwd'")
+    ap.add_argument("--no-requant", action="store_true",
+                    help="skip the forward matmul under the second reading of the accumulator "
+                         "(hdqt_gemm_requant, 'requant_fwd')")
+    ap.add_argument("--requant", action="store_true", help="(accepted, the leg runs by default)")
     ap.add_argument("--separate", action="store_true",
                     help="run the step as the three per-matmul entry points instead of hdqt_layer_step")
     ap.add_argument("--calib-copy", action="store_true",
@@ -603,7 +604,7 @@ def main():
             ms_w = (time.perf_counter() - t_w) / 10 * 1e3
             line["width_sweep"][f"b{b_in}_a{a_acc}"] = {"ms": ms_w, "TOPS": 3 * 2.0 * M * K * N / (ms_w * 1e-3) / 1e12}
             del ws_w
-    if args.requant:
+    if not args.no_requant and not args.separate:
         k = kinds[0]
         need = B.load().hdqt_gemm_requant_workspace_size(k, M, K, N, prm[k].c())
         ws2 = torch.empty(need, dtype=torch.uint8, device=dev)
@@ -613,10 +614,10 @@ def main():
         B.profile_enable(True)
         B.profile_collect()
         t2 = time.perf_counter()
-        for _ in range(5):
+        for _ in range(20):
             B.gemm_requant(k, X, W, M, K, N, prm[k], workspace=ws2)
         torch.cuda.synchronize()
-        dt2 = (time.perf_counter() - t2) / 5
+        dt2 = (time.perf_counter() - t2) / 20
         B.profile_enable(False)
         kern2 = B.profile_collect()
         tiles = (K + args.s - 1) // args.s

@@ -18,7 +18,7 @@ def run_bench(*flags):
 @pytest.mark.gpu
 def test_bench_line_has_the_contract_fields():
     r = run_bench("--steps", "3", "--warmup", "1", "--no-large-quantize", "--no-square", "--no-conv",
-                  "--no-sweep", "--no-others", "--dist-steps", "20", "--cpu-rows", "2048")
+                  "--no-sweep", "--no-others", "--no-requant", "--dist-steps", "20", "--cpu-rows", "2048")
     assert r.returncode == 0, r.stderr[-2000:]
     lines = [ln for ln in r.stdout.splitlines() if ln.strip()]
     assert len(lines) == 1, "exactly one line on stdout"
@@ -67,3 +67,7 @@ def test_bench_line_has_the_extra_legs():
     assert set(others) == {"har", "resnet_k576"}
     for o in others.values():
         assert o["ms_per_step"] > 0 and o["TOPS"] > 0 and o["kernels_us"]
+    # the forward product under the second reading of the accumulator: two passes, no tile sums stored
+    rq = d["requant_fwd"]
+    assert rq["tile_sums_materialised_bytes"] == 0 and rq["workspace_bytes"] < 64 << 20
+    assert 0 < rq["matmul_us"] < 1000 and {"requant_tile_sums", "requant_quantize_sum"} <= set(rq["kernels_us"])
