@@ -126,6 +126,8 @@ def main():
                     help="skip the activation-source variant of the step ('conv_step')")
     ap.add_argument("--no-sweep", action="store_true",
                     help="skip the sweep of input and accumulator widths on the same layer")
+    ap.add_argument("--no-fallbacks", action="store_true",
+                    help="skip the timings of the paths behind the fast kernels' shape limits ('fallback_paths')")
     ap.add_argument("--no-requant", action="store_true",
                     help="skip the forward matmul under the second reading of the accumulator "
                          "(hdqt_gemm_requant, 'requant_fwd')")
@@ -666,6 +668,50 @@ def main():
                                               + 4.0 * (Mo * No + Mo * Ko + Ko * No),
                 "kernels_us": {n_: tot / l * 1e3 for n_, (l, tot) in k_o.items()}}
             del Xo, Wo, Go, ws_o, out_o, lay_o
+    if not args.no_fallbacks and not args.separate:
+        # The paths behind the fast kernels' shape limits, each on the benchmark layer's forward
+        # operands changed just enough to leave the fast path (not `value`; these paths have
+        # parity tests and otherwise no figure anywhere).
+        def timed(fn, reps=10):
+            fn()
+            torch.cuda.synchronize()
+            B.profile_enable(True)
+            B.profile_collect()
+            t_f = time.perf_counter()
+            for _ in range(reps):
+                fn()
+            torch.cuda.synchronize()
+            dt_f = (time.perf_counter() - t_f) / reps
+            B.profile_enable(False)
+            return dt_f, {n_: tot / l * 1e3 for n_, (l, tot) in B.profile_collect().items()}
+        fb = {}
+        pf = prm[kinds[0]]
+        # contraction length that is no multiple of 32: the generic tiled kernel (16-code MFMA steps)
+        Kf = K - 8
+        Xf, Wf = X[:, :Kf].contiguous(), W[:Kf].contiguous()
+        dt_f, k_f = timed(lambda: B.gemm(kinds[0], Xf, Wf, M, Kf, N, pf))
+        fb["fwd_K_not_multiple_of_32"] = {"shape": [M, Kf, N], "ms": dt_f * 1e3, "kernels_us": k_f,
+                                         "TOPS": 2.0 * M * Kf * N / dt_f / 1e12}
+        # 4-bit activations against 8-bit weights: packed codes on one side, a byte per code on the other
+        pm = B.Params(had_block=n, acc_bits=16, s=args.s, seed=pf.seed, A=pf.A,
+                      B=B.Operand(8, pf.B.round, pf.B.clip, pf.B.tensor_id))
+        dt_f, k_f = timed(lambda: B.gemm(kinds[0], X, W, M, K, N, pm))
+        fb["fwd_mixed_4bit_8bit"] = {"shape": [M, K, N], "ms": dt_f * 1e3, "kernels_us": k_f,
+                                    "TOPS": 2.0 * M * K * N / dt_f / 1e12}
+        # axis-0 quantization of a tensor whose column count is no multiple of 4 (generic column kernel)
+        Xq = X[:, :K - 2].contiguous()
+        dt_f, k_f = timed(lambda: B.quantize(Xq, 0, n, pf.A, 0))
+        fb["quantize_axis0_cols_not_multiple_of_4"] = {
+            "shape": [M, K - 2], "ms": dt_f * 1e3, "kernels_us": k_f,
+            "GBps": 8.5 * M * (K - 2) / dt_f / 1e9}
+        # a step with Hadamard blocks of 128: beyond the two-axis kernels, each axis of each tensor
+        # is a pass of the single-axis kernels
+        prm_f = [step_params(B, k, 128, args.s, args.acc_bits) for k in kinds]
+        ws_f = torch.empty(B.layer_step_workspace_size(M, K, N, *prm_f), dtype=torch.uint8, device=dev)
+        dt_f, k_f = timed(lambda: B.layer_step(X, W, G, *prm_f, out=step_out, workspace=ws_f))
+        fb["step_had_block_128"] = {"ms": dt_f * 1e3, "kernels_us": k_f, "TOPS": ops_step / dt_f / 1e12}
+        line["fallback_paths"] = fb
+        del Xf, Wf, Xq, ws_f
     if not args.no_cpu_baseline:
         line["cpu_baseline"] = cpu_baseline(layer, n, args.s, min(args.cpu_rows, M))
     print(json.dumps(line))

@@ -18,7 +18,8 @@ def run_bench(*flags):
 @pytest.mark.gpu
 def test_bench_line_has_the_contract_fields():
     r = run_bench("--steps", "3", "--warmup", "1", "--no-large-quantize", "--no-square", "--no-conv",
-                  "--no-sweep", "--no-others", "--no-requant", "--dist-steps", "20", "--cpu-rows", "2048")
+                  "--no-sweep", "--no-others", "--no-requant", "--no-fallbacks", "--dist-steps", "20", "--cpu-rows",
+                  "2048")
     assert r.returncode == 0, r.stderr[-2000:]
     lines = [ln for ln in r.stdout.splitlines() if ln.strip()]
     assert len(lines) == 1, "exactly one line on stdout"
@@ -67,6 +68,13 @@ def test_bench_line_has_the_extra_legs():
     assert set(others) == {"har", "resnet_k576"}
     for o in others.values():
         assert o["ms_per_step"] > 0 and o["TOPS"] > 0 and o["kernels_us"]
+    # the paths behind the fast kernels' shape limits carry a figure each
+    fb = d["fallback_paths"]
+    assert set(fb) == {"fwd_K_not_multiple_of_32", "fwd_mixed_4bit_8bit", "quantize_axis0_cols_not_multiple_of_4",
+                       "step_had_block_128"}
+    assert all(v["ms"] > 0 and v["kernels_us"] for v in fb.values())
+    assert "gemm_tiled_generic" in fb["fwd_K_not_multiple_of_32"]["kernels_us"] or \
+        "gemm_tiled_aligned" in fb["fwd_K_not_multiple_of_32"]["kernels_us"]
     # the forward product under the second reading of the accumulator: two passes, no tile sums stored
     rq = d["requant_fwd"]
     assert rq["tile_sums_materialised_bytes"] == 0 and rq["workspace_bytes"] < 64 << 20
