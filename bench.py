@@ -686,12 +686,13 @@ def main():
             return dt_f, {n_: tot / l * 1e3 for n_, (l, tot) in B.profile_collect().items()}
         fb = {}
         pf = prm[kinds[0]]
-        # contraction length that is no multiple of 32: the generic tiled kernel (16-code MFMA steps)
-        Kf = K - 8
-        Xf, Wf = X[:, :Kf].contiguous(), W[:Kf].contiguous()
-        dt_f, k_f = timed(lambda: B.gemm(kinds[0], Xf, Wf, M, Kf, N, pf))
-        fb["fwd_K_not_multiple_of_32"] = {"shape": [M, Kf, N], "ms": dt_f * 1e3, "kernels_us": k_f,
-                                         "TOPS": 2.0 * M * Kf * N / dt_f / 1e12}
+        # contraction lengths that are no multiple of 32: a multiple of 8 still runs the matrix-core
+        # kernel (the rows' last 16-byte unit is padded with zeros on its way to LDS), anything else
+        # the generic tiled kernel
+        for key, Kf in (("fwd_K_multiple_of_8_not_32", K - 8), ("fwd_K_not_multiple_of_8", K - 4)):
+            Xf, Wf = X[:, :Kf].contiguous(), W[:Kf].contiguous()
+            dt_f, k_f = timed(lambda: B.gemm(kinds[0], Xf, Wf, M, Kf, N, pf))
+            fb[key] = {"shape": [M, Kf, N], "ms": dt_f * 1e3, "kernels_us": k_f, "TOPS": 2.0 * M * Kf * N / dt_f / 1e12}
         # 4-bit activations against 8-bit weights: packed codes on one side, a byte per code on the other
         pm = B.Params(had_block=n, acc_bits=16, s=args.s, seed=pf.seed, A=pf.A,
                       B=B.Operand(8, pf.B.round, pf.B.clip, pf.B.tensor_id))

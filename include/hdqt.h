@@ -253,7 +253,7 @@ int hdqt_gemm_codes_bf16(const void *qA, const void *qB, int bA, int bB, const f
  * Arguments as for hdqt_gemm_codes; acc_bits 2..24; acc_out (nullable) receives acc.
  * HDQT_EINVAL_TILE if a tile sum may not be exact in binary32 (s * 2^(bA+bB-2) >= 2^24),
  * HDQT_EINVAL_ACC if acc may leave int32.
- * Packed 4-bit codes on both sides, D and s multiples of 32, acc_bits <= 16 (and at most
+ * Packed 4-bit codes on both sides, D a multiple of 8, s of 32, acc_bits <= 16 (and at most
  * 512 tiles per part of a split contraction): two passes through the matrix-core kernel,
  * the first keeping only the maxima m_t, the second quantizing every tile sum as it is
  * produced; no tile sum is stored, and the workspace holds the maxima and, for a split

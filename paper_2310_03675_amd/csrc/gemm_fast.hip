@@ -4,7 +4,8 @@
 // each tile's sum clamped to the a-bit accumulator range, 32-bit total), for
 //   both operands packed 4-bit, or both with a byte per code (the WIDE instances: the
 //   bytes go to LDS as they are, nothing is scaled, generic clamp only);
-//   s a multiple of 32, D a multiple of 32.
+//   s a multiple of 32 (or 16), D a multiple of 8 (packed) or 4 (bytes): rows of whole dwords;
+//   a row that ends inside a 32-code unit is padded with zeros on its way to LDS.
 //
 // What differs from the generic kernel:
 //   * v_mfma_i32_32x32x32_i8: one MFMA consumes 32 contraction positions.
@@ -129,6 +130,18 @@ __device__ __forceinline__ void store_unit(uint8_t* lds_row_k, const uint4& w)
     const uint4 odd = make_uint4(w.x & m, w.y & m, w.z & m, w.w & m);
     *reinterpret_cast<uint4*>(lds_row_k) = even;
     *reinterpret_cast<uint4*>(lds_row_k + 16) = odd;
+}
+
+// A unit that straddles the end of a row (D no multiple of 32) was loaded with the first codes
+// of the next row behind its own: dword j holds `per_dword` codes starting at first + j *
+// per_dword of the unit and is kept only where that lies below `valid`, the number of the
+// unit's codes inside the row (a multiple of per_dword, see gemm_fast_eligible).
+__device__ __forceinline__ void mask_tail(uint4& w, int valid, int per_dword, int first)
+{
+    w.x = first < valid ? w.x : 0u;
+    w.y = first + per_dword < valid ? w.y : 0u;
+    w.z = first + 2 * per_dword < valid ? w.z : 0u;
+    w.w = first + 3 * per_dword < valid ? w.w : 0u;
 }
 
 // total += clamp(p0/256, -128, 127) + clamp(p1/256, -128, 127)
@@ -435,6 +448,18 @@ __global__ __launch_bounds__(64 * WAVES, WAVES == 8 ? (MASK ? 3 : 4) : 2) void g
     // One barrier per stage is enough: buffer `buf` was last read two stages ago,
     // and every wave has passed the previous stage's barrier since.
     auto stage = [&](Staged<UNITS * REGS, UNITS_B * REGS>& st, const int buf) {
+        if (g.D & (KSTEP - 1)) {
+            // rows that end inside a 32-code unit: the thread's units of this stage all start at
+            // the same position of their rows
+            const int64_t valid = g.D - (c_k + lks * KSTEP);
+            if (valid < KSTEP) {
+#pragma unroll
+                for (int i = 0; i < UNITS * REGS; ++i) {
+                    mask_tail(st.a[i], (int)valid, WIDE ? 4 : 8, WIDE ? 16 * (i & 1) : 0);
+                    if (i < UNITS_B * REGS) mask_tail(st.b[i], (int)valid, WIDE ? 4 : 8, WIDE ? 16 * (i & 1) : 0);
+                }
+            }
+        }
 #pragma unroll
         for (int i = 0; i < UNITS; ++i) {
             const int r = lrow + ROWS_PER_PASS * i;
@@ -931,7 +956,7 @@ bool gemm_fold_plan(GemmArgs* g, int64_t batch, int C, int H, int W, int kh, int
     auto log2i = [](int v) { int l = 0; while ((1 << l) < v) ++l; return l; };
     if (batch < 1 || C < 1 || H < 1 || W < 1 || kh < 1 || kw < 1 || kh % 2 == 0 || kw % 2 == 0) return false;
     if (!pow2(W) || W > BM || kh * kw > BN || kh > 15 || kw > 15) return false;
-    if (g->RA != batch * (int64_t)H * W || g->RB != (int64_t)C * kh * kw) return false;
+    if (g->RA != batch * (int64_t)H * W || g->RB != (int64_t)C * kh * kw || g->D % KSTEP != 0) return false;
     g->splits = 1;                        // short contractions; the fold needs whole totals
     g->tiles_per_split = g->n_tiles;
     if (batch * (int64_t)C * H * W >= ((int64_t)1 << 40)) return false;
@@ -964,7 +989,9 @@ bool gemm_fold_plan(GemmArgs* g, int64_t batch, int C, int H, int W, int kh, int
 bool gemm_fast_eligible(const GemmArgs& g)
 {
     if ((g.bA > 4) != (g.bB > 4)) return false;      // packed or bytes, the same on both sides
-    if (g.D % KSTEP != 0) return false;
+    // rows of whole dwords (the 16-byte loads then start on one); a row may end inside a 32-code
+    // unit, whose remainder the kernel clears
+    if (g.D % (g.bA > 4 ? 4 : 8) != 0) return false;
     if (g.RB > ((int64_t)1 << 21)) return false;     // 32-bit offsets inside an output tile
     // 32-bit offsets into the operands, with room for the "outside" offset
     if ((g.RA + 256) * g.pitchA >= ((int64_t)1 << 31) || (g.RB + 256) * g.pitchB >= ((int64_t)1 << 31)) return false;
@@ -1024,7 +1051,7 @@ static bool narrow_tiles(const GemmArgs& g)
 bool gemm_requant_fast_eligible(const GemmArgs& g, int acc_bits)
 {
     if (g.bA > 4 || g.bB > 4 || g.fold || g.out_bf16 || g.mask_src) return false;
-    if (g.D % KSTEP != 0 || g.s % KSTEP != 0) return false;
+    if (g.D % 8 != 0 || g.s % KSTEP != 0) return false;
     if (acc_bits < 2 || acc_bits > 16) return false;
     if (g.RB > ((int64_t)1 << 21)) return false;
     if ((g.RA + 256) * g.pitchA >= ((int64_t)1 << 31) || (g.RB + 256) * g.pitchB >= ((int64_t)1 << 31)) return false;

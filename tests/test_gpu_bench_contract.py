@@ -70,11 +70,11 @@ def test_bench_line_has_the_extra_legs():
         assert o["ms_per_step"] > 0 and o["TOPS"] > 0 and o["kernels_us"]
     # the paths behind the fast kernels' shape limits carry a figure each
     fb = d["fallback_paths"]
-    assert set(fb) == {"fwd_K_not_multiple_of_32", "fwd_mixed_4bit_8bit", "quantize_axis0_cols_not_multiple_of_4",
-                       "step_had_block_128"}
+    assert set(fb) == {"fwd_K_multiple_of_8_not_32", "fwd_K_not_multiple_of_8", "fwd_mixed_4bit_8bit",
+                       "quantize_axis0_cols_not_multiple_of_4", "step_had_block_128"}
     assert all(v["ms"] > 0 and v["kernels_us"] for v in fb.values())
-    assert "gemm_tiled_generic" in fb["fwd_K_not_multiple_of_32"]["kernels_us"] or \
-        "gemm_tiled_aligned" in fb["fwd_K_not_multiple_of_32"]["kernels_us"]
+    assert "gemm_i4_fwd" in fb["fwd_K_multiple_of_8_not_32"]["kernels_us"]
+    assert any(k.startswith("gemm_tiled") for k in fb["fwd_K_not_multiple_of_8"]["kernels_us"])
     # the forward product under the second reading of the accumulator: two passes, no tile sums stored
     rq = d["requant_fwd"]
     assert rq["tile_sums_materialised_bytes"] == 0 and rq["workspace_bytes"] < 64 << 20

@@ -221,6 +221,27 @@ def test_gemm_codes_saturation_through_int16(bA, bB, accs):
             assert np.array_equal(host(acc), capi.tiled_matmul(cA, cB, s, accs[0])), (va, vb, s)
 
 
+@pytest.mark.parametrize("D", [40, 72, 216, 1144, 4104])
+def test_gemm_codes_rows_that_end_inside_a_step(D):
+    """Contraction lengths that are multiples of 8 (packed codes) or 4 (a byte per code) but
+    not of 32: the matrix-core kernel takes them and clears, on the way to LDS, what the last
+    16-byte unit of a row read from the next row.  Half the codes at the range ends, so that
+    a code leaking in from the next row would change a saturating tile."""
+    for s, a in ((32, 8), (64, 8), (16, 8), (32, 12), (96, 32), (128, 16), (256, 16)):
+        if s > D and s != 32:
+            continue
+        check_gemm_codes(200, 136, D, 4, 4, s, a, n=8, extreme=0.5)
+    check_gemm_codes(130, 40, D, 4, 4, 32, 8, n=8, extreme=0.5)           # the 128 x 64 tile
+    check_gemm_codes(200, 136, D + 4, 8, 8, 32, 16, n=4, extreme=0.5)     # bytes: a multiple of 4
+    check_gemm_codes(200, 136, D + 12, 6, 7, 64, 32, n=4, extreme=0.5)
+    check_requant_codes(200, 136, D, 4, 4, 32, 8, n=8, extreme=0.3)
+
+
+def test_gemm_codes_rows_that_end_inside_a_step_split_contraction():
+    check_gemm_codes(128, 128, 65544, 4, 4, 32, 8, n=8, extreme=0.3)      # 2049 tiles, split into parts
+    check_gemm_codes(256, 64, 32776, 4, 4, 64, 8, n=8, extreme=0.3)
+
+
 @pytest.mark.parametrize("RA,RB", [(300, 64), (128, 33), (1000, 1), (50, 60), (513, 64)])
 def test_gemm_codes_outputs_of_at_most_64_columns(RA, RB):
     """The 128 x 64 workgroup tile: every epilogue that has such instances, ragged rows and
