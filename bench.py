@@ -35,8 +35,24 @@ TRAFFIC_SOURCE = "profiles/bench_resnet_k1152_hbm_traffic.md (rocprofv3 --pmc FE
 VALU_SOURCE = "profiles/bench_resnet_k1152_valu_issue.md (rocprofv3 --pmc SQ_INSTS_VALU, not measured in this run)"
 MEASURED_TRAFFIC = {
     "fwht_dual_absmax_batch": 336.4e6, "fwht_dual_quant_batch": 421.7e6,
-    "gemm_i4_fwd": 74.7e6, "gemm_i4_bwd_input": 307.3e6, "gemm_i4_bwd_weight": 77.0e6,
+    "gemm_i4_fwd": 74.5e6, "gemm_i4_bwd_input": 307.4e6, "gemm_i4_bwd_weight": 77.0e6,
 }
+# The kernels' sources as they were when those counters were collected: a SHA-256 over the
+# files below, in this order.  The bench line says whether they have changed since (then the
+# counter figures describe older kernels; re-collect them and update this value).
+PROFILED_SOURCES = ("common.hpp", "lane_ops.hpp", "quantize_dual.hip", "gemm_fast.hip", "gemm.hip")
+PROFILED_SOURCES_SHA256 = "c44b99befc0879b63d992ecd87570e494607d09e5af6b95298b43d3c621b78e8"
+
+
+def profiled_sources_sha256():
+    import hashlib
+    h = hashlib.sha256()
+    for f in PROFILED_SOURCES:
+        with open(os.path.join(ROOT, "paper_2310_03675_amd", "csrc", f), "rb") as fh:
+            h.update(fh.read())
+    return h.hexdigest()
+
+
 INT8_MFMA_PEAK_TOPS = 5000.0    # MI355X dense int8
 # Wave-wide vector-ALU instructions per launch of the two quantizer kernels on this workload
 # (rocprofv3 --pmc SQ_INSTS_VALU, profiles/bench_resnet_k1152_valu_issue.md), and the chip's
@@ -315,9 +331,17 @@ def main():
                 roof_all[name] = {"bound": "mfma", "achieved": tops, "peak": INT8_MFMA_PEAK_TOPS,
                                   "unit": "TOP/s", "frac": f_mfma, "traffic": measured.get(name),
                                   "algorithmic_ops_per_launch": ops_step / 3, "hbm_GBps": gbps}
+    try:
+        counters_stale = profiled_sources_sha256() != PROFILED_SOURCES_SHA256
+    except OSError:
+        counters_stale = None          # sources not shipped next to the library
+    if counters_stale:
+        print("bench.py: the kernels' sources have changed since the rocprofv3 counters in profiles/ were "
+              "collected; 'traffic' and 'valu_issue' describe the older kernels", file=sys.stderr)
     for r_ in roof_all.values():
         if r_.get("traffic") is not None:
             r_["traffic_source"] = TRAFFIC_SOURCE
+            r_["traffic_sources_changed_since_profile"] = counters_stale
         if "valu_issue" in r_:
             r_["valu_issue"]["source"] = VALU_SOURCE
     dominant = max(roof_all, key=lambda k: kern[k][1])
