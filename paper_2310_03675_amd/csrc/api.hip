@@ -246,6 +246,17 @@ hdqt::GemmArgs plan_gemm(const void* qA, const void* qB, int bA, int bB, const f
                 g.s = grp;
                 break;
             }
+        // Tiles that cannot saturate at all: every clamp is the identity and the result is the
+        // plain integer product, so the tiles may as well be longer (the kernels clamp at tile
+        // ends: 2048 codes are 16 stages of the matrix-core kernel between two clamps) and the
+        // accumulator 32 bits wide -- as long as the product itself, times the factor 256 the
+        // packed-code kernel carries, stays inside int32.
+        const int64_t room = (bA <= 4 && bB <= 4) ? ((int64_t)1 << 22) : ((int64_t)1 << 31);
+        if (g.s % 128 == 0 && g.s * max_prod <= (int64_t)g.acc_hi && D * max_prod < room) {
+            while (g.s * 2 <= 2048 && g.s * 2 <= D) g.s *= 2;
+            g.acc_lo = INT_MIN;
+            g.acc_hi = INT_MAX;
+        }
     }
     g.s_pad = (int)((g.s + 15) / 16 * 16);
     g.n_tiles = (D + g.s - 1) / g.s;
