@@ -375,7 +375,7 @@ def main():
         # per-pass HBM rate of hdqt_quantize, algorithmic bytes 4 B per element for pass 1 and
         # 4.5 B for pass 2.  Legs: contraction along a row (axis 1) and along a column (axis 0,
         # the transposing write), Hadamard block 64 (registers and lane exchanges only) and
-        # 256 (axis 1: more lane stages; axis 0: the fallback kernel that pairs waves through LDS).
+        # 256 (axis 1: more lane stages; axis 0: the strip's 256 rows held whole in registers).
         big = torch.randn((16384, 16384), device=dev)
         op = B.Operand(4, B.ROUND_NEAREST, 1.0, 0)
         elems_big = 16384.0 * 16384.0
@@ -402,7 +402,22 @@ def main():
             line["quantize_1GiB"][f"axis{axis_q}_n{n_q}"] = leg
         # (the figures of the first leg at the top level too, where earlier runs had them)
         line["quantize_1GiB"].update({k_: v_ for k_, v_ in line["quantize_1GiB"]["axis1_n64"].items() if k_ != "kernels"})
-        del big
+        # what a plain device-to-device copy of the same tensor reaches on this machine (PyTorch's
+        # copy kernel, read + write): the streaming ceiling the fractions above can be held against
+        dst_big = torch.empty_like(big)
+        dst_big.copy_(big)
+        torch.cuda.synchronize()
+        ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        ev0.record()
+        for _ in range(5):
+            dst_big.copy_(big)
+        ev1.record()
+        torch.cuda.synchronize()
+        copy_gbps = 2.0 * 4.0 * elems_big / (ev0.elapsed_time(ev1) / 5 * 1e-3) / 1e9
+        line["quantize_1GiB"]["device_copy_1GiB_GBps"] = copy_gbps
+        for leg_ in ("axis1_n64", "axis0_n64", "axis1_n256", "axis0_n256"):
+            line["quantize_1GiB"][leg_]["both_frac_of_device_copy"] = line["quantize_1GiB"][leg_]["both_GBps"] / copy_gbps
+        del big, dst_big
     if not args.no_square:
         # The matrix pipe's own rate and the shader clock under that load, for three kinds of
         # operands (hdqt_probe_matrix_clock: independent MFMAs on fragments held in registers,
