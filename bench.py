@@ -120,8 +120,8 @@ def cpu_baseline(layer, n, s, rows):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=20)
-    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--workload", default="resnet_k1152", choices=sorted(WORKLOADS))
     ap.add_argument("--s", type=int, default=32, help="tile length along the contraction")
     ap.add_argument("--acc-bits", type=int, default=8)
