@@ -387,8 +387,9 @@ int hdqt_conv_fwd(const float *act, const hdqt_conv_t *geo, const float *W, floa
  * K = channels*kh*kw.
  * Taken: 4-bit codes, s and N multiples of 32, ceil(N/s) * 2^(acc_bits-1) <= 32767 (the
  * folded tile is kept as 16-bit integers); kh, kw odd; width a power
- * of two <= 128; height*width a power of two <= 128, or 128/width >= kh image rows per
- * strip.  Anything else: HDQT_EINVAL_GEOMETRY (before anything is launched), and the caller
+ * of two <= 128; height*width a power of two <= 128, or height*width = 256 with N <= 128
+ * and a window of at most nine taps (a workgroup multiplies both halves of an image), or
+ * 128/width >= kh image rows per strip.  Anything else: HDQT_EINVAL_GEOMETRY (before anything is launched), and the caller
  * takes hdqt_layer_bwd and folds its dX.
  */
 int hdqt_conv_bwd(const float *G, const float *W, const void *saved, const hdqt_conv_t *geo,

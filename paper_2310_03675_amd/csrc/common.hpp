@@ -113,6 +113,8 @@ struct GemmArgs {
     int f_rows_out;         // strip mode: image rows a row tile writes
     int f_strips;           // strip mode: row tiles per image
     int f_cg;               // channels per column tile: 128 / (kh*kw)
+    int f_pair;             // images of 256 pixels, one stage per tile: a workgroup computes both
+                            // 128-pixel halves of an image (grid.y = images) and folds them together
 };
 // fills the fold fields from the geometry; false if the fast kernel does not take it
 bool gemm_fold_plan(GemmArgs* g, int64_t batch, int C, int H, int W, int kh, int kw);

@@ -229,9 +229,10 @@ __device__ __forceinline__ int clamp3(int v, int lo, int hi)
 // positive, +0 elsewhere.  An instance of its own: the 32 values cost registers.  (The fold
 // epilogue masks with a run-time test: it reads one value per output element anyway.)
 template <int EPI, int KS, bool STREAM, int WAVES, bool BF16, bool FOLD, bool WIDE = false, bool NARROW = false,
-          bool MASK = false>
+          bool MASK = false, bool PAIR = false>
 __global__ __launch_bounds__(64 * WAVES, WAVES == 8 ? (MASK ? 3 : 4) : 2) void gemm_i4_kernel(GemmArgs g)
 {
+    static_assert(!PAIR || FOLD, "pair mode is a way of folding");
     static_assert(!MASK || (!BF16 && !FOLD && !WIDE && !NARROW), "masked output: plain packed instances only");
     static_assert(!NARROW || (WAVES == 8 && !BF16 && !FOLD && !WIDE), "narrow tiles: plain packed instances only");
     constexpr int TM = BM, TN = NARROW ? 64 : BN;   // the workgroup's tile
@@ -290,7 +291,12 @@ __global__ __launch_bounds__(64 * WAVES, WAVES == 8 ? (MASK ? 3 : 4) : 2) void g
     const int f_ph = FOLD ? (g.fkh - 1) / 2 : 0, f_pw = FOLD ? (g.fkw - 1) / 2 : 0;
     const int f_img = (FOLD && !g.f_imgs) ? (int)blockIdx.y / g.f_strips : 0;
     const int f_y0 = (FOLD && !g.f_imgs) ? ((int)blockIdx.y % g.f_strips) * g.f_rows_out - f_ph : 0;
+    // fold, pair mode: row tiles 2 blockIdx.y and 2 blockIdx.y + 1 are the two halves of image
+    // blockIdx.y; the load stream and the multiply stream each know which half they are at
+    constexpr bool f_pair = PAIR;     // (an instance of its own: where a pixel's accumulators lie is then a compile-time choice)
+    int f_half = 0, c_half = 0;
     auto a_row = [&](int r) -> int64_t {          // source row of qA for row r of the tile, -1: zero
+        if (f_pair) return ((int64_t)blockIdx.y * 2 + f_half) * TM + r;
         if (!FOLD || g.f_imgs) return row0 + r;
         const int yy = f_y0 + (r >> g.f_log2w);
         if (yy < 0 || yy >= g.fH) return -1;
@@ -365,7 +371,11 @@ __global__ __launch_bounds__(64 * WAVES, WAVES == 8 ? (MASK ? 3 : 4) : 2) void g
             }
         }
         f_k += KS;
-        if (f_k >= k_end) { f_k = k_begin; f_ct += gridDim.z; }
+        if (f_k >= k_end) {
+            f_k = k_begin;
+            if (f_pair && f_half == 0) f_half = 1;      // the image's other half, same column tile
+            else { f_half = 0; f_ct += gridDim.z; }
+        }
     };
     auto frag = [&](const uint8_t(*lds)[LDP], int base_row, int ks) -> v4i {
         return *reinterpret_cast<const v4i*>(&lds[base_row + (lane & 31)][ks * KSTEP + (lane >> 5) * 16]);
@@ -704,6 +714,79 @@ __global__ __launch_bounds__(64 * WAVES, WAVES == 8 ? (MASK ? 3 : 4) : 2) void g
 #pragma unroll
                     for (int r = 0; r < 16; ++r) total[a][c][r] = (int)((uint32_t)total[a][c][r] - corr);
         }
+        if constexpr (PAIR) {
+            // ---- fold, pair mode (images of 256 pixels, one stage per tile): half 0 multiplied out
+            // of buffer 0 and half 1 out of buffer 1, so the image's 256 pixel rows of accumulators
+            // (int16) lie in four quarters of 64 -- As[0], Bs[0] (half 0, written while half 1
+            // still needs the buffers 1), As[1], Bs[1] (half 1) -- and are folded after the second
+            // half.  Offsets in int16 from the start of As.
+            constexpr int AP = 130;      // pitch in int16 (65 dwords: neighbouring pixels, neighbouring banks)
+            constexpr int kQuarter = 64 * AP;
+            static_assert(sizeof(As[0]) >= ((size_t)kQuarter + BN) * sizeof(int16_t) &&
+                          sizeof(Bs[0]) >= (size_t)kQuarter * sizeof(int16_t), "a quarter must fit one stage buffer");
+            int16_t* accP = reinterpret_cast<int16_t*>(&As[0][0][0]);
+            const int dB = (int)((reinterpret_cast<uintptr_t>(&Bs[0][0][0]) - reinterpret_cast<uintptr_t>(&As[0][0][0])) / 2);
+            constexpr int dBuf = (int)(sizeof(As[0]) / 2);
+            auto quarter = [&](int qi) { return (qi & 1) * dB + (qi >> 1) * dBuf; };
+            __syncthreads();             // every wave is done reading this half's operands
+            {
+                // (a wave's 64 rows are one quarter: wm = 0, 1; rr + 4 * (lane >> 5) < 64)
+                int16_t* dst = accP + quarter(2 * c_half + wm) + (4 * (lane >> 5)) * AP + lane_col;
+#pragma unroll
+                for (int a = 0; a < RS; ++a)
+#pragma unroll
+                    for (int c = 0; c < CS; ++c)
+#pragma unroll
+                        for (int r = 0; r < 16; ++r) {
+                            const int rr = a * 32 + 8 * (r >> 2) + (r & 3);
+                            dst[rr * AP + c * 32] = (int16_t)(total[a][c][r] >> fin_shift);
+                            total[a][c][r] = 0;
+                        }
+            }
+            c_k = k_begin;
+            if (c_half == 0) {
+                // the words read for taps outside the image, behind the first quarter
+                if (tid < BN) accP[kQuarter + tid] = 0;
+                c_half = 1;              // (the barrier of the next stage orders these writes)
+                return;
+            }
+            c_half = 0;
+            __syncthreads();
+            const int W = g.fW, H = g.fH, kw = g.fkw, khw = g.fkh * g.fkw;
+            const int q = tid & 255;                         // pixel of the image
+            const int ry = q >> g.f_log2w, x = q & (W - 1);
+            int off[9];
+            int ty = 0, tx = 0;
+#pragma unroll
+            for (int t = 0; t < 9; ++t) {
+                const int ryp = ry - ty + f_ph, xp = x - tx + f_pw;
+                const bool ok = t < khw && ryp >= 0 && ryp < H && xp >= 0 && xp < W;
+                const int p = (ryp << g.f_log2w) + xp;
+                off[t] = ok ? quarter(p >> 6) + (p & 63) * AP + t : kQuarter;
+                if (++tx == kw) { tx = 0; ++ty; }
+            }
+            const int cbase = c_ct * g.f_cg;
+            // the thread's channels: c0, c0 + 2, ... below c_end; their outputs lie a whole image apart
+            const int c0 = tid >> 8, c_end = min(g.f_cg, g.fC - cbase);
+            const int64_t o0 = ((int64_t)blockIdx.y * g.fC + cbase + c0) * (H * W) + q;
+            const int64_t o_step = (int64_t)(NTHREADS / 256) * (H * W);
+            float* po = g.out + o0;
+            const float* pm = g.mask_src ? g.mask_src + o0 : nullptr;
+            const int16_t* col = accP + c0 * khw;
+            for (int c = c0; c < c_end; c += NTHREADS / 256) {
+                int sum = 0;
+#pragma unroll
+                for (int t = 0; t < 9; ++t) sum += col[off[t]];
+                float f = (float)sum * dq;
+                if (pm) { f = pm[0] > 0.0f ? f : 0.0f; pm += o_step; }
+                po[0] = f;
+                po += o_step;
+                col += (NTHREADS / 256) * khw;
+            }
+            __syncthreads();             // the next stage overwrites the buffers the sums were read from
+            c_ct += gridDim.z;
+            return;
+        }
         if constexpr (FOLD) {
             // ---- fold: the tile's accumulators go to LDS (int16: at most 255 tiles of +-128),
             // then every thread adds up the kh*kw taps of its pixels and channels.  Both operand
@@ -970,6 +1053,12 @@ bool gemm_fold_plan(GemmArgs* g, int64_t batch, int C, int H, int W, int kh, int
         g->f_imgs = BM / (int)hw;
         g->f_log2hw = log2i((int)hw);
         g->f_rows_c = H; g->f_rows_out = H; g->f_strips = 1;
+    } else if (hw == 2 * BM && kh * kw <= 9 && kh * kw > 1 && g->D <= KS_LONG && batch <= 65535) {
+        // an image is two row tiles and a tile one stage: both halves in one workgroup, no halo
+        g->f_pair = 1;
+        g->f_imgs = 0;
+        g->f_log2hw = 8;
+        g->f_rows_c = H; g->f_rows_out = H; g->f_strips = 1;
     } else {
         g->f_imgs = 0;
         g->f_log2hw = 7;                  // unused: one image part per tile
@@ -1106,7 +1195,7 @@ hipError_t launch_gemm_fast(const GemmArgs& g_in, hipStream_t stream)
     if (narrow) n_ct = (g.RB + 63) / 64;
     if (g.fold) {
         n_ct = (g.fC + g.f_cg - 1) / g.f_cg;
-        n_rt = g.f_imgs ? (g.fbatch + g.f_imgs - 1) / g.f_imgs : g.fbatch * g.f_strips;
+        n_rt = g.f_imgs ? (g.fbatch + g.f_imgs - 1) / g.f_imgs : g.fbatch * g.f_strips;      // (pair mode: images)
     }
     const bool s32 = sat8_path(g) && g.s == 32;
     const bool sat16 = sat16_path(g, &g);
@@ -1127,7 +1216,9 @@ hipError_t launch_gemm_fast(const GemmArgs& g_in, hipStream_t stream)
         if (masked) {                                                                                \
             if (g.stream_out) hipLaunchKernelGGL((gemm_i4_kernel<EPI, KS_LONG, true, kWaves, false, false, false, false, true>), grid, block, 0, stream, g); \
             else hipLaunchKernelGGL((gemm_i4_kernel<EPI, KS_LONG, false, kWaves, false, false, false, false, true>), grid, block, 0, stream, g); \
-        } else if (g.fold)                                                                           \
+        } else if (g.fold && g.f_pair)                                                               \
+            hipLaunchKernelGGL((gemm_i4_kernel<EPI, KS_LONG, false, kWaves, false, true, false, false, false, true>), grid, block, 0, stream, g); \
+        else if (g.fold)                                                                             \
             hipLaunchKernelGGL((gemm_i4_kernel<EPI, KS_LONG, false, kWaves, false, true>), grid, block, 0, stream, g); \
         else if (narrow) {                                                                           \
             if (g.stream_out) hipLaunchKernelGGL((gemm_i4_kernel<EPI, KS_LONG, true, kWaves, false, false, false, true>), grid, block, 0, stream, g); \

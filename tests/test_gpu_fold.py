@@ -29,7 +29,7 @@ def random_codes(rng, lines, D, extreme=0.0):
     return c
 
 
-# (batch, C, H, W, kh, kw, N, s, a): strips with halo rows (16x16, 32x32), strips without (64 wide, 1 x 3), whole images per
+# (batch, C, H, W, kh, kw, N, s, a): strips with halo rows (32x32; 16x16 with a long contraction), strips without (64 wide, 1 x 3), whole images per
 # tile (8x8, 4x4, 2 x 64), a batch that does not fill the last tile, 1-D and 1x1 and 5x5 windows,
 # channel counts that are not multiples of the channels per column tile, every epilogue
 CASES = [
@@ -44,6 +44,13 @@ CASES = [
     (2, 20, 16, 16, 3, 3, 128, 128, 12),
     (2, 20, 16, 16, 3, 3, 96, 96, 10),
     (1, 3, 40, 16, 3, 1, 32, 32, 6),
+    # images of 256 pixels with a contraction of one stage: both halves of an image in one workgroup
+    (1, 4, 2, 128, 3, 3, 64, 32, 8),
+    (3, 14, 8, 32, 3, 3, 128, 32, 8),
+    (2, 15, 32, 8, 3, 3, 128, 64, 8),
+    (2, 29, 16, 16, 1, 3, 128, 32, 8),
+    (3, 20, 16, 16, 3, 1, 64, 32, 8),
+    (2, 20, 16, 16, 3, 3, 160, 32, 8),      # two stages per tile: strips again
 ]
 
 
@@ -70,7 +77,7 @@ def test_unsupported_folds_are_refused():
     q = torch.zeros((64, 16), dtype=torch.uint8, device="cuda:0")
     for shape, kh, kw, a in (((1, 4, 4, 12), 3, 3, 8),        # width not a power of two
                              ((1, 4, 16, 16), 2, 2, 8),       # even window
-                             ((1, 4, 2, 128), 3, 3, 8),       # a strip of one image row cannot hold the halo
+                             ((1, 4, 4, 128), 3, 3, 8),       # a strip of one image row cannot hold the halo
                              ((1, 4, 8, 8), 3, 3, 16)):       # totals do not fit 16 bits
         b, c, h, w = shape
         qG = torch.zeros((b * h * w, 16), dtype=torch.uint8, device="cuda:0")
