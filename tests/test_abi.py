@@ -377,7 +377,7 @@ def test_folded_input_gradient_argument_errors():
     # geometries and settings the fold does not take: refused before anything is launched
     assert rc(geo=B.CConv(2, 64, 12, 12, 3, 3)) == E["HDQT_EINVAL_GEOMETRY"]
     assert rc(geo=B.CConv(2, 64, 16, 16, 2, 2)) == E["HDQT_EINVAL_GEOMETRY"]
-    assert rc(geo=B.CConv(2, 64, 2, 128, 3, 3)) == E["HDQT_EINVAL_GEOMETRY"]
+    assert rc(geo=B.CConv(2, 64, 4, 128, 3, 3)) == E["HDQT_EINVAL_GEOMETRY"]
     assert rc(a=16) == E["HDQT_EINVAL_GEOMETRY"]           # totals beyond 16 bits
     assert rc(bG=8) == E["HDQT_EINVAL_GEOMETRY"]           # 8-bit codes: not the 4-bit kernel
     assert rc(s=48) == E["HDQT_EINVAL_GEOMETRY"]           # tile length not a multiple of 32
