@@ -142,6 +142,8 @@ def main():
                     help="skip the activation-source variant of the step ('conv_step')")
     ap.add_argument("--no-sweep", action="store_true",
                     help="skip the sweep of input and accumulator widths on the same layer")
+    ap.add_argument("--no-resnet18", action="store_true",
+                    help="skip the 21 layer shapes of a ResNet-18 step ('resnet18_batch128')")
     ap.add_argument("--no-fallbacks", action="store_true",
                     help="skip the timings of the paths behind the fast kernels' shape limits ('fallback_paths')")
     ap.add_argument("--no-requant", action="store_true",
@@ -707,6 +709,45 @@ def main():
                                               + 4.0 * (Mo * No + Mo * Ko + Ko * No),
                 "kernels_us": {n_: tot / l * 1e3 for n_, (l, tot) in k_o.items()}}
             del Xo, Wo, Go, ws_o, out_o, lay_o
+    if not args.no_resnet18 and not args.separate:
+        # The 21 matmul layers of a CIFAR-width ResNet-18 at batch 128, each as one hdqt_layer_step
+        # on synthetic tensors of its shape (ReLU-like activations, Kaiming weights, small Gaussian
+        # gradients; the first layer's input gradient, which training does not need, is left out):
+        # time per layer shape, and the whole network's matmul time per training step (not `value`).
+        from paper_2310_03675_amd import workloads as wl18
+        per_shape, net_ms, net_ops = {}, 0.0, 0.0
+        table = wl18.resnet18_layer_table(128)
+        for name_l, Ml, Kl, Nl in table:
+            key = f"{Ml}x{Kl}x{Nl}"
+            with_dx = name_l != "stem"
+            if key not in per_shape:
+                g18 = torch.Generator(device="cpu").manual_seed(18 + len(per_shape))
+                Xl = torch.relu(torch.randn((Ml, Kl), generator=g18)).to(dev)
+                Wl = (torch.randn((Kl, Nl), generator=g18) * (2.0 / Kl) ** 0.5).to(dev)
+                Gl = (torch.randn((Ml, Nl), generator=g18) * 1e-2).to(dev)
+                p18 = [step_params(B, k, 64, args.s, args.acc_bits) for k in kinds]
+                p_in = p18[kinds.index(B.GEMM_BWD_INPUT)] if with_dx else None
+                p_fw, p_bw = p18[kinds.index(B.GEMM_FWD)], p18[kinds.index(B.GEMM_BWD_WEIGHT)]
+                Zl, dXl, dWl, wsl = B.layer_step(Xl, Wl, Gl, p_fw, p_in, p_bw)
+                f18 = lambda: B.layer_step(Xl, Wl, Gl, p_fw, p_in, p_bw, out=(Zl, dXl, dWl), workspace=wsl)
+                for _ in range(3):
+                    f18()
+                torch.cuda.synchronize()
+                t18 = time.perf_counter()
+                for _ in range(20):
+                    f18()
+                torch.cuda.synchronize()
+                ms18 = (time.perf_counter() - t18) / 20 * 1e3
+                ops18 = (3 if with_dx else 2) * 2.0 * Ml * Kl * Nl
+                per_shape[key] = {"ms_per_step": ms18, "TOPS": ops18 / (ms18 * 1e-3) / 1e12, "layers": 0,
+                                  "matmuls": 3 if with_dx else 2}
+                del Xl, Wl, Gl, Zl, dXl, dWl, wsl
+            per_shape[key]["layers"] += 1
+            net_ms += per_shape[key]["ms_per_step"]
+            net_ops += per_shape[key]["TOPS"] * per_shape[key]["ms_per_step"] * 1e9
+        line["resnet18_batch128"] = {"layers": len(table), "matmul_ms_per_training_step": net_ms,
+                                     "GOP_per_training_step": net_ops / 1e9,
+                                     "TOPS": net_ops / (net_ms * 1e-3) / 1e12, "per_shape": per_shape}
     if not args.no_fallbacks and not args.separate:
         # The paths behind the fast kernels' shape limits, each on the benchmark layer's forward
         # operands changed just enough to leave the fast path (not `value`; these paths have

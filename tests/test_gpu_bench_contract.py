@@ -18,7 +18,7 @@ def run_bench(*flags):
 @pytest.mark.gpu
 def test_bench_line_has_the_contract_fields():
     r = run_bench("--steps", "3", "--warmup", "1", "--no-large-quantize", "--no-square", "--no-conv",
-                  "--no-sweep", "--no-others", "--no-requant", "--no-fallbacks", "--dist-steps", "20", "--cpu-rows",
+                  "--no-sweep", "--no-others", "--no-requant", "--no-resnet18", "--no-fallbacks", "--dist-steps", "20", "--cpu-rows",
                   "2048")
     assert r.returncode == 0, r.stderr[-2000:]
     lines = [ln for ln in r.stdout.splitlines() if ln.strip()]
@@ -68,6 +68,10 @@ def test_bench_line_has_the_extra_legs():
     assert set(others) == {"har", "resnet_k576"}
     for o in others.values():
         assert o["ms_per_step"] > 0 and o["TOPS"] > 0 and o["kernels_us"]
+    # the 21 layer shapes of a ResNet-18 training step
+    r18 = d["resnet18_batch128"]
+    assert r18["layers"] == 21 and len(r18["per_shape"]) == 12 and r18["matmul_ms_per_training_step"] > 0
+    assert 420 < r18["GOP_per_training_step"] < 430
     # the paths behind the fast kernels' shape limits carry a figure each
     fb = d["fallback_paths"]
     assert set(fb) == {"fwd_K_multiple_of_8_not_32", "fwd_K_not_multiple_of_8", "fwd_mixed_4bit_8bit",
