@@ -385,8 +385,8 @@ int hdqt_conv_fwd(const float *act, const hdqt_conv_t *geo, const float *W, floa
  * order-free) and dequantized once.  dW as for hdqt_layer_bwd.  dAct, bwd_input and W are
  * required.  Workspace: hdqt_layer_bwd_workspace_size(M, K, N, ...) with M = batch*height*width,
  * K = channels*kh*kw.
- * Taken: 4-bit codes, s and N multiples of 32, ceil(N/s) * 2^(acc_bits-1) <= 32767 (the
- * folded tile is kept as 16-bit integers); kh, kw odd; width a power
+ * Taken: 4-bit codes, s and N multiples of 32, ceil(N/s) * min(2^(acc_bits-1), 64 s) <= 32767
+ * (the folded tile is kept as 16-bit integers); kh, kw odd; width a power
  * of two <= 128; height*width a power of two <= 128, or height*width = 256 with N <= 128
  * and a window of at most nine taps (a workgroup multiplies both halves of an image), or
  * 128/width >= kh image rows per strip.  Anything else: HDQT_EINVAL_GEOMETRY (before anything is launched), and the caller

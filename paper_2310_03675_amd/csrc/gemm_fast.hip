@@ -1069,8 +1069,9 @@ bool gemm_fold_plan(GemmArgs* g, int64_t batch, int C, int H, int W, int kh, int
         if (batch * g->f_strips > 65535) return false;      // grid.y
     }
     if (g->f_imgs && (batch + g->f_imgs - 1) / g->f_imgs > 65535) return false;
-    // int16 accumulator tile: |total| <= tiles * 2^(a-1)
-    const int64_t per_tile = (int64_t)g->acc_hi + 1;
+    // int16 accumulator tile: |total| <= tiles * min(2^(a-1), what a tile's products can add up to)
+    const int64_t tile_sum = g->s * (((int64_t)1 << (g->bA - 1)) * ((int64_t)1 << (g->bB - 1)));
+    const int64_t per_tile = tile_sum < (int64_t)g->acc_hi + 1 ? tile_sum : (int64_t)g->acc_hi + 1;
     if (per_tile > 32767 || per_tile * g->n_tiles > 32767) return false;
     return gemm_fast_eligible(*g);
 }

@@ -378,7 +378,7 @@ def test_folded_input_gradient_argument_errors():
     assert rc(geo=B.CConv(2, 64, 12, 12, 3, 3)) == E["HDQT_EINVAL_GEOMETRY"]
     assert rc(geo=B.CConv(2, 64, 16, 16, 2, 2)) == E["HDQT_EINVAL_GEOMETRY"]
     assert rc(geo=B.CConv(2, 64, 4, 128, 3, 3)) == E["HDQT_EINVAL_GEOMETRY"]
-    assert rc(a=16) == E["HDQT_EINVAL_GEOMETRY"]           # totals beyond 16 bits
+    assert rc(a=16, N=1024) == E["HDQT_EINVAL_GEOMETRY"]   # 32 tiles of up to 2048: totals beyond 16 bits
     assert rc(bG=8) == E["HDQT_EINVAL_GEOMETRY"]           # 8-bit codes: not the 4-bit kernel
     assert rc(s=48) == E["HDQT_EINVAL_GEOMETRY"]           # tile length not a multiple of 32
     p = _cparams()

@@ -51,6 +51,8 @@ CASES = [
     (2, 29, 16, 16, 1, 3, 128, 32, 8),
     (3, 20, 16, 16, 3, 1, 64, 32, 8),
     (2, 20, 16, 16, 3, 3, 160, 32, 8),      # two stages per tile: strips again
+    (3, 30, 8, 8, 3, 3, 128, 32, 16),       # wide accumulators whose tiles cannot reach 16 bits
+    (2, 20, 16, 16, 3, 3, 128, 128, 15),    # tiles that cannot saturate, merged by the planner
 ]
 
 
@@ -74,18 +76,16 @@ def test_gemm_codes_fold(batch, C, H, W, kh, kw, N, s, a):
 
 def test_unsupported_folds_are_refused():
     one = torch.ones(1, device="cuda:0")
-    q = torch.zeros((64, 16), dtype=torch.uint8, device="cuda:0")
-    for shape, kh, kw, a in (((1, 4, 4, 12), 3, 3, 8),        # width not a power of two
-                             ((1, 4, 16, 16), 2, 2, 8),       # even window
-                             ((1, 4, 4, 128), 3, 3, 8),       # a strip of one image row cannot hold the halo
-                             ((1, 4, 8, 8), 3, 3, 16)):       # totals do not fit 16 bits
+    for shape, kh, kw, a, N in (((1, 4, 4, 12), 3, 3, 8, 32),       # width not a power of two
+                                ((1, 4, 16, 16), 2, 2, 8, 32),      # even window
+                                ((1, 4, 4, 128), 3, 3, 8, 32),      # a strip of one image row cannot hold the halo
+                                ((1, 4, 8, 8), 3, 3, 16, 1024)):    # 32 tiles of up to 2048: totals do not fit 16 bits
         b, c, h, w = shape
-        qG = torch.zeros((b * h * w, 16), dtype=torch.uint8, device="cuda:0")
-        qW = torch.zeros((c * kh * kw, 16), dtype=torch.uint8, device="cuda:0")
+        qG = torch.zeros((b * h * w, N // 2), dtype=torch.uint8, device="cuda:0")
+        qW = torch.zeros((c * kh * kw, N // 2), dtype=torch.uint8, device="cuda:0")
         with pytest.raises(B.HdqtError) as e:
             B.gemm_codes_fold(qG, qW, 4, 4, one, one, shape, kh, kw, 32, a, 32)
         assert e.value.code == -13, (shape, kh, kw, a, e.value.code)
-    del q
 
 
 def test_conv_bwd_matches_layer_bwd_and_library_fold():
