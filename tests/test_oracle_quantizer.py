@@ -277,3 +277,21 @@ def test_packed_format():
     assert p[1].tolist() == [0x1 | (0x2 << 4), 0x3 | (0x4 << 4), 0x5]
     p8 = capi.pack_codes(codes, 8)
     assert p8.shape == (2, 5) and np.array_equal(p8.view(np.int8), codes)
+
+
+def test_quantize_is_the_transform_followed_by_the_quantizer_at_block_order_one():
+    """The oracle's quantizer calls its own transform first: quantizing the transformed tensor
+    with block order 1 gives the same codes and the same scale.  (The full-size GPU tests rely
+    on this to take the transform of a 2^28-element operand once for several code widths.)"""
+    rng = np.random.default_rng(0)
+    T = rng.standard_normal((96, 512)).astype(np.float32)
+    for axis, n in ((1, 256), (0, 32), (1, 64), (0, 64)):
+        D = T.shape[1] if axis == 1 else T.shape[0]
+        ne = capi.n_eff(D, n)
+        Y = capi.hadamard_transform(T, axis, ne)
+        for b, rnd, clip in ((4, 0, 1.0), (8, 0, 0.975), (4, 1, 1.0), (6, 1, 1.0)):
+            op = capi.Operand(b, rnd, clip, 3)
+            c1, s1, n1 = capi.quantize(T, axis, n, op, 5)
+            c2, s2, n2 = capi.quantize(Y, axis, 1, op, 5)
+            assert n1 == ne and n2 == 1
+            assert s1 == s2 and np.array_equal(c1, c2), (axis, n, b, rnd)
