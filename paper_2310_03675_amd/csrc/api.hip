@@ -947,10 +947,17 @@ int run_layer_step(const float* X, const hdqt_conv_t* geo, const float* W, const
             rc = run_quantize(W, K, N, 0, nF, &fwd->B, fwd->seed, meta(T_W0), codes(T_W0), nullptr, stream);
         if (rc) return rc;
     }
-    rc = run_planned_gemm(plan_gemm(codes(T_X1), codes(T_W0), fwd->A.b, fwd->B.b, &meta(T_X1)->scale,
-                                    &meta(T_W0)->scale, M, N, K, nF, fwd->acc_bits, fwd->s, Z, nullptr,
-                                    1 + HDQT_GEMM_FWD),
-                          acc(HDQT_GEMM_FWD), L.acc_bytes[HDQT_GEMM_FWD], stream);
+    hdqt::GemmArgs g_fwd = plan_gemm(codes(T_X1), codes(T_W0), fwd->A.b, fwd->B.b, &meta(T_X1)->scale,
+                                     &meta(T_W0)->scale, M, N, K, nF, fwd->acc_bits, fwd->s, Z, nullptr,
+                                     1 + HDQT_GEMM_FWD);
+    // Nobody can read Z before the two backward products of this call have run, and those move
+    // several times the memory-side cache: from 16 MB on, Z is written with streaming stores
+    // too.  (Measured on the 65536 x 1152 x 128 layer, Z = 33.5 MB: left in the cache as dirty
+    // lines it is written back under the kernels that follow -- forward 30.1 -> 28.1 us, and
+    // the next call's pass over X 66.6 -> 60.8 us.)  The forward call on its own keeps the
+    // 128 MB mark: its caller reads Z next.
+    if (M * N * (int64_t)sizeof(float) >= ((int64_t)16 << 20)) g_fwd.stream_out = 1;
+    rc = run_planned_gemm(g_fwd, acc(HDQT_GEMM_FWD), L.acc_bytes[HDQT_GEMM_FWD], stream);
     if (rc) return rc;
 
     // ---- backward: G along N and along M.  The weight gradient goes first: its
