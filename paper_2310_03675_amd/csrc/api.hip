@@ -305,10 +305,18 @@ int run_planned_gemm(hdqt::GemmArgs g, void* ws, size_t ws_bytes, hipStream_t st
         if (!ws || ws_bytes < (size_t)g.splits * (size_t)(g.RA * g.RB) * sizeof(int32_t))
             return HDQT_EWORKSPACE;
         g.partial = static_cast<int32_t*>(ws);
+        // A part of few tiles has totals of 16 bits: slices of half the bytes (the matrix-core
+        // kernel's packed-code instances write them, the many-slices pass reads them).
+        const int64_t max_prod = ((int64_t)1 << (g.bA - 1)) * ((int64_t)1 << (g.bB - 1));
+        const int64_t tile_sum = g.s * max_prod;
+        const int64_t per_tile = tile_sum < (int64_t)g.acc_hi + 1 ? tile_sum : (int64_t)g.acc_hi + 1;
+        g.partial16 = (hdqt::gemm_fast_eligible(g) && g.bA <= 4 && !g.fold &&
+                       per_tile * g.tiles_per_split <= 32767 &&
+                       hdqt::reduce_takes_slices16(g.splits, g.RA * g.RB)) ? 1 : 0;
         e = hdqt::launch_gemm(g, stream);
         if (e != hipSuccess) return hip_fail(e);
         e = hdqt::launch_reduce(g.partial, g.splits, g.RA * g.RB, g.scaleA, g.scaleB, g.inv_n, g.out,
-                                g.out_bf16, g.acc_out, stream, g.mask_src);
+                                g.out_bf16, g.acc_out, stream, g.mask_src, g.partial16 != 0);
         return e == hipSuccess ? HDQT_OK : hip_fail(e);
     }
     e = hdqt::launch_gemm(g, stream);

@@ -91,6 +91,7 @@ struct GemmArgs {
                             // where mask_src > 0 and +0 elsewhere (the rectifier's backward pass
                             // behind an input gradient); the integer outputs are not masked
     int32_t* acc_out;       // [RA, RB] or null
+    int partial16;          // the slices hold 16-bit integers (a part's totals fit: parts of few tiles)
     int32_t* partial;       // [splits, RA, RB] when splits > 1: one slice per part of the contraction;
                             // second reading of the accumulator: [n_tiles, RA, RB], every tile's sums
     uint32_t* tile_max;     // second reading only: max |tile sum| per tile, zero beforehand
@@ -155,7 +156,9 @@ hipError_t launch_zero2(uint32_t* a, int64_t na, uint32_t* b, int64_t nb, hipStr
 // out_bf16 (nullable): the dequantized totals narrowed to bfloat16
 hipError_t launch_reduce(const int32_t* partial, int splits, int64_t count, const float* scaleA,
                          const float* scaleB, float inv_n, float* out, uint16_t* out_bf16,
-                         int32_t* acc_out, hipStream_t stream, const float* mask_src = nullptr);
+                         int32_t* acc_out, hipStream_t stream, const float* mask_src = nullptr,
+                         bool slices16 = false);
+bool reduce_takes_slices16(int splits, int64_t count);
 // out[e] = mask_src[e] > 0 ? out[e] : +0 (for the matmul paths that do not mask in their epilogue)
 hipError_t launch_relu_mask(float* out, const float* mask_src, int64_t count, hipStream_t stream);
 // whether the matrix-core kernel applies g.mask_src in its own epilogue

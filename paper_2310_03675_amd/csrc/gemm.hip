@@ -262,7 +262,7 @@ __global__ __launch_bounds__(256) void reduce_kernel(const int32_t* partial, int
 // every sixteenth slice, and the first of them adds the sixteen sums from LDS.  A thread of
 // the kernel above walks all slices one after the other, which is latency, not bandwidth,
 // once there are more than a few dozen.
-template <int VEC>
+template <int VEC, bool S16 = false>
 __global__ __launch_bounds__(256) void reduce_many_kernel(const int32_t* partial, int splits, int64_t count,
                                                           const float* scaleA, const float* scaleB,
                                                           float inv_n, float* out, uint16_t* out_bf16,
@@ -274,14 +274,24 @@ __global__ __launch_bounds__(256) void reduce_many_kernel(const int32_t* partial
     const int64_t e = ((int64_t)blockIdx.x * EPB + el) * VEC;
     int t[4] = {0, 0, 0, 0};
     if (e < count) {
-        const int32_t* src = partial + (int64_t)sg * count + e;
+        if constexpr (S16) {
+            // slices of 16-bit integers (VEC = 4: four of them are one 8-byte load)
+            const int16_t* src = reinterpret_cast<const int16_t*>(partial) + (int64_t)sg * count + e;
 #pragma unroll 4
-        for (int z = sg; z < splits; z += SG, src += (int64_t)SG * count) {
-            if (VEC == 4) {
-                const int4 v = *reinterpret_cast<const int4*>(src);
+            for (int z = sg; z < splits; z += SG, src += (int64_t)SG * count) {
+                const short4 v = *reinterpret_cast<const short4*>(src);
                 t[0] += v.x; t[1] += v.y; t[2] += v.z; t[3] += v.w;
-            } else {
-                t[0] += src[0];
+            }
+        } else {
+            const int32_t* src = partial + (int64_t)sg * count + e;
+#pragma unroll 4
+            for (int z = sg; z < splits; z += SG, src += (int64_t)SG * count) {
+                if (VEC == 4) {
+                    const int4 v = *reinterpret_cast<const int4*>(src);
+                    t[0] += v.x; t[1] += v.y; t[2] += v.z; t[3] += v.w;
+                } else {
+                    t[0] += src[0];
+                }
             }
         }
     }
@@ -365,16 +375,26 @@ hipError_t launch_relu_mask(float* out, const float* mask_src, int64_t count, hi
     return hipGetLastError();
 }
 
+// 16-bit slices are read by the many-slices kernel only, four elements per 8-byte load
+bool reduce_takes_slices16(int splits, int64_t count)
+{
+    return splits >= 32 && count % 4 == 0 && (count / 4 + 15) / 16 < ((int64_t)1 << 31);
+}
+
 hipError_t launch_reduce(const int32_t* partial, int splits, int64_t count, const float* scaleA,
                          const float* scaleB, float inv_n, float* out, uint16_t* out_bf16,
-                         int32_t* acc_out, hipStream_t stream, const float* mask_src)
+                         int32_t* acc_out, hipStream_t stream, const float* mask_src, bool slices16)
 {
     const bool vec = (count % 4 == 0);
     const int64_t groups = vec ? count / 4 : count;
+    if (slices16 && !reduce_takes_slices16(splits, count)) return hipErrorInvalidValue;
     if (splits >= 32 && (groups + 15) / 16 < ((int64_t)1 << 31)) {
         ProfileScope ps(K_REDUCE, stream);
         const dim3 grid((unsigned)((groups + 15) / 16));
-        if (vec)
+        if (slices16)
+            hipLaunchKernelGGL((reduce_many_kernel<4, true>), grid, dim3(256), 0, stream, partial, splits, count,
+                               scaleA, scaleB, inv_n, out, out_bf16, acc_out, mask_src);
+        else if (vec)
             hipLaunchKernelGGL(reduce_many_kernel<4>, grid, dim3(256), 0, stream, partial, splits, count, scaleA,
                                scaleB, inv_n, out, out_bf16, acc_out, mask_src);
         else

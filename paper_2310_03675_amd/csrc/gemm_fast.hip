@@ -887,8 +887,12 @@ __global__ __launch_bounds__(64 * WAVES, WAVES == 8 ? (MASK ? 3 : 4) : 2) void g
         // bfloat16 output of an interior tile with an even row length: lanes l and l ^ 1 hold
         // neighbouring columns and trade their values, so that every lane stores one dword
         const bool pair_bf16 = hb && interior && (g.RB % 2 == 0);
-        int32_t* ab = g.splits > 1 ? g.partial + (int64_t)blockIdx.x * g.RA * g.RB + tile_off
-                                   : (g.acc_out ? g.acc_out + tile_off : nullptr);
+        const bool slice16 = g.splits > 1 && g.partial16;
+        int32_t* ab = slice16 ? nullptr
+                              : (g.splits > 1 ? g.partial + (int64_t)blockIdx.x * g.RA * g.RB + tile_off
+                                              : (g.acc_out ? g.acc_out + tile_off : nullptr));
+        int16_t* ab16 = slice16 ? reinterpret_cast<int16_t*>(g.partial) + (int64_t)blockIdx.x * g.RA * g.RB + tile_off
+                                : nullptr;
         if constexpr (BF16) if (pair_bf16) {
             const bool odd = lane & 1;
             auto value = [&](int t) -> float {
@@ -953,6 +957,7 @@ __global__ __launch_bounds__(64 * WAVES, WAVES == 8 ? (MASK ? 3 : 4) : 2) void g
                     if (BF16 && hb && !pair_bf16 && ok) (hb + uo)[lane_off] = (uint16_t)bf16_bits((float)v * dq);
                     if (ok) {
                         if (ab) (ab + uo)[lane_off] = v;
+                        if (ab16) (ab16 + uo)[lane_off] = (int16_t)v;
                         if (ob) {
                             // (a template flag, not a run-time branch: merging the two stores
                             // would drop the streaming hint)
