@@ -246,14 +246,34 @@ hdqt::GemmArgs plan_gemm(const void* qA, const void* qB, int bA, int bB, const f
                 g.s = grp;
                 break;
             }
+    }
+    // The parts of a split contraction are chosen from the tiles as they stand here; parts
+    // begin on a stage of the matrix-core kernel (128 codes) when the tile length divides
+    // one: every 16-byte load of a part then lies inside one 64-byte run of its row
+    // (measured on the benchmark layer's weight gradient: 37 -> 40 tiles per part, 35.7 ->
+    // 33.1 us), and a tile of 16 codes never starts in the middle of a 32-code step.
+    const int64_t plan_tiles = (D + g.s - 1) / g.s;
+    g.splits = choose_splits(RA, RB, D, plan_tiles);
+    int64_t part_tiles = (plan_tiles + g.splits - 1) / g.splits;
+    if (g.splits > 1 && g.s < 128 && 128 % g.s == 0) {
+        const int64_t q = 128 / g.s;
+        part_tiles = (part_tiles + q - 1) / q * q;
+    }
+    const int64_t part_codes = part_tiles * g.s;
+    if (!keep_tiles) {
         // Tiles that cannot saturate at all: every clamp is the identity and the result is the
         // plain integer product, so the tiles may as well be longer (the kernels clamp at tile
         // ends: 2048 codes are 16 stages of the matrix-core kernel between two clamps) and the
         // accumulator 32 bits wide -- as long as the product itself, times the factor 256 the
-        // packed-code kernel carries, stays inside int32.
+        // packed-code kernel carries, stays inside int32, and a part of a split contraction
+        // stays a whole number of tiles (fewer, longer parts would leave compute units idle:
+        // the weight gradient of the 65536 x 1152 x 128 layer with 8-bit codes and 32-bit
+        // accumulators fell from 52 parts to 8).
+        const int64_t max_prod = ((int64_t)1 << (bA - 1)) * ((int64_t)1 << (bB - 1));
         const int64_t room = (bA <= 4 && bB <= 4) ? ((int64_t)1 << 22) : ((int64_t)1 << 31);
         if (g.s % 128 == 0 && g.s * max_prod <= (int64_t)g.acc_hi && D * max_prod < room) {
-            while (g.s * 2 <= 2048 && g.s * 2 <= D) g.s *= 2;
+            while (g.s * 2 <= 2048 && g.s * 2 <= D && (g.splits == 1 || part_codes % (g.s * 2) == 0))
+                g.s *= 2;
             g.acc_lo = INT_MIN;
             g.acc_hi = INT_MAX;
         }
@@ -269,16 +289,7 @@ hdqt::GemmArgs plan_gemm(const void* qA, const void* qB, int bA, int bB, const f
     // the input gradient of the 65536 x 1152 layer takes 90 us instead of 53 us).
     const int64_t out_elem = out ? (int64_t)sizeof(float) : (int64_t)sizeof(uint16_t);
     g.stream_out = (RA * RB * out_elem >= ((int64_t)128 << 20)) ? 1 : 0;
-    g.splits = choose_splits(RA, RB, D, g.n_tiles);
-    g.tiles_per_split = (g.n_tiles + g.splits - 1) / g.splits;
-    // Parts begin on a stage of the matrix-core kernel (128 codes) when the tile length
-    // divides one: every 16-byte load of a part then lies inside one 64-byte run of its row
-    // (measured on the benchmark layer's weight gradient: 37 -> 40 tiles per part, 35.7 ->
-    // 33.1 us), and a tile of 16 codes never starts in the middle of a 32-code step.
-    if (g.splits > 1 && g.s < 128 && 128 % g.s == 0) {
-        const int64_t q = 128 / g.s;
-        g.tiles_per_split = (g.tiles_per_split + q - 1) / q * q;
-    }
+    g.tiles_per_split = g.splits > 1 ? part_codes / g.s : g.n_tiles;
     g.splits = (int)((g.n_tiles + g.tiles_per_split - 1) / g.tiles_per_split);
     return g;
 }
