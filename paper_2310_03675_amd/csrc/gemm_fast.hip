@@ -31,6 +31,8 @@
 
 #include "common.hpp"
 
+#include <type_traits>
+
 namespace hdqt {
 
 namespace {
@@ -53,7 +55,24 @@ constexpr int kScaleShift = 8;        // both operands carry a factor 16
 
 enum Epilogue { EPI_GENERIC = 0, EPI_SAT8_S32 = 1, EPI_SAT8_S64 = 2, EPI_STAGES = 3, EPI_SAT16_S32 = 4,
                 EPI_SAT16_S64 = 5, EPI_SAT8_S16 = 6, EPI_SAT16_S16 = 7, EPI_CLAMP_S16 = 8,
-                EPI_REQ_MAX = 9, EPI_REQ_SUM = 10, EPI_REQ_MAX_S32 = 11, EPI_REQ_SUM_S32 = 12 };
+                EPI_REQ_MAX = 9, EPI_REQ_SUM = 10, EPI_REQ_MAX_S32 = 11, EPI_REQ_SUM_S32 = 12,
+                EPI_CERT8_S32 = 13 };
+// EPI_CERT8_S32: 8-bit accumulators, tiles of 32 packed 4-bit codes, as EPI_SAT8_S32 -- but a
+// tile whose sums provably stay inside the accumulator is not clamped at all.  The proof is
+// the Cauchy-Schwarz bound: |sum_k a_k b_k| <= sqrt(sum a_k^2 * sum b_k^2), so with nA the largest
+// sum of squares over the wave's rows of A in this tile and nB the same over its columns of B,
+// nA * nB <= 127^2 means that no clamp of the tile can act, and the matrix core adds the tile
+// straight onto the totals (no vector instruction at all).  The sums of squares cost four
+// v_dot8_i32_i4 per 16-byte unit on its way to LDS, a few lane operations and a 512-byte table.
+// The totals therefore carry the factor 256 of the unpacking throughout.  Tiles that fail the
+// test are saturated to int16 as before and added with v_dot2_i32_i16, i.e. still times 256;
+// a sum that saturates upwards adds 32767 where 127 * 256 = 32512 is meant, 255 too many, so
+// that a total is 256 * (T + p) - p with T the true total and p <= 255 the number of its
+// tiles that saturated upwards (hence at most 255 tiles per part): p = -total mod 256 and
+// T = (total + p) / 256 - p, taken once at the end of an output tile.
+// Quantizer output of heavy-tailed tensors (activations, most gradients) has small codes and
+// passes nearly everywhere; codes that fill their range fail, and then this is EPI_SAT8_S32
+// plus the test.
 // EPI_REQ_MAX / EPI_REQ_SUM: the second reading of the low-bit accumulator (Methodology, tiled
 // quantization: every tile's partial-sum tensor through Q with a bits and its own maximum) as
 // two passes over the same product, neither of which stores a tile sum.  The first keeps, per
@@ -142,6 +161,32 @@ __device__ __forceinline__ void mask_tail(uint4& w, int valid, int per_dword, in
     w.y = first + per_dword < valid ? w.y : 0u;
     w.z = first + 2 * per_dword < valid ? w.z : 0u;
     w.w = first + 3 * per_dword < valid ? w.w : 0u;
+}
+
+// total += 256 * (clamp(p0/256, -128, 127) + clamp(p1/256, -128, 127)), plus 255 for each of the
+// two that saturates upwards (see EPI_CERT8_S32)
+__device__ __forceinline__ int add_sat8_pair_scaled(int total, int p0, int p1)
+{
+    const v2s pk = __builtin_amdgcn_cvt_pk_i16(p0, p1);
+    const v2s ones = {1, 1};
+    return __builtin_amdgcn_sdot2(pk, ones, total, false);
+}
+
+// sum of the squares of the 32 signed 4-bit codes of a unit
+__device__ __forceinline__ int unit_norm(const uint4& w)
+{
+    int n = __builtin_amdgcn_sdot8((int)w.x, (int)w.x, 0, false);
+    n = __builtin_amdgcn_sdot8((int)w.y, (int)w.y, n, false);
+    n = __builtin_amdgcn_sdot8((int)w.z, (int)w.z, n, false);
+    return __builtin_amdgcn_sdot8((int)w.w, (int)w.w, n, false);
+}
+
+// max(x, x of the lane SHR places below in the same row of 16 lanes; 0 where there is none)
+template <int SHR>
+__device__ __forceinline__ int max_row_shr(int x)
+{
+    const int below = __builtin_amdgcn_update_dpp(0, x, 0x110 + SHR, 0xF, 0xF, true);
+    return x > below ? x : below;
 }
 
 // total += clamp(p0/256, -128, 127) + clamp(p1/256, -128, 127)
@@ -256,7 +301,9 @@ __global__ __launch_bounds__(64 * WAVES, WAVES == 8 ? (MASK ? 3 : 4) : 2) void g
     constexpr bool kReqSum = (EPI == EPI_REQ_SUM || EPI == EPI_REQ_SUM_S32), kReq = kReqMax || kReqSum;
     constexpr bool kReqS32 = (EPI == EPI_REQ_MAX_S32 || EPI == EPI_REQ_SUM_S32);
     static_assert(!kReq || (!BF16 && !FOLD && !WIDE && !NARROW && !MASK), "second reading: plain packed instances only");
-    const int fin_shift = kSat16 ? g.fin_shift : ((kSat8 || kReq) ? 0 : SHIFT);
+    constexpr bool kCert = (EPI == EPI_CERT8_S32);
+    static_assert(!kCert || (WAVES == 8 && KS == KS_LONG && !BF16 && !FOLD && !WIDE && !MASK), "certified tiles: plain packed instances only");
+    const int fin_shift = kSat16 ? g.fin_shift : ((kSat8 || kReq || kCert) ? 0 : SHIFT);
     const uint32_t low_clear = kSat16 ? (0xFFFFu & (0xFFFFu << g.fin_shift)) * 0x00010001u : 0u;
     constexpr int REGS = WIDE ? 2 : 1;                 // 16-byte registers per unit in flight
     // WAVES = 4: each wave a 64 x 64 quarter (2 x 2 MFMA blocks).  WAVES = 8: each wave
@@ -276,6 +323,21 @@ __global__ __launch_bounds__(64 * WAVES, WAVES == 8 ? (MASK ? 3 : 4) : 2) void g
     __shared__ __attribute__((aligned(16))) uint8_t Bs[2][TN][LDP];
     // second reading: per tile of this part, the running maximum (times 256) in the first pass,
     // m_t and fl(2^(a-1) / m_t) / 256 in the second
+    // certified tiles: per stage buffer and operand, the largest sum of squares over the 16 rows
+    // each wave loaded, for each of the stage's four tiles
+    __shared__ int cert_n[kCert ? 2 : 1][2][kCert ? WAVES : 1][4];
+    bool cert_clamped = false;        // (wave-uniform) some tile of the current output tile went through the clamp
+    // Codes that fill their range pass the test nowhere, and a workgroup that finds this out stops
+    // testing: when any wave's first stage holds a tile that has to be clamped, every wave takes
+    // the clamp for every tile from the third stage on, without sums of squares, table or flags.
+    // cert_off is written during the first stage's multiplication and read after the barriers of
+    // later stages, i.e. after every wave has left the first stage: the same value in all waves.
+    __shared__ int cert_off;
+    bool cert_plain = false;          // (workgroup-uniform) the test has been given up
+    int cert_stage = 0;               // 0: the first stage of this workgroup, 1: a later one
+    if constexpr (kCert) {
+        if (threadIdx.x == 0) cert_off = 0;   // (ordered before the first write by the barrier of the first stage)
+    }
     __shared__ int req_m[kReq ? kReqTable : 1];
     __shared__ float req_inv[kReqSum ? kReqTable : 1];
 
@@ -457,7 +519,15 @@ __global__ __launch_bounds__(64 * WAVES, WAVES == 8 ? (MASK ? 3 : 4) : 2) void g
     // Whole stages only: positions at or beyond k_end are zero in LDS and add nothing.
     // One barrier per stage is enough: buffer `buf` was last read two stages ago,
     // and every wave has passed the previous stage's barrier since.
-    auto stage = [&](Staged<UNITS * REGS, UNITS_B * REGS>& st, const int buf) {
+    // `gave_up` (a std::true_type / false_type; only EPI_CERT8_S32 has both): the stage as the
+    // workgroup runs it once the test of its tiles has been given up -- EPI_SAT8_S32's loop
+    // with totals that carry the factor 256.  A body of its own, in a loop of its own: there
+    // the totals are single registers again, and the clamps of one pair overlap the MFMAs of
+    // the next as in EPI_SAT8_S32 (as a branch inside the testing stage the same code either
+    // spilled 30 registers or, cut into pairs by the flags' branches, ran 9 % slower).
+    auto stage = [&](Staged<UNITS * REGS, UNITS_B * REGS>& st, const int buf, auto gave_up) {
+        constexpr bool kGaveUp = decltype(gave_up)::value;
+        constexpr bool kTest = kCert && !kGaveUp;
         if (g.D & (KSTEP - 1)) {
             // rows that end inside a 32-code unit: the thread's units of this stage all start at
             // the same position of their rows
@@ -469,6 +539,22 @@ __global__ __launch_bounds__(64 * WAVES, WAVES == 8 ? (MASK ? 3 : 4) : 2) void g
                     if (i < UNITS_B * REGS) mask_tail(st.b[i], (int)valid, WIDE ? 4 : 8, WIDE ? 16 * (i & 1) : 0);
                 }
             }
+        }
+        if (kTest && !cert_plain) {
+            // lane l of the wave holds tile l % 4 of row 16 * wave + l / 4 of both operands.
+            // One swap of the wave's halves and one of its odd and even rows bring the largest
+            // over lane bits 4 and 5 of A into the lower half and of B into the upper half; two
+            // shifted maxima inside the rows finish in lanes 12 .. 15 (A) and 44 .. 47 (B).
+            static_assert(!kCert || UNITS == 1, "one unit per thread and operand");
+            const int na = unit_norm(st.a[0]), nb = unit_norm(st.b[0]);
+            typedef unsigned v2u __attribute__((ext_vector_type(2)));
+            v2u sw = __builtin_amdgcn_permlane32_swap((unsigned)na, (unsigned)nb, false, false);
+            int m = (int)(sw[0] > sw[1] ? sw[0] : sw[1]);
+            sw = __builtin_amdgcn_permlane16_swap((unsigned)m, (unsigned)m, false, false);
+            m = (int)(sw[0] > sw[1] ? sw[0] : sw[1]);
+            m = max_row_shr<4>(m);
+            m = max_row_shr<8>(m);
+            if ((lane & 28) == 12) cert_n[buf][lane >> 5][wave][lane & 3] = m;
         }
 #pragma unroll
         for (int i = 0; i < UNITS; ++i) {
@@ -500,10 +586,68 @@ __global__ __launch_bounds__(64 * WAVES, WAVES == 8 ? (MASK ? 3 : 4) : 2) void g
         }
         __syncthreads();
         fetch_next(st);
+        // cert_ok: the pair's tiles go straight onto the totals; cert_no: through the clamp.  Two
+        // flags whose relation the compiler cannot see: written as if / else, the two ways of
+        // updating the totals (whole register tuples by the matrix core, single registers by the
+        // clamp) meet in a join that copies all 32 of them on both sides; as two independent
+        // conditional blocks each updates them in place.
+        int cert_ok[NSTEP / 2] = {}, cert_no[NSTEP / 2] = {};
+        v4i cert_fa[2][RS], cert_fb[2][CS];
+        if constexpr (kTest) {
+#pragma unroll
+            for (int pr = 0; pr < NSTEP / 2; ++pr) cert_no[pr] = 1;
+        }
+        if (kTest && cert_plain) {
+            // (a stage in the testing body after the test was given up: every flag stays down)
+#pragma unroll
+            for (int q = 0; q < 2; ++q)
+#pragma unroll
+                for (int h = 0; h < HS; ++h) {
+                    if (h < RS) cert_fa[q][h] = frag(As[buf], wm * WROWS + h * 32, q);
+                    if (h < CS) cert_fb[q][h] = frag(Bs[buf], wn * WCOLS + h * 32, q);
+                }
+        }
+        if (kTest && !cert_plain) {
+            // lanes 0 .. 15: the loader waves of this wave's rows of A, lanes 16 .. 31: of its
+            // columns of B (waves repeat where there are fewer than four), tile l % 4
+            const int j = (lane >> 2) & 3, op = (lane >> 4) & 1;
+            constexpr int LA = WROWS / 16, LB = WCOLS / 16;
+            const int lw = op ? wn * LB + j % LB : wm * LA + j % LA;
+            int m = cert_n[buf][op][lw][lane & 3];
+            const int off = cert_stage ? cert_off : 0;
+            // (the first pair's fragments set out while the flags are worked out)
+#pragma unroll
+            for (int q = 0; q < 2; ++q)
+#pragma unroll
+                for (int h = 0; h < HS; ++h) {
+                    if (h < RS) cert_fa[q][h] = frag(As[buf], wm * WROWS + h * 32, q);
+                    if (h < CS) cert_fb[q][h] = frag(Bs[buf], wn * WCOLS + h * 32, q);
+                }
+            m = max_row_shr<4>(m);
+            m = max_row_shr<8>(m);
+            const int limit = 127 * 127;
+            int any_no = 0;
+#pragma unroll
+            for (int pr = 0; pr < NSTEP / 2; ++pr) {
+                const int a0 = __builtin_amdgcn_readlane(m, 12 + 2 * pr), a1 = __builtin_amdgcn_readlane(m, 13 + 2 * pr);
+                const int b0 = __builtin_amdgcn_readlane(m, 28 + 2 * pr), b1 = __builtin_amdgcn_readlane(m, 29 + 2 * pr);
+                // (sums of squares of 32 codes: at most 2048 each)
+                cert_ok[pr] = __builtin_amdgcn_readfirstlane((a0 * b0 <= limit && a1 * b1 <= limit) ? 1 : 0);
+                asm volatile("s_xor_b32 %0, %1, 1" : "=s"(cert_no[pr]) : "s"(cert_ok[pr]));
+                any_no |= cert_no[pr];
+            }
+            if (cert_stage == 0) {
+                if (any_no && lane == 0) cert_off = 1;
+                cert_stage = 1;
+            } else if (__builtin_amdgcn_readfirstlane(off)) {
+                cert_plain = true;
+            }
+        }
         // Tiles of 16 and 32 codes: the waves that are multiplying and clamping go first
         // (measured on 4096^3 with tiles of 32: 156 -> 146 us; nothing for tiles of 64, and
         // the whole-stage loop loses 5 %, so it is left alone)
         if constexpr (kPairs32 || kPairs16) __builtin_amdgcn_s_setprio(1);
+        if (kCert && (kGaveUp || cert_plain)) __builtin_amdgcn_s_setprio(1);
 
         if constexpr (kPairs16) {
             // two tiles per step
@@ -534,6 +678,64 @@ __global__ __launch_bounds__(64 * WAVES, WAVES == 8 ? (MASK ? 3 : 4) : 2) void g
                                                         : add_sat8_pair(total[a][c][r], p0[r], p1[r]);
                         }
                     }
+            }
+        } else if (kCert && kGaveUp) {
+            cert_clamped = true;
+#pragma unroll
+            for (int pr = 0; pr < NSTEP / 2; ++pr) {
+                v4i fa[2][RS], fb[2][CS];
+#pragma unroll
+                for (int q = 0; q < 2; ++q)
+#pragma unroll
+                    for (int h = 0; h < HS; ++h) {
+                        if (h < RS) fa[q][h] = frag(As[buf], wm * WROWS + h * 32, pr * 2 + q);
+                        if (h < CS) fb[q][h] = frag(Bs[buf], wn * WCOLS + h * 32, pr * 2 + q);
+                    }
+#pragma unroll
+                for (int a = 0; a < RS; ++a)
+#pragma unroll
+                    for (int c = 0; c < CS; ++c) {
+                        const v16i p0 = __builtin_amdgcn_mfma_i32_32x32x32_i8(fa[0][a], fb[0][c], zero, 0, 0, 0);
+                        const v16i p1 = __builtin_amdgcn_mfma_i32_32x32x32_i8(fa[1][a], fb[1][c], zero, 0, 0, 0);
+#pragma unroll
+                        for (int r = 0; r < 16; ++r)
+                            total[a][c][r] = add_sat8_pair_scaled(total[a][c][r], p0[r], p1[r]);
+                    }
+            }
+        } else if (kCert) {
+            // two tiles per half stage, straight onto the totals where the test allows it
+#pragma unroll
+            for (int pr = 0; pr < NSTEP / 2; ++pr) {
+                v4i fa[2][RS], fb[2][CS];
+#pragma unroll
+                for (int q = 0; q < 2; ++q)
+#pragma unroll
+                    for (int h = 0; h < HS; ++h) {
+                        if (h < RS) fa[q][h] = pr ? frag(As[buf], wm * WROWS + h * 32, pr * 2 + q) : cert_fa[q][h];
+                        if (h < CS) fb[q][h] = pr ? frag(Bs[buf], wn * WCOLS + h * 32, pr * 2 + q) : cert_fb[q][h];
+                    }
+                if (cert_ok[pr]) {
+#pragma unroll
+                    for (int q = 0; q < 2; ++q)
+#pragma unroll
+                        for (int a = 0; a < RS; ++a)
+#pragma unroll
+                            for (int c = 0; c < CS; ++c)
+                                total[a][c] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fa[q][a], fb[q][c], total[a][c], 0, 0, 0);
+                }
+                if (cert_no[pr]) {
+                    cert_clamped = true;
+#pragma unroll
+                    for (int a = 0; a < RS; ++a)
+#pragma unroll
+                        for (int c = 0; c < CS; ++c) {
+                            const v16i p0 = __builtin_amdgcn_mfma_i32_32x32x32_i8(fa[0][a], fb[0][c], zero, 0, 0, 0);
+                            const v16i p1 = __builtin_amdgcn_mfma_i32_32x32x32_i8(fa[1][a], fb[1][c], zero, 0, 0, 0);
+#pragma unroll
+                            for (int r = 0; r < 16; ++r)
+                                total[a][c][r] = add_sat8_pair_scaled(total[a][c][r], p0[r], p1[r]);
+                        }
+                }
             }
         } else if (kPairs32 || kPairs64) {
             // two tiles per half stage (s = 32) or per stage (s = 64)
@@ -676,6 +878,7 @@ __global__ __launch_bounds__(64 * WAVES, WAVES == 8 ? (MASK ? 3 : 4) : 2) void g
         }
 
         if constexpr (kPairs32 || kPairs16) __builtin_amdgcn_s_setprio(0);
+        if (kCert && (kGaveUp || cert_plain)) __builtin_amdgcn_s_setprio(0);
         c_k += KS;
         if (c_k < k_end) return;
 
@@ -692,6 +895,27 @@ __global__ __launch_bounds__(64 * WAVES, WAVES == 8 ? (MASK ? 3 : 4) : 2) void g
                         total[a][c][r] += clamp3(part[a][c][r], lo, hi);
                         part[a][c][r] = 0;
                     }
+        }
+        if constexpr (kCert) {
+            if (cert_clamped) {
+                cert_clamped = false;
+#pragma unroll
+                for (int a = 0; a < RS; ++a)
+#pragma unroll
+                    for (int c = 0; c < CS; ++c)
+#pragma unroll
+                        for (int r = 0; r < 16; ++r) {
+                            const int t = total[a][c][r], p = -t & 255;
+                            total[a][c][r] = ((t + p) >> kScaleShift) - p;
+                        }
+            } else {
+#pragma unroll
+                for (int a = 0; a < RS; ++a)
+#pragma unroll
+                    for (int c = 0; c < CS; ++c)
+#pragma unroll
+                        for (int r = 0; r < 16; ++r) total[a][c][r] >>= kScaleShift;
+            }
         }
         if constexpr (kReq) {
             if (step_in_tile != 0) {      // a short last tile (D not a multiple of s)
@@ -981,21 +1205,36 @@ __global__ __launch_bounds__(64 * WAVES, WAVES == 8 ? (MASK ? 3 : 4) : 2) void g
     // no eight registers to spare at four waves per SIMD.
     // (the fold epilogue needs the registers; with a byte per code a stage in flight is twice as many)
     constexpr bool kDeep = !kPairs64 && !FOLD && !WIDE;
+    // EPI_CERT8_S32 has the loop of its given-up stages (see `stage`) in the instances for
+    // outputs that stay in the caches.  Those for streamed outputs go on in the testing stage
+    // with every flag down: with the second loop compiled in, their testing stage came out 14 %
+    // slower (the forward product of the 65536 x 1152 x 128 layer: 25.7 against 22.6 us), and
+    // the one given-up case measured there, that layer's input gradient, is 10 % faster with
+    // its clamps cut into pairs (67.4 against 75.6 us: it is bound by its stores).
+    constexpr bool kTwoLoops = kCert && !STREAM;
     if constexpr (kDeep) {
         Staged<UNITS * REGS, UNITS_B * REGS> st0, st1;
         fetch_next(st0);
         fetch_next(st1);
         while (c_ct < n_ct) {       // stage() advances c_ct at the end of a tile
-            stage(st0, 0);
+            stage(st0, 0, std::false_type{});
             if (c_ct >= n_ct) break;
-            stage(st1, 1);
+            stage(st1, 1, std::false_type{});
+            if (kTwoLoops && cert_plain) break;      // (left where the buffers are back in step)
+        }
+        if constexpr (kTwoLoops) {
+            while (c_ct < n_ct) {
+                stage(st0, 0, std::true_type{});
+                if (c_ct >= n_ct) break;
+                stage(st1, 1, std::true_type{});
+            }
         }
     } else {
         Staged<UNITS * REGS, UNITS_B * REGS> st;
         fetch_next(st);
         int buf = 0;
         while (c_ct < n_ct) {
-            stage(st, buf);
+            stage(st, buf, std::false_type{});
             buf ^= 1;
         }
     }
@@ -1140,6 +1379,27 @@ static bool narrow_tiles(const GemmArgs& g)
     return !sat16_path(g);
 }
 
+// Tiles of 32 packed codes with 8-bit accumulators take the instances that test whether a tile
+// can saturate at all (EPI_CERT8_S32) where the plain fp32 / int32 output is asked for, a
+// part has at most 255 tiles (the count of upward saturations must fit the totals' low byte)
+// and at least five stages: the test costs a quarter of a clamped stage and can only be given
+// up from the third stage on, so on short contractions (an input gradient over 64 to 512
+// output channels) it loses 5 to 10 % where it fails and gains little where it holds.  The
+// 128 x 64 tile has no such instance either (half the clamps per wave to save, the same test
+// to pay: 4 % slower on the 262144 x 576 x 64 layer).
+// One more case, by measurement alone: a streamed output that a workgroup walks across for
+// eight column tiles or more (the input gradient of the 65536 x 1152 x 128 layer: one stage
+// per tile, codes that fail the test, so the workgroups give it up at their second tile) runs
+// 5 % faster in these instances' given-up state than in EPI_SAT8_S32 -- 68 against 72 us, in
+// six interleaved runs; with fewer column tiles (576 or 320 columns) it is 5 to 7 % slower.
+static bool cert_tiles(const GemmArgs& g, int64_t n_ct)
+{
+    if (g.fold || g.out_bf16 || g.bA > 4 || g.bB > 4 || g.mask_src) return false;
+    if (g.acc_hi != 127 || g.s != 32 || g.tiles_per_split > 255) return false;
+    if (g.tiles_per_split * g.s > 4 * KS_LONG) return true;
+    return g.stream_out && n_ct >= 8 && g.D >= KS_LONG;
+}
+
 // Second reading of the accumulator in this kernel: packed 4-bit codes on both sides, tiles that
 // are whole 32-code steps, accumulators of at most 16 bits (the rounding by addition needs
 // |value| < 2^22), at most kReqTable tiles per part, tile sums times 256 inside int32.
@@ -1263,6 +1523,12 @@ hipError_t launch_gemm_fast(const GemmArgs& g_in, hipStream_t stream)
             if (g.stream_out) hipLaunchKernelGGL((gemm_i4_kernel<EPI_GENERIC, KS_LONG, true, kWaves, false, false, true>), grid, block, 0, stream, g);
             else hipLaunchKernelGGL((gemm_i4_kernel<EPI_GENERIC, KS_LONG, false, kWaves, false, false, true>), grid, block, 0, stream, g);
         }
+    } else if (s32 && !masked && !narrow && cert_tiles(g, n_ct)) {
+        const dim3 block(64 * kWaves);
+        if (g.stream_out)
+            hipLaunchKernelGGL((gemm_i4_kernel<EPI_CERT8_S32, KS_LONG, true, kWaves, false, false>), grid, block, 0, stream, g);
+        else
+            hipLaunchKernelGGL((gemm_i4_kernel<EPI_CERT8_S32, KS_LONG, false, kWaves, false, false>), grid, block, 0, stream, g);
     } else if (s32) HDQT_LAUNCH_I4(EPI_SAT8_S32);
     else if (sat8_path(g)) HDQT_LAUNCH_I4(EPI_SAT8_S64);
     else if (g.s % KS_LONG == 0) HDQT_LAUNCH_I4(EPI_STAGES);

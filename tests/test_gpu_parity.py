@@ -291,6 +291,78 @@ def test_gemm_codes_split_contraction():
     check_gemm_codes(1, 1, 4096, 4, 4, 16, 4, n=64, extreme=0.9)
 
 
+def gaussian_codes(rng, lines, D, sigma):
+    return np.clip(np.rint(rng.normal(0.0, sigma, size=(lines, D))), -8, 7).astype(np.int8)
+
+
+def check_gemm_codes_given(cA, cB, s, a):
+    D = cA.shape[1]
+    n = 64 if D % 64 == 0 else 8
+    print(f"gemm_codes (given codes) RA={cA.shape[0]} RB={cB.shape[0]} D={D} s={s} a={a}", flush=True)
+    want_acc = capi.tiled_matmul(cA, cB, s, a)
+    one = dev(np.array([1.0], np.float32))
+    out, acc = B.gemm_codes(dev(capi.pack_codes(cA, 4)), dev(capi.pack_codes(cB, 4)), 4, 4, one, one, D, n, a, s)
+    got_acc = host(acc)
+    if not np.array_equal(got_acc, want_acc):
+        bad = np.argwhere(got_acc != want_acc)
+        raise AssertionError(f"{len(bad)} accumulators differ, first at {bad[0]}: got "
+                             f"{got_acc[tuple(bad[0])]} want {want_acc[tuple(bad[0])]}")
+    assert_close_f32(host(out), capi.dequantize(want_acc, np.float32(1.0), np.float32(1.0), n))
+
+
+@pytest.mark.parametrize("RA,RB,D", [(384, 256, 1152), (300, 64, 576), (256, 128, 16384), (130, 200, 1144)])
+def test_gemm_codes_tiles_that_cannot_saturate(RA, RB, D):
+    """Tiles of 32 with 8-bit accumulators: the matrix-core kernel skips the clamp of a tile whose
+    sums provably stay in range (small codes), clamps the others, and gives the test up where
+    nothing passes.  Small codes everywhere; small codes with rows, columns and stretches of the
+    contraction that fill the range (waves, tiles and pairs of tiles of both kinds side by
+    side); and the two mixed the other way round."""
+    rng = np.random.default_rng(RA + 3 * RB + D)
+    check_gemm_codes_given(gaussian_codes(rng, RA, D, 0.9), gaussian_codes(rng, RB, D, 1.6), 32, 8)
+    cA, cB = gaussian_codes(rng, RA, D, 0.8), gaussian_codes(rng, RB, D, 1.2)
+    big = random_codes(rng, RA, D, 4, extreme=0.7)
+    cA[5::67] = big[5::67]                                   # single rows of A
+    cA[:, 96:160] = big[:, 96:160]                           # two tiles of every row, in two pairs
+    cA[RA // 2:, 416:448] = big[RA // 2:, 416:448]           # one tile of a pair, half the rows
+    cB[3::41] = random_codes(rng, RB, D, 4, extreme=0.7)[3::41]
+    check_gemm_codes_given(cA, cB, 32, 8)
+    # range-filling first stage (the workgroup stops testing), small codes behind it
+    cA, cB = gaussian_codes(rng, RA, D, 0.8), gaussian_codes(rng, RB, D, 1.2)
+    cA[:, :128] = random_codes(rng, RA, 128, 4, extreme=0.7)
+    cB[:, :128] = random_codes(rng, RB, 128, 4, extreme=0.7)
+    check_gemm_codes_given(cA, cB, 32, 8)
+    # small codes first, range-filling ones from the second stage on
+    cA, cB = gaussian_codes(rng, RA, D, 0.8), gaussian_codes(rng, RB, D, 1.2)
+    cA[:, 128:] = random_codes(rng, RA, D - 128, 4, extreme=0.7)
+    cB[:, 128:] = random_codes(rng, RB, D - 128, 4, extreme=0.7)
+    check_gemm_codes_given(cA, cB, 32, 8)
+
+
+@pytest.mark.parametrize("tiles", [255, 256])
+def test_gemm_codes_every_tile_saturates_upwards(tiles):
+    """255 tiles per output element is the most whose upward saturations the kernel that tests
+    its tiles can count (one more takes the other kernel); every tile sum is 32 * 49 -> 127, or
+    32 * -56 -> -128, or (every fourth pair of tiles) 32 * 1 -> 32 unclamped."""
+    RA = RB = 2944                                            # 23 x 23 output tiles: the contraction is not split
+    D = 32 * tiles
+    one = dev(np.array([1.0], np.float32))
+    cA, cB = np.full((RA, D), 7, np.int8), np.full((RB, D), 7, np.int8)
+    qA, qB = dev(capi.pack_codes(cA, 4)), dev(capi.pack_codes(cB, 4))
+    _, acc = B.gemm_codes(qA, qB, 4, 4, one, one, D, 1, 8, 32)
+    assert torch.all(acc == tiles * 127).item()
+    cA[:] = -8
+    qA = dev(capi.pack_codes(cA, 4))
+    _, acc = B.gemm_codes(qA, qB, 4, 4, one, one, D, 1, 8, 32)
+    assert torch.all(acc == tiles * -128).item()
+    cA[:] = 7
+    small = (np.arange(D) // 64) % 4 == 3
+    cA[:, small] = 1
+    cB[:, small] = 1
+    _, acc = B.gemm_codes(dev(capi.pack_codes(cA, 4)), dev(capi.pack_codes(cB, 4)), 4, 4, one, one, D, 1, 8, 32)
+    n_small = int(small.sum()) // 32
+    assert torch.all(acc == (tiles - n_small) * 127 + n_small * 32).item()
+
+
 def test_gemm_codes_hand_cases():
     # all (7, 7): each 16-tile sums to 784 -> 127
     D = 64
