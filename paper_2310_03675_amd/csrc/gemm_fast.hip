@@ -23,6 +23,9 @@
 //     v_dot4c_i32_i8 with the byte selector (0,1,0,1) adds the two high bytes
 //     to the running total: one VALU instruction per tile sum.  The two sums
 //     of a pair are two consecutive tiles of the same output element.
+//   * the same setting with tiles of 32, plain output, at most 255 tiles per part: the
+//     kernel first asks whether a tile can saturate at all (EPI_CERT8_S32, below) and
+//     adds the ones that cannot straight onto the totals in the matrix core.
 //   * any other accumulator width or tile length: v_med3_i32 against bounds
 //     scaled by 256, add, and one exact shift at the end.
 //   * LDS holds int8, double-buffered, and the global loads run two stages
