@@ -59,7 +59,7 @@ constexpr int kScaleShift = 8;        // both operands carry a factor 16
 enum Epilogue { EPI_GENERIC = 0, EPI_SAT8_S32 = 1, EPI_SAT8_S64 = 2, EPI_STAGES = 3, EPI_SAT16_S32 = 4,
                 EPI_SAT16_S64 = 5, EPI_SAT8_S16 = 6, EPI_SAT16_S16 = 7, EPI_CLAMP_S16 = 8,
                 EPI_REQ_MAX = 9, EPI_REQ_SUM = 10, EPI_REQ_MAX_S32 = 11, EPI_REQ_SUM_S32 = 12,
-                EPI_CERT8_S32 = 13 };
+                EPI_CERT8_S32 = 13, EPI_CERT16_S32 = 14 };
 // EPI_CERT8_S32: 8-bit accumulators, tiles of 32 packed 4-bit codes, as EPI_SAT8_S32 -- but a
 // tile whose sums provably stay inside the accumulator is not clamped at all.  The proof is
 // the Cauchy-Schwarz bound: |sum_k a_k b_k| <= sqrt(sum a_k^2 * sum b_k^2), so with nA the largest
@@ -76,6 +76,11 @@ enum Epilogue { EPI_GENERIC = 0, EPI_SAT8_S32 = 1, EPI_SAT8_S64 = 2, EPI_STAGES 
 // Quantizer output of heavy-tailed tensors (activations, most gradients) has small codes and
 // passes nearly everywhere; codes that fill their range fail, and then this is EPI_SAT8_S32
 // plus the test.
+// EPI_CERT16_S32: the same test in front of EPI_SAT16_S32 (packed 4-bit codes, accumulators of
+// 9 to 12 bits: wider ones cannot saturate on tiles of 32 at all).  The bound is the
+// accumulator's own, (2^(a-1) - 1)^2, which nearly every tile of nearly any data meets; the
+// operands go to LDS scaled as for EPI_SAT16, the clamped tiles are added with their low bits
+// cleared as there, so the totals are exact multiples of 2^(16-a) and need no correction.
 // EPI_REQ_MAX / EPI_REQ_SUM: the second reading of the low-bit accumulator (Methodology, tiled
 // quantization: every tile's partial-sum tensor through Q with a bits and its own maximum) as
 // two passes over the same product, neither of which stores a tile sum.  The first keeps, per
@@ -304,10 +309,11 @@ __global__ __launch_bounds__(64 * WAVES, WAVES == 8 ? (MASK ? 3 : 4) : 2) void g
     constexpr bool kReqSum = (EPI == EPI_REQ_SUM || EPI == EPI_REQ_SUM_S32), kReq = kReqMax || kReqSum;
     constexpr bool kReqS32 = (EPI == EPI_REQ_MAX_S32 || EPI == EPI_REQ_SUM_S32);
     static_assert(!kReq || (!BF16 && !FOLD && !WIDE && !NARROW && !MASK), "second reading: plain packed instances only");
-    constexpr bool kCert = (EPI == EPI_CERT8_S32);
+    constexpr bool kCert16 = (EPI == EPI_CERT16_S32);
+    constexpr bool kCert = (EPI == EPI_CERT8_S32) || kCert16;
     static_assert(!kCert || (WAVES == 8 && KS == KS_LONG && !BF16 && !FOLD && !WIDE && !MASK), "certified tiles: plain packed instances only");
-    const int fin_shift = kSat16 ? g.fin_shift : ((kSat8 || kReq || kCert) ? 0 : SHIFT);
-    const uint32_t low_clear = kSat16 ? (0xFFFFu & (0xFFFFu << g.fin_shift)) * 0x00010001u : 0u;
+    const int fin_shift = (kSat16 || kCert16) ? g.fin_shift : ((kSat8 || kReq || kCert) ? 0 : SHIFT);
+    const uint32_t low_clear = (kSat16 || kCert16) ? (0xFFFFu & (0xFFFFu << g.fin_shift)) * 0x00010001u : 0u;
     constexpr int REGS = WIDE ? 2 : 1;                 // 16-byte registers per unit in flight
     // WAVES = 4: each wave a 64 x 64 quarter (2 x 2 MFMA blocks).  WAVES = 8: each wave
     // 64 rows x 32 columns (2 x 1 MFMA blocks): half the accumulators per wave, so four
@@ -579,7 +585,7 @@ __global__ __launch_bounds__(64 * WAVES, WAVES == 8 ? (MASK ? 3 : 4) : 2) void g
                     *reinterpret_cast<uint4*>(&Bs[buf][r][lks * KSTEP + 16 * hf]) =
                         kSat16 ? scale_bytes(st.b[2 * i + hf], g.jB) : st.b[2 * i + hf];
                 }
-            } else if constexpr (kSat16) {
+            } else if constexpr (kSat16 || kCert16) {
                 store_unit_scaled(&As[buf][r][lks * KSTEP], st.a[i], g.jA);
                 if (i < UNITS_B && (!NARROW || r < TN)) store_unit_scaled(&Bs[buf][r][lks * KSTEP], st.b[i], g.jB);
             } else {
@@ -628,7 +634,7 @@ __global__ __launch_bounds__(64 * WAVES, WAVES == 8 ? (MASK ? 3 : 4) : 2) void g
                 }
             m = max_row_shr<4>(m);
             m = max_row_shr<8>(m);
-            const int limit = 127 * 127;
+            const int limit = kCert16 ? g.acc_hi * g.acc_hi : 127 * 127;      // (a <= 12: no overflow)
             int any_no = 0;
 #pragma unroll
             for (int pr = 0; pr < NSTEP / 2; ++pr) {
@@ -702,7 +708,8 @@ __global__ __launch_bounds__(64 * WAVES, WAVES == 8 ? (MASK ? 3 : 4) : 2) void g
                         const v16i p1 = __builtin_amdgcn_mfma_i32_32x32x32_i8(fa[1][a], fb[1][c], zero, 0, 0, 0);
 #pragma unroll
                         for (int r = 0; r < 16; ++r)
-                            total[a][c][r] = add_sat8_pair_scaled(total[a][c][r], p0[r], p1[r]);
+                            total[a][c][r] = kCert16 ? add_sat16_pair(total[a][c][r], p0[r], p1[r], low_clear)
+                                                     : add_sat8_pair_scaled(total[a][c][r], p0[r], p1[r]);
                     }
             }
         } else if (kCert) {
@@ -736,7 +743,8 @@ __global__ __launch_bounds__(64 * WAVES, WAVES == 8 ? (MASK ? 3 : 4) : 2) void g
                             const v16i p1 = __builtin_amdgcn_mfma_i32_32x32x32_i8(fa[1][a], fb[1][c], zero, 0, 0, 0);
 #pragma unroll
                             for (int r = 0; r < 16; ++r)
-                                total[a][c][r] = add_sat8_pair_scaled(total[a][c][r], p0[r], p1[r]);
+                                total[a][c][r] = kCert16 ? add_sat16_pair(total[a][c][r], p0[r], p1[r], low_clear)
+                                                         : add_sat8_pair_scaled(total[a][c][r], p0[r], p1[r]);
                         }
                 }
             }
@@ -899,7 +907,7 @@ __global__ __launch_bounds__(64 * WAVES, WAVES == 8 ? (MASK ? 3 : 4) : 2) void g
                         part[a][c][r] = 0;
                     }
         }
-        if constexpr (kCert) {
+        if constexpr (kCert && !kCert16) {
             if (cert_clamped) {
                 cert_clamped = false;
 #pragma unroll
@@ -1403,6 +1411,14 @@ static bool cert_tiles(const GemmArgs& g, int64_t n_ct)
     return g.stream_out && n_ct >= 8 && g.D >= KS_LONG;
 }
 
+// The same test in front of the int16-saturation instances (EPI_CERT16_S32): packed codes, at
+// least five stages per part, accumulators narrow enough for the squared bound to fit 32 bits.
+static bool cert16_tiles(const GemmArgs& g)
+{
+    if (g.bA > 4 || g.bB > 4 || g.mask_src || g.s != 32 || g.acc_hi > 2047) return false;
+    return g.tiles_per_split * g.s > 4 * KS_LONG;
+}
+
 // Second reading of the accumulator in this kernel: packed 4-bit codes on both sides, tiles that
 // are whole 32-code steps, accumulators of at most 16 bits (the rounding by addition needs
 // |value| < 2^22), at most kReqTable tiles per part, tile sums times 256 inside int32.
@@ -1515,6 +1531,7 @@ hipError_t launch_gemm_fast(const GemmArgs& g_in, hipStream_t stream)
     } else if (sat16) {
         if (wide && g.s == 32) HDQT_LAUNCH_SAT16(EPI_SAT16_S32, true);
         else if (wide) HDQT_LAUNCH_SAT16(EPI_SAT16_S64, true);
+        else if (g.s == 32 && cert16_tiles(g)) HDQT_LAUNCH_SAT16(EPI_CERT16_S32, false);
         else if (g.s == 32) HDQT_LAUNCH_SAT16(EPI_SAT16_S32, false);
         else HDQT_LAUNCH_SAT16(EPI_SAT16_S64, false);
     } else if (wide) {

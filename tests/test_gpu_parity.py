@@ -338,6 +338,28 @@ def test_gemm_codes_tiles_that_cannot_saturate(RA, RB, D):
     check_gemm_codes_given(cA, cB, 32, 8)
 
 
+@pytest.mark.parametrize("a", [9, 10, 12])
+@pytest.mark.parametrize("RA,RB,D", [(384, 256, 1152), (256, 128, 16384)])
+def test_gemm_codes_tiles_that_cannot_saturate_wider_accumulators(RA, RB, D, a):
+    """The same test of the tiles in front of the int16-saturation kernel (accumulators of 9 to
+    12 bits): quantizer-like codes (everything passes), codes at the range ends everywhere
+    (sums of up to 2048: nothing passes, the workgroups give up), and stretches of the one
+    inside the other."""
+    rng = np.random.default_rng(RA + 3 * RB + D + a)
+    check_gemm_codes_given(gaussian_codes(rng, RA, D, 1.5), gaussian_codes(rng, RB, D, 1.8), 32, a)
+    ends = lambda lines, cols: random_codes(rng, lines, cols, 4, extreme=1.0)
+    check_gemm_codes_given(ends(RA, D), ends(RB, D), 32, a)
+    cA, cB = gaussian_codes(rng, RA, D, 1.5), gaussian_codes(rng, RB, D, 1.8)
+    cA[:, 256:448], cB[:, 256:448] = ends(RA, 192), ends(RB, 192)
+    cA[7::50, 640:] = ends(len(cA[7::50]), D - 640)
+    cB[::2, 640:704] = np.sign(cB[::2, 640:704] + 0.5).astype(np.int8) * 7
+    check_gemm_codes_given(cA, cB, 32, a)
+    cA, cB = ends(RA, D), ends(RB, D)
+    cA[:, 128:] = gaussian_codes(rng, RA, D - 128, 1.5)
+    cB[:, 128:] = gaussian_codes(rng, RB, D - 128, 1.8)
+    check_gemm_codes_given(cA, cB, 32, a)
+
+
 @pytest.mark.parametrize("tiles", [255, 256])
 def test_gemm_codes_every_tile_saturates_upwards(tiles):
     """255 tiles per output element is the most whose upward saturations the kernel that tests
