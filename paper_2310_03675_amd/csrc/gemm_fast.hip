@@ -1176,6 +1176,27 @@ __global__ __launch_bounds__(64 * WAVES, WAVES == 8 ? (MASK ? 3 : 4) : 2) void g
                 }
             }
         }
+        // The common case on a path of its own -- fp32 output only, a tile inside the output:
+        // nothing is tested per element, so the 32 stores of a wave are one run of
+        // conversions and stores (with the tests, each store sat in an exec-masked block of
+        // its own behind its own branches).
+        const bool plain_out = !MASK && interior && ob && !ab && !ab16 && !(BF16 && hb);
+        if (plain_out) {
+#pragma unroll
+            for (int a = 0; a < RS; ++a)
+#pragma unroll
+                for (int c = 0; c < CS; ++c)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) {
+                        const int rr = a * 32 + 8 * (r >> 2) + (r & 3);
+                        const int64_t uo = (int64_t)rr * g.RB + c * 32;
+                        const float f = (float)(total[a][c][r] >> fin_shift) * dq;
+                        total[a][c][r] = 0;
+                        if (STREAM) __builtin_nontemporal_store(f, &(ob + uo)[lane_off]);
+                        else (ob + uo)[lane_off] = f;
+                    }
+        }
+        if (!plain_out) {
 #pragma unroll
         for (int a = 0; a < RS; ++a)
 #pragma unroll
@@ -1203,6 +1224,7 @@ __global__ __launch_bounds__(64 * WAVES, WAVES == 8 ? (MASK ? 3 : 4) : 2) void g
                         }
                     }
                 }
+        }
         // the next tile's mask values set out now: a tile's worth of time to arrive
         if constexpr (MASK) prefetch_mask(c_ct + (int)gridDim.z);
         c_k = k_begin;
