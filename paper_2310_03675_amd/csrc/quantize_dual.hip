@@ -497,7 +497,23 @@ struct DualBatch {
     int gx[kMaxDualBatch];       // workgroups along the columns
     int WC[kMaxDualBatch];       // waves side by side in a workgroup (1, 2 or 4)
     int lds_per_wave;            // floats of LDS per wave (convolution sources), a multiple of 4
+    int spread;                  // pass 2: every spread-th workgroup of the grid is one of tensor 0 (0: off)
 };
+
+// Workgroup number -> number in the tensor-after-tensor order.  With `spread`, the workgroups of
+// tensor 0 (the stochastically rounded one of a per-tensor launch: twice the vector
+// instructions per tile, a tenth of the bytes) stand at every spread-th place of the grid
+// instead of in front of it, so that they run beside the memory-bound tiles of the others,
+// not before them.
+__device__ __forceinline__ int batch_order(const DualBatch& b)
+{
+    const int bid = (int)blockIdx.x;
+    if (!b.spread) return bid;
+    const int c0 = b.first[1], slot = bid / b.spread;
+    if (bid - slot * b.spread == 0 && slot < c0) return slot;
+    const int before = slot + 1 < c0 ? slot + 1 : c0;      // tensor 0's workgroups at or before this place
+    return bid - before + c0;
+}
 
 // Wave w of a workgroup owns the tile at columns [64*wc, 64*wc + 64) of the
 // workgroup's strip and rows [64*wr, 64*wr + 64), (wc, wr) = (w % WC, w / WC).
@@ -514,13 +530,13 @@ constexpr int kRoundPerTensor = 4;
 constexpr int kRoundWide = 8;        // added to ROUND: codes of 5 to 8 bits, one per byte
 
 template <bool QUANT, int ROUND, bool N64, bool CONV>
-__device__ __forceinline__ void dual_block(const DualBatch& b, int k, float (*red)[2], float* lds)
+__device__ __forceinline__ void dual_block(const DualBatch& b, int k, int vb, float (*red)[2], float* lds)
 {
     const DualArgs& q = b.t[k];
     const int count = b.first[k + 1] - b.first[k];
     // pass 2 walks a tensor from its end to its start: it begins with what pass 1
     // read last, which is most likely still in the memory-side cache
-    int local = (int)blockIdx.x - b.first[k];
+    int local = vb - b.first[k];
     if (QUANT) local = count - 1 - local;
     const int gx = b.gx[k], WC = b.WC[k];
     const int64_t by = local / gx, bx = local - (local / gx) * gx;
@@ -557,15 +573,16 @@ __global__ __launch_bounds__(kThreads) void fwht_dual_kernel(DualBatch b)
     __shared__ float red[kThreads / kWave][2];
     extern __shared__ __attribute__((aligned(16))) float lds[];      // CONV: one patch per wave
 
+    const int vb = QUANT ? batch_order(b) : (int)blockIdx.x;
     int k = 0;
-    while (k + 1 < b.n && (int)blockIdx.x >= b.first[k + 1]) ++k;
+    while (k + 1 < b.n && vb >= b.first[k + 1]) ++k;
     if constexpr ((ROUND & 7) == kRoundPerTensor) {
         // two complete bodies, chosen per workgroup: sharing anything between them
         // (one load, one setup) lets the compiler keep both paths' registers alive
-        if (b.t[k].st_row) dual_block<QUANT, 3 | (ROUND & kRoundWide), N64, CONV>(b, k, red, lds);
-        else dual_block<QUANT, ROUND & kRoundWide, N64, CONV>(b, k, red, lds);
+        if (b.t[k].st_row) dual_block<QUANT, 3 | (ROUND & kRoundWide), N64, CONV>(b, k, vb, red, lds);
+        else dual_block<QUANT, ROUND & kRoundWide, N64, CONV>(b, k, vb, red, lds);
     } else {
-        dual_block<QUANT, ROUND, N64, CONV>(b, k, red, lds);
+        dual_block<QUANT, ROUND, N64, CONV>(b, k, vb, red, lds);
     }
 }
 
@@ -601,6 +618,7 @@ bool make_batch(const DualArgs* qs, int n, DualBatch* b)
     }
     b->first[n] = (int)total;
     b->lds_per_wave = lds;
+    b->spread = 0;
     return true;
 }
 
@@ -694,6 +712,18 @@ hipError_t launch_dual_pass2(const DualArgs* qs, int n, hipStream_t stream)
         else hipLaunchKernelGGL((fwht_dual_kernel<true, ROUND, false, false>), grid, block, 0, stream, b); \
     } while (0)
     const int mode = !same ? kRoundPerTensor : (qs[0].st_row ? 1 : 0) | (qs[0].st_col ? 2 : 0);
+    // A stochastic tensor in front of nearest ones: its workgroups among theirs (see batch_order),
+    // over the first three quarters of the grid (a heavy workgroup among the last ones is the
+    // kernel's tail: spread over the whole grid the launch took 102 us instead of 95.6) and at
+    // an odd distance: workgroups go to the eight XCDs in turn, and at a distance of 8 (6) every
+    // heavy one lands on the same XCD (on four of them): 122 (100) us.  At 7: 93.4 us.
+    if (mode == kRoundPerTensor && qs[0].st_row && b.first[1] > 0) {
+        bool rest_nearest = true;
+        for (int k = 1; k < n; ++k) rest_nearest = rest_nearest && !qs[k].st_row;
+        int64_t q = (int64_t)b.first[n] * 3 / (4 * (int64_t)b.first[1]);
+        if (q % 2 == 0) --q;
+        if (rest_nearest && q >= 3 && q < ((int64_t)1 << 30)) b.spread = (int)q;
+    }
     if (qs[0].b_row > 4) {
         switch (mode) {
         case kRoundPerTensor: HDQT_LAUNCH_PASS2(kRoundPerTensor | kRoundWide); break;
