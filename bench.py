@@ -793,6 +793,28 @@ def main():
         fb["step_had_block_128"] = {"ms": dt_f * 1e3, "kernels_us": k_f, "TOPS": ops_step / dt_f / 1e12}
         line["fallback_paths"] = fb
         del Xf, Wf, Xq, ws_f
+        # The matmul's test of its tiles (tiles of 32, 8-bit accumulators: a tile whose sums
+        # provably stay in range is not clamped) depends on the codes, not on the shape: the
+        # forward product's launch on the layer's own codes, where nearly every tile passes,
+        # and on codes drawn uniformly from the whole range, where none does and the
+        # workgroups give the test up.  Same shape, same kernel instance.
+        if args.s == 32 and args.acc_bits == 8:
+            qx, sx = B.quantize(X, 1, n, pf.A, 0)
+            qw, sw = B.quantize(W, 0, n, pf.B, 0)
+            g_t = torch.Generator(device=dev)
+            g_t.manual_seed(1234)
+            ux = torch.randint(0, 256, qx.shape, dtype=torch.uint8, device=dev, generator=g_t)
+            uw = torch.randint(0, 256, qw.shape, dtype=torch.uint8, device=dev, generator=g_t)
+            o_t = torch.empty((M, N), dtype=torch.float32, device=dev)
+            ws_t = torch.empty(max(B.load().hdqt_gemm_codes_workspace_size(M, N, K, args.s), 256),
+                               dtype=torch.uint8, device=dev)
+            tt = {}
+            for key, (a_, b_) in (("fwd_layer_codes", (qx, qw)), ("fwd_codes_uniform_over_the_range", (ux, uw))):
+                _, k_f = timed(lambda: B.gemm_codes(a_, b_, 4, 4, sx, sw, K, n, 8, args.s, want_acc=False,
+                                                    out=o_t, workspace=ws_t))
+                tt[key + "_us"] = sum(v for n_, v in k_f.items() if n_.startswith("gemm"))
+            line["tile_test"] = tt
+            del qx, qw, ux, uw, o_t, ws_t
     if not args.no_cpu_baseline:
         line["cpu_baseline"] = cpu_baseline(layer, n, args.s, min(args.cpu_rows, M))
     print(json.dumps(line))

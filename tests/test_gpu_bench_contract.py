@@ -79,6 +79,9 @@ def test_bench_line_has_the_extra_legs():
     assert all(v["ms"] > 0 and v["kernels_us"] for v in fb.values())
     assert "gemm_i4_fwd" in fb["fwd_K_multiple_of_8_not_32"]["kernels_us"]
     assert any(k.startswith("gemm_tiled") for k in fb["fwd_K_not_multiple_of_8"]["kernels_us"])
+    # the matmul's test of its tiles: one figure where nearly every tile passes, one where none does
+    tt = d["tile_test"]
+    assert tt["fwd_layer_codes_us"] > 0 and tt["fwd_codes_uniform_over_the_range_us"] > 0
     # the forward product under the second reading of the accumulator: two passes, no tile sums stored
     rq = d["requant_fwd"]
     assert rq["tile_sums_materialised_bytes"] == 0 and rq["workspace_bytes"] < 64 << 20
