@@ -360,6 +360,46 @@ def test_gemm_codes_tiles_that_cannot_saturate_wider_accumulators(RA, RB, D, a):
     check_gemm_codes_given(cA, cB, 32, a)
 
 
+def patchwork_codes(rng, lines, D):
+    """4-bit codes in patches (up to 96 rows by up to 256 positions), each patch with a
+    distribution of its own: small, quantizer-like, uniform over the range, range ends only, zeros."""
+    out = np.empty((lines, D), np.int8)
+    r = 0
+    while r < lines:
+        h, k = int(rng.integers(1, 97)), 0
+        while k < D:
+            w = int(rng.integers(1, 9)) * 32
+            shape = (min(h, lines - r), min(w, D - k))
+            kind = int(rng.integers(0, 5))
+            if kind == 0:
+                blk = np.clip(np.rint(rng.normal(0, 0.7, shape)), -8, 7)
+            elif kind == 1:
+                blk = np.clip(np.rint(rng.normal(0, 1.5, shape)), -8, 7)
+            elif kind == 2:
+                blk = rng.integers(-8, 8, shape)
+            elif kind == 3:
+                blk = np.where(rng.random(shape) < 0.5, -8, 7)
+            else:
+                blk = np.zeros(shape)
+            out[r:r + shape[0], k:k + shape[1]] = blk
+            k += w
+        r += h
+    return out
+
+
+@pytest.mark.parametrize("seed", range(12))
+def test_gemm_codes_tile_test_on_patchworks(seed):
+    """Random shapes (every third with a split contraction) and patchwork codes, so that tiles
+    that pass the matmul's saturation test and tiles that fail it meet in every arrangement;
+    accumulators of 8, 9, 10 and 12 bits."""
+    rng = np.random.default_rng(1000 + seed)
+    RA, RB, D = int(rng.integers(1, 600)), int(rng.integers(65, 400)), int(rng.integers(20, 700)) * 8
+    if seed % 3 == 0:
+        RA, RB, D = int(rng.integers(64, 256)), int(rng.integers(65, 200)), int(rng.integers(1024, 4096)) * 8
+    a = [8, 8, 10, 8, 12, 9][seed % 6]
+    check_gemm_codes_given(patchwork_codes(rng, RA, D), patchwork_codes(rng, RB, D), 32, a)
+
+
 @pytest.mark.parametrize("tiles", [255, 256])
 def test_gemm_codes_every_tile_saturates_upwards(tiles):
     """255 tiles per output element is the most whose upward saturations the kernel that tests
