@@ -642,7 +642,7 @@ __global__ __launch_bounds__(64 * WAVES, WAVES == 8 ? (MASK ? 3 : 4) : 2) void g
                 const int b0 = __builtin_amdgcn_readlane(m, 28 + 2 * pr), b1 = __builtin_amdgcn_readlane(m, 29 + 2 * pr);
                 // (sums of squares of 32 codes: at most 2048 each)
                 cert_ok[pr] = __builtin_amdgcn_readfirstlane((a0 * b0 <= limit && a1 * b1 <= limit) ? 1 : 0);
-                asm volatile("s_xor_b32 %0, %1, 1" : "=s"(cert_no[pr]) : "s"(cert_ok[pr]));
+                asm volatile("s_xor_b32 %0, %1, 1" : "=s"(cert_no[pr]) : "s"(cert_ok[pr]) : "scc");
                 any_no |= cert_no[pr];
             }
             if (cert_stage == 0) {

@@ -400,6 +400,15 @@ def test_gemm_codes_tile_test_on_patchworks(seed):
     check_gemm_codes_given(patchwork_codes(rng, RA, D), patchwork_codes(rng, RB, D), 32, a)
 
 
+def test_gemm_codes_tile_test_streamed_output():
+    """Outputs of 128 MB and more take the instances with streaming stores (waves one block
+    high and two wide), which go on in the testing stage after giving the test up: patchwork
+    codes on a contraction of nine stages, and on the input gradient's single stage."""
+    rng = np.random.default_rng(77)
+    check_gemm_codes_given(patchwork_codes(rng, 32768, 1152), patchwork_codes(rng, 1024, 1152), 32, 8)
+    check_gemm_codes_given(patchwork_codes(rng, 65536, 128), patchwork_codes(rng, 1152, 128), 32, 8)
+
+
 @pytest.mark.parametrize("tiles", [255, 256])
 def test_gemm_codes_every_tile_saturates_upwards(tiles):
     """255 tiles per output element is the most whose upward saturations the kernel that tests
