@@ -407,6 +407,15 @@ def test_gemm_codes_tile_test_streamed_output():
     rng = np.random.default_rng(77)
     check_gemm_codes_given(patchwork_codes(rng, 32768, 1152), patchwork_codes(rng, 1024, 1152), 32, 8)
     check_gemm_codes_given(patchwork_codes(rng, 65536, 128), patchwork_codes(rng, 1152, 128), 32, 8)
+    check_gemm_codes_given(patchwork_codes(rng, 32768, 1152), patchwork_codes(rng, 1024, 1152), 32, 10)
+
+
+def test_gemm_codes_tile_test_many_workgroups():
+    """An output that stays in the caches, large enough for several rounds of workgroups per
+    compute unit (1024 output tiles, 18 stages each)."""
+    rng = np.random.default_rng(78)
+    check_gemm_codes_given(patchwork_codes(rng, 8192, 2304), patchwork_codes(rng, 2048, 2304), 32, 8)
+    check_gemm_codes_given(patchwork_codes(rng, 4096, 2304), patchwork_codes(rng, 2048, 2304), 32, 12)
 
 
 @pytest.mark.parametrize("tiles", [255, 256])
