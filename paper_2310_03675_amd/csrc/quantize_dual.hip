@@ -56,12 +56,15 @@ struct DualCtx {
 __device__ __forceinline__ void tile_load(Tile& t, const DualArgs& q, const DualCtx& x, int64_t row0,
                                           int64_t col0)
 {
-    const float* src = q.T + (row0 + x.rg * 8) * q.cols + col0 + x.cg * 4;
+    // a uniform address per (i, h) plus one 32-bit offset per lane (cols < 2^26: quantize_dual_eligible):
+    // the loads take the scalar-base form and no vector instruction forms their addresses
+    const float* base = q.T + row0 * q.cols + col0;
+    const uint32_t lo = (uint32_t)(x.rg * 8) * (uint32_t)q.cols + (uint32_t)(x.cg * 4);
 #pragma unroll
     for (int i = 0; i < 8; ++i)
 #pragma unroll
         for (int h = 0; h < 2; ++h) {
-            const float4 a = *reinterpret_cast<const float4*>(src + i * q.cols + 32 * h);
+            const float4 a = *reinterpret_cast<const float4*>(&(base + i * q.cols + 32 * h)[lo]);
             t.v[h][0][i] = a.x; t.v[h][1][i] = a.y; t.v[h][2][i] = a.z; t.v[h][3][i] = a.w;
         }
 }
@@ -318,7 +321,9 @@ __device__ __forceinline__ void row_line(const Tile& t, int i, const DualCtx& x,
     const bool odd = (x.cg & 1) != 0;
     const uint32_t word = __builtin_amdgcn_perm(other, both, odd ? 0x03020706u : 0x05040100u);
     const int byte_off = odd ? 16 + 2 * (x.cg - 1) : 2 * x.cg;
-    *reinterpret_cast<uint32_t*>(q.codes_row + row * (q.cols >> 1) + (col0 >> 1) + byte_off) = word;
+    // (uniform address of the tile's row i, 32-bit offset of the lane's row group and bytes)
+    const uint32_t lo = (uint32_t)(x.rg * 8) * (uint32_t)(q.cols >> 1) + (uint32_t)byte_off;
+    *reinterpret_cast<uint32_t*>(&(q.codes_row + (row0 + i) * (q.cols >> 1) + (col0 >> 1))[lo]) = word;
 }
 
 // Axis 0 on the whole tile, in place.  The two lanes of a swap stage carry the
@@ -385,7 +390,8 @@ __device__ __forceinline__ void col_codes(const Tile& t, const DualCtx& x, int64
                 uint8_t* dst = q.codes_col + (col0 + 32 * h + x.cg * 4 + j) * pitch + row0 + x.rg * 8;
                 *reinterpret_cast<uint2*>(dst) = make_uint2(pack_bytes(cw[h][j]), pack_bytes(cw[h][j] + 4));
             } else {
-                uint8_t* dst = q.codes_col + (col0 + 32 * h + x.cg * 4 + j) * pitch + (row0 >> 1) + x.rg * 4;
+                const uint32_t lo = (uint32_t)(x.cg * 4) * (uint32_t)pitch + (uint32_t)(x.rg * 4);
+                uint8_t* dst = &(q.codes_col + (col0 + 32 * h + j) * pitch + (row0 >> 1))[lo];
                 *reinterpret_cast<uint32_t*>(dst) = pack_nibbles(cw[h][j]);
             }
         }
@@ -541,7 +547,7 @@ __device__ __forceinline__ void dual_block(const DualBatch& b, int k, int vb, fl
     const int gx = b.gx[k], WC = b.WC[k];
     const int64_t by = local / gx, bx = local - (local / gx) * gx;
 
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
     const int wc = wave % WC, wr = wave / WC, WR = 4 / WC;
     const int64_t col0 = (bx * WC + wc) * kTile;
     const int64_t row0 = (by * WR + wr) * kTile;
@@ -649,6 +655,7 @@ bool dual_conv_plan(DualArgs* q)
 
 bool quantize_dual_eligible(const DualArgs& q)
 {
+    if (q.cols >= ((int64_t)1 << 26) || q.rows >= ((int64_t)1 << 26)) return false;      // 32-bit lane offsets
     return (q.rows % kTile == 0) && (q.cols % kTile == 0) && q.log2n_row <= 6 && q.log2n_col <= 6 &&
            q.b_row <= 8 && q.b_col <= 8 && (q.b_row <= 4) == (q.b_col <= 4) &&
            (q.rows / kTile) * (q.cols / kTile) < ((int64_t)1 << 30);
