@@ -34,14 +34,14 @@ HBM_PEAK_GBPS = 8000.0          # MI355X HBM3E
 TRAFFIC_SOURCE = "profiles/bench_resnet_k1152_hbm_traffic.md (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, not measured in this run)"
 VALU_SOURCE = "profiles/bench_resnet_k1152_valu_issue.md (rocprofv3 --pmc SQ_INSTS_VALU, not measured in this run)"
 MEASURED_TRAFFIC = {
-    "fwht_dual_absmax_batch": 336.4e6, "fwht_dual_quant_batch": 422.6e6,
+    "fwht_dual_absmax_batch": 336.4e6, "fwht_dual_quant_batch": 422.8e6,
     "gemm_i4_fwd": 74.6e6, "gemm_i4_bwd_input": 307.4e6, "gemm_i4_bwd_weight": 61.7e6,
 }
 # The kernels' sources as they were when those counters were collected: a SHA-256 over the
 # files below, in this order.  The bench line says whether they have changed since (then the
 # counter figures describe older kernels; re-collect them and update this value).
 PROFILED_SOURCES = ("common.hpp", "lane_ops.hpp", "quantize_dual.hip", "gemm_fast.hip", "gemm.hip")
-PROFILED_SOURCES_SHA256 = "b1d511d1804c8d232f216e9b858edb056bcb428fb701da06a648be7545252bed"
+PROFILED_SOURCES_SHA256 = "97016e69f062f8d216ac81edc5a9ee2eb6bc61a4ab91909c4d1d29768c9c9480"
 
 
 def profiled_sources_sha256():
@@ -57,7 +57,7 @@ INT8_MFMA_PEAK_TOPS = 5000.0    # MI355X dense int8
 # Wave-wide vector-ALU instructions per launch of the two quantizer kernels on this workload
 # (rocprofv3 --pmc SQ_INSTS_VALU, profiles/bench_resnet_k1152_valu_issue.md), and the chip's
 # issue peak: one such instruction per SIMD every four cycles, 256 CUs x 4 SIMDs x 2.4 GHz / 4.
-MEASURED_VALU_INSTS = {"fwht_dual_absmax_batch": 21.00e6, "fwht_dual_quant_batch": 40.89e6}
+MEASURED_VALU_INSTS = {"fwht_dual_absmax_batch": 20.73e6, "fwht_dual_quant_batch": 39.24e6}
 VALU_ISSUE_PEAK = 256 * 4 * 2.4e9 / 4
 
 WORKLOADS = {
