@@ -57,7 +57,8 @@ __device__ __forceinline__ void tile_load(Tile& t, const DualArgs& q, const Dual
                                           int64_t col0)
 {
     // a uniform address per (i, h) plus one 32-bit offset per lane (cols < 2^26: quantize_dual_eligible):
-    // the loads take the scalar-base form and no vector instruction forms their addresses
+    // one 64-bit vector addition per row of the tile is all that is left of the address arithmetic
+    // (buffer loads with scalar offsets take that out too, 21 instructions of 1711, and change no time)
     const float* base = q.T + row0 * q.cols + col0;
     const uint32_t lo = (uint32_t)(x.rg * 8) * (uint32_t)q.cols + (uint32_t)(x.cg * 4);
 #pragma unroll
